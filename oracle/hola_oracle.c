@@ -1,0 +1,507 @@
+/*
+ * hola_oracle.c -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+ *
+ * A plain, slow, float64 CPU statement of what one batched verify step of
+ * HOLA's Hierarchical Speculative Decoding (HSD) computes.  It exists so that
+ * the HIP path can be checked element by element; it shares no code, header,
+ * table or helper with the HIP path, and only the tests, the smoke check and
+ * the benchmark's CPU-baseline leg may call it.
+ *
+ * What the paper fixes (Section 3.1, "HSD Module"; Algorithm 1, Step 1;
+ * Equation (1); Section 4.3 for the magnitude of tau):
+ *   - the per-position entropy of the DRAFT distribution, H = -sum_i q_i log q_i;
+ *   - the gate g(t) = 1[H < tau] with a strict inequality;
+ *   - gate = 1 keeps the drafted token without consulting the verifier,
+ *     gate = 0 falls back to the verifier.
+ * What the paper leaves open and this file fills in with the standard
+ * draft-and-verify rule of the literature the paper's related-work section
+ * points at (all of it restated here, every reading listed in the design
+ * notes of the repository):
+ *   - temperature-scaled softmax of both models' logits;
+ *   - verifier branch = acceptance test  u * q(x) < p(x),  u uniform on [0,1);
+ *   - the sequence stops at its first rejected position;
+ *   - at a rejection the next token is drawn from  max(0, p - q) / Z  by
+ *     inverse CDF; when every draft is accepted a bonus token is drawn from p;
+ *   - uniforms come from Philox4x32-10 keyed on (seed, sequence, position, level);
+ *   - "hierarchical": the output of one verify level is the draft of the next.
+ *
+ * Arithmetic: IEEE double, libm exp/log, sums taken in ascending index order,
+ * no blocking, no fusion.  bf16 inputs are widened exactly (bits << 16).
+ *
+ * Parity pins (tests/test_oracle_*.py, all CPU): Philox known-answer vectors of
+ * the published generator; scipy logsumexp / entropy; closed forms for uniform,
+ * one-hot, two-point and geometric logits; q = p accepts everything; p(x) = 0
+ * always rejects; full-lattice enumeration of the uniform; numpy cumsum +
+ * searchsorted for the inverse CDF; Z = 1 - sum min(p,q); brute-force output
+ * marginal = p on tiny vocabularies; monotonicity of accept length in tau.
+ * No function in this file is "parity unpinned".
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------- */
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as    */
+/* easy as 1, 2, 3", SC'11).  Ten rounds; the key is bumped between rounds.   */
+/* ------------------------------------------------------------------------- */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) { k0 += W0; k1 += W1; }
+        uint64_t prod0 = (uint64_t)M0 * c0;
+        uint64_t prod1 = (uint64_t)M1 * c2;
+        uint32_t hi0 = (uint32_t)(prod0 >> 32), lo0 = (uint32_t)prod0;
+        uint32_t hi1 = (uint32_t)(prod1 >> 32), lo1 = (uint32_t)prod1;
+        uint32_t n0 = hi1 ^ c1 ^ k0;
+        uint32_t n1 = lo1;
+        uint32_t n2 = hi0 ^ c3 ^ k1;
+        uint32_t n3 = lo0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* 24-bit uniform on the lattice {0, 1, ..., 2^24 - 1} * 2^-24, a subset of [0,1). */
+double oracle_u24(uint32_t r) { return (double)(r >> 8) * (1.0 / 16777216.0); }
+
+/* The random block of one (sequence, position, level): counter words are
+ * (position, low and high half of the global sequence index, level), the key
+ * is the 64-bit seed split in halves. */
+static void hsd_random_block(uint64_t seed, int64_t seq, uint32_t pos, uint32_t level, uint32_t out[4])
+{
+    uint32_t ctr[4] = { pos, (uint32_t)((uint64_t)seq & 0xffffffffu), (uint32_t)((uint64_t)seq >> 32), level };
+    uint32_t key[2] = { (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32) };
+    oracle_philox4x32_10(ctr, key, out);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Logit access.  dtype 0: IEEE float; dtype 1: bfloat16 as raw 16-bit words. */
+/* ------------------------------------------------------------------------- */
+static double logit_at(const void* base, int32_t dtype, int64_t idx)
+{
+    if (dtype == 0) return (double)((const float*)base)[idx];
+    uint32_t bits = (uint32_t)((const uint16_t*)base)[idx] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+/* Scaled logit z_i = x_i / T.  For a greedy row (T == 0) the entropy gate is
+ * evaluated on the unscaled logits, i.e. as if T = 1. */
+static double scaled(double x, double T) { return T > 0.0 ? x / T : x; }
+
+/* ------------------------------------------------------------------------- */
+/* Row statistics: log-sum-exp, Shannon entropy (nats), argmax.               */
+/* Entropy as Section 3.1 defines it, H = -sum_i p_i log p_i, with             */
+/* p_i = exp(z_i - lse) and log p_i = z_i - lse, so                            */
+/*   H = lse - sum_i z_i exp(z_i - lse);   a term whose probability is 0       */
+/* (including z_i = -inf) contributes 0.                                       */
+/* A row with no finite maximum has no distribution: lse = -inf, H = NaN.      */
+/* ------------------------------------------------------------------------- */
+void oracle_row_stats(const void* logits, int32_t dtype, int64_t offset, int32_t V, double T,
+                      double* lse_out, double* H_out, int32_t* argmax_out)
+{
+    double m = -INFINITY;
+    int32_t am = -1;
+    for (int32_t i = 0; i < V; ++i) {
+        double z = scaled(logit_at(logits, dtype, offset + i), T);
+        if (z > m) { m = z; am = i; }          /* strict: lowest index wins ties */
+    }
+    if (argmax_out) *argmax_out = am;
+    if (!(m > -INFINITY) || !(m < INFINITY)) {  /* all -inf, or NaN / +inf present */
+        if (lse_out) *lse_out = (m == INFINITY) ? INFINITY : -INFINITY;
+        if (H_out) *H_out = NAN;
+        return;
+    }
+    double S = 0.0;
+    for (int32_t i = 0; i < V; ++i) {
+        double z = scaled(logit_at(logits, dtype, offset + i), T);
+        S += exp(z - m);
+    }
+    double lse = m + log(S);
+    double acc = 0.0;
+    for (int32_t i = 0; i < V; ++i) {
+        double z = scaled(logit_at(logits, dtype, offset + i), T);
+        double p = exp(z - lse);
+        if (p > 0.0) acc += z * p;
+    }
+    if (lse_out) *lse_out = lse;
+    if (H_out) *H_out = lse - acc;
+}
+
+/* Probability of token x in the row whose log-sum-exp is lse. */
+static double prob_at(const void* logits, int32_t dtype, int64_t offset, int32_t x, double T, double lse)
+{
+    double z = scaled(logit_at(logits, dtype, offset + x), T);
+    return exp(z - lse);
+}
+
+/* ------------------------------------------------------------------------- */
+/* The acceptance test of the verifier branch:  accept  iff  u * q_x < p_x.   */
+/* With u in [0,1): p_x = 0 rejects for every u (also u = 0); q_x = 0 < p_x   */
+/* accepts; p_x >= q_x > 0 accepts for every u.  Accept probability is         */
+/* min(1, p_x / q_x).                                                          */
+/* ------------------------------------------------------------------------- */
+int32_t oracle_ratio_accept(double u, double p_x, double q_x) { return (u * q_x < p_x) ? 1 : 0; }
+
+/* ------------------------------------------------------------------------- */
+/* Inverse-CDF draw from unnormalised weights w[0..V): the smallest i whose    */
+/* inclusive running sum C_i (ascending order) exceeds t = u * Z, Z = C_{V-1}. */
+/* If rounding leaves no such i, the largest i with w_i > 0; if no weight is   */
+/* positive, -1.  margin_out = distance from t to the nearer end of the chosen */
+/* interval, in units of Z.                                                    */
+/* ------------------------------------------------------------------------- */
+int32_t oracle_inverse_cdf(const double* w, int32_t V, double u, double* Z_out, double* margin_out)
+{
+    double Z = 0.0;
+    for (int32_t i = 0; i < V; ++i) Z += w[i];
+    if (Z_out) *Z_out = Z;
+    if (margin_out) *margin_out = NAN;
+    if (!(Z > 0.0)) return -1;
+    double t = u * Z;
+    double C = 0.0;
+    int32_t last_pos = -1;
+    for (int32_t i = 0; i < V; ++i) {
+        double prev = C;
+        C += w[i];
+        if (w[i] > 0.0) last_pos = i;
+        if (C > t) {
+            if (margin_out) {
+                double lo = t - prev, hi = C - t;
+                *margin_out = (lo < hi ? lo : hi) / Z;
+            }
+            return i;
+        }
+    }
+    if (margin_out) *margin_out = 0.0;
+    return last_pos;
+}
+
+/* Test aids: exact accept / selection frequencies over the whole 24-bit lattice
+ * of the uniform (stride > 1 walks a coarser sub-lattice), obtained by calling
+ * the two functions above once per lattice point. */
+int64_t oracle_ratio_accept_lattice_count(double p_x, double q_x, int32_t stride)
+{
+    int64_t n = 0;
+    for (uint32_t k = 0; k < (1u << 24); k += (uint32_t)stride)
+        n += oracle_ratio_accept((double)k * (1.0 / 16777216.0), p_x, q_x);
+    return n;
+}
+
+void oracle_inverse_cdf_lattice_hist(const double* w, int32_t V, int32_t stride, int64_t* hist)
+{
+    for (int32_t i = 0; i < V; ++i) hist[i] = 0;
+    for (uint32_t k = 0; k < (1u << 24); k += (uint32_t)stride) {
+        int32_t t = oracle_inverse_cdf(w, V, (double)k * (1.0 / 16777216.0), NULL, NULL);
+        if (t >= 0) hist[t] += 1;
+    }
+}
+
+/* Residual weights at one position: w_i = max(0, p_i - q_i); bonus: w_i = p_i. */
+void oracle_residual_weights(const void* target, const void* draft, int32_t dtype,
+                             int64_t t_off, int64_t d_off, int32_t V, double T,
+                             double lseP, double lseD, int32_t bonus, double* w)
+{
+    for (int32_t i = 0; i < V; ++i) {
+        double p = prob_at(target, dtype, t_off, i, T, lseP);
+        if (bonus) { w[i] = p; continue; }
+        double q = prob_at(draft, dtype, d_off, i, T, lseD);
+        double d = p - q;
+        w[i] = d > 0.0 ? d : 0.0;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* One verify level.                                                           */
+/* ------------------------------------------------------------------------- */
+typedef struct {
+    const void* target_logits;      /* [B, gamma+1, V], row stride target_ld elements (0 => V) */
+    const void* draft_logits;       /* [B, gamma,   V], row stride draft_ld  elements (0 => V) */
+    int32_t dtype;                  /* 0 = float, 1 = bfloat16 bits */
+    int64_t target_ld, draft_ld;
+    const int32_t* draft_tokens;    /* [B, gamma] */
+    const int32_t* draft_len;       /* [B] in [0, gamma], or NULL => gamma */
+    const float* row_temperature;   /* [B] or NULL => temperature; 0 => greedy row */
+    const int32_t* force_accept_len;/* [B] or NULL; entry >= 0 overrides the scan result (test aid) */
+    uint64_t seed;
+    uint32_t level;
+    int64_t seq_base;
+    int32_t B, gamma, V;
+    float temperature, entropy_threshold;
+    /* outputs; any may be NULL */
+    int32_t* out_accept_len;        /* [B] */
+    int32_t* out_next_token;        /* [B] */
+    float* out_entropy;             /* [B, gamma], -1 beyond draft_len */
+    double* out_entropy64;          /* [B, gamma], NaN beyond draft_len */
+    double* out_lse_draft;          /* [B, gamma] */
+    double* out_lse_target;         /* [B, gamma+1] */
+    double* out_H_target;           /* [B, gamma+1] entropy of the target rows (next level's gate) */
+    uint8_t* out_gate;              /* [B, gamma] */
+    uint8_t* out_ratio_ok;          /* [B, gamma] */
+    double* out_gate_margin;        /* [B, gamma] |H - tau| */
+    double* out_ratio_margin;       /* [B, gamma] |u - p_x/q_x|, NaN when q_x == 0 or greedy */
+    double* out_sample_margin;      /* [B] */
+    double* out_Z;                  /* [B] total residual (or bonus) weight; NaN for greedy */
+    int32_t num_threads;            /* <= 0: library default */
+} oracle_verify_args;
+
+static void verify_one_sequence(const oracle_verify_args* a, int32_t b, double* w)
+{
+    const int32_t g = a->gamma, V = a->V;
+    const int64_t tld = a->target_ld ? a->target_ld : V;
+    const int64_t dld = a->draft_ld ? a->draft_ld : V;
+    const int32_t len = a->draft_len ? a->draft_len[b] : g;
+    const double T = (double)(a->row_temperature ? a->row_temperature[b] : a->temperature);
+    const int greedy = !(T > 0.0);
+    const double tau = (double)a->entropy_threshold;
+    const int64_t seq = a->seq_base + b;
+
+    double lseD[64], HD[64], lseP[65], HP[65];
+    int32_t amP[65];
+
+    for (int32_t j = 0; j < g; ++j) {
+        if (a->out_entropy) a->out_entropy[(int64_t)b * g + j] = -1.0f;
+        if (a->out_entropy64) a->out_entropy64[(int64_t)b * g + j] = NAN;
+        if (a->out_gate) a->out_gate[(int64_t)b * g + j] = 0;
+        if (a->out_ratio_ok) a->out_ratio_ok[(int64_t)b * g + j] = 0;
+        if (a->out_gate_margin) a->out_gate_margin[(int64_t)b * g + j] = NAN;
+        if (a->out_ratio_margin) a->out_ratio_margin[(int64_t)b * g + j] = NAN;
+        if (a->out_lse_draft) a->out_lse_draft[(int64_t)b * g + j] = NAN;
+    }
+    for (int32_t j = 0; j <= g; ++j) {
+        if (a->out_lse_target) a->out_lse_target[(int64_t)b * (g + 1) + j] = NAN;
+        if (a->out_H_target) a->out_H_target[(int64_t)b * (g + 1) + j] = NAN;
+    }
+
+    /* draft rows: lse and entropy of q */
+    for (int32_t j = 0; j < len; ++j) {
+        oracle_row_stats(a->draft_logits, a->dtype, ((int64_t)b * g + j) * dld, V, T, &lseD[j], &HD[j], NULL);
+        if (a->out_entropy) a->out_entropy[(int64_t)b * g + j] = (float)HD[j];
+        if (a->out_entropy64) a->out_entropy64[(int64_t)b * g + j] = HD[j];
+        if (a->out_lse_draft) a->out_lse_draft[(int64_t)b * g + j] = lseD[j];
+    }
+    /* target rows: lse (argmax for greedy rows); entropy kept for a following level */
+    for (int32_t j = 0; j <= len; ++j) {
+        oracle_row_stats(a->target_logits, a->dtype, ((int64_t)b * (g + 1) + j) * tld, V, T, &lseP[j], &HP[j], &amP[j]);
+        if (a->out_lse_target) a->out_lse_target[(int64_t)b * (g + 1) + j] = lseP[j];
+        if (a->out_H_target) a->out_H_target[(int64_t)b * (g + 1) + j] = HP[j];
+    }
+
+    /* gate, ratio test, first rejection */
+    int32_t acc_len = len;
+    for (int32_t j = 0; j < len; ++j) {
+        int gate = (HD[j] < tau) ? 1 : 0;                 /* Algorithm 1, Step 1: H < tau, strict */
+        int32_t x = a->draft_tokens[(int64_t)b * g + j];
+        uint32_t r[4];
+        hsd_random_block(a->seed, seq, (uint32_t)j, a->level, r);
+        double u = oracle_u24(r[0]);
+        int ok;
+        double rmargin = NAN;
+        if (greedy) {
+            ok = (x == amP[j]);
+        } else {
+            double p_x = 0.0, q_x = 1.0;
+            if (x >= 0 && x < V) {
+                p_x = prob_at(a->target_logits, a->dtype, ((int64_t)b * (g + 1) + j) * tld, x, T, lseP[j]);
+                q_x = prob_at(a->draft_logits, a->dtype, ((int64_t)b * g + j) * dld, x, T, lseD[j]);
+            }
+            ok = oracle_ratio_accept(u, p_x, q_x);
+            if (q_x > 0.0) rmargin = fabs(u - p_x / q_x);
+        }
+        if (a->out_gate) a->out_gate[(int64_t)b * g + j] = (uint8_t)gate;
+        if (a->out_ratio_ok) a->out_ratio_ok[(int64_t)b * g + j] = (uint8_t)ok;
+        if (a->out_gate_margin) a->out_gate_margin[(int64_t)b * g + j] = fabs(HD[j] - tau);
+        if (a->out_ratio_margin) a->out_ratio_margin[(int64_t)b * g + j] = rmargin;
+        if (!(gate || ok) && acc_len == len) acc_len = j; /* Equation (1): gate keeps the draft, else verifier */
+    }
+    if (a->force_accept_len && a->force_accept_len[b] >= 0) acc_len = a->force_accept_len[b];
+    if (a->out_accept_len) a->out_accept_len[b] = acc_len;
+
+    /* next token at the stop row */
+    const int32_t rrow = acc_len;
+    int32_t tok;
+    double smargin = NAN, Z = NAN;
+    if (greedy) {
+        tok = amP[rrow];
+    } else {
+        uint32_t r[4];
+        hsd_random_block(a->seed, seq, (uint32_t)rrow, a->level, r);
+        double u2 = oracle_u24(r[1]);
+        int32_t bonus = (acc_len >= len);
+        int64_t t_off = ((int64_t)b * (g + 1) + rrow) * tld;
+        int64_t d_off = ((int64_t)b * g + (bonus ? 0 : rrow)) * dld;
+        oracle_residual_weights(a->target_logits, a->draft_logits, a->dtype, t_off, d_off, V, T,
+                                lseP[rrow], bonus ? 0.0 : lseD[rrow], bonus, w);
+        tok = oracle_inverse_cdf(w, V, u2, &Z, &smargin);
+        if (!bonus && !(Z > 0.0)) {                        /* p == q everywhere: fall back to p */
+            oracle_residual_weights(a->target_logits, a->draft_logits, a->dtype, t_off, d_off, V, T,
+                                    lseP[rrow], 0.0, 1, w);
+            tok = oracle_inverse_cdf(w, V, u2, &Z, &smargin);
+        }
+    }
+    if (a->out_next_token) a->out_next_token[b] = tok;
+    if (a->out_sample_margin) a->out_sample_margin[b] = smargin;
+    if (a->out_Z) a->out_Z[b] = Z;
+}
+
+/* Returns 0, or -1 on an argument the oracle does not take. */
+int32_t oracle_verify(const oracle_verify_args* a)
+{
+    if (!a || a->B < 0 || a->gamma < 1 || a->gamma > 63 || a->V < 1) return -1;
+    int nthreads = 1;
+#ifdef _OPENMP
+    nthreads = a->num_threads > 0 ? a->num_threads : omp_get_max_threads();
+#endif
+    (void)nthreads;
+#pragma omp parallel num_threads(nthreads)
+    {
+        double* w = (double*)malloc((size_t)a->V * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int32_t b = 0; b < a->B; ++b) verify_one_sequence(a, b, w);
+        free(w);
+    }
+    return 0;
+}
+
+/* The interval [C_{tok-1}, C_tok] / Z of token `tok` in the distribution the
+ * stop row of sequence b is sampled from (residual when acc_len < len, bonus
+ * otherwise), for judging a sample that differs from the oracle's. */
+int32_t oracle_sample_interval(const oracle_verify_args* a, int32_t b, int32_t acc_len, int32_t tok,
+                               double* lo_out, double* hi_out)
+{
+    const int32_t g = a->gamma, V = a->V;
+    if (tok < 0 || tok >= V || acc_len < 0 || acc_len > g) return -1;
+    const int64_t tld = a->target_ld ? a->target_ld : V;
+    const int64_t dld = a->draft_ld ? a->draft_ld : V;
+    const int32_t len = a->draft_len ? a->draft_len[b] : g;
+    const double T = (double)(a->row_temperature ? a->row_temperature[b] : a->temperature);
+    if (!(T > 0.0)) return -1;
+    int32_t bonus = (acc_len >= len);
+    int64_t t_off = ((int64_t)b * (g + 1) + acc_len) * tld;
+    int64_t d_off = ((int64_t)b * g + (bonus ? 0 : acc_len)) * dld;
+    double lseP, lseD = 0.0;
+    oracle_row_stats(a->target_logits, a->dtype, t_off, V, T, &lseP, NULL, NULL);
+    if (!bonus) oracle_row_stats(a->draft_logits, a->dtype, d_off, V, T, &lseD, NULL, NULL);
+    double* w = (double*)malloc((size_t)V * sizeof(double));
+    oracle_residual_weights(a->target_logits, a->draft_logits, a->dtype, t_off, d_off, V, T, lseP, lseD, bonus, w);
+    double Z = 0.0;
+    for (int32_t i = 0; i < V; ++i) Z += w[i];
+    if (!bonus && !(Z > 0.0)) {
+        oracle_residual_weights(a->target_logits, a->draft_logits, a->dtype, t_off, d_off, V, T, lseP, 0.0, 1, w);
+        Z = 0.0;
+        for (int32_t i = 0; i < V; ++i) Z += w[i];
+    }
+    double C = 0.0, prev = 0.0;
+    for (int32_t i = 0; i <= tok; ++i) { prev = C; C += w[i]; }
+    free(w);
+    if (!(Z > 0.0)) return -1;
+    *lo_out = prev / Z;
+    *hi_out = C / Z;
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Hierarchical verify over n_models logit sets, smallest drafter first.       */
+/* Level k (k = 1 .. n_models-1) verifies with models[k] the drafts that       */
+/* level k-1 produced: its accepted tokens followed by its next token.         */
+/* models[k] has gamma+k rows per sequence; tau[k-1] gates level k on the      */
+/* entropy of models[k-1].                                                     */
+/* ------------------------------------------------------------------------- */
+int32_t oracle_hsd_verify(const void* const* model_logits, const int64_t* model_ld, int32_t n_models,
+                          int32_t dtype, const int32_t* draft_tokens, uint64_t seed, int64_t seq_base,
+                          int32_t B, int32_t gamma, int32_t V,
+                          const float* row_temperature, float temperature, const float* tau,
+                          int32_t* out_tokens,      /* [B, gamma + n_models - 1], -1 beyond the drafts */
+                          int32_t* out_accept_len,  /* [B] final level */
+                          int32_t* out_next_token,  /* [B] final level */
+                          float* out_entropy,       /* [n_models-1, B, gamma + n_models - 2], -1 where unused */
+                          int32_t* out_level_accept,/* [n_models-1, B] or NULL */
+                          int32_t* out_level_next,  /* [n_models-1, B] or NULL */
+                          int32_t num_threads)
+{
+    if (n_models < 2 || B < 0 || gamma < 1 || gamma + n_models - 2 > 63) return -1;
+    const int32_t L = n_models - 1;
+    const int32_t gmax = gamma + L - 1;           /* drafts at the last level */
+    const int32_t wout = gamma + L;               /* width of out_tokens */
+    int32_t* toks = (int32_t*)malloc((size_t)B * (gmax + 1) * sizeof(int32_t));
+    int32_t* lens = (int32_t*)malloc((size_t)B * sizeof(int32_t));
+    int32_t* acc = (int32_t*)malloc((size_t)B * sizeof(int32_t));
+    int32_t* nxt = (int32_t*)malloc((size_t)B * sizeof(int32_t));
+    float* ent = (float*)malloc((size_t)B * gmax * sizeof(float));
+    int32_t* cur = (int32_t*)malloc((size_t)B * gmax * sizeof(int32_t));
+    for (int32_t b = 0; b < B; ++b) {
+        lens[b] = gamma;
+        for (int32_t j = 0; j < gamma; ++j) toks[(int64_t)b * (gmax + 1) + j] = draft_tokens[(int64_t)b * gamma + j];
+    }
+    if (out_entropy)
+        for (int64_t i = 0; i < (int64_t)L * B * gmax; ++i) out_entropy[i] = -1.0f;
+    int32_t rc = 0;
+    for (int32_t k = 1; k <= L && rc == 0; ++k) {
+        const int32_t gk = gamma + k - 1;         /* drafts offered at this level */
+        for (int32_t b = 0; b < B; ++b)
+            for (int32_t j = 0; j < gk; ++j)
+                cur[(int64_t)b * gk + j] = (j < lens[b]) ? toks[(int64_t)b * (gmax + 1) + j] : -1;
+        oracle_verify_args a;
+        memset(&a, 0, sizeof a);
+        a.target_logits = model_logits[k];
+        a.draft_logits = model_logits[k - 1];
+        a.dtype = dtype;
+        a.target_ld = model_ld ? model_ld[k] : 0;
+        a.draft_ld = model_ld ? model_ld[k - 1] : 0;
+        a.draft_tokens = cur;
+        a.draft_len = lens;
+        a.row_temperature = row_temperature;
+        a.seed = seed;
+        a.level = (uint32_t)(k - 1);
+        a.seq_base = seq_base;
+        a.B = B; a.gamma = gk; a.V = V;
+        a.temperature = temperature;
+        a.entropy_threshold = tau[k - 1];
+        a.out_accept_len = acc;
+        a.out_next_token = nxt;
+        a.out_entropy = ent;
+        a.num_threads = num_threads;
+        rc = oracle_verify(&a);
+        for (int32_t b = 0; b < B && rc == 0; ++b) {
+            if (out_entropy)
+                for (int32_t j = 0; j < gk; ++j)
+                    out_entropy[((int64_t)(k - 1) * B + b) * gmax + j] = ent[(int64_t)b * gk + j];
+            if (out_level_accept) out_level_accept[(int64_t)(k - 1) * B + b] = acc[b];
+            if (out_level_next) out_level_next[(int64_t)(k - 1) * B + b] = nxt[b];
+            if (k < L) {                          /* next level's drafts: accepted prefix + next token */
+                toks[(int64_t)b * (gmax + 1) + acc[b]] = nxt[b];
+                lens[b] = acc[b] + 1;
+            }
+        }
+    }
+    if (rc == 0) {
+        for (int32_t b = 0; b < B; ++b) {
+            if (out_accept_len) out_accept_len[b] = acc[b];
+            if (out_next_token) out_next_token[b] = nxt[b];
+            if (out_tokens)
+                for (int32_t j = 0; j < wout; ++j)
+                    out_tokens[(int64_t)b * wout + j] = (j < lens[b]) ? toks[(int64_t)b * (gmax + 1) + j] : -1;
+        }
+    }
+    free(toks); free(lens); free(acc); free(nxt); free(ent); free(cur);
+    return rc;
+}
+
+int32_t oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

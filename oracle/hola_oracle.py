@@ -1,0 +1,299 @@
+"""ctypes front end of the float64 CPU oracle (``hola_oracle.c``).
+
+TEST INFRASTRUCTURE, NOT THE PRODUCT: only ``tests/``, the smoke check and the
+benchmark's CPU-baseline leg may import this module.  It shares nothing with the
+HIP path.  The arithmetic lives in the C file; this module only marshals numpy
+arrays (argument passing, no method steps).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hola_oracle.c")
+_LIB = os.path.join(_HERE, "libhola_oracle.so")
+
+F32, BF16 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, no fast-math, OpenMP over sequences)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Args(C.Structure):
+    _fields_ = [
+        ("target_logits", C.c_void_p), ("draft_logits", C.c_void_p), ("dtype", C.c_int32),
+        ("target_ld", C.c_int64), ("draft_ld", C.c_int64),
+        ("draft_tokens", C.c_void_p), ("draft_len", C.c_void_p), ("row_temperature", C.c_void_p),
+        ("force_accept_len", C.c_void_p),
+        ("seed", C.c_uint64), ("level", C.c_uint32), ("seq_base", C.c_int64),
+        ("B", C.c_int32), ("gamma", C.c_int32), ("V", C.c_int32),
+        ("temperature", C.c_float), ("entropy_threshold", C.c_float),
+        ("out_accept_len", C.c_void_p), ("out_next_token", C.c_void_p), ("out_entropy", C.c_void_p),
+        ("out_entropy64", C.c_void_p), ("out_lse_draft", C.c_void_p), ("out_lse_target", C.c_void_p),
+        ("out_H_target", C.c_void_p),
+        ("out_gate", C.c_void_p), ("out_ratio_ok", C.c_void_p),
+        ("out_gate_margin", C.c_void_p), ("out_ratio_margin", C.c_void_p),
+        ("out_sample_margin", C.c_void_p), ("out_Z", C.c_void_p),
+        ("num_threads", C.c_int32),
+    ]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        L.oracle_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oracle_philox4x32_10.restype = None
+        L.oracle_u24.argtypes = [C.c_uint32]
+        L.oracle_u24.restype = C.c_double
+        L.oracle_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_double,
+                                       C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oracle_row_stats.restype = None
+        L.oracle_ratio_accept.argtypes = [C.c_double, C.c_double, C.c_double]
+        L.oracle_ratio_accept.restype = C.c_int32
+        L.oracle_inverse_cdf.argtypes = [C.c_void_p, C.c_int32, C.c_double, C.c_void_p, C.c_void_p]
+        L.oracle_inverse_cdf.restype = C.c_int32
+        L.oracle_ratio_accept_lattice_count.argtypes = [C.c_double, C.c_double, C.c_int32]
+        L.oracle_ratio_accept_lattice_count.restype = C.c_int64
+        L.oracle_inverse_cdf_lattice_hist.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+        L.oracle_inverse_cdf_lattice_hist.restype = None
+        L.oracle_residual_weights.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64,
+                                              C.c_int32, C.c_double, C.c_double, C.c_double, C.c_int32,
+                                              C.c_void_p]
+        L.oracle_residual_weights.restype = None
+        L.oracle_verify.argtypes = [C.POINTER(_Args)]
+        L.oracle_verify.restype = C.c_int32
+        L.oracle_sample_interval.argtypes = [C.POINTER(_Args), C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_void_p, C.c_void_p]
+        L.oracle_sample_interval.restype = C.c_int32
+        L.oracle_hsd_verify.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                        C.c_uint64, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                        C.c_void_p, C.c_float, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_int32]
+        L.oracle_hsd_verify.restype = C.c_int32
+        L.oracle_max_threads.argtypes = []
+        L.oracle_max_threads.restype = C.c_int32
+        _lib = L
+    return _lib
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data
+
+
+def _logits(a: np.ndarray) -> tuple[np.ndarray, int]:
+    """Accept float32 logits or bf16 logits given as uint16 bit patterns."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float32:
+        return a, F32
+    if a.dtype == np.uint16:
+        return a, BF16
+    raise TypeError(f"logits must be float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+def philox4x32_10(ctr: Sequence[int], key: Sequence[int]) -> tuple[int, int, int, int]:
+    c = np.asarray(ctr, dtype=np.uint32)
+    k = np.asarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().oracle_philox4x32_10(_ptr(c), _ptr(k), _ptr(out))
+    return tuple(int(x) for x in out)
+
+
+def u24(r: int) -> float:
+    return float(lib().oracle_u24(C.c_uint32(r)))
+
+
+def hsd_uniforms(seed: int, seq: int, pos: int, level: int = 0) -> tuple[float, float]:
+    """(accept uniform, sampling uniform) of one (sequence, position, level)."""
+    r = philox4x32_10([pos & 0xFFFFFFFF, seq & 0xFFFFFFFF, (seq >> 32) & 0xFFFFFFFF, level],
+                      [seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF])
+    return u24(r[0]), u24(r[1])
+
+
+def row_stats(row: np.ndarray, T: float = 1.0) -> tuple[float, float, int]:
+    """(lse, entropy in nats, argmax) of softmax(row / T); T == 0 means T = 1 (greedy rows)."""
+    row, dt = _logits(row)
+    lse, H, am = C.c_double(), C.c_double(), C.c_int32()
+    lib().oracle_row_stats(_ptr(row), dt, 0, row.shape[-1], float(T),
+                           C.addressof(lse), C.addressof(H), C.addressof(am))
+    return lse.value, H.value, am.value
+
+
+def ratio_accept(u: float, p_x: float, q_x: float) -> bool:
+    return bool(lib().oracle_ratio_accept(u, p_x, q_x))
+
+
+def inverse_cdf(w: np.ndarray, u: float) -> tuple[int, float, float]:
+    """(token, Z, margin) of the inverse-CDF draw from unnormalised weights w."""
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    Z, m = C.c_double(), C.c_double()
+    tok = lib().oracle_inverse_cdf(_ptr(w), w.shape[0], float(u), C.addressof(Z), C.addressof(m))
+    return int(tok), Z.value, m.value
+
+
+def ratio_accept_lattice_count(p_x: float, q_x: float, stride: int = 1) -> int:
+    """Number of lattice uniforms k*stride*2^-24 that pass the acceptance test."""
+    return int(lib().oracle_ratio_accept_lattice_count(float(p_x), float(q_x), int(stride)))
+
+
+def inverse_cdf_lattice_hist(w: np.ndarray, stride: int = 1) -> np.ndarray:
+    """How many lattice uniforms select each token."""
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    hist = np.zeros(w.shape[0], dtype=np.int64)
+    lib().oracle_inverse_cdf_lattice_hist(_ptr(w), w.shape[0], int(stride), _ptr(hist))
+    return hist
+
+
+def residual_weights(target_row: np.ndarray, draft_row: Optional[np.ndarray], T: float,
+                     bonus: bool = False) -> np.ndarray:
+    """max(0, p - q) over one position (or p itself when bonus)."""
+    target_row, dt = _logits(target_row)
+    V = target_row.shape[-1]
+    lseP, _, _ = row_stats(target_row, T)
+    if bonus:
+        draft_row, lseD = target_row, 0.0
+    else:
+        draft_row, dt2 = _logits(draft_row)
+        assert dt2 == dt
+        lseD, _, _ = row_stats(draft_row, T)
+    w = np.zeros(V, dtype=np.float64)
+    lib().oracle_residual_weights(_ptr(target_row), _ptr(draft_row), dt, 0, 0, V, float(T),
+                                  lseP, lseD, int(bonus), _ptr(w))
+    return w
+
+
+@dataclass
+class VerifyResult:
+    accept_len: np.ndarray
+    next_token: np.ndarray
+    entropy: np.ndarray          # float32 [B, gamma]
+    entropy64: np.ndarray        # float64 [B, gamma]
+    lse_draft: np.ndarray
+    lse_target: np.ndarray
+    H_target: np.ndarray
+    gate: np.ndarray
+    ratio_ok: np.ndarray
+    gate_margin: np.ndarray
+    ratio_margin: np.ndarray
+    sample_margin: np.ndarray
+    Z: np.ndarray
+
+
+class VerifyCall:
+    """Holds the marshalled arguments of one ``oracle_verify`` call (keeps arrays alive)."""
+
+    def __init__(self, target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold,
+                 draft_len=None, row_temperature=None, level=0, seq_base=0, force_accept_len=None,
+                 num_threads=0):
+        self.P, dt = _logits(target_logits)
+        self.D, dt2 = _logits(draft_logits)
+        assert dt == dt2, "target and draft logits must share a dtype"
+        B, g1, V = self.P.shape
+        g = g1 - 1
+        assert self.D.shape == (B, g, V), (self.D.shape, (B, g, V))
+        self.tok = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+        assert self.tok.shape == (B, g)
+        self.len = None if draft_len is None else np.ascontiguousarray(draft_len, dtype=np.int32)
+        self.rowT = None if row_temperature is None else np.ascontiguousarray(row_temperature, dtype=np.float32)
+        self.force = None if force_accept_len is None else np.ascontiguousarray(force_accept_len, dtype=np.int32)
+        self.B, self.g, self.V = B, g, V
+        a = _Args()
+        a.target_logits, a.draft_logits, a.dtype = _ptr(self.P), _ptr(self.D), dt
+        a.target_ld = a.draft_ld = 0
+        a.draft_tokens, a.draft_len = _ptr(self.tok), _ptr(self.len)
+        a.row_temperature, a.force_accept_len = _ptr(self.rowT), _ptr(self.force)
+        a.seed, a.level, a.seq_base = int(seed), int(level), int(seq_base)
+        a.B, a.gamma, a.V = B, g, V
+        a.temperature, a.entropy_threshold = float(temperature), float(entropy_threshold)
+        a.num_threads = int(num_threads)
+        self.args = a
+
+    def run(self) -> VerifyResult:
+        B, g = self.B, self.g
+        r = VerifyResult(
+            accept_len=np.zeros(B, np.int32), next_token=np.zeros(B, np.int32),
+            entropy=np.zeros((B, g), np.float32), entropy64=np.zeros((B, g), np.float64),
+            lse_draft=np.zeros((B, g), np.float64), lse_target=np.zeros((B, g + 1), np.float64),
+            H_target=np.zeros((B, g + 1), np.float64),
+            gate=np.zeros((B, g), np.uint8), ratio_ok=np.zeros((B, g), np.uint8),
+            gate_margin=np.zeros((B, g), np.float64), ratio_margin=np.zeros((B, g), np.float64),
+            sample_margin=np.zeros(B, np.float64), Z=np.zeros(B, np.float64))
+        a = self.args
+        a.out_accept_len, a.out_next_token = _ptr(r.accept_len), _ptr(r.next_token)
+        a.out_entropy, a.out_entropy64 = _ptr(r.entropy), _ptr(r.entropy64)
+        a.out_lse_draft, a.out_lse_target, a.out_H_target = _ptr(r.lse_draft), _ptr(r.lse_target), _ptr(r.H_target)
+        a.out_gate, a.out_ratio_ok = _ptr(r.gate), _ptr(r.ratio_ok)
+        a.out_gate_margin, a.out_ratio_margin = _ptr(r.gate_margin), _ptr(r.ratio_margin)
+        a.out_sample_margin, a.out_Z = _ptr(r.sample_margin), _ptr(r.Z)
+        rc = lib().oracle_verify(C.byref(a))
+        if rc != 0:
+            raise ValueError("oracle_verify rejected its arguments")
+        return r
+
+    def sample_interval(self, b: int, acc_len: int, tok: int) -> Optional[tuple[float, float]]:
+        lo, hi = C.c_double(), C.c_double()
+        rc = lib().oracle_sample_interval(C.byref(self.args), int(b), int(acc_len), int(tok),
+                                          C.addressof(lo), C.addressof(hi))
+        return None if rc != 0 else (lo.value, hi.value)
+
+
+def verify(target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold, **kw) -> VerifyResult:
+    return VerifyCall(target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold, **kw).run()
+
+
+@dataclass
+class HsdResult:
+    tokens: np.ndarray           # [B, gamma + n_models - 1]
+    accept_len: np.ndarray       # [B]
+    next_token: np.ndarray       # [B]
+    entropy: np.ndarray          # [n_models-1, B, gamma + n_models - 2]
+    level_accept: np.ndarray     # [n_models-1, B]
+    level_next: np.ndarray       # [n_models-1, B]
+
+
+def hsd_verify(models: Sequence[np.ndarray], draft_tokens, seed, temperature, tau: Sequence[float],
+               row_temperature=None, seq_base=0, num_threads=0) -> HsdResult:
+    """Hierarchical verify: models[0] is the smallest drafter [B,gamma,V], models[k] has gamma+k rows."""
+    arrs, dts = zip(*[_logits(m) for m in models])
+    assert len(set(dts)) == 1
+    n = len(arrs)
+    B, g, V = arrs[0].shape
+    for k, m in enumerate(arrs):
+        assert m.shape == (B, g + k, V), (k, m.shape)
+    tok = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+    rowT = None if row_temperature is None else np.ascontiguousarray(row_temperature, dtype=np.float32)
+    tau_a = np.ascontiguousarray(tau, dtype=np.float32)
+    assert tau_a.shape == (n - 1,)
+    ptrs = (C.c_void_p * n)(*[m.ctypes.data for m in arrs])
+    L, gmax = n - 1, g + n - 2
+    r = HsdResult(tokens=np.zeros((B, g + n - 1), np.int32), accept_len=np.zeros(B, np.int32),
+                  next_token=np.zeros(B, np.int32), entropy=np.zeros((L, B, gmax), np.float32),
+                  level_accept=np.zeros((L, B), np.int32), level_next=np.zeros((L, B), np.int32))
+    rc = lib().oracle_hsd_verify(C.addressof(ptrs), None, n, dts[0], _ptr(tok), int(seed), int(seq_base),
+                                 B, g, V, _ptr(rowT), float(temperature), _ptr(tau_a),
+                                 _ptr(r.tokens), _ptr(r.accept_len), _ptr(r.next_token), _ptr(r.entropy),
+                                 _ptr(r.level_accept), _ptr(r.level_next), int(num_threads))
+    if rc != 0:
+        raise ValueError("oracle_hsd_verify rejected its arguments")
+    return r
+
+
+def max_threads() -> int:
+    return int(lib().oracle_max_threads())
