@@ -1,0 +1,196 @@
+/*
+ * hola.h -- C ABI of libhola.so: the batched verify step of HOLA's Hierarchical
+ * Speculative Decoding (HSD) on one AMD MI355X (gfx950).
+ *
+ * What one call computes, for B sequences each carrying gamma drafted tokens over a
+ * vocabulary of V entries (paper Section 3.1 "HSD Module", Algorithm 1 Step 1, Equation (1)):
+ *
+ *   1. p = softmax(target_logits / T) and q = softmax(draft_logits / T) per position
+ *      (temperature scaling is not in the paper; T = 1 reproduces it);
+ *   2. the entropy of the DRAFT distribution, H = -sum_i q_i ln q_i, per position
+ *      (Section 3.1; natural log, so the threshold is in nats);
+ *   3. the entropy gate g = 1[H < tau], strict (Algorithm 1 Step 1; Section 4.3 for tau);
+ *   4. Equation (1): gate = 1 keeps the drafted token without consulting the verifier;
+ *      gate = 0 falls back to the verifier, here the draft-and-verify acceptance test
+ *      u * q(x) < p(x) with u uniform on [0,1);
+ *   5. the first position that is neither gated nor accepted ends the sequence
+ *      (accept_len = number of drafts kept);
+ *   6. the next token: at a rejection, drawn by inverse CDF from max(0, p - q) / Z at that
+ *      position; when all drafts were kept, a bonus token drawn from p at position len;
+ *   7. "Hierarchical": the kept tokens plus the next token of one level are the drafts of
+ *      the next level, verified by the next larger model (hola_hsd_verify).
+ *
+ * Uniforms: Philox4x32-10 with key = (seed low, seed high) and counter =
+ * (position, sequence low, sequence high, level), sequence = seq_base + b; output word 0
+ * drives the acceptance test of that position, word 1 the sample taken at that position;
+ * each is reduced to 24 bits, u = (word >> 8) * 2^-24.
+ *
+ * Layout.  All tensors are row-major and contiguous unless a leading dimension is given:
+ *   target_logits [B, gamma+1, V]   (row gamma is the bonus position)
+ *   draft_logits  [B, gamma,   V]
+ *   draft_tokens  [B, gamma]        int32
+ *   out_accept_len[B], out_next_token[B]  int32;  out_entropy [B, gamma] float (nats)
+ * bf16 logits are passed as raw 16-bit patterns.  gamma <= 32.
+ *
+ * Ownership and memory spaces.  Every pointer named "device" is caller-owned DEVICE memory
+ * (for PyTorch: tensor.data_ptr()); host pointers are marked "host".  The library never
+ * frees caller memory.  hola_verify_f32 / hola_verify_bf16 use one library-owned workspace
+ * per device, allocated on first use and grown when a larger shape arrives (hipMalloc; not on
+ * the steady-state path), released by hola_shutdown().  hola_verify_ex and hola_hsd_verify
+ * use the caller's workspace only and never allocate.
+ *
+ * Asynchrony.  All work is enqueued on `stream`; nothing synchronises with the host.
+ * Outputs are valid once the stream has been synchronised; inputs and the workspace must
+ * stay alive and unmodified until then.  Calls sharing a workspace must be on one stream
+ * (or otherwise ordered).
+ *
+ * Errors.  Return codes only.  Argument errors (a required pointer NULL, B < 0, gamma < 1 or
+ * > 32, V < 1, a negative or NaN temperature, NaN tau, a leading dimension < V, a logits
+ * pointer not aligned to its element size, a workspace that is too small or not 256-byte
+ * aligned) are detected on the host before any launch and leave the outputs untouched.
+ * HIP launch or allocation failures return HOLA_ERR_HIP; hola_last_hip_error() names the last
+ * one seen by the calling thread.  B == 0 is a successful no-op.
+ * Data problems cannot be reported synchronously: a drafted token outside [0, V) has
+ * p(x) = 0 (never ratio-accepted, still gate-acceptable); a target row with no finite
+ * probability mass yields next_token = -1; -inf logits are allowed (masked vocabulary);
+ * +inf or NaN logits give NaN statistics for that row (never a fault).
+ */
+#ifndef HOLA_H
+#define HOLA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ihipStream_t* hola_stream_t;   /* == hipStream_t; NULL is the default stream */
+
+typedef enum {
+    HOLA_OK = 0,
+    HOLA_ERR_INVALID_ARG = 1,
+    HOLA_ERR_UNSUPPORTED = 2,
+    HOLA_ERR_WORKSPACE = 3,
+    HOLA_ERR_HIP = 4
+} hola_status;
+
+enum { HOLA_DTYPE_F32 = 0, HOLA_DTYPE_BF16 = 1 };
+enum { HOLA_MAX_GAMMA = 32 };
+
+/* One verify level on float logits.  Steps 1-6 above with a single temperature (> 0) and
+ * threshold; seq_base = 0, level = 0.  All pointers device; stream may be NULL. */
+hola_status hola_verify_f32(const float* target_logits, const float* draft_logits,
+                            const int32_t* draft_tokens, uint64_t seed,
+                            int32_t B, int32_t gamma, int32_t V,
+                            float temperature, float entropy_threshold,
+                            int32_t* out_accept_len, int32_t* out_next_token, float* out_entropy,
+                            hola_stream_t stream);
+
+/* Same on bfloat16 logits given as raw 16-bit patterns. */
+hola_status hola_verify_bf16(const uint16_t* target_logits, const uint16_t* draft_logits,
+                             const int32_t* draft_tokens, uint64_t seed,
+                             int32_t B, int32_t gamma, int32_t V,
+                             float temperature, float entropy_threshold,
+                             int32_t* out_accept_len, int32_t* out_next_token, float* out_entropy,
+                             hola_stream_t stream);
+
+/* Extended form of one verify level. */
+typedef struct {
+    const void* target_logits;      /* device [B, gamma+1, V] */
+    const void* draft_logits;       /* device [B, gamma,   V] */
+    int32_t dtype;                  /* HOLA_DTYPE_F32 | HOLA_DTYPE_BF16 */
+    int64_t target_ld, draft_ld;    /* row stride in elements, >= V; 0 => V */
+    const int32_t* draft_tokens;    /* device [B, gamma] */
+    const int32_t* draft_len;       /* device [B], each in [0, gamma]; NULL => gamma everywhere */
+    const float* row_temperature;   /* device [B]; NULL => `temperature` everywhere.  An entry of
+                                       0 marks a greedy row: accept iff token == argmax(target) (lowest
+                                       index on ties), next token = argmax at the stop row, gate entropy
+                                       taken at T = 1 */
+    const double* draft_stats_in;   /* device [B, gamma, 2] = (lse, H) of the draft rows in nats, as a
+                                       previous level's target_stats_out produced them; NULL => computed
+                                       here.  When given, the draft rows are read only for the gathers and
+                                       at the stop row */
+    double* target_stats_out;       /* device [B, gamma+1, 2] = (lse, H) of the target rows j <= len;
+                                       NULL => not wanted */
+    uint64_t seed;
+    uint32_t level;                 /* Philox counter word 3 */
+    int64_t seq_base;               /* global index of sequence 0 of this call (Philox counter words 1,2) */
+    int32_t B, gamma, V;
+    float temperature;              /* >= 0; used where row_temperature is NULL */
+    float entropy_threshold;        /* tau, nats.  tau <= 0 never gates; +inf gates everything */
+    int32_t* out_accept_len;        /* device [B] */
+    int32_t* out_next_token;        /* device [B] */
+    float* out_entropy;             /* device [B, entropy_ld]: draft entropy for j < len, -1 beyond; NULL ok */
+    int64_t entropy_ld;             /* row stride of out_entropy in elements, >= gamma; 0 => gamma */
+    void* workspace;                /* device, 256-byte aligned, >= hola_workspace_bytes(B, gamma, V) */
+    size_t workspace_bytes;
+    hola_stream_t stream;
+} hola_verify_args;
+
+/* Bytes of workspace hola_verify_ex needs for this shape (either dtype); 0 on invalid shape. */
+size_t hola_workspace_bytes(int32_t B, int32_t gamma, int32_t V);
+
+hola_status hola_verify_ex(const hola_verify_args* args /* host */);
+
+/* Hierarchical driver (step 7).  models[0] is the smallest drafter, models[n_models-1] the
+ * target; n_models - 1 verify levels.  models[k].logits is device [B, gamma+k, V].
+ * Level k (1-based) verifies with models[k] the drafts level k-1 produced (its kept tokens
+ * followed by its next token; level 1 takes draft_tokens), gated by tau[k-1] on the entropy of
+ * models[k-1], with Philox level word k-1.  The statistics of each middle model are computed
+ * once, when it is the target, and reused when it is the draft. */
+typedef struct {
+    const void* logits;             /* device */
+    int64_t ld;                     /* row stride in elements; 0 => V */
+} hola_model_logits;
+
+hola_status hola_hsd_verify(const hola_model_logits* models /* host array */, int32_t n_models, int32_t dtype,
+                            const int32_t* draft_tokens /* device [B, gamma], drawn from models[0] */,
+                            uint64_t seed, int64_t seq_base, int32_t B, int32_t gamma, int32_t V,
+                            const float* row_temperature /* device [B] or NULL */, float temperature,
+                            const float* tau /* host array [n_models-1] */,
+                            int32_t* out_tokens     /* device [B, gamma+n_models-1]: the last level's drafts, -1 beyond */,
+                            int32_t* out_accept_len /* device [B], last level */,
+                            int32_t* out_next_token /* device [B], last level */,
+                            float* out_entropy      /* device [n_models-1, B, gamma+n_models-2], -1 where unused; NULL ok */,
+                            void* workspace, size_t workspace_bytes, hola_stream_t stream);
+
+size_t hola_hsd_workspace_bytes(int32_t n_models, int32_t B, int32_t gamma, int32_t V);
+
+/* Row statistics alone (steps 1-2): (lse, H) in nats of softmax(logits[r, :] / T) for R rows,
+ * written to stats_out as device [R, 2] doubles.  Greedy convention does not apply (T > 0).
+ * workspace as for hola_verify_ex with B = R, gamma = 1. */
+hola_status hola_row_stats(const void* logits /* device [R, V] */, int32_t dtype, int64_t ld,
+                           int32_t R, int32_t V, float temperature,
+                           double* stats_out /* device [R, 2] */,
+                           void* workspace, size_t workspace_bytes, hola_stream_t stream);
+
+/* Launch-shape knobs.  Zero in a field keeps the built-in choice for MI355X. */
+typedef struct {
+    int32_t stats_split;            /* workgroups per logits row in the row-statistics kernel */
+    int32_t stats_unroll;           /* 16-byte loads in flight per lane there: 2, 4 or 8 */
+    int32_t stats_single_c;         /* 1: single-constant exponent scaling (faster, entropy error up to ~1e-6) */
+    int32_t sampler_tile_chunks;    /* reserved */
+} hola_tuning;
+hola_status hola_set_tuning(const hola_tuning* t /* host; NULL restores defaults */);
+
+/* Per-kernel timing aid for benchmarks.  While enabled, each call records HIP events around
+ * each of its kernels on the call's stream.  hola_profile_collect() waits for the recorded
+ * events, ADDS elapsed milliseconds and launch counts per stage to the host arrays, and
+ * forgets the events.  Stages: 0 row statistics, 1 accept/first-reject, 2 residual tile sums,
+ * 3 inverse-CDF select, 4 level glue. */
+enum { HOLA_N_STAGES = 5 };
+hola_status hola_profile_enable(int32_t on);
+hola_status hola_profile_collect(double* ms_out /* host [HOLA_N_STAGES] */, int64_t* launches_out /* host [HOLA_N_STAGES] */);
+
+/* Frees the library-owned workspaces and profiling events of every device. */
+void hola_shutdown(void);
+
+const char* hola_status_string(hola_status s);
+const char* hola_last_hip_error(void);
+const char* hola_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HOLA_H */

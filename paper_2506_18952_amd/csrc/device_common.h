@@ -1,0 +1,99 @@
+// Device-side helpers for the gfx950 kernels of libhola.so: logit unpacking, the scaled
+// exponent, 64-lane reductions and scans, Philox4x32-10.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hola {
+
+constexpr double kLog2e = 1.4426950408889634074;
+constexpr double kLn2 = 0.69314718055994530942;
+
+__device__ __forceinline__ float bits_f32(uint32_t u) { return __uint_as_float(u); }
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// 2^y on the transcendental unit (v_exp_f32); y below -126 gives 0.
+__device__ __forceinline__ float fast_exp2(float y) { return __builtin_amdgcn_exp2f(y); }
+
+// Scaled exponent y = x*c + b with c = c_hi + c_lo carried in two floats: the product with
+// c_hi is added to the reference first, so the small correction lands on a small number.
+template <bool SINGLE_C>
+__device__ __forceinline__ float scaled_exponent(float x, float c_hi, float c_lo, float b)
+{
+    float y = __builtin_fmaf(x, c_hi, b);
+    if (!SINGLE_C) y = __builtin_fmaf(x, c_lo, y);
+    return y;
+}
+
+// Element k (0..EPL-1) of a 16-byte chunk as float.
+template <bool BF16>
+__device__ __forceinline__ float chunk_elem(const uint4& v, int k)
+{
+    if (BF16) {
+        uint32_t w = (k < 2) ? v.x : (k < 4) ? v.y : (k < 6) ? v.z : v.w;
+        return (k & 1) ? bf16_hi(w) : bf16_lo(w);
+    } else {
+        uint32_t w = (k == 0) ? v.x : (k == 1) ? v.y : (k == 2) ? v.z : v.w;
+        return bits_f32(w);
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ float load_logit(const void* base, int64_t idx)
+{
+    if (BF16) return __uint_as_float((uint32_t)((const uint16_t*)base)[idx] << 16);
+    return ((const float*)base)[idx];
+}
+
+// ---- 64-lane wavefront collectives (not on the streaming path) ------------------------------
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_min(float v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v = fminf(v, __shfl_xor(v, m, 64));
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+// Inclusive prefix sum over the lanes of a wavefront.
+__device__ __forceinline__ double wave_inclusive_scan(double v, int lane)
+{
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        double o = __shfl_up(v, d, 64);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// ---- Philox4x32-10 (Salmon et al., SC'11) ---------------------------------------------------
+struct Philox4 { uint32_t x, y, z, w; };
+
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1)
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    return Philox4{c0, c1, c2, c3};
+}
+
+// Uniform on the 24-bit lattice in [0,1): exact in float and double.
+__device__ __forceinline__ float u24(uint32_t r) { return (float)(r >> 8) * 5.9604644775390625e-8f; }
+
+}  // namespace hola

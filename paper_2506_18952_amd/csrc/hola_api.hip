@@ -1,0 +1,463 @@
+// Host side of libhola.so: the C ABI, argument checks, workspace carving, the per-level launch
+// sequence and the hierarchical level driver.  No host synchronisation and no allocation on the
+// steady-state path; everything is enqueued on the caller's stream.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "device_common.h"
+#include "hola_internal.h"
+
+namespace hola {
+
+// ---------------------------------------------------------------------------------------------
+// small device kernels of the driver
+// ---------------------------------------------------------------------------------------------
+__global__ void fill_f32_kernel(float* p, int64_t n, float v)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// Drafts of the next level: the kept tokens of this level followed by its next token.
+__global__ void level_glue_kernel(const int32_t* __restrict__ cur_tok, int32_t gk, const int32_t* __restrict__ acc,
+                                  const int32_t* __restrict__ nxt, int32_t B, int32_t* __restrict__ new_tok,
+                                  int32_t* __restrict__ new_len)
+{
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int a = acc[b];
+    a = a < 0 ? 0 : (a > gk ? gk : a);
+    for (int j = 0; j <= gk; ++j)
+        new_tok[(int64_t)b * (gk + 1) + j] = j < a ? cur_tok[(int64_t)b * gk + j] : (j == a ? nxt[b] : -1);
+    new_len[b] = a + 1;
+}
+
+__global__ void export_tokens_kernel(const int32_t* __restrict__ tok, int32_t gk, const int32_t* __restrict__ len,
+                                     int32_t B, int32_t width, int32_t* __restrict__ out)
+{
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int l = len ? len[b] : gk;
+    for (int j = 0; j < width; ++j) out[(int64_t)b * width + j] = (j < l && j < gk) ? tok[(int64_t)b * gk + j] : -1;
+}
+
+// ---------------------------------------------------------------------------------------------
+// process-wide state
+// ---------------------------------------------------------------------------------------------
+static thread_local char g_last_hip[256] = "";
+static Tuning g_tuning;
+static std::mutex g_mu;
+
+struct DeviceWs { void* ptr = nullptr; size_t bytes = 0; };
+static DeviceWs g_ws[64];
+
+struct ProfEvent { int stage; hipEvent_t a, b; };
+static bool g_prof_on = false;
+static std::vector<ProfEvent> g_prof_live;
+static std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_free;
+
+static hola_status hip_fail(hipError_t e, const char* what)
+{
+    snprintf(g_last_hip, sizeof g_last_hip, "%s: %s", what, hipGetErrorString(e));
+    return HOLA_ERR_HIP;
+}
+
+struct StageTimer {
+    int stage; hipStream_t s; bool on; hipEvent_t a = nullptr, b = nullptr;
+    StageTimer(int stage_, hipStream_t s_) : stage(stage_), s(s_), on(g_prof_on)
+    {
+        if (!on) return;
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (!g_prof_free.empty()) { a = g_prof_free.back().first; b = g_prof_free.back().second; g_prof_free.pop_back(); }
+        else if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
+        hipEventRecord(a, s);
+    }
+    ~StageTimer()
+    {
+        if (!on) return;
+        hipEventRecord(b, s);
+        std::lock_guard<std::mutex> lk(g_mu);
+        g_prof_live.push_back(ProfEvent{stage, a, b});
+    }
+};
+
+static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static Workspace carve(void* base, int32_t B, int32_t gamma, int32_t V)
+{
+    Workspace w;
+    char* p = (char*)base;
+    size_t off = 0;
+    const size_t rows = (size_t)B * (2 * (size_t)gamma + 1);
+    const int ntiles = sampler_tiles(V, HOLA_DTYPE_F32);       // the larger of the two dtypes
+    w.partials = (Partial*)(p + off); off = align_up(off + rows * kMaxSplit * kWaves * sizeof(Partial));
+    w.statsD = (double*)(p + off);    off = align_up(off + (size_t)B * gamma * 2 * sizeof(double));
+    w.statsP = (double*)(p + off);    off = align_up(off + (size_t)B * (gamma + 1) * 2 * sizeof(double));
+    w.argmaxP = (int32_t*)(p + off);  off = align_up(off + (size_t)B * (gamma + 1) * sizeof(int32_t));
+    w.seq = (SeqInfo*)(p + off);      off = align_up(off + (size_t)B * sizeof(SeqInfo));
+    w.tiles = (double*)(p + off);     off = align_up(off + (size_t)B * ntiles * sizeof(double));
+    w.bytes = off;
+    return w;
+}
+
+static bool shape_ok(int32_t B, int32_t gamma, int32_t V)
+{
+    return B >= 0 && gamma >= 1 && gamma <= HOLA_MAX_GAMMA && V >= 1;
+}
+
+static hola_status check_args(const hola_verify_args& a)
+{
+    if (!shape_ok(a.B, a.gamma, a.V)) return HOLA_ERR_INVALID_ARG;
+    if (a.dtype != HOLA_DTYPE_F32 && a.dtype != HOLA_DTYPE_BF16) return HOLA_ERR_UNSUPPORTED;
+    if (a.B == 0) return HOLA_OK;
+    if (!a.target_logits || !a.draft_logits || !a.draft_tokens || !a.out_accept_len || !a.out_next_token)
+        return HOLA_ERR_INVALID_ARG;
+    const size_t es = a.dtype == HOLA_DTYPE_BF16 ? 2 : 4;
+    if (((uintptr_t)a.target_logits % es) || ((uintptr_t)a.draft_logits % es)) return HOLA_ERR_INVALID_ARG;
+    if ((a.target_ld && a.target_ld < a.V) || (a.draft_ld && a.draft_ld < a.V)) return HOLA_ERR_INVALID_ARG;
+    if (a.entropy_ld && a.entropy_ld < a.gamma) return HOLA_ERR_INVALID_ARG;
+    if (!(a.temperature >= 0.f) || std::isinf(a.temperature)) return HOLA_ERR_INVALID_ARG;   // rejects NaN too
+    if (std::isnan(a.entropy_threshold)) return HOLA_ERR_INVALID_ARG;
+    if (!a.workspace || ((uintptr_t)a.workspace & 255)) return HOLA_ERR_WORKSPACE;
+    if (a.workspace_bytes < hola_workspace_bytes(a.B, a.gamma, a.V)) return HOLA_ERR_WORKSPACE;
+    return HOLA_OK;
+}
+
+static hola_status run_level(const hola_verify_args& a)
+{
+    hola_status st = check_args(a);
+    if (st != HOLA_OK || a.B == 0) return st;
+    hipStream_t s = (hipStream_t)a.stream;
+    const Workspace w = carve(a.workspace, a.B, a.gamma, a.V);
+    const int64_t tld = a.target_ld ? a.target_ld : a.V, dld = a.draft_ld ? a.draft_ld : a.V;
+    const int skip_draft = a.draft_stats_in ? 1 : 0;
+    const int64_t rows = (int64_t)a.B * (skip_draft ? a.gamma + 1 : 2 * a.gamma + 1);
+    Tuning tune;
+    { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
+    const int nsplit = choose_split(rows, a.V, a.dtype, tune);
+
+    RowStatsParams rs{};
+    rs.target = a.target_logits; rs.draft = a.draft_logits; rs.target_ld = tld; rs.draft_ld = dld;
+    rs.draft_len = a.draft_len; rs.row_temperature = a.row_temperature; rs.temperature = a.temperature;
+    rs.B = a.B; rs.gamma = a.gamma; rs.V = a.V; rs.nsplit = nsplit; rs.skip_draft = skip_draft;
+    rs.partials = w.partials;
+    hipError_t e;
+    { StageTimer t(0, s); e = launch_row_stats(rs, a.dtype, tune, s); }
+    if (e != hipSuccess) return hip_fail(e, "row statistics launch");
+
+    AcceptParams ap{};
+    ap.target = a.target_logits; ap.draft = a.draft_logits; ap.dtype = a.dtype; ap.target_ld = tld; ap.draft_ld = dld;
+    ap.tokens = a.draft_tokens; ap.draft_len = a.draft_len; ap.row_temperature = a.row_temperature;
+    ap.draft_stats_in = a.draft_stats_in; ap.target_stats_out = a.target_stats_out;
+    ap.seed = a.seed; ap.level = a.level; ap.seq_base = a.seq_base;
+    ap.B = a.B; ap.gamma = a.gamma; ap.V = a.V; ap.nparts = nsplit * kWaves;
+    ap.temperature = a.temperature; ap.tau = a.entropy_threshold;
+    ap.partials = w.partials; ap.statsD = w.statsD; ap.statsP = w.statsP; ap.argmaxP = w.argmaxP; ap.seq = w.seq;
+    ap.out_accept_len = a.out_accept_len; ap.out_next_token = a.out_next_token;
+    ap.out_entropy = a.out_entropy; ap.entropy_ld = a.entropy_ld;
+    { StageTimer t(1, s); e = launch_accept(ap, s); }
+    if (e != hipSuccess) return hip_fail(e, "accept launch");
+
+    SamplerParams sp{};
+    sp.target = a.target_logits; sp.draft = a.draft_logits; sp.dtype = a.dtype; sp.target_ld = tld; sp.draft_ld = dld;
+    sp.row_temperature = a.row_temperature; sp.temperature = a.temperature;
+    sp.B = a.B; sp.gamma = a.gamma; sp.V = a.V; sp.ntiles = sampler_tiles(a.V, a.dtype);
+    sp.seq = w.seq; sp.tiles = w.tiles; sp.out_next_token = a.out_next_token;
+    { StageTimer t(2, s); e = launch_tile_sums(sp, s); }
+    if (e != hipSuccess) return hip_fail(e, "tile sums launch");
+    { StageTimer t(3, s); e = launch_select(sp, s); }
+    if (e != hipSuccess) return hip_fail(e, "select launch");
+    return HOLA_OK;
+}
+
+// Library-owned workspace of the current device for the short forms.
+static hola_status own_workspace(size_t need, void** out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= 64) return HOLA_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lk(g_mu);
+    DeviceWs& d = g_ws[dev];
+    if (d.bytes < need) {
+        if (d.ptr) { e = hipFree(d.ptr); d.ptr = nullptr; d.bytes = 0; if (e != hipSuccess) return hip_fail(e, "hipFree"); }
+        size_t want = need + need / 4;
+        e = hipMalloc(&d.ptr, want);
+        if (e != hipSuccess) { d.ptr = nullptr; return hip_fail(e, "hipMalloc(workspace)"); }
+        d.bytes = want;
+    }
+    *out = d.ptr;
+    return HOLA_OK;
+}
+
+static hola_status verify_short(const void* target, const void* draft, int dtype, const int32_t* tokens, uint64_t seed,
+                                int32_t B, int32_t gamma, int32_t V, float temperature, float tau,
+                                int32_t* out_accept_len, int32_t* out_next_token, float* out_entropy, hola_stream_t stream)
+{
+    if (!shape_ok(B, gamma, V)) return HOLA_ERR_INVALID_ARG;
+    if (!(temperature > 0.f)) return HOLA_ERR_INVALID_ARG;     // the short forms have no greedy rows
+    if (B == 0) return HOLA_OK;
+    hola_verify_args a;
+    memset(&a, 0, sizeof a);
+    a.target_logits = target; a.draft_logits = draft; a.dtype = dtype;
+    a.draft_tokens = tokens; a.seed = seed; a.B = B; a.gamma = gamma; a.V = V;
+    a.temperature = temperature; a.entropy_threshold = tau;
+    a.out_accept_len = out_accept_len; a.out_next_token = out_next_token; a.out_entropy = out_entropy;
+    a.stream = stream;
+    // argument errors first, so that a bad call never allocates
+    a.workspace = (void*)(uintptr_t)256; a.workspace_bytes = (size_t)-1;
+    hola_status st = check_args(a);
+    if (st != HOLA_OK) return st;
+    a.workspace_bytes = hola_workspace_bytes(B, gamma, V);
+    st = own_workspace(a.workspace_bytes, &a.workspace);
+    if (st != HOLA_OK) return st;
+    return run_level(a);
+}
+
+}  // namespace hola
+
+using namespace hola;
+
+extern "C" {
+
+size_t hola_workspace_bytes(int32_t B, int32_t gamma, int32_t V)
+{
+    if (!shape_ok(B, gamma, V)) return 0;
+    return carve(nullptr, B, gamma, V).bytes + 256;
+}
+
+hola_status hola_verify_ex(const hola_verify_args* args)
+{
+    if (!args) return HOLA_ERR_INVALID_ARG;
+    return run_level(*args);
+}
+
+hola_status hola_verify_f32(const float* target_logits, const float* draft_logits, const int32_t* draft_tokens,
+                            uint64_t seed, int32_t B, int32_t gamma, int32_t V, float temperature,
+                            float entropy_threshold, int32_t* out_accept_len, int32_t* out_next_token,
+                            float* out_entropy, hola_stream_t stream)
+{
+    return verify_short(target_logits, draft_logits, HOLA_DTYPE_F32, draft_tokens, seed, B, gamma, V, temperature,
+                        entropy_threshold, out_accept_len, out_next_token, out_entropy, stream);
+}
+
+hola_status hola_verify_bf16(const uint16_t* target_logits, const uint16_t* draft_logits, const int32_t* draft_tokens,
+                             uint64_t seed, int32_t B, int32_t gamma, int32_t V, float temperature,
+                             float entropy_threshold, int32_t* out_accept_len, int32_t* out_next_token,
+                             float* out_entropy, hola_stream_t stream)
+{
+    return verify_short(target_logits, draft_logits, HOLA_DTYPE_BF16, draft_tokens, seed, B, gamma, V, temperature,
+                        entropy_threshold, out_accept_len, out_next_token, out_entropy, stream);
+}
+
+// Workspace of the hierarchical driver: one level workspace at the widest level, two token / length /
+// statistics buffers that alternate between levels.
+namespace {
+struct HsdWs {
+    void* level; size_t level_bytes;
+    int32_t* tok[2]; int32_t* len[2]; double* stats[2];
+    size_t bytes;
+};
+HsdWs carve_hsd(void* base, int32_t n_models, int32_t B, int32_t gamma, int32_t V)
+{
+    HsdWs h;
+    const int32_t gmax = gamma + n_models - 2;
+    char* p = (char*)base;
+    size_t off = 0;
+    h.level = p; h.level_bytes = hola_workspace_bytes(B, gmax, V); off = align_up(h.level_bytes);
+    for (int i = 0; i < 2; ++i) { h.tok[i] = (int32_t*)(p + off); off = align_up(off + (size_t)B * (gmax + 1) * sizeof(int32_t)); }
+    for (int i = 0; i < 2; ++i) { h.len[i] = (int32_t*)(p + off); off = align_up(off + (size_t)B * sizeof(int32_t)); }
+    for (int i = 0; i < 2; ++i) { h.stats[i] = (double*)(p + off); off = align_up(off + (size_t)B * (gmax + 1) * 2 * sizeof(double)); }
+    h.bytes = off;
+    return h;
+}
+}  // namespace
+
+size_t hola_hsd_workspace_bytes(int32_t n_models, int32_t B, int32_t gamma, int32_t V)
+{
+    if (n_models < 2 || !shape_ok(B, gamma, V) || gamma + n_models - 2 > HOLA_MAX_GAMMA) return 0;
+    return carve_hsd(nullptr, n_models, B, gamma, V).bytes + 256;
+}
+
+hola_status hola_hsd_verify(const hola_model_logits* models, int32_t n_models, int32_t dtype,
+                            const int32_t* draft_tokens, uint64_t seed, int64_t seq_base, int32_t B, int32_t gamma,
+                            int32_t V, const float* row_temperature, float temperature, const float* tau,
+                            int32_t* out_tokens, int32_t* out_accept_len, int32_t* out_next_token, float* out_entropy,
+                            void* workspace, size_t workspace_bytes, hola_stream_t stream)
+{
+    if (!models || !tau || n_models < 2 || !shape_ok(B, gamma, V) || gamma + n_models - 2 > HOLA_MAX_GAMMA)
+        return HOLA_ERR_INVALID_ARG;
+    if (dtype != HOLA_DTYPE_F32 && dtype != HOLA_DTYPE_BF16) return HOLA_ERR_UNSUPPORTED;
+    if (B == 0) return HOLA_OK;
+    if (!draft_tokens || !out_accept_len || !out_next_token) return HOLA_ERR_INVALID_ARG;
+    for (int k = 0; k < n_models; ++k) {
+        if (!models[k].logits) return HOLA_ERR_INVALID_ARG;
+        if (models[k].ld && models[k].ld < V) return HOLA_ERR_INVALID_ARG;
+        if (k < n_models - 1 && std::isnan(tau[k])) return HOLA_ERR_INVALID_ARG;
+    }
+    if (!(temperature >= 0.f) || std::isinf(temperature)) return HOLA_ERR_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace & 255)) return HOLA_ERR_WORKSPACE;
+    if (workspace_bytes < hola_hsd_workspace_bytes(n_models, B, gamma, V)) return HOLA_ERR_WORKSPACE;
+
+    hipStream_t s = (hipStream_t)stream;
+    const int L = n_models - 1;
+    const int32_t gmax = gamma + L - 1;
+    const HsdWs h = carve_hsd(workspace, n_models, B, gamma, V);
+    const int tpb = 128, nb = (B + tpb - 1) / tpb;
+    if (out_entropy) {
+        const int64_t n = (int64_t)L * B * gmax;
+        StageTimer t(4, s);
+        hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, out_entropy, n, -1.0f);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "fill launch");
+    }
+    const int32_t* cur_tok = draft_tokens;
+    const int32_t* cur_len = nullptr;
+    const double* cur_stats = nullptr;
+    for (int k = 1; k <= L; ++k) {
+        const int32_t gk = gamma + k - 1;
+        hola_verify_args a;
+        memset(&a, 0, sizeof a);
+        a.target_logits = models[k].logits; a.draft_logits = models[k - 1].logits; a.dtype = dtype;
+        a.target_ld = models[k].ld; a.draft_ld = models[k - 1].ld;
+        a.draft_tokens = cur_tok; a.draft_len = cur_len; a.row_temperature = row_temperature;
+        a.draft_stats_in = cur_stats;
+        a.target_stats_out = (k < L) ? h.stats[k & 1] : nullptr;
+        a.seed = seed; a.level = (uint32_t)(k - 1); a.seq_base = seq_base;
+        a.B = B; a.gamma = gk; a.V = V; a.temperature = temperature; a.entropy_threshold = tau[k - 1];
+        a.out_accept_len = out_accept_len; a.out_next_token = out_next_token;
+        a.out_entropy = out_entropy ? out_entropy + (int64_t)(k - 1) * B * gmax : nullptr;
+        a.entropy_ld = gmax;
+        a.workspace = h.level; a.workspace_bytes = h.level_bytes; a.stream = stream;
+        hola_status st = run_level(a);
+        if (st != HOLA_OK) return st;
+        if (k < L) {
+            StageTimer t(4, s);
+            hipLaunchKernelGGL(level_glue_kernel, dim3(nb), dim3(tpb), 0, s, cur_tok, gk, out_accept_len, out_next_token,
+                               B, h.tok[k & 1], h.len[k & 1]);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return hip_fail(e, "glue launch");
+            cur_tok = h.tok[k & 1];
+            cur_len = h.len[k & 1];
+            cur_stats = h.stats[k & 1];
+        }
+    }
+    if (out_tokens) {
+        StageTimer t(4, s);
+        hipLaunchKernelGGL(export_tokens_kernel, dim3(nb), dim3(tpb), 0, s, cur_tok, gmax, cur_len, B, gamma + L, out_tokens);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "export launch");
+    }
+    return HOLA_OK;
+}
+
+hola_status hola_row_stats(const void* logits, int32_t dtype, int64_t ld, int32_t R, int32_t V, float temperature,
+                           double* stats_out, void* workspace, size_t workspace_bytes, hola_stream_t stream)
+{
+    if (R < 0 || V < 1) return HOLA_ERR_INVALID_ARG;
+    if (dtype != HOLA_DTYPE_F32 && dtype != HOLA_DTYPE_BF16) return HOLA_ERR_UNSUPPORTED;
+    if (R == 0) return HOLA_OK;
+    if (!logits || !stats_out || !(temperature > 0.f) || std::isinf(temperature)) return HOLA_ERR_INVALID_ARG;
+    if (ld && ld < V) return HOLA_ERR_INVALID_ARG;
+    if ((uintptr_t)logits % (dtype == HOLA_DTYPE_BF16 ? 2 : 4)) return HOLA_ERR_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace & 255)) return HOLA_ERR_WORKSPACE;
+    if (workspace_bytes < hola_workspace_bytes(R, 1, V)) return HOLA_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const Workspace w = carve(workspace, R, 1, V);
+    Tuning tune;
+    { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
+    const int nsplit = choose_split(R, V, dtype, tune);
+    // R plain rows are laid out as R "sequences" with no draft and one target row each.
+    RowStatsParams rs{};
+    rs.target = logits; rs.draft = logits; rs.target_ld = ld ? ld : V; rs.draft_ld = rs.target_ld;
+    rs.temperature = temperature; rs.B = R; rs.gamma = 0; rs.V = V; rs.nsplit = nsplit; rs.skip_draft = 1;
+    rs.partials = w.partials;
+    hipError_t e;
+    { StageTimer t(0, s); e = launch_row_stats(rs, dtype, tune, s); }
+    if (e != hipSuccess) return hip_fail(e, "row statistics launch");
+    {
+        StageTimer t(1, s);
+        e = launch_finalize_rows(w.partials, nsplit * kWaves, R, stats_out, s);
+    }
+    if (e != hipSuccess) return hip_fail(e, "finalize launch");
+    return HOLA_OK;
+}
+
+hola_status hola_set_tuning(const hola_tuning* t)
+{
+    Tuning n;
+    if (t) {
+        if (t->stats_split < 0 || t->stats_split > kMaxSplit) return HOLA_ERR_INVALID_ARG;
+        if (t->stats_unroll != 0 && t->stats_unroll != 2 && t->stats_unroll != 4 && t->stats_unroll != 8)
+            return HOLA_ERR_INVALID_ARG;
+        n.split = t->stats_split; n.unroll = t->stats_unroll; n.single_c = t->stats_single_c ? 1 : 0;
+    }
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_tuning = n;
+    return HOLA_OK;
+}
+
+hola_status hola_profile_enable(int32_t on)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_prof_on = on != 0;
+    return HOLA_OK;
+}
+
+hola_status hola_profile_collect(double* ms_out, int64_t* launches_out)
+{
+    if (!ms_out || !launches_out) return HOLA_ERR_INVALID_ARG;
+    std::vector<ProfEvent> live;
+    { std::lock_guard<std::mutex> lk(g_mu); live.swap(g_prof_live); }
+    hola_status st = HOLA_OK;
+    for (const ProfEvent& ev : live) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(ev.b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.a, ev.b);
+        if (e != hipSuccess) st = hip_fail(e, "profile event");
+        else if (ev.stage >= 0 && ev.stage < HOLA_N_STAGES) { ms_out[ev.stage] += ms; launches_out[ev.stage] += 1; }
+    }
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (const ProfEvent& ev : live) g_prof_free.emplace_back(ev.a, ev.b);
+    return st;
+}
+
+void hola_shutdown(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    int cur = 0;
+    bool have_dev = hipGetDevice(&cur) == hipSuccess;
+    for (int d = 0; d < 64; ++d) {
+        if (!g_ws[d].ptr) continue;
+        if (have_dev) hipSetDevice(d);
+        hipFree(g_ws[d].ptr);
+        g_ws[d].ptr = nullptr; g_ws[d].bytes = 0;
+    }
+    if (have_dev) hipSetDevice(cur);
+    for (auto& ev : g_prof_live) { hipEventDestroy(ev.a); hipEventDestroy(ev.b); }
+    for (auto& ev : g_prof_free) { hipEventDestroy(ev.first); hipEventDestroy(ev.second); }
+    g_prof_live.clear();
+    g_prof_free.clear();
+}
+
+const char* hola_status_string(hola_status s)
+{
+    switch (s) {
+        case HOLA_OK: return "ok";
+        case HOLA_ERR_INVALID_ARG: return "invalid argument";
+        case HOLA_ERR_UNSUPPORTED: return "unsupported";
+        case HOLA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case HOLA_ERR_HIP: return "HIP error";
+    }
+    return "unknown status";
+}
+
+const char* hola_last_hip_error(void) { return g_last_hip; }
+const char* hola_version(void) { return "hola-verify 0.1 (gfx950)"; }
+
+}  // extern "C"

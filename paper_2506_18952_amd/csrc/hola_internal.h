@@ -1,0 +1,97 @@
+// Internal declarations shared by the translation units of libhola.so (host side).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/hola.h"
+
+namespace hola {
+
+constexpr int kWaves = 4;              // wavefronts per workgroup in the streaming kernels
+constexpr int kBlock = 64 * kWaves;    // 256 threads
+constexpr int kMaxSplit = 16;          // workgroups per row, upper bound (sizes the partials)
+constexpr int kTileChunks = 4;         // 16-byte chunks per lane in one sampler tile
+
+// One wavefront's share of a row: the sums are S = sum 2^(x*c + bref), T = sum (x*c + bref) 2^(x*c + bref)
+// with c = log2(e)/T and bref an integer-valued reference chosen so the largest term is O(1).
+struct Partial {
+    double bref, S, T;
+    float vmax;                        // largest logit seen (argmax rows only)
+    int32_t imax;                      // its lowest index
+};
+
+// Per-sequence hand-over from the accept kernel to the sampler.
+struct SeqInfo {
+    double lseP, lseD;                 // natural-log lse of the stop row in target and draft
+    float u;                           // sampling uniform
+    int32_t row;                       // stop row (= accept length)
+    int32_t mode;                      // 0 residual, 1 bonus, 2 nothing to sample (greedy / done)
+    int32_t pad;
+};
+
+struct Shape {
+    int32_t B, gamma, V, dtype;
+    int64_t target_ld, draft_ld;
+    int32_t nsplit;                    // workgroups per row (row statistics)
+    int32_t nparts;                    // partials per row = nsplit * kWaves
+    int32_t ntiles;                    // sampler tiles per row
+};
+
+// Workspace carve-up (all offsets 256-byte aligned).
+struct Workspace {
+    Partial* partials;                 // [(B*gamma) + B*(gamma+1)] * nparts
+    double* statsD;                    // [B, gamma, 2]   (lse, H) nats
+    double* statsP;                    // [B, gamma+1, 2]
+    int32_t* argmaxP;                  // [B, gamma+1]
+    SeqInfo* seq;                      // [B]
+    double* tiles;                     // [B, ntiles]
+    size_t bytes;
+};
+
+struct Tuning {
+    int split = 0, unroll = 0, single_c = 0;
+};
+
+struct RowStatsParams {
+    const void* target; const void* draft;
+    int64_t target_ld, draft_ld;
+    const int32_t* draft_len;          // device or null
+    const float* row_temperature;      // device or null
+    float temperature;
+    int32_t B, gamma, V;
+    int32_t nsplit;
+    int32_t skip_draft;                // draft statistics come from a previous level
+    Partial* partials;
+};
+
+struct AcceptParams {
+    const void* target; const void* draft; int32_t dtype;
+    int64_t target_ld, draft_ld;
+    const int32_t* tokens; const int32_t* draft_len; const float* row_temperature;
+    const double* draft_stats_in; double* target_stats_out;
+    uint64_t seed; uint32_t level; int64_t seq_base;
+    int32_t B, gamma, V, nparts;
+    float temperature, tau;
+    const Partial* partials;
+    double* statsD; double* statsP; int32_t* argmaxP; SeqInfo* seq;
+    int32_t* out_accept_len; int32_t* out_next_token; float* out_entropy; int64_t entropy_ld;
+};
+
+struct SamplerParams {
+    const void* target; const void* draft; int32_t dtype;
+    int64_t target_ld, draft_ld;
+    const float* row_temperature; float temperature;
+    int32_t B, gamma, V, ntiles;
+    const SeqInfo* seq; double* tiles;
+    int32_t* out_next_token;
+};
+
+hipError_t launch_row_stats(const RowStatsParams& p, int dtype, const Tuning& t, hipStream_t s);
+hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
+hipError_t launch_finalize_rows(const Partial* partials, int nparts, int32_t R, double* out, hipStream_t s);
+hipError_t launch_tile_sums(const SamplerParams& p, hipStream_t s);
+hipError_t launch_select(const SamplerParams& p, hipStream_t s);
+
+int choose_split(int64_t rows, int V, int dtype, const Tuning& t);
+int sampler_tiles(int V, int dtype);
+
+}  // namespace hola

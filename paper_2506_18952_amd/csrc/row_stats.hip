@@ -1,0 +1,104 @@
+// Split-row statistics kernel: one streaming pass over every logit of the draft and target rows,
+// one workgroup of 4 wavefronts per (row, segment).  Used when there are too few sequences to give
+// every compute unit a sequence of its own (see fused.hip for that case) and by hola_row_stats.
+//
+// A lane reads 16-byte chunks with workgroup stride, UNROLL of them in flight; each wavefront writes
+// one Partial (stats_device.h), merged later in double by the accept kernel.  HBM-bound: no LDS, no
+// barrier, no matrix cores (there is no contraction here).
+#include "stats_device.h"
+
+namespace hola {
+
+template <bool BF16, bool ARGMAX, int U>
+__device__ __forceinline__ void row_segment(const void* row, int32_t V, int seg, int nsplit, const ExpScale& sc,
+                                            Partial* __restrict__ out /* [kWaves] of this (row, segment) */)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const RowGeom g = make_geom<BF16>(row, V);
+    const int64_t nfull = g.c_end - g.c_first;
+    int64_t per = (nfull + nsplit - 1) / nsplit;            // full chunks per segment,
+    per = (per + kBlock - 1) / kBlock * kBlock;             // a multiple of the workgroup stride
+    int64_t seg_lo = g.c_first + (int64_t)seg * per;
+    int64_t seg_hi = seg_lo + per;
+    if (seg_lo > g.c_end) seg_lo = g.c_end;
+    if (seg_hi > g.c_end) seg_hi = g.c_end;
+    const bool do_edges = (seg == 0 && wave == 0);
+    const Partial res = wave_row_share<BF16, ARGMAX, U>(g, seg_lo + tid, seg_hi, kBlock, do_edges, sc, lane);
+    if (lane == 0) out[wave] = res;
+}
+
+template <bool BF16, int U>
+__global__ __launch_bounds__(kBlock) void row_stats_kernel(RowStatsParams p)
+{
+    const int nsplit = p.nsplit;
+    const int64_t blk = blockIdx.x;
+    const int seg = (int)(blk % nsplit);
+    const int64_t r = blk / nsplit;
+    const int g = p.gamma;
+    const int rows_per_seq = p.skip_draft ? (g + 1) : (2 * g + 1);
+    const int b = (int)(r / rows_per_seq);
+    const int k = (int)(r % rows_per_seq);
+    const bool is_draft = !p.skip_draft && k < g;
+    const int j = is_draft ? k : (p.skip_draft ? k : k - g);
+    int len = p.draft_len ? p.draft_len[b] : g;
+    len = len < 0 ? 0 : (len > g ? g : len);
+    if (is_draft ? (j >= len) : (j > len)) return;          // row not needed (uniform exit)
+
+    const float Tb = p.row_temperature ? p.row_temperature[b] : p.temperature;
+    const bool greedy = !(Tb > 0.f);
+    const ExpScale sc = make_scale(greedy ? kLog2e : kLog2e / (double)Tb);
+    constexpr int ES = BF16 ? 2 : 4;
+    const char* row;
+    int64_t slot;
+    if (is_draft) {
+        row = (const char*)p.draft + ((int64_t)b * g + j) * p.draft_ld * ES;
+        slot = (int64_t)b * g + j;
+    } else {
+        row = (const char*)p.target + ((int64_t)b * (g + 1) + j) * p.target_ld * ES;
+        slot = (int64_t)p.B * g + (int64_t)b * (g + 1) + j;
+    }
+    Partial* out = p.partials + (slot * nsplit + seg) * kWaves;
+    if (greedy && !is_draft) row_segment<BF16, true, U>(row, p.V, seg, nsplit, sc, out);
+    else row_segment<BF16, false, U>(row, p.V, seg, nsplit, sc, out);
+}
+
+int choose_split(int64_t rows, int V, int dtype, const Tuning& t)
+{
+    const int epl = (dtype == HOLA_DTYPE_BF16) ? 8 : 4;
+    const int64_t chunks = ((int64_t)V + epl - 1) / epl;
+    int max_useful = (int)((chunks + kBlock - 1) / kBlock);  // at least one chunk per lane per segment
+    if (max_useful < 1) max_useful = 1;
+    int s = t.split;
+    if (s <= 0) {
+        // Aim for >= 8192 workgroups (32 per compute unit) so the tail of the grid is short, but keep
+        // at least 4 chunks per lane in a segment.
+        s = 1;
+        while (rows * s < 8192 && s < kMaxSplit && chunks / (s * 2) >= (int64_t)kBlock * 4) s *= 2;
+    }
+    if (s > kMaxSplit) s = kMaxSplit;
+    if (s > max_useful) s = max_useful;
+    return s < 1 ? 1 : s;
+}
+
+template <bool BF16>
+static hipError_t launch_typed(const RowStatsParams& p, const Tuning& t, hipStream_t s)
+{
+    const int g = p.gamma;
+    const int64_t rows = (int64_t)p.B * (p.skip_draft ? (g + 1) : (2 * g + 1));
+    const int64_t nblk = rows * p.nsplit;
+    if (nblk <= 0) return hipSuccess;
+    if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+    dim3 grid((unsigned)nblk), block(kBlock);
+    const int U = t.unroll ? t.unroll : 8;
+    if (U == 2) hipLaunchKernelGGL((row_stats_kernel<BF16, 2>), grid, block, 0, s, p);
+    else if (U == 4) hipLaunchKernelGGL((row_stats_kernel<BF16, 4>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((row_stats_kernel<BF16, 8>), grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_row_stats(const RowStatsParams& p, int dtype, const Tuning& t, hipStream_t s)
+{
+    return dtype == HOLA_DTYPE_BF16 ? launch_typed<true>(p, t, s) : launch_typed<false>(p, t, s);
+}
+
+}  // namespace hola

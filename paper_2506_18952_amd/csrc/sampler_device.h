@@ -1,0 +1,239 @@
+// Device code of the next-token sampler (shared by the split kernels and the fused per-sequence kernel):
+// inverse CDF over the residual max(0, p - q) at the first rejected position, or over p at the bonus
+// position when every draft was kept.
+//
+// A row is cut into tiles of 64 lanes x 4 chunks of 16 bytes.  Tile weights are summed in double; the
+// selecting wavefront scans them, finds the tile where the running sum first exceeds u * Z, re-reads
+// only that tile and scans inside it: lanes, then the 4 or 8 elements of one chunk.  Element weights
+// come from one device function, so the sweep and the re-read agree bit for bit.
+//
+// Numerics: p_i = 2^(x_i c - L), L = lse / ln 2 from the accept stage.  The exponent argument is
+// formed against a float reference as in the row statistics (exact bf16 product / fp32 difference);
+// what the reference misses is put back exactly: w_i = 2^rP * max(0, eP_i - kappa eQ_i) with
+// kappa = 2^(rQ - rP) carried as a float pair and the common factor applied to chunk sums in double.
+// Chunk sums are fp32 over 4-8 elements, everything above a chunk is double.
+#pragma once
+#include "stats_device.h"
+
+namespace hola {
+
+struct RowPair {
+    const uint4* Pv; const uint4* Dv;   // 16-byte aligned chunk grids (Dv null => element loads of D)
+    const void* D;                      // draft row (element addressing)
+    int32_t head;                       // elements of chunk 0 that precede the target row
+    int32_t V;
+    int64_t nchunks;                    // chunks that hold at least one element of the row
+    ExpScale sc;
+    float refP, refQ, k_hi, k_lo;
+    double scale;                       // 2^rP
+    int32_t bonus;                      // weights are p itself
+    int32_t ok;                         // the target row has a finite normaliser
+};
+
+// Reference for rows whose log2-normaliser is L: bf16 an integer near -L, fp32 a logit near L / c.
+template <bool BF16>
+__device__ __forceinline__ float ref_for_norm(double L, const ExpScale& sc)
+{
+    return BF16 ? (float)rint(-L) : (float)(L / sc.cstar);
+}
+
+template <bool BF16>
+__device__ __forceinline__ void make_row_pair(RowPair& rp, const void* target, const void* draft, int64_t target_ld,
+                                              int64_t draft_ld, int32_t gamma, int32_t V, float Tb, int b,
+                                              const SeqInfo& si, int force_bonus)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    constexpr int ES = BF16 ? 2 : 4;
+    const int g = gamma;
+    rp.sc = make_scale(kLog2e / (double)Tb);
+    rp.V = V;
+    const char* rowP = (const char*)target + ((int64_t)b * (g + 1) + si.row) * target_ld * ES;
+    const uintptr_t aP = (uintptr_t)rowP;
+    rp.head = (int32_t)((aP & 15) / ES);
+    rp.Pv = (const uint4*)(aP & ~(uintptr_t)15);
+    rp.nchunks = ((int64_t)V + rp.head + N - 1) / N;
+    rp.ok = (si.lseP - si.lseP == 0.0) ? 1 : 0;                      // finite
+    rp.bonus = (force_bonus || si.mode == 1 || !(si.lseD - si.lseD == 0.0)) ? 1 : 0;
+    const double LP = si.lseP / kLn2;
+    rp.refP = ref_for_norm<BF16>(LP, rp.sc);
+    const double rP = -LP - ref_offset<BF16>(rp.refP, rp.sc);          // p_i = 2^(y_i + rP)
+    rp.scale = exp2(rP);
+    rp.Dv = nullptr; rp.D = nullptr; rp.refQ = 0.f; rp.k_hi = 0.f; rp.k_lo = 0.f;
+    if (!rp.bonus) {
+        const int jd = si.row < g ? si.row : g - 1;
+        const char* rowD = (const char*)draft + ((int64_t)b * g + jd) * draft_ld * ES;
+        const uintptr_t aD = (uintptr_t)rowD;
+        rp.D = rowD;
+        if ((int32_t)((aD & 15) / ES) == rp.head) rp.Dv = (const uint4*)(aD & ~(uintptr_t)15);
+        const double LD = si.lseD / kLn2;
+        rp.refQ = ref_for_norm<BF16>(LD, rp.sc);
+        const double rQ = -LD - ref_offset<BF16>(rp.refQ, rp.sc);
+        const double kappa = exp2(rQ - rP);
+        rp.k_hi = (float)kappa;
+        rp.k_lo = (float)(kappa - (double)rp.k_hi);
+    }
+}
+
+// Weights of the N elements of chunk c (0 for elements outside the row) and their fp32 sum in index order.
+template <bool BF16>
+__device__ __forceinline__ float chunk_weights(const RowPair& rp, int64_t c, float* w)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    if (c >= rp.nchunks) {
+#pragma unroll
+        for (int k = 0; k < N; ++k) w[k] = 0.f;
+        return 0.f;
+    }
+    const uint4 vp = rp.Pv[c];
+    const int32_t e0 = (int32_t)(c * N) - rp.head;
+    const bool edge = (c == 0) || (c == rp.nchunks - 1);
+    uint4 vd = make_uint4(0, 0, 0, 0);
+    const bool dvec = !rp.bonus && rp.Dv != nullptr;
+    if (dvec) vd = rp.Dv[c];
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const int32_t e = e0 + k;
+        const bool valid = !edge || (e >= 0 && e < rp.V);
+        const float xp = chunk_elem<BF16>(vp, k);
+        const float ep = fast_exp2(exp_arg<BF16>(xp, rp.refP, rp.sc));
+        float wk;
+        if (rp.bonus) {
+            wk = ep;
+        } else {
+            float xd;
+            if (dvec) xd = chunk_elem<BF16>(vd, k);
+            else xd = valid ? load_logit<BF16>(rp.D, e) : 0.f;
+            const float eq = fast_exp2(exp_arg<BF16>(xd, rp.refQ, rp.sc));
+            wk = fmaxf(0.f, __builtin_fmaf(-rp.k_lo, eq, __builtin_fmaf(-rp.k_hi, eq, ep)));
+        }
+        if (!valid || !(wk == wk)) wk = 0.f;
+        w[k] = wk;
+        sum += wk;
+    }
+    return sum;
+}
+
+// Weight of one tile: lanes take chunks tile*256 + g*64 + lane, g = 0..3.  Every lane returns the sum.
+template <bool BF16>
+__device__ __forceinline__ double tile_weight(const RowPair& rp, int64_t tile, int lane)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    double acc = 0.0;
+#pragma unroll
+    for (int g = 0; g < kTileChunks; ++g) {
+        float w[N];
+        acc += (double)chunk_weights<BF16>(rp, tile * (64 * kTileChunks) + g * 64 + lane, w);
+    }
+    return wave_sum(acc) * rp.scale;
+}
+
+// Tile weights may be rewritten by one lane and read by the others of the same wavefront (fallback
+// below); global memory is read with device-scope loads so no stale first-level-cache line is seen.
+template <bool LDS>
+__device__ __forceinline__ double read_tile(const double* t)
+{
+    if (LDS) return *(const volatile double*)t;
+    unsigned long long bits = __hip_atomic_load((const unsigned long long*)t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __longlong_as_double((long long)bits);
+}
+
+// One wavefront selects the token from the tile weights: returns the token (all lanes), -1 if the
+// weights carry no mass, or -2 if the caller should recompute the tiles as bonus weights (residual with
+// Z == 0: p == q everywhere, or a broken draft row) and call again.
+template <bool BF16, bool LDS>
+__device__ __forceinline__ int32_t select_token(const RowPair& rp, const double* tiles, int ntiles, float u, int lane)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    const int per = (ntiles + 63) / 64;
+    // ---- tile level: each lane sums a contiguous run of tiles, then a scan over lanes
+    double mine = 0.0;
+    for (int i = 0; i < per; ++i) {
+        const int t = lane * per + i;
+        if (t < ntiles) mine += read_tile<LDS>(tiles + t);
+    }
+    const double incl = wave_inclusive_scan(mine, lane);
+    const double Z = __shfl(incl, 63, 64);
+    if (!(Z > 0.0) || !(Z - Z == 0.0)) return rp.bonus ? -1 : -2;
+    const double target = (double)u * Z;
+    const unsigned long long hit = __ballot(incl > target);
+    // The lane whose run of tiles holds the crossing walks it; if rounding hides the crossing it settles
+    // for its last tile with weight.  With no such lane at all (rounding at the top end) the last lane that
+    // holds weight does the same.
+    const unsigned long long haveW = __ballot(mine > 0.0);
+    if (!haveW) return -1;
+    const int src = hit ? (__ffsll((long long)hit) - 1) : (63 - __clzll((long long)haveW));
+    int tl = -1, tl_last = -1;
+    double run = incl - mine, run_last = 0.0;                        // exclusive prefix of this lane
+    for (int i = 0; i < per; ++i) {
+        const int t = lane * per + i;
+        if (t < ntiles && tl < 0) {
+            const double wt = read_tile<LDS>(tiles + t);
+            const double nx = run + wt;
+            if (wt > 0.0) { tl_last = t; run_last = run; }
+            if (nx > target) tl = t; else run = nx;
+        }
+    }
+    const bool force_last = __shfl((int)(tl < 0), src, 64) != 0;
+    if (tl < 0) { tl = tl_last; run = run_last; }
+    const int tile = __shfl(tl, src, 64);
+    const double before = __shfl(run, src, 64);
+    if (tile < 0) return -1;
+    // ---- inside the tile
+    float w[kTileChunks][N];
+    float cs[kTileChunks];
+#pragma unroll
+    for (int g = 0; g < kTileChunks; ++g)
+        cs[g] = chunk_weights<BF16>(rp, (int64_t)tile * (64 * kTileChunks) + g * 64 + lane, w[g]);
+    double base = before;
+    int found_g = -1, found_lane = -1;
+    double found_excl = 0.0;
+#pragma unroll
+    for (int g = 0; g < kTileChunks; ++g) {
+        const double v = (double)cs[g] * rp.scale;
+        const double inc = wave_inclusive_scan(v, lane);
+        const unsigned long long h = force_last ? 0ull : __ballot(base + inc > target);
+        if (h && found_g < 0) {
+            found_g = g;
+            found_lane = __ffsll((long long)h) - 1;
+            found_excl = base + __shfl(inc - v, found_lane, 64);
+        }
+        base += __shfl(inc, 63, 64);
+    }
+    int32_t tok = -1;
+    if (found_g >= 0) {
+        if (lane == found_lane) {
+            double r = found_excl;
+            int32_t lastpos = -1;
+#pragma unroll
+            for (int g = 0; g < kTileChunks; ++g) {
+                if (g != found_g) continue;
+                const int64_t c = (int64_t)tile * (64 * kTileChunks) + g * 64 + lane;
+#pragma unroll
+                for (int k = 0; k < N; ++k) {
+                    if (w[g][k] > 0.f) lastpos = (int32_t)(c * N) + k - rp.head;
+                    r += (double)w[g][k] * rp.scale;
+                    if (tok < 0 && r > target) tok = (int32_t)(c * N) + k - rp.head;
+                }
+            }
+            if (tok < 0) tok = lastpos;
+        }
+        tok = __shfl(tok, found_lane, 64);
+    } else {
+        // the last element of the tile with positive weight
+        int32_t lastpos = -1;
+#pragma unroll
+        for (int g = 0; g < kTileChunks; ++g) {
+            const int64_t c = (int64_t)tile * (64 * kTileChunks) + g * 64 + lane;
+#pragma unroll
+            for (int k = 0; k < N; ++k)
+                if (w[g][k] > 0.f) { const int32_t e = (int32_t)(c * N) + k - rp.head; lastpos = e > lastpos ? e : lastpos; }
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) { const int32_t o = __shfl_xor(lastpos, m, 64); lastpos = o > lastpos ? o : lastpos; }
+        tok = lastpos;
+    }
+    return tok;
+}
+
+}  // namespace hola

@@ -1,0 +1,336 @@
+// Device code of the row statistics (shared by the split-row kernel and the fused per-sequence kernel).
+//
+// For one logits row the entropy of Section 3.1 (H = -sum p_i log p_i) and the softmax normaliser
+// follow from two sums over y_i = x_i * c + beta, c = log2(e)/temperature:
+//     S = sum_i 2^(y_i),   T = sum_i y_i 2^(y_i);   lse = ln S - beta ln 2,   H = ln S - ln2 * T / S.
+// Each lane streams 16-byte chunks and keeps (S, T) in DOUBLE, fed by fp32 chunk sums of 4-8 terms, so a
+// dominant term never sits in an fp32 accumulator while hundreds of small ones are added to it.
+//
+// The exponent argument is formed so that its rounding is unbiased and consistent over the row:
+//   bf16 logits: c = c1 + c2 with c1 cut to 16 significant bits, so x * c1 is exact in fp32;
+//                y = fma(x, c2, fma(x, c1, b)) with an integer-valued reference b (beta = b).
+//   fp32 logits: d = x - m against a reference logit m, y = fma(d, c_hi, d * c_lo) (beta = -m c).
+// The reference comes from the wavefront's first chunk and moves only when a logit exceeds it by more
+// than a binade (rare); the lane's double sums are then re-referenced exactly in double.
+#pragma once
+#include "device_common.h"
+#include "hola_internal.h"
+
+namespace hola {
+
+struct ExpScale {
+    double cstar;          // log2(e) / temperature
+    float c_hi, c_lo;      // cstar = c_hi + c_lo (fp32 pair)
+    float c1, c2;          // cstar = c1 + c2 with c1 of 16 significant bits (bf16 path)
+    float inv_c;           // 1 / c_hi
+};
+
+__device__ __forceinline__ ExpScale make_scale(double cstar)
+{
+    ExpScale s;
+    s.cstar = cstar;
+    s.c_hi = (float)cstar;
+    s.c_lo = (float)(cstar - (double)s.c_hi);
+    s.c1 = __uint_as_float((__float_as_uint(s.c_hi) + 0x80u) & 0xffffff00u);
+    s.c2 = (float)(cstar - (double)s.c1);
+    s.inv_c = 1.0f / s.c_hi;
+    return s;
+}
+
+// Exponent argument y for logit x against reference ref.
+template <bool BF16>
+__device__ __forceinline__ float exp_arg(float x, float ref, const ExpScale& sc)
+{
+    if (BF16) return __builtin_fmaf(x, sc.c2, __builtin_fmaf(x, sc.c1, ref));
+    const float d = x - ref;
+    return __builtin_fmaf(d, sc.c_hi, d * sc.c_lo);
+}
+
+// Offset beta such that y = x * cstar + beta.
+template <bool BF16>
+__device__ __forceinline__ double ref_offset(float ref, const ExpScale& sc)
+{
+    return BF16 ? (double)ref : -(double)ref * sc.cstar;
+}
+
+// Reference that puts logit mx at y ~ 0, and the logit above which y would exceed ~1.
+template <bool BF16>
+__device__ __forceinline__ float ref_for(float mx, const ExpScale& sc) { return BF16 ? -rintf(mx * sc.c_hi) : mx; }
+template <bool BF16>
+__device__ __forceinline__ float thr_for(float ref, const ExpScale& sc)
+{
+    return BF16 ? (1.f - ref) * sc.inv_c : ref + sc.inv_c;
+}
+
+struct LaneState {
+    double Sd, Td;         // sums at offset ref_offset(ref)
+    float ref, thr_ref;    // current reference; logit above which it must move
+    float thr;             // trigger of the rare path (thr_ref, or the running maximum on argmax rows)
+    float vmax; int32_t imax;
+};
+
+__device__ __forceinline__ void lane_init(LaneState& st)
+{
+    st.Sd = 0.0; st.Td = 0.0; st.ref = 0.f; st.thr_ref = -INFINITY; st.thr = -INFINITY;
+    st.vmax = -INFINITY; st.imax = -1;
+}
+
+// Move the lane to a reference built from logit mx; the sums are rescaled exactly in double.
+template <bool BF16>
+__device__ __forceinline__ void re_reference(LaneState& st, float mx, const ExpScale& sc)
+{
+    const float nref = ref_for<BF16>(mx, sc);
+    if (st.Sd != 0.0 || st.Td != 0.0) {
+        const double delta = ref_offset<BF16>(nref, sc) - ref_offset<BF16>(st.ref, sc);   // < 0
+        const double f = exp2(delta);
+        st.Td = (st.Td + delta * st.Sd) * f;
+        st.Sd *= f;
+    }
+    st.ref = nref;
+    st.thr_ref = thr_for<BF16>(nref, sc);
+}
+
+// Rare path: a logit above the lane's trigger arrived.
+template <bool BF16, bool ARGMAX>
+__device__ __forceinline__ void on_exceed(LaneState& st, float mx, int32_t idx, const ExpScale& sc)
+{
+    if (ARGMAX && mx > st.vmax) { st.vmax = mx; st.imax = idx; }
+    if (mx > st.thr_ref) re_reference<BF16>(st, mx, sc);
+    st.thr = ARGMAX ? st.vmax : st.thr_ref;
+}
+
+// One element with every guard (edge elements and the fallback pass): -inf logits carry no mass.
+template <bool BF16, bool ARGMAX>
+__device__ __forceinline__ void accum_elem(LaneState& st, float x, int32_t idx, const ExpScale& sc)
+{
+    if (x == -INFINITY) return;
+    if (x > st.thr) on_exceed<BF16, ARGMAX>(st, x, idx, sc);
+    const float y = exp_arg<BF16>(x, st.ref, sc);
+    const float e = fast_exp2(y);
+    st.Sd += (double)e;
+    st.Td += (double)(y * e);
+}
+
+// Fast path: one 16-byte chunk, no per-element guards.
+template <bool BF16, bool ARGMAX>
+__device__ __forceinline__ void accum_chunk(LaneState& st, const uint4& v, int32_t elem0, const ExpScale& sc)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    float x[N];
+#pragma unroll
+    for (int k = 0; k < N; ++k) x[k] = chunk_elem<BF16>(v, k);
+    float mx = x[0];
+#pragma unroll
+    for (int k = 1; k < N; ++k) mx = fmaxf(mx, x[k]);
+    if (mx > st.thr) {
+        int32_t idx = elem0;
+        if (ARGMAX) {
+#pragma unroll
+            for (int k = N - 1; k >= 0; --k) if (x[k] == mx) idx = elem0 + k;   // lowest index wins
+        }
+        on_exceed<BF16, ARGMAX>(st, mx, idx, sc);
+    }
+    float e[N], t[2] = {0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const float y = exp_arg<BF16>(x[k], st.ref, sc);
+        e[k] = fast_exp2(y);
+        t[k & 1] = __builtin_fmaf(y, e[k], t[k & 1]);
+    }
+    float s;
+    if (N == 8) s = ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
+    else s = (e[0] + e[1]) + (e[2] + e[3]);
+    st.Sd += (double)s;
+    st.Td += (double)(t[0] + t[1]);
+}
+
+template <bool BF16, bool ARGMAX>
+__device__ __forceinline__ void accum_chunk_robust(LaneState& st, const uint4& v, int32_t elem0, const ExpScale& sc)
+{
+    constexpr int N = BF16 ? 8 : 4;
+#pragma unroll
+    for (int k = 0; k < N; ++k) accum_elem<BF16, ARGMAX>(st, chunk_elem<BF16>(v, k), elem0 + k, sc);
+}
+
+// Merge the 64 lane states in double; every lane returns the wavefront's Partial.
+template <bool BF16, bool ARGMAX>
+__device__ __forceinline__ Partial wave_merge(const LaneState& st, const ExpScale& sc)
+{
+    const bool has = !(st.Sd == 0.0 && st.Td == 0.0);   // also true for NaN
+    const double beta = ref_offset<BF16>(st.ref, sc);
+    double bmin = has ? beta : INFINITY;
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) bmin = fmin(bmin, __shfl_xor(bmin, m, 64));
+    double S = 0.0, T = 0.0;
+    if (has) {
+        const double diff = bmin - beta;                // <= 0
+        S = st.Sd; T = st.Td;
+        if (diff != 0.0) {
+            const double f = exp2(diff);
+            T = (T + diff * S) * f;
+            S *= f;
+        }
+        if (!(beta == beta)) { S = NAN; T = NAN; }
+    }
+    Partial out;
+    out.S = wave_sum(S);
+    out.T = wave_sum(T);
+    out.bref = (bmin == INFINITY) ? 0.0 : bmin;
+    out.vmax = -INFINITY;
+    out.imax = -1;
+    if (ARGMAX) {
+        float v = st.vmax;
+        int32_t i = st.imax;
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            const float ov = __shfl_xor(v, m, 64);
+            const int32_t oi = __shfl_xor(i, m, 64);
+            const bool take = (oi >= 0) && (i < 0 || ov > v || (ov == v && oi < i));
+            if (take) { v = ov; i = oi; }
+        }
+        out.vmax = v;
+        out.imax = i;
+    }
+    return out;
+}
+
+// Geometry of a row on the 16-byte chunk grid anchored at the row pointer aligned down to 16 bytes.
+struct RowGeom {
+    const uint4* rowv;       // aligned chunk grid
+    const void* row;         // the row itself (element addressing of the edges)
+    int32_t head;            // elements of chunk 0 that precede the row
+    int32_t V;
+    int64_t c_first, c_end;  // full chunks [c_first, c_end)
+    int32_t edge_lo_end;     // row elements [0, edge_lo_end) precede the first full chunk
+    int32_t edge_hi_begin;   // row elements [edge_hi_begin, V) follow the last full chunk
+};
+
+template <bool BF16>
+__device__ __forceinline__ RowGeom make_geom(const void* row, int32_t V)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    constexpr int ES = BF16 ? 2 : 4;
+    RowGeom g;
+    const uintptr_t addr = (uintptr_t)row;
+    g.row = row;
+    g.V = V;
+    g.head = (int32_t)((addr & 15) / ES);
+    g.rowv = (const uint4*)(addr & ~(uintptr_t)15);
+    g.c_first = g.head ? 1 : 0;
+    g.c_end = ((int64_t)V + g.head) / N;
+    if (g.c_end < g.c_first) g.c_end = g.c_first;
+    int32_t lo = g.head ? (N - g.head) : 0;
+    if (lo > V) lo = V;
+    g.edge_lo_end = lo;
+    int32_t hi = (int32_t)(g.c_end * N) - g.head;
+    if (hi < lo) hi = lo;
+    g.edge_hi_begin = hi;
+    return g;
+}
+
+// One wavefront's pass over the chunks c0, c0 + stride, ... < c_hi of a row (c0 already holds the lane's
+// offset), plus, if do_edges, the edge elements (fewer than two chunks' worth, one per lane).
+template <bool BF16, bool ARGMAX, int U, bool ROBUST>
+__device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64_t c0, int64_t c_hi, int64_t stride,
+                                          bool do_edges, const ExpScale& sc, int lane)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    lane_init(st);
+    int64_t c = c0;
+    if (!ARGMAX && !ROBUST) {
+        // Common reference from the wavefront's first chunks, so that lanes rarely re-reference.
+        float mx = -INFINITY;
+        if (c < c_hi) {
+            const uint4 v = g.rowv[c];
+#pragma unroll
+            for (int k = 0; k < N; ++k) mx = fmaxf(mx, chunk_elem<BF16>(v, k));
+        }
+        mx = wave_max(mx);
+        if (mx > -INFINITY && mx < INFINITY) {
+            st.ref = ref_for<BF16>(mx, sc);
+            st.thr_ref = thr_for<BF16>(st.ref, sc);
+            st.thr = st.thr_ref;
+        }
+    }
+    while (c + (int64_t)(U - 1) * stride < c_hi) {
+        uint4 buf[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) buf[u] = g.rowv[c + u * stride];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int32_t e0 = (int32_t)((c + u * stride) * N) - g.head;
+            if (ROBUST) accum_chunk_robust<BF16, ARGMAX>(st, buf[u], e0, sc);
+            else accum_chunk<BF16, ARGMAX>(st, buf[u], e0, sc);
+        }
+        c += (int64_t)U * stride;
+    }
+    for (; c < c_hi; c += stride) {
+        const uint4 v = g.rowv[c];
+        const int32_t e0 = (int32_t)(c * N) - g.head;
+        if (ROBUST) accum_chunk_robust<BF16, ARGMAX>(st, v, e0, sc);
+        else accum_chunk<BF16, ARGMAX>(st, v, e0, sc);
+    }
+    if (do_edges) {
+        const int32_t n_lo = g.edge_lo_end, n_hi = g.V - g.edge_hi_begin;
+        int32_t e = -1;
+        if (lane < n_lo) e = lane;
+        else if (lane - n_lo < n_hi) e = g.edge_hi_begin + (lane - n_lo);
+        if (e >= 0) accum_elem<BF16, ARGMAX>(st, load_logit<BF16>(g.row, e), e, sc);
+    }
+}
+
+// A wavefront's share of a row, with the fallback pass when the fast pass meets a -inf logit (its
+// y * 2^y is NaN) or anything else non-finite.
+template <bool BF16, bool ARGMAX, int U>
+__device__ __forceinline__ Partial wave_row_share(const RowGeom& g, int64_t c0, int64_t c_hi, int64_t stride,
+                                                  bool do_edges, const ExpScale& sc, int lane)
+{
+    LaneState st;
+    wave_pass<BF16, ARGMAX, U, false>(st, g, c0, c_hi, stride, do_edges, sc, lane);
+    Partial res = wave_merge<BF16, ARGMAX>(st, sc);
+    const bool finite = (res.S - res.S == 0.0) && (res.T - res.T == 0.0);
+    if (!finite) {                                      // wavefront-uniform
+        wave_pass<BF16, ARGMAX, 2, true>(st, g, c0, c_hi, stride, do_edges, sc, lane);
+        res = wave_merge<BF16, ARGMAX>(st, sc);
+    }
+    return res;
+}
+
+// ---- merging partials of one row (accept stage) ------------------------------------------------
+struct RowStat { double lse, H; int32_t argmax; };
+
+__device__ __forceinline__ RowStat merge_partials(const Partial* __restrict__ ps, int n)
+{
+    double bmin = INFINITY;
+    bool bad = false;
+    for (int i = 0; i < n; ++i) {
+        const double S = ps[i].S;
+        if (!(S == S)) bad = true;
+        if (S > 0.0 && ps[i].bref < bmin) bmin = ps[i].bref;
+    }
+    double S = 0.0, T = 0.0;
+    float vmax = -INFINITY;
+    int32_t imax = -1;
+    for (int i = 0; i < n; ++i) {
+        const Partial q = ps[i];
+        if (q.S > 0.0) {
+            const double d = bmin - q.bref;             // <= 0
+            if (d == 0.0) { S += q.S; T += q.T; }
+            else { const double f = exp2(d); S += q.S * f; T += (q.T + d * q.S) * f; }
+        }
+        if (q.imax >= 0 && (imax < 0 || q.vmax > vmax || (q.vmax == vmax && q.imax < imax))) {
+            vmax = q.vmax;
+            imax = q.imax;
+        }
+    }
+    RowStat r;
+    r.argmax = imax;
+    if (bad || !(T == T)) { r.lse = NAN; r.H = NAN; return r; }
+    if (!(S > 0.0)) { r.lse = -INFINITY; r.H = NAN; return r; }   // no finite logit in the row
+    const double lnS = log(S);
+    r.lse = lnS - bmin * kLn2;
+    r.H = lnS - kLn2 * (T / S);
+    return r;
+}
+
+}  // namespace hola

@@ -1,0 +1,131 @@
+"""The C-ABI library loads without a GPU, exports every symbol include/hola.h declares, and its host
+logic (argument checks, workspace sizing, status strings) behaves as the header states.  No compute."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from conftest import ROOT
+from paper_2506_18952_amd import binding as hb
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "hola.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hola_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = _declared_functions()
+    assert len(names) >= 14
+    L = hb.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in include/hola.h but not exported"
+    assert set(names) == set(hb.EXPORTS)
+
+
+def test_status_strings_and_version():
+    L = hb.lib()
+    seen = {L.hola_status_string(i) for i in range(5)}
+    assert len(seen) == 5 and all(seen)
+    assert b"gfx950" in L.hola_version()
+
+
+def test_workspace_bytes():
+    assert hb.hola_workspace_bytes(0, 4, 100) > 0
+    assert hb.hola_workspace_bytes(4, 0, 100) == 0           # gamma < 1
+    assert hb.hola_workspace_bytes(4, 33, 100) == 0          # gamma > 32
+    assert hb.hola_workspace_bytes(4, 4, 0) == 0
+    assert hb.hola_workspace_bytes(-1, 4, 100) == 0
+    a, b, c = (hb.hola_workspace_bytes(*s) for s in ((8, 4, 1000), (16, 4, 1000), (16, 8, 128256)))
+    assert a < b < c
+    assert hb.hola_workspace_bytes(256, 8, 128256) < 64 << 20
+    assert hb.hola_hsd_workspace_bytes(3, 128, 8, 151936) > hb.hola_workspace_bytes(128, 9, 151936)
+    assert hb.hola_hsd_workspace_bytes(1, 8, 4, 100) == 0    # needs at least two models
+    assert hb.hola_hsd_workspace_bytes(3, 8, 32, 100) == 0   # gamma grows past the limit
+
+
+def _args(**kw):
+    a = hb.VerifyArgs()
+    fake = 0x1000                                             # never dereferenced: checks come first
+    a.target_logits = a.draft_logits = a.draft_tokens = fake
+    a.out_accept_len = a.out_next_token = fake
+    a.dtype, a.B, a.gamma, a.V = hb.HOLA_DTYPE_BF16, 4, 3, 100
+    a.temperature, a.entropy_threshold = 1.0, 2.0
+    a.workspace, a.workspace_bytes = 0x10000, 1 << 30
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(B=-1), hb.HOLA_ERR_INVALID_ARG),
+    (dict(gamma=0), hb.HOLA_ERR_INVALID_ARG),
+    (dict(gamma=33), hb.HOLA_ERR_INVALID_ARG),
+    (dict(V=0), hb.HOLA_ERR_INVALID_ARG),
+    (dict(dtype=7), hb.HOLA_ERR_UNSUPPORTED),
+    (dict(target_logits=None), hb.HOLA_ERR_INVALID_ARG),
+    (dict(draft_logits=None), hb.HOLA_ERR_INVALID_ARG),
+    (dict(draft_tokens=None), hb.HOLA_ERR_INVALID_ARG),
+    (dict(out_accept_len=None), hb.HOLA_ERR_INVALID_ARG),
+    (dict(out_next_token=None), hb.HOLA_ERR_INVALID_ARG),
+    (dict(target_logits=0x1001), hb.HOLA_ERR_INVALID_ARG),    # not aligned to the element size
+    (dict(target_ld=99), hb.HOLA_ERR_INVALID_ARG),
+    (dict(draft_ld=50), hb.HOLA_ERR_INVALID_ARG),
+    (dict(entropy_ld=2), hb.HOLA_ERR_INVALID_ARG),
+    (dict(temperature=-0.5), hb.HOLA_ERR_INVALID_ARG),
+    (dict(temperature=float("nan")), hb.HOLA_ERR_INVALID_ARG),
+    (dict(temperature=float("inf")), hb.HOLA_ERR_INVALID_ARG),
+    (dict(entropy_threshold=float("nan")), hb.HOLA_ERR_INVALID_ARG),
+    (dict(workspace=None), hb.HOLA_ERR_WORKSPACE),
+    (dict(workspace=0x10010), hb.HOLA_ERR_WORKSPACE),         # not 256-byte aligned
+    (dict(workspace_bytes=1024), hb.HOLA_ERR_WORKSPACE),
+    (dict(B=0), hb.HOLA_OK),                                  # empty batch: successful no-op
+])
+def test_verify_ex_argument_errors(kw, want):
+    a = _args(**kw)
+    assert hb.lib().hola_verify_ex(C.byref(a)) == want
+
+
+def test_null_args_and_short_forms():
+    L = hb.lib()
+    assert L.hola_verify_ex(None) == hb.HOLA_ERR_INVALID_ARG
+    f = 0x1000
+    for fn in (L.hola_verify_f32, L.hola_verify_bf16):
+        assert fn(None, f, f, 0, 2, 2, 10, 1.0, 1.0, f, f, f, None) == hb.HOLA_ERR_INVALID_ARG
+        assert fn(f, f, f, 0, 2, 0, 10, 1.0, 1.0, f, f, f, None) == hb.HOLA_ERR_INVALID_ARG
+        assert fn(f, f, f, 0, 2, 2, 10, 0.0, 1.0, f, f, f, None) == hb.HOLA_ERR_INVALID_ARG   # no greedy short form
+        assert fn(f, f, f, 0, 0, 2, 10, 1.0, 1.0, f, f, f, None) == hb.HOLA_OK
+    assert L.hola_row_stats(None, 0, 0, 4, 10, 1.0, f, 0x10000, 1 << 30, None) == hb.HOLA_ERR_INVALID_ARG
+    assert L.hola_row_stats(f, 0, 0, 4, 10, 0.0, f, 0x10000, 1 << 30, None) == hb.HOLA_ERR_INVALID_ARG
+    assert L.hola_row_stats(f, 0, 0, 0, 10, 1.0, f, 0x10000, 1 << 30, None) == hb.HOLA_OK
+    taus = (C.c_float * 2)(1.0, 2.0)
+    models = (hb.ModelLogits * 3)()
+    assert L.hola_hsd_verify(models, 3, 1, f, 0, 0, 4, 2, 10, None, 1.0, taus, f, f, f, None, 0x10000, 1 << 30,
+                             None) == hb.HOLA_ERR_INVALID_ARG                                 # NULL model logits
+    for m in models:
+        m.logits = f
+    assert L.hola_hsd_verify(models, 3, 1, f, 0, 0, 4, 2, 10, None, 1.0, taus, f, f, f, None, 0x10000, 16,
+                             None) == hb.HOLA_ERR_WORKSPACE
+    assert L.hola_hsd_verify(models, 1, 1, f, 0, 0, 4, 2, 10, None, 1.0, taus, f, f, f, None, 0x10000, 1 << 30,
+                             None) == hb.HOLA_ERR_INVALID_ARG
+
+
+def test_tuning_validation():
+    hb.hola_set_tuning(2, 4, 0)
+    with pytest.raises(hb.HolaError):
+        hb.hola_set_tuning(0, 3, 0)
+    with pytest.raises(hb.HolaError):
+        hb.hola_set_tuning(99, 0, 0)
+    hb.hola_set_tuning()
+
+
+def test_product_does_not_import_the_oracle():
+    """The HIP path's Python and C++ sources never name the oracle."""
+    pkg = os.path.join(ROOT, "paper_2506_18952_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "hola_oracle" not in text and "from oracle" not in text and "import oracle" not in text, f

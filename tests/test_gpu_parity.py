@@ -1,0 +1,354 @@
+"""GPU parity: the HIP path through the C ABI against the float64 oracle, element by element, on the
+named workloads (full size, in the launch configuration bench.py times) and on edge cases."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import hola_oracle as orc
+from paper_2506_18952_amd import binding as hb
+from paper_2506_18952_amd import workloads as wl
+from parity import DEV, compare_level, run_gpu_level, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _report(name, rep):
+    line = f"[parity] {name}: {rep}"
+    print(line, flush=True)
+    path = os.environ.get("HOLA_PARITY_REPORT")
+    if path:
+        with open(path, "a") as f:
+            f.write(line + "\n")
+
+
+def _level(w, tau, **kw):
+    gpu = run_gpu_level(w.target, w.draft, w.tokens, w.seed, w.temperature, tau,
+                        row_temperature=w.row_temperature, **kw)
+    okw = {k: v for k, v in kw.items() if k in ("draft_len", "seq_base", "level")}
+    rep = compare_level(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, gpu,
+                        row_temperature=w.row_temperature, **okw)
+    return gpu, rep
+
+
+# ----------------------------------------------------------------------------- named workloads
+def test_config1_f32_single_sequence():
+    w = wl.config1()
+    for tau in w.taus + [0.0, float("inf")]:
+        for short in (False, True):
+            gpu = run_gpu_level(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, short=short)
+            rep = compare_level(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, gpu)
+            _report(f"{w.name} tau={tau:.3f} short={short}", rep)
+            assert rep.max_entropy_abs < 1e-6
+
+
+def test_config2_bf16():
+    w = wl.config2()
+    for tau in w.taus + [0.0]:
+        gpu, rep = _level(w, tau)
+        _report(f"{w.name} tau={tau:.3f}", rep)
+        assert rep.max_entropy_abs < 1e-6
+    g2 = run_gpu_level(w.target, w.draft, w.tokens, w.seed, w.temperature, w.taus[0], short=True)
+    rep = compare_level(w.target, w.draft, w.tokens, w.seed, w.temperature, w.taus[0], g2)
+    _report(f"{w.name} short form", rep)
+
+
+@pytest.fixture(scope="module")
+def cfg3():
+    return wl.config3()
+
+
+@pytest.mark.timeout(420)
+def test_config3_bf16_headline_full_size(cfg3):
+    """B=256, gamma=8, V=128256 bf16, T=0.8 at three thresholds and with the gate off."""
+    w = cfg3
+    P, D, tok = to_dev(w.target), to_dev(w.draft), to_dev(w.tokens)
+    hist = {}
+    for tau in w.taus + [0.0]:
+        gpu = run_gpu_level(P, D, tok, w.seed, w.temperature, tau)
+        rep = compare_level(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, gpu)
+        _report(f"{w.name} tau={tau:.3f}", rep)
+        assert rep.max_entropy_abs < 1e-6
+        hist[tau] = np.bincount(gpu.accept_len, minlength=w.gamma + 1)
+    print("[parity] accept-length histograms:", {f"{k:.2f}": v.tolist() for k, v in hist.items()})
+    # determinism: a second run is bit-identical
+    a = run_gpu_level(P, D, tok, w.seed, w.temperature, w.taus[1])
+    b = run_gpu_level(P, D, tok, w.seed, w.temperature, w.taus[1])
+    assert np.array_equal(a.accept_len, b.accept_len) and np.array_equal(a.next_token, b.next_token)
+    assert np.array_equal(a.entropy, b.entropy)
+
+
+def test_config3_launch_shapes_agree(cfg3):
+    """Every launch shape of the row-statistics kernel gives the same decisions."""
+    w = cfg3
+    sub = slice(0, 32)
+    P, D, tok = to_dev(w.target[sub]), to_dev(w.draft[sub]), to_dev(w.tokens[sub])
+    tau = w.taus[1]
+    try:
+        for split, unroll, single in ((1, 4, 0), (2, 2, 0), (4, 8, 0), (16, 4, 0), (1, 8, 1)):
+            hb.hola_set_tuning(split, unroll, single)
+            gpu = run_gpu_level(P, D, tok, w.seed, w.temperature, tau)
+            rep = compare_level(w.target[sub], w.draft[sub], w.tokens[sub], w.seed, w.temperature, tau, gpu)
+            _report(f"{w.name}[:32] split={split} unroll={unroll} single_c={single}", rep)
+    finally:
+        hb.hola_set_tuning()
+
+
+@pytest.mark.timeout(420)
+def test_config5_f32_greedy_and_stochastic_rows_sampled():
+    """B=1024, gamma=4, V=256000 fp32 through one call with per-row temperatures; the oracle checks a
+    contiguous block of sequences straddling the greedy / stochastic boundary."""
+    B = 1024
+    w = wl.config5(B=B)
+    tau = w.taus[0]
+    gpu = run_gpu_level(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, row_temperature=w.row_temperature)
+    lo, hi = B // 2 - 20, B // 2 + 20
+    sub = slice(lo, hi)
+    from parity import GpuOut
+    gsub = GpuOut(gpu.accept_len[sub], gpu.next_token[sub], gpu.entropy[sub])
+    rep = compare_level(w.target[sub], w.draft[sub], w.tokens[sub], w.seed, w.temperature, tau, gsub,
+                        row_temperature=w.row_temperature[sub], seq_base=lo)
+    _report(f"{w.name} sequences {lo}..{hi - 1}", rep)
+    assert rep.max_entropy_abs < 1e-6
+    # properties that hold at any size: greedy rows accept exactly the argmax prefix
+    am = np.argmax(w.target[:8], axis=-1)
+    for b in range(8):
+        match = w.tokens[b] == am[b, :w.gamma]
+        a = int(np.flatnonzero(~match)[0]) if (~match).any() else w.gamma
+        # the gate may keep a non-argmax draft; without gate hits the prefix rule is exact
+        assert gpu.accept_len[b] >= a and gpu.next_token[b] == am[b, gpu.accept_len[b]]
+    assert np.all((gpu.accept_len >= 0) & (gpu.accept_len <= w.gamma))
+    assert np.all((gpu.next_token >= 0) & (gpu.next_token < w.V))
+
+
+# ----------------------------------------------------------------------------- two-level hierarchy
+def _hsd_gpu(models, tokens, seed, T, taus, row_temperature=None):
+    ms = [to_dev(m) for m in models]
+    n = len(ms)
+    B, g, V = ms[0].shape
+    L, gmax = n - 1, g + n - 2
+    out_tok = torch.full((B, g + n - 1), -7, dtype=torch.int32, device=DEV)
+    acc = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    nxt = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    ent = torch.full((L, B, gmax), -7.0, dtype=torch.float32, device=DEV)
+    ws = hb.alloc_workspace(hb.hola_hsd_workspace_bytes(n, B, g, V), DEV)
+    rt = None if row_temperature is None else to_dev(row_temperature)
+    hb.hola_hsd_verify(ms, to_dev(tokens), seed, B, g, V, T, taus, out_tok, acc, nxt, ent, ws, row_temperature=rt)
+    torch.cuda.synchronize()
+    return out_tok.cpu().numpy(), acc.cpu().numpy(), nxt.cpu().numpy(), ent.cpu().numpy()
+
+
+def _check_hsd(models, tokens, seed, T, taus, name):
+    out_tok, acc, nxt, ent = _hsd_gpu(models, tokens, seed, T, taus)
+    ref = orc.hsd_verify(models, tokens, seed, T, taus)
+    n = len(models)
+    B, g, V = models[0].shape
+    # Walk the chain level by level so that a listed near-threshold flip is judged where it happens:
+    # each level of the GPU chain is compared with the oracle run on the GPU's own inputs to that level.
+    cur_tok, cur_len = np.asarray(tokens, np.int32), np.full(B, g, np.int32)
+    flips = 0
+    for k in range(1, n):
+        gk = g + k - 1
+        gl = run_gpu_level(models[k], models[k - 1], cur_tok, seed, T, taus[k - 1], draft_len=cur_len, level=k - 1)
+        rep = compare_level(models[k], models[k - 1], cur_tok, seed, T, taus[k - 1], gl, draft_len=cur_len, level=k - 1)
+        _report(f"{name} level {k}", rep)
+        flips += rep.accept_mismatch + rep.token_mismatch
+        # driver (middle model's statistics reused) == stand-alone level (recomputed), up to summation order
+        np.testing.assert_allclose(ent[k - 1][:, :gk], gl.entropy, rtol=2e-6, atol=1e-6)
+        assert np.all(ent[k - 1][:, gk:] == -1.0)
+        if k < n - 1:
+            nt = np.full((B, gk + 1), -1, np.int32)
+            for b in range(B):
+                a = gl.accept_len[b]
+                nt[b, :a] = cur_tok[b, :a]
+                nt[b, a] = gl.next_token[b]
+            cur_tok, cur_len = nt, gl.accept_len + 1
+        else:
+            np.testing.assert_array_equal(acc, gl.accept_len)
+            np.testing.assert_array_equal(nxt, gl.next_token)
+            for b in range(B):
+                assert np.array_equal(out_tok[b, :cur_len[b]], cur_tok[b, :cur_len[b]])
+                assert np.all(out_tok[b, cur_len[b]:] == -1)
+    if flips == 0:                                                             # whole chain == oracle chain
+        np.testing.assert_array_equal(acc, ref.accept_len)
+        np.testing.assert_array_equal(nxt, ref.next_token)
+        np.testing.assert_array_equal(out_tok, ref.tokens)
+        np.testing.assert_allclose(ent, ref.entropy, rtol=2e-3, atol=2e-6)
+
+
+@pytest.mark.timeout(420)
+def test_config4_two_level_bf16_full_size():
+    w = wl.config4()
+    _check_hsd(w.models, w.tokens, w.seed, w.temperature, w.taus, w.name)
+
+
+def test_three_level_small_f32():
+    rng = np.random.default_rng(5)
+    B, g, V = 9, 3, 1003
+    base = (2 * rng.standard_normal((B, g + 3, V))).astype(np.float32)
+    models = [(base[:, :g + k] + (0.9 - 0.3 * k) * rng.standard_normal((B, g + k, V))).astype(np.float32)
+              for k in range(3)] + [base]
+    q = np.exp(models[0].astype(np.float64))
+    tok = np.array([[rng.choice(V, p=q[b, j] / q[b, j].sum()) for j in range(g)] for b in range(B)], np.int32)
+    _check_hsd(models, tok, 11, 1.0, [2.0, 3.0, 4.0], "three-level small")
+
+
+# ----------------------------------------------------------------------------- row statistics alone
+def test_row_stats_entry_closed_forms_and_oracle():
+    V = 128256
+    rows = np.zeros((4, V), np.float32)
+    rows[1] = -(2.0 ** -13) * np.arange(V)                 # geometric, exact in float32
+    rows[2] = -(2.0 ** -5) * np.arange(V)
+    rows[3] = np.random.default_rng(0).standard_normal(V).astype(np.float32) * 3
+    for arr, rtol in ((rows, 1e-5), (wl.f32_to_bf16_bits(rows), 2e-3)):
+        t = to_dev(arr)
+        out = torch.zeros((4, 2), dtype=torch.float64, device=DEV)
+        ws = hb.alloc_workspace(hb.hola_workspace_bytes(4, 1, V), DEV)
+        hb.hola_row_stats(t, 4, V, 1.0, out, ws)
+        torch.cuda.synchronize()
+        o = out.cpu().numpy()
+        for r in range(4):
+            lse, H, _ = orc.row_stats(arr[r], 1.0)
+            assert abs(o[r, 0] - lse) < 2e-6 and abs(o[r, 1] - H) <= max(rtol * abs(H), 2e-6), (r, o[r], lse, H)
+        assert abs(o[0, 1] - math.log(V)) < 1e-6            # uniform logits: H = ln V
+        a = 2.0 ** -13
+        if arr.dtype == np.float32:
+            lse_cf = math.log(-math.expm1(-a * V) / -math.expm1(-a))
+            assert abs(o[1, 0] - lse_cf) < 2e-6
+
+
+# ----------------------------------------------------------------------------- ragged shapes and edge cases
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,g,V", [(1, 1, 1), (3, 1, 7), (2, 2, 8), (5, 3, 1001), (4, 4, 2049), (7, 5, 4099),
+                                   (3, 32, 517), (2, 2, 70001)])
+def test_ragged_shapes(B, g, V, dtype):
+    w = wl.small_case(B, g, V, dtype=dtype, temperature=0.9, case_id=200 + V % 97)
+    for tau in (0.0, w.taus[0]):
+        gpu, rep = _level(w, tau)
+        _report(f"{w.name} tau={tau:.3f}", rep)
+        assert rep.max_entropy_abs < 1e-6
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_misaligned_rows_via_leading_dimension(dtype):
+    """Rows that do not start on 16-byte boundaries (ld = V + odd), target and draft misaligned differently."""
+    B, g, V = 4, 3, 1237
+    w = wl.small_case(B, g, V, dtype=dtype, case_id=301)
+    np_dt = w.target.dtype
+    ldP, ldD = V + 3, V + 5
+    bufP = np.zeros((B, g + 1, ldP), np_dt)
+    bufD = np.zeros((B, g, ldD), np_dt)
+    bufP[:, :, :V], bufD[:, :, :V] = w.target, w.draft
+    P, D, tok = to_dev(bufP), to_dev(bufD), to_dev(w.tokens)
+    acc = torch.zeros(B, dtype=torch.int32, device=DEV)
+    nxt = torch.zeros(B, dtype=torch.int32, device=DEV)
+    ent = torch.zeros((B, g), dtype=torch.float32, device=DEV)
+    ws = hb.alloc_workspace(hb.hola_workspace_bytes(B, g, V), DEV)
+    from parity import GpuOut
+    for tau in (0.0, w.taus[0]):
+        hb.hola_verify_ex(target_logits=P, draft_logits=D, draft_tokens=tok, seed=w.seed, B=B, gamma=g, V=V,
+                          temperature=w.temperature, entropy_threshold=tau, out_accept_len=acc, out_next_token=nxt,
+                          out_entropy=ent, workspace=ws, target_ld=ldP, draft_ld=ldD)
+        torch.cuda.synchronize()
+        gpu = GpuOut(acc.cpu().numpy(), nxt.cpu().numpy(), ent.cpu().numpy())
+        rep = compare_level(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, gpu)
+        _report(f"{w.name} misaligned tau={tau:.3f}", rep)
+
+
+def test_ragged_draft_len_and_seq_base():
+    w = wl.small_case(9, 5, 3001, dtype="bf16", case_id=302)
+    lens = np.array([0, 1, 2, 3, 4, 5, 5, 2, 0], np.int32)
+    for tau in (0.0, w.taus[0]):
+        gpu, rep = _level(w, tau, draft_len=lens, seq_base=(1 << 33) + 5, level=3)
+        _report(f"{w.name} ragged tau={tau:.3f}", rep)
+        assert np.all(gpu.accept_len <= lens)
+    # a batch row equals the single-sequence call with seq_base = b
+    full = run_gpu_level(w.target, w.draft, w.tokens, w.seed, w.temperature, 0.0)
+    for b in (0, 4, 8):
+        one = run_gpu_level(w.target[b:b + 1], w.draft[b:b + 1], w.tokens[b:b + 1], w.seed, w.temperature, 0.0, seq_base=b)
+        assert one.accept_len[0] == full.accept_len[b] and one.next_token[0] == full.next_token[b]
+
+
+def test_masked_vocabulary_and_degenerate_rows():
+    B, g, V = 6, 3, 2500
+    w = wl.small_case(B, g, V, dtype="f32", case_id=303)
+    P, D, tok = w.target.copy(), w.draft.copy(), w.tokens.copy()
+    rng = np.random.default_rng(1)
+    mask = rng.random(V) < 0.4                              # -inf logits: masked vocabulary
+    P[:, :, mask] = -np.inf
+    D[:, :, mask] = -np.inf
+    for b in range(B):
+        for j in range(g):
+            if mask[tok[b, j]]:
+                tok[b, j] = int(np.flatnonzero(~mask)[0])
+    P[1, 0, tok[1, 0]] = -np.inf                            # p(x) = 0: always rejected with the gate off
+    P[2, 1, :] = -np.inf                                    # a target row with no mass
+    P[3, :, :] = D[3, 0, :]                                 # identical rows ...
+    D[3, :, :] = D[3, 0, :]
+    tok[3, 0] = V + 9                                       # ... and an out-of-range token: Z = 0 fallback
+    tok[4, 1] = -2
+    for tau in (0.0, 0.5 * math.log(V)):
+        gpu = run_gpu_level(P, D, tok, 5, 1.0, tau)
+        rep = compare_level(P, D, tok, 5, 1.0, tau, gpu)
+        _report(f"masked/degenerate tau={tau:.3f}", rep)
+        if tau == 0.0:
+            assert gpu.accept_len[1] == 0 and gpu.accept_len[3] == 0
+    gpu = run_gpu_level(P, D, tok, 5, 1.0, float("inf"))    # gate keeps everything, also p(x) = 0
+    assert np.all(gpu.accept_len == g)
+    # a stop row without mass gives -1
+    tok2 = tok.copy()
+    P2 = P.copy()
+    P2[2, 0, :] = -np.inf
+    g2 = run_gpu_level(P2, D, tok2, 5, 1.0, 0.0)
+    r2 = orc.verify(P2, D, tok2, 5, 1.0, 0.0)
+    assert g2.accept_len[2] == r2.accept_len[2] == 0 and g2.next_token[2] == r2.next_token[2] == -1
+
+
+def test_huge_dynamic_range_and_identical_models():
+    rng = np.random.default_rng(2)
+    B, g, V = 4, 3, 5000
+    P = rng.standard_normal((B, g + 1, V)).astype(np.float32)
+    hot = rng.integers(0, V, (B, g + 1))
+    for b in range(B):
+        for j in range(g + 1):
+            P[b, j, hot[b, j]] += 1e4                       # one-hot-like rows
+    D = P[:, :g].copy()
+    tok = hot[:, :g].astype(np.int32)
+    tok[1, 1] = (tok[1, 1] + 1) % V
+    for rowT in (None, np.zeros(B, np.float32)):
+        gpu = run_gpu_level(P, D, tok, 1, 1.0, 0.0, row_temperature=rowT)
+        rep = compare_level(P, D, tok, 1, 1.0, 0.0, gpu, row_temperature=rowT)
+        _report(f"one-hot rows greedy={rowT is not None}", rep)
+        assert list(gpu.accept_len) == [g, 1, g, g] and gpu.next_token[1] == hot[1, 1]
+    # identical models accept everything for every seed
+    w = wl.small_case(8, 4, 3000, dtype="bf16", case_id=304)
+    for seed in range(5):
+        gpu = run_gpu_level(w.target, w.target[:, :4].copy(), w.tokens, seed, 0.8, 0.0)
+        assert np.all(gpu.accept_len == 4)
+
+
+def test_greedy_rows_with_ties_small():
+    B, g, V = 6, 3, 777
+    w = wl.small_case(B, g, V, dtype="bf16", greedy_below=3, temperature=0.7, case_id=305)
+    P = w.target.copy()
+    P[0, 0, 100] = P[0, 0, 600] = np.uint16(0x4200)         # two equal maxima (32.0): lowest index wins
+    tok = w.tokens.copy()
+    tok[0, 0] = 100
+    gpu = run_gpu_level(P, w.draft, tok, w.seed, w.temperature, 0.0, row_temperature=w.row_temperature)
+    rep = compare_level(P, w.draft, tok, w.seed, w.temperature, 0.0, gpu, row_temperature=w.row_temperature)
+    _report("greedy ties", rep)
+    assert gpu.accept_len[0] >= 1
+
+
+def test_gate_monotone_in_tau_on_gpu():
+    w = wl.small_case(32, 6, 5003, dtype="bf16", case_id=306)
+    P, D, tok = to_dev(w.target), to_dev(w.draft), to_dev(w.tokens)
+    prev = None
+    for tau in np.linspace(0, math.log(w.V) + 0.5, 12):
+        gpu = run_gpu_level(P, D, tok, w.seed, w.temperature, float(tau))
+        if prev is not None:
+            assert np.all(gpu.accept_len >= prev)
+        prev = gpu.accept_len
+    assert np.all(prev == w.gamma)
