@@ -2,16 +2,19 @@
 """Benchmark of the HSD batched-verify step on one MI355X.
 
 A step is one whole pass of the hot path (row statistics -> accept / first reject -> residual tile
-sums -> inverse-CDF select) through the C ABI over one batch of the headline workload:
+weights -> inverse-CDF select) through the C ABI over one batch of the headline workload:
 B=256 sequences x gamma=8 drafts, V=128256, bf16 logits, T=0.8, with the entropy threshold cycling
 through {0.25, 0.5, 0.75} ln V from step to step.  Inputs are synthetic (seeded, LLM-shaped logits)
 and resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--steps K] [--warmup W]      the benchmark
+  python bench.py --copy-calibration            only a plain copy kernel of known size, for scaling the
+                                                FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run
 """
 from __future__ import annotations
 
 import argparse
 import json
-import math
 import os
 import sys
 import time
@@ -22,33 +25,39 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 
+# HBM traffic of one launch of the dominant kernel on the headline workload, from rocprofv3 --pmc
+# FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy of known size (see profiles/); None until measured.
+MEASURED_TRAFFIC_BYTES = {"row_stats_kernel": None, "fused_kernel": None}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(w, tau, n_seq):
-    """The float64 oracle, as it stands, on the first n_seq sequences of the same workload."""
-    import numpy as np
-    from oracle import hola_oracle as orc
-    threads = orc.max_threads()
-    sub = slice(0, n_seq)
-    call = orc.VerifyCall(w.target[sub], w.draft[sub], w.tokens[sub], w.seed, w.temperature, tau,
-                          num_threads=threads)
-    t0 = time.perf_counter()
-    ref = call.run()
-    dt = time.perf_counter() - t0
-    return ref, dt, threads
+def copy_calibration() -> int:
+    """Launch the library's plain copy kernel on 1 GiB a few times (nothing else touches the GPU)."""
+    import torch
+    from paper_2506_18952_amd import binding as hb
+    n = 1 << 30
+    src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    for _ in range(5):
+        hb.hola_copy_bytes(dst, src, n)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_calibration_bytes_per_launch": n, "launches": 5}), flush=True)
+    return 0
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=60)
-    ap.add_argument("--warmup", type=int, default=6)
+    ap.add_argument("--steps", type=int, default=90)
+    ap.add_argument("--warmup", type=int, default=9)
     ap.add_argument("--batch", type=int, default=256, help="sequences (256 = the headline workload)")
-    ap.add_argument("--cpu-seqs", type=int, default=0, help="oracle sample size (0: 8 per host thread, max 128)")
+    ap.add_argument("--path", choices=["auto", "split", "fused"], default="auto", help="kernel path (auto: library's choice)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-baseline leg")
+    ap.add_argument("--copy-calibration", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build is one-GPU only (sharding by sequence is a design note, not code); "
@@ -66,6 +75,9 @@ def main() -> int:
     hb.lib()                                                 # fails loudly if the HIP library is not built
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        return copy_calibration()
+    hb.hola_set_tuning(path={"auto": hb.PATH_AUTO, "split": hb.PATH_SPLIT, "fused": hb.PATH_FUSED}[args.path])
 
     t0 = time.perf_counter()
     w = wl.config3(B=args.batch)
@@ -81,52 +93,58 @@ def main() -> int:
     stream = torch.cuda.current_stream()
     taus = w.taus
 
-    def step(i):
-        hb.hola_verify_ex(target_logits=P, draft_logits=D, draft_tokens=tok, seed=w.seed + i, B=B, gamma=g, V=V,
-                          temperature=w.temperature, entropy_threshold=taus[i % len(taus)], out_accept_len=acc,
-                          out_next_token=nxt, out_entropy=ent, workspace=ws, stream=stream)
+    def step(i, seed_offset=True):
+        hb.hola_verify_ex(target_logits=P, draft_logits=D, draft_tokens=tok, seed=w.seed + (i if seed_offset else 0),
+                          B=B, gamma=g, V=V, temperature=w.temperature, entropy_threshold=taus[i % len(taus)],
+                          out_accept_len=acc, out_next_token=nxt, out_entropy=ent, workspace=ws, stream=stream)
 
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly K steps, per-kernel HIP events recorded on the launch stream
-    hb.hola_profile_enable(True)
-    hb.hola_profile_collect()                                # forget anything older
-    torch.cuda.synchronize()
+    # ---- timed region: exactly K steps
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    stage_ms, stage_n = hb.hola_profile_collect()
-    hb.hola_profile_enable(False)
-
-    # ---- the same K steps without the events, as a cross-check of their overhead
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    dt_plain = time.perf_counter() - t1
-
     ms_per_step = dt * 1e3 / args.steps
     positions_per_s = B * g * args.steps / dt
 
-    # ---- roofline of the dominant kernel (row statistics): algorithmic bytes = every logit of the
-    # gamma draft rows and gamma+1 target rows read once
-    k1_ms = stage_ms[0] / max(stage_n[0], 1)
-    k1_bytes = B * (2 * g + 1) * V * 2
-    achieved = k1_bytes / (k1_ms * 1e-3) / 1e9 if k1_ms > 0 else 0.0
-    roofline = {"bound": "hbm", "kernel": "row_stats_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                "algorithmic_bytes_per_launch": k1_bytes, "avg_launch_ms": round(k1_ms, 5)}
-    stages = {hb.STAGE_NAMES[i]: round(stage_ms[i] / max(stage_n[i], 1), 5) for i in range(4)}
+    # ---- the same K steps again with HIP events recorded around every kernel on the launch stream
+    # (the events cost a few microseconds per kernel, so they stay out of the region `value` comes from)
+    hb.hola_profile_enable(True)
+    hb.hola_profile_collect()                                # forget anything older
+    resid_total = 0
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    stage_ms, stage_n = hb.hola_profile_collect()
+    hb.hola_profile_enable(False)
 
-    # whole-call effective bandwidth: pass-1 bytes + the stop rows the sampler re-reads
-    acc_h = acc.cpu().numpy()
-    resid = int((acc_h < g).sum())
-    call_bytes = k1_bytes + (2 * resid + (B - resid)) * V * 2
+    # bytes the sampler re-reads per step, averaged over the threshold cycle
+    for i in range(len(taus)):
+        step(i)
+        torch.cuda.synchronize()
+        resid_total += int((acc.cpu().numpy() < g).sum())
+    resid = resid_total / len(taus)
+
+    # ---- roofline of the dominant kernel.  Algorithmic bytes: every logit of the gamma draft rows and
+    # gamma+1 target rows read once (split path); the fused kernel also reads the stop rows once more.
+    pass1_bytes = B * (2 * g + 1) * V * 2
+    stop_bytes = (2 * resid + (B - resid)) * V * 2
+    fused = stage_n[5] > 0
+    if fused:
+        kname, k_ms, k_bytes = "fused_kernel", stage_ms[5] / stage_n[5], pass1_bytes + stop_bytes
+    else:
+        kname, k_ms, k_bytes = "row_stats_kernel", stage_ms[0] / max(stage_n[0], 1), pass1_bytes
+    achieved = k_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0
+    roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(kname),
+                "algorithmic_bytes_per_launch": int(k_bytes), "avg_launch_ms": round(k_ms, 5)}
+    stages = {hb.STAGE_NAMES[i]: round(stage_ms[i] / stage_n[i], 5) for i in range(hb.HOLA_N_STAGES) if stage_n[i]}
+    call_bytes = pass1_bytes + stop_bytes
     call_gbps = call_bytes / (ms_per_step * 1e-3) / 1e9
 
     out = {
@@ -135,34 +153,36 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"cfg3: B={B} gamma={g} V={V} bf16 T=0.8, tau cycling (0.25,0.5,0.75) ln V",
-                   "entry_point": "hola_verify_ex", "parallelism": "single GPU"},
+        "config": {"workload": f"cfg3: B={B} gamma={g} V={V} bf16 logits T=0.8, tau cycling (0.25,0.5,0.75) ln V",
+                   "entry_point": "hola_verify_ex", "kernel_path": "fused" if fused else "split",
+                   "parallelism": "single GPU"},
         "hbm_gbps_whole_call": round(call_gbps, 1), "hbm_frac_whole_call": round(call_gbps / HBM_PEAK_GBPS, 4),
-        "ms_per_step_without_events": round(dt_plain * 1e3 / args.steps, 5),
+        "algorithmic_bytes_per_step": int(call_bytes),
         "stage_ms": stages,
-        "accept_len_hist_last_step": np.bincount(acc_h, minlength=g + 1).tolist(),
+        "mean_rejections_per_step": round(resid, 1),
         "roofline": roofline,
     }
 
     if not args.no_cpu:
+        # The float64 oracle as it stands, on the same workload: all B sequences at each of the thresholds.
         from oracle import hola_oracle as orc
         threads = orc.max_threads()
-        n_seq = args.cpu_seqs or min(128, 8 * threads, B)
-        n_seq = min(n_seq, B)
-        tau = taus[(args.steps - 1) % len(taus)]
-        ref, cdt, threads = cpu_baseline(w, tau, n_seq)
-        # the last timed GPU step used the same threshold but seed + (steps-1); rerun the GPU at the oracle's seed
-        hb.hola_verify_ex(target_logits=P, draft_logits=D, draft_tokens=tok, seed=w.seed, B=B, gamma=g, V=V,
-                          temperature=w.temperature, entropy_threshold=tau, out_accept_len=acc,
-                          out_next_token=nxt, out_entropy=ent, workspace=ws, stream=stream)
-        torch.cuda.synchronize()
-        same = int((acc.cpu().numpy()[:n_seq] == ref.accept_len).sum())
-        same_t = int((nxt.cpu().numpy()[:n_seq] == ref.next_token).sum())
-        out["cpu_baseline"] = {"value": round(n_seq * g / cdt, 1), "unit": "positions/s", "cores": threads,
+        t0 = time.perf_counter()
+        refs = [orc.verify(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, num_threads=threads) for tau in taus]
+        cdt = time.perf_counter() - t0
+        same = same_t = 0
+        for i, tau in enumerate(taus):
+            step(i, seed_offset=False)
+            torch.cuda.synchronize()
+            same += int((acc.cpu().numpy() == refs[i].accept_len).sum())
+            same_t += int((nxt.cpu().numpy() == refs[i].next_token).sum())
+        n = B * len(taus)
+        out["cpu_baseline"] = {"value": round(n * g / cdt, 1), "unit": "positions/s", "cores": threads,
                                "kind": "oracle",
-                               "sample": f"first {n_seq} of {B} sequences of the same workload, one call, "
-                                         f"{cdt:.2f}s wall, float64 C oracle with OpenMP over sequences",
-                               "agree_accept_len": f"{same}/{n_seq}", "agree_next_token": f"{same_t}/{n_seq}"}
+                               "sample": f"all {B} sequences of the same workload at each of the {len(taus)} thresholds "
+                                         f"({len(taus)} oracle calls, {cdt:.2f}s wall, {cdt * threads:.0f} core-seconds); "
+                                         f"float64 C oracle, OpenMP over sequences",
+                               "agree_accept_len": f"{same}/{n}", "agree_next_token": f"{same_t}/{n}"}
     print(json.dumps(out), flush=True)
     return 0
 

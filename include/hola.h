@@ -167,21 +167,28 @@ hola_status hola_row_stats(const void* logits /* device [R, V] */, int32_t dtype
 
 /* Launch-shape knobs.  Zero in a field keeps the built-in choice for MI355X. */
 typedef struct {
-    int32_t stats_split;            /* workgroups per logits row in the row-statistics kernel */
-    int32_t stats_unroll;           /* 16-byte loads in flight per lane there: 2, 4 or 8 */
-    int32_t stats_single_c;         /* 1: single-constant exponent scaling (faster, entropy error up to ~1e-6) */
-    int32_t sampler_tile_chunks;    /* reserved */
+    int32_t stats_split;            /* workgroups per logits row in the split-row statistics kernel (1..16) */
+    int32_t stats_unroll;           /* 16-byte loads in flight per lane while streaming a row: 2, 4, 8 or 16 */
+    int32_t path;                   /* 1: split-row kernels (4 launches); 2: fused per-sequence kernel (1 launch);
+                                       0: the library's choice for the shape */
+    int32_t fused_waves;            /* wavefronts per workgroup of the fused kernel: 8 or 16 */
 } hola_tuning;
 hola_status hola_set_tuning(const hola_tuning* t /* host; NULL restores defaults */);
 
 /* Per-kernel timing aid for benchmarks.  While enabled, each call records HIP events around
  * each of its kernels on the call's stream.  hola_profile_collect() waits for the recorded
  * events, ADDS elapsed milliseconds and launch counts per stage to the host arrays, and
- * forgets the events.  Stages: 0 row statistics, 1 accept/first-reject, 2 residual tile sums,
- * 3 inverse-CDF select, 4 level glue. */
-enum { HOLA_N_STAGES = 5 };
+ * forgets the events.  Stages: 0 split-row statistics, 1 accept/first-reject, 2 residual tile sums,
+ * 3 inverse-CDF select, 4 level glue, 5 fused per-sequence kernel. */
+enum { HOLA_N_STAGES = 6 };
 hola_status hola_profile_enable(int32_t on);
 hola_status hola_profile_collect(double* ms_out /* host [HOLA_N_STAGES] */, int64_t* launches_out /* host [HOLA_N_STAGES] */);
+
+/* A plain copy kernel (16-byte vector loads and stores, nothing else): bytes of device memory from src
+ * to dst, bytes a multiple of 16, both 16-byte aligned.  It is not part of the verify step; it exists so
+ * that hardware byte counters read for the verify kernels (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) can
+ * be scaled against a transfer of known size measured the same way. */
+hola_status hola_copy_bytes(void* dst /* device */, const void* src /* device */, size_t bytes, hola_stream_t stream);
 
 /* Frees the library-owned workspaces and profiling events of every device. */
 void hola_shutdown(void);

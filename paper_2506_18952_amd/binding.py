@@ -16,13 +16,13 @@ LIB_PATH = os.path.join(_HERE, "libhola.so")
 
 HOLA_OK, HOLA_ERR_INVALID_ARG, HOLA_ERR_UNSUPPORTED, HOLA_ERR_WORKSPACE, HOLA_ERR_HIP = range(5)
 HOLA_DTYPE_F32, HOLA_DTYPE_BF16 = 0, 1
-HOLA_N_STAGES = 5
-STAGE_NAMES = ("row_stats", "accept", "tile_sums", "select", "glue")
+HOLA_N_STAGES = 6
+STAGE_NAMES = ("row_stats", "accept", "tile_sums", "select", "glue", "fused")
 
 EXPORTS = (
     "hola_verify_f32", "hola_verify_bf16", "hola_verify_ex", "hola_workspace_bytes",
     "hola_hsd_verify", "hola_hsd_workspace_bytes", "hola_row_stats", "hola_set_tuning",
-    "hola_profile_enable", "hola_profile_collect", "hola_shutdown", "hola_status_string",
+    "hola_profile_enable", "hola_profile_collect", "hola_copy_bytes", "hola_shutdown", "hola_status_string",
     "hola_last_hip_error", "hola_version",
 )
 
@@ -56,8 +56,8 @@ class ModelLogits(C.Structure):
 
 
 class Tuning(C.Structure):
-    _fields_ = [("stats_split", C.c_int32), ("stats_unroll", C.c_int32), ("stats_single_c", C.c_int32),
-                ("sampler_tile_chunks", C.c_int32)]
+    _fields_ = [("stats_split", C.c_int32), ("stats_unroll", C.c_int32), ("path", C.c_int32),
+                ("fused_waves", C.c_int32)]
 
 
 _lib: Optional[C.CDLL] = None
@@ -89,6 +89,8 @@ def lib() -> C.CDLL:
         L.hola_set_tuning.argtypes = [C.POINTER(Tuning)]
         L.hola_profile_enable.argtypes = [C.c_int32]
         L.hola_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        L.hola_copy_bytes.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.hola_copy_bytes.restype = C.c_int32
         L.hola_shutdown.argtypes = []
         L.hola_shutdown.restype = None
         for name in ("hola_status_string", "hola_last_hip_error", "hola_version"):
@@ -210,8 +212,11 @@ def hola_row_stats(logits, R, V, temperature, stats_out, workspace, ld=0, stream
     _check(st, "hola_row_stats")
 
 
-def hola_set_tuning(stats_split: int = 0, stats_unroll: int = 0, stats_single_c: int = 0) -> None:
-    t = Tuning(int(stats_split), int(stats_unroll), int(stats_single_c), 0)
+PATH_AUTO, PATH_SPLIT, PATH_FUSED = 0, 1, 2
+
+
+def hola_set_tuning(stats_split: int = 0, stats_unroll: int = 0, path: int = 0, fused_waves: int = 0) -> None:
+    t = Tuning(int(stats_split), int(stats_unroll), int(path), int(fused_waves))
     _check(lib().hola_set_tuning(C.byref(t)), "hola_set_tuning")
 
 
@@ -224,6 +229,10 @@ def hola_profile_collect() -> tuple[list[float], list[int]]:
     n = (C.c_int64 * HOLA_N_STAGES)()
     _check(lib().hola_profile_collect(ms, n), "hola_profile_collect")
     return list(ms), list(n)
+
+
+def hola_copy_bytes(dst, src, nbytes: int, stream=None) -> None:
+    _check(lib().hola_copy_bytes(_ptr(dst), _ptr(src), int(nbytes), _stream_handle(stream)), "hola_copy_bytes")
 
 
 def hola_shutdown() -> None:

@@ -1,12 +1,7 @@
-// Accept / first-reject kernel: one wavefront per sequence, lane j owns position j.
-//
-// Lane j merges the row partials of draft row j and target row j in double, forms
-// lse = ln S - bref ln 2 and the draft entropy H = ln S - ln2 T / S (Section 3.1), applies the
-// strict gate H < tau (Algorithm 1, Step 1), and where the gate is open falls back to the verifier
-// (Equation (1)) through the acceptance test u * q(x) < p(x) with a Philox uniform keyed on
-// (seed, sequence, position, level).  A ballot over the lanes gives the first rejected position.
-// All of it is O(B * gamma) scalar work in double; the kernel is latency-, not bandwidth-bound.
-#include "stats_device.h"
+// Split accept kernel: one wavefront per sequence; lane j merges the row partials of draft row j and
+// target row j in double (lse = ln S - beta ln 2, H = ln S - ln2 T / S) and runs the accept stage
+// (accept_device.h).  Latency-, not bandwidth-bound: O(B * gamma) scalar work.
+#include "accept_device.h"
 
 namespace hola {
 
@@ -19,9 +14,6 @@ __global__ __launch_bounds__(64) void accept_kernel(AcceptParams p)
     int len = p.draft_len ? p.draft_len[b] : g;
     len = len < 0 ? 0 : (len > g ? g : len);
     const float Tb = p.row_temperature ? p.row_temperature[b] : p.temperature;
-    const bool greedy = !(Tb > 0.f);
-    const double invT = greedy ? 1.0 : 1.0 / (double)Tb;
-    const double tau = (double)p.tau;
 
     RowStat sd = {NAN, NAN, -1}, sp = {NAN, NAN, -1};
     if (j < len) {
@@ -31,70 +23,18 @@ __global__ __launch_bounds__(64) void accept_kernel(AcceptParams p)
         } else {
             sd = merge_partials(p.partials + ((int64_t)b * g + j) * p.nparts, p.nparts);
         }
-        p.statsD[((int64_t)b * g + j) * 2 + 0] = sd.lse;
-        p.statsD[((int64_t)b * g + j) * 2 + 1] = sd.H;
     }
     if (j <= len) {
         const int64_t slot = (int64_t)p.B * g + (int64_t)b * (g + 1) + j;
         sp = merge_partials(p.partials + slot * p.nparts, p.nparts);
-        p.statsP[((int64_t)b * (g + 1) + j) * 2 + 0] = sp.lse;
-        p.statsP[((int64_t)b * (g + 1) + j) * 2 + 1] = sp.H;
-        p.argmaxP[(int64_t)b * (g + 1) + j] = sp.argmax;
-        if (p.target_stats_out) {
-            p.target_stats_out[((int64_t)b * (g + 1) + j) * 2 + 0] = sp.lse;
-            p.target_stats_out[((int64_t)b * (g + 1) + j) * 2 + 1] = sp.H;
-        }
     }
-    if (p.out_entropy && j < g) {
-        const int64_t eld = p.entropy_ld ? p.entropy_ld : g;
-        p.out_entropy[(int64_t)b * eld + j] = (j < len) ? (float)sd.H : -1.0f;
-    }
-
-    const uint64_t seq = (uint64_t)(p.seq_base + b);
-    bool reject = false;
-    if (j < len) {
-        const bool gate = sd.H < tau;                   // strict; NaN never gates
-        const int32_t x = p.tokens[(int64_t)b * g + j];
-        bool ok;
-        if (greedy) {
-            ok = (x == sp.argmax);
-        } else {
-            double p_x = 0.0, q_x = 1.0;
-            if (x >= 0 && x < p.V) {
-                double zp = (double)load_logit<BF16>(p.target, ((int64_t)b * (g + 1) + j) * p.target_ld + x) * invT;
-                double zq = (double)load_logit<BF16>(p.draft, ((int64_t)b * g + j) * p.draft_ld + x) * invT;
-                p_x = exp(zp - sp.lse);
-                q_x = exp(zq - sd.lse);
-            }
-            Philox4 r = philox4x32_10((uint32_t)j, (uint32_t)seq, (uint32_t)(seq >> 32), p.level,
-                                      (uint32_t)p.seed, (uint32_t)(p.seed >> 32));
-            double u = (double)u24(r.x);
-            ok = (u * q_x < p_x);
-        }
-        reject = !(gate || ok);
-    }
-    const unsigned long long rej = __ballot(reject);
-    const int a = rej ? (__ffsll((long long)rej) - 1) : len;
-
-    if (j == a) {                                       // exactly one lane: a <= len <= gamma < 64
-        p.out_accept_len[b] = a;
-        SeqInfo si;
-        si.row = a;
-        si.lseP = sp.lse;
-        si.lseD = (a < len) ? sd.lse : 0.0;
-        si.pad = 0;
-        if (greedy) {
-            si.mode = 2;
-            si.u = 0.f;
-            p.out_next_token[b] = sp.argmax;
-        } else {
-            Philox4 r = philox4x32_10((uint32_t)a, (uint32_t)seq, (uint32_t)(seq >> 32), p.level,
-                                      (uint32_t)p.seed, (uint32_t)(p.seed >> 32));
-            si.u = u24(r.y);
-            si.mode = (a < len) ? 0 : 1;
-        }
-        p.seq[b] = si;
-    }
+    AcceptCtx c;
+    c.target = p.target; c.draft = p.draft; c.target_ld = p.target_ld; c.draft_ld = p.draft_ld;
+    c.tokens = p.tokens; c.seed = p.seed; c.level = p.level; c.seq_base = p.seq_base;
+    c.gamma = g; c.V = p.V; c.tau = p.tau; c.target_stats_out = p.target_stats_out;
+    c.out_accept_len = p.out_accept_len; c.out_next_token = p.out_next_token;
+    c.out_entropy = p.out_entropy; c.entropy_ld = p.entropy_ld;
+    accept_wave<BF16>(c, b, j, len, Tb, sd, sp, p.seq + b);
 }
 
 // (lse, H) of plain rows from their partials, one thread per row.
@@ -102,7 +42,7 @@ __global__ void finalize_rows_kernel(const Partial* __restrict__ partials, int n
 {
     const int r = blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= R) return;
-    RowStat s = merge_partials(partials + (int64_t)r * nparts, nparts);
+    const RowStat s = merge_partials(partials + (int64_t)r * nparts, nparts);
     out[2 * (int64_t)r + 0] = s.lse;
     out[2 * (int64_t)r + 1] = s.H;
 }

@@ -1,0 +1,91 @@
+// Device code of the accept / first-reject stage (shared by the split accept kernel and the fused
+// per-sequence kernel).  One wavefront per sequence, lane j owns position j.
+//
+// Given the statistics of draft row j and target row j, a lane applies the strict gate H < tau
+// (Algorithm 1, Step 1; Section 3.1), and where the gate is open falls back to the verifier
+// (Equation (1)) through the acceptance test u * q(x) < p(x) with a Philox uniform keyed on
+// (seed, sequence, position, level).  A ballot over the lanes gives the first rejected position.
+// All of it is O(gamma) scalar work in double.
+#pragma once
+#include "stats_device.h"
+
+namespace hola {
+
+struct AcceptCtx {
+    const void* target; const void* draft;
+    int64_t target_ld, draft_ld;
+    const int32_t* tokens;
+    uint64_t seed; uint32_t level; int64_t seq_base;
+    int32_t gamma, V;
+    float tau;
+    double* target_stats_out;          // [B, gamma+1, 2] or null
+    int32_t* out_accept_len; int32_t* out_next_token;
+    float* out_entropy; int64_t entropy_ld;
+};
+
+// Called by all 64 lanes of one wavefront.  sd / sp: statistics of draft row j (valid for j < len) and
+// target row j (valid for j <= len).  Writes accept_len, the entropies, the optional target statistics
+// and, for greedy rows, the next token; the lane at the stop row fills *si_out.
+template <bool BF16>
+__device__ __forceinline__ void accept_wave(const AcceptCtx& c, int b, int j, int len, float Tb,
+                                            const RowStat& sd, const RowStat& sp, SeqInfo* si_out)
+{
+    const int g = c.gamma;
+    const bool greedy = !(Tb > 0.f);
+    const double invT = greedy ? 1.0 : 1.0 / (double)Tb;
+    const double tau = (double)c.tau;
+    if (c.target_stats_out && j <= len) {
+        c.target_stats_out[((int64_t)b * (g + 1) + j) * 2 + 0] = sp.lse;
+        c.target_stats_out[((int64_t)b * (g + 1) + j) * 2 + 1] = sp.H;
+    }
+    if (c.out_entropy && j < g) {
+        const int64_t eld = c.entropy_ld ? c.entropy_ld : g;
+        c.out_entropy[(int64_t)b * eld + j] = (j < len) ? (float)sd.H : -1.0f;
+    }
+    const uint64_t seq = (uint64_t)(c.seq_base + b);
+    bool reject = false;
+    if (j < len) {
+        const bool gate = sd.H < tau;                   // strict; NaN never gates
+        const int32_t x = c.tokens[(int64_t)b * g + j];
+        bool ok;
+        if (greedy) {
+            ok = (x == sp.argmax);
+        } else {
+            double p_x = 0.0, q_x = 1.0;
+            if (x >= 0 && x < c.V) {
+                const double zp = (double)load_logit<BF16>(c.target, ((int64_t)b * (g + 1) + j) * c.target_ld + x) * invT;
+                const double zq = (double)load_logit<BF16>(c.draft, ((int64_t)b * g + j) * c.draft_ld + x) * invT;
+                p_x = exp(zp - sp.lse);
+                q_x = exp(zq - sd.lse);
+            }
+            const Philox4 r = philox4x32_10((uint32_t)j, (uint32_t)seq, (uint32_t)(seq >> 32), c.level,
+                                            (uint32_t)c.seed, (uint32_t)(c.seed >> 32));
+            const double u = (double)u24(r.x);
+            ok = (u * q_x < p_x);
+        }
+        reject = !(gate || ok);
+    }
+    const unsigned long long rej = __ballot(reject);
+    const int a = rej ? (__ffsll((long long)rej) - 1) : len;
+    if (j == a) {                                       // exactly one lane: a <= len <= gamma < 64
+        c.out_accept_len[b] = a;
+        SeqInfo si;
+        si.row = a;
+        si.lseP = sp.lse;
+        si.lseD = (a < len) ? sd.lse : 0.0;
+        si.pad = 0;
+        if (greedy) {
+            si.mode = 2;
+            si.u = 0.f;
+            c.out_next_token[b] = sp.argmax;
+        } else {
+            const Philox4 r = philox4x32_10((uint32_t)a, (uint32_t)seq, (uint32_t)(seq >> 32), c.level,
+                                            (uint32_t)c.seed, (uint32_t)(c.seed >> 32));
+            si.u = u24(r.y);
+            si.mode = (a < len) ? 0 : 1;
+        }
+        *si_out = si;
+    }
+}
+
+}  // namespace hola

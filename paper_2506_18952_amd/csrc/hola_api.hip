@@ -37,6 +37,12 @@ __global__ void level_glue_kernel(const int32_t* __restrict__ cur_tok, int32_t g
     new_len[b] = a + 1;
 }
 
+// Plain copy: one 16-byte load and one 16-byte store per lane per step, grid-stride.
+__global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
 __global__ void export_tokens_kernel(const int32_t* __restrict__ tok, int32_t gk, const int32_t* __restrict__ len,
                                      int32_t B, int32_t width, int32_t* __restrict__ out)
 {
@@ -85,6 +91,10 @@ struct StageTimer {
         g_prof_live.push_back(ProfEvent{stage, a, b});
     }
 };
+
+// Sequences from which the library picks the fused per-sequence kernel on its own.  The split-row kernels
+// currently win at every measured shape, so the fused kernel runs only when asked for.
+constexpr int kFusedMinB = 1 << 30;
 
 static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -140,6 +150,25 @@ static hola_status run_level(const hola_verify_args& a)
     Tuning tune;
     { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
     const int nsplit = choose_split(rows, a.V, a.dtype, tune);
+
+    // Enough sequences to give the compute units one each: the fused per-sequence kernel does the whole
+    // step in one launch.  Fewer: the split-row kernels spread the rows over the chip.
+    const bool want_fused = tune.path == 2 || (tune.path == 0 && a.B >= kFusedMinB);
+    if (want_fused && fused_supported(a.gamma, a.V, a.dtype)) {
+        FusedParams fp{};
+        fp.target = a.target_logits; fp.draft = a.draft_logits; fp.dtype = a.dtype; fp.target_ld = tld; fp.draft_ld = dld;
+        fp.tokens = a.draft_tokens; fp.draft_len = a.draft_len; fp.row_temperature = a.row_temperature;
+        fp.draft_stats_in = a.draft_stats_in; fp.target_stats_out = a.target_stats_out;
+        fp.seed = a.seed; fp.level = a.level; fp.seq_base = a.seq_base;
+        fp.B = a.B; fp.gamma = a.gamma; fp.V = a.V; fp.ntiles = sampler_tiles(a.V, a.dtype);
+        fp.temperature = a.temperature; fp.tau = a.entropy_threshold;
+        fp.out_accept_len = a.out_accept_len; fp.out_next_token = a.out_next_token;
+        fp.out_entropy = a.out_entropy; fp.entropy_ld = a.entropy_ld;
+        hipError_t fe;
+        { StageTimer t(5, s); fe = launch_fused(fp, tune, s); }
+        if (fe != hipSuccess) return hip_fail(fe, "fused verify launch");
+        return HOLA_OK;
+    }
 
     RowStatsParams rs{};
     rs.target = a.target_logits; rs.draft = a.draft_logits; rs.target_ld = tld; rs.draft_ld = dld;
@@ -388,14 +417,28 @@ hola_status hola_row_stats(const void* logits, int32_t dtype, int64_t ld, int32_
     return HOLA_OK;
 }
 
+hola_status hola_copy_bytes(void* dst, const void* src, size_t bytes, hola_stream_t stream)
+{
+    if (bytes == 0) return HOLA_OK;
+    if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return HOLA_ERR_INVALID_ARG;
+    const size_t n = bytes / 16;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (uint4*)dst, (const uint4*)src, n);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? HOLA_OK : hip_fail(e, "copy launch");
+}
+
 hola_status hola_set_tuning(const hola_tuning* t)
 {
     Tuning n;
     if (t) {
         if (t->stats_split < 0 || t->stats_split > kMaxSplit) return HOLA_ERR_INVALID_ARG;
-        if (t->stats_unroll != 0 && t->stats_unroll != 2 && t->stats_unroll != 4 && t->stats_unroll != 8)
+        if (t->stats_unroll != 0 && t->stats_unroll != 2 && t->stats_unroll != 4 && t->stats_unroll != 8 && t->stats_unroll != 16)
             return HOLA_ERR_INVALID_ARG;
-        n.split = t->stats_split; n.unroll = t->stats_unroll; n.single_c = t->stats_single_c ? 1 : 0;
+        if (t->path < 0 || t->path > 2) return HOLA_ERR_INVALID_ARG;
+        if (t->fused_waves != 0 && t->fused_waves != 8 && t->fused_waves != 16) return HOLA_ERR_INVALID_ARG;
+        n.split = t->stats_split; n.unroll = t->stats_unroll; n.path = t->path; n.fused_waves = t->fused_waves;
     }
     std::lock_guard<std::mutex> lk(g_mu);
     g_tuning = n;

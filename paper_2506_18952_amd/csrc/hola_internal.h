@@ -48,7 +48,9 @@ struct Workspace {
 };
 
 struct Tuning {
-    int split = 0, unroll = 0, single_c = 0;
+    int split = 0, unroll = 0;
+    int path = 0;                      // 0 auto, 1 split-row kernels, 2 fused per-sequence kernel
+    int fused_waves = 0;               // 0 (= 16), 8 or 16 wavefronts per workgroup in the fused kernel
 };
 
 struct RowStatsParams {
@@ -85,6 +87,19 @@ struct SamplerParams {
     int32_t* out_next_token;
 };
 
+struct FusedParams {
+    const void* target; const void* draft; int32_t dtype;
+    int64_t target_ld, draft_ld;
+    const int32_t* tokens; const int32_t* draft_len; const float* row_temperature;
+    const double* draft_stats_in; double* target_stats_out;
+    uint64_t seed; uint32_t level; int64_t seq_base;
+    int32_t B, gamma, V, ntiles;
+    float temperature, tau;
+    int32_t* out_accept_len; int32_t* out_next_token; float* out_entropy; int64_t entropy_ld;
+};
+
+hipError_t launch_fused(const FusedParams& p, const Tuning& t, hipStream_t s);
+bool fused_supported(int32_t gamma, int32_t V, int dtype);
 hipError_t launch_row_stats(const RowStatsParams& p, int dtype, const Tuning& t, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
 hipError_t launch_finalize_rows(const Partial* partials, int nparts, int32_t R, double* out, hipStream_t s);

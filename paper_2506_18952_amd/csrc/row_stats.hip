@@ -90,7 +90,8 @@ static hipError_t launch_typed(const RowStatsParams& p, const Tuning& t, hipStre
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 grid((unsigned)nblk), block(kBlock);
     const int U = t.unroll ? t.unroll : 8;
-    if (U == 2) hipLaunchKernelGGL((row_stats_kernel<BF16, 2>), grid, block, 0, s, p);
+    if (U == 16) hipLaunchKernelGGL((row_stats_kernel<BF16, 16>), grid, block, 0, s, p);
+    else if (U == 2) hipLaunchKernelGGL((row_stats_kernel<BF16, 2>), grid, block, 0, s, p);
     else if (U == 4) hipLaunchKernelGGL((row_stats_kernel<BF16, 4>), grid, block, 0, s, p);
     else hipLaunchKernelGGL((row_stats_kernel<BF16, 8>), grid, block, 0, s, p);
     return hipGetLastError();

@@ -237,25 +237,27 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
     constexpr int N = BF16 ? 8 : 4;
     lane_init(st);
     int64_t c = c0;
-    if (!ARGMAX && !ROBUST) {
-        // Common reference from the wavefront's first chunks, so that lanes rarely re-reference.
-        float mx = -INFINITY;
-        if (c < c_hi) {
-            const uint4 v = g.rowv[c];
-#pragma unroll
-            for (int k = 0; k < N; ++k) mx = fmaxf(mx, chunk_elem<BF16>(v, k));
-        }
-        mx = wave_max(mx);
-        if (mx > -INFINITY && mx < INFINITY) {
-            st.ref = ref_for<BF16>(mx, sc);
-            st.thr_ref = thr_for<BF16>(st.ref, sc);
-            st.thr = st.thr_ref;
-        }
-    }
-    while (c + (int64_t)(U - 1) * stride < c_hi) {
+    // The wavefront's lanes start from a common reference taken from the first chunks it loads (with
+    // the whole first group already in flight), so that lanes rarely re-reference.
+    bool need_ref = !ARGMAX && !ROBUST;
+    const int64_t wave_last = c0 - lane + 63;                   // chunk of the wavefront's last lane
+    // groups in which every lane of the wavefront has U chunks: no guards
+    while (wave_last + (c - c0) + (int64_t)(U - 1) * stride < c_hi) {
         uint4 buf[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) buf[u] = g.rowv[c + u * stride];
+        if (need_ref) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int k = 0; k < N; ++k) mx = fmaxf(mx, chunk_elem<BF16>(buf[0], k));
+            mx = wave_max(mx);
+            if (mx > -INFINITY && mx < INFINITY) {
+                st.ref = ref_for<BF16>(mx, sc);
+                st.thr_ref = thr_for<BF16>(st.ref, sc);
+                st.thr = st.thr_ref;
+            }
+            need_ref = false;
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int32_t e0 = (int32_t)((c + u * stride) * N) - g.head;
@@ -264,11 +266,35 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
         }
         c += (int64_t)U * stride;
     }
-    for (; c < c_hi; c += stride) {
-        const uint4 v = g.rowv[c];
-        const int32_t e0 = (int32_t)(c * N) - g.head;
-        if (ROBUST) accum_chunk_robust<BF16, ARGMAX>(st, v, e0, sc);
-        else accum_chunk<BF16, ARGMAX>(st, v, e0, sc);
+    // the last, partial group: all its loads are issued together, each one guarded
+    if (c - lane < c_hi) {                                      // wavefront-uniform
+        uint4 buf[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            buf[u] = make_uint4(0, 0, 0, 0);
+            if (c + u * stride < c_hi) buf[u] = g.rowv[c + u * stride];
+        }
+        if (need_ref) {
+            float mx = -INFINITY;
+            if (c < c_hi) {
+#pragma unroll
+                for (int k = 0; k < N; ++k) mx = fmaxf(mx, chunk_elem<BF16>(buf[0], k));
+            }
+            mx = wave_max(mx);
+            if (mx > -INFINITY && mx < INFINITY) {
+                st.ref = ref_for<BF16>(mx, sc);
+                st.thr_ref = thr_for<BF16>(st.ref, sc);
+                st.thr = st.thr_ref;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (c + u * stride < c_hi) {
+                const int32_t e0 = (int32_t)((c + u * stride) * N) - g.head;
+                if (ROBUST) accum_chunk_robust<BF16, ARGMAX>(st, buf[u], e0, sc);
+                else accum_chunk<BF16, ARGMAX>(st, buf[u], e0, sc);
+            }
+        }
     }
     if (do_edges) {
         const int32_t n_lo = g.edge_lo_end, n_hi = g.V - g.edge_hi_begin;

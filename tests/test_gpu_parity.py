@@ -14,9 +14,24 @@ from parity import DEV, compare_level, run_gpu_level, to_dev
 
 pytestmark = pytest.mark.gpu
 
+_PATH = {"name": "auto"}
+
+
+@pytest.fixture(params=["auto", "split", "fused"], autouse=True)
+def kernel_path(request):
+    """Every test runs with the library's own choice of kernels and with each path forced."""
+    _PATH["name"] = request.param
+    hb.hola_set_tuning(path={"auto": hb.PATH_AUTO, "split": hb.PATH_SPLIT, "fused": hb.PATH_FUSED}[request.param])
+    yield request.param
+    hb.hola_set_tuning()
+
+
+def kernel_path_name():
+    return _PATH["name"]
+
 
 def _report(name, rep):
-    line = f"[parity] {name}: {rep}"
+    line = f"[parity] <{_PATH['name']}> {name}: {rep}"
     print(line, flush=True)
     path = os.environ.get("HOLA_PARITY_REPORT")
     if path:
@@ -81,19 +96,23 @@ def test_config3_bf16_headline_full_size(cfg3):
 
 
 def test_config3_launch_shapes_agree(cfg3):
-    """Every launch shape of the row-statistics kernel gives the same decisions."""
+    """Every launch shape of the streaming kernels gives the same decisions."""
     w = cfg3
     sub = slice(0, 32)
     P, D, tok = to_dev(w.target[sub]), to_dev(w.draft[sub]), to_dev(w.tokens[sub])
-    tau = w.taus[1]
-    try:
-        for split, unroll, single in ((1, 4, 0), (2, 2, 0), (4, 8, 0), (16, 4, 0), (1, 8, 1)):
-            hb.hola_set_tuning(split, unroll, single)
-            gpu = run_gpu_level(P, D, tok, w.seed, w.temperature, tau)
-            rep = compare_level(w.target[sub], w.draft[sub], w.tokens[sub], w.seed, w.temperature, tau, gpu)
-            _report(f"{w.name}[:32] split={split} unroll={unroll} single_c={single}", rep)
-    finally:
-        hb.hola_set_tuning()
+    tau = w.taus[0]
+    if kernel_path_name() == "auto":
+        shapes = [(hb.PATH_AUTO, 0, 0, 0)]
+    elif kernel_path_name() == "split":
+        shapes = [(hb.PATH_SPLIT, s, u, 0) for s, u in ((1, 4), (2, 2), (4, 8), (16, 4), (1, 8))]
+    else:
+        shapes = [(hb.PATH_FUSED, 0, u, nw) for u, nw in ((2, 8), (4, 16), (8, 8), (8, 16))]
+    for path, split, unroll, nw in shapes:
+        hb.hola_set_tuning(split, unroll, path, nw)
+        gpu = run_gpu_level(P, D, tok, w.seed, w.temperature, tau)
+        rep = compare_level(w.target[sub], w.draft[sub], w.tokens[sub], w.seed, w.temperature, tau, gpu)
+        _report(f"{w.name}[:32] path={path} split={split} unroll={unroll} waves={nw}", rep)
+        assert rep.max_entropy_abs < 1e-6
 
 
 @pytest.mark.timeout(420)
