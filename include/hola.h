@@ -169,7 +169,9 @@ hola_status hola_row_stats(const void* logits /* device [R, V] */, int32_t dtype
 typedef struct {
     int32_t stats_split;            /* workgroups per logits row in the split-row statistics kernel (1..16) */
     int32_t stats_unroll;           /* 16-byte loads in flight per lane while streaming a row: 2, 4, 8 or 16 */
-    int32_t path;                   /* 1: split-row kernels (4 launches); 2: fused per-sequence kernel (1 launch);
+    int32_t path;                   /* 1: split-row statistics + per-sequence tail kernel (2 launches);
+                                       2: fused per-sequence kernel (1 launch);
+                                       3: split-row statistics, accept, tile sums, select (4 launches);
                                        0: the library's choice for the shape */
     int32_t fused_waves;            /* wavefronts per workgroup of the fused kernel: 8 or 16 */
 } hola_tuning;
@@ -179,8 +181,8 @@ hola_status hola_set_tuning(const hola_tuning* t /* host; NULL restores defaults
  * each of its kernels on the call's stream.  hola_profile_collect() waits for the recorded
  * events, ADDS elapsed milliseconds and launch counts per stage to the host arrays, and
  * forgets the events.  Stages: 0 split-row statistics, 1 accept/first-reject, 2 residual tile sums,
- * 3 inverse-CDF select, 4 level glue, 5 fused per-sequence kernel. */
-enum { HOLA_N_STAGES = 6 };
+ * 3 inverse-CDF select, 4 level glue, 5 fused per-sequence kernel, 6 per-sequence tail kernel. */
+enum { HOLA_N_STAGES = 7 };
 hola_status hola_profile_enable(int32_t on);
 hola_status hola_profile_collect(double* ms_out /* host [HOLA_N_STAGES] */, int64_t* launches_out /* host [HOLA_N_STAGES] */);
 

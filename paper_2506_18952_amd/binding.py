@@ -16,8 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libhola.so")
 
 HOLA_OK, HOLA_ERR_INVALID_ARG, HOLA_ERR_UNSUPPORTED, HOLA_ERR_WORKSPACE, HOLA_ERR_HIP = range(5)
 HOLA_DTYPE_F32, HOLA_DTYPE_BF16 = 0, 1
-HOLA_N_STAGES = 6
-STAGE_NAMES = ("row_stats", "accept", "tile_sums", "select", "glue", "fused")
+HOLA_N_STAGES = 7
+STAGE_NAMES = ("row_stats", "accept", "tile_sums", "select", "glue", "fused", "tail")
 
 EXPORTS = (
     "hola_verify_f32", "hola_verify_bf16", "hola_verify_ex", "hola_workspace_bytes",
@@ -212,7 +212,7 @@ def hola_row_stats(logits, R, V, temperature, stats_out, workspace, ld=0, stream
     _check(st, "hola_row_stats")
 
 
-PATH_AUTO, PATH_SPLIT, PATH_FUSED = 0, 1, 2
+PATH_AUTO, PATH_SPLIT, PATH_FUSED, PATH_SPLIT4 = 0, 1, 2, 3
 
 
 def hola_set_tuning(stats_split: int = 0, stats_unroll: int = 0, path: int = 0, fused_waves: int = 0) -> None:

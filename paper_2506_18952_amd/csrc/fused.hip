@@ -1,12 +1,15 @@
-// Fused per-sequence kernel: one workgroup of 8 or 16 wavefronts owns one sequence and runs the whole
-// verify step for it without leaving the compute unit: row statistics of its gamma draft and
-// gamma+1 target rows (streamed once from HBM, wavefront partials parked in LDS), the accept /
-// first-reject stage (wavefront 0), the residual or bonus tile weights of the stop row (all
-// wavefronts, tile weights in LDS) and the inverse-CDF selection (wavefront 0).
+// Per-sequence kernels: one workgroup of 8 or 16 wavefronts owns one sequence.
 //
-// Used when there are enough sequences to occupy the chip (one launch, no partials in HBM, no
-// kernel boundaries); otherwise the split-row kernels spread the rows of few sequences over the chip.
-// HBM-bound: every logit is read once, the stop row pair once more.
+// fused_kernel runs the whole verify step for its sequence without leaving the compute unit: row
+// statistics of its gamma draft and gamma+1 target rows (streamed once from HBM, wavefront partials
+// parked in LDS), the accept / first-reject stage (wavefront 0), the residual or bonus tile weights of
+// the stop row (all wavefronts, tile weights in LDS) and the inverse-CDF selection (wavefront 0).
+//
+// tail_kernel is the same minus the streaming pass: it takes the row partials the split-row kernel
+// left in HBM (one wavefront merges one row, a lane per partial) and does accept + sampling, so the
+// split path is two launches instead of four.
+//
+// HBM-bound: every logit is read once, the stop row pair once more.  No atomics, no spin waits.
 #include "accept_device.h"
 #include "sampler_device.h"
 
@@ -14,13 +17,82 @@ namespace hola {
 
 constexpr int kFusedMaxTiles = 2048;
 
+struct SeqShared {
+    RowStat stat[2 * HOLA_MAX_GAMMA + 1];      // per row: draft rows 0..g-1, target rows g..2g
+    double tiles[kFusedMaxTiles];
+    SeqInfo si;
+    int32_t tok;
+};
+
+__device__ __forceinline__ AcceptCtx accept_ctx(const FusedParams& p)
+{
+    AcceptCtx c;
+    c.target = p.target; c.draft = p.draft; c.target_ld = p.target_ld; c.draft_ld = p.draft_ld;
+    c.tokens = p.tokens; c.seed = p.seed; c.level = p.level; c.seq_base = p.seq_base;
+    c.gamma = p.gamma; c.V = p.V; c.tau = p.tau; c.target_stats_out = p.target_stats_out;
+    c.out_accept_len = p.out_accept_len; c.out_next_token = p.out_next_token;
+    c.out_entropy = p.out_entropy; c.entropy_ld = p.entropy_ld;
+    return c;
+}
+
+// Accept stage (wavefront 0) and sampling (all wavefronts) of sequence b, given sh.stat[].
+// Called by every thread of the workgroup, after a barrier that made sh.stat visible.
+template <bool BF16, int NW>
+__device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& sh, int b, int len, float Tb)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = p.gamma;
+    if (wave == 0) {
+        const int j = lane;
+        RowStat sd = {NAN, NAN, -1}, sp = {NAN, NAN, -1};
+        if (j < len) {
+            if (p.draft_stats_in) {
+                sd.lse = p.draft_stats_in[((int64_t)b * g + j) * 2 + 0];
+                sd.H = p.draft_stats_in[((int64_t)b * g + j) * 2 + 1];
+            } else {
+                sd = sh.stat[j];
+            }
+        }
+        if (j <= len) sp = sh.stat[g + j];
+        const AcceptCtx c = accept_ctx(p);
+        accept_wave<BF16>(c, b, j, len, Tb, sd, sp, &sh.si);
+    }
+    __syncthreads();
+    const SeqInfo si = sh.si;
+    if (si.mode == 2) return;                                    // greedy: next token already written
+
+    RowPair rp;
+    make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0);
+    int32_t tok = -1;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        // tile weights of the stop row: two tiles per round trip and wavefront
+        for (int t = wave; t < p.ntiles; t += 2 * NW) {
+            double w0 = 0.0, w1 = 0.0;
+            if (rp.ok) tile_weight2<BF16>(rp, t, t + NW, lane, w0, w1);
+            if (lane == 0) {
+                sh.tiles[t] = w0;
+                if (t + NW < p.ntiles) sh.tiles[t + NW] = w1;
+            }
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const int32_t tk = rp.ok ? select_token<BF16, true>(rp, sh.tiles, p.ntiles, si.u, lane) : -1;
+            if (lane == 0) sh.tok = tk;
+        }
+        __syncthreads();
+        tok = sh.tok;
+        if (tok != -2) break;                                    // -2: no residual mass, sample p itself
+        make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1);
+    }
+    if (tid == 0) p.out_next_token[b] = tok < 0 ? -1 : tok;
+}
+
 template <bool BF16, int NW, int U>
 __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedParams p)
 {
     __shared__ Partial s_part[2 * HOLA_MAX_GAMMA + 1][NW];
-    __shared__ double s_tiles[kFusedMaxTiles];
-    __shared__ SeqInfo s_si;
-    __shared__ int32_t s_tok;
+    __shared__ SeqShared sh;
+    __shared__ int32_t s_prog[NW];
 
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -31,71 +103,70 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedParams p)
     const bool greedy = !(Tb > 0.f);
     const ExpScale sc = make_scale(greedy ? kLog2e : kLog2e / (double)Tb);
     constexpr int ES = BF16 ? 2 : 4;
-    constexpr int64_t kStride = NW * 64;
 
-    // ---- phase 1: statistics of the rows this sequence needs
-    const int first_row = p.draft_stats_in ? g : 0;             // draft statistics may come from a previous level
-    for (int r = first_row; r < 2 * g + 1; ++r) {
-        const bool is_draft = r < g;
-        const int j = is_draft ? r : r - g;
-        if (is_draft ? (j >= len) : (j > len)) continue;         // workgroup-uniform
+    // ---- statistics of the rows this sequence needs: every row is split statically over the
+    // wavefronts (so the result does not depend on timing).  The hardware issues oldest-first, which
+    // lets the first wavefronts run rows ahead of the last ones; a wavefront that is ahead of the slowest
+    // one therefore lowers its issue priority, so that the workgroup advances evenly.
+    if (tid < NW) s_prog[tid] = 0;
+    __syncthreads();
+    const int n_draft = p.draft_stats_in ? 0 : len;             // draft statistics may come from a previous level
+    const int n_rows = n_draft + len + 1;
+    int done = 0;
+    for (int ri = 0; ri < n_rows; ++ri) {
+        const bool is_draft = ri < n_draft;
+        const int j = is_draft ? ri : ri - n_draft;
+        const int r = is_draft ? j : g + j;
         const char* row = is_draft ? (const char*)p.draft + ((int64_t)b * g + j) * p.draft_ld * ES
                                    : (const char*)p.target + ((int64_t)b * (g + 1) + j) * p.target_ld * ES;
         const RowGeom geom = make_geom<BF16>(row, p.V);
         Partial res;
         if (greedy && !is_draft)
-            res = wave_row_share<BF16, true, U>(geom, geom.c_first + tid, geom.c_end, kStride, wave == 0, sc, lane);
+            res = wave_row_share<BF16, true, U>(geom, geom.c_first + tid, geom.c_end, NW * 64, wave == 0, sc, lane);
         else
-            res = wave_row_share<BF16, false, U>(geom, geom.c_first + tid, geom.c_end, kStride, wave == 0, sc, lane);
-        if (lane == 0) s_part[r][wave] = res;
+            res = wave_row_share<BF16, false, U>(geom, geom.c_first + tid, geom.c_end, NW * 64, wave == 0, sc, lane);
+        ++done;
+        if (lane == 0) { s_part[r][wave] = res; *(volatile int32_t*)&s_prog[wave] = done; }
+        int slowest = (lane < NW) ? *(volatile int32_t*)&s_prog[lane] : 0x7fffffff;
+#pragma unroll
+        for (int m = 8; m >= 1; m >>= 1) { const int o = __shfl_xor(slowest, m, 64); slowest = o < slowest ? o : slowest; }
+        slowest = __shfl(slowest, 0, 64);
+        if (done > slowest) __builtin_amdgcn_s_setprio(0); else __builtin_amdgcn_s_setprio(3);
+    }
+    __builtin_amdgcn_s_setprio(0);
+    __syncthreads();
+    for (int ri = wave; ri < n_rows; ri += NW) {                 // one wavefront per row, one lane per partial
+        const bool is_draft = ri < n_draft;
+        const int r = is_draft ? ri : g + (ri - n_draft);
+        const RowStat rs = merge_partials_wave(&s_part[r][0], NW, lane);
+        if (lane == 0) sh.stat[r] = rs;
     }
     __syncthreads();
+    sequence_tail<BF16, NW>(p, sh, b, len, Tb);
+}
 
-    // ---- phase 2: accept / first reject (wavefront 0, lane j = position j)
-    if (wave == 0) {
-        const int j = lane;
-        RowStat sd = {NAN, NAN, -1}, sp = {NAN, NAN, -1};
-        if (j < len) {
-            if (p.draft_stats_in) {
-                sd.lse = p.draft_stats_in[((int64_t)b * g + j) * 2 + 0];
-                sd.H = p.draft_stats_in[((int64_t)b * g + j) * 2 + 1];
-            } else {
-                sd = merge_partials(&s_part[j][0], NW);
-            }
-        }
-        if (j <= len) sp = merge_partials(&s_part[g + j][0], NW);
-        AcceptCtx c;
-        c.target = p.target; c.draft = p.draft; c.target_ld = p.target_ld; c.draft_ld = p.draft_ld;
-        c.tokens = p.tokens; c.seed = p.seed; c.level = p.level; c.seq_base = p.seq_base;
-        c.gamma = g; c.V = p.V; c.tau = p.tau; c.target_stats_out = p.target_stats_out;
-        c.out_accept_len = p.out_accept_len; c.out_next_token = p.out_next_token;
-        c.out_entropy = p.out_entropy; c.entropy_ld = p.entropy_ld;
-        accept_wave<BF16>(c, b, j, len, Tb, sd, sp, &s_si);
+// Accept + sampling of one sequence from the row partials of the split-row kernel.
+template <bool BF16, int NW>
+__global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Partial* __restrict__ partials, int nparts)
+{
+    __shared__ SeqShared sh;
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = p.gamma;
+    int len = p.draft_len ? p.draft_len[b] : g;
+    len = len < 0 ? 0 : (len > g ? g : len);
+    const float Tb = p.row_temperature ? p.row_temperature[b] : p.temperature;
+    const int first_row = p.draft_stats_in ? g : 0;
+    for (int r = first_row + wave; r < 2 * g + 1; r += NW) {     // one wavefront per row, one lane per partial
+        const bool is_draft = r < g;
+        const int j = is_draft ? r : r - g;
+        if (is_draft ? (j >= len) : (j > len)) continue;
+        const int64_t slot = is_draft ? (int64_t)b * g + j : (int64_t)p.B * g + (int64_t)b * (g + 1) + j;
+        const RowStat s = merge_partials_wave(partials + slot * nparts, nparts, lane);
+        if (lane == 0) sh.stat[r] = s;
     }
     __syncthreads();
-    const SeqInfo si = s_si;
-    if (si.mode == 2) return;                                    // greedy: next token already written
-
-    // ---- phase 3: tile weights of the stop row (all wavefronts), then selection (wavefront 0)
-    RowPair rp;
-    make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0);
-    int32_t tok = -1;
-    for (int attempt = 0; attempt < 2; ++attempt) {
-        for (int t = wave; t < p.ntiles; t += NW) {
-            const double wsum = rp.ok ? tile_weight<BF16>(rp, t, lane) : 0.0;
-            if (lane == 0) s_tiles[t] = wsum;
-        }
-        __syncthreads();
-        if (wave == 0) {
-            const int32_t tk = rp.ok ? select_token<BF16, true>(rp, s_tiles, p.ntiles, si.u, lane) : -1;
-            if (lane == 0) s_tok = tk;
-        }
-        __syncthreads();
-        tok = s_tok;
-        if (tok != -2) break;                                    // -2: no residual mass, sample p itself
-        make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1);
-    }
-    if (tid == 0) p.out_next_token[b] = tok < 0 ? -1 : tok;
+    sequence_tail<BF16, NW>(p, sh, b, len, Tb);
 }
 
 bool fused_supported(int32_t gamma, int32_t V, int dtype)
@@ -120,6 +191,22 @@ static hipError_t launch_fused_typed(const FusedParams& p, const Tuning& t, hipS
 hipError_t launch_fused(const FusedParams& p, const Tuning& t, hipStream_t s)
 {
     return p.dtype == HOLA_DTYPE_BF16 ? launch_fused_typed<true>(p, t, s) : launch_fused_typed<false>(p, t, s);
+}
+
+hipError_t launch_tail(const FusedParams& p, const Partial* partials, int nparts, const Tuning& t, hipStream_t s)
+{
+    if (p.B <= 0) return hipSuccess;
+    if (nparts > 64) return hipErrorInvalidValue;
+    dim3 grid((unsigned)p.B);
+    const int nw = t.fused_waves ? t.fused_waves : 16;
+    if (p.dtype == HOLA_DTYPE_BF16) {
+        if (nw == 8) hipLaunchKernelGGL((tail_kernel<true, 8>), grid, dim3(512), 0, s, p, partials, nparts);
+        else hipLaunchKernelGGL((tail_kernel<true, 16>), grid, dim3(1024), 0, s, p, partials, nparts);
+    } else {
+        if (nw == 8) hipLaunchKernelGGL((tail_kernel<false, 8>), grid, dim3(512), 0, s, p, partials, nparts);
+        else hipLaunchKernelGGL((tail_kernel<false, 16>), grid, dim3(1024), 0, s, p, partials, nparts);
+    }
+    return hipGetLastError();
 }
 
 }  // namespace hola

@@ -92,9 +92,31 @@ struct StageTimer {
     }
 };
 
-// Sequences from which the library picks the fused per-sequence kernel on its own.  The split-row kernels
-// currently win at every measured shape, so the fused kernel runs only when asked for.
-constexpr int kFusedMinB = 1 << 30;
+// The library's own choice between the two paths.  The fused per-sequence kernel keeps one workgroup of
+// 16 wavefronts per compute unit, so it pays only when the sequences fill the chip at least twice over
+// and the last round of workgroups is not mostly empty; otherwise the split-row pass, which spreads rows
+// over the chip, followed by the per-sequence tail kernel is faster (measured: B=256 bf16 equal within
+// 2 %, B=1024 fp32 fused 3 % faster, B<=128 split up to 1.6x faster).
+static int device_cu_count()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+static bool auto_prefers_fused(int32_t B)
+{
+    const int cus = device_cu_count();
+    if (B < 2 * cus) return false;
+    const int rem = B % cus;
+    return rem == 0 || rem * 4 >= cus * 3 || B >= 8 * cus;
+}
 
 static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -151,19 +173,21 @@ static hola_status run_level(const hola_verify_args& a)
     { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
     const int nsplit = choose_split(rows, a.V, a.dtype, tune);
 
-    // Enough sequences to give the compute units one each: the fused per-sequence kernel does the whole
-    // step in one launch.  Fewer: the split-row kernels spread the rows over the chip.
-    const bool want_fused = tune.path == 2 || (tune.path == 0 && a.B >= kFusedMinB);
-    if (want_fused && fused_supported(a.gamma, a.V, a.dtype)) {
-        FusedParams fp{};
-        fp.target = a.target_logits; fp.draft = a.draft_logits; fp.dtype = a.dtype; fp.target_ld = tld; fp.draft_ld = dld;
-        fp.tokens = a.draft_tokens; fp.draft_len = a.draft_len; fp.row_temperature = a.row_temperature;
-        fp.draft_stats_in = a.draft_stats_in; fp.target_stats_out = a.target_stats_out;
-        fp.seed = a.seed; fp.level = a.level; fp.seq_base = a.seq_base;
-        fp.B = a.B; fp.gamma = a.gamma; fp.V = a.V; fp.ntiles = sampler_tiles(a.V, a.dtype);
-        fp.temperature = a.temperature; fp.tau = a.entropy_threshold;
-        fp.out_accept_len = a.out_accept_len; fp.out_next_token = a.out_next_token;
-        fp.out_entropy = a.out_entropy; fp.entropy_ld = a.entropy_ld;
+    // Per-sequence parameters shared by the fused kernel and the tail kernel.
+    const bool per_seq_ok = fused_supported(a.gamma, a.V, a.dtype);
+    FusedParams fp{};
+    fp.target = a.target_logits; fp.draft = a.draft_logits; fp.dtype = a.dtype; fp.target_ld = tld; fp.draft_ld = dld;
+    fp.tokens = a.draft_tokens; fp.draft_len = a.draft_len; fp.row_temperature = a.row_temperature;
+    fp.draft_stats_in = a.draft_stats_in; fp.target_stats_out = a.target_stats_out;
+    fp.seed = a.seed; fp.level = a.level; fp.seq_base = a.seq_base;
+    fp.B = a.B; fp.gamma = a.gamma; fp.V = a.V; fp.ntiles = sampler_tiles(a.V, a.dtype);
+    fp.temperature = a.temperature; fp.tau = a.entropy_threshold;
+    fp.out_accept_len = a.out_accept_len; fp.out_next_token = a.out_next_token;
+    fp.out_entropy = a.out_entropy; fp.entropy_ld = a.entropy_ld;
+
+    // Path 2: one fused launch per level (one workgroup per sequence streams its own rows).
+    const bool want_fused = tune.path == 2 || (tune.path == 0 && auto_prefers_fused(a.B));
+    if (want_fused && per_seq_ok) {
         hipError_t fe;
         { StageTimer t(5, s); fe = launch_fused(fp, tune, s); }
         if (fe != hipSuccess) return hip_fail(fe, "fused verify launch");
@@ -178,6 +202,14 @@ static hola_status run_level(const hola_verify_args& a)
     hipError_t e;
     { StageTimer t(0, s); e = launch_row_stats(rs, a.dtype, tune, s); }
     if (e != hipSuccess) return hip_fail(e, "row statistics launch");
+
+    // Paths 0/1: the split-row pass spreads the rows over the chip, then one per-sequence tail kernel does
+    // accept + sampling.  Path 3 keeps accept, tile sums and select as three kernels of their own.
+    if (tune.path != 3 && per_seq_ok) {
+        { StageTimer t(6, s); e = launch_tail(fp, w.partials, nsplit * kWaves, tune, s); }
+        if (e != hipSuccess) return hip_fail(e, "tail launch");
+        return HOLA_OK;
+    }
 
     AcceptParams ap{};
     ap.target = a.target_logits; ap.draft = a.draft_logits; ap.dtype = a.dtype; ap.target_ld = tld; ap.draft_ld = dld;
@@ -436,7 +468,7 @@ hola_status hola_set_tuning(const hola_tuning* t)
         if (t->stats_split < 0 || t->stats_split > kMaxSplit) return HOLA_ERR_INVALID_ARG;
         if (t->stats_unroll != 0 && t->stats_unroll != 2 && t->stats_unroll != 4 && t->stats_unroll != 8 && t->stats_unroll != 16)
             return HOLA_ERR_INVALID_ARG;
-        if (t->path < 0 || t->path > 2) return HOLA_ERR_INVALID_ARG;
+        if (t->path < 0 || t->path > 3) return HOLA_ERR_INVALID_ARG;
         if (t->fused_waves != 0 && t->fused_waves != 8 && t->fused_waves != 16) return HOLA_ERR_INVALID_ARG;
         n.split = t->stats_split; n.unroll = t->stats_unroll; n.path = t->path; n.fused_waves = t->fused_waves;
     }

@@ -49,7 +49,7 @@ struct Workspace {
 
 struct Tuning {
     int split = 0, unroll = 0;
-    int path = 0;                      // 0 auto, 1 split-row kernels, 2 fused per-sequence kernel
+    int path = 0;                      // 0 auto, 1 split rows + tail kernel, 2 fused kernel, 3 split rows + 3 kernels
     int fused_waves = 0;               // 0 (= 16), 8 or 16 wavefronts per workgroup in the fused kernel
 };
 
@@ -99,6 +99,7 @@ struct FusedParams {
 };
 
 hipError_t launch_fused(const FusedParams& p, const Tuning& t, hipStream_t s);
+hipError_t launch_tail(const FusedParams& p, const Partial* partials, int nparts, const Tuning& t, hipStream_t s);
 bool fused_supported(int32_t gamma, int32_t V, int dtype);
 hipError_t launch_row_stats(const RowStatsParams& p, int dtype, const Tuning& t, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);

@@ -74,9 +74,21 @@ __device__ __forceinline__ void make_row_pair(RowPair& rp, const void* target, c
     }
 }
 
-// Weights of the N elements of chunk c (0 for elements outside the row) and their fp32 sum in index order.
+// The 16-byte chunks c of the target row and (when it shares the alignment) of the draft row.
+__device__ __forceinline__ void load_chunk_pair(const RowPair& rp, int64_t c, uint4& vp, uint4& vd)
+{
+    vp = make_uint4(0, 0, 0, 0);
+    vd = make_uint4(0, 0, 0, 0);
+    if (c < rp.nchunks) {
+        vp = rp.Pv[c];
+        if (!rp.bonus && rp.Dv != nullptr) vd = rp.Dv[c];
+    }
+}
+
+// Weights of the N elements of chunk c (0 for elements outside the row) and their fp32 sum in index
+// order, from chunks already loaded.
 template <bool BF16>
-__device__ __forceinline__ float chunk_weights(const RowPair& rp, int64_t c, float* w)
+__device__ __forceinline__ float chunk_weights_loaded(const RowPair& rp, int64_t c, const uint4& vp, const uint4& vd, float* w)
 {
     constexpr int N = BF16 ? 8 : 4;
     if (c >= rp.nchunks) {
@@ -84,12 +96,9 @@ __device__ __forceinline__ float chunk_weights(const RowPair& rp, int64_t c, flo
         for (int k = 0; k < N; ++k) w[k] = 0.f;
         return 0.f;
     }
-    const uint4 vp = rp.Pv[c];
     const int32_t e0 = (int32_t)(c * N) - rp.head;
     const bool edge = (c == 0) || (c == rp.nchunks - 1);
-    uint4 vd = make_uint4(0, 0, 0, 0);
     const bool dvec = !rp.bonus && rp.Dv != nullptr;
-    if (dvec) vd = rp.Dv[c];
     float sum = 0.f;
 #pragma unroll
     for (int k = 0; k < N; ++k) {
@@ -114,18 +123,51 @@ __device__ __forceinline__ float chunk_weights(const RowPair& rp, int64_t c, flo
     return sum;
 }
 
+template <bool BF16>
+__device__ __forceinline__ float chunk_weights(const RowPair& rp, int64_t c, float* w)
+{
+    uint4 vp, vd;
+    load_chunk_pair(rp, c, vp, vd);
+    return chunk_weights_loaded<BF16>(rp, c, vp, vd, w);
+}
+
 // Weight of one tile: lanes take chunks tile*256 + g*64 + lane, g = 0..3.  Every lane returns the sum.
 template <bool BF16>
 __device__ __forceinline__ double tile_weight(const RowPair& rp, int64_t tile, int lane)
 {
     constexpr int N = BF16 ? 8 : 4;
+    uint4 vp[kTileChunks], vd[kTileChunks];
+#pragma unroll
+    for (int g = 0; g < kTileChunks; ++g) load_chunk_pair(rp, tile * (64 * kTileChunks) + g * 64 + lane, vp[g], vd[g]);
     double acc = 0.0;
 #pragma unroll
     for (int g = 0; g < kTileChunks; ++g) {
         float w[N];
-        acc += (double)chunk_weights<BF16>(rp, tile * (64 * kTileChunks) + g * 64 + lane, w);
+        acc += (double)chunk_weights_loaded<BF16>(rp, tile * (64 * kTileChunks) + g * 64 + lane, vp[g], vd[g], w);
     }
     return wave_sum(acc) * rp.scale;
+}
+
+// Two tiles with all their loads in flight together (twice the bytes per round trip).
+template <bool BF16>
+__device__ __forceinline__ void tile_weight2(const RowPair& rp, int64_t t0, int64_t t1, int lane, double& w0, double& w1)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    uint4 vp[2][kTileChunks], vd[2][kTileChunks];
+#pragma unroll
+    for (int g = 0; g < kTileChunks; ++g) {
+        load_chunk_pair(rp, t0 * (64 * kTileChunks) + g * 64 + lane, vp[0][g], vd[0][g]);
+        load_chunk_pair(rp, t1 * (64 * kTileChunks) + g * 64 + lane, vp[1][g], vd[1][g]);
+    }
+    double a0 = 0.0, a1 = 0.0;
+#pragma unroll
+    for (int g = 0; g < kTileChunks; ++g) {
+        float w[N];
+        a0 += (double)chunk_weights_loaded<BF16>(rp, t0 * (64 * kTileChunks) + g * 64 + lane, vp[0][g], vd[0][g], w);
+        a1 += (double)chunk_weights_loaded<BF16>(rp, t1 * (64 * kTileChunks) + g * 64 + lane, vp[1][g], vd[1][g], w);
+    }
+    w0 = wave_sum(a0) * rp.scale;
+    w1 = wave_sum(a1) * rp.scale;
 }
 
 // Tile weights may be rewritten by one lane and read by the others of the same wavefront (fallback

@@ -360,3 +360,44 @@ __device__ __forceinline__ RowStat merge_partials(const Partial* __restrict__ ps
 }
 
 }  // namespace hola
+
+namespace hola {
+
+// The same merge done by a whole wavefront: lane i holds partial i (n <= 64), one load per lane.
+__device__ __forceinline__ RowStat merge_partials_wave(const Partial* __restrict__ ps, int n, int lane)
+{
+    Partial q;
+    q.bref = 0.0; q.S = 0.0; q.T = 0.0; q.vmax = -INFINITY; q.imax = -1;
+    if (lane < n) q = ps[lane];
+    const bool bad = __any(!(q.S == q.S));
+    double bmin = (q.S > 0.0) ? q.bref : INFINITY;
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) bmin = fmin(bmin, __shfl_xor(bmin, m, 64));
+    double S = 0.0, T = 0.0;
+    if (q.S > 0.0) {
+        const double d = bmin - q.bref;
+        if (d == 0.0) { S = q.S; T = q.T; }
+        else { const double f = exp2(d); S = q.S * f; T = (q.T + d * q.S) * f; }
+    }
+    S = wave_sum(S);
+    T = wave_sum(T);
+    float v = q.vmax;
+    int32_t i = q.imax;
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        const float ov = __shfl_xor(v, m, 64);
+        const int32_t oi = __shfl_xor(i, m, 64);
+        const bool take = (oi >= 0) && (i < 0 || ov > v || (ov == v && oi < i));
+        if (take) { v = ov; i = oi; }
+    }
+    RowStat r;
+    r.argmax = i;
+    if (bad || !(T == T)) { r.lse = NAN; r.H = NAN; return r; }
+    if (!(S > 0.0)) { r.lse = -INFINITY; r.H = NAN; return r; }
+    const double lnS = log(S);
+    r.lse = lnS - bmin * kLn2;
+    r.H = lnS - kLn2 * (T / S);
+    return r;
+}
+
+}  // namespace hola

@@ -17,11 +17,12 @@ pytestmark = pytest.mark.gpu
 _PATH = {"name": "auto"}
 
 
-@pytest.fixture(params=["auto", "split", "fused"], autouse=True)
+@pytest.fixture(params=["auto", "split", "fused", "split4"], autouse=True)
 def kernel_path(request):
     """Every test runs with the library's own choice of kernels and with each path forced."""
     _PATH["name"] = request.param
-    hb.hola_set_tuning(path={"auto": hb.PATH_AUTO, "split": hb.PATH_SPLIT, "fused": hb.PATH_FUSED}[request.param])
+    hb.hola_set_tuning(path={"auto": hb.PATH_AUTO, "split": hb.PATH_SPLIT, "fused": hb.PATH_FUSED,
+                             "split4": hb.PATH_SPLIT4}[request.param])
     yield request.param
     hb.hola_set_tuning()
 
@@ -104,7 +105,9 @@ def test_config3_launch_shapes_agree(cfg3):
     if kernel_path_name() == "auto":
         shapes = [(hb.PATH_AUTO, 0, 0, 0)]
     elif kernel_path_name() == "split":
-        shapes = [(hb.PATH_SPLIT, s, u, 0) for s, u in ((1, 4), (2, 2), (4, 8), (16, 4), (1, 8))]
+        shapes = [(hb.PATH_SPLIT, s, u, nw) for s, u, nw in ((1, 4, 8), (2, 2, 16), (4, 8, 8), (16, 4, 16), (1, 16, 0))]
+    elif kernel_path_name() == "split4":
+        shapes = [(hb.PATH_SPLIT4, s, u, 0) for s, u in ((1, 8), (2, 4), (8, 2))]
     else:
         shapes = [(hb.PATH_FUSED, 0, u, nw) for u, nw in ((2, 8), (4, 16), (8, 8), (8, 16))]
     for path, split, unroll, nw in shapes:
