@@ -374,3 +374,51 @@ def test_gate_monotone_in_tau_on_gpu():
             assert np.all(gpu.accept_len >= prev)
         prev = gpu.accept_len
     assert np.all(prev == w.gamma)
+
+
+def test_huge_vocabulary_falls_back_to_the_split_sampler():
+    """More sampler tiles than the per-sequence kernels hold in LDS: the library must take the
+    four-kernel path on its own, whatever path was asked for, and still match the oracle."""
+    B, g, V = 2, 1, 2_200_000
+    w = wl.small_case(B, g, V, dtype="f32", temperature=1.0, zipf_slope=None, peak_prob=0.0, case_id=307)
+    for tau in (0.0, float("inf")):
+        gpu, rep = _level(w, tau)
+        _report(f"{w.name} tau={tau}", rep)
+        assert rep.max_entropy_abs < 1e-6
+
+
+def test_graph_capture_and_replay():
+    """hola_verify_ex enqueues kernels only (no allocation, no host synchronisation, no memset), so a
+    call can be captured in a HIP graph; every replay must reproduce the eager result."""
+    w = wl.small_case(40, 4, 20011, dtype="bf16", temperature=0.8, case_id=308)
+    B, g, V = w.B, w.gamma, w.V
+    P, D, tok = to_dev(w.target), to_dev(w.draft), to_dev(w.tokens)
+    ws = hb.alloc_workspace(hb.hola_workspace_bytes(B, g, V), DEV)
+    outs = [torch.zeros(B, dtype=torch.int32, device=DEV), torch.zeros(B, dtype=torch.int32, device=DEV),
+            torch.zeros((B, g), dtype=torch.float32, device=DEV)]
+
+    def call(stream=None):
+        hb.hola_verify_ex(target_logits=P, draft_logits=D, draft_tokens=tok, seed=w.seed, B=B, gamma=g, V=V,
+                          temperature=w.temperature, entropy_threshold=0.0, out_accept_len=outs[0],
+                          out_next_token=outs[1], out_entropy=outs[2], workspace=ws, stream=stream)
+
+    call()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            call(stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for o in outs:
+            o.fill_(-5)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert torch.equal(o, e), f"replay {rep} differs from the eager call"
+        call()                                              # eager work between the replays
+        torch.cuda.synchronize()
