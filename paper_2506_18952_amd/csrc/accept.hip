@@ -30,7 +30,7 @@ __global__ __launch_bounds__(64) void accept_kernel(AcceptParams p)
     }
     AcceptCtx c;
     c.target = p.target; c.draft = p.draft; c.target_ld = p.target_ld; c.draft_ld = p.draft_ld;
-    c.tokens = p.tokens; c.seed = p.seed; c.level = p.level; c.seq_base = p.seq_base;
+    c.tokens = p.tokens; c.tokens_ld = p.tokens_ld; c.pad_entropy = p.pad_entropy; c.seed = p.seed; c.level = p.level; c.seq_base = p.seq_base;
     c.gamma = g; c.V = p.V; c.tau = p.tau; c.target_stats_out = p.target_stats_out;
     c.out_accept_len = p.out_accept_len; c.out_next_token = p.out_next_token;
     c.out_entropy = p.out_entropy; c.entropy_ld = p.entropy_ld;

@@ -14,7 +14,8 @@ namespace hola {
 struct AcceptCtx {
     const void* target; const void* draft;
     int64_t target_ld, draft_ld;
-    const int32_t* tokens;
+    const int32_t* tokens; int64_t tokens_ld;
+    int32_t pad_entropy;
     uint64_t seed; uint32_t level; int64_t seq_base;
     int32_t gamma, V;
     float tau;
@@ -38,15 +39,17 @@ __device__ __forceinline__ void accept_wave(const AcceptCtx& c, int b, int j, in
         c.target_stats_out[((int64_t)b * (g + 1) + j) * 2 + 0] = sp.lse;
         c.target_stats_out[((int64_t)b * (g + 1) + j) * 2 + 1] = sp.H;
     }
-    if (c.out_entropy && j < g) {
+    if (c.out_entropy) {
         const int64_t eld = c.entropy_ld ? c.entropy_ld : g;
-        c.out_entropy[(int64_t)b * eld + j] = (j < len) ? (float)sd.H : -1.0f;
+        const int64_t width = c.pad_entropy ? eld : g;
+        for (int64_t jj = j; jj < width; jj += 64)
+            c.out_entropy[(int64_t)b * eld + jj] = (jj < len) ? (float)sd.H : -1.0f;
     }
     const uint64_t seq = (uint64_t)(c.seq_base + b);
     bool reject = false;
     if (j < len) {
         const bool gate = sd.H < tau;                   // strict; NaN never gates
-        const int32_t x = c.tokens[(int64_t)b * g + j];
+        const int32_t x = c.tokens[(int64_t)b * c.tokens_ld + j];
         bool ok;
         if (greedy) {
             ok = (x == sp.argmax);
@@ -73,10 +76,11 @@ __device__ __forceinline__ void accept_wave(const AcceptCtx& c, int b, int j, in
         si.row = a;
         si.lseP = sp.lse;
         si.lseD = (a < len) ? sd.lse : 0.0;
-        si.pad = 0;
+        si.greedy_tok = -1;
         if (greedy) {
             si.mode = 2;
             si.u = 0.f;
+            si.greedy_tok = sp.argmax;
             c.out_next_token[b] = sp.argmax;
         } else {
             const Philox4 r = philox4x32_10((uint32_t)a, (uint32_t)seq, (uint32_t)(seq >> 32), c.level,

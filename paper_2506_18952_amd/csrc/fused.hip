@@ -28,11 +28,20 @@ __device__ __forceinline__ AcceptCtx accept_ctx(const FusedParams& p)
 {
     AcceptCtx c;
     c.target = p.target; c.draft = p.draft; c.target_ld = p.target_ld; c.draft_ld = p.draft_ld;
-    c.tokens = p.tokens; c.seed = p.seed; c.level = p.level; c.seq_base = p.seq_base;
+    c.tokens = p.tokens; c.tokens_ld = p.tokens_ld; c.pad_entropy = p.pad_entropy; c.seed = p.seed; c.level = p.level; c.seq_base = p.seq_base;
     c.gamma = p.gamma; c.V = p.V; c.tau = p.tau; c.target_stats_out = p.target_stats_out;
     c.out_accept_len = p.out_accept_len; c.out_next_token = p.out_next_token;
     c.out_entropy = p.out_entropy; c.entropy_ld = p.entropy_ld;
     return c;
+}
+
+// Drafts of the next verify level: the kept tokens of this level followed by its next token.
+__device__ __forceinline__ void write_glue(const FusedParams& p, int b, int a, int32_t next)
+{
+    if (!p.glue_tok) return;
+    for (int64_t j = threadIdx.x; j < p.glue_ld; j += blockDim.x)
+        p.glue_tok[(int64_t)b * p.glue_ld + j] = j < a ? p.tokens[(int64_t)b * p.tokens_ld + j] : (j == a ? next : -1);
+    if (threadIdx.x == 0) p.glue_len[b] = a + 1;
 }
 
 // Accept stage (wavefront 0) and sampling (all wavefronts) of sequence b, given sh.stat[].
@@ -59,7 +68,10 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
     }
     __syncthreads();
     const SeqInfo si = sh.si;
-    if (si.mode == 2) return;                                    // greedy: next token already written
+    if (si.mode == 2) {                                          // greedy: next token already written
+        write_glue(p, b, si.row, si.greedy_tok);
+        return;
+    }
 
     RowPair rp;
     make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0);
@@ -85,6 +97,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
         make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1);
     }
     if (tid == 0) p.out_next_token[b] = tok < 0 ? -1 : tok;
+    write_glue(p, b, si.row, tok < 0 ? -1 : tok);
 }
 
 template <bool BF16, int NW, int U>

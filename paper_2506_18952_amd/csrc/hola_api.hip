@@ -17,23 +17,18 @@ namespace hola {
 // ---------------------------------------------------------------------------------------------
 // small device kernels of the driver
 // ---------------------------------------------------------------------------------------------
-__global__ void fill_f32_kernel(float* p, int64_t n, float v)
-{
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = v;
-}
-
-// Drafts of the next level: the kept tokens of this level followed by its next token.
-__global__ void level_glue_kernel(const int32_t* __restrict__ cur_tok, int32_t gk, const int32_t* __restrict__ acc,
-                                  const int32_t* __restrict__ nxt, int32_t B, int32_t* __restrict__ new_tok,
-                                  int32_t* __restrict__ new_len)
+// Drafts of the next level: the kept tokens of this level followed by its next token (only used on the
+// four-kernel path; the per-sequence kernels write them themselves).
+__global__ void level_glue_kernel(const int32_t* __restrict__ cur_tok, int64_t cur_ld, int32_t gk,
+                                  const int32_t* __restrict__ acc, const int32_t* __restrict__ nxt, int32_t B,
+                                  int32_t* __restrict__ new_tok, int64_t new_ld, int32_t* __restrict__ new_len)
 {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     int a = acc[b];
     a = a < 0 ? 0 : (a > gk ? gk : a);
-    for (int j = 0; j <= gk; ++j)
-        new_tok[(int64_t)b * (gk + 1) + j] = j < a ? cur_tok[(int64_t)b * gk + j] : (j == a ? nxt[b] : -1);
+    for (int64_t j = 0; j < new_ld; ++j)
+        new_tok[(int64_t)b * new_ld + j] = j < a ? cur_tok[(int64_t)b * cur_ld + j] : (j == a ? nxt[b] : -1);
     new_len[b] = a + 1;
 }
 
@@ -43,13 +38,13 @@ __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst, cons
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
 }
 
-__global__ void export_tokens_kernel(const int32_t* __restrict__ tok, int32_t gk, const int32_t* __restrict__ len,
-                                     int32_t B, int32_t width, int32_t* __restrict__ out)
+__global__ void export_tokens_kernel(const int32_t* __restrict__ tok, int64_t tok_ld, int32_t gk,
+                                     const int32_t* __restrict__ len, int32_t B, int32_t width, int32_t* __restrict__ out)
 {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     int l = len ? len[b] : gk;
-    for (int j = 0; j < width; ++j) out[(int64_t)b * width + j] = (j < l && j < gk) ? tok[(int64_t)b * gk + j] : -1;
+    for (int j = 0; j < width; ++j) out[(int64_t)b * width + j] = (j < l && j < gk) ? tok[(int64_t)b * tok_ld + j] : -1;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -160,7 +155,15 @@ static hola_status check_args(const hola_verify_args& a)
     return HOLA_OK;
 }
 
-static hola_status run_level(const hola_verify_args& a)
+// What the hierarchical driver adds to one level: a row stride for the drafted tokens, -1 padding of the
+// entropy row up to entropy_ld, and the next level's drafts written by the level itself.
+struct LevelExtras {
+    int64_t tokens_ld = 0;             // 0 => gamma
+    int32_t pad_entropy = 0;
+    int32_t* glue_tok = nullptr; int32_t* glue_len = nullptr; int64_t glue_ld = 0;
+};
+
+static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = LevelExtras())
 {
     hola_status st = check_args(a);
     if (st != HOLA_OK || a.B == 0) return st;
@@ -181,6 +184,8 @@ static hola_status run_level(const hola_verify_args& a)
     fp.draft_stats_in = a.draft_stats_in; fp.target_stats_out = a.target_stats_out;
     fp.seed = a.seed; fp.level = a.level; fp.seq_base = a.seq_base;
     fp.B = a.B; fp.gamma = a.gamma; fp.V = a.V; fp.ntiles = sampler_tiles(a.V, a.dtype);
+    fp.tokens_ld = x.tokens_ld ? x.tokens_ld : a.gamma; fp.pad_entropy = x.pad_entropy;
+    fp.glue_tok = x.glue_tok; fp.glue_len = x.glue_len; fp.glue_ld = x.glue_ld;
     fp.temperature = a.temperature; fp.tau = a.entropy_threshold;
     fp.out_accept_len = a.out_accept_len; fp.out_next_token = a.out_next_token;
     fp.out_entropy = a.out_entropy; fp.entropy_ld = a.entropy_ld;
@@ -217,6 +222,7 @@ static hola_status run_level(const hola_verify_args& a)
     ap.draft_stats_in = a.draft_stats_in; ap.target_stats_out = a.target_stats_out;
     ap.seed = a.seed; ap.level = a.level; ap.seq_base = a.seq_base;
     ap.B = a.B; ap.gamma = a.gamma; ap.V = a.V; ap.nparts = nsplit * kWaves;
+    ap.tokens_ld = fp.tokens_ld; ap.pad_entropy = x.pad_entropy;
     ap.temperature = a.temperature; ap.tau = a.entropy_threshold;
     ap.partials = w.partials; ap.statsD = w.statsD; ap.statsP = w.statsP; ap.argmaxP = w.argmaxP; ap.seq = w.seq;
     ap.out_accept_len = a.out_accept_len; ap.out_next_token = a.out_next_token;
@@ -233,6 +239,14 @@ static hola_status run_level(const hola_verify_args& a)
     if (e != hipSuccess) return hip_fail(e, "tile sums launch");
     { StageTimer t(3, s); e = launch_select(sp, s); }
     if (e != hipSuccess) return hip_fail(e, "select launch");
+    if (x.glue_tok) {                                  // this path has no per-sequence kernel to do it
+        StageTimer t(4, s);
+        const int tpb = 128;
+        hipLaunchKernelGGL(level_glue_kernel, dim3((a.B + tpb - 1) / tpb), dim3(tpb), 0, s, a.draft_tokens, fp.tokens_ld,
+                           a.gamma, a.out_accept_len, a.out_next_token, a.B, x.glue_tok, x.glue_ld, x.glue_len);
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "glue launch");
+    }
     return HOLA_OK;
 }
 
@@ -368,16 +382,10 @@ hola_status hola_hsd_verify(const hola_model_logits* models, int32_t n_models, i
     hipStream_t s = (hipStream_t)stream;
     const int L = n_models - 1;
     const int32_t gmax = gamma + L - 1;
+    const int64_t out_ld = gamma + L;                  // width of out_tokens
     const HsdWs h = carve_hsd(workspace, n_models, B, gamma, V);
-    const int tpb = 128, nb = (B + tpb - 1) / tpb;
-    if (out_entropy) {
-        const int64_t n = (int64_t)L * B * gmax;
-        StageTimer t(4, s);
-        hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, out_entropy, n, -1.0f);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return hip_fail(e, "fill launch");
-    }
     const int32_t* cur_tok = draft_tokens;
+    int64_t cur_ld = gamma;
     const int32_t* cur_len = nullptr;
     const double* cur_stats = nullptr;
     for (int k = 1; k <= L; ++k) {
@@ -395,22 +403,29 @@ hola_status hola_hsd_verify(const hola_model_logits* models, int32_t n_models, i
         a.out_entropy = out_entropy ? out_entropy + (int64_t)(k - 1) * B * gmax : nullptr;
         a.entropy_ld = gmax;
         a.workspace = h.level; a.workspace_bytes = h.level_bytes; a.stream = stream;
-        hola_status st = run_level(a);
+        LevelExtras x;
+        x.tokens_ld = cur_ld;
+        x.pad_entropy = 1;
+        if (k < L) {
+            // The next level's drafts are written by this level.  The last middle level writes them
+            // straight into out_tokens (when given), which the last level then reads in place.
+            x.glue_len = h.len[k & 1];
+            if (k == L - 1 && out_tokens) { x.glue_tok = out_tokens; x.glue_ld = out_ld; }
+            else { x.glue_tok = h.tok[k & 1]; x.glue_ld = gk + 1; }
+        }
+        hola_status st = run_level(a, x);
         if (st != HOLA_OK) return st;
         if (k < L) {
-            StageTimer t(4, s);
-            hipLaunchKernelGGL(level_glue_kernel, dim3(nb), dim3(tpb), 0, s, cur_tok, gk, out_accept_len, out_next_token,
-                               B, h.tok[k & 1], h.len[k & 1]);
-            hipError_t e = hipGetLastError();
-            if (e != hipSuccess) return hip_fail(e, "glue launch");
-            cur_tok = h.tok[k & 1];
-            cur_len = h.len[k & 1];
+            cur_tok = x.glue_tok; cur_ld = x.glue_ld;
+            cur_len = x.glue_len;
             cur_stats = h.stats[k & 1];
         }
     }
-    if (out_tokens) {
+    if (out_tokens && cur_tok != out_tokens) {          // a single level: its drafts are the caller's tokens
         StageTimer t(4, s);
-        hipLaunchKernelGGL(export_tokens_kernel, dim3(nb), dim3(tpb), 0, s, cur_tok, gmax, cur_len, B, gamma + L, out_tokens);
+        const int tpb = 128, nb = (B + tpb - 1) / tpb;
+        hipLaunchKernelGGL(export_tokens_kernel, dim3(nb), dim3(tpb), 0, s, cur_tok, cur_ld, gmax, cur_len, B,
+                           (int32_t)out_ld, out_tokens);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "export launch");
     }

@@ -25,7 +25,7 @@ struct SeqInfo {
     float u;                           // sampling uniform
     int32_t row;                       // stop row (= accept length)
     int32_t mode;                      // 0 residual, 1 bonus, 2 nothing to sample (greedy / done)
-    int32_t pad;
+    int32_t greedy_tok;                // next token of a greedy row (mode 2)
 };
 
 struct Shape {
@@ -72,6 +72,8 @@ struct AcceptParams {
     const double* draft_stats_in; double* target_stats_out;
     uint64_t seed; uint32_t level; int64_t seq_base;
     int32_t B, gamma, V, nparts;
+    int64_t tokens_ld;                 // row stride of tokens (>= gamma)
+    int32_t pad_entropy;               // also write -1 into out_entropy columns gamma .. entropy_ld-1
     float temperature, tau;
     const Partial* partials;
     double* statsD; double* statsP; int32_t* argmaxP; SeqInfo* seq;
@@ -94,8 +96,13 @@ struct FusedParams {
     const double* draft_stats_in; double* target_stats_out;
     uint64_t seed; uint32_t level; int64_t seq_base;
     int32_t B, gamma, V, ntiles;
+    int64_t tokens_ld;                 // row stride of tokens (>= gamma)
+    int32_t pad_entropy;               // also write -1 into out_entropy columns gamma .. entropy_ld-1
     float temperature, tau;
     int32_t* out_accept_len; int32_t* out_next_token; float* out_entropy; int64_t entropy_ld;
+    // drafts of the next verify level, written by the per-sequence kernels when given: the kept tokens
+    // followed by the next token, -1 up to glue_ld; glue_len[b] = accept length + 1
+    int32_t* glue_tok; int32_t* glue_len; int64_t glue_ld;
 };
 
 hipError_t launch_fused(const FusedParams& p, const Tuning& t, hipStream_t s);
