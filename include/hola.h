@@ -157,6 +157,27 @@ hola_status hola_hsd_verify(const hola_model_logits* models /* host array */, in
 
 size_t hola_hsd_workspace_bytes(int32_t n_models, int32_t B, int32_t gamma, int32_t V);
 
+/* The same driver with its options in a struct.  survivors_only = 1 selects the other reading of "the
+ * target verifies the survivors": level k passes on only the tokens it kept (length accept_len, possibly
+ * 0), not its next token; that chain conditions on acceptance and is not lossless, it is offered because
+ * the paper does not say which one HSD means.  Every other field is as in hola_hsd_verify. */
+typedef struct {
+    const hola_model_logits* models;  /* host array [n_models] */
+    int32_t n_models, dtype;
+    const int32_t* draft_tokens;      /* device [B, gamma] */
+    uint64_t seed; int64_t seq_base;
+    int32_t B, gamma, V;
+    const float* row_temperature;     /* device [B] or NULL */
+    float temperature;
+    const float* tau;                 /* host array [n_models-1] */
+    int32_t survivors_only;
+    int32_t* out_tokens;              /* device [B, gamma+n_models-1] or NULL */
+    int32_t* out_accept_len; int32_t* out_next_token;   /* device [B] */
+    float* out_entropy;               /* device [n_models-1, B, gamma+n_models-2] or NULL */
+    void* workspace; size_t workspace_bytes; hola_stream_t stream;
+} hola_hsd_args;
+hola_status hola_hsd_verify_ex(const hola_hsd_args* args /* host */);
+
 /* Row statistics alone (steps 1-2): (lse, H) in nats of softmax(logits[r, :] / T) for R rows,
  * written to stats_out as device [R, 2] doubles.  Greedy convention does not apply (T > 0).
  * workspace as for hola_verify_ex with B = R, gamma = 1. */

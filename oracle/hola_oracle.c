@@ -413,7 +413,9 @@ int32_t oracle_sample_interval(const oracle_verify_args* a, int32_t b, int32_t a
 /* ------------------------------------------------------------------------- */
 /* Hierarchical verify over n_models logit sets, smallest drafter first.       */
 /* Level k (k = 1 .. n_models-1) verifies with models[k] the drafts that       */
-/* level k-1 produced: its accepted tokens followed by its next token.         */
+/* level k-1 produced: its accepted tokens followed by its next token (or,     */
+/* with survivors_only, its accepted tokens alone: the other reading of "the   */
+/* target verifies the survivors", which is not lossless).                     */
 /* models[k] has gamma+k rows per sequence; tau[k-1] gates level k on the      */
 /* entropy of models[k-1].                                                     */
 /* ------------------------------------------------------------------------- */
@@ -427,6 +429,7 @@ int32_t oracle_hsd_verify(const void* const* model_logits, const int64_t* model_
                           float* out_entropy,       /* [n_models-1, B, gamma + n_models - 2], -1 where unused */
                           int32_t* out_level_accept,/* [n_models-1, B] or NULL */
                           int32_t* out_level_next,  /* [n_models-1, B] or NULL */
+                          int32_t survivors_only,   /* alternative reading: pass on the kept tokens only */
                           int32_t num_threads)
 {
     if (n_models < 2 || B < 0 || gamma < 1 || gamma + n_models - 2 > 63) return -1;
@@ -478,9 +481,13 @@ int32_t oracle_hsd_verify(const void* const* model_logits, const int64_t* model_
                     out_entropy[((int64_t)(k - 1) * B + b) * gmax + j] = ent[(int64_t)b * gk + j];
             if (out_level_accept) out_level_accept[(int64_t)(k - 1) * B + b] = acc[b];
             if (out_level_next) out_level_next[(int64_t)(k - 1) * B + b] = nxt[b];
-            if (k < L) {                          /* next level's drafts: accepted prefix + next token */
-                toks[(int64_t)b * (gmax + 1) + acc[b]] = nxt[b];
-                lens[b] = acc[b] + 1;
+            if (k < L) {
+                if (survivors_only) {             /* alternative reading: the kept tokens only */
+                    lens[b] = acc[b];
+                } else {                          /* next level's drafts: accepted prefix + next token */
+                    toks[(int64_t)b * (gmax + 1) + acc[b]] = nxt[b];
+                    lens[b] = acc[b] + 1;
+                }
             }
         }
     }

@@ -21,7 +21,7 @@ STAGE_NAMES = ("row_stats", "accept", "tile_sums", "select", "glue", "fused", "t
 
 EXPORTS = (
     "hola_verify_f32", "hola_verify_bf16", "hola_verify_ex", "hola_workspace_bytes",
-    "hola_hsd_verify", "hola_hsd_workspace_bytes", "hola_row_stats", "hola_set_tuning",
+    "hola_hsd_verify", "hola_hsd_verify_ex", "hola_hsd_workspace_bytes", "hola_row_stats", "hola_set_tuning",
     "hola_profile_enable", "hola_profile_collect", "hola_copy_bytes", "hola_shutdown", "hola_status_string",
     "hola_last_hip_error", "hola_version",
 )
@@ -55,6 +55,19 @@ class ModelLogits(C.Structure):
     _fields_ = [("logits", C.c_void_p), ("ld", C.c_int64)]
 
 
+class HsdArgs(C.Structure):
+    _fields_ = [
+        ("models", C.POINTER(ModelLogits)), ("n_models", C.c_int32), ("dtype", C.c_int32),
+        ("draft_tokens", C.c_void_p), ("seed", C.c_uint64), ("seq_base", C.c_int64),
+        ("B", C.c_int32), ("gamma", C.c_int32), ("V", C.c_int32),
+        ("row_temperature", C.c_void_p), ("temperature", C.c_float), ("tau", C.POINTER(C.c_float)),
+        ("survivors_only", C.c_int32),
+        ("out_tokens", C.c_void_p), ("out_accept_len", C.c_void_p), ("out_next_token", C.c_void_p),
+        ("out_entropy", C.c_void_p),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p),
+    ]
+
+
 class Tuning(C.Structure):
     _fields_ = [("stats_split", C.c_int32), ("stats_unroll", C.c_int32), ("path", C.c_int32),
                 ("fused_waves", C.c_int32)]
@@ -82,6 +95,8 @@ def lib() -> C.CDLL:
                                       C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_float,
                                       C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_size_t, C.c_void_p]
+        L.hola_hsd_verify_ex.argtypes = [C.POINTER(HsdArgs)]
+        L.hola_hsd_verify_ex.restype = C.c_int32
         L.hola_hsd_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.hola_hsd_workspace_bytes.restype = C.c_size_t
         L.hola_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_float,
@@ -203,6 +218,28 @@ def hola_hsd_verify(models: Sequence, draft_tokens, seed, B, gamma, V, temperatu
                                _ptr(out_tokens), _ptr(out_accept_len), _ptr(out_next_token), _ptr(out_entropy),
                                _ptr(workspace), workspace.numel() * workspace.element_size(), _stream_handle(stream))
     _check(st, "hola_hsd_verify")
+
+
+def hola_hsd_verify_ex(models: Sequence, draft_tokens, seed, B, gamma, V, temperature, tau: Sequence[float],
+                       out_tokens, out_accept_len, out_next_token, out_entropy, workspace, survivors_only=False,
+                       row_temperature=None, seq_base=0, lds: Optional[Sequence[int]] = None, stream=None) -> None:
+    n = len(models)
+    arr = (ModelLogits * n)()
+    for k, m in enumerate(models):
+        arr[k].logits = _ptr(m)
+        arr[k].ld = int(lds[k]) if lds else 0
+    taus = (C.c_float * (n - 1))(*[float(x) for x in tau])
+    a = HsdArgs()
+    a.models, a.n_models, a.dtype = arr, n, _logit_dtype(models[0])
+    a.draft_tokens, a.seed, a.seq_base = _ptr(draft_tokens), int(seed), int(seq_base)
+    a.B, a.gamma, a.V = int(B), int(gamma), int(V)
+    a.row_temperature, a.temperature, a.tau = _ptr(row_temperature), float(temperature), taus
+    a.survivors_only = 1 if survivors_only else 0
+    a.out_tokens, a.out_accept_len, a.out_next_token = _ptr(out_tokens), _ptr(out_accept_len), _ptr(out_next_token)
+    a.out_entropy = _ptr(out_entropy)
+    a.workspace, a.workspace_bytes = _ptr(workspace), workspace.numel() * workspace.element_size()
+    a.stream = _stream_handle(stream)
+    _check(lib().hola_hsd_verify_ex(C.byref(a)), "hola_hsd_verify_ex")
 
 
 def hola_row_stats(logits, R, V, temperature, stats_out, workspace, ld=0, stream=None) -> None:

@@ -40,8 +40,9 @@ __device__ __forceinline__ void write_glue(const FusedParams& p, int b, int a, i
 {
     if (!p.glue_tok) return;
     for (int64_t j = threadIdx.x; j < p.glue_ld; j += blockDim.x)
-        p.glue_tok[(int64_t)b * p.glue_ld + j] = j < a ? p.tokens[(int64_t)b * p.tokens_ld + j] : (j == a ? next : -1);
-    if (threadIdx.x == 0) p.glue_len[b] = a + 1;
+        p.glue_tok[(int64_t)b * p.glue_ld + j] =
+            j < a ? p.tokens[(int64_t)b * p.tokens_ld + j] : ((j == a && p.glue_keep_next) ? next : -1);
+    if (threadIdx.x == 0) p.glue_len[b] = a + (p.glue_keep_next ? 1 : 0);
 }
 
 // Accept stage (wavefront 0) and sampling (all wavefronts) of sequence b, given sh.stat[].

@@ -21,15 +21,16 @@ namespace hola {
 // four-kernel path; the per-sequence kernels write them themselves).
 __global__ void level_glue_kernel(const int32_t* __restrict__ cur_tok, int64_t cur_ld, int32_t gk,
                                   const int32_t* __restrict__ acc, const int32_t* __restrict__ nxt, int32_t B,
-                                  int32_t* __restrict__ new_tok, int64_t new_ld, int32_t* __restrict__ new_len)
+                                  int32_t* __restrict__ new_tok, int64_t new_ld, int32_t* __restrict__ new_len,
+                                  int32_t keep_next)
 {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     int a = acc[b];
     a = a < 0 ? 0 : (a > gk ? gk : a);
     for (int64_t j = 0; j < new_ld; ++j)
-        new_tok[(int64_t)b * new_ld + j] = j < a ? cur_tok[(int64_t)b * cur_ld + j] : (j == a ? nxt[b] : -1);
-    new_len[b] = a + 1;
+        new_tok[(int64_t)b * new_ld + j] = j < a ? cur_tok[(int64_t)b * cur_ld + j] : ((j == a && keep_next) ? nxt[b] : -1);
+    new_len[b] = a + (keep_next ? 1 : 0);
 }
 
 // Plain copy: one 16-byte load and one 16-byte store per lane per step, grid-stride.
@@ -161,6 +162,7 @@ struct LevelExtras {
     int64_t tokens_ld = 0;             // 0 => gamma
     int32_t pad_entropy = 0;
     int32_t* glue_tok = nullptr; int32_t* glue_len = nullptr; int64_t glue_ld = 0;
+    int32_t glue_keep_next = 1;
 };
 
 static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = LevelExtras())
@@ -185,7 +187,7 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     fp.seed = a.seed; fp.level = a.level; fp.seq_base = a.seq_base;
     fp.B = a.B; fp.gamma = a.gamma; fp.V = a.V; fp.ntiles = sampler_tiles(a.V, a.dtype);
     fp.tokens_ld = x.tokens_ld ? x.tokens_ld : a.gamma; fp.pad_entropy = x.pad_entropy;
-    fp.glue_tok = x.glue_tok; fp.glue_len = x.glue_len; fp.glue_ld = x.glue_ld;
+    fp.glue_tok = x.glue_tok; fp.glue_len = x.glue_len; fp.glue_ld = x.glue_ld; fp.glue_keep_next = x.glue_keep_next;
     fp.temperature = a.temperature; fp.tau = a.entropy_threshold;
     fp.out_accept_len = a.out_accept_len; fp.out_next_token = a.out_next_token;
     fp.out_entropy = a.out_entropy; fp.entropy_ld = a.entropy_ld;
@@ -243,7 +245,7 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
         StageTimer t(4, s);
         const int tpb = 128;
         hipLaunchKernelGGL(level_glue_kernel, dim3((a.B + tpb - 1) / tpb), dim3(tpb), 0, s, a.draft_tokens, fp.tokens_ld,
-                           a.gamma, a.out_accept_len, a.out_next_token, a.B, x.glue_tok, x.glue_ld, x.glue_len);
+                           a.gamma, a.out_accept_len, a.out_next_token, a.B, x.glue_tok, x.glue_ld, x.glue_len, x.glue_keep_next);
         e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "glue launch");
     }
@@ -365,6 +367,34 @@ hola_status hola_hsd_verify(const hola_model_logits* models, int32_t n_models, i
                             int32_t* out_tokens, int32_t* out_accept_len, int32_t* out_next_token, float* out_entropy,
                             void* workspace, size_t workspace_bytes, hola_stream_t stream)
 {
+    hola_hsd_args a;
+    memset(&a, 0, sizeof a);
+    a.models = models; a.n_models = n_models; a.dtype = dtype; a.draft_tokens = draft_tokens;
+    a.seed = seed; a.seq_base = seq_base; a.B = B; a.gamma = gamma; a.V = V;
+    a.row_temperature = row_temperature; a.temperature = temperature; a.tau = tau; a.survivors_only = 0;
+    a.out_tokens = out_tokens; a.out_accept_len = out_accept_len; a.out_next_token = out_next_token;
+    a.out_entropy = out_entropy; a.workspace = workspace; a.workspace_bytes = workspace_bytes; a.stream = stream;
+    return hola_hsd_verify_ex(&a);
+}
+
+hola_status hola_hsd_verify_ex(const hola_hsd_args* args)
+{
+    if (!args) return HOLA_ERR_INVALID_ARG;
+    const hola_model_logits* models = args->models;
+    const int32_t n_models = args->n_models, dtype = args->dtype, B = args->B, gamma = args->gamma, V = args->V;
+    const int32_t* draft_tokens = args->draft_tokens;
+    const uint64_t seed = args->seed;
+    const int64_t seq_base = args->seq_base;
+    const float* row_temperature = args->row_temperature;
+    const float temperature = args->temperature;
+    const float* tau = args->tau;
+    int32_t* out_tokens = args->out_tokens;
+    int32_t* out_accept_len = args->out_accept_len;
+    int32_t* out_next_token = args->out_next_token;
+    float* out_entropy = args->out_entropy;
+    void* workspace = args->workspace;
+    const size_t workspace_bytes = args->workspace_bytes;
+    hola_stream_t stream = args->stream;
     if (!models || !tau || n_models < 2 || !shape_ok(B, gamma, V) || gamma + n_models - 2 > HOLA_MAX_GAMMA)
         return HOLA_ERR_INVALID_ARG;
     if (dtype != HOLA_DTYPE_F32 && dtype != HOLA_DTYPE_BF16) return HOLA_ERR_UNSUPPORTED;
@@ -406,6 +436,7 @@ hola_status hola_hsd_verify(const hola_model_logits* models, int32_t n_models, i
         LevelExtras x;
         x.tokens_ld = cur_ld;
         x.pad_entropy = 1;
+        x.glue_keep_next = args->survivors_only ? 0 : 1;
         if (k < L) {
             // The next level's drafts are written by this level.  The last middle level writes them
             // straight into out_tokens (when given), which the last level then reads in place.

@@ -103,6 +103,7 @@ struct FusedParams {
     // drafts of the next verify level, written by the per-sequence kernels when given: the kept tokens
     // followed by the next token, -1 up to glue_ld; glue_len[b] = accept length + 1
     int32_t* glue_tok; int32_t* glue_len; int64_t glue_ld;
+    int32_t glue_keep_next;            // 1: append the next token; 0: the kept tokens only
 };
 
 hipError_t launch_fused(const FusedParams& p, const Tuning& t, hipStream_t s);

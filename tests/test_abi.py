@@ -18,7 +18,7 @@ def _declared_functions():
 
 def test_header_symbols_are_exported():
     names = _declared_functions()
-    assert len(names) >= 14
+    assert len(names) >= 16
     L = hb.lib()
     for n in names:
         assert hasattr(L, n), f"{n} declared in include/hola.h but not exported"

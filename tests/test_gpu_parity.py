@@ -146,7 +146,7 @@ def test_config5_f32_greedy_and_stochastic_rows_sampled():
 
 
 # ----------------------------------------------------------------------------- two-level hierarchy
-def _hsd_gpu(models, tokens, seed, T, taus, row_temperature=None):
+def _hsd_gpu(models, tokens, seed, T, taus, row_temperature=None, survivors_only=False):
     ms = [to_dev(m) for m in models]
     n = len(ms)
     B, g, V = ms[0].shape
@@ -157,14 +157,18 @@ def _hsd_gpu(models, tokens, seed, T, taus, row_temperature=None):
     ent = torch.full((L, B, gmax), -7.0, dtype=torch.float32, device=DEV)
     ws = hb.alloc_workspace(hb.hola_hsd_workspace_bytes(n, B, g, V), DEV)
     rt = None if row_temperature is None else to_dev(row_temperature)
-    hb.hola_hsd_verify(ms, to_dev(tokens), seed, B, g, V, T, taus, out_tok, acc, nxt, ent, ws, row_temperature=rt)
+    if survivors_only:
+        hb.hola_hsd_verify_ex(ms, to_dev(tokens), seed, B, g, V, T, taus, out_tok, acc, nxt, ent, ws,
+                              survivors_only=True, row_temperature=rt)
+    else:
+        hb.hola_hsd_verify(ms, to_dev(tokens), seed, B, g, V, T, taus, out_tok, acc, nxt, ent, ws, row_temperature=rt)
     torch.cuda.synchronize()
     return out_tok.cpu().numpy(), acc.cpu().numpy(), nxt.cpu().numpy(), ent.cpu().numpy()
 
 
-def _check_hsd(models, tokens, seed, T, taus, name):
-    out_tok, acc, nxt, ent = _hsd_gpu(models, tokens, seed, T, taus)
-    ref = orc.hsd_verify(models, tokens, seed, T, taus)
+def _check_hsd(models, tokens, seed, T, taus, name, survivors_only=False):
+    out_tok, acc, nxt, ent = _hsd_gpu(models, tokens, seed, T, taus, survivors_only=survivors_only)
+    ref = orc.hsd_verify(models, tokens, seed, T, taus, survivors_only=survivors_only)
     n = len(models)
     B, g, V = models[0].shape
     # Walk the chain level by level so that a listed near-threshold flip is judged where it happens:
@@ -185,8 +189,9 @@ def _check_hsd(models, tokens, seed, T, taus, name):
             for b in range(B):
                 a = gl.accept_len[b]
                 nt[b, :a] = cur_tok[b, :a]
-                nt[b, a] = gl.next_token[b]
-            cur_tok, cur_len = nt, gl.accept_len + 1
+                if not survivors_only:
+                    nt[b, a] = gl.next_token[b]
+            cur_tok, cur_len = nt, gl.accept_len + (0 if survivors_only else 1)
         else:
             np.testing.assert_array_equal(acc, gl.accept_len)
             np.testing.assert_array_equal(nxt, gl.next_token)
@@ -215,6 +220,13 @@ def test_three_level_small_f32():
     q = np.exp(models[0].astype(np.float64))
     tok = np.array([[rng.choice(V, p=q[b, j] / q[b, j].sum()) for j in range(g)] for b in range(B)], np.int32)
     _check_hsd(models, tok, 11, 1.0, [2.0, 3.0, 4.0], "three-level small")
+    _check_hsd(models, tok, 11, 1.0, [2.0, 3.0, 4.0], "three-level small, survivors only", survivors_only=True)
+
+
+def test_two_level_survivors_only_bf16():
+    """The other reading of the hierarchy: a level passes on only the tokens it kept."""
+    w = wl.config4(B=24, V=30011, gamma=5)
+    _check_hsd(w.models, w.tokens, w.seed, w.temperature, [0.0, w.taus[1]], w.name + " survivors only", survivors_only=True)
 
 
 # ----------------------------------------------------------------------------- row statistics alone

@@ -333,6 +333,24 @@ def test_two_level_is_two_one_level_calls():
     assert orc.hsd_uniforms(3, 0, 0, 0) != orc.hsd_uniforms(3, 0, 0, 1)
 
 
+def test_two_level_survivors_only_reading():
+    """The alternative reading: level 2 gets only the tokens level 1 kept (no next token)."""
+    models, tok = _hier_case(B=30)
+    B, g, V = models[0].shape
+    taus = [0.0, 0.5 * math.log(V)]
+    h = orc.hsd_verify(models, tok, 3, 1.0, taus, survivors_only=True)
+    l1 = orc.verify(models[1], models[0], tok, 3, 1.0, taus[0], level=0)
+    tok2 = np.full((B, g + 1), -1, np.int32)
+    for b in range(B):
+        tok2[b, :l1.accept_len[b]] = tok[b, :l1.accept_len[b]]
+    l2 = orc.verify(models[2], models[1], tok2, 3, 1.0, taus[1], draft_len=l1.accept_len, level=1)
+    assert np.array_equal(h.accept_len, l2.accept_len) and np.array_equal(h.next_token, l2.next_token)
+    assert np.array_equal(h.tokens[:, :g + 1], tok2) and np.all(h.accept_len <= l1.accept_len)
+    assert (l1.accept_len == 0).any()                    # an empty survivor list: the level samples its row 0
+    dflt = orc.hsd_verify(models, tok, 3, 1.0, taus)
+    assert not np.array_equal(dflt.tokens, h.tokens)     # the two readings differ
+
+
 def test_two_level_first_emitted_token_follows_final_target():
     """Gate off, tiny V: over many sequences with the same logits, the first emitted token of the
     two-level chain is distributed as the final target's p_0 (lossless chain)."""
