@@ -133,6 +133,16 @@ size_t hola_workspace_bytes(int32_t B, int32_t gamma, int32_t V);
 
 hola_status hola_verify_ex(const hola_verify_args* args /* host */);
 
+/* Equation (1) of the paper taken literally, as an alternative to steps 4-6: no ratio test and no stop.
+ * For every drafted position t < len, y_t = the drafted token if H(draft_t) < tau, otherwise
+ * f_ver(x, draft_<t): a draw from softmax(target_logits[b, t] / T) with the sampling uniform of position t
+ * (the argmax on greedy rows).  Target row gamma is not read.  args is used as in hola_verify_ex except that
+ * out_accept_len / out_next_token are ignored (may be NULL) and draft_stats_in / target_stats_out must be
+ * NULL.  out_tokens: device [B, gamma], -1 beyond draft_len.  out_verifier_calls: device [B] or NULL, the
+ * number of positions that fell back to the verifier (the k of Section 3.1).  HOLA_ERR_UNSUPPORTED above
+ * 2048 sampler tiles per row (V > 4.2 M bf16 / 2.1 M float). */
+hola_status hola_verify_literal_ex(const hola_verify_args* args /* host */, int32_t* out_tokens, int32_t* out_verifier_calls);
+
 /* Hierarchical driver (step 7).  models[0] is the smallest drafter, models[n_models-1] the
  * target; n_models - 1 verify levels.  models[k].logits is device [B, gamma+k, V].
  * Level k (1-based) verifies with models[k] the drafts level k-1 produced (its kept tokens

@@ -504,6 +504,66 @@ int32_t oracle_hsd_verify(const void* const* model_logits, const int64_t* model_
     return rc;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Equation (1) taken literally (no stop at a replaced token): for every       */
+/* drafted position t, y_t = draft token if g(t) = 1[H(draft_t) < tau] = 1,     */
+/* otherwise y_t = f_ver(x, draft_<t): a token of the verifier's distribution  */
+/* at position t given the drafted prefix, i.e. a draw from                    */
+/* p_t = softmax(target[b, t] / T) (argmax on greedy rows) with the sampling   */
+/* uniform of position t.  Target row gamma is not used.  Section 3.1 counts   */
+/* the verifier invocations k; out_calls returns them per sequence.            */
+/* Uses the fields of oracle_verify_args; out_accept_len / out_next_token /    */
+/* ratio outputs are ignored.                                                  */
+/* ------------------------------------------------------------------------- */
+int32_t oracle_verify_literal(const oracle_verify_args* a, int32_t* out_tokens /* [B, gamma], -1 beyond len */,
+                              int32_t* out_calls /* [B] */, double* out_pos_sample_margin /* [B, gamma] or NULL */)
+{
+    if (!a || a->B < 0 || a->gamma < 1 || a->gamma > 63 || a->V < 1) return -1;
+    const int32_t g = a->gamma, V = a->V;
+    const int64_t tld = a->target_ld ? a->target_ld : V;
+    const int64_t dld = a->draft_ld ? a->draft_ld : V;
+    const double tau = (double)a->entropy_threshold;
+    double* w = (double*)malloc((size_t)V * sizeof(double));
+    for (int32_t b = 0; b < a->B; ++b) {
+        const int32_t len = a->draft_len ? a->draft_len[b] : g;
+        const double T = (double)(a->row_temperature ? a->row_temperature[b] : a->temperature);
+        const int greedy = !(T > 0.0);
+        int32_t calls = 0;
+        for (int32_t t = 0; t < g; ++t) {
+            const int64_t o = (int64_t)b * g + t;
+            out_tokens[o] = -1;
+            if (a->out_entropy) a->out_entropy[o] = -1.0f;
+            if (a->out_entropy64) a->out_entropy64[o] = NAN;
+            if (a->out_gate) a->out_gate[o] = 0;
+            if (a->out_gate_margin) a->out_gate_margin[o] = NAN;
+            if (out_pos_sample_margin) out_pos_sample_margin[o] = NAN;
+            if (t >= len) continue;
+            double lseD, HD;
+            oracle_row_stats(a->draft_logits, a->dtype, o * dld, V, T, &lseD, &HD, NULL);
+            const int gate = (HD < tau) ? 1 : 0;
+            if (a->out_entropy) a->out_entropy[o] = (float)HD;
+            if (a->out_entropy64) a->out_entropy64[o] = HD;
+            if (a->out_gate) a->out_gate[o] = (uint8_t)gate;
+            if (a->out_gate_margin) a->out_gate_margin[o] = fabs(HD - tau);
+            if (gate) { out_tokens[o] = a->draft_tokens[o]; continue; }
+            ++calls;
+            const int64_t t_off = ((int64_t)b * (g + 1) + t) * tld;
+            double lseP, HP, Z, m = NAN;
+            int32_t am;
+            oracle_row_stats(a->target_logits, a->dtype, t_off, V, T, &lseP, &HP, &am);
+            if (greedy) { out_tokens[o] = am; continue; }
+            uint32_t r[4];
+            hsd_random_block(a->seed, a->seq_base + b, (uint32_t)t, a->level, r);
+            oracle_residual_weights(a->target_logits, a->draft_logits, a->dtype, t_off, 0, V, T, lseP, 0.0, 1, w);
+            out_tokens[o] = oracle_inverse_cdf(w, V, oracle_u24(r[1]), &Z, &m);
+            if (out_pos_sample_margin) out_pos_sample_margin[o] = m;
+        }
+        if (out_calls) out_calls[b] = calls;
+    }
+    free(w);
+    return 0;
+}
+
 int32_t oracle_max_threads(void)
 {
 #ifdef _OPENMP

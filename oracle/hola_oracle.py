@@ -88,6 +88,8 @@ def lib() -> C.CDLL:
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]
         L.oracle_hsd_verify.restype = C.c_int32
+        L.oracle_verify_literal.argtypes = [C.POINTER(_Args), C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oracle_verify_literal.restype = C.c_int32
         L.oracle_max_threads.argtypes = []
         L.oracle_max_threads.restype = C.c_int32
         _lib = L
@@ -292,6 +294,34 @@ def hsd_verify(models: Sequence[np.ndarray], draft_tokens, seed, temperature, ta
                                  _ptr(r.level_accept), _ptr(r.level_next), int(bool(survivors_only)), int(num_threads))
     if rc != 0:
         raise ValueError("oracle_hsd_verify rejected its arguments")
+    return r
+
+
+@dataclass
+class LiteralResult:
+    tokens: np.ndarray           # [B, gamma]
+    calls: np.ndarray            # [B] verifier invocations
+    entropy: np.ndarray          # float32 [B, gamma]
+    entropy64: np.ndarray
+    gate: np.ndarray
+    gate_margin: np.ndarray
+    sample_margin: np.ndarray    # [B, gamma], NaN where no sample was drawn
+
+
+def verify_literal(target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold, **kw) -> LiteralResult:
+    """Equation (1) without stopping: gate keeps the draft token, otherwise a draw from the target row."""
+    call = VerifyCall(target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold, **kw)
+    B, g = call.B, call.g
+    r = LiteralResult(tokens=np.zeros((B, g), np.int32), calls=np.zeros(B, np.int32),
+                      entropy=np.zeros((B, g), np.float32), entropy64=np.zeros((B, g), np.float64),
+                      gate=np.zeros((B, g), np.uint8), gate_margin=np.zeros((B, g), np.float64),
+                      sample_margin=np.zeros((B, g), np.float64))
+    a = call.args
+    a.out_entropy, a.out_entropy64 = _ptr(r.entropy), _ptr(r.entropy64)
+    a.out_gate, a.out_gate_margin = _ptr(r.gate), _ptr(r.gate_margin)
+    rc = lib().oracle_verify_literal(C.byref(a), _ptr(r.tokens), _ptr(r.calls), _ptr(r.sample_margin))
+    if rc != 0:
+        raise ValueError("oracle_verify_literal rejected its arguments")
     return r
 
 

@@ -20,7 +20,7 @@ HOLA_N_STAGES = 7
 STAGE_NAMES = ("row_stats", "accept", "tile_sums", "select", "glue", "fused", "tail")
 
 EXPORTS = (
-    "hola_verify_f32", "hola_verify_bf16", "hola_verify_ex", "hola_workspace_bytes",
+    "hola_verify_f32", "hola_verify_bf16", "hola_verify_ex", "hola_verify_literal_ex", "hola_workspace_bytes",
     "hola_hsd_verify", "hola_hsd_verify_ex", "hola_hsd_workspace_bytes", "hola_row_stats", "hola_set_tuning",
     "hola_profile_enable", "hola_profile_collect", "hola_copy_bytes", "hola_shutdown", "hola_status_string",
     "hola_last_hip_error", "hola_version",
@@ -89,6 +89,8 @@ def lib() -> C.CDLL:
         L.hola_verify_f32.argtypes = short
         L.hola_verify_bf16.argtypes = short
         L.hola_verify_ex.argtypes = [C.POINTER(VerifyArgs)]
+        L.hola_verify_literal_ex.argtypes = [C.POINTER(VerifyArgs), C.c_void_p, C.c_void_p]
+        L.hola_verify_literal_ex.restype = C.c_int32
         L.hola_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
         L.hola_workspace_bytes.restype = C.c_size_t
         L.hola_hsd_verify.argtypes = [C.POINTER(ModelLogits), C.c_int32, C.c_int32, C.c_void_p, C.c_uint64,
@@ -202,6 +204,26 @@ def hola_verify_ex(*, target_logits, draft_logits, draft_tokens, seed, B, gamma,
     a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     a.stream = _stream_handle(stream)
     _check(lib().hola_verify_ex(C.byref(a)), "hola_verify_ex")
+
+
+def hola_verify_literal_ex(*, target_logits, draft_logits, draft_tokens, seed, B, gamma, V, temperature,
+                           entropy_threshold, out_tokens, out_verifier_calls=None, out_entropy=None, workspace,
+                           draft_len=None, row_temperature=None, level=0, seq_base=0, target_ld=0, draft_ld=0,
+                           entropy_ld=0, stream=None) -> None:
+    a = VerifyArgs()
+    a.target_logits, a.draft_logits = _ptr(target_logits), _ptr(draft_logits)
+    a.dtype = _logit_dtype(target_logits)
+    a.target_ld, a.draft_ld = int(target_ld), int(draft_ld)
+    a.draft_tokens, a.draft_len = _ptr(draft_tokens), _ptr(draft_len)
+    a.row_temperature = _ptr(row_temperature)
+    a.seed, a.level, a.seq_base = int(seed), int(level), int(seq_base)
+    a.B, a.gamma, a.V = int(B), int(gamma), int(V)
+    a.temperature, a.entropy_threshold = float(temperature), float(entropy_threshold)
+    a.out_entropy, a.entropy_ld = _ptr(out_entropy), int(entropy_ld)
+    a.workspace = _ptr(workspace)
+    a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    a.stream = _stream_handle(stream)
+    _check(lib().hola_verify_literal_ex(C.byref(a), _ptr(out_tokens), _ptr(out_verifier_calls)), "hola_verify_literal_ex")
 
 
 def hola_hsd_verify(models: Sequence, draft_tokens, seed, B, gamma, V, temperature, tau: Sequence[float],

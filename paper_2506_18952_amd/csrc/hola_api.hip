@@ -138,13 +138,13 @@ static bool shape_ok(int32_t B, int32_t gamma, int32_t V)
     return B >= 0 && gamma >= 1 && gamma <= HOLA_MAX_GAMMA && V >= 1;
 }
 
-static hola_status check_args(const hola_verify_args& a)
+static hola_status check_args(const hola_verify_args& a, bool literal = false)
 {
     if (!shape_ok(a.B, a.gamma, a.V)) return HOLA_ERR_INVALID_ARG;
     if (a.dtype != HOLA_DTYPE_F32 && a.dtype != HOLA_DTYPE_BF16) return HOLA_ERR_UNSUPPORTED;
     if (a.B == 0) return HOLA_OK;
-    if (!a.target_logits || !a.draft_logits || !a.draft_tokens || !a.out_accept_len || !a.out_next_token)
-        return HOLA_ERR_INVALID_ARG;
+    if (!a.target_logits || !a.draft_logits || !a.draft_tokens) return HOLA_ERR_INVALID_ARG;
+    if (!literal && (!a.out_accept_len || !a.out_next_token)) return HOLA_ERR_INVALID_ARG;
     const size_t es = a.dtype == HOLA_DTYPE_BF16 ? 2 : 4;
     if (((uintptr_t)a.target_logits % es) || ((uintptr_t)a.draft_logits % es)) return HOLA_ERR_INVALID_ARG;
     if ((a.target_ld && a.target_ld < a.V) || (a.draft_ld && a.draft_ld < a.V)) return HOLA_ERR_INVALID_ARG;
@@ -252,6 +252,42 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     return HOLA_OK;
 }
 
+// Equation (1) literal mode: split-row statistics of the draft rows and of target rows j < len, then one
+// per-sequence kernel that gates every position and draws the non-gated ones from their target rows.
+static hola_status run_literal(const hola_verify_args& a, int32_t* out_tokens, int32_t* out_calls)
+{
+    hola_status st = check_args(a, true);
+    if (st != HOLA_OK) return st;
+    if (a.B == 0) return HOLA_OK;
+    if (!out_tokens) return HOLA_ERR_INVALID_ARG;
+    if (a.draft_stats_in || a.target_stats_out) return HOLA_ERR_UNSUPPORTED;
+    if (!literal_supported(a.gamma, a.V, a.dtype)) return HOLA_ERR_UNSUPPORTED;
+    hipStream_t s = (hipStream_t)a.stream;
+    const Workspace w = carve(a.workspace, a.B, a.gamma, a.V);
+    const int64_t tld = a.target_ld ? a.target_ld : a.V, dld = a.draft_ld ? a.draft_ld : a.V;
+    Tuning tune;
+    { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
+    const int nsplit = choose_split((int64_t)a.B * (2 * a.gamma + 1), a.V, a.dtype, tune);
+    RowStatsParams rs{};
+    rs.target = a.target_logits; rs.draft = a.draft_logits; rs.target_ld = tld; rs.draft_ld = dld;
+    rs.draft_len = a.draft_len; rs.row_temperature = a.row_temperature; rs.temperature = a.temperature;
+    rs.B = a.B; rs.gamma = a.gamma; rs.V = a.V; rs.nsplit = nsplit; rs.skip_draft = 0; rs.literal = 1;
+    rs.partials = w.partials;
+    hipError_t e;
+    { StageTimer t(0, s); e = launch_row_stats(rs, a.dtype, tune, s); }
+    if (e != hipSuccess) return hip_fail(e, "row statistics launch");
+    FusedParams fp{};
+    fp.target = a.target_logits; fp.draft = a.draft_logits; fp.dtype = a.dtype; fp.target_ld = tld; fp.draft_ld = dld;
+    fp.tokens = a.draft_tokens; fp.draft_len = a.draft_len; fp.row_temperature = a.row_temperature;
+    fp.seed = a.seed; fp.level = a.level; fp.seq_base = a.seq_base;
+    fp.B = a.B; fp.gamma = a.gamma; fp.V = a.V; fp.ntiles = sampler_tiles(a.V, a.dtype);
+    fp.tokens_ld = a.gamma; fp.temperature = a.temperature; fp.tau = a.entropy_threshold;
+    fp.out_entropy = a.out_entropy; fp.entropy_ld = a.entropy_ld;
+    { StageTimer t(6, s); e = launch_literal(fp, w.partials, nsplit * kWaves, out_tokens, out_calls, s); }
+    if (e != hipSuccess) return hip_fail(e, "literal launch");
+    return HOLA_OK;
+}
+
 // Library-owned workspace of the current device for the short forms.
 static hola_status own_workspace(size_t need, void** out)
 {
@@ -312,6 +348,12 @@ hola_status hola_verify_ex(const hola_verify_args* args)
 {
     if (!args) return HOLA_ERR_INVALID_ARG;
     return run_level(*args);
+}
+
+hola_status hola_verify_literal_ex(const hola_verify_args* args, int32_t* out_tokens, int32_t* out_verifier_calls)
+{
+    if (!args) return HOLA_ERR_INVALID_ARG;
+    return run_literal(*args, out_tokens, out_verifier_calls);
 }
 
 hola_status hola_verify_f32(const float* target_logits, const float* draft_logits, const int32_t* draft_tokens,

@@ -62,6 +62,7 @@ struct RowStatsParams {
     int32_t B, gamma, V;
     int32_t nsplit;
     int32_t skip_draft;                // draft statistics come from a previous level
+    int32_t literal;                   // Equation (1) literal mode: target row j is needed only for j < len
     Partial* partials;
 };
 
@@ -109,6 +110,9 @@ struct FusedParams {
 hipError_t launch_fused(const FusedParams& p, const Tuning& t, hipStream_t s);
 hipError_t launch_tail(const FusedParams& p, const Partial* partials, int nparts, const Tuning& t, hipStream_t s);
 bool fused_supported(int32_t gamma, int32_t V, int dtype);
+bool literal_supported(int32_t gamma, int32_t V, int dtype);
+hipError_t launch_literal(const FusedParams& p, const Partial* partials, int nparts, int32_t* out_tokens,
+                          int32_t* out_calls, hipStream_t s);
 hipError_t launch_row_stats(const RowStatsParams& p, int dtype, const Tuning& t, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
 hipError_t launch_finalize_rows(const Partial* partials, int nparts, int32_t R, double* out, hipStream_t s);

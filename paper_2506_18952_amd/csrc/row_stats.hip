@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(RowStatsParams p)
     const int j = is_draft ? k : (p.skip_draft ? k : k - g);
     int len = p.draft_len ? p.draft_len[b] : g;
     len = len < 0 ? 0 : (len > g ? g : len);
-    if (is_draft ? (j >= len) : (j > len)) return;          // row not needed (uniform exit)
+    if (is_draft ? (j >= len) : (p.literal ? (j >= len) : (j > len))) return;   // row not needed (uniform exit)
 
     const float Tb = p.row_temperature ? p.row_temperature[b] : p.temperature;
     const bool greedy = !(Tb > 0.f);
