@@ -26,6 +26,15 @@ __device__ __forceinline__ float scaled_exponent(float x, float c_hi, float c_lo
     return y;
 }
 
+// Streaming 16-byte load: the logits are read once, so the load carries the non-temporal hint and does not
+// allocate in the caches (on MI355X a pure reader goes from ~6.1 TB/s with plain loads to ~7.0 TB/s).
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream(const uint4* p)
+{
+    const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // Element k (0..EPL-1) of a 16-byte chunk as float.
 template <bool BF16>
 __device__ __forceinline__ float chunk_elem(const uint4& v, int k)

@@ -80,8 +80,8 @@ __device__ __forceinline__ void load_chunk_pair(const RowPair& rp, int64_t c, ui
     vp = make_uint4(0, 0, 0, 0);
     vd = make_uint4(0, 0, 0, 0);
     if (c < rp.nchunks) {
-        vp = rp.Pv[c];
-        if (!rp.bonus && rp.Dv != nullptr) vd = rp.Dv[c];
+        vp = load_stream(rp.Pv + c);
+        if (!rp.bonus && rp.Dv != nullptr) vd = load_stream(rp.Dv + c);
     }
 }
 

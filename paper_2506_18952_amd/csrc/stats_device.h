@@ -245,7 +245,7 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
     while (wave_last + (c - c0) + (int64_t)(U - 1) * stride < c_hi) {
         uint4 buf[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) buf[u] = g.rowv[c + u * stride];
+        for (int u = 0; u < U; ++u) buf[u] = load_stream(g.rowv + c + u * stride);
         if (need_ref) {
             float mx = -INFINITY;
 #pragma unroll
@@ -272,7 +272,7 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             buf[u] = make_uint4(0, 0, 0, 0);
-            if (c + u * stride < c_hi) buf[u] = g.rowv[c + u * stride];
+            if (c + u * stride < c_hi) buf[u] = load_stream(g.rowv + c + u * stride);
         }
         if (need_ref) {
             float mx = -INFINITY;
