@@ -29,11 +29,14 @@ __device__ __forceinline__ float scaled_exponent(float x, float c_hi, float c_lo
 // Streaming 16-byte load: the logits are read once, so the load carries the non-temporal hint and does not
 // allocate in the caches (on MI355X a pure reader goes from ~6.1 TB/s with plain loads to ~7.0 TB/s).
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 load_stream(const uint4* p)
+typedef const __attribute__((address_space(1))) u32x4_t* global_chunk_ptr;   // global (not flat) addressing
+typedef const __attribute__((address_space(1))) char* global_byte_ptr;
+__device__ __forceinline__ uint4 load_stream(global_chunk_ptr p)
 {
-    const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
+    const u32x4_t v = __builtin_nontemporal_load(p);
     return make_uint4(v.x, v.y, v.z, v.w);
 }
+__device__ __forceinline__ uint4 load_stream(const uint4* p) { return load_stream((global_chunk_ptr)p); }
 
 // Element k (0..EPL-1) of a 16-byte chunk as float.
 template <bool BF16>
@@ -53,6 +56,14 @@ __device__ __forceinline__ float load_logit(const void* base, int64_t idx)
 {
     if (BF16) return __uint_as_float((uint32_t)((const uint16_t*)base)[idx] << 16);
     return ((const float*)base)[idx];
+}
+
+// A value that is the same in every lane, moved to scalar registers so that the compiler knows it.
+__device__ __forceinline__ int64_t wave_uniform(int64_t v)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
 // ---- 64-lane wavefront collectives (not on the streaming path) ------------------------------

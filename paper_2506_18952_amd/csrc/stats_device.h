@@ -75,6 +75,10 @@ __device__ __forceinline__ void lane_init(LaneState& st)
     st.vmax = -INFINITY; st.imax = -1;
 }
 
+// 2^d in double for the rare path.  Kept out of line: inlined into the streaming loop, the constants of its
+// polynomial would occupy vector registers for the whole loop.
+__device__ __noinline__ double exp2_out_of_line(double d) { return exp2(d); }
+
 // Move the lane to a reference built from logit mx; the sums are rescaled exactly in double.
 template <bool BF16>
 __device__ __forceinline__ void re_reference(LaneState& st, float mx, const ExpScale& sc)
@@ -82,7 +86,8 @@ __device__ __forceinline__ void re_reference(LaneState& st, float mx, const ExpS
     const float nref = ref_for<BF16>(mx, sc);
     if (st.Sd != 0.0 || st.Td != 0.0) {
         const double delta = ref_offset<BF16>(nref, sc) - ref_offset<BF16>(st.ref, sc);   // < 0
-        const double f = exp2(delta);
+        // bf16 references are integers, so the factor is an exact power of two
+        const double f = BF16 ? ldexp(1.0, (int)fmax(delta, -4096.0)) : exp2_out_of_line(delta);
         st.Td = (st.Td + delta * st.Sd) * f;
         st.Sd *= f;
     }
