@@ -203,8 +203,12 @@ typedef struct {
     int32_t path;                   /* 1: split-row statistics + per-sequence tail kernel (2 launches);
                                        2: fused per-sequence kernel (1 launch);
                                        3: split-row statistics, accept, tile sums, select (4 launches);
-                                       0: the library's choice for the shape */
-    int32_t fused_waves;            /* wavefronts per workgroup of the fused kernel: 8 or 16 */
+                                       0: the library's choice for the shape (path 1 whenever the
+                                          per-sequence kernels support it, else path 3) */
+    int32_t fused_waves;            /* wavefronts per workgroup of the per-sequence kernels: 4 (tail kernel
+                                       only; the fused kernel then uses 8), 8 or 16; 0: 16 for the fused
+                                       kernel, and for the tail kernel 16 / 8 / 4 as the batch grows past
+                                       one / three sequences per compute unit */
 } hola_tuning;
 hola_status hola_set_tuning(const hola_tuning* t /* host; NULL restores defaults */);
 

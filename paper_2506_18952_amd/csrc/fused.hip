@@ -196,7 +196,7 @@ static hipError_t launch_fused_typed(const FusedParams& p, const Tuning& t, hipS
     const int nw = t.fused_waves ? t.fused_waves : 16;
     const int U = t.unroll ? t.unroll : 8;
 #define HOLA_FUSED(NW, UU) hipLaunchKernelGGL((fused_kernel<BF16, NW, UU>), grid, dim3(NW * 64), 0, s, p)
-    if (nw == 8) { if (U == 2) HOLA_FUSED(8, 2); else if (U == 4) HOLA_FUSED(8, 4); else if (U == 16) HOLA_FUSED(8, 16); else HOLA_FUSED(8, 8); }
+    if (nw <= 8) { if (U == 2) HOLA_FUSED(8, 2); else if (U == 4) HOLA_FUSED(8, 4); else if (U == 16) HOLA_FUSED(8, 16); else HOLA_FUSED(8, 8); }
     else { if (U == 2) HOLA_FUSED(16, 2); else if (U == 4) HOLA_FUSED(16, 4); else if (U == 16) HOLA_FUSED(16, 16); else HOLA_FUSED(16, 8); }
 #undef HOLA_FUSED
     return hipGetLastError();
@@ -214,10 +214,12 @@ hipError_t launch_tail(const FusedParams& p, const Partial* partials, int nparts
     dim3 grid((unsigned)p.B);
     const int nw = t.fused_waves ? t.fused_waves : 16;
     if (p.dtype == HOLA_DTYPE_BF16) {
-        if (nw == 8) hipLaunchKernelGGL((tail_kernel<true, 8>), grid, dim3(512), 0, s, p, partials, nparts);
+        if (nw == 4) hipLaunchKernelGGL((tail_kernel<true, 4>), grid, dim3(256), 0, s, p, partials, nparts);
+        else if (nw == 8) hipLaunchKernelGGL((tail_kernel<true, 8>), grid, dim3(512), 0, s, p, partials, nparts);
         else hipLaunchKernelGGL((tail_kernel<true, 16>), grid, dim3(1024), 0, s, p, partials, nparts);
     } else {
-        if (nw == 8) hipLaunchKernelGGL((tail_kernel<false, 8>), grid, dim3(512), 0, s, p, partials, nparts);
+        if (nw == 4) hipLaunchKernelGGL((tail_kernel<false, 4>), grid, dim3(256), 0, s, p, partials, nparts);
+        else if (nw == 8) hipLaunchKernelGGL((tail_kernel<false, 8>), grid, dim3(512), 0, s, p, partials, nparts);
         else hipLaunchKernelGGL((tail_kernel<false, 16>), grid, dim3(1024), 0, s, p, partials, nparts);
     }
     return hipGetLastError();

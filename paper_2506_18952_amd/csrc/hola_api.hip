@@ -88,11 +88,12 @@ struct StageTimer {
     }
 };
 
-// The library's own choice between the two paths.  The fused per-sequence kernel keeps one workgroup of
-// 16 wavefronts per compute unit, so it pays only when the sequences fill the chip at least twice over
-// and the last round of workgroups is not mostly empty; otherwise the split-row pass, which spreads rows
-// over the chip, followed by the per-sequence tail kernel is faster (measured: B=256 bf16 equal within
-// 2 %, B=1024 fp32 fused 3 % faster, B<=128 split up to 1.6x faster).
+// The library's own choices.  Path: the split-row pass, which spreads rows over the whole chip, followed by
+// the per-sequence tail kernel; the fused per-sequence kernel stays selectable but was slower at every batch
+// size measured (B = 1 .. 8192) once the split-row kernel streamed at ~6.6 TB/s.  Tail workgroup: 16
+// wavefronts while every sequence has a compute unit of its own, smaller workgroups (several sequences per
+// compute unit, their latency-bound phases overlapping) beyond that (measured: B=512 8 wavefronts 4-12 %
+// faster than 16, B>=2048 4 wavefronts 4-15 % faster than 8 unless the rows are very long).
 static int device_cu_count()
 {
     static int cached[64] = {0};
@@ -106,12 +107,11 @@ static int device_cu_count()
     return cached[dev];
 }
 
-static bool auto_prefers_fused(int32_t B)
+static int auto_tail_waves(int32_t B, int64_t row_bytes)
 {
     const int cus = device_cu_count();
-    if (B < 2 * cus) return false;
-    const int rem = B % cus;
-    return rem == 0 || rem * 4 >= cus * 3 || B >= 8 * cus;
+    if (B <= cus) return 16;
+    return (B > 3 * cus && row_bytes < (512 << 10)) ? 4 : 8;   // 1 MB rows: 8 beats 4 by 2 % (sweep is bandwidth-bound)
 }
 
 static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -193,7 +193,7 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     fp.out_entropy = a.out_entropy; fp.entropy_ld = a.entropy_ld;
 
     // Path 2: one fused launch per level (one workgroup per sequence streams its own rows).
-    const bool want_fused = tune.path == 2 || (tune.path == 0 && auto_prefers_fused(a.B));
+    const bool want_fused = tune.path == 2;
     if (want_fused && per_seq_ok) {
         hipError_t fe;
         { StageTimer t(5, s); fe = launch_fused(fp, tune, s); }
@@ -213,6 +213,7 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     // Paths 0/1: the split-row pass spreads the rows over the chip, then one per-sequence tail kernel does
     // accept + sampling.  Path 3 keeps accept, tile sums and select as three kernels of their own.
     if (tune.path != 3 && per_seq_ok) {
+        if (tune.fused_waves == 0) tune.fused_waves = auto_tail_waves(a.B, (int64_t)a.V * (a.dtype == HOLA_DTYPE_BF16 ? 2 : 4));
         { StageTimer t(6, s); e = launch_tail(fp, w.partials, nsplit * kWaves, tune, s); }
         if (e != hipSuccess) return hip_fail(e, "tail launch");
         return HOLA_OK;
@@ -557,7 +558,7 @@ hola_status hola_set_tuning(const hola_tuning* t)
         if (t->stats_unroll != 0 && t->stats_unroll != 2 && t->stats_unroll != 4 && t->stats_unroll != 8 && t->stats_unroll != 16)
             return HOLA_ERR_INVALID_ARG;
         if (t->path < 0 || t->path > 3) return HOLA_ERR_INVALID_ARG;
-        if (t->fused_waves != 0 && t->fused_waves != 8 && t->fused_waves != 16) return HOLA_ERR_INVALID_ARG;
+        if (t->fused_waves != 0 && t->fused_waves != 4 && t->fused_waves != 8 && t->fused_waves != 16) return HOLA_ERR_INVALID_ARG;
         n.split = t->stats_split; n.unroll = t->stats_unroll; n.path = t->path; n.fused_waves = t->fused_waves;
     }
     std::lock_guard<std::mutex> lk(g_mu);

@@ -70,10 +70,12 @@ int choose_split(int64_t rows, int V, int dtype, const Tuning& t)
     if (max_useful < 1) max_useful = 1;
     int s = t.split;
     if (s <= 0) {
-        // Aim for >= 8192 workgroups (32 per compute unit) so the tail of the grid is short, but keep
-        // at least 4 chunks per lane in a segment.
+        // Few rows: split until ~2048 workgroups (8 per compute unit) exist, down to 4 chunks per lane.  Beyond
+        // that, split towards 8192 workgroups only while a lane keeps at least 24 chunks (three groups of 8
+        // loads): shorter segments cost more in ramp-up than the shorter last round of the grid gains.
         s = 1;
-        while (rows * s < 8192 && s < kMaxSplit && chunks / (s * 2) >= (int64_t)kBlock * 4) s *= 2;
+        while (rows * s < 2048 && s < kMaxSplit && chunks / (s * 2) >= (int64_t)kBlock * 4) s *= 2;
+        while (rows * s < 8192 && s < kMaxSplit && chunks / (s * 2) >= (int64_t)kBlock * 24) s *= 2;
     }
     if (s > kMaxSplit) s = kMaxSplit;
     if (s > max_useful) s = max_useful;

@@ -236,21 +236,28 @@ __device__ __forceinline__ RowGeom make_geom(const void* row, int32_t V)
 // One wavefront's pass over the chunks c0, c0 + stride, ... < c_hi of a row (c0 already holds the lane's
 // offset), plus, if do_edges, the edge elements (fewer than two chunks' worth, one per lane).
 template <bool BF16, bool ARGMAX, int U, bool ROBUST>
-__device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64_t c0, int64_t c_hi, int64_t stride,
+__device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64_t c0, int64_t c_hi_in, int64_t stride_in,
                                           bool do_edges, const ExpScale& sc, int lane)
 {
+    const int64_t c_hi = wave_uniform(c_hi_in), stride = wave_uniform(stride_in);
     constexpr int N = BF16 ? 8 : 4;
     lane_init(st);
-    int64_t c = c0;
     // The wavefront's lanes start from a common reference taken from the first chunks it loads (with
     // the whole first group already in flight), so that lanes rarely re-reference.
     bool need_ref = !ARGMAX && !ROBUST;
-    const int64_t wave_last = c0 - lane + 63;                   // chunk of the wavefront's last lane
+    // Loop control and addresses are wavefront-uniform (scalar registers): a load is scalar base + lane offset.
+    const int64_t w0 = wave_uniform(c0 - lane);                  // chunk of the wavefront's first lane
+    int64_t w = w0;
+    global_byte_ptr wb = (global_byte_ptr)wave_uniform((int64_t)(uintptr_t)(g.rowv + w0));
+    const uint32_t voff = (uint32_t)lane * 16u;
+    const int64_t sb = stride * 16;
     // groups in which every lane of the wavefront has U chunks: no guards
-    while (wave_last + (c - c0) + (int64_t)(U - 1) * stride < c_hi) {
+    while (w + 63 + (int64_t)(U - 1) * stride < c_hi) {
         uint4 buf[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) buf[u] = load_stream(g.rowv + c + u * stride);
+        for (int u = 0; u < U; ++u) buf[u] = load_stream((global_chunk_ptr)(wb + u * sb + voff));
+        __builtin_amdgcn_sched_barrier(0);                      // every load of the group is issued before any is used
+        const int64_t c = w + lane;
         if (need_ref) {
             float mx = -INFINITY;
 #pragma unroll
@@ -269,15 +276,17 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
             if (ROBUST) accum_chunk_robust<BF16, ARGMAX>(st, buf[u], e0, sc);
             else accum_chunk<BF16, ARGMAX>(st, buf[u], e0, sc);
         }
-        c += (int64_t)U * stride;
+        w += (int64_t)U * stride;
+        wb += (int64_t)U * sb;
     }
     // the last, partial group: all its loads are issued together, each one guarded
-    if (c - lane < c_hi) {                                      // wavefront-uniform
+    if (w < c_hi) {
+        const int64_t c = w + lane;
         uint4 buf[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             buf[u] = make_uint4(0, 0, 0, 0);
-            if (c + u * stride < c_hi) buf[u] = load_stream(g.rowv + c + u * stride);
+            if (c + u * stride < c_hi) buf[u] = load_stream((global_chunk_ptr)(wb + u * sb + voff));
         }
         if (need_ref) {
             float mx = -INFINITY;
