@@ -33,7 +33,8 @@
  * one-hot, two-point and geometric logits; q = p accepts everything; p(x) = 0
  * always rejects; full-lattice enumeration of the uniform; numpy cumsum +
  * searchsorted for the inverse CDF; Z = 1 - sum min(p,q); brute-force output
- * marginal = p on tiny vocabularies; monotonicity of accept length in tau.
+ * marginal = p on tiny vocabularies; monotonicity of accept length in tau;
+ * tile merge = statistics of the whole row (itself pinned to scipy).
  * No function in this file is "parity unpinned".
  */
 #include <math.h>
@@ -137,6 +138,42 @@ void oracle_row_stats(const void* logits, int32_t dtype, int64_t offset, int32_t
     }
     if (lse_out) *lse_out = lse;
     if (H_out) *H_out = lse - acc;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Statistics of a row from the statistics of its column tiles (the row is     */
+/* the concatenation of the tiles; tile t has log-sum-exp lse_t and entropy    */
+/* H_t of its own normalised distribution).  With w_t = exp(lse_t - lse) the   */
+/* probability of element i of tile t is w_t p_{i|t}, so Section 3.1's         */
+/*   H = -sum_i p_i log p_i = sum_t w_t (H_t - log w_t),                       */
+/*   lse = log sum_t exp(lse_t).                                               */
+/* A tile with lse_t = -inf (no finite logit) has w_t = 0 and contributes      */
+/* nothing, whatever its H_t; a row of such tiles gives lse = -inf, H = NaN.   */
+/* A NaN or +inf lse_t makes the row NaN / (+inf, NaN) as oracle_row_stats.    */
+/* ------------------------------------------------------------------------- */
+void oracle_merge_tile_stats(const double* tile_stats /* [ntiles][2] = (lse_t, H_t) */, int32_t ntiles,
+                             double* lse_out, double* H_out)
+{
+    double m = -INFINITY;
+    int bad = 0;
+    for (int32_t t = 0; t < ntiles; ++t) {
+        double l = tile_stats[2 * t];
+        if (l != l) bad = 1;
+        if (l > m) m = l;
+    }
+    if (bad) { *lse_out = NAN; *H_out = NAN; return; }
+    if (!(m > -INFINITY) || !(m < INFINITY)) { *lse_out = (m == INFINITY) ? INFINITY : -INFINITY; *H_out = NAN; return; }
+    double S = 0.0;
+    for (int32_t t = 0; t < ntiles; ++t) S += exp(tile_stats[2 * t] - m);
+    double lse = m + log(S);
+    double H = 0.0;
+    for (int32_t t = 0; t < ntiles; ++t) {
+        double logw = tile_stats[2 * t] - lse;
+        double w = exp(logw);
+        if (w > 0.0) H += w * (tile_stats[2 * t + 1] - logw);
+    }
+    *lse_out = lse;
+    *H_out = H;
 }
 
 /* Probability of token x in the row whose log-sum-exp is lse. */

@@ -65,6 +65,8 @@ def lib() -> C.CDLL:
         L.oracle_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_double,
                                        C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_row_stats.restype = None
+        L.oracle_merge_tile_stats.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        L.oracle_merge_tile_stats.restype = None
         L.oracle_ratio_accept.argtypes = [C.c_double, C.c_double, C.c_double]
         L.oracle_ratio_accept.restype = C.c_int32
         L.oracle_inverse_cdf.argtypes = [C.c_void_p, C.c_int32, C.c_double, C.c_void_p, C.c_void_p]
@@ -136,6 +138,36 @@ def row_stats(row: np.ndarray, T: float = 1.0) -> tuple[float, float, int]:
     lib().oracle_row_stats(_ptr(row), dt, 0, row.shape[-1], float(T),
                            C.addressof(lse), C.addressof(H), C.addressof(am))
     return lse.value, H.value, am.value
+
+
+def tile_stats(rows: np.ndarray, tile_cols: int, T: float = 1.0) -> np.ndarray:
+    """(lse_t, H_t) of every column tile [t*tile_cols, min(V, (t+1)*tile_cols)) of every row: [R, ntiles, 2].
+    Each tile is a row of its own to oracle_row_stats."""
+    rows, dt = _logits(rows)
+    rows = rows.reshape(-1, rows.shape[-1])
+    R, V = rows.shape
+    nt = (V + tile_cols - 1) // tile_cols
+    out = np.empty((R, nt, 2), dtype=np.float64)
+    lse, H = C.c_double(), C.c_double()
+    for r in range(R):
+        for t in range(nt):
+            c0 = t * tile_cols
+            lib().oracle_row_stats(_ptr(rows), dt, r * V + c0, min(tile_cols, V - c0), float(T),
+                                   C.addressof(lse), C.addressof(H), None)
+            out[r, t] = (lse.value, H.value)
+    return out
+
+
+def merge_tile_stats(ts: np.ndarray) -> np.ndarray:
+    """[R, ntiles, 2] tile statistics -> [R, 2] row statistics (entropy chain rule)."""
+    ts = np.ascontiguousarray(ts, dtype=np.float64)
+    R, nt, _ = ts.shape
+    out = np.empty((R, 2), dtype=np.float64)
+    lse, H = C.c_double(), C.c_double()
+    for r in range(R):
+        lib().oracle_merge_tile_stats(ts[r].ctypes.data, nt, C.addressof(lse), C.addressof(H))
+        out[r] = (lse.value, H.value)
+    return out
 
 
 def ratio_accept(u: float, p_x: float, q_x: float) -> bool:
