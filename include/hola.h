@@ -113,6 +113,14 @@ typedef struct {
                                        at the stop row */
     double* target_stats_out;       /* device [B, gamma+1, 2] = (lse, H) of the target rows j <= len;
                                        NULL => not wanted */
+    const double* target_stats_in;  /* device [B, gamma+1, 2] = (lse, H) of the target rows in nats (H is not
+                                       used), e.g. merged from the tile statistics of the LM head that
+                                       produced the logits (hola_merge_tile_stats); NULL => computed here.
+                                       With draft_stats_in also given no logits row is streamed: the call
+                                       reads only the gathered logits of the drafted tokens and the stop
+                                       rows.  Needs temperature > 0 and row_temperature == NULL (the
+                                       statistics carry no argmax for greedy rows), else
+                                       HOLA_ERR_UNSUPPORTED; also unsupported above 2048 sampler tiles per row */
     uint64_t seed;
     uint32_t level;                 /* Philox counter word 3 */
     int64_t seq_base;               /* global index of sequence 0 of this call (Philox counter words 1,2) */
@@ -195,6 +203,26 @@ hola_status hola_row_stats(const void* logits /* device [R, V] */, int32_t dtype
                            int32_t R, int32_t V, float temperature,
                            double* stats_out /* device [R, 2] */,
                            void* workspace, size_t workspace_bytes, hola_stream_t stream);
+
+/* Vocabulary-tiled statistics: what the epilogue of a vocabulary-tiled LM-head GEMM, or each rank of a
+ * vocabulary-sharded head, can compute from the tile of logits it holds, and their merge.  For row r and
+ * column tile t = [t * tile_cols, min(V, (t+1) * tile_cols)), tile_stats_out[r, t] = (lse_t, H_t): the
+ * log-sum-exp and the entropy (Section 3.1, nats) of softmax(logits[r, tile] / T) taken over the tile alone;
+ * a tile with no finite logit gives (-inf, NaN).  ntiles = ceil(V / tile_cols).  Tiles need no alignment.
+ * workspace: device, 256-byte aligned, >= hola_tile_stats_workspace_bytes(R, V, tile_cols). */
+hola_status hola_tile_stats(const void* logits /* device [R, V] */, int32_t dtype, int64_t ld,
+                            int32_t R, int32_t V, int32_t tile_cols, float temperature /* > 0 */,
+                            double* tile_stats_out /* device [R, ntiles, 2] */,
+                            void* workspace, size_t workspace_bytes, hola_stream_t stream);
+size_t hola_tile_stats_workspace_bytes(int32_t R, int32_t V, int32_t tile_cols);   /* 0 on invalid shape */
+
+/* Row statistics from tile statistics: the row's distribution is the mixture of its tiles' with weights
+ * w_t = exp(lse_t - lse), so lse = ln sum_t exp(lse_t) and, by Section 3.1's definition of the entropy,
+ * H = sum_t w_t (H_t - ln w_t).  Tiles with lse_t = -inf carry no mass (their H_t is ignored); a row of
+ * such tiles gives (-inf, NaN); a NaN lse_t gives (NaN, NaN).  The tiles may come from hola_tile_stats, from
+ * another device, or from a GEMM epilogue.  No workspace; both arrays are device memory. */
+hola_status hola_merge_tile_stats(const double* tile_stats /* device [R, ntiles, 2] */, int32_t R, int32_t ntiles,
+                                  double* stats_out /* device [R, 2] = (lse, H) */, hola_stream_t stream);
 
 /* Launch-shape knobs.  Zero in a field keeps the built-in choice for MI355X. */
 typedef struct {

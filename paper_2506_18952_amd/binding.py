@@ -21,7 +21,8 @@ STAGE_NAMES = ("row_stats", "accept", "tile_sums", "select", "glue", "fused", "t
 
 EXPORTS = (
     "hola_verify_f32", "hola_verify_bf16", "hola_verify_ex", "hola_verify_literal_ex", "hola_workspace_bytes",
-    "hola_hsd_verify", "hola_hsd_verify_ex", "hola_hsd_workspace_bytes", "hola_row_stats", "hola_set_tuning",
+    "hola_hsd_verify", "hola_hsd_verify_ex", "hola_hsd_workspace_bytes", "hola_row_stats", "hola_tile_stats",
+    "hola_tile_stats_workspace_bytes", "hola_merge_tile_stats", "hola_set_tuning",
     "hola_profile_enable", "hola_profile_collect", "hola_copy_bytes", "hola_shutdown", "hola_status_string",
     "hola_last_hip_error", "hola_version",
 )
@@ -41,7 +42,7 @@ class VerifyArgs(C.Structure):
         ("target_logits", C.c_void_p), ("draft_logits", C.c_void_p), ("dtype", C.c_int32),
         ("target_ld", C.c_int64), ("draft_ld", C.c_int64),
         ("draft_tokens", C.c_void_p), ("draft_len", C.c_void_p), ("row_temperature", C.c_void_p),
-        ("draft_stats_in", C.c_void_p), ("target_stats_out", C.c_void_p),
+        ("draft_stats_in", C.c_void_p), ("target_stats_out", C.c_void_p), ("target_stats_in", C.c_void_p),
         ("seed", C.c_uint64), ("level", C.c_uint32), ("seq_base", C.c_int64),
         ("B", C.c_int32), ("gamma", C.c_int32), ("V", C.c_int32),
         ("temperature", C.c_float), ("entropy_threshold", C.c_float),
@@ -103,6 +104,13 @@ def lib() -> C.CDLL:
         L.hola_hsd_workspace_bytes.restype = C.c_size_t
         L.hola_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_float,
                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.hola_tile_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_float,
+                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.hola_tile_stats.restype = C.c_int32
+        L.hola_tile_stats_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+        L.hola_tile_stats_workspace_bytes.restype = C.c_size_t
+        L.hola_merge_tile_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.hola_merge_tile_stats.restype = C.c_int32
         L.hola_set_tuning.argtypes = [C.POINTER(Tuning)]
         L.hola_profile_enable.argtypes = [C.c_int32]
         L.hola_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -186,8 +194,8 @@ def hola_verify_bf16(target_logits, draft_logits, draft_tokens, seed, B, gamma, 
 
 def hola_verify_ex(*, target_logits, draft_logits, draft_tokens, seed, B, gamma, V, temperature, entropy_threshold,
                    out_accept_len, out_next_token, out_entropy=None, workspace, draft_len=None,
-                   row_temperature=None, draft_stats_in=None, target_stats_out=None, level=0, seq_base=0,
-                   target_ld=0, draft_ld=0, entropy_ld=0, stream=None) -> None:
+                   row_temperature=None, draft_stats_in=None, target_stats_out=None, target_stats_in=None, level=0,
+                   seq_base=0, target_ld=0, draft_ld=0, entropy_ld=0, stream=None) -> None:
     a = VerifyArgs()
     a.target_logits, a.draft_logits = _ptr(target_logits), _ptr(draft_logits)
     a.dtype = _logit_dtype(target_logits)
@@ -195,6 +203,7 @@ def hola_verify_ex(*, target_logits, draft_logits, draft_tokens, seed, B, gamma,
     a.draft_tokens, a.draft_len = _ptr(draft_tokens), _ptr(draft_len)
     a.row_temperature = _ptr(row_temperature)
     a.draft_stats_in, a.target_stats_out = _ptr(draft_stats_in), _ptr(target_stats_out)
+    a.target_stats_in = _ptr(target_stats_in)
     a.seed, a.level, a.seq_base = int(seed), int(level), int(seq_base)
     a.B, a.gamma, a.V = int(B), int(gamma), int(V)
     a.temperature, a.entropy_threshold = float(temperature), float(entropy_threshold)
@@ -269,6 +278,22 @@ def hola_row_stats(logits, R, V, temperature, stats_out, workspace, ld=0, stream
                               _ptr(stats_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
                               _stream_handle(stream))
     _check(st, "hola_row_stats")
+
+
+def hola_tile_stats_workspace_bytes(R: int, V: int, tile_cols: int) -> int:
+    return int(lib().hola_tile_stats_workspace_bytes(int(R), int(V), int(tile_cols)))
+
+
+def hola_tile_stats(logits, R, V, tile_cols, temperature, tile_stats_out, workspace, ld=0, stream=None) -> None:
+    st = lib().hola_tile_stats(_ptr(logits), _logit_dtype(logits), int(ld), int(R), int(V), int(tile_cols),
+                               float(temperature), _ptr(tile_stats_out), _ptr(workspace),
+                               workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    _check(st, "hola_tile_stats")
+
+
+def hola_merge_tile_stats(tile_stats, R, ntiles, stats_out, stream=None) -> None:
+    st = lib().hola_merge_tile_stats(_ptr(tile_stats), int(R), int(ntiles), _ptr(stats_out), _stream_handle(stream))
+    _check(st, "hola_merge_tile_stats")
 
 
 PATH_AUTO, PATH_SPLIT, PATH_FUSED, PATH_SPLIT4 = 0, 1, 2, 3

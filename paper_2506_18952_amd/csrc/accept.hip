@@ -54,6 +54,48 @@ hipError_t launch_finalize_rows(const Partial* partials, int nparts, int32_t R, 
     return hipGetLastError();
 }
 
+// Row statistics from the statistics of the row's column tiles, one thread per row, double.  The row's
+// distribution is the mixture of the tiles' with weights w_t = exp(lse_t - lse), so Section 3.1's entropy is
+// H = sum_t w_t (H_t - ln w_t); tiles without a finite logit (lse_t = -inf) carry no mass.
+__global__ void merge_tile_stats_kernel(const double* __restrict__ ts, int32_t R, int32_t nt, double* __restrict__ out)
+{
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= R) return;
+    const double* t = ts + (int64_t)r * nt * 2;
+    double m = -INFINITY;
+    bool bad = false;
+    for (int i = 0; i < nt; ++i) {
+        const double l = t[2 * i];
+        if (!(l == l)) bad = true;
+        m = fmax(m, l);
+    }
+    double lse, H = NAN;
+    if (bad) {
+        lse = NAN;
+    } else if (!(m > -INFINITY) || !(m < INFINITY)) {
+        lse = m;
+    } else {
+        double S = 0.0;
+        for (int i = 0; i < nt; ++i) S += exp(t[2 * i] - m);
+        lse = m + log(S);
+        H = 0.0;
+        for (int i = 0; i < nt; ++i) {
+            const double lw = t[2 * i] - lse;
+            const double wt = exp(lw);
+            if (wt > 0.0) H += wt * (t[2 * i + 1] - lw);
+        }
+    }
+    out[2 * (int64_t)r + 0] = lse;
+    out[2 * (int64_t)r + 1] = H;
+}
+
+hipError_t launch_merge_tile_stats(const double* ts, int32_t R, int32_t nt, double* out, hipStream_t s)
+{
+    if (R <= 0) return hipSuccess;
+    hipLaunchKernelGGL(merge_tile_stats_kernel, dim3((unsigned)((R + 127) / 128)), dim3(128), 0, s, ts, R, nt, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s)
 {
     if (p.B <= 0) return hipSuccess;

@@ -63,7 +63,14 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
                 sd = sh.stat[j];
             }
         }
-        if (j <= len) sp = sh.stat[g + j];
+        if (j <= len) {
+            if (p.target_stats_in) {
+                sp.lse = p.target_stats_in[((int64_t)b * (g + 1) + j) * 2 + 0];
+                sp.H = p.target_stats_in[((int64_t)b * (g + 1) + j) * 2 + 1];
+            } else {
+                sp = sh.stat[g + j];
+            }
+        }
         const AcceptCtx c = accept_ctx(p);
         accept_wave<BF16>(c, b, j, len, Tb, sd, sp, &sh.si);
     }
@@ -171,7 +178,8 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
     len = len < 0 ? 0 : (len > g ? g : len);
     const float Tb = p.row_temperature ? p.row_temperature[b] : p.temperature;
     const int first_row = p.draft_stats_in ? g : 0;
-    for (int r = first_row + wave; r < 2 * g + 1; r += NW) {     // one wavefront per row, one lane per partial
+    const int end_row = p.target_stats_in ? g : 2 * g + 1;      // statistics the caller supplies are not merged here
+    for (int r = first_row + wave; r < end_row; r += NW) {      // one wavefront per row, one lane per partial
         const bool is_draft = r < g;
         const int j = is_draft ? r : r - g;
         if (is_draft ? (j >= len) : (j > len)) continue;

@@ -151,6 +151,8 @@ static hola_status check_args(const hola_verify_args& a, bool literal = false)
     if (a.entropy_ld && a.entropy_ld < a.gamma) return HOLA_ERR_INVALID_ARG;
     if (!(a.temperature >= 0.f) || std::isinf(a.temperature)) return HOLA_ERR_INVALID_ARG;   // rejects NaN too
     if (std::isnan(a.entropy_threshold)) return HOLA_ERR_INVALID_ARG;
+    // Supplied target statistics carry no argmax, which greedy rows need.
+    if (a.target_stats_in && (a.row_temperature || !(a.temperature > 0.f))) return HOLA_ERR_UNSUPPORTED;
     if (!a.workspace || ((uintptr_t)a.workspace & 255)) return HOLA_ERR_WORKSPACE;
     if (a.workspace_bytes < hola_workspace_bytes(a.B, a.gamma, a.V)) return HOLA_ERR_WORKSPACE;
     return HOLA_OK;
@@ -172,18 +174,20 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     hipStream_t s = (hipStream_t)a.stream;
     const Workspace w = carve(a.workspace, a.B, a.gamma, a.V);
     const int64_t tld = a.target_ld ? a.target_ld : a.V, dld = a.draft_ld ? a.draft_ld : a.V;
-    const int skip_draft = a.draft_stats_in ? 1 : 0;
-    const int64_t rows = (int64_t)a.B * (skip_draft ? a.gamma + 1 : 2 * a.gamma + 1);
+    const int skip_draft = a.draft_stats_in ? 1 : 0, skip_target = a.target_stats_in ? 1 : 0;
+    const int64_t rows = (int64_t)a.B * ((skip_draft ? 0 : a.gamma) + (skip_target ? 0 : a.gamma + 1));
     Tuning tune;
     { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
-    const int nsplit = choose_split(rows, a.V, a.dtype, tune);
+    const int nsplit = choose_split(rows > 0 ? rows : 1, a.V, a.dtype, tune);
 
     // Per-sequence parameters shared by the fused kernel and the tail kernel.
     const bool per_seq_ok = fused_supported(a.gamma, a.V, a.dtype);
+    if (skip_target && !per_seq_ok) return HOLA_ERR_UNSUPPORTED;    // only the tail kernel takes them
+    if (skip_target) tune.path = 1;
     FusedParams fp{};
     fp.target = a.target_logits; fp.draft = a.draft_logits; fp.dtype = a.dtype; fp.target_ld = tld; fp.draft_ld = dld;
     fp.tokens = a.draft_tokens; fp.draft_len = a.draft_len; fp.row_temperature = a.row_temperature;
-    fp.draft_stats_in = a.draft_stats_in; fp.target_stats_out = a.target_stats_out;
+    fp.draft_stats_in = a.draft_stats_in; fp.target_stats_out = a.target_stats_out; fp.target_stats_in = a.target_stats_in;
     fp.seed = a.seed; fp.level = a.level; fp.seq_base = a.seq_base;
     fp.B = a.B; fp.gamma = a.gamma; fp.V = a.V; fp.ntiles = sampler_tiles(a.V, a.dtype);
     fp.tokens_ld = x.tokens_ld ? x.tokens_ld : a.gamma; fp.pad_entropy = x.pad_entropy;
@@ -204,10 +208,10 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     RowStatsParams rs{};
     rs.target = a.target_logits; rs.draft = a.draft_logits; rs.target_ld = tld; rs.draft_ld = dld;
     rs.draft_len = a.draft_len; rs.row_temperature = a.row_temperature; rs.temperature = a.temperature;
-    rs.B = a.B; rs.gamma = a.gamma; rs.V = a.V; rs.nsplit = nsplit; rs.skip_draft = skip_draft;
+    rs.B = a.B; rs.gamma = a.gamma; rs.V = a.V; rs.nsplit = nsplit; rs.skip_draft = skip_draft; rs.skip_target = skip_target;
     rs.partials = w.partials;
-    hipError_t e;
-    { StageTimer t(0, s); e = launch_row_stats(rs, a.dtype, tune, s); }
+    hipError_t e = hipSuccess;
+    if (rows > 0) { StageTimer t(0, s); e = launch_row_stats(rs, a.dtype, tune, s); }   // nothing to stream when both are supplied
     if (e != hipSuccess) return hip_fail(e, "row statistics launch");
 
     // Paths 0/1: the split-row pass spreads the rows over the chip, then one per-sequence tail kernel does
@@ -261,7 +265,7 @@ static hola_status run_literal(const hola_verify_args& a, int32_t* out_tokens, i
     if (st != HOLA_OK) return st;
     if (a.B == 0) return HOLA_OK;
     if (!out_tokens) return HOLA_ERR_INVALID_ARG;
-    if (a.draft_stats_in || a.target_stats_out) return HOLA_ERR_UNSUPPORTED;
+    if (a.draft_stats_in || a.target_stats_out || a.target_stats_in) return HOLA_ERR_UNSUPPORTED;
     if (!literal_supported(a.gamma, a.V, a.dtype)) return HOLA_ERR_UNSUPPORTED;
     hipStream_t s = (hipStream_t)a.stream;
     const Workspace w = carve(a.workspace, a.B, a.gamma, a.V);
@@ -536,6 +540,61 @@ hola_status hola_row_stats(const void* logits, int32_t dtype, int64_t ld, int32_
     }
     if (e != hipSuccess) return hip_fail(e, "finalize launch");
     return HOLA_OK;
+}
+
+// Vocabulary-tiled statistics.  A tile is a row of its own to the split-row kernel (R * ntiles virtual rows).
+static int tiles_of(int32_t V, int32_t tile_cols) { return (int)(((int64_t)V + tile_cols - 1) / tile_cols); }
+
+size_t hola_tile_stats_workspace_bytes(int32_t R, int32_t V, int32_t tile_cols)
+{
+    if (R < 0 || V < 1 || tile_cols < 1) return 0;
+    const int64_t vr = (int64_t)R * tiles_of(V, tile_cols);
+    if (vr > 0x7fffffffLL) return 0;
+    return hola_workspace_bytes((int32_t)vr, 1, tile_cols < V ? tile_cols : V);
+}
+
+hola_status hola_tile_stats(const void* logits, int32_t dtype, int64_t ld, int32_t R, int32_t V, int32_t tile_cols,
+                            float temperature, double* tile_stats_out, void* workspace, size_t workspace_bytes,
+                            hola_stream_t stream)
+{
+    if (R < 0 || V < 1 || tile_cols < 1) return HOLA_ERR_INVALID_ARG;
+    if (dtype != HOLA_DTYPE_F32 && dtype != HOLA_DTYPE_BF16) return HOLA_ERR_UNSUPPORTED;
+    if (R == 0) return HOLA_OK;
+    if (!logits || !tile_stats_out || !(temperature > 0.f) || std::isinf(temperature)) return HOLA_ERR_INVALID_ARG;
+    if (ld && ld < V) return HOLA_ERR_INVALID_ARG;
+    if ((uintptr_t)logits % (dtype == HOLA_DTYPE_BF16 ? 2 : 4)) return HOLA_ERR_INVALID_ARG;
+    const int nt = tiles_of(V, tile_cols);
+    const int64_t vr = (int64_t)R * nt;
+    if (vr > 0x7fffffffLL) return HOLA_ERR_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace & 255)) return HOLA_ERR_WORKSPACE;
+    if (workspace_bytes < hola_tile_stats_workspace_bytes(R, V, tile_cols)) return HOLA_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    const int32_t tc = tile_cols < V ? tile_cols : V;
+    const Workspace w = carve(workspace, (int32_t)vr, 1, tc);
+    Tuning tune;
+    { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
+    const int nsplit = choose_split(vr, tc, dtype, tune);
+    RowStatsParams rs{};
+    rs.target = logits; rs.draft = logits; rs.target_ld = ld ? ld : V; rs.draft_ld = rs.target_ld;
+    rs.temperature = temperature; rs.B = (int32_t)vr; rs.gamma = 0; rs.V = V; rs.nsplit = nsplit; rs.skip_draft = 1;
+    rs.tile_cols = tc; rs.ntiles = nt;
+    rs.partials = w.partials;
+    hipError_t e;
+    { StageTimer t(0, s); e = launch_row_stats(rs, dtype, tune, s); }
+    if (e != hipSuccess) return hip_fail(e, "tile statistics launch");
+    { StageTimer t(1, s); e = launch_finalize_rows(w.partials, nsplit * kWaves, (int32_t)vr, tile_stats_out, s); }
+    if (e != hipSuccess) return hip_fail(e, "finalize launch");
+    return HOLA_OK;
+}
+
+hola_status hola_merge_tile_stats(const double* tile_stats, int32_t R, int32_t ntiles, double* stats_out, hola_stream_t stream)
+{
+    if (R < 0 || ntiles < 1) return HOLA_ERR_INVALID_ARG;
+    if (R == 0) return HOLA_OK;
+    if (!tile_stats || !stats_out) return HOLA_ERR_INVALID_ARG;
+    hipError_t e;
+    { StageTimer t(4, (hipStream_t)stream); e = launch_merge_tile_stats(tile_stats, R, ntiles, stats_out, (hipStream_t)stream); }
+    return e == hipSuccess ? HOLA_OK : hip_fail(e, "tile merge launch");
 }
 
 hola_status hola_copy_bytes(void* dst, const void* src, size_t bytes, hola_stream_t stream)

@@ -62,6 +62,8 @@ struct RowStatsParams {
     int32_t B, gamma, V;
     int32_t nsplit;
     int32_t skip_draft;                // draft statistics come from a previous level
+    int32_t skip_target;               // target statistics are given by the caller
+    int32_t tile_cols, ntiles;         // ntiles > 0: "sequence" b is column tile b % ntiles of plain row b / ntiles
     int32_t literal;                   // Equation (1) literal mode: target row j is needed only for j < len
     Partial* partials;
 };
@@ -94,7 +96,7 @@ struct FusedParams {
     const void* target; const void* draft; int32_t dtype;
     int64_t target_ld, draft_ld;
     const int32_t* tokens; const int32_t* draft_len; const float* row_temperature;
-    const double* draft_stats_in; double* target_stats_out;
+    const double* draft_stats_in; double* target_stats_out; const double* target_stats_in;
     uint64_t seed; uint32_t level; int64_t seq_base;
     int32_t B, gamma, V, ntiles;
     int64_t tokens_ld;                 // row stride of tokens (>= gamma)
@@ -115,6 +117,7 @@ hipError_t launch_literal(const FusedParams& p, const Partial* partials, int npa
                           int32_t* out_calls, hipStream_t s);
 hipError_t launch_row_stats(const RowStatsParams& p, int dtype, const Tuning& t, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
+hipError_t launch_merge_tile_stats(const double* ts, int32_t R, int32_t nt, double* out, hipStream_t s);
 hipError_t launch_finalize_rows(const Partial* partials, int nparts, int32_t R, double* out, hipStream_t s);
 hipError_t launch_tile_sums(const SamplerParams& p, hipStream_t s);
 hipError_t launch_select(const SamplerParams& p, hipStream_t s);

@@ -35,11 +35,12 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(RowStatsParams p)
     const int seg = (int)(blk % nsplit);
     const int64_t r = blk / nsplit;
     const int g = p.gamma;
-    const int rows_per_seq = p.skip_draft ? (g + 1) : (2 * g + 1);
+    const int n_d = p.skip_draft ? 0 : g, n_t = p.skip_target ? 0 : g + 1;
+    const int rows_per_seq = n_d + n_t;
     const int b = (int)(r / rows_per_seq);
     const int k = (int)(r % rows_per_seq);
-    const bool is_draft = !p.skip_draft && k < g;
-    const int j = is_draft ? k : (p.skip_draft ? k : k - g);
+    const bool is_draft = k < n_d;
+    const int j = is_draft ? k : k - n_d;
     int len = p.draft_len ? p.draft_len[b] : g;
     len = len < 0 ? 0 : (len > g ? g : len);
     if (is_draft ? (j >= len) : (p.literal ? (j >= len) : (j > len))) return;   // row not needed (uniform exit)
@@ -50,7 +51,14 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(RowStatsParams p)
     constexpr int ES = BF16 ? 2 : 4;
     const char* row;
     int64_t slot;
-    if (is_draft) {
+    int32_t Vrow = p.V;
+    if (p.ntiles > 0) {                                          // column tile of a plain row
+        const int64_t pr = b / p.ntiles, t = b % p.ntiles;
+        row = (const char*)p.target + (pr * p.target_ld + t * p.tile_cols) * ES;
+        const int64_t left = (int64_t)p.V - t * p.tile_cols;
+        Vrow = (int32_t)(left < p.tile_cols ? left : p.tile_cols);
+        slot = b;
+    } else if (is_draft) {
         row = (const char*)p.draft + ((int64_t)b * g + j) * p.draft_ld * ES;
         slot = (int64_t)b * g + j;
     } else {
@@ -58,8 +66,8 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(RowStatsParams p)
         slot = (int64_t)p.B * g + (int64_t)b * (g + 1) + j;
     }
     Partial* out = p.partials + (slot * nsplit + seg) * kWaves;
-    if (greedy && !is_draft) row_segment<BF16, true, U>(row, p.V, seg, nsplit, sc, out);
-    else row_segment<BF16, false, U>(row, p.V, seg, nsplit, sc, out);
+    if (greedy && !is_draft) row_segment<BF16, true, U>(row, Vrow, seg, nsplit, sc, out);
+    else row_segment<BF16, false, U>(row, Vrow, seg, nsplit, sc, out);
 }
 
 int choose_split(int64_t rows, int V, int dtype, const Tuning& t)
@@ -86,7 +94,7 @@ template <bool BF16>
 static hipError_t launch_typed(const RowStatsParams& p, const Tuning& t, hipStream_t s)
 {
     const int g = p.gamma;
-    const int64_t rows = (int64_t)p.B * (p.skip_draft ? (g + 1) : (2 * g + 1));
+    const int64_t rows = (int64_t)p.B * ((p.skip_draft ? 0 : g) + (p.skip_target ? 0 : g + 1));
     const int64_t nblk = rows * p.nsplit;
     if (nblk <= 0) return hipSuccess;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;

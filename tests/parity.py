@@ -44,8 +44,8 @@ class GpuOut:
 
 
 def run_gpu_level(target, draft, tokens, seed, temperature, tau, *, draft_len=None, row_temperature=None,
-                  seq_base=0, level=0, draft_stats_in=None, want_target_stats=False, short=False,
-                  dev_inputs=None) -> GpuOut:
+                  seq_base=0, level=0, draft_stats_in=None, target_stats_in=None, want_target_stats=False,
+                  short=False, dev_inputs=None) -> GpuOut:
     """One level through the C ABI.  `target`/`draft` are numpy (uint16 = bf16 bits) or device tensors."""
     P = target if torch.is_tensor(target) else to_dev(target)
     D = draft if torch.is_tensor(draft) else to_dev(draft)
@@ -64,11 +64,12 @@ def run_gpu_level(target, draft, tokens, seed, temperature, tau, *, draft_len=No
         dl = None if draft_len is None else to_dev(np.ascontiguousarray(draft_len, np.int32))
         rt = None if row_temperature is None else to_dev(np.ascontiguousarray(row_temperature, np.float32))
         dsi = None if draft_stats_in is None else to_dev(np.ascontiguousarray(draft_stats_in, np.float64))
+        tsi = None if target_stats_in is None else to_dev(np.ascontiguousarray(target_stats_in, np.float64))
         tstats = torch.full((B, g + 1, 2), float("nan"), dtype=torch.float64, device=DEV) if want_target_stats else None
         hb.hola_verify_ex(target_logits=P, draft_logits=D, draft_tokens=tok, seed=seed, B=B, gamma=g, V=V,
                           temperature=temperature, entropy_threshold=tau, out_accept_len=acc, out_next_token=nxt,
                           out_entropy=ent, workspace=ws, draft_len=dl, row_temperature=rt, draft_stats_in=dsi,
-                          target_stats_out=tstats, level=level, seq_base=seq_base)
+                          target_stats_out=tstats, target_stats_in=tsi, level=level, seq_base=seq_base)
     torch.cuda.synchronize()
     return GpuOut(acc.cpu().numpy(), nxt.cpu().numpy(), ent.cpu().numpy(),
                   None if tstats is None else tstats.cpu().numpy())

@@ -129,3 +129,31 @@ def test_product_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "hola_oracle" not in text and "from oracle" not in text and "import oracle" not in text, f
+
+
+def test_tile_entry_points_argument_checks():
+    L = hb.lib()
+    f = 0x1000
+    assert hb.hola_tile_stats_workspace_bytes(4, 1000, 128) > 0
+    assert hb.hola_tile_stats_workspace_bytes(4, 1000, 0) == 0
+    assert hb.hola_tile_stats_workspace_bytes(-1, 1000, 128) == 0
+    assert hb.hola_tile_stats_workspace_bytes(8, 1000, 10) > hb.hola_tile_stats_workspace_bytes(8, 1000, 500)
+    ws, wb = 0x10000, 1 << 30
+    assert L.hola_tile_stats(f, 0, 0, 4, 100, 0, 1.0, f, ws, wb, None) == hb.HOLA_ERR_INVALID_ARG      # tile_cols < 1
+    assert L.hola_tile_stats(None, 0, 0, 4, 100, 10, 1.0, f, ws, wb, None) == hb.HOLA_ERR_INVALID_ARG
+    assert L.hola_tile_stats(f, 0, 0, 4, 100, 10, 0.0, f, ws, wb, None) == hb.HOLA_ERR_INVALID_ARG     # T must be > 0
+    assert L.hola_tile_stats(f, 0, 50, 4, 100, 10, 1.0, f, ws, wb, None) == hb.HOLA_ERR_INVALID_ARG    # ld < V
+    assert L.hola_tile_stats(f, 5, 0, 4, 100, 10, 1.0, f, ws, wb, None) == hb.HOLA_ERR_UNSUPPORTED
+    assert L.hola_tile_stats(f, 0, 0, 4, 100, 10, 1.0, f, ws, 64, None) == hb.HOLA_ERR_WORKSPACE
+    assert L.hola_tile_stats(f, 0, 0, 0, 100, 10, 1.0, f, ws, wb, None) == hb.HOLA_OK                  # no rows
+    assert L.hola_merge_tile_stats(None, 4, 3, f, None) == hb.HOLA_ERR_INVALID_ARG
+    assert L.hola_merge_tile_stats(f, 4, 0, f, None) == hb.HOLA_ERR_INVALID_ARG
+    assert L.hola_merge_tile_stats(f, 0, 3, f, None) == hb.HOLA_OK
+
+
+def test_supplied_target_statistics_argument_checks():
+    a = _args(target_stats_in=0x2000)
+    a.row_temperature = 0x3000
+    assert hb.lib().hola_verify_ex(C.byref(a)) == hb.HOLA_ERR_UNSUPPORTED
+    a = _args(target_stats_in=0x2000, temperature=0.0)
+    assert hb.lib().hola_verify_ex(C.byref(a)) == hb.HOLA_ERR_UNSUPPORTED
