@@ -34,7 +34,10 @@
  * always rejects; full-lattice enumeration of the uniform; numpy cumsum +
  * searchsorted for the inverse CDF; Z = 1 - sum min(p,q); brute-force output
  * marginal = p on tiny vocabularies; monotonicity of accept length in tau;
- * tile merge = statistics of the whole row (itself pinned to scipy).
+ * tile merge = statistics of the whole row (itself pinned to scipy); top-k /
+ * top-p keep sets = numpy stable sort + cumsum, filtered statistics = scipy on
+ * the kept subset, filters off = the unfiltered step, output marginal = the
+ * filtered target.
  * No function in this file is "parity unpinned".
  */
 #include <math.h>
@@ -406,6 +409,233 @@ int32_t oracle_verify(const oracle_verify_args* a)
 #pragma omp for schedule(dynamic, 1)
         for (int32_t b = 0; b < a->B; ++b) verify_one_sequence(a, b, w);
         free(w);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Filtered distributions: top-k, then top-p (nucleus) on what top-k left.     */
+/* The paper does not filter; these are the usual sampling-time truncations,   */
+/* applied to both models before the acceptance test so that the drafted       */
+/* token, the test and the residual all speak of the distributions that are    */
+/* actually sampled.  Definition used here: order the tokens by scaled logit,  */
+/* largest first, equal logits by ascending index (a stable order); top-k      */
+/* keeps the first k (k <= 0 or k >= V: all); top-p then keeps the shortest    */
+/* prefix of those whose probability, as a fraction of the top-k mass,         */
+/* reaches top_p (top_p >= 1: all of them; at least one token is kept).        */
+/* Tokens with logit -inf are never kept.  The kept tokens are renormalised:   */
+/* lse_out / H_out are the log-sum-exp and entropy (nats) over the kept set.   */
+/* margin_out: distance of the nucleus target from the nearer of the two       */
+/* cumulative sums that decide the cut, as a fraction of the top-k mass (NaN   */
+/* when top-p is off).  Returns the number of kept tokens.                     */
+/* ------------------------------------------------------------------------- */
+typedef struct { double z; int32_t i; } oracle_zi;
+
+static int zi_desc(const void* pa, const void* pb)
+{
+    const oracle_zi* a = (const oracle_zi*)pa;
+    const oracle_zi* b = (const oracle_zi*)pb;
+    if (a->z > b->z) return -1;
+    if (a->z < b->z) return 1;
+    return (a->i > b->i) - (a->i < b->i);
+}
+
+int32_t oracle_filter_row(const void* logits, int32_t dtype, int64_t offset, int32_t V, double T,
+                          int32_t top_k, double top_p, uint8_t* keep, double* lse_out, double* H_out,
+                          double* margin_out)
+{
+    double lse, H;
+    oracle_row_stats(logits, dtype, offset, V, T, &lse, &H, NULL);
+    for (int32_t i = 0; i < V; ++i) keep[i] = 0;
+    if (margin_out) *margin_out = NAN;
+    if (!(lse > -INFINITY) || !(lse < INFINITY)) { *lse_out = lse; *H_out = NAN; return 0; }
+
+    oracle_zi* o = (oracle_zi*)malloc((size_t)V * sizeof(oracle_zi));
+    int32_t n_finite = 0;
+    for (int32_t i = 0; i < V; ++i) {
+        o[i].z = scaled(logit_at(logits, dtype, offset + i), T);
+        o[i].i = i;
+        if (o[i].z > -INFINITY) ++n_finite;
+    }
+    qsort(o, (size_t)V, sizeof(oracle_zi), zi_desc);
+
+    int32_t m = (top_k > 0 && top_k < V) ? top_k : V;
+    if (m > n_finite) m = n_finite;
+    if (top_p < 1.0) {
+        double Zk = 0.0;
+        for (int32_t r = 0; r < m; ++r) Zk += exp(o[r].z - lse);
+        const double target = top_p * Zk;
+        double c = 0.0;
+        for (int32_t r = 0; r < m; ++r) {
+            const double c_prev = c;
+            c += exp(o[r].z - lse);
+            if (c >= target) {
+                if (margin_out) { double hi = c - target, lo = target - c_prev; *margin_out = (hi < lo ? hi : lo) / Zk; }
+                m = r + 1;
+                break;
+            }
+        }
+    }
+    for (int32_t r = 0; r < m; ++r) keep[o[r].i] = 1;
+    free(o);
+
+    /* statistics of the kept tokens, in index order */
+    double mx = -INFINITY;
+    for (int32_t i = 0; i < V; ++i)
+        if (keep[i]) { double z = scaled(logit_at(logits, dtype, offset + i), T); if (z > mx) mx = z; }
+    double S = 0.0;
+    for (int32_t i = 0; i < V; ++i)
+        if (keep[i]) S += exp(scaled(logit_at(logits, dtype, offset + i), T) - mx);
+    const double lseK = mx + log(S);
+    double acc = 0.0;
+    for (int32_t i = 0; i < V; ++i)
+        if (keep[i]) { double z = scaled(logit_at(logits, dtype, offset + i), T); acc += z * exp(z - lseK); }
+    *lse_out = lseK;
+    *H_out = lseK - acc;
+    return m;
+}
+
+/* Probability of token x under the filtered, renormalised distribution. */
+static double filtered_prob_at(const void* logits, int32_t dtype, int64_t offset, int32_t x, double T,
+                               const uint8_t* keep, double lseK)
+{
+    return keep[x] ? prob_at(logits, dtype, offset, x, T, lseK) : 0.0;
+}
+
+/* One verify level on filtered distributions: the steps of oracle_verify with
+ * q and p replaced by their filtered, renormalised versions everywhere (gate
+ * entropy, acceptance test, residual, bonus).  Stochastic rows only (every
+ * temperature > 0).  Extra outputs, any may be NULL: out_filter_margin
+ * [B, 2 gamma + 1] (draft rows 0..gamma-1, then target rows 0..gamma; NaN for
+ * rows not needed or with top-p off), out_keep_count likewise (-1 unused).
+ * force_accept_len and the out_lse / out_H_target arrays refer to the filtered
+ * statistics.  Returns 0, or -1 on an argument the oracle does not take. */
+static void verify_filtered_one_sequence(const oracle_verify_args* a, int32_t top_k, double top_p, int32_t b,
+                                         double* w, uint8_t* keepD, uint8_t* keepP,
+                                         double* out_filter_margin, int32_t* out_keep_count)
+{
+    const int32_t g = a->gamma, V = a->V;
+    const int64_t tld = a->target_ld ? a->target_ld : V;
+    const int64_t dld = a->draft_ld ? a->draft_ld : V;
+    const int32_t len = a->draft_len ? a->draft_len[b] : g;
+    const double T = (double)(a->row_temperature ? a->row_temperature[b] : a->temperature);
+    const double tau = (double)a->entropy_threshold;
+    const int64_t seq = a->seq_base + b;
+    const int32_t R = 2 * g + 1;
+
+    double lseD[64], HD[64], lseP[65], HP[65];
+    for (int32_t j = 0; j < g; ++j) {
+        if (a->out_entropy) a->out_entropy[(int64_t)b * g + j] = -1.0f;
+        if (a->out_entropy64) a->out_entropy64[(int64_t)b * g + j] = NAN;
+        if (a->out_gate) a->out_gate[(int64_t)b * g + j] = 0;
+        if (a->out_ratio_ok) a->out_ratio_ok[(int64_t)b * g + j] = 0;
+        if (a->out_gate_margin) a->out_gate_margin[(int64_t)b * g + j] = NAN;
+        if (a->out_ratio_margin) a->out_ratio_margin[(int64_t)b * g + j] = NAN;
+        if (a->out_lse_draft) a->out_lse_draft[(int64_t)b * g + j] = NAN;
+    }
+    for (int32_t j = 0; j <= g; ++j) {
+        if (a->out_lse_target) a->out_lse_target[(int64_t)b * (g + 1) + j] = NAN;
+        if (a->out_H_target) a->out_H_target[(int64_t)b * (g + 1) + j] = NAN;
+    }
+    for (int32_t k = 0; k < R; ++k) {
+        if (out_filter_margin) out_filter_margin[(int64_t)b * R + k] = NAN;
+        if (out_keep_count) out_keep_count[(int64_t)b * R + k] = -1;
+    }
+
+    for (int32_t j = 0; j < len; ++j) {
+        double mg;
+        int32_t n = oracle_filter_row(a->draft_logits, a->dtype, ((int64_t)b * g + j) * dld, V, T, top_k, top_p,
+                                      keepD + (size_t)j * V, &lseD[j], &HD[j], &mg);
+        if (out_filter_margin) out_filter_margin[(int64_t)b * R + j] = mg;
+        if (out_keep_count) out_keep_count[(int64_t)b * R + j] = n;
+        if (a->out_entropy) a->out_entropy[(int64_t)b * g + j] = (float)HD[j];
+        if (a->out_entropy64) a->out_entropy64[(int64_t)b * g + j] = HD[j];
+        if (a->out_lse_draft) a->out_lse_draft[(int64_t)b * g + j] = lseD[j];
+    }
+    for (int32_t j = 0; j <= len; ++j) {
+        double mg;
+        int32_t n = oracle_filter_row(a->target_logits, a->dtype, ((int64_t)b * (g + 1) + j) * tld, V, T, top_k, top_p,
+                                      keepP + (size_t)j * V, &lseP[j], &HP[j], &mg);
+        if (out_filter_margin) out_filter_margin[(int64_t)b * R + g + j] = mg;
+        if (out_keep_count) out_keep_count[(int64_t)b * R + g + j] = n;
+        if (a->out_lse_target) a->out_lse_target[(int64_t)b * (g + 1) + j] = lseP[j];
+        if (a->out_H_target) a->out_H_target[(int64_t)b * (g + 1) + j] = HP[j];
+    }
+
+    int32_t acc_len = len;
+    for (int32_t j = 0; j < len; ++j) {
+        int gate = (HD[j] < tau) ? 1 : 0;
+        int32_t x = a->draft_tokens[(int64_t)b * g + j];
+        uint32_t r[4];
+        hsd_random_block(a->seed, seq, (uint32_t)j, a->level, r);
+        double u = oracle_u24(r[0]);
+        double p_x = 0.0, q_x = 1.0, rmargin = NAN;
+        if (x >= 0 && x < V) {
+            p_x = filtered_prob_at(a->target_logits, a->dtype, ((int64_t)b * (g + 1) + j) * tld, x, T, keepP + (size_t)j * V, lseP[j]);
+            q_x = filtered_prob_at(a->draft_logits, a->dtype, ((int64_t)b * g + j) * dld, x, T, keepD + (size_t)j * V, lseD[j]);
+        }
+        int ok = oracle_ratio_accept(u, p_x, q_x);
+        if (q_x > 0.0) rmargin = fabs(u - p_x / q_x);
+        if (a->out_gate) a->out_gate[(int64_t)b * g + j] = (uint8_t)gate;
+        if (a->out_ratio_ok) a->out_ratio_ok[(int64_t)b * g + j] = (uint8_t)ok;
+        if (a->out_gate_margin) a->out_gate_margin[(int64_t)b * g + j] = fabs(HD[j] - tau);
+        if (a->out_ratio_margin) a->out_ratio_margin[(int64_t)b * g + j] = rmargin;
+        if (!(gate || ok) && acc_len == len) acc_len = j;
+    }
+    if (a->force_accept_len && a->force_accept_len[b] >= 0) acc_len = a->force_accept_len[b];
+    if (a->out_accept_len) a->out_accept_len[b] = acc_len;
+
+    const int32_t rrow = acc_len;
+    uint32_t r[4];
+    hsd_random_block(a->seed, seq, (uint32_t)rrow, a->level, r);
+    const double u2 = oracle_u24(r[1]);
+    const int32_t bonus = (acc_len >= len);
+    const int64_t t_off = ((int64_t)b * (g + 1) + rrow) * tld;
+    const int64_t d_off = ((int64_t)b * g + (bonus ? 0 : rrow)) * dld;
+    const uint8_t* kP = keepP + (size_t)rrow * V;
+    const uint8_t* kD = keepD + (size_t)(bonus ? 0 : rrow) * V;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int as_bonus = bonus || pass == 1;             /* second pass: residual without mass, sample p itself */
+        for (int32_t i = 0; i < V; ++i) {
+            double p = filtered_prob_at(a->target_logits, a->dtype, t_off, i, T, kP, lseP[rrow]);
+            if (as_bonus) { w[i] = p; continue; }
+            double q = filtered_prob_at(a->draft_logits, a->dtype, d_off, i, T, kD, lseD[rrow]);
+            double d = p - q;
+            w[i] = d > 0.0 ? d : 0.0;
+        }
+        double Z, smargin;
+        int32_t tok = oracle_inverse_cdf(w, V, u2, &Z, &smargin);
+        if (as_bonus || Z > 0.0) {
+            if (a->out_next_token) a->out_next_token[b] = tok;
+            if (a->out_sample_margin) a->out_sample_margin[b] = smargin;
+            if (a->out_Z) a->out_Z[b] = Z;
+            break;
+        }
+    }
+}
+
+int32_t oracle_verify_filtered(const oracle_verify_args* a, int32_t top_k, double top_p,
+                               double* out_filter_margin, int32_t* out_keep_count)
+{
+    if (!a || a->B < 0 || a->gamma < 1 || a->gamma > 63 || a->V < 1) return -1;
+    if (!(top_p > 0.0)) return -1;
+    if (!a->row_temperature && !(a->temperature > 0.f)) return -1;
+    if (a->row_temperature)
+        for (int32_t b = 0; b < a->B; ++b) if (!(a->row_temperature[b] > 0.f)) return -1;
+    int nthreads = 1;
+#ifdef _OPENMP
+    nthreads = a->num_threads > 0 ? a->num_threads : omp_get_max_threads();
+#endif
+    (void)nthreads;
+#pragma omp parallel num_threads(nthreads)
+    {
+        double* w = (double*)malloc((size_t)a->V * sizeof(double));
+        uint8_t* keepD = (uint8_t*)malloc((size_t)a->gamma * a->V);
+        uint8_t* keepP = (uint8_t*)malloc((size_t)(a->gamma + 1) * a->V);
+#pragma omp for schedule(dynamic, 1)
+        for (int32_t b = 0; b < a->B; ++b)
+            verify_filtered_one_sequence(a, top_k, top_p, b, w, keepD, keepP, out_filter_margin, out_keep_count);
+        free(w); free(keepD); free(keepP);
     }
     return 0;
 }

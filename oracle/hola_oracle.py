@@ -81,6 +81,11 @@ def lib() -> C.CDLL:
         L.oracle_residual_weights.restype = None
         L.oracle_verify.argtypes = [C.POINTER(_Args)]
         L.oracle_verify.restype = C.c_int32
+        L.oracle_filter_row.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_double, C.c_int32,
+                                        C.c_double, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oracle_filter_row.restype = C.c_int32
+        L.oracle_verify_filtered.argtypes = [C.POINTER(_Args), C.c_int32, C.c_double, C.c_void_p, C.c_void_p]
+        L.oracle_verify_filtered.restype = C.c_int32
         L.oracle_sample_interval.argtypes = [C.POINTER(_Args), C.c_int32, C.c_int32, C.c_int32,
                                              C.c_void_p, C.c_void_p]
         L.oracle_sample_interval.restype = C.c_int32
@@ -228,6 +233,8 @@ class VerifyResult:
     ratio_margin: np.ndarray
     sample_margin: np.ndarray
     Z: np.ndarray
+    filter_margin: Optional[np.ndarray] = None   # [B, 2 gamma + 1], filtered step only
+    keep_count: Optional[np.ndarray] = None
 
 
 class VerifyCall:
@@ -259,7 +266,8 @@ class VerifyCall:
         a.num_threads = int(num_threads)
         self.args = a
 
-    def run(self) -> VerifyResult:
+    def run(self, top_k: Optional[int] = None, top_p: Optional[float] = None) -> VerifyResult:
+        """top_k / top_p given: the step on filtered distributions (oracle_verify_filtered)."""
         B, g = self.B, self.g
         r = VerifyResult(
             accept_len=np.zeros(B, np.int32), next_token=np.zeros(B, np.int32),
@@ -276,9 +284,16 @@ class VerifyCall:
         a.out_gate, a.out_ratio_ok = _ptr(r.gate), _ptr(r.ratio_ok)
         a.out_gate_margin, a.out_ratio_margin = _ptr(r.gate_margin), _ptr(r.ratio_margin)
         a.out_sample_margin, a.out_Z = _ptr(r.sample_margin), _ptr(r.Z)
-        rc = lib().oracle_verify(C.byref(a))
+        if top_k is None and top_p is None:
+            rc = lib().oracle_verify(C.byref(a))
+        else:
+            R = 2 * g + 1
+            r.filter_margin = np.zeros((B, R), np.float64)
+            r.keep_count = np.zeros((B, R), np.int32)
+            rc = lib().oracle_verify_filtered(C.byref(a), int(top_k or 0), float(1.0 if top_p is None else top_p),
+                                              _ptr(r.filter_margin), _ptr(r.keep_count))
         if rc != 0:
-            raise ValueError("oracle_verify rejected its arguments")
+            raise ValueError("the oracle rejected its arguments")
         return r
 
     def sample_interval(self, b: int, acc_len: int, tok: int) -> Optional[tuple[float, float]]:
@@ -290,6 +305,24 @@ class VerifyCall:
 
 def verify(target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold, **kw) -> VerifyResult:
     return VerifyCall(target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold, **kw).run()
+
+
+def verify_filtered(target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold, top_k=0,
+                    top_p=1.0, **kw) -> VerifyResult:
+    call = VerifyCall(target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold, **kw)
+    return call.run(top_k=top_k, top_p=top_p)
+
+
+def filter_row(row: np.ndarray, T: float = 1.0, top_k: int = 0, top_p: float = 1.0):
+    """(keep mask [V] bool, lse and entropy of the kept, renormalised tokens, nucleus cut margin)."""
+    row, dt = _logits(row)
+    V = row.shape[-1]
+    keep = np.zeros(V, np.uint8)
+    lse, H, mg = C.c_double(), C.c_double(), C.c_double()
+    n = lib().oracle_filter_row(_ptr(row), dt, 0, V, float(T), int(top_k), float(top_p), _ptr(keep),
+                                C.addressof(lse), C.addressof(H), C.addressof(mg))
+    assert n == int(keep.sum())
+    return keep.astype(bool), lse.value, H.value, mg.value
 
 
 @dataclass

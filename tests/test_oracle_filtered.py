@@ -1,0 +1,175 @@
+"""Pins of the oracle's filtered (top-k / top-p) verify step, CPU only.  The paper does not filter; the
+definition is the usual one (stable descending order, top-k prefix, then the shortest prefix reaching top_p of
+the top-k mass), pinned here to numpy's stable sort and cumulative sums, to scipy on the kept subset, to closed
+forms, to the unfiltered step when the filters are off, and to the property that makes the rule worth having:
+with drafts drawn from the filtered q the emitted token follows the filtered p."""
+import math
+
+import numpy as np
+import pytest
+import scipy.special
+import scipy.stats
+
+from oracle import hola_oracle as orc
+from paper_2506_18952_amd import workloads as wl
+
+
+def _np_keep(z, top_k, top_p):
+    V = z.shape[0]
+    order = np.argsort(-z, kind="stable")
+    p = scipy.special.softmax(z)
+    m = top_k if 0 < top_k < V else V
+    m = min(m, int(np.isfinite(z).sum()))
+    if top_p < 1.0:
+        ps = p[order[:m]]
+        c = np.cumsum(ps)
+        m = min(m, int(np.searchsorted(c, top_p * c[-1], side="left")) + 1)
+    keep = np.zeros(V, bool)
+    keep[order[:m]] = True
+    return keep
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("top_k,top_p", [(1, 1.0), (5, 1.0), (50, 1.0), (0, 0.3), (0, 0.9), (0, 0.999), (40, 0.8),
+                                         (1000000, 1.0), (3, 0.0001)])
+def test_keep_set_is_numpy_stable_sort_prefix(dtype, top_k, top_p):
+    w = wl.small_case(3, 2, 2003, dtype=dtype, temperature=0.7, case_id=31)
+    T = float(np.float32(0.7))
+    for row in w.target.reshape(-1, w.V)[:5]:
+        z = wl.as_f32(row).astype(np.float64) / T
+        keep, lse, H, mg = orc.filter_row(row, T, top_k, top_p)
+        want = _np_keep(z, top_k, top_p)
+        if top_p < 1.0 and mg < 1e-12:
+            continue                                          # the cut itself is a rounding matter
+        assert np.array_equal(keep, want)
+        assert lse == pytest.approx(scipy.special.logsumexp(z[keep]), abs=1e-12)
+        assert H == pytest.approx(scipy.stats.entropy(scipy.special.softmax(z[keep])), abs=1e-11)
+        assert (top_p < 1.0) == (not math.isnan(mg))
+
+
+def test_ties_are_broken_by_ascending_index_and_closed_forms():
+    V = 100
+    row = np.zeros(V, np.float32)                              # uniform: every logit ties
+    keep, lse, H, _ = orc.filter_row(row, 1.0, 7, 1.0)
+    assert np.flatnonzero(keep).tolist() == list(range(7)) and H == pytest.approx(math.log(7), abs=1e-14)
+    keep, lse, H, mg = orc.filter_row(row, 1.0, 0, 0.495)
+    assert np.flatnonzero(keep).tolist() == list(range(50)) and H == pytest.approx(math.log(50), abs=1e-14)
+    assert mg == pytest.approx(0.005, abs=1e-12)               # 50/100 - 0.495
+    keep, _, _, _ = orc.filter_row(row, 1.0, 0, 0.505)
+    assert keep.sum() == 51
+    keep, _, H, mg = orc.filter_row(row, 1.0, 20, 0.26)         # nucleus is taken of the top-k mass: 0.26 * 20 -> 6
+    assert np.flatnonzero(keep).tolist() == list(range(6)) and mg == pytest.approx(0.01, abs=1e-12)   # (0.052 - 0.05) / 0.2
+    # two-point distribution: p = (0.8, 0.2) in reversed index order
+    row = np.log(np.array([0.2, 0.8])).astype(np.float32)
+    keep, lse, H, mg = orc.filter_row(row, 1.0, 0, 0.7)
+    assert keep.tolist() == [False, True] and H == pytest.approx(0.0, abs=1e-15)
+    assert mg == pytest.approx(0.1, abs=1e-7) and lse == pytest.approx(math.log(0.8), abs=1e-7)
+    keep, _, H, _ = orc.filter_row(row, 1.0, 0, 0.85)
+    assert keep.all() and H == pytest.approx(-(0.8 * math.log(0.8) + 0.2 * math.log(0.2)), abs=1e-7)
+
+
+def test_masked_logits_are_never_kept():
+    row = np.full(10, -np.inf, np.float32)
+    row[[2, 7, 8]] = [1.0, 3.0, 1.0]
+    keep, lse, H, _ = orc.filter_row(row, 1.0, 5, 1.0)
+    assert np.flatnonzero(keep).tolist() == [2, 7, 8]
+    keep, _, _, _ = orc.filter_row(row, 1.0, 2, 1.0)
+    assert np.flatnonzero(keep).tolist() == [2, 7]              # the tie at 1.0 goes to the lower index
+    keep, lse, H, _ = orc.filter_row(np.full(4, -np.inf, np.float32), 1.0, 2, 0.5)
+    assert not keep.any() and lse == -math.inf and math.isnan(H)
+
+
+def test_filters_off_is_the_unfiltered_step():
+    for dtype in ("f32", "bf16"):
+        w = wl.small_case(8, 4, 301, dtype=dtype, temperature=0.8, case_id=12)
+        for tau in (0.0, w.taus[0]):
+            a = orc.verify(w.target, w.draft, w.tokens, w.seed, 0.8, tau)
+            b = orc.verify_filtered(w.target, w.draft, w.tokens, w.seed, 0.8, tau, top_k=0, top_p=1.0)
+            c = orc.verify_filtered(w.target, w.draft, w.tokens, w.seed, 0.8, tau, top_k=w.V, top_p=1.0)
+            for r in (b, c):
+                assert np.array_equal(a.accept_len, r.accept_len) and np.array_equal(a.next_token, r.next_token)
+                assert np.array_equal(a.gate, r.gate) and np.array_equal(a.ratio_ok, r.ratio_ok)
+                np.testing.assert_allclose(a.entropy64, r.entropy64, atol=1e-12)
+                np.testing.assert_allclose(a.Z, r.Z, rtol=1e-12)
+                assert (r.keep_count == w.V).all()
+
+
+def test_decisions_recomputed_by_brute_force():
+    top_k, top_p = 60, 0.85
+    w = wl.small_case(10, 5, 401, dtype="bf16", temperature=0.8, case_id=44)
+    T = float(np.float32(0.8))
+    tau = 0.35 * math.log(w.V)
+    tau32 = float(np.float32(tau))
+    r = orc.verify_filtered(w.target, w.draft, w.tokens, w.seed, T, tau, top_k=top_k, top_p=top_p)
+
+    def dist(row):
+        z = wl.as_f32(row).astype(np.float64) / T
+        keep = _np_keep(z, top_k, top_p)
+        d = np.where(keep, np.exp(z - scipy.special.logsumexp(z[keep])), 0.0)
+        return d
+
+    for b in range(w.B):
+        if np.nanmin(r.filter_margin[b]) < 1e-9:
+            continue
+        a = w.gamma
+        for j in range(w.gamma):
+            q, p = dist(w.draft[b, j]), dist(w.target[b, j])
+            H = scipy.stats.entropy(q[q > 0])
+            assert r.entropy64[b, j] == pytest.approx(H, abs=1e-10)
+            u = orc.hsd_uniforms(w.seed, b, j, 0)[0]
+            x = w.tokens[b, j]
+            gate, ok = H < tau32, u * q[x] < p[x]
+            if abs(H - tau32) > 1e-9 and (q[x] == 0 or abs(u - p[x] / q[x]) > 1e-9):
+                assert bool(r.gate[b, j]) == gate and bool(r.ratio_ok[b, j]) == ok, (b, j)
+        acc = np.logical_or(r.gate[b], r.ratio_ok[b])
+        rej = np.flatnonzero(~acc)
+        a = int(rej[0]) if len(rej) else w.gamma
+        assert r.accept_len[b] == a
+        u2 = orc.hsd_uniforms(w.seed, b, a, 0)[1]
+        p = dist(w.target[b, a])
+        wts = p if a == w.gamma else np.maximum(0.0, p - dist(w.draft[b, a]))
+        C = np.cumsum(wts)
+        if C[-1] > 0 and r.sample_margin[b] > 1e-9:
+            assert r.next_token[b] == int(np.searchsorted(C, u2 * C[-1], side="right"))
+            assert r.Z[b] == pytest.approx(C[-1], rel=1e-9)
+        assert wts[r.next_token[b]] > 0                        # the sample lies in the support
+
+
+def test_emitted_tokens_follow_the_filtered_target():
+    """Monte Carlo through oracle_verify_filtered (gate off): drafts drawn from the filtered q, the token
+    emitted at position 0 is distributed as the filtered p_0 and never leaves its support."""
+    rng = np.random.default_rng(7)
+    V, g, N = 8, 2, 200_000
+    top_k, top_p = 6, 0.9
+    P1 = (1.3 * rng.standard_normal((g + 1, V))).astype(np.float32)
+    D1 = (1.3 * rng.standard_normal((g, V))).astype(np.float32)
+
+    def dist(row):
+        z = row.astype(np.float64)
+        keep = _np_keep(z, top_k, top_p)
+        return np.where(keep, np.exp(z - scipy.special.logsumexp(z[keep])), 0.0)
+
+    q = np.stack([dist(D1[j]) for j in range(g)])
+    p = np.stack([dist(P1[j]) for j in range(g + 1)])
+    P = np.broadcast_to(P1, (N, g + 1, V)).copy()
+    D = np.broadcast_to(D1, (N, g, V)).copy()
+    tok = np.stack([rng.choice(V, size=N, p=q[j]) for j in range(g)], axis=1).astype(np.int32)
+    r = orc.verify_filtered(P, D, tok, 4242, 1.0, 0.0, top_k=top_k, top_p=top_p)
+    first = np.where(r.accept_len >= 1, tok[:, 0], r.next_token)
+    cnt = np.bincount(first, minlength=V)
+    sup = p[0] > 0
+    assert cnt[~sup].sum() == 0 and 2 <= sup.sum() < V
+    assert scipy.stats.chisquare(cnt[sup], N * p[0][sup]).pvalue > 1e-3
+    rate = np.minimum(p[0], q[0]).sum()
+    assert abs((r.accept_len >= 1).mean() - rate) < 5 * math.sqrt(rate * (1 - rate) / N)
+    # teeth: the unfiltered target is a different distribution
+    pu = scipy.special.softmax(P1[0].astype(np.float64))
+    assert scipy.stats.chisquare(cnt[sup], N * pu[sup] / pu[sup].sum() ).pvalue < 1e-6 or abs(pu[sup].sum() - 1) > 0.02
+
+
+def test_rejects_greedy_rows_and_bad_top_p():
+    w = wl.small_case(2, 2, 50, case_id=3)
+    with pytest.raises(ValueError):
+        orc.verify_filtered(w.target, w.draft, w.tokens, 1, 0.0, 1.0, top_k=5)
+    with pytest.raises(ValueError):
+        orc.verify_filtered(w.target, w.draft, w.tokens, 1, 1.0, 1.0, top_p=0.0)
