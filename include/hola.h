@@ -121,6 +121,19 @@ typedef struct {
                                        rows.  Needs temperature > 0 and row_temperature == NULL (the
                                        statistics carry no argmax for greedy rows), else
                                        HOLA_ERR_UNSUPPORTED; also unsupported above 2048 sampler tiles per row */
+    int32_t top_k;                  /* > 0: both models' distributions are truncated to their top_k largest
+                                       logits (equal logits: lower index first) and renormalised before the
+                                       gate entropy, the acceptance test and the residual; 0 or >= V: off */
+    float top_p;                    /* in (0, 1): after top_k, keep the shortest prefix of the tokens in
+                                       descending order whose probability reaches top_p of the top_k mass
+                                       (at least one token), renormalised; 0 or >= 1: off.  With either filter
+                                       on: temperature > 0, row_temperature / draft_stats_in / target_stats_in
+                                       / target_stats_out NULL, V < 2^22 and at most 2048 sampler tiles per
+                                       row, else HOLA_ERR_UNSUPPORTED; out_entropy is the entropy of the
+                                       filtered draft distribution */
+    int32_t* out_keep_count;        /* device [B, 2*gamma+1] or NULL; written only with a filter on: the
+                                       number of tokens kept in draft rows 0..gamma-1, then in target rows
+                                       0..gamma, of each sequence; -1 for rows the call does not use */
     uint64_t seed;
     uint32_t level;                 /* Philox counter word 3 */
     int64_t seq_base;               /* global index of sequence 0 of this call (Philox counter words 1,2) */

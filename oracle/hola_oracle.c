@@ -428,6 +428,8 @@ int32_t oracle_verify(const oracle_verify_args* a)
 /* margin_out: distance of the nucleus target from the nearer of the two       */
 /* cumulative sums that decide the cut, as a fraction of the top-k mass (NaN   */
 /* when top-p is off).  Returns the number of kept tokens.                     */
+/* force_m >= 0 (test aid) overrides the length of the kept prefix, so that a  */
+/* cut that differs within rounding can be followed through the later steps.   */
 /* ------------------------------------------------------------------------- */
 typedef struct { double z; int32_t i; } oracle_zi;
 
@@ -441,8 +443,8 @@ static int zi_desc(const void* pa, const void* pb)
 }
 
 int32_t oracle_filter_row(const void* logits, int32_t dtype, int64_t offset, int32_t V, double T,
-                          int32_t top_k, double top_p, uint8_t* keep, double* lse_out, double* H_out,
-                          double* margin_out)
+                          int32_t top_k, double top_p, int32_t force_m, uint8_t* keep, double* lse_out,
+                          double* H_out, double* margin_out)
 {
     double lse, H;
     oracle_row_stats(logits, dtype, offset, V, T, &lse, &H, NULL);
@@ -476,6 +478,7 @@ int32_t oracle_filter_row(const void* logits, int32_t dtype, int64_t offset, int
             }
         }
     }
+    if (force_m >= 0) m = force_m < n_finite ? force_m : n_finite;
     for (int32_t r = 0; r < m; ++r) keep[o[r].i] = 1;
     free(o);
 
@@ -512,7 +515,8 @@ static double filtered_prob_at(const void* logits, int32_t dtype, int64_t offset
  * statistics.  Returns 0, or -1 on an argument the oracle does not take. */
 static void verify_filtered_one_sequence(const oracle_verify_args* a, int32_t top_k, double top_p, int32_t b,
                                          double* w, uint8_t* keepD, uint8_t* keepP,
-                                         double* out_filter_margin, int32_t* out_keep_count)
+                                         double* out_filter_margin, int32_t* out_keep_count,
+                                         const int32_t* force_keep_count)
 {
     const int32_t g = a->gamma, V = a->V;
     const int64_t tld = a->target_ld ? a->target_ld : V;
@@ -545,6 +549,7 @@ static void verify_filtered_one_sequence(const oracle_verify_args* a, int32_t to
     for (int32_t j = 0; j < len; ++j) {
         double mg;
         int32_t n = oracle_filter_row(a->draft_logits, a->dtype, ((int64_t)b * g + j) * dld, V, T, top_k, top_p,
+                                      force_keep_count ? force_keep_count[(int64_t)b * R + j] : -1,
                                       keepD + (size_t)j * V, &lseD[j], &HD[j], &mg);
         if (out_filter_margin) out_filter_margin[(int64_t)b * R + j] = mg;
         if (out_keep_count) out_keep_count[(int64_t)b * R + j] = n;
@@ -555,6 +560,7 @@ static void verify_filtered_one_sequence(const oracle_verify_args* a, int32_t to
     for (int32_t j = 0; j <= len; ++j) {
         double mg;
         int32_t n = oracle_filter_row(a->target_logits, a->dtype, ((int64_t)b * (g + 1) + j) * tld, V, T, top_k, top_p,
+                                      force_keep_count ? force_keep_count[(int64_t)b * R + g + j] : -1,
                                       keepP + (size_t)j * V, &lseP[j], &HP[j], &mg);
         if (out_filter_margin) out_filter_margin[(int64_t)b * R + g + j] = mg;
         if (out_keep_count) out_keep_count[(int64_t)b * R + g + j] = n;
@@ -615,7 +621,8 @@ static void verify_filtered_one_sequence(const oracle_verify_args* a, int32_t to
 }
 
 int32_t oracle_verify_filtered(const oracle_verify_args* a, int32_t top_k, double top_p,
-                               double* out_filter_margin, int32_t* out_keep_count)
+                               double* out_filter_margin, int32_t* out_keep_count,
+                               const int32_t* force_keep_count /* [B, 2 gamma + 1] or NULL; entries < 0: not forced */)
 {
     if (!a || a->B < 0 || a->gamma < 1 || a->gamma > 63 || a->V < 1) return -1;
     if (!(top_p > 0.0)) return -1;
@@ -634,7 +641,8 @@ int32_t oracle_verify_filtered(const oracle_verify_args* a, int32_t top_k, doubl
         uint8_t* keepP = (uint8_t*)malloc((size_t)(a->gamma + 1) * a->V);
 #pragma omp for schedule(dynamic, 1)
         for (int32_t b = 0; b < a->B; ++b)
-            verify_filtered_one_sequence(a, top_k, top_p, b, w, keepD, keepP, out_filter_margin, out_keep_count);
+            verify_filtered_one_sequence(a, top_k, top_p, b, w, keepD, keepP, out_filter_margin, out_keep_count,
+                                         force_keep_count);
         free(w); free(keepD); free(keepP);
     }
     return 0;

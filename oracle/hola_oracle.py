@@ -82,9 +82,9 @@ def lib() -> C.CDLL:
         L.oracle_verify.argtypes = [C.POINTER(_Args)]
         L.oracle_verify.restype = C.c_int32
         L.oracle_filter_row.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_double, C.c_int32,
-                                        C.c_double, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+                                        C.c_double, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_filter_row.restype = C.c_int32
-        L.oracle_verify_filtered.argtypes = [C.POINTER(_Args), C.c_int32, C.c_double, C.c_void_p, C.c_void_p]
+        L.oracle_verify_filtered.argtypes = [C.POINTER(_Args), C.c_int32, C.c_double, C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_verify_filtered.restype = C.c_int32
         L.oracle_sample_interval.argtypes = [C.POINTER(_Args), C.c_int32, C.c_int32, C.c_int32,
                                              C.c_void_p, C.c_void_p]
@@ -266,7 +266,8 @@ class VerifyCall:
         a.num_threads = int(num_threads)
         self.args = a
 
-    def run(self, top_k: Optional[int] = None, top_p: Optional[float] = None) -> VerifyResult:
+    def run(self, top_k: Optional[int] = None, top_p: Optional[float] = None,
+            force_keep_count: Optional[np.ndarray] = None) -> VerifyResult:
         """top_k / top_p given: the step on filtered distributions (oracle_verify_filtered)."""
         B, g = self.B, self.g
         r = VerifyResult(
@@ -290,8 +291,9 @@ class VerifyCall:
             R = 2 * g + 1
             r.filter_margin = np.zeros((B, R), np.float64)
             r.keep_count = np.zeros((B, R), np.int32)
+            fk = None if force_keep_count is None else np.ascontiguousarray(force_keep_count, np.int32).reshape(B, R)
             rc = lib().oracle_verify_filtered(C.byref(a), int(top_k or 0), float(1.0 if top_p is None else top_p),
-                                              _ptr(r.filter_margin), _ptr(r.keep_count))
+                                              _ptr(r.filter_margin), _ptr(r.keep_count), _ptr(fk))
         if rc != 0:
             raise ValueError("the oracle rejected its arguments")
         return r
@@ -308,9 +310,9 @@ def verify(target_logits, draft_logits, draft_tokens, seed, temperature, entropy
 
 
 def verify_filtered(target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold, top_k=0,
-                    top_p=1.0, **kw) -> VerifyResult:
+                    top_p=1.0, force_keep_count=None, **kw) -> VerifyResult:
     call = VerifyCall(target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold, **kw)
-    return call.run(top_k=top_k, top_p=top_p)
+    return call.run(top_k=top_k, top_p=top_p, force_keep_count=force_keep_count)
 
 
 def filter_row(row: np.ndarray, T: float = 1.0, top_k: int = 0, top_p: float = 1.0):
@@ -319,7 +321,7 @@ def filter_row(row: np.ndarray, T: float = 1.0, top_k: int = 0, top_p: float = 1
     V = row.shape[-1]
     keep = np.zeros(V, np.uint8)
     lse, H, mg = C.c_double(), C.c_double(), C.c_double()
-    n = lib().oracle_filter_row(_ptr(row), dt, 0, V, float(T), int(top_k), float(top_p), _ptr(keep),
+    n = lib().oracle_filter_row(_ptr(row), dt, 0, V, float(T), int(top_k), float(top_p), -1, _ptr(keep),
                                 C.addressof(lse), C.addressof(H), C.addressof(mg))
     assert n == int(keep.sum())
     return keep.astype(bool), lse.value, H.value, mg.value

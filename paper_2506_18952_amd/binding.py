@@ -43,6 +43,7 @@ class VerifyArgs(C.Structure):
         ("target_ld", C.c_int64), ("draft_ld", C.c_int64),
         ("draft_tokens", C.c_void_p), ("draft_len", C.c_void_p), ("row_temperature", C.c_void_p),
         ("draft_stats_in", C.c_void_p), ("target_stats_out", C.c_void_p), ("target_stats_in", C.c_void_p),
+        ("top_k", C.c_int32), ("top_p", C.c_float), ("out_keep_count", C.c_void_p),
         ("seed", C.c_uint64), ("level", C.c_uint32), ("seq_base", C.c_int64),
         ("B", C.c_int32), ("gamma", C.c_int32), ("V", C.c_int32),
         ("temperature", C.c_float), ("entropy_threshold", C.c_float),
@@ -195,7 +196,8 @@ def hola_verify_bf16(target_logits, draft_logits, draft_tokens, seed, B, gamma, 
 def hola_verify_ex(*, target_logits, draft_logits, draft_tokens, seed, B, gamma, V, temperature, entropy_threshold,
                    out_accept_len, out_next_token, out_entropy=None, workspace, draft_len=None,
                    row_temperature=None, draft_stats_in=None, target_stats_out=None, target_stats_in=None, level=0,
-                   seq_base=0, target_ld=0, draft_ld=0, entropy_ld=0, stream=None) -> None:
+                   seq_base=0, target_ld=0, draft_ld=0, entropy_ld=0, top_k=0, top_p=0.0, out_keep_count=None,
+                   stream=None) -> None:
     a = VerifyArgs()
     a.target_logits, a.draft_logits = _ptr(target_logits), _ptr(draft_logits)
     a.dtype = _logit_dtype(target_logits)
@@ -204,6 +206,7 @@ def hola_verify_ex(*, target_logits, draft_logits, draft_tokens, seed, B, gamma,
     a.row_temperature = _ptr(row_temperature)
     a.draft_stats_in, a.target_stats_out = _ptr(draft_stats_in), _ptr(target_stats_out)
     a.target_stats_in = _ptr(target_stats_in)
+    a.top_k, a.top_p, a.out_keep_count = int(top_k), float(top_p), _ptr(out_keep_count)
     a.seed, a.level, a.seq_base = int(seed), int(level), int(seq_base)
     a.B, a.gamma, a.V = int(B), int(gamma), int(V)
     a.temperature, a.entropy_threshold = float(temperature), float(entropy_threshold)

@@ -22,16 +22,37 @@ struct AcceptCtx {
     double* target_stats_out;          // [B, gamma+1, 2] or null
     int32_t* out_accept_len; int32_t* out_next_token;
     float* out_entropy; int64_t entropy_ld;
+    const RowFilter* filters = nullptr; // top-k / top-p keep sets and statistics, slots as the partials; or null
+    int32_t B = 0;
 };
+
+// Membership of token i with logit x in a filtered row's keep set.
+__device__ __forceinline__ bool filter_keeps(float x, int32_t i, float theta, int32_t idx_cut)
+{
+    return x > theta || (x == theta && i <= idx_cut);
+}
 
 // Called by all 64 lanes of one wavefront.  sd / sp: statistics of draft row j (valid for j < len) and
 // target row j (valid for j <= len).  Writes accept_len, the entropies, the optional target statistics
 // and, for greedy rows, the next token; the lane at the stop row fills *si_out.
 template <bool BF16>
 __device__ __forceinline__ void accept_wave(const AcceptCtx& c, int b, int j, int len, float Tb,
-                                            const RowStat& sd, const RowStat& sp, SeqInfo* si_out)
+                                            const RowStat& sd_in, const RowStat& sp_in, SeqInfo* si_out)
 {
     const int g = c.gamma;
+    RowStat sd = sd_in, sp = sp_in;
+    float thD = -INFINITY, thP = -INFINITY;
+    int32_t cutD = 0x7fffffff, cutP = 0x7fffffff;
+    if (c.filters) {                                    // filtered distributions: their own statistics and keep sets
+        if (j < len) {
+            const RowFilter f = c.filters[(int64_t)b * g + j];
+            sd.lse = f.lse; sd.H = f.H; thD = f.theta; cutD = f.idx_cut;
+        }
+        if (j <= len) {
+            const RowFilter f = c.filters[(int64_t)c.B * g + (int64_t)b * (g + 1) + j];
+            sp.lse = f.lse; sp.H = f.H; thP = f.theta; cutP = f.idx_cut;
+        }
+    }
     const bool greedy = !(Tb > 0.f);
     const double invT = greedy ? 1.0 : 1.0 / (double)Tb;
     const double tau = (double)c.tau;
@@ -56,10 +77,14 @@ __device__ __forceinline__ void accept_wave(const AcceptCtx& c, int b, int j, in
         } else {
             double p_x = 0.0, q_x = 1.0;
             if (x >= 0 && x < c.V) {
-                const double zp = (double)load_logit<BF16>(c.target, ((int64_t)b * (g + 1) + j) * c.target_ld + x) * invT;
-                const double zq = (double)load_logit<BF16>(c.draft, ((int64_t)b * g + j) * c.draft_ld + x) * invT;
-                p_x = exp(zp - sp.lse);
-                q_x = exp(zq - sd.lse);
+                const float xp = load_logit<BF16>(c.target, ((int64_t)b * (g + 1) + j) * c.target_ld + x);
+                const float xq = load_logit<BF16>(c.draft, ((int64_t)b * g + j) * c.draft_ld + x);
+                p_x = exp((double)xp * invT - sp.lse);
+                q_x = exp((double)xq * invT - sd.lse);
+                if (c.filters) {
+                    if (!filter_keeps(xp, x, thP, cutP)) p_x = 0.0;
+                    if (!filter_keeps(xq, x, thD, cutD)) q_x = 0.0;
+                }
             }
             const Philox4 r = philox4x32_10((uint32_t)j, (uint32_t)seq, (uint32_t)(seq >> 32), c.level,
                                             (uint32_t)c.seed, (uint32_t)(c.seed >> 32));

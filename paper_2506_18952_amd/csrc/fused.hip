@@ -32,6 +32,7 @@ __device__ __forceinline__ AcceptCtx accept_ctx(const FusedParams& p)
     c.gamma = p.gamma; c.V = p.V; c.tau = p.tau; c.target_stats_out = p.target_stats_out;
     c.out_accept_len = p.out_accept_len; c.out_next_token = p.out_next_token;
     c.out_entropy = p.out_entropy; c.entropy_ld = p.entropy_ld;
+    c.filters = p.filters; c.B = p.B;
     return c;
 }
 
@@ -47,7 +48,7 @@ __device__ __forceinline__ void write_glue(const FusedParams& p, int b, int a, i
 
 // Accept stage (wavefront 0) and sampling (all wavefronts) of sequence b, given sh.stat[].
 // Called by every thread of the workgroup, after a barrier that made sh.stat visible.
-template <bool BF16, int NW>
+template <bool BF16, int NW, bool FILT = false>
 __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& sh, int b, int len, float Tb)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -82,13 +83,13 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
     }
 
     RowPair rp;
-    make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0);
+    make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0, FILT ? p.filters : nullptr, p.B);
     int32_t tok = -1;
     for (int attempt = 0; attempt < 2; ++attempt) {
         // tile weights of the stop row: two tiles per round trip and wavefront
         for (int t = wave; t < p.ntiles; t += 2 * NW) {
             double w0 = 0.0, w1 = 0.0;
-            if (rp.ok) tile_weight2<BF16>(rp, t, t + NW, lane, w0, w1);
+            if (rp.ok) tile_weight2<BF16, FILT>(rp, t, t + NW, lane, w0, w1);
             if (lane == 0) {
                 sh.tiles[t] = w0;
                 if (t + NW < p.ntiles) sh.tiles[t + NW] = w1;
@@ -96,13 +97,13 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
         }
         __syncthreads();
         if (wave == 0) {
-            const int32_t tk = rp.ok ? select_token<BF16, true>(rp, sh.tiles, p.ntiles, si.u, lane) : -1;
+            const int32_t tk = rp.ok ? select_token<BF16, true, FILT>(rp, sh.tiles, p.ntiles, si.u, lane) : -1;
             if (lane == 0) sh.tok = tk;
         }
         __syncthreads();
         tok = sh.tok;
         if (tok != -2) break;                                    // -2: no residual mass, sample p itself
-        make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1);
+        make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1, FILT ? p.filters : nullptr, p.B);
     }
     if (tid == 0) p.out_next_token[b] = tok < 0 ? -1 : tok;
     write_glue(p, b, si.row, tok < 0 ? -1 : tok);
@@ -167,7 +168,7 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedParams p)
 }
 
 // Accept + sampling of one sequence from the row partials of the split-row kernel.
-template <bool BF16, int NW>
+template <bool BF16, int NW, bool FILT = false>
 __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Partial* __restrict__ partials, int nparts)
 {
     __shared__ SeqShared sh;
@@ -178,8 +179,8 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
     len = len < 0 ? 0 : (len > g ? g : len);
     const float Tb = p.row_temperature ? p.row_temperature[b] : p.temperature;
     const int first_row = p.draft_stats_in ? g : 0;
-    const int end_row = p.target_stats_in ? g : 2 * g + 1;      // statistics the caller supplies are not merged here
-    for (int r = first_row + wave; r < end_row; r += NW) {      // one wavefront per row, one lane per partial
+    const int end_row = (p.target_stats_in || FILT) ? g : 2 * g + 1;   // supplied or filtered statistics are not merged here
+    for (int r = (FILT ? g : first_row) + wave; r < end_row; r += NW) {   // one wavefront per row, one lane per partial
         const bool is_draft = r < g;
         const int j = is_draft ? r : r - g;
         if (is_draft ? (j >= len) : (j > len)) continue;
@@ -188,7 +189,7 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
         if (lane == 0) sh.stat[r] = s;
     }
     __syncthreads();
-    sequence_tail<BF16, NW>(p, sh, b, len, Tb);
+    sequence_tail<BF16, NW, FILT>(p, sh, b, len, Tb);
 }
 
 bool fused_supported(int32_t gamma, int32_t V, int dtype)
@@ -221,6 +222,11 @@ hipError_t launch_tail(const FusedParams& p, const Partial* partials, int nparts
     if (nparts > 64) return hipErrorInvalidValue;
     dim3 grid((unsigned)p.B);
     const int nw = t.fused_waves ? t.fused_waves : 16;
+    if (p.filters) {                                             // filtered distributions: 8 wavefronts, more registers
+        if (p.dtype == HOLA_DTYPE_BF16) hipLaunchKernelGGL((tail_kernel<true, 8, true>), grid, dim3(512), 0, s, p, partials, nparts);
+        else hipLaunchKernelGGL((tail_kernel<false, 8, true>), grid, dim3(512), 0, s, p, partials, nparts);
+        return hipGetLastError();
+    }
     if (p.dtype == HOLA_DTYPE_BF16) {
         if (nw == 4) hipLaunchKernelGGL((tail_kernel<true, 4>), grid, dim3(256), 0, s, p, partials, nparts);
         else if (nw == 8) hipLaunchKernelGGL((tail_kernel<true, 8>), grid, dim3(512), 0, s, p, partials, nparts);

@@ -129,6 +129,7 @@ static Workspace carve(void* base, int32_t B, int32_t gamma, int32_t V)
     w.argmaxP = (int32_t*)(p + off);  off = align_up(off + (size_t)B * (gamma + 1) * sizeof(int32_t));
     w.seq = (SeqInfo*)(p + off);      off = align_up(off + (size_t)B * sizeof(SeqInfo));
     w.tiles = (double*)(p + off);     off = align_up(off + (size_t)B * ntiles * sizeof(double));
+    w.filters = (RowFilter*)(p + off); off = align_up(off + rows * sizeof(RowFilter));
     w.bytes = off;
     return w;
 }
@@ -136,6 +137,11 @@ static Workspace carve(void* base, int32_t B, int32_t gamma, int32_t V)
 static bool shape_ok(int32_t B, int32_t gamma, int32_t V)
 {
     return B >= 0 && gamma >= 1 && gamma <= HOLA_MAX_GAMMA && V >= 1;
+}
+
+static bool filters_on(const hola_verify_args& a)
+{
+    return (a.top_k != 0 && a.top_k < a.V) || (a.top_p != 0.f && !(a.top_p >= 1.f));
 }
 
 static hola_status check_args(const hola_verify_args& a, bool literal = false)
@@ -151,6 +157,14 @@ static hola_status check_args(const hola_verify_args& a, bool literal = false)
     if (a.entropy_ld && a.entropy_ld < a.gamma) return HOLA_ERR_INVALID_ARG;
     if (!(a.temperature >= 0.f) || std::isinf(a.temperature)) return HOLA_ERR_INVALID_ARG;   // rejects NaN too
     if (std::isnan(a.entropy_threshold)) return HOLA_ERR_INVALID_ARG;
+    // Filtered distributions: stochastic rows with one temperature; their statistics are not interchangeable
+    // with unfiltered ones, so none are taken or handed on.
+    if (filters_on(a)) {
+        if (a.top_k < 0 || !(a.top_p >= 0.f)) return HOLA_ERR_INVALID_ARG;
+        if (literal || a.row_temperature || !(a.temperature > 0.f) || a.draft_stats_in || a.target_stats_in ||
+            a.target_stats_out || a.V >= (1 << 22) || !fused_supported(a.gamma, a.V, a.dtype))
+            return HOLA_ERR_UNSUPPORTED;
+    }
     // Supplied target statistics carry no argmax, which greedy rows need.
     if (a.target_stats_in && (a.row_temperature || !(a.temperature > 0.f))) return HOLA_ERR_UNSUPPORTED;
     if (!a.workspace || ((uintptr_t)a.workspace & 255)) return HOLA_ERR_WORKSPACE;
@@ -196,6 +210,8 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     fp.out_accept_len = a.out_accept_len; fp.out_next_token = a.out_next_token;
     fp.out_entropy = a.out_entropy; fp.entropy_ld = a.entropy_ld;
 
+    const bool filtered = filters_on(a);
+    if (filtered) tune.path = 1;                                  // statistics, keep sets, then the tail kernel
     // Path 2: one fused launch per level (one workgroup per sequence streams its own rows).
     const bool want_fused = tune.path == 2;
     if (want_fused && per_seq_ok) {
@@ -213,6 +229,15 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     hipError_t e = hipSuccess;
     if (rows > 0) { StageTimer t(0, s); e = launch_row_stats(rs, a.dtype, tune, s); }   // nothing to stream when both are supplied
     if (e != hipSuccess) return hip_fail(e, "row statistics launch");
+
+    if (filtered) {
+        StageTimer t(2, s);
+        e = launch_filter(a.target_logits, a.draft_logits, a.dtype, tld, dld, a.draft_len, a.temperature, a.B, a.gamma, a.V,
+                          a.top_k, (a.top_p > 0.f && a.top_p < 1.f) ? a.top_p : 1.f, w.partials, nsplit * kWaves, w.filters,
+                          a.out_keep_count, s);
+        if (e != hipSuccess) return hip_fail(e, "filter launch");
+        fp.filters = w.filters;
+    }
 
     // Paths 0/1: the split-row pass spreads the rows over the chip, then one per-sequence tail kernel does
     // accept + sampling.  Path 3 keeps accept, tile sums and select as three kernels of their own.

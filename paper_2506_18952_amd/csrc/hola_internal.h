@@ -28,6 +28,16 @@ struct SeqInfo {
     int32_t greedy_tok;                // next token of a greedy row (mode 2)
 };
 
+// Keep set and statistics of one top-k / top-p filtered row: token i with logit x is kept iff x > theta, or
+// x == theta and i <= idx_cut.  lse and H (nats) are those of the kept, renormalised tokens.
+struct RowFilter {
+    double lse, H;
+    float theta;
+    int32_t idx_cut;
+    int32_t n_keep;                    // kept tokens (-1: every finite logit)
+    int32_t pad;
+};
+
 struct Shape {
     int32_t B, gamma, V, dtype;
     int64_t target_ld, draft_ld;
@@ -44,6 +54,7 @@ struct Workspace {
     int32_t* argmaxP;                  // [B, gamma+1]
     SeqInfo* seq;                      // [B]
     double* tiles;                     // [B, ntiles]
+    RowFilter* filters;                // [(B*gamma) + B*(gamma+1)], filtered calls only
     size_t bytes;
 };
 
@@ -107,6 +118,7 @@ struct FusedParams {
     // followed by the next token, -1 up to glue_ld; glue_len[b] = accept length + 1
     int32_t* glue_tok; int32_t* glue_len; int64_t glue_ld;
     int32_t glue_keep_next;            // 1: append the next token; 0: the kept tokens only
+    const RowFilter* filters;          // top-k / top-p keep sets (slots as the partials), or null
 };
 
 hipError_t launch_fused(const FusedParams& p, const Tuning& t, hipStream_t s);
@@ -116,6 +128,10 @@ bool literal_supported(int32_t gamma, int32_t V, int dtype);
 hipError_t launch_literal(const FusedParams& p, const Partial* partials, int nparts, int32_t* out_tokens,
                           int32_t* out_calls, hipStream_t s);
 hipError_t launch_row_stats(const RowStatsParams& p, int dtype, const Tuning& t, hipStream_t s);
+hipError_t launch_filter(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
+                         const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
+                         int32_t top_k, float top_p, const Partial* partials, int nparts, RowFilter* filters,
+                         int32_t* out_keep_count, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
 hipError_t launch_merge_tile_stats(const double* ts, int32_t R, int32_t nt, double* out, hipStream_t s);
 hipError_t launch_finalize_rows(const Partial* partials, int nparts, int32_t R, double* out, hipStream_t s);

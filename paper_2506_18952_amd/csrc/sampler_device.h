@@ -28,6 +28,7 @@ struct RowPair {
     double scale;                       // 2^rP
     int32_t bonus;                      // weights are p itself
     int32_t ok;                         // the target row has a finite normaliser
+    float thP, thQ; int32_t cutP, cutQ; // keep sets of filtered rows (x > th, or x == th and index <= cut)
 };
 
 // Reference for rows whose log2-normaliser is L: bf16 an integer near -L, fp32 a logit near L / c.
@@ -40,7 +41,8 @@ __device__ __forceinline__ float ref_for_norm(double L, const ExpScale& sc)
 template <bool BF16>
 __device__ __forceinline__ void make_row_pair(RowPair& rp, const void* target, const void* draft, int64_t target_ld,
                                               int64_t draft_ld, int32_t gamma, int32_t V, float Tb, int b,
-                                              const SeqInfo& si, int force_bonus)
+                                              const SeqInfo& si, int force_bonus, const RowFilter* filters = nullptr,
+                                              int32_t B = 0)
 {
     constexpr int N = BF16 ? 8 : 4;
     constexpr int ES = BF16 ? 2 : 4;
@@ -59,6 +61,15 @@ __device__ __forceinline__ void make_row_pair(RowPair& rp, const void* target, c
     const double rP = -LP - ref_offset<BF16>(rp.refP, rp.sc);          // p_i = 2^(y_i + rP)
     rp.scale = exp2(rP);
     rp.Dv = nullptr; rp.D = nullptr; rp.refQ = 0.f; rp.k_hi = 0.f; rp.k_lo = 0.f;
+    rp.thP = rp.thQ = -INFINITY; rp.cutP = rp.cutQ = 0x7fffffff;
+    if (filters) {
+        const RowFilter f = filters[(int64_t)B * g + (int64_t)b * (g + 1) + si.row];
+        rp.thP = f.theta; rp.cutP = f.idx_cut;
+        if (!rp.bonus) {
+            const RowFilter fq = filters[(int64_t)b * g + (si.row < g ? si.row : g - 1)];
+            rp.thQ = fq.theta; rp.cutQ = fq.idx_cut;
+        }
+    }
     if (!rp.bonus) {
         const int jd = si.row < g ? si.row : g - 1;
         const char* rowD = (const char*)draft + ((int64_t)b * g + jd) * draft_ld * ES;
@@ -87,7 +98,7 @@ __device__ __forceinline__ void load_chunk_pair(const RowPair& rp, int64_t c, ui
 
 // Weights of the N elements of chunk c (0 for elements outside the row) and their fp32 sum in index
 // order, from chunks already loaded.
-template <bool BF16>
+template <bool BF16, bool FILT = false>
 __device__ __forceinline__ float chunk_weights_loaded(const RowPair& rp, int64_t c, const uint4& vp, const uint4& vd, float* w)
 {
     constexpr int N = BF16 ? 8 : 4;
@@ -105,7 +116,8 @@ __device__ __forceinline__ float chunk_weights_loaded(const RowPair& rp, int64_t
         const int32_t e = e0 + k;
         const bool valid = !edge || (e >= 0 && e < rp.V);
         const float xp = chunk_elem<BF16>(vp, k);
-        const float ep = fast_exp2(exp_arg<BF16>(xp, rp.refP, rp.sc));
+        float ep = fast_exp2(exp_arg<BF16>(xp, rp.refP, rp.sc));
+        if (FILT && !(xp > rp.thP || (xp == rp.thP && e <= rp.cutP))) ep = 0.f;
         float wk;
         if (rp.bonus) {
             wk = ep;
@@ -113,7 +125,8 @@ __device__ __forceinline__ float chunk_weights_loaded(const RowPair& rp, int64_t
             float xd;
             if (dvec) xd = chunk_elem<BF16>(vd, k);
             else xd = valid ? load_logit<BF16>(rp.D, e) : 0.f;
-            const float eq = fast_exp2(exp_arg<BF16>(xd, rp.refQ, rp.sc));
+            float eq = fast_exp2(exp_arg<BF16>(xd, rp.refQ, rp.sc));
+            if (FILT && !(xd > rp.thQ || (xd == rp.thQ && e <= rp.cutQ))) eq = 0.f;
             wk = fmaxf(0.f, __builtin_fmaf(-rp.k_lo, eq, __builtin_fmaf(-rp.k_hi, eq, ep)));
         }
         if (!valid || !(wk == wk)) wk = 0.f;
@@ -123,12 +136,12 @@ __device__ __forceinline__ float chunk_weights_loaded(const RowPair& rp, int64_t
     return sum;
 }
 
-template <bool BF16>
+template <bool BF16, bool FILT = false>
 __device__ __forceinline__ float chunk_weights(const RowPair& rp, int64_t c, float* w)
 {
     uint4 vp, vd;
     load_chunk_pair(rp, c, vp, vd);
-    return chunk_weights_loaded<BF16>(rp, c, vp, vd, w);
+    return chunk_weights_loaded<BF16, FILT>(rp, c, vp, vd, w);
 }
 
 // Weight of one tile: lanes take chunks tile*256 + g*64 + lane, g = 0..3.  Every lane returns the sum.
@@ -149,7 +162,7 @@ __device__ __forceinline__ double tile_weight(const RowPair& rp, int64_t tile, i
 }
 
 // Two tiles with all their loads in flight together (twice the bytes per round trip).
-template <bool BF16>
+template <bool BF16, bool FILT = false>
 __device__ __forceinline__ void tile_weight2(const RowPair& rp, int64_t t0, int64_t t1, int lane, double& w0, double& w1)
 {
     constexpr int N = BF16 ? 8 : 4;
@@ -163,8 +176,8 @@ __device__ __forceinline__ void tile_weight2(const RowPair& rp, int64_t t0, int6
 #pragma unroll
     for (int g = 0; g < kTileChunks; ++g) {
         float w[N];
-        a0 += (double)chunk_weights_loaded<BF16>(rp, t0 * (64 * kTileChunks) + g * 64 + lane, vp[0][g], vd[0][g], w);
-        a1 += (double)chunk_weights_loaded<BF16>(rp, t1 * (64 * kTileChunks) + g * 64 + lane, vp[1][g], vd[1][g], w);
+        a0 += (double)chunk_weights_loaded<BF16, FILT>(rp, t0 * (64 * kTileChunks) + g * 64 + lane, vp[0][g], vd[0][g], w);
+        a1 += (double)chunk_weights_loaded<BF16, FILT>(rp, t1 * (64 * kTileChunks) + g * 64 + lane, vp[1][g], vd[1][g], w);
     }
     w0 = wave_sum(a0) * rp.scale;
     w1 = wave_sum(a1) * rp.scale;
@@ -183,7 +196,7 @@ __device__ __forceinline__ double read_tile(const double* t)
 // One wavefront selects the token from the tile weights: returns the token (all lanes), -1 if the
 // weights carry no mass, or -2 if the caller should recompute the tiles as bonus weights (residual with
 // Z == 0: p == q everywhere, or a broken draft row) and call again.
-template <bool BF16, bool LDS>
+template <bool BF16, bool LDS, bool FILT = false>
 __device__ __forceinline__ int32_t select_token(const RowPair& rp, const double* tiles, int ntiles, float u, int lane)
 {
     constexpr int N = BF16 ? 8 : 4;
@@ -226,7 +239,7 @@ __device__ __forceinline__ int32_t select_token(const RowPair& rp, const double*
     float cs[kTileChunks];
 #pragma unroll
     for (int g = 0; g < kTileChunks; ++g)
-        cs[g] = chunk_weights<BF16>(rp, (int64_t)tile * (64 * kTileChunks) + g * 64 + lane, w[g]);
+        cs[g] = chunk_weights<BF16, FILT>(rp, (int64_t)tile * (64 * kTileChunks) + g * 64 + lane, w[g]);
     double base = before;
     int found_g = -1, found_lane = -1;
     double found_excl = 0.0;

@@ -370,6 +370,7 @@ __device__ __forceinline__ RowStat merge_partials(const Partial* __restrict__ ps
     const double lnS = log(S);
     r.lse = lnS - bmin * kLn2;
     r.H = lnS - kLn2 * (T / S);
+    if (r.H < 0.0) r.H = 0.0;                           // rounding on a one-hot row; keeps "tau <= 0 never gates" exact
     return r;
 }
 
@@ -411,6 +412,7 @@ __device__ __forceinline__ RowStat merge_partials_wave(const Partial* __restrict
     const double lnS = log(S);
     r.lse = lnS - bmin * kLn2;
     r.H = lnS - kLn2 * (T / S);
+    if (r.H < 0.0) r.H = 0.0;                           // rounding on a one-hot row; keeps "tau <= 0 never gates" exact
     return r;
 }
 

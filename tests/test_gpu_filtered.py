@@ -1,0 +1,220 @@
+"""GPU parity of the verify level on top-k / top-p filtered distributions against the oracle's filtered step.
+
+Bar: accept lengths and next tokens bit-exact for every sequence none of whose deciding comparisons the oracle
+lists as near-threshold (margin < 1e-6: a gate, a ratio test, the sampling uniform against its CDF interval, or a
+nucleus cut of a row the sequence uses); listed sequences are counted and must stay rare.  Entropies of the
+filtered draft rows to the same tolerance as the unfiltered ones.  Top-k alone has no floating-point decision:
+its keep sets are exact, ties included."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import hola_oracle as orc
+from paper_2506_18952_amd import binding as hb, workloads as wl
+from parity import DEV, ENTROPY_ABS_FLOOR, MARGIN, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def run_filtered(target, draft, tokens, seed, T, tau, top_k, top_p, draft_len=None, target_ld=0, draft_ld=0,
+                 dev=None):
+    P, D = dev if dev is not None else (to_dev(target), to_dev(draft))
+    B, g = tokens.shape
+    V = target.shape[-1]
+    tok = to_dev(np.ascontiguousarray(tokens, np.int32))
+    acc = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    nxt = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    ent = torch.full((B, g), -7.0, dtype=torch.float32, device=DEV)
+    keep = torch.full((B, 2 * g + 1), -9, dtype=torch.int32, device=DEV)
+    ws = hb.alloc_workspace(hb.hola_workspace_bytes(B, g, V), DEV)
+    dl = None if draft_len is None else to_dev(np.ascontiguousarray(draft_len, np.int32))
+    hb.hola_verify_ex(target_logits=P, draft_logits=D, draft_tokens=tok, seed=seed, B=B, gamma=g, V=V, temperature=T,
+                      entropy_threshold=tau, out_accept_len=acc, out_next_token=nxt, out_entropy=ent, workspace=ws,
+                      draft_len=dl, top_k=top_k, top_p=top_p, target_ld=target_ld, draft_ld=draft_ld,
+                      out_keep_count=keep)
+    torch.cuda.synchronize()
+    return acc.cpu().numpy(), nxt.cpu().numpy(), ent.cpu().numpy(), keep.cpu().numpy()
+
+
+CUT_TOL = 1e-6      # a nucleus cut may differ from the oracle's only where the cumulative mass is this close to the target
+
+
+def _cut_is_within_tolerance(row, T, top_k, top_p, m_gpu):
+    """The prefix length m_gpu satisfies the nucleus rule up to CUT_TOL of the top-k mass."""
+    z = wl.as_f32(row).astype(np.float64) / T
+    order = np.argsort(-z, kind="stable")
+    p = np.exp(z - np.logaddexp.reduce(z[np.isfinite(z)]))
+    mk = top_k if 0 < top_k < z.shape[0] else z.shape[0]
+    mk = min(mk, int(np.isfinite(z).sum()))
+    c = np.cumsum(p[order[:mk]])
+    target = top_p * c[-1]
+    if not (1 <= m_gpu <= mk):
+        return False
+    reaches = c[m_gpu - 1] >= target - CUT_TOL * c[-1]
+    shortest = m_gpu == 1 or c[m_gpu - 2] < target + CUT_TOL * c[-1]
+    return bool(reaches and shortest)
+
+
+def compare_filtered(target, draft, tokens, seed, T, tau, top_k, top_p, got, draft_len=None, max_listed=None):
+    """Keep counts: equal to the oracle's (top-k alone: always; nucleus: unless the rule holds for the GPU's count
+    within CUT_TOL).  Then the oracle follows the GPU's cuts and every decision must match outside the listed
+    near-threshold comparisons (gate, ratio, sampling uniform)."""
+    acc, nxt, ent, keep = got
+    T = float(np.float32(T))
+    tp = top_p if 0.0 < top_p < 1.0 else 1.0
+    ref0 = orc.verify_filtered(target, draft, tokens, seed, T, tau, top_k=top_k, top_p=tp, draft_len=draft_len)
+    B, g = tokens.shape
+    lens = np.full(B, g, np.int32) if draft_len is None else np.asarray(draft_len, np.int32)
+    moved = 0
+    filters_on = (0 < top_k < target.shape[-1]) or tp < 1.0    # otherwise the call takes the unfiltered path
+    for b in range(B if filters_on else 0):
+        L = int(lens[b])
+        for k in range(2 * g + 1):
+            is_d = k < g
+            j = k if is_d else k - g
+            used = (j < L) if is_d else (j <= L)
+            if not used:
+                assert keep[b, k] == -1, (b, k, keep[b, k])
+                continue
+            if keep[b, k] != ref0.keep_count[b, k]:
+                assert tp < 1.0, f"top-k keep count differs at seq {b} row {k}: {keep[b, k]} vs {ref0.keep_count[b, k]}"
+                row = draft[b, j] if is_d else target[b, j]
+                assert _cut_is_within_tolerance(row, T, top_k, tp, int(keep[b, k])), (b, k, keep[b, k], ref0.keep_count[b, k])
+                moved += 1
+    ref = ref0 if moved == 0 else orc.verify_filtered(target, draft, tokens, seed, T, tau, top_k=top_k, top_p=tp,
+                                                      draft_len=draft_len, force_keep_count=keep)
+    rtol = 1e-5 if np.asarray(target).dtype == np.float32 else 2e-3
+    gm = np.where(np.isnan(ref.gate_margin), np.inf, ref.gate_margin)
+    rm = np.where(np.isnan(ref.ratio_margin), np.inf, ref.ratio_margin)
+    sm = np.where(np.isnan(ref.sample_margin), np.inf, ref.sample_margin)
+    listed, max_dh = 0, 0.0
+    for b in range(B):
+        L = int(lens[b])
+        assert np.all(ent[b, L:] == -1.0)
+        for j in range(L):
+            h, hg = ref.entropy64[b, j], float(ent[b, j])
+            err = abs(hg - h)
+            max_dh = max(max_dh, err)
+            assert err <= max(rtol * abs(h), ENTROPY_ABS_FLOOR) and err < 1e-6, (b, j, hg, h)
+        margins = [sm[b]] + [gm[b, j] for j in range(L)] + [rm[b, j] for j in range(L)]
+        if min(margins) < MARGIN:
+            listed += 1
+            assert 0 <= acc[b] <= L
+            continue
+        assert acc[b] == ref.accept_len[b], (b, acc[b], ref.accept_len[b])
+        assert nxt[b] == ref.next_token[b], (b, nxt[b], ref.next_token[b], ref.sample_margin[b])
+    if max_listed is None:
+        max_listed = max(2, B // 20)
+    assert listed <= max_listed, f"{listed} of {B} sequences near a threshold"
+    return listed, max_dh, ref
+
+
+FILTERS = [(50, 0.0), (0, 0.9), (40, 0.8), (1, 0.0), (0, 0.05), (0, 0.999), (1000, 0.97)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("top_k,top_p", FILTERS)
+def test_small_cases(dtype, top_k, top_p):
+    w = wl.small_case(12, 4, 3001, dtype=dtype, temperature=0.8, case_id=300 + top_k % 7)
+    for tau in (-1.0, 0.3 * math.log(w.V)):
+        got = run_filtered(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, top_k, top_p)
+        listed, dh, ref = compare_filtered(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, top_k, top_p, got)
+        print(f"[parity] filtered {w.name} k={top_k} p={top_p} tau={tau:.2f}: listed={listed} max|dH|={dh:.2e} "
+              f"accept hist {np.bincount(got[0], minlength=w.gamma + 1).tolist()}", flush=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("B,g,V", [(3, 1, 7), (2, 2, 8), (5, 3, 1001), (4, 4, 2049), (3, 2, 70001), (2, 1, 1)])
+def test_ragged_shapes(B, g, V, dtype):
+    w = wl.small_case(B, g, V, dtype=dtype, temperature=1.1, case_id=400 + V % 31)
+    dl = np.array([(b * 2 + 1) % (g + 1) for b in range(B)], np.int32)
+    for top_k, top_p in ((3, 0.0), (0, 0.7), (5, 0.9)):
+        got = run_filtered(w.target, w.draft, w.tokens, w.seed, w.temperature, -1.0, top_k, top_p, draft_len=dl)
+        compare_filtered(w.target, w.draft, w.tokens, w.seed, w.temperature, -1.0, top_k, top_p, got, draft_len=dl,
+                         max_listed=B)
+
+
+def test_runs_of_equal_logits_are_cut_by_index():
+    """Rows made of few distinct values: the cut falls inside long runs of ties, kept by ascending index."""
+    rng = np.random.default_rng(12)
+    B, g, V = 6, 3, 5000
+    P = rng.integers(-2, 3, (B, g + 1, V)).astype(np.float32)
+    D = rng.integers(-2, 3, (B, g, V)).astype(np.float32)
+    P[0] = 0.0; D[0] = 0.0                                      # uniform rows: every logit ties
+    tok = rng.integers(0, V, (B, g)).astype(np.int32)
+    tok[0] = [3, 6, 4999]
+    for top_k, top_p in ((7, 0.0), (700, 0.0), (0, 0.5), (2500, 0.3), (4999, 0.0)):
+        got = run_filtered(P, D, tok, 5, 1.0, -1.0, top_k, top_p)
+        listed, dh, ref = compare_filtered(P, D, tok, 5, 1.0, -1.0, top_k, top_p, got, max_listed=B)
+        if top_k == 7:
+            # sequence 0: q~ = p~ = uniform over tokens 0..6: tokens 3 and 6 accepted, 4999 lies outside both keep
+            # sets (0 < 0 fails) and the residual is empty, so the next token comes from p~ itself
+            assert got[0][0] == 2 and 0 <= got[1][0] < 7
+    # the bf16 version of the same rows
+    Pb, Db = wl.f32_to_bf16_bits(P), wl.f32_to_bf16_bits(D)
+    got = run_filtered(Pb, Db, tok, 5, 1.0, -1.0, 700, 0.6)
+    compare_filtered(Pb, Db, tok, 5, 1.0, -1.0, 700, 0.6, got, max_listed=B)
+
+
+def test_masked_and_strided_rows():
+    rng = np.random.default_rng(2)
+    B, g, V, ld = 4, 2, 1000, 1064
+    Pbuf = rng.normal(0, 3, (B, g + 1, ld)).astype(np.float32)
+    Dbuf = (Pbuf[:, :g] + rng.normal(0, 1, (B, g, ld))).astype(np.float32)
+    Pbuf[1, :, 10:900] = -np.inf                                # fewer finite logits than top_k
+    Dbuf[1, :, 10:900] = -np.inf
+    P, D = np.ascontiguousarray(Pbuf[..., :V]), np.ascontiguousarray(Dbuf[..., :V])
+    tok = rng.integers(0, V, (B, g)).astype(np.int32)
+    for top_k, top_p in ((200, 0.0), (0, 0.9), (150, 0.95)):
+        got = run_filtered(P, D, tok, 9, 0.9, -1.0, top_k, top_p, target_ld=ld, draft_ld=ld,
+                           dev=(to_dev(Pbuf), to_dev(Dbuf)))
+        compare_filtered(P, D, tok, 9, 0.9, -1.0, top_k, top_p, got, max_listed=B)
+
+
+def test_filters_off_values_take_the_unfiltered_path():
+    w = wl.small_case(8, 3, 2000, dtype="bf16", temperature=0.8, case_id=9)
+    base = run_filtered(w.target, w.draft, w.tokens, w.seed, 0.8, 2.0, 0, 0.0)
+    for top_k, top_p in ((w.V, 0.0), (0, 1.0), (w.V + 5, 1.5)):
+        got = run_filtered(w.target, w.draft, w.tokens, w.seed, 0.8, 2.0, top_k, top_p)
+        assert all(np.array_equal(a, b) for a, b in zip(base[:3], got[:3]))
+
+
+def test_config2_and_headline_vocabulary():
+    w = wl.config2()
+    for top_k, top_p in ((50, 0.0), (0, 0.9), (100, 0.95)):
+        got = run_filtered(w.target, w.draft, w.tokens, w.seed, w.temperature, -1.0, top_k, top_p)
+        listed, dh, _ = compare_filtered(w.target, w.draft, w.tokens, w.seed, w.temperature, -1.0, top_k, top_p, got)
+        print(f"[parity] filtered cfg2 k={top_k} p={top_p}: listed={listed} max|dH|={dh:.2e}", flush=True)
+    w = wl.config3(B=12)
+    for top_k, top_p in ((50, 0.95), (0, 0.9)):
+        got = run_filtered(w.target, w.draft, w.tokens, w.seed, w.temperature, w.taus[0], top_k, top_p)
+        listed, dh, _ = compare_filtered(w.target, w.draft, w.tokens, w.seed, w.temperature, w.taus[0], top_k, top_p, got)
+        print(f"[parity] filtered cfg3(B=12) k={top_k} p={top_p}: listed={listed} max|dH|={dh:.2e}", flush=True)
+
+
+def test_deterministic_across_calls():
+    w = wl.small_case(16, 4, 20000, dtype="bf16", temperature=0.7, case_id=21)
+    a = run_filtered(w.target, w.draft, w.tokens, w.seed, 0.7, 1.0, 64, 0.9)
+    for _ in range(3):
+        b = run_filtered(w.target, w.draft, w.tokens, w.seed, 0.7, 1.0, 64, 0.9)
+        assert all(np.array_equal(x, y) for x, y in zip(a, b))
+
+
+def test_unsupported_combinations():
+    w = wl.small_case(2, 2, 100, dtype="f32", temperature=1.0, case_id=5)
+    P, D, tok = to_dev(w.target), to_dev(w.draft), to_dev(w.tokens)
+    acc = torch.zeros(2, dtype=torch.int32, device=DEV); nxt = torch.zeros(2, dtype=torch.int32, device=DEV)
+    ws = hb.alloc_workspace(hb.hola_workspace_bytes(2, 2, 100), DEV)
+    kw = dict(target_logits=P, draft_logits=D, draft_tokens=tok, seed=1, B=2, gamma=2, V=100, entropy_threshold=1.0,
+              out_accept_len=acc, out_next_token=nxt, workspace=ws)
+    with pytest.raises(hb.HolaError) as e:
+        hb.hola_verify_ex(temperature=0.0, top_k=5, **kw)
+    assert e.value.status == hb.HOLA_ERR_UNSUPPORTED
+    with pytest.raises(hb.HolaError) as e:
+        hb.hola_verify_ex(temperature=1.0, top_k=5, row_temperature=torch.ones(2, device=DEV), **kw)
+    assert e.value.status == hb.HOLA_ERR_UNSUPPORTED
+    with pytest.raises(hb.HolaError) as e:
+        hb.hola_verify_ex(temperature=1.0, top_k=-1, top_p=0.5, **kw)
+    assert e.value.status == hb.HOLA_ERR_INVALID_ARG

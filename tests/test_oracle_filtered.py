@@ -173,3 +173,20 @@ def test_rejects_greedy_rows_and_bad_top_p():
         orc.verify_filtered(w.target, w.draft, w.tokens, 1, 0.0, 1.0, top_k=5)
     with pytest.raises(ValueError):
         orc.verify_filtered(w.target, w.draft, w.tokens, 1, 1.0, 1.0, top_p=0.0)
+
+
+def test_forced_keep_count_moves_only_the_cut():
+    w = wl.small_case(4, 3, 500, case_id=8)
+    base = orc.verify_filtered(w.target, w.draft, w.tokens, w.seed, 1.0, 0.0, top_k=0, top_p=0.8)
+    same = orc.verify_filtered(w.target, w.draft, w.tokens, w.seed, 1.0, 0.0, top_k=0, top_p=0.8,
+                               force_keep_count=base.keep_count)
+    assert np.array_equal(base.accept_len, same.accept_len) and np.array_equal(base.next_token, same.next_token)
+    np.testing.assert_array_equal(base.entropy64, same.entropy64)
+    fk = np.full_like(base.keep_count, -1)
+    fk[2, 0] = base.keep_count[2, 0] + 3                       # three more tokens in one draft row
+    moved = orc.verify_filtered(w.target, w.draft, w.tokens, w.seed, 1.0, 0.0, top_k=0, top_p=0.8, force_keep_count=fk)
+    assert moved.keep_count[2, 0] == base.keep_count[2, 0] + 3
+    assert moved.entropy64[2, 0] > base.entropy64[2, 0]
+    mask = np.ones_like(base.keep_count, bool); mask[2, 0] = False
+    assert np.array_equal(moved.keep_count[mask], base.keep_count[mask])
+    assert np.array_equal(np.delete(moved.entropy64.ravel(), 2 * 3), np.delete(base.entropy64.ravel(), 2 * 3))
