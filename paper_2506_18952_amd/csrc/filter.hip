@@ -25,9 +25,12 @@ constexpr int kFilterBins = 1 << kLevelBits;
 constexpr int kMassBits = 42;
 constexpr uint64_t kMassMask = (1ull << kMassBits) - 1;
 constexpr double kMassUnit = 1099511627776.0;                  // 2^40
+constexpr int kFilterCand = 4096;                               // candidate list in LDS (fast path)
 
 struct FilterShared {
     unsigned long long hist[kFilterBins];
+    unsigned long long cand[kFilterCand];                       // (key << 32) | index of the tokens near the top
+    unsigned int ncand;
     double red[2 * kFilterWaves];
     unsigned long long wsum[kFilterWaves];
     unsigned int wave_cnt[kFilterWaves];
@@ -59,12 +62,12 @@ struct FilterRow {
     ExpScale sc; float ref; double scale;                       // p_i = 2^(exp_arg(x_i)) * scale
 };
 
-// Calls f(x, index) for every element of the row with a logit above -inf, four chunks per lane in flight.
+// Calls f(x, index) for every element of the row with a logit above -inf, eight chunks per lane in flight.
 template <bool BF16, typename F>
 __device__ __forceinline__ void for_each_logit(const FilterRow& fr, int64_t c_lo, int64_t c_hi, F f)
 {
     constexpr int N = BF16 ? 8 : 4;
-    constexpr int U = 4;
+    constexpr int U = 8;
     for (int64_t c0 = c_lo + threadIdx.x; c0 < c_hi; c0 += (int64_t)U * kFilterThreads) {
         uint4 v[U];
 #pragma unroll
@@ -85,6 +88,45 @@ __device__ __forceinline__ void for_each_logit(const FilterRow& fr, int64_t c_lo
                 if (edge && (e < 0 || e >= fr.V)) continue;
                 const float x = chunk_elem<BF16>(v[u], k);
                 if (x > -INFINITY) f(x, e);
+            }
+        }
+    }
+}
+
+// One streaming pass that splits the row at a logit value: above(x, index) for x >= edge (edge is finite, so
+// -inf never qualifies), below(x) for the other logits above -inf when BELOW is set.  Non-temporal loads, eight
+// chunks per lane in flight; a chunk without a logit at or above the edge costs one compare per element.
+template <bool BF16, bool BELOW, typename FA, typename FB>
+__device__ __forceinline__ void split_pass(const FilterRow& fr, float edge, FA above, FB below)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    constexpr int U = 8;
+    for (int64_t c0 = threadIdx.x; c0 < fr.nchunks; c0 += (int64_t)U * kFilterThreads) {
+        uint4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t c = c0 + (int64_t)u * kFilterThreads;
+            v[u] = make_uint4(0, 0, 0, 0);
+            if (c < fr.nchunks) v[u] = load_stream(fr.rowv + c);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t c = c0 + (int64_t)u * kFilterThreads;
+            if (c >= fr.nchunks) continue;
+            const int32_t e0 = (int32_t)(c * N) - fr.head;
+            const bool edge_chunk = (c == 0) || (c == fr.nchunks - 1);
+            float x[N];
+            bool any = false;
+#pragma unroll
+            for (int k = 0; k < N; ++k) { x[k] = chunk_elem<BF16>(v[u], k); any = any || (x[k] >= edge); }
+            if (any || BELOW) {
+#pragma unroll
+                for (int k = 0; k < N; ++k) {
+                    const int32_t e = e0 + k;
+                    if (edge_chunk && (e < 0 || e >= fr.V)) continue;
+                    if (x[k] >= edge) above(x[k], e);
+                    else if (BELOW && x[k] > -INFINITY) below(x[k]);
+                }
             }
         }
     }
@@ -144,10 +186,14 @@ struct Cut {
 };
 
 // Radix select: by count (the need-th largest element) or by mass (the element at which the cumulative mass,
-// largest first, reaches need).  Every thread returns the same Cut.
-template <bool BF16>
-__device__ __forceinline__ Cut radix_select(FilterShared& sh, const FilterRow& fr, bool by_mass, uint64_t need)
+// largest first, reaches need; with frac > 0 the need is frac times the mass of the whole row, which the first
+// level's histogram gives, and is returned in *need_out).  MASS = false leaves the masses out of the
+// histograms (count search only).  Every thread returns the same Cut.
+template <bool BF16, bool MASS>
+__device__ __forceinline__ Cut radix_select(FilterShared& sh, const FilterRow& fr, bool by_mass, uint64_t need,
+                                            double frac = 0.0, uint64_t* need_out = nullptr, int64_t c_end = -1)
 {
+    const int64_t c_hi = c_end < 0 ? fr.nchunks : c_end;        // c_end: search a leading part of the row only
     constexpr int KB = BF16 ? 16 : 32;
     uint32_t prefix = 0;
     int done = 0;
@@ -160,13 +206,74 @@ __device__ __forceinline__ Cut radix_select(FilterShared& sh, const FilterRow& f
         for (int i = threadIdx.x; i < nbins; i += kFilterThreads) sh.hist[i] = 0;
         __syncthreads();
         const int pshift = KB - done;
-        for_each_logit<BF16>(fr, 0, fr.nchunks, [&](float x, int32_t) {
+        for_each_logit<BF16>(fr, 0, c_hi, [&](float x, int32_t) {
             const uint32_t key = order_key<BF16>(x);
             if (done == 0 || (key >> pshift) == prefix) {
                 const uint32_t bin = (key >> shift) & (uint32_t)(nbins - 1);
-                atomicAdd(&sh.hist[bin], (1ull << kMassBits) + mass_fixed<BF16>(fr, x));
+                atomicAdd(&sh.hist[bin], (1ull << kMassBits) + (MASS ? mass_fixed<BF16>(fr, x) : 0ull));
             }
         });
+        __syncthreads();
+        if (MASS && done == 0 && frac > 0.0) {                  // need = frac * mass of the row
+            uint64_t s = 0;
+            for (int i = threadIdx.x; i < nbins; i += kFilterThreads) s += sh.hist[i];
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor((unsigned long long)s, m, 64);
+            if ((threadIdx.x & 63) == 0) sh.wsum[threadIdx.x >> 6] = s;
+            __syncthreads();
+            uint64_t tot = 0;
+            for (int i = 0; i < kFilterWaves; ++i) tot += sh.wsum[i];
+            need = (uint64_t)(frac * (double)(tot & kMassMask) + 0.5);
+            if (need < 1) need = 1;
+            if (need_out) *need_out = need;
+        }
+        const uint64_t rest = by_mass ? (need > mass_above ? need - mass_above : 1) : need - cnt_above;
+        if (threadIdx.x < 64) scan_level(sh, nbins, by_mass, rest);
+        __syncthreads();
+        const uint32_t bin = sh.bin;
+        const uint64_t above = sh.above;
+        cnt_above += above >> kMassBits;
+        mass_above += above & kMassMask;
+        prefix = (prefix << nb) | bin;
+        done += nb;
+        if (done >= KB) {
+            const uint64_t h = sh.hist[bin];
+            cut.n_ties = (uint32_t)(h >> kMassBits);
+            cut.f_theta = cut.n_ties ? (h & kMassMask) / cut.n_ties : 0;
+        }
+        __syncthreads();
+    }
+    cut.key = prefix;
+    cut.cnt_above = cnt_above;
+    cut.mass_above = mass_above;
+    return cut;
+}
+
+// The same search over the candidate list in LDS: entries that satisfy pred, ordered by keyfn (KB bits).
+template <bool BF16, bool MASS, typename Pred, typename KeyFn>
+__device__ __forceinline__ Cut list_select(FilterShared& sh, const FilterRow& fr, int n, int KB, Pred pred, KeyFn keyfn,
+                                           bool by_mass, uint64_t need)
+{
+    uint32_t prefix = 0;
+    int done = 0;
+    uint64_t cnt_above = 0, mass_above = 0;
+    Cut cut{};
+    while (done < KB) {
+        const int nb = (KB - done) < kLevelBits ? (KB - done) : kLevelBits;
+        const int shift = KB - done - nb;
+        const int nbins = 1 << nb;
+        for (int i = threadIdx.x; i < nbins; i += kFilterThreads) sh.hist[i] = 0;
+        __syncthreads();
+        const int pshift = KB - done;
+        for (int i = threadIdx.x; i < n; i += kFilterThreads) {
+            const unsigned long long ent = sh.cand[i];
+            if (!pred(ent)) continue;
+            const uint32_t key = keyfn(ent);
+            if (done == 0 || (key >> pshift) == prefix) {
+                const uint32_t bin = (key >> shift) & (uint32_t)(nbins - 1);
+                atomicAdd(&sh.hist[bin], (1ull << kMassBits) + (MASS ? mass_fixed<BF16>(fr, key_to_logit<BF16>(key)) : 0ull));
+            }
+        }
         __syncthreads();
         const uint64_t rest = by_mass ? (need > mass_above ? need - mass_above : 1) : need - cnt_above;
         if (threadIdx.x < 64) scan_level(sh, nbins, by_mass, rest);
@@ -203,7 +310,7 @@ struct FilterParams {
 };
 
 template <bool BF16>
-__global__ __launch_bounds__(kFilterThreads) void filter_kernel(FilterParams p)
+__global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(6, 6))) void filter_kernel(FilterParams p)
 {
     __shared__ FilterShared sh;
     constexpr int N = BF16 ? 8 : 4;
@@ -249,191 +356,389 @@ __global__ __launch_bounds__(kFilterThreads) void filter_kernel(FilterParams p)
     const double beta = ref_offset<BF16>(fr.ref, fr.sc);
     fr.scale = exp2(-L - beta);
 
-    // ---- top-k: the k-th largest logit
     const uint64_t kbig = ~0ull;
+    const bool want_k = p.top_k > 0 && p.top_k < p.V;
+    const bool want_p = p.top_p > 0.f && p.top_p < 1.f;
     bool have_cut = false;
     Cut cut{};
     uint64_t r_keep = 0;                                        // ties at theta that are kept
-    uint64_t zk = kbig;                                         // fixed-point mass of the top-k set (kbig: whole row)
-    uint64_t n_finite = kbig;
-    if (p.top_k > 0 && p.top_k < p.V) {
-        cut = radix_select<BF16>(sh, fr, false, (uint64_t)p.top_k);
-        // fewer than k finite logits: everything finite is kept (the scan then settled on the lowest key)
-        const uint64_t total = cut.cnt_above + cut.n_ties;
-        if (total >= (uint64_t)p.top_k) {
-            r_keep = (uint64_t)p.top_k - cut.cnt_above;
-        } else {
-            r_keep = cut.n_ties;
+    float theta = -INFINITY;
+    int idx_cut = 0x7fffffff;                                   // every tie is kept
+    double S = 0.0, T = 0.0;
+
+    // ---- decisions from a list in LDS that holds every token at or above some first-level bin (the cut among them)
+    auto decide_from_list = [&](int n, uint64_t target_abs) {
+        constexpr int KB = BF16 ? 16 : 32;
+        auto logit_key = [](unsigned long long ent) { return (uint32_t)(ent >> 32); };
+        auto every = [](unsigned long long) { return true; };
+        uint64_t zk = kbig;
+        if (want_k) {
+            cut = want_p ? list_select<BF16, true>(sh, fr, n, KB, every, logit_key, false, (uint64_t)p.top_k)
+                         : list_select<BF16, false>(sh, fr, n, KB, every, logit_key, false, (uint64_t)p.top_k);
+            const uint64_t total = cut.cnt_above + cut.n_ties;
+            r_keep = total >= (uint64_t)p.top_k ? (uint64_t)p.top_k - cut.cnt_above : cut.n_ties;
+            zk = cut.mass_above + r_keep * cut.f_theta;
+            have_cut = true;
         }
-        zk = cut.mass_above + r_keep * cut.f_theta;
-        have_cut = true;
-    }
-    // ---- top-p: the shortest prefix whose mass reaches top_p of the top-k mass
-    if (p.top_p > 0.f && p.top_p < 1.f) {
-        if (zk == kbig) {
-            // mass of the whole row in the same fixed point: one more counting pass, level 0 only
-            for (int i = tid; i < kFilterBins; i += kFilterThreads) sh.hist[i] = 0;
+        if (want_p) {
+            uint64_t target = target_abs;
+            if (zk != kbig) {
+                target = (uint64_t)((double)p.top_p * (double)zk + 0.5);
+                if (target < 1) target = 1;
+            }
+            const Cut cp = list_select<BF16, true>(sh, fr, n, KB, every, logit_key, true, target);
+            uint64_t r = 1;
+            if (cp.f_theta > 0 && target > cp.mass_above) r = (target - cp.mass_above + cp.f_theta - 1) / cp.f_theta;
+            if (r < 1) r = 1;
+            if (r > cp.n_ties) r = cp.n_ties;
+            if (have_cut && cp.key == cut.key && r > r_keep) r = r_keep;   // never beyond the top-k cut
+            cut = cp;
+            r_keep = r;
+            have_cut = true;
+        }
+        theta = key_to_logit<BF16>(cut.key);
+        // sums over the kept tokens above theta, in fixed point so that the order of the list does not matter
+        uint32_t kmax = 0;
+        for (int i = tid; i < n; i += kFilterThreads) { const uint32_t k = (uint32_t)(sh.cand[i] >> 32); kmax = k > kmax ? k : kmax; }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) { const uint32_t o = __shfl_xor(kmax, m, 64); kmax = o > kmax ? o : kmax; }
+        if (lane == 0) sh.wave_cnt[wave] = kmax;
+        __syncthreads();
+        for (int i = 0; i < kFilterWaves; ++i) kmax = sh.wave_cnt[i] > kmax ? sh.wave_cnt[i] : kmax;
+        const float y_top = exp_arg<BF16>(key_to_logit<BF16>(kmax), fr.ref, fr.sc);
+        int sft = (int)floorf(-y_top);
+        sft = sft < -60 ? -60 : (sft > 900 ? 900 : sft);
+        const double up = ldexp(1.0, sft);
+        unsigned long long Sfix = 0;
+        long long Tfix = 0;
+        for (int i = tid; i < n; i += kFilterThreads) {
+            const uint32_t k = (uint32_t)(sh.cand[i] >> 32);
+            if (k > cut.key) {
+                const float y = exp_arg<BF16>(key_to_logit<BF16>(k), fr.ref, fr.sc);
+                const double ex = (double)fast_exp2(y) * up;
+                Sfix += (unsigned long long)(ex * 562949953421312.0 + 0.5);            // 2^49
+                Tfix += (long long)rint((double)y * ex * 2199023255552.0);            // 2^41
+            }
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            Sfix += __shfl_xor(Sfix, m, 64);
+            Tfix += (long long)__shfl_xor((unsigned long long)Tfix, m, 64);
+        }
+        __syncthreads();
+        if (lane == 0) { sh.wsum[wave] = Sfix; sh.red[wave] = __longlong_as_double(Tfix); }
+        __syncthreads();
+        unsigned long long Sall = 0;
+        long long Tall = 0;
+        for (int i = 0; i < kFilterWaves; ++i) { Sall += sh.wsum[i]; Tall += __double_as_longlong(sh.red[i]); }
+        S = ldexp((double)Sall, -49 - sft);
+        T = ldexp((double)Tall, -41 - sft);
+        if (r_keep > 0) {
+            const float y = exp_arg<BF16>(theta, fr.ref, fr.sc);
+            const double ex = (double)fast_exp2(y);
+            S += (double)r_keep * ex;
+            T += (double)r_keep * ((double)y * ex);
+        }
+        if (r_keep < cut.n_ties) {
+            // the r-th smallest index among the ties: largest-first select on the complemented index
+            const uint32_t tkey = cut.key;
+            auto is_tie = [tkey](unsigned long long ent) { return (uint32_t)(ent >> 32) == tkey; };
+            auto inv_index = [](unsigned long long ent) { return 0x3fffffu - (uint32_t)(ent & 0xffffffffu); };
             __syncthreads();
-            for_each_logit<BF16>(fr, 0, fr.nchunks, [&](float x, int32_t) {
-                atomicAdd(&sh.hist[order_key<BF16>(x) >> ((BF16 ? 16 : 32) - kLevelBits)], (1ull << kMassBits) + mass_fixed<BF16>(fr, x));
+            const Cut ci = list_select<BF16, false>(sh, fr, n, 22, is_tie, inv_index, false, r_keep);
+            idx_cut = (int)(0x3fffffu - ci.key);
+        }
+    };
+
+    // ---- one pass on a guess.  A sample of the row (its first chunks) suggests a first-level bin below the cut:
+    // for top-k the sample's k-th largest logit, which bounds the row's from below; for top-p alone the value
+    // above which the sample suggests a list of about 3/8 of the capacity.  One pass then lists the
+    // tokens at or above that value and totals the rest; the guess is checked afterwards (the list must hold at
+    // least k tokens, or the nucleus target must lie inside the list's mass), so a bad guess costs a pass, never
+    // a wrong result.
+    bool solved = false;
+    bool sample_ok = false;
+    float edge_v = -3.4028234e38f;                              // logits below it are not among the k largest of the row
+    {
+        const int64_t sample_chunks = fr.nchunks < 4 * kFilterThreads ? fr.nchunks : 4 * kFilterThreads;
+        // top-p alone: aim at a list of about 3/8 of its capacity, i.e. that share of the sample
+        uint64_t need_g = (uint64_t)p.top_k;
+        if (!want_k) {
+            need_g = (uint64_t)(kFilterCand * 3 / 8) * (uint64_t)sample_chunks / (uint64_t)fr.nchunks;
+            if (need_g < 1) need_g = 1;
+        }
+        const Cut cs = radix_select<BF16, false>(sh, fr, false, need_g, 0.0, nullptr, sample_chunks);
+        const uint64_t samp = cs.cnt_above + cs.n_ties;         // sample logits at or above that value
+        sample_ok = samp >= need_g;                             // else the sample has fewer finite logits than asked
+        edge_v = sample_ok ? key_to_logit<BF16>(cs.key) : -3.4028234e38f;
+        if (!(edge_v >= -3.4028234e38f)) edge_v = -3.4028234e38f;
+        const bool try_it = sample_ok && samp * (uint64_t)fr.nchunks <= (uint64_t)(kFilterCand * 3 / 4) * (uint64_t)sample_chunks;
+        if (try_it) {
+            if (tid == 0) sh.ncand = 0;
+            __syncthreads();
+            unsigned long long below = 0;                       // fixed-point mass of what is not listed (top-p alone)
+            auto to_list = [&](float x, int32_t e) {
+                const unsigned int slot = atomicAdd(&sh.ncand, 1u);
+                if (slot < (unsigned int)kFilterCand) sh.cand[slot] = ((unsigned long long)order_key<BF16>(x) << 32) | (uint32_t)e;
+            };
+            if (want_k) split_pass<BF16, false>(fr, edge_v, to_list, [](float) {});
+            else split_pass<BF16, true>(fr, edge_v, to_list, [&](float x) { below += mass_fixed<BF16>(fr, x); });
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) below += __shfl_xor(below, m, 64);
+            if (lane == 0) sh.wsum[wave] = below;
+            __syncthreads();
+            below = 0;
+            for (int i = 0; i < kFilterWaves; ++i) below += sh.wsum[i];
+            const unsigned int n_all = sh.ncand;
+            bool ok = n_all <= (unsigned int)kFilterCand;
+            uint64_t target = 0;
+            if (want_k) {
+                ok = ok && n_all >= (unsigned int)p.top_k;
+            } else if (ok) {
+                unsigned long long lm = 0;                      // mass of the list
+                for (int i = tid; i < (int)n_all; i += kFilterThreads)
+                    lm += mass_fixed<BF16>(fr, key_to_logit<BF16>((uint32_t)(sh.cand[i] >> 32)));
+#pragma unroll
+                for (int m = 32; m >= 1; m >>= 1) lm += __shfl_xor(lm, m, 64);
+                __syncthreads();
+                if (lane == 0) sh.wsum[wave] = lm;
+                __syncthreads();
+                lm = 0;
+                for (int i = 0; i < kFilterWaves; ++i) lm += sh.wsum[i];
+                target = (uint64_t)((double)p.top_p * (double)(lm + below) + 0.5);
+                if (target < 1) target = 1;
+                ok = lm >= target;
+            }
+            __syncthreads();
+            if (ok) {
+                decide_from_list((int)n_all, target);
+                solved = true;
+            }
+        }
+    }
+
+    if (!solved) {
+        // ---- otherwise pass A: first-level histogram of the whole row; the bin that holds the cut, and how many tokens lie at or above it
+        for (int i = tid; i < kFilterBins; i += kFilterThreads) sh.hist[i] = 0;
+        __syncthreads();
+        {
+            constexpr int sh0 = (BF16 ? 16 : 32) - kLevelBits;
+            if (want_p && !want_k)
+                for_each_logit<BF16>(fr, 0, fr.nchunks, [&](float x, int32_t) {
+                    atomicAdd(&sh.hist[order_key<BF16>(x) >> sh0], (1ull << kMassBits) + mass_fixed<BF16>(fr, x));
+                });
+            else if (want_k && want_p)                          // logits below the sample's k-th largest cannot matter
+                split_pass<BF16, false>(fr, edge_v, [&](float x, int32_t) {
+                    atomicAdd(&sh.hist[order_key<BF16>(x) >> sh0], (1ull << kMassBits) + mass_fixed<BF16>(fr, x)); }, [](float) {});
+            else
+                split_pass<BF16, false>(fr, edge_v, [&](float x, int32_t) {
+                    atomicAdd(&sh.hist[order_key<BF16>(x) >> sh0], 1ull << kMassBits); }, [](float) {});
+        }
+        __syncthreads();
+        uint64_t row_total = 0;                                     // packed count and mass of the whole row
+        {
+            uint64_t sacc = 0;
+            for (int i = tid; i < kFilterBins; i += kFilterThreads) sacc += sh.hist[i];
+    #pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) sacc += __shfl_xor((unsigned long long)sacc, m, 64);
+            if (lane == 0) sh.wsum[wave] = sacc;
+            __syncthreads();
+            for (int i = 0; i < kFilterWaves; ++i) row_total += sh.wsum[i];
+        }
+        uint64_t target_p = 0;
+        if (want_p && !want_k) {
+            target_p = (uint64_t)((double)p.top_p * (double)(row_total & kMassMask) + 0.5);
+            if (target_p < 1) target_p = 1;
+        }
+        if (wave == 0) scan_level(sh, kFilterBins, !want_k, want_k ? (uint64_t)p.top_k : target_p);
+        __syncthreads();
+        const uint32_t bin0 = sh.bin;
+        const uint64_t n_cand = (sh.above >> kMassBits) + (sh.hist[bin0] >> kMassBits);
+        const bool fast = n_cand <= (uint64_t)kFilterCand;
+        __syncthreads();
+
+        if (fast) {
+            // ---- pass B: the tokens at or above that bin go to a list in LDS; everything else is decided there
+            constexpr int sh0 = (BF16 ? 16 : 32) - kLevelBits;
+            if (tid == 0) sh.ncand = 0;
+            __syncthreads();
+            for_each_logit<BF16>(fr, 0, fr.nchunks, [&](float x, int32_t e) {
+                const uint32_t key = order_key<BF16>(x);
+                if ((key >> sh0) >= bin0) {
+                    const unsigned int slot = atomicAdd(&sh.ncand, 1u);
+                    if (slot < (unsigned int)kFilterCand) sh.cand[slot] = ((unsigned long long)key << 32) | (uint32_t)e;
+                }
             });
             __syncthreads();
-            uint64_t s = 0;
-            for (int i = tid; i < kFilterBins; i += kFilterThreads) s += sh.hist[i];
-#pragma unroll
-            for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor((unsigned long long)s, m, 64);
-            if (lane == 0) sh.wsum[wave] = s;
-            __syncthreads();
-            uint64_t tot = 0;
-            for (int i = 0; i < kFilterWaves; ++i) tot += sh.wsum[i];
-            __syncthreads();
-            zk = tot & kMassMask;
-            n_finite = tot >> kMassBits;
-        }
-        uint64_t target = (uint64_t)((double)p.top_p * (double)zk + 0.5);
-        if (target < 1) target = 1;
-        const Cut cp = radix_select<BF16>(sh, fr, true, target);
-        uint64_t r = 1;
-        if (cp.f_theta > 0 && target > cp.mass_above) r = (target - cp.mass_above + cp.f_theta - 1) / cp.f_theta;
-        if (r < 1) r = 1;
-        if (r > cp.n_ties) r = cp.n_ties;
-        if (have_cut && cp.key == cut.key && r > r_keep) r = r_keep;   // never beyond the top-k cut
-        cut = cp;
-        r_keep = r;
-        have_cut = true;
-    }
-    (void)n_finite;
-
-    // ---- statistics of the kept tokens; position of the last kept tie
-    const float theta = have_cut ? key_to_logit<BF16>(cut.key) : -INFINITY;
-    const bool partial_ties = have_cut && r_keep < cut.n_ties;
-    const int64_t cps = ((fr.nchunks + kFilterBins - 1) / kFilterBins + kFilterThreads - 1) / kFilterThreads * kFilterThreads;
-    unsigned int* sbties = (unsigned int*)sh.hist;
-    if (partial_ties) {
-        for (int i = tid; i < kFilterBins; i += kFilterThreads) sbties[i] = 0;
-        __syncthreads();
-    }
-    double Sd = 0.0, Td = 0.0;
-    {
-        constexpr int U = 4;
-        for (int64_t c0 = tid; c0 < fr.nchunks; c0 += (int64_t)U * kFilterThreads) {
-            uint4 v[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t c = c0 + (int64_t)u * kFilterThreads;
-                v[u] = make_uint4(0, 0, 0, 0);
-                if (c < fr.nchunks) v[u] = fr.rowv[c];
+        decide_from_list((int)(sh.ncand < (unsigned int)kFilterCand ? sh.ncand : (unsigned int)kFilterCand), target_p);
+        } else {
+            // ---- top-k: the k-th largest logit
+            uint64_t zk = kbig;                                         // fixed-point mass of the top-k set (kbig: whole row)
+            if (p.top_k > 0 && p.top_k < p.V) {
+                cut = want_p ? radix_select<BF16, true>(sh, fr, false, (uint64_t)p.top_k)
+                             : radix_select<BF16, false>(sh, fr, false, (uint64_t)p.top_k);
+                // fewer than k finite logits: everything finite is kept (the scan then settled on the lowest key)
+                const uint64_t total = cut.cnt_above + cut.n_ties;
+                if (total >= (uint64_t)p.top_k) {
+                    r_keep = (uint64_t)p.top_k - cut.cnt_above;
+                } else {
+                    r_keep = cut.n_ties;
+                }
+                zk = cut.mass_above + r_keep * cut.f_theta;
+                have_cut = true;
             }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t c = c0 + (int64_t)u * kFilterThreads;
-                if (c >= fr.nchunks) continue;
-                const int32_t e0 = (int32_t)(c * N) - fr.head;
-                const bool edge = (c == 0) || (c == fr.nchunks - 1);
-                float s = 0.f, t = 0.f;
-                unsigned int ties = 0;
-#pragma unroll
-                for (int kk = 0; kk < N; ++kk) {
-                    const int32_t e = e0 + kk;
-                    const bool valid = !edge || (e >= 0 && e < fr.V);
-                    const float x = chunk_elem<BF16>(v[u], kk);
-                    if (valid && x > theta) {
-                        const float y = exp_arg<BF16>(x, fr.ref, fr.sc);
-                        const float ex = fast_exp2(y);
-                        s += ex;
-                        t = __builtin_fmaf(y, ex, t);
+            // ---- top-p: the shortest prefix whose mass reaches top_p of the top-k mass
+            if (want_p) {
+                uint64_t target = 0;
+                Cut cp;
+                if (zk == kbig) {
+                    cp = radix_select<BF16, true>(sh, fr, true, 0, (double)p.top_p, &target);   // of the whole row's mass
+                } else {
+                    target = (uint64_t)((double)p.top_p * (double)zk + 0.5);
+                    if (target < 1) target = 1;
+                    cp = radix_select<BF16, true>(sh, fr, true, target);
+                }
+                uint64_t r = 1;
+                if (cp.f_theta > 0 && target > cp.mass_above) r = (target - cp.mass_above + cp.f_theta - 1) / cp.f_theta;
+                if (r < 1) r = 1;
+                if (r > cp.n_ties) r = cp.n_ties;
+                if (have_cut && cp.key == cut.key && r > r_keep) r = r_keep;   // never beyond the top-k cut
+                cut = cp;
+                r_keep = r;
+                have_cut = true;
+            }
+
+            // ---- statistics of the kept tokens; position of the last kept tie
+            theta = have_cut ? key_to_logit<BF16>(cut.key) : -INFINITY;
+            const bool partial_ties = have_cut && r_keep < cut.n_ties;
+            const int64_t cps = ((fr.nchunks + kFilterBins - 1) / kFilterBins + kFilterThreads - 1) / kFilterThreads * kFilterThreads;
+            unsigned int* sbties = (unsigned int*)sh.hist;
+            if (partial_ties) {
+                for (int i = tid; i < kFilterBins; i += kFilterThreads) sbties[i] = 0;
+                __syncthreads();
+            }
+            double Sd = 0.0, Td = 0.0;
+            {
+                constexpr int U = 4;
+                for (int64_t c0 = tid; c0 < fr.nchunks; c0 += (int64_t)U * kFilterThreads) {
+                    uint4 v[U];
+        #pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int64_t c = c0 + (int64_t)u * kFilterThreads;
+                        v[u] = make_uint4(0, 0, 0, 0);
+                        if (c < fr.nchunks) v[u] = fr.rowv[c];
                     }
-                    if (valid && x == theta) ++ties;
-                }
-                Sd += (double)s;
-                Td += (double)t;
-                if (partial_ties && ties) atomicAdd(&sbties[c / cps], ties);
-            }
-        }
-    }
-    Sd = wave_sum(Sd);
-    Td = wave_sum(Td);
-    if (lane == 0) { sh.red[2 * wave] = Sd; sh.red[2 * wave + 1] = Td; }
-    __syncthreads();
-    double S = 0.0, T = 0.0;
-    for (int i = 0; i < kFilterWaves; ++i) { S += sh.red[2 * i]; T += sh.red[2 * i + 1]; }
-    if (have_cut && r_keep > 0) {                               // the kept ties, all with the same term
-        const float y = exp_arg<BF16>(theta, fr.ref, fr.sc);
-        const double ex = (double)fast_exp2(y);
-        S += (double)r_keep * ex;
-        T += (double)r_keep * ((double)y * ex);
-    }
-
-    int idx_cut = 0x7fffffff;                                   // every tie is kept
-    if (partial_ties) {
-        // super-block that holds the r-th tie (ascending index), then the element inside it
-        if (wave == 0) {
-            const int nsb = (int)((fr.nchunks + cps - 1) / cps);
-            const int per = (nsb + 63) / 64;
-            unsigned int mine = 0;
-            for (int i = 0; i < per; ++i) { const int q = lane * per + i; if (q < nsb) mine += sbties[q]; }
-            unsigned int incl = mine;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) { const unsigned int o = __shfl_up(incl, d, 64); if (lane >= d) incl += o; }
-            const unsigned long long hit = __ballot((uint64_t)incl >= r_keep);
-            const int src = hit ? (__ffsll((long long)hit) - 1) : 63;
-            if (lane == src) {
-                unsigned int run = incl - mine;
-                int found = nsb - 1;
-                for (int i = 0; i < per; ++i) {
-                    const int q = lane * per + i;
-                    if (q >= nsb) break;
-                    if ((uint64_t)run + sbties[q] >= r_keep) { found = q; break; }
-                    run += sbties[q];
-                }
-                sh.sb = (unsigned int)found;
-                sh.rank_in_sb = (unsigned int)(r_keep - run);
-            }
-        }
-        if (tid == 0) sh.idx_cut = fr.V - 1;
-        __syncthreads();
-        const int64_t c_lo = (int64_t)sh.sb * cps;
-        const int64_t c_hi = c_lo + cps < fr.nchunks ? c_lo + cps : fr.nchunks;
-        unsigned int want = sh.rank_in_sb;                      // 1-based rank inside the super-block
-        bool finished = false;
-        for (int64_t base = c_lo; base < c_hi; base += kFilterThreads) {   // uniform trip count
-            const int64_t c = base + tid;
-            unsigned int ties = 0;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            int32_t e0 = 0;
-            if (c < c_hi) {
-                v = fr.rowv[c];
-                e0 = (int32_t)(c * N) - fr.head;
-#pragma unroll
-                for (int kk = 0; kk < N; ++kk) {
-                    const int32_t e = e0 + kk;
-                    if (e >= 0 && e < fr.V && chunk_elem<BF16>(v, kk) == theta) ++ties;
-                }
-            }
-            unsigned int incl = ties;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) { const unsigned int o = __shfl_up(incl, d, 64); if (lane >= d) incl += o; }
-            if (lane == 63) sh.wave_cnt[wave] = incl;
-            __syncthreads();
-            unsigned int before = 0, total = 0;
-            for (int i = 0; i < kFilterWaves; ++i) { const unsigned int wc = sh.wave_cnt[i]; if (i < wave) before += wc; total += wc; }
-            const unsigned int excl = before + incl - ties;
-            if (!finished && want > excl && want <= excl + ties) {
-                unsigned int seen = excl;
-#pragma unroll
-                for (int kk = 0; kk < N; ++kk) {
-                    const int32_t e = e0 + kk;
-                    if (e >= 0 && e < fr.V && chunk_elem<BF16>(v, kk) == theta) {
-                        ++seen;
-                        if (seen == want) sh.idx_cut = e;
+        #pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        const int64_t c = c0 + (int64_t)u * kFilterThreads;
+                        if (c >= fr.nchunks) continue;
+                        const int32_t e0 = (int32_t)(c * N) - fr.head;
+                        const bool edge = (c == 0) || (c == fr.nchunks - 1);
+                        float s = 0.f, t = 0.f;
+                        unsigned int ties = 0;
+        #pragma unroll
+                        for (int kk = 0; kk < N; ++kk) {
+                            const int32_t e = e0 + kk;
+                            const bool valid = !edge || (e >= 0 && e < fr.V);
+                            const float x = chunk_elem<BF16>(v[u], kk);
+                            if (valid && x > theta) {
+                                const float y = exp_arg<BF16>(x, fr.ref, fr.sc);
+                                const float ex = fast_exp2(y);
+                                s += ex;
+                                t = __builtin_fmaf(y, ex, t);
+                            }
+                            if (valid && x == theta) ++ties;
+                        }
+                        Sd += (double)s;
+                        Td += (double)t;
+                        if (partial_ties && ties) atomicAdd(&sbties[c / cps], ties);
                     }
                 }
             }
-            if (want <= total) finished = true; else want -= total;
+            Sd = wave_sum(Sd);
+            Td = wave_sum(Td);
+            if (lane == 0) { sh.red[2 * wave] = Sd; sh.red[2 * wave + 1] = Td; }
             __syncthreads();
-            if (finished) break;                                // uniform: every thread saw the same totals
+            for (int i = 0; i < kFilterWaves; ++i) { S += sh.red[2 * i]; T += sh.red[2 * i + 1]; }
+            if (have_cut && r_keep > 0) {                               // the kept ties, all with the same term
+                const float y = exp_arg<BF16>(theta, fr.ref, fr.sc);
+                const double ex = (double)fast_exp2(y);
+                S += (double)r_keep * ex;
+                T += (double)r_keep * ((double)y * ex);
+            }
+
+            if (partial_ties) {
+                // super-block that holds the r-th tie (ascending index), then the element inside it
+                if (wave == 0) {
+                    const int nsb = (int)((fr.nchunks + cps - 1) / cps);
+                    const int per = (nsb + 63) / 64;
+                    unsigned int mine = 0;
+                    for (int i = 0; i < per; ++i) { const int q = lane * per + i; if (q < nsb) mine += sbties[q]; }
+                    unsigned int incl = mine;
+        #pragma unroll
+                    for (int d = 1; d < 64; d <<= 1) { const unsigned int o = __shfl_up(incl, d, 64); if (lane >= d) incl += o; }
+                    const unsigned long long hit = __ballot((uint64_t)incl >= r_keep);
+                    const int src = hit ? (__ffsll((long long)hit) - 1) : 63;
+                    if (lane == src) {
+                        unsigned int run = incl - mine;
+                        int found = nsb - 1;
+                        for (int i = 0; i < per; ++i) {
+                            const int q = lane * per + i;
+                            if (q >= nsb) break;
+                            if ((uint64_t)run + sbties[q] >= r_keep) { found = q; break; }
+                            run += sbties[q];
+                        }
+                        sh.sb = (unsigned int)found;
+                        sh.rank_in_sb = (unsigned int)(r_keep - run);
+                    }
+                }
+                if (tid == 0) sh.idx_cut = fr.V - 1;
+                __syncthreads();
+                const int64_t c_lo = (int64_t)sh.sb * cps;
+                const int64_t c_hi = c_lo + cps < fr.nchunks ? c_lo + cps : fr.nchunks;
+                unsigned int want = sh.rank_in_sb;                      // 1-based rank inside the super-block
+                bool finished = false;
+                for (int64_t base = c_lo; base < c_hi; base += kFilterThreads) {   // uniform trip count
+                    const int64_t c = base + tid;
+                    unsigned int ties = 0;
+                    uint4 v = make_uint4(0, 0, 0, 0);
+                    int32_t e0 = 0;
+                    if (c < c_hi) {
+                        v = fr.rowv[c];
+                        e0 = (int32_t)(c * N) - fr.head;
+        #pragma unroll
+                        for (int kk = 0; kk < N; ++kk) {
+                            const int32_t e = e0 + kk;
+                            if (e >= 0 && e < fr.V && chunk_elem<BF16>(v, kk) == theta) ++ties;
+                        }
+                    }
+                    unsigned int incl = ties;
+        #pragma unroll
+                    for (int d = 1; d < 64; d <<= 1) { const unsigned int o = __shfl_up(incl, d, 64); if (lane >= d) incl += o; }
+                    if (lane == 63) sh.wave_cnt[wave] = incl;
+                    __syncthreads();
+                    unsigned int before = 0, total = 0;
+                    for (int i = 0; i < kFilterWaves; ++i) { const unsigned int wc = sh.wave_cnt[i]; if (i < wave) before += wc; total += wc; }
+                    const unsigned int excl = before + incl - ties;
+                    if (!finished && want > excl && want <= excl + ties) {
+                        unsigned int seen = excl;
+        #pragma unroll
+                        for (int kk = 0; kk < N; ++kk) {
+                            const int32_t e = e0 + kk;
+                            if (e >= 0 && e < fr.V && chunk_elem<BF16>(v, kk) == theta) {
+                                ++seen;
+                                if (seen == want) sh.idx_cut = e;
+                            }
+                        }
+                    }
+                    if (want <= total) finished = true; else want -= total;
+                    __syncthreads();
+                    if (finished) break;                                // uniform: every thread saw the same totals
+                }
+                idx_cut = sh.idx_cut;
+            }
+
         }
-        idx_cut = sh.idx_cut;
     }
 
     out.theta = theta;
