@@ -225,6 +225,7 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     rs.target = a.target_logits; rs.draft = a.draft_logits; rs.target_ld = tld; rs.draft_ld = dld;
     rs.draft_len = a.draft_len; rs.row_temperature = a.row_temperature; rs.temperature = a.temperature;
     rs.B = a.B; rs.gamma = a.gamma; rs.V = a.V; rs.nsplit = nsplit; rs.skip_draft = skip_draft; rs.skip_target = skip_target;
+    rs.lse_only_targets = a.target_stats_out ? 0 : 1;           // the accept stage and the sampler use only their lse
     rs.partials = w.partials;
     hipError_t e = hipSuccess;
     if (rows > 0) { StageTimer t(0, s); e = launch_row_stats(rs, a.dtype, tune, s); }   // nothing to stream when both are supplied

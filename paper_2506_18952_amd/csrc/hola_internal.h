@@ -74,6 +74,7 @@ struct RowStatsParams {
     int32_t nsplit;
     int32_t skip_draft;                // draft statistics come from a previous level
     int32_t skip_target;               // target statistics are given by the caller
+    int32_t lse_only_targets;          // nobody asks for the entropy of the target rows: their pass leaves T out
     int32_t tile_cols, ntiles;         // ntiles > 0: "sequence" b is column tile b % ntiles of plain row b / ntiles
     int32_t literal;                   // Equation (1) literal mode: target row j is needed only for j < len
     Partial* partials;

@@ -9,7 +9,7 @@
 
 namespace hola {
 
-template <bool BF16, bool ARGMAX, int U>
+template <bool BF16, bool ARGMAX, int U, bool WITH_T = true>
 __device__ __forceinline__ void row_segment(const void* row, int32_t V, int seg, int nsplit, const ExpScale& sc,
                                             Partial* __restrict__ out /* [kWaves] of this (row, segment) */)
 {
@@ -23,7 +23,7 @@ __device__ __forceinline__ void row_segment(const void* row, int32_t V, int seg,
     if (seg_lo > g.c_end) seg_lo = g.c_end;
     if (seg_hi > g.c_end) seg_hi = g.c_end;
     const bool do_edges = (seg == 0 && wave == 0);
-    const Partial res = wave_row_share<BF16, ARGMAX, U>(g, seg_lo + tid, seg_hi, kBlock, do_edges, sc, lane);
+    const Partial res = wave_row_share<BF16, ARGMAX, U, WITH_T>(g, seg_lo + tid, seg_hi, kBlock, do_edges, sc, lane);
     if (lane == 0) out[wave] = res;
 }
 
@@ -67,6 +67,7 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(RowStatsParams p)
     }
     Partial* out = p.partials + (slot * nsplit + seg) * kWaves;
     if (greedy && !is_draft) row_segment<BF16, true, U>(row, Vrow, seg, nsplit, sc, out);
+    else if (!is_draft && p.lse_only_targets) row_segment<BF16, false, U, false>(row, Vrow, seg, nsplit, sc, out);
     else row_segment<BF16, false, U>(row, Vrow, seg, nsplit, sc, out);
 }
 

@@ -116,8 +116,9 @@ __device__ __forceinline__ void accum_elem(LaneState& st, float x, int32_t idx, 
     st.Td += (double)(y * e);
 }
 
-// Fast path: one 16-byte chunk, no per-element guards.
-template <bool BF16, bool ARGMAX>
+// Fast path: one 16-byte chunk, no per-element guards.  WITH_T = false leaves out T = sum y 2^y (rows of which
+// only the normaliser is wanted: a -inf logit then simply adds nothing).
+template <bool BF16, bool ARGMAX, bool WITH_T = true>
 __device__ __forceinline__ void accum_chunk(LaneState& st, const uint4& v, int32_t elem0, const ExpScale& sc)
 {
     constexpr int N = BF16 ? 8 : 4;
@@ -140,13 +141,13 @@ __device__ __forceinline__ void accum_chunk(LaneState& st, const uint4& v, int32
     for (int k = 0; k < N; ++k) {
         const float y = exp_arg<BF16>(x[k], st.ref, sc);
         e[k] = fast_exp2(y);
-        t[k & 1] = __builtin_fmaf(y, e[k], t[k & 1]);
+        if (WITH_T) t[k & 1] = __builtin_fmaf(y, e[k], t[k & 1]);
     }
     float s;
     if (N == 8) s = ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
     else s = (e[0] + e[1]) + (e[2] + e[3]);
     st.Sd += (double)s;
-    st.Td += (double)(t[0] + t[1]);
+    if (WITH_T) st.Td += (double)(t[0] + t[1]);
 }
 
 template <bool BF16, bool ARGMAX>
@@ -235,7 +236,7 @@ __device__ __forceinline__ RowGeom make_geom(const void* row, int32_t V)
 
 // One wavefront's pass over the chunks c0, c0 + stride, ... < c_hi of a row (c0 already holds the lane's
 // offset), plus, if do_edges, the edge elements (fewer than two chunks' worth, one per lane).
-template <bool BF16, bool ARGMAX, int U, bool ROBUST>
+template <bool BF16, bool ARGMAX, int U, bool ROBUST, bool WITH_T = true>
 __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64_t c0, int64_t c_hi_in, int64_t stride_in,
                                           bool do_edges, const ExpScale& sc, int lane)
 {
@@ -274,7 +275,7 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
         for (int u = 0; u < U; ++u) {
             const int32_t e0 = (int32_t)((c + u * stride) * N) - g.head;
             if (ROBUST) accum_chunk_robust<BF16, ARGMAX>(st, buf[u], e0, sc);
-            else accum_chunk<BF16, ARGMAX>(st, buf[u], e0, sc);
+            else accum_chunk<BF16, ARGMAX, WITH_T>(st, buf[u], e0, sc);
         }
         w += (int64_t)U * stride;
         wb += (int64_t)U * sb;
@@ -306,7 +307,7 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
             if (c + u * stride < c_hi) {
                 const int32_t e0 = (int32_t)((c + u * stride) * N) - g.head;
                 if (ROBUST) accum_chunk_robust<BF16, ARGMAX>(st, buf[u], e0, sc);
-                else accum_chunk<BF16, ARGMAX>(st, buf[u], e0, sc);
+                else accum_chunk<BF16, ARGMAX, WITH_T>(st, buf[u], e0, sc);
             }
         }
     }
@@ -321,12 +322,12 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
 
 // A wavefront's share of a row, with the fallback pass when the fast pass meets a -inf logit (its
 // y * 2^y is NaN) or anything else non-finite.
-template <bool BF16, bool ARGMAX, int U>
+template <bool BF16, bool ARGMAX, int U, bool WITH_T = true>
 __device__ __forceinline__ Partial wave_row_share(const RowGeom& g, int64_t c0, int64_t c_hi, int64_t stride,
                                                   bool do_edges, const ExpScale& sc, int lane)
 {
     LaneState st;
-    wave_pass<BF16, ARGMAX, U, false>(st, g, c0, c_hi, stride, do_edges, sc, lane);
+    wave_pass<BF16, ARGMAX, U, false, WITH_T>(st, g, c0, c_hi, stride, do_edges, sc, lane);
     Partial res = wave_merge<BF16, ARGMAX>(st, sc);
     const bool finite = (res.S - res.S == 0.0) && (res.T - res.T == 0.0);
     if (!finite) {                                      // wavefront-uniform
