@@ -56,6 +56,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--batch", type=int, default=256, help="sequences (256 = the headline workload)")
     ap.add_argument("--path", choices=["auto", "split", "fused"], default="auto", help="kernel path (auto: library's choice)")
+    ap.add_argument("--top-k", type=int, default=0, help="top-k filter on both models (0: off; not the headline workload)")
+    ap.add_argument("--top-p", type=float, default=0.0, help="top-p filter on both models (0: off; not the headline workload)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-baseline leg")
     ap.add_argument("--copy-calibration", action="store_true")
     args = ap.parse_args()
@@ -96,8 +98,10 @@ def main() -> int:
     def step(i, seed_offset=True):
         hb.hola_verify_ex(target_logits=P, draft_logits=D, draft_tokens=tok, seed=w.seed + (i if seed_offset else 0),
                           B=B, gamma=g, V=V, temperature=w.temperature, entropy_threshold=taus[i % len(taus)],
-                          out_accept_len=acc, out_next_token=nxt, out_entropy=ent, workspace=ws, stream=stream)
+                          out_accept_len=acc, out_next_token=nxt, out_entropy=ent, workspace=ws, stream=stream,
+                          top_k=args.top_k, top_p=args.top_p)
 
+    filtered = (0 < args.top_k < V) or (0.0 < args.top_p < 1.0)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -136,6 +140,8 @@ def main() -> int:
     fused = stage_n[5] > 0
     if fused:
         kname, k_ms, k_bytes = "fused_kernel", stage_ms[5] / stage_n[5], pass1_bytes + stop_bytes
+    elif filtered and stage_n[7] > 0:                      # the keep-set kernel dominates: it must read every row once
+        kname, k_ms, k_bytes = "filter_kernel", stage_ms[7] / stage_n[7], pass1_bytes
     else:
         kname, k_ms, k_bytes = "row_stats_kernel", stage_ms[0] / max(stage_n[0], 1), pass1_bytes
     achieved = k_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0
@@ -153,7 +159,8 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"cfg3: B={B} gamma={g} V={V} bf16 logits T=0.8, tau cycling (0.25,0.5,0.75) ln V",
+        "config": {"workload": f"cfg3: B={B} gamma={g} V={V} bf16 logits T=0.8, tau cycling (0.25,0.5,0.75) ln V"
+                               + (f", top_k={args.top_k} top_p={args.top_p} (not the headline workload)" if filtered else ""),
                    "entry_point": "hola_verify_ex", "kernel_path": "fused" if fused else "split",
                    "parallelism": "single GPU"},
         "hbm_gbps_whole_call": round(call_gbps, 1), "hbm_frac_whole_call": round(call_gbps / HBM_PEAK_GBPS, 4),
@@ -168,21 +175,32 @@ def main() -> int:
         from oracle import hola_oracle as orc
         threads = orc.max_threads()
         t0 = time.perf_counter()
-        refs = [orc.verify(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, num_threads=threads) for tau in taus]
+        if filtered:
+            refs = [orc.verify_filtered(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, top_k=args.top_k,
+                                        top_p=args.top_p if 0.0 < args.top_p < 1.0 else 1.0, num_threads=threads)
+                    for tau in taus]
+        else:
+            refs = [orc.verify(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, num_threads=threads) for tau in taus]
         cdt = time.perf_counter() - t0
-        same = same_t = 0
+        same = same_t = near = 0
         for i, tau in enumerate(taus):
             step(i, seed_offset=False)
             torch.cuda.synchronize()
             same += int((acc.cpu().numpy() == refs[i].accept_len).sum())
             same_t += int((nxt.cpu().numpy() == refs[i].next_token).sum())
+            # sequences with a deciding comparison the oracle lists as near-threshold (margin < 1e-6)
+            m = np.minimum(np.nan_to_num(refs[i].sample_margin, nan=np.inf),
+                           np.minimum(np.nan_to_num(refs[i].gate_margin, nan=np.inf).min(axis=1),
+                                      np.nan_to_num(refs[i].ratio_margin, nan=np.inf).min(axis=1)))
+            near += int((m < 1e-6).sum())
         n = B * len(taus)
         out["cpu_baseline"] = {"value": round(n * g / cdt, 1), "unit": "positions/s", "cores": threads,
                                "kind": "oracle",
                                "sample": f"all {B} sequences of the same workload at each of the {len(taus)} thresholds "
                                          f"({len(taus)} oracle calls, {cdt:.2f}s wall, {cdt * threads:.0f} core-seconds); "
                                          f"float64 C oracle, OpenMP over sequences",
-                               "agree_accept_len": f"{same}/{n}", "agree_next_token": f"{same_t}/{n}"}
+                               "agree_accept_len": f"{same}/{n}", "agree_next_token": f"{same_t}/{n}",
+                               "oracle_listed_near_threshold": near}
     print(json.dumps(out), flush=True)
     return 0
 

@@ -232,7 +232,7 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     if (e != hipSuccess) return hip_fail(e, "row statistics launch");
 
     if (filtered) {
-        StageTimer t(2, s);
+        StageTimer t(7, s);
         e = launch_filter(a.target_logits, a.draft_logits, a.dtype, tld, dld, a.draft_len, a.temperature, a.B, a.gamma, a.V,
                           a.top_k, (a.top_p > 0.f && a.top_p < 1.f) ? a.top_p : 1.f, w.partials, nsplit * kWaves, w.filters,
                           a.out_keep_count, s);
