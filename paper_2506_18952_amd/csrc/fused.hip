@@ -180,13 +180,18 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
     const float Tb = p.row_temperature ? p.row_temperature[b] : p.temperature;
     const int first_row = p.draft_stats_in ? g : 0;
     const int end_row = (p.target_stats_in || FILT) ? g : 2 * g + 1;   // supplied or filtered statistics are not merged here
-    for (int r = (FILT ? g : first_row) + wave; r < end_row; r += NW) {   // one wavefront per row, one lane per partial
+    // `width` lanes per row (one lane per partial), 64 / width rows per wavefront
+    int width = 4;
+    while (width < nparts) width <<= 1;
+    const int per_wave = 64 / width, seg = lane / width, sl = lane % width;
+    for (int r0 = (FILT ? g : first_row) + wave * per_wave; r0 < end_row; r0 += NW * per_wave) {
+        const int r = r0 + seg;
         const bool is_draft = r < g;
         const int j = is_draft ? r : r - g;
-        if (is_draft ? (j >= len) : (j > len)) continue;
+        const bool need = r < end_row && (is_draft ? (j < len) : (j <= len));
         const int64_t slot = is_draft ? (int64_t)b * g + j : (int64_t)p.B * g + (int64_t)b * (g + 1) + j;
-        const RowStat s = merge_partials_wave(partials + slot * nparts, nparts, lane);
-        if (lane == 0) sh.stat[r] = s;
+        const RowStat s = merge_partials_seg(need ? partials + slot * nparts : nullptr, nparts, sl, width);
+        if (need && sl == 0) sh.stat[r] = s;
     }
     __syncthreads();
     sequence_tail<BF16, NW, FILT>(p, sh, b, len, Tb);

@@ -417,4 +417,46 @@ __device__ __forceinline__ RowStat merge_partials_wave(const Partial* __restrict
     return r;
 }
 
+// The same merge on a segment of the wavefront: `width` (a power of two >= n) consecutive lanes hold the
+// partials of one row, so a wavefront merges 64 / width rows at once.  ps is the row's first partial (null:
+// the segment has no row), sl the lane's index inside its segment.  Butterflies with masks below `width` stay
+// inside a segment and add in the same order as the whole-wavefront merge, so the results are bit-identical.
+__device__ __forceinline__ RowStat merge_partials_seg(const Partial* __restrict__ ps, int n, int sl, int width)
+{
+    Partial q;
+    q.bref = 0.0; q.S = 0.0; q.T = 0.0; q.vmax = -INFINITY; q.imax = -1;
+    if (ps && sl < n) q = ps[sl];
+    int badi = !(q.S == q.S) ? 1 : 0;
+    double bmin = (q.S > 0.0) ? q.bref : INFINITY;
+    for (int m = width >> 1; m >= 1; m >>= 1) {
+        bmin = fmin(bmin, __shfl_xor(bmin, m, 64));
+        badi |= __shfl_xor(badi, m, 64);
+    }
+    double S = 0.0, T = 0.0;
+    if (q.S > 0.0) {
+        const double d = bmin - q.bref;
+        if (d == 0.0) { S = q.S; T = q.T; }
+        else { const double f = exp2(d); S = q.S * f; T = (q.T + d * q.S) * f; }
+    }
+    float v = q.vmax;
+    int32_t i = q.imax;
+    for (int m = width >> 1; m >= 1; m >>= 1) {
+        S += __shfl_xor(S, m, 64);
+        T += __shfl_xor(T, m, 64);
+        const float ov = __shfl_xor(v, m, 64);
+        const int32_t oi = __shfl_xor(i, m, 64);
+        const bool take = (oi >= 0) && (i < 0 || ov > v || (ov == v && oi < i));
+        if (take) { v = ov; i = oi; }
+    }
+    RowStat r;
+    r.argmax = i;
+    if (badi || !(T == T)) { r.lse = NAN; r.H = NAN; return r; }
+    if (!(S > 0.0)) { r.lse = -INFINITY; r.H = NAN; return r; }
+    const double lnS = log(S);
+    r.lse = lnS - bmin * kLn2;
+    r.H = lnS - kLn2 * (T / S);
+    if (r.H < 0.0) r.H = 0.0;
+    return r;
+}
+
 }  // namespace hola
