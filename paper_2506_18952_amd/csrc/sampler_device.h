@@ -110,26 +110,27 @@ __device__ __forceinline__ float chunk_weights_loaded(const RowPair& rp, int64_t
     const int32_t e0 = (int32_t)(c * N) - rp.head;
     const bool edge = (c == 0) || (c == rp.nchunks - 1);
     const bool dvec = !rp.bonus && rp.Dv != nullptr;
+    // Elements of an edge chunk that lie outside the row become -inf logits (weight 0), so the loop below
+    // carries no per-element guard; a NaN weight is dropped by the max with 0.
     float sum = 0.f;
 #pragma unroll
     for (int k = 0; k < N; ++k) {
         const int32_t e = e0 + k;
-        const bool valid = !edge || (e >= 0 && e < rp.V);
-        const float xp = chunk_elem<BF16>(vp, k);
+        float xp = chunk_elem<BF16>(vp, k);
+        if (edge && (e < 0 || e >= rp.V)) xp = -INFINITY;
         float ep = fast_exp2(exp_arg<BF16>(xp, rp.refP, rp.sc));
         if (FILT && !(xp > rp.thP || (xp == rp.thP && e <= rp.cutP))) ep = 0.f;
         float wk;
         if (rp.bonus) {
-            wk = ep;
+            wk = fmaxf(ep, 0.f);
         } else {
             float xd;
             if (dvec) xd = chunk_elem<BF16>(vd, k);
-            else xd = valid ? load_logit<BF16>(rp.D, e) : 0.f;
+            else xd = (e >= 0 && e < rp.V) ? load_logit<BF16>(rp.D, e) : 0.f;
             float eq = fast_exp2(exp_arg<BF16>(xd, rp.refQ, rp.sc));
             if (FILT && !(xd > rp.thQ || (xd == rp.thQ && e <= rp.cutQ))) eq = 0.f;
             wk = fmaxf(0.f, __builtin_fmaf(-rp.k_lo, eq, __builtin_fmaf(-rp.k_hi, eq, ep)));
         }
-        if (!valid || !(wk == wk)) wk = 0.f;
         w[k] = wk;
         sum += wk;
     }
