@@ -85,14 +85,36 @@ __device__ __forceinline__ void make_row_pair(RowPair& rp, const void* target, c
     }
 }
 
-// The 16-byte chunks c of the target row and (when it shares the alignment) of the draft row.
+// The 16-byte chunks c of the target row and (when it shares the alignment) of the draft row.  In the first
+// and last chunk the elements that lie outside the row are replaced by -inf logits (weight 0), so the weight
+// loop needs no guard.
+template <bool BF16>
 __device__ __forceinline__ void load_chunk_pair(const RowPair& rp, int64_t c, uint4& vp, uint4& vd)
 {
+    constexpr int N = BF16 ? 8 : 4;
     vp = make_uint4(0, 0, 0, 0);
     vd = make_uint4(0, 0, 0, 0);
     if (c < rp.nchunks) {
         vp = load_stream(rp.Pv + c);
-        if (!rp.bonus && rp.Dv != nullptr) vd = load_stream(rp.Dv + c);
+        const bool dvec = !rp.bonus && rp.Dv != nullptr;
+        if (dvec) vd = load_stream(rp.Dv + c);
+        if (c == 0 || c == rp.nchunks - 1) {
+            const int32_t e0 = (int32_t)(c * N) - rp.head;
+            uint32_t* wp = (uint32_t*)&vp;
+            uint32_t* wd = (uint32_t*)&vd;
+#pragma unroll
+            for (int k = 0; k < N; ++k) {
+                if (e0 + k >= 0 && e0 + k < rp.V) continue;
+                if (BF16) {
+                    const uint32_t m = (k & 1) ? 0x0000ffffu : 0xffff0000u, v = (k & 1) ? 0xff800000u : 0x0000ff80u;
+                    wp[k >> 1] = (wp[k >> 1] & m) | v;
+                    wd[k >> 1] = (wd[k >> 1] & m) | v;
+                } else {
+                    wp[k] = 0xff800000u;
+                    wd[k] = 0xff800000u;
+                }
+            }
+        }
     }
 }
 
@@ -108,16 +130,14 @@ __device__ __forceinline__ float chunk_weights_loaded(const RowPair& rp, int64_t
         return 0.f;
     }
     const int32_t e0 = (int32_t)(c * N) - rp.head;
-    const bool edge = (c == 0) || (c == rp.nchunks - 1);
     const bool dvec = !rp.bonus && rp.Dv != nullptr;
-    // Elements of an edge chunk that lie outside the row become -inf logits (weight 0), so the loop below
-    // carries no per-element guard; a NaN weight is dropped by the max with 0.
+    // Out-of-row elements of an edge chunk arrive as -inf logits (load_chunk_pair), so the loop carries no
+    // per-element guard; a NaN weight is dropped by the max with 0.
     float sum = 0.f;
 #pragma unroll
     for (int k = 0; k < N; ++k) {
         const int32_t e = e0 + k;
-        float xp = chunk_elem<BF16>(vp, k);
-        if (edge && (e < 0 || e >= rp.V)) xp = -INFINITY;
+        const float xp = chunk_elem<BF16>(vp, k);
         float ep = fast_exp2(exp_arg<BF16>(xp, rp.refP, rp.sc));
         if (FILT && !(xp > rp.thP || (xp == rp.thP && e <= rp.cutP))) ep = 0.f;
         float wk;
@@ -141,7 +161,7 @@ template <bool BF16, bool FILT = false>
 __device__ __forceinline__ float chunk_weights(const RowPair& rp, int64_t c, float* w)
 {
     uint4 vp, vd;
-    load_chunk_pair(rp, c, vp, vd);
+    load_chunk_pair<BF16>(rp, c, vp, vd);
     return chunk_weights_loaded<BF16, FILT>(rp, c, vp, vd, w);
 }
 
@@ -152,7 +172,7 @@ __device__ __forceinline__ double tile_weight(const RowPair& rp, int64_t tile, i
     constexpr int N = BF16 ? 8 : 4;
     uint4 vp[kTileChunks], vd[kTileChunks];
 #pragma unroll
-    for (int g = 0; g < kTileChunks; ++g) load_chunk_pair(rp, tile * (64 * kTileChunks) + g * 64 + lane, vp[g], vd[g]);
+    for (int g = 0; g < kTileChunks; ++g) load_chunk_pair<BF16>(rp, tile * (64 * kTileChunks) + g * 64 + lane, vp[g], vd[g]);
     double acc = 0.0;
 #pragma unroll
     for (int g = 0; g < kTileChunks; ++g) {
@@ -170,8 +190,8 @@ __device__ __forceinline__ void tile_weight2(const RowPair& rp, int64_t t0, int6
     uint4 vp[2][kTileChunks], vd[2][kTileChunks];
 #pragma unroll
     for (int g = 0; g < kTileChunks; ++g) {
-        load_chunk_pair(rp, t0 * (64 * kTileChunks) + g * 64 + lane, vp[0][g], vd[0][g]);
-        load_chunk_pair(rp, t1 * (64 * kTileChunks) + g * 64 + lane, vp[1][g], vd[1][g]);
+        load_chunk_pair<BF16>(rp, t0 * (64 * kTileChunks) + g * 64 + lane, vp[0][g], vd[0][g]);
+        load_chunk_pair<BF16>(rp, t1 * (64 * kTileChunks) + g * 64 + lane, vp[1][g], vd[1][g]);
     }
     double a0 = 0.0, a1 = 0.0;
 #pragma unroll
