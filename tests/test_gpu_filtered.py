@@ -218,3 +218,24 @@ def test_unsupported_combinations():
     with pytest.raises(hb.HolaError) as e:
         hb.hola_verify_ex(temperature=1.0, top_k=-1, top_p=0.5, **kw)
     assert e.value.status == hb.HOLA_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T", [0.05, 30.0])
+def test_extreme_temperatures_and_signs(dtype, T):
+    """Very peaked and very flat distributions; rows of negative-only and positive-only logits (the order keys
+    of negative floats run backwards)."""
+    rng = np.random.default_rng(17)
+    B, g, V = 6, 3, 4000
+    P = rng.normal(0, 4, (B, g + 1, V)).astype(np.float32)
+    P[1] = -np.abs(P[1]) - 1.0                                  # all negative
+    P[2] = np.abs(P[2]) + 1.0                                   # all positive
+    P[3] *= 25.0                                                # |logits| up to ~100
+    D = (P[:, :g] + rng.normal(0, 0.5, (B, g, V))).astype(np.float32)
+    if dtype == "bf16":
+        P, D = wl.f32_to_bf16_bits(P), wl.f32_to_bf16_bits(D)
+    Df = wl.as_f32(D)
+    tok = np.argmax(Df + rng.gumbel(size=Df.shape) * T, axis=-1).astype(np.int32)
+    for top_k, top_p in ((20, 0.0), (0, 0.8), (300, 0.9)):
+        got = run_filtered(P, D, tok, 3, T, -1.0, top_k, top_p)
+        compare_filtered(P, D, tok, 3, T, -1.0, top_k, top_p, got, max_listed=B)
