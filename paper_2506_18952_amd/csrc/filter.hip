@@ -62,7 +62,8 @@ struct FilterRow {
     ExpScale sc; float ref; double scale;                       // p_i = 2^(exp_arg(x_i)) * scale
 };
 
-// Calls f(x, index) for every element of the row with a logit above -inf, eight chunks per lane in flight.
+// Calls f(x, index) for every element of chunks [c_lo, c_hi) with a logit above -inf, eight chunks per lane in
+// flight.
 template <bool BF16, typename F>
 __device__ __forceinline__ void for_each_logit(const FilterRow& fr, int64_t c_lo, int64_t c_hi, F f)
 {
@@ -89,6 +90,36 @@ __device__ __forceinline__ void for_each_logit(const FilterRow& fr, int64_t c_lo
                 const float x = chunk_elem<BF16>(v[u], k);
                 if (x > -INFINITY) f(x, e);
             }
+        }
+    }
+}
+
+// The same over a sample of the row: ns chunks (at most four per thread) taken as blocks of 64 chunks (1 KB)
+// that start bstride chunks apart.
+template <bool BF16, typename F>
+__device__ __forceinline__ void for_each_sample_logit(const FilterRow& fr, int32_t ns, int32_t bstride, F f)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    uint4 v[4];
+    int32_t cc[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int32_t c = (int32_t)threadIdx.x + u * kFilterThreads;
+        cc[u] = (c >> 6) * bstride + (c & 63);
+        v[u] = make_uint4(0, 0, 0, 0);
+        if (c < ns) v[u] = fr.rowv[cc[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        if ((int32_t)threadIdx.x + u * kFilterThreads >= ns) continue;
+        const int32_t e0 = cc[u] * N - fr.head;
+        const bool edge = (cc[u] == 0) || (cc[u] == (int32_t)fr.nchunks - 1);
+#pragma unroll
+        for (int k = 0; k < N; ++k) {
+            const int32_t e = e0 + k;
+            if (edge && (e < 0 || e >= fr.V)) continue;
+            const float x = chunk_elem<BF16>(v[u], k);
+            if (x > -INFINITY) f(x, e);
         }
     }
 }
@@ -191,9 +222,9 @@ struct Cut {
 // histograms (count search only).  Every thread returns the same Cut.
 template <bool BF16, bool MASS>
 __device__ __forceinline__ Cut radix_select(FilterShared& sh, const FilterRow& fr, bool by_mass, uint64_t need,
-                                            double frac = 0.0, uint64_t* need_out = nullptr, int64_t c_end = -1)
+                                            double frac = 0.0, uint64_t* need_out = nullptr, int32_t sample_n = 0,
+                                            int32_t sample_bstride = 64)
 {
-    const int64_t c_hi = c_end < 0 ? fr.nchunks : c_end;        // c_end: search a leading part of the row only
     constexpr int KB = BF16 ? 16 : 32;
     uint32_t prefix = 0;
     int done = 0;
@@ -206,13 +237,15 @@ __device__ __forceinline__ Cut radix_select(FilterShared& sh, const FilterRow& f
         for (int i = threadIdx.x; i < nbins; i += kFilterThreads) sh.hist[i] = 0;
         __syncthreads();
         const int pshift = KB - done;
-        for_each_logit<BF16>(fr, 0, c_hi, [&](float x, int32_t) {
+        auto tally = [&](float x, int32_t) {
             const uint32_t key = order_key<BF16>(x);
             if (done == 0 || (key >> pshift) == prefix) {
                 const uint32_t bin = (key >> shift) & (uint32_t)(nbins - 1);
                 atomicAdd(&sh.hist[bin], (1ull << kMassBits) + (MASS ? mass_fixed<BF16>(fr, x) : 0ull));
             }
-        });
+        };
+        if (sample_n > 0) for_each_sample_logit<BF16>(fr, sample_n, sample_bstride, tally);   // a sample of the row only
+        else for_each_logit<BF16>(fr, 0, fr.nchunks, tally);
         __syncthreads();
         if (MASS && done == 0 && frac > 0.0) {                  // need = frac * mass of the row
             uint64_t s = 0;
@@ -450,7 +483,7 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
         }
     };
 
-    // ---- one pass on a guess.  A sample of the row (its first chunks) suggests a first-level bin below the cut:
+    // ---- one pass on a guess.  A sample of the row (32 evenly spaced blocks of 64 chunks) suggests a value below the cut:
     // for top-k the sample's k-th largest logit, which bounds the row's from below; for top-p alone the value
     // above which the sample suggests a list of about 3/8 of the capacity.  One pass then lists the
     // tokens at or above that value and totals the rest; the guess is checked afterwards (the list must hold at
@@ -460,14 +493,17 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
     bool sample_ok = false;
     float edge_v = -3.4028234e38f;                              // logits below it are not among the k largest of the row
     {
+        // 32 evenly spaced blocks of 64 chunks (vocabularies tend to put their frequent tokens first)
         const int64_t sample_chunks = fr.nchunks < 4 * kFilterThreads ? fr.nchunks : 4 * kFilterThreads;
+        int64_t sample_step = 64;
+        if (fr.nchunks > sample_chunks) sample_step = (fr.nchunks - 64) / (sample_chunks / 64 - 1) / 8 * 8;
         // top-p alone: aim at a list of about 3/8 of its capacity, i.e. that share of the sample
         uint64_t need_g = (uint64_t)p.top_k;
         if (!want_k) {
             need_g = (uint64_t)(kFilterCand * 3 / 8) * (uint64_t)sample_chunks / (uint64_t)fr.nchunks;
             if (need_g < 1) need_g = 1;
         }
-        const Cut cs = radix_select<BF16, false>(sh, fr, false, need_g, 0.0, nullptr, sample_chunks);
+        const Cut cs = radix_select<BF16, false>(sh, fr, false, need_g, 0.0, nullptr, (int32_t)sample_chunks, (int32_t)sample_step);
         const uint64_t samp = cs.cnt_above + cs.n_ties;         // sample logits at or above that value
         sample_ok = samp >= need_g;                             // else the sample has fewer finite logits than asked
         edge_v = sample_ok ? key_to_logit<BF16>(cs.key) : -3.4028234e38f;
