@@ -5,15 +5,23 @@
 // prefix of those whose probability, as a fraction of the top-k mass, reaches top_p.  Logits of -inf are never
 // kept.  The kept set is described by (theta, idx_cut): x > theta, or x == theta and index <= idx_cut.
 //
-// One workgroup of 512 threads per row.  Selection is a radix select over order-preserving integer keys of the
-// logits (16 key bits for bf16, 32 for float), 11 bits per level, most significant first.  A level builds a
-// histogram in LDS over the elements that match the key prefix found so far; an entry packs the element count
-// (22 bits) and the probability mass in fixed point (42 bits, unit 2^-40), so one 64-bit LDS atomic per element
-// serves both the by-count (top-k) and the by-mass (top-p) search, and integer addition keeps the result
-// independent of the order in which the atomics land.  Probabilities use the row's unfiltered normaliser, merged
-// from the partials of the split-row statistics kernel.  The first pass over a row comes from HBM, the others
-// find it in L2.  A last pass sums S = sum 2^y and T = sum y 2^y over x > theta (ties at theta are added in
-// closed form) and, when the cut falls inside a run of equal logits, locates the index of the last kept one.
+// One workgroup of 512 threads per row; the kernel needs nothing but the logits (no earlier statistics pass).
+// Selection is a radix select over order-preserving integer keys of the logits (16 key bits for bf16, 32 for
+// float), 11 bits per level, most significant first.  A level builds a histogram in LDS whose 64-bit entries
+// pack an element count and a probability mass in fixed point, so one integer LDS atomic per element serves both
+// the by-count (top-k) and the by-mass (top-p) search and the result does not depend on the order in which the
+// atomics land.
+//
+// Usual course, one pass over the row: an exact select on a sample (32 evenly spaced 1 KB blocks) gives a value
+// `edge` at or below the cut (top-k: the sample's k-th largest bounds the row's from below; top-p alone: a
+// guess); one streaming pass lists every token at or above the edge in LDS (key, index) and, for top-p, sums
+// the mass of the others relative to the edge; the guess is then verified (at least k listed; nucleus target
+// inside the list's mass) and the cut, the top-k mass, the nucleus, the statistics of the kept tokens (integer
+// fixed-point sums, order-independent) and the index of the last kept tie all come from radix selects over the
+// list, with masses relative to the row's largest logit.  If the guess fails or the list would exceed 4096
+// tokens: two passes (first-level histogram of the whole row, then the list), and for very large keep sets a
+// radix select with one pass over the row per level plus a pass for the statistics; those need absolute
+// probabilities, whose normaliser the first pass has already summed.
 #include "sampler_device.h"
 
 namespace hola {
@@ -22,19 +30,26 @@ constexpr int kFilterThreads = 512;
 constexpr int kFilterWaves = kFilterThreads / 64;
 constexpr int kLevelBits = 11;
 constexpr int kFilterBins = 1 << kLevelBits;
+// Histogram entries.  Whole rows: count in the top 22 bits, mass of absolute probabilities (sum <= 1) in 42 bits,
+// unit 2^-40.  Candidate list (at most 4096 tokens): count in 13 bits, mass relative to the reference of the
+// row's largest logit (each <= ~1) in 51 bits, unit 2^-38.
 constexpr int kMassBits = 42;
-constexpr uint64_t kMassMask = (1ull << kMassBits) - 1;
 constexpr double kMassUnit = 1099511627776.0;                  // 2^40
+constexpr uint64_t kMassMask = (1ull << kMassBits) - 1;
+constexpr int kListMassBits = 51;
+constexpr uint64_t kListMassMask = (1ull << kListMassBits) - 1;
+constexpr double kListMassUnit = 274877906944.0;               // 2^38
 constexpr int kFilterCand = 4096;                               // candidate list in LDS (fast path)
 
 struct FilterShared {
     unsigned long long hist[kFilterBins];
     unsigned long long cand[kFilterCand];                       // (key << 32) | index of the tokens near the top
     unsigned int ncand;
+    unsigned int kmax;                                          // largest key met at or above the edge
+    unsigned int bad;                                           // a NaN or +inf logit was met
     double red[2 * kFilterWaves];
     unsigned long long wsum[kFilterWaves];
     unsigned int wave_cnt[kFilterWaves];
-    double lse;
     unsigned int bin; unsigned long long above;                 // result of a level scan
     int idx_cut; unsigned int sb; unsigned int rank_in_sb;
 };
@@ -126,12 +141,14 @@ __device__ __forceinline__ void for_each_sample_logit(const FilterRow& fr, int32
 
 // One streaming pass that splits the row at a logit value: above(x, index) for x >= edge (edge is finite, so
 // -inf never qualifies), below(x) for the other logits above -inf when BELOW is set.  Non-temporal loads, eight
-// chunks per lane in flight; a chunk without a logit at or above the edge costs one compare per element.
+// chunks per lane in flight; a chunk without a logit at or above the edge costs one compare per element (which
+// also catches NaN; returns true if the thread met a NaN or +inf logit).
 template <bool BF16, bool BELOW, typename FA, typename FB>
-__device__ __forceinline__ void split_pass(const FilterRow& fr, float edge, FA above, FB below)
+__device__ __forceinline__ bool split_pass(const FilterRow& fr, float edge, FA above, FB below)
 {
     constexpr int N = BF16 ? 8 : 4;
     constexpr int U = 8;
+    bool bad = false;
     for (int64_t c0 = threadIdx.x; c0 < fr.nchunks; c0 += (int64_t)U * kFilterThreads) {
         uint4 v[U];
 #pragma unroll
@@ -147,34 +164,46 @@ __device__ __forceinline__ void split_pass(const FilterRow& fr, float edge, FA a
             const int32_t e0 = (int32_t)(c * N) - fr.head;
             const bool edge_chunk = (c == 0) || (c == fr.nchunks - 1);
             float x[N];
-            bool any = false;
+            bool any = false;                                   // a logit at or above the edge, or a NaN
 #pragma unroll
-            for (int k = 0; k < N; ++k) { x[k] = chunk_elem<BF16>(v[u], k); any = any || (x[k] >= edge); }
+            for (int k = 0; k < N; ++k) { x[k] = chunk_elem<BF16>(v[u], k); any = any || !(x[k] < edge); }
             if (any || BELOW) {
 #pragma unroll
                 for (int k = 0; k < N; ++k) {
                     const int32_t e = e0 + k;
                     if (edge_chunk && (e < 0 || e >= fr.V)) continue;
-                    if (x[k] >= edge) above(x[k], e);
+                    if (!(x[k] < INFINITY)) bad = true;
+                    else if (x[k] >= edge) above(x[k], e);
                     else if (BELOW && x[k] > -INFINITY) below(x[k]);
                 }
             }
         }
     }
+    return bad;
 }
 
+// Fixed-point mass of one logit: 2^(exp_arg(x)) * scale in the unit of the whole-row histograms (scale makes it
+// the absolute probability) or of the list histograms.
 template <bool BF16>
 __device__ __forceinline__ uint64_t mass_fixed(const FilterRow& fr, float x)
 {
     const double p = (double)fast_exp2(exp_arg<BF16>(x, fr.ref, fr.sc)) * fr.scale;
     return (uint64_t)(p * kMassUnit + 0.5);
 }
+template <bool BF16>
+__device__ __forceinline__ uint64_t list_mass_fixed(const FilterRow& fr, float x)
+{
+    const double p = (double)fast_exp2(exp_arg<BF16>(x, fr.ref, fr.sc)) * fr.scale;
+    return (uint64_t)(p * kListMassUnit + 0.5);
+}
 
 // Wavefront 0: walk the bins from the top and find the first one at which the running (count or mass), added
 // to what lies above the current prefix, reaches `need`.  Leaves the bin and the packed sum of the bins above
 // it in shared memory.
+template <int MB>
 __device__ __forceinline__ void scan_level(FilterShared& sh, int nbins, bool by_mass, uint64_t need)
 {
+    constexpr uint64_t kMask = (1ull << MB) - 1;
     const int lane = threadIdx.x & 63;
     const int per = nbins >= 64 ? nbins / 64 : 1;
     const int top = nbins - lane * per;                         // this lane covers bins [top - per, top)
@@ -187,7 +216,7 @@ __device__ __forceinline__ void scan_level(FilterShared& sh, int nbins, bool by_
         const uint64_t o = __shfl_up((unsigned long long)incl, d, 64);
         if (lane >= d) incl += o;
     }
-    const uint64_t val = by_mass ? (incl & kMassMask) : (incl >> kMassBits);
+    const uint64_t val = by_mass ? (incl & kMask) : (incl >> MB);
     const unsigned long long hit = __ballot(val >= need);
     // If rounding keeps the mass from reaching `need`, settle for the lowest occupied bin.
     const unsigned long long occ = __ballot(mine != 0);
@@ -200,7 +229,7 @@ __device__ __forceinline__ void scan_level(FilterShared& sh, int nbins, bool by_
             const uint64_t h = sh.hist[top - i];
             const uint64_t nx = run + h;
             if (h != 0) { last_occ = top - i; run_last = run; }
-            const uint64_t v = by_mass ? (nx & kMassMask) : (nx >> kMassBits);
+            const uint64_t v = by_mass ? (nx & kMask) : (nx >> MB);
             if (v >= need && h != 0) found = top - i; else run = nx;
         }
         if (found < 0) { found = last_occ < 0 ? 0 : last_occ; run = run_last; }
@@ -261,7 +290,7 @@ __device__ __forceinline__ Cut radix_select(FilterShared& sh, const FilterRow& f
             if (need_out) *need_out = need;
         }
         const uint64_t rest = by_mass ? (need > mass_above ? need - mass_above : 1) : need - cnt_above;
-        if (threadIdx.x < 64) scan_level(sh, nbins, by_mass, rest);
+        if (threadIdx.x < 64) scan_level<kMassBits>(sh, nbins, by_mass, rest);
         __syncthreads();
         const uint32_t bin = sh.bin;
         const uint64_t above = sh.above;
@@ -282,7 +311,8 @@ __device__ __forceinline__ Cut radix_select(FilterShared& sh, const FilterRow& f
     return cut;
 }
 
-// The same search over the candidate list in LDS: entries that satisfy pred, ordered by keyfn (KB bits).
+// The same search over the candidate list in LDS: entries that satisfy pred, ordered by keyfn (KB bits); masses
+// in the list unit.
 template <bool BF16, bool MASS, typename Pred, typename KeyFn>
 __device__ __forceinline__ Cut list_select(FilterShared& sh, const FilterRow& fr, int n, int KB, Pred pred, KeyFn keyfn,
                                            bool by_mass, uint64_t need)
@@ -304,23 +334,23 @@ __device__ __forceinline__ Cut list_select(FilterShared& sh, const FilterRow& fr
             const uint32_t key = keyfn(ent);
             if (done == 0 || (key >> pshift) == prefix) {
                 const uint32_t bin = (key >> shift) & (uint32_t)(nbins - 1);
-                atomicAdd(&sh.hist[bin], (1ull << kMassBits) + (MASS ? mass_fixed<BF16>(fr, key_to_logit<BF16>(key)) : 0ull));
+                atomicAdd(&sh.hist[bin], (1ull << kListMassBits) + (MASS ? list_mass_fixed<BF16>(fr, key_to_logit<BF16>(key)) : 0ull));
             }
         }
         __syncthreads();
         const uint64_t rest = by_mass ? (need > mass_above ? need - mass_above : 1) : need - cnt_above;
-        if (threadIdx.x < 64) scan_level(sh, nbins, by_mass, rest);
+        if (threadIdx.x < 64) scan_level<kListMassBits>(sh, nbins, by_mass, rest);
         __syncthreads();
         const uint32_t bin = sh.bin;
         const uint64_t above = sh.above;
-        cnt_above += above >> kMassBits;
-        mass_above += above & kMassMask;
+        cnt_above += above >> kListMassBits;
+        mass_above += above & kListMassMask;
         prefix = (prefix << nb) | bin;
         done += nb;
         if (done >= KB) {
             const uint64_t h = sh.hist[bin];
-            cut.n_ties = (uint32_t)(h >> kMassBits);
-            cut.f_theta = cut.n_ties ? (h & kMassMask) / cut.n_ties : 0;
+            cut.n_ties = (uint32_t)(h >> kListMassBits);
+            cut.f_theta = cut.n_ties ? (h & kListMassMask) / cut.n_ties : 0;
         }
         __syncthreads();
     }
@@ -337,7 +367,6 @@ struct FilterParams {
     float temperature;
     int32_t B, gamma, V;
     int32_t top_k; float top_p;
-    const Partial* partials; int32_t nparts;
     RowFilter* filters;
     int32_t* out_keep_count;           // [B, 2 gamma + 1] or null
 };
@@ -348,6 +377,8 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
     __shared__ FilterShared sh;
     constexpr int N = BF16 ? 8 : 4;
     constexpr int ES = BF16 ? 2 : 4;
+    constexpr int KB = BF16 ? 16 : 32;
+    constexpr int sh0 = KB - kLevelBits;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = p.gamma;
     const int rows_per_seq = 2 * g + 1;
@@ -364,19 +395,6 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
     const char* row = is_draft ? (const char*)p.draft + ((int64_t)b * g + j) * p.draft_ld * ES
                                : (const char*)p.target + ((int64_t)b * (g + 1) + j) * p.target_ld * ES;
 
-    if (wave == 0) {
-        const RowStat rs = merge_partials_wave(p.partials + slot * p.nparts, p.nparts, lane);
-        if (lane == 0) sh.lse = rs.lse;
-    }
-    __syncthreads();
-    const double lse = sh.lse;
-    RowFilter out;
-    out.lse = lse; out.H = NAN; out.theta = INFINITY; out.idx_cut = -1; out.n_keep = 0; out.pad = 0;
-    if (!(lse - lse == 0.0)) {                                  // no finite normaliser: nothing is kept
-        if (tid == 0) { p.filters[slot] = out; if (p.out_keep_count) p.out_keep_count[blockIdx.x] = 0; }
-        return;
-    }
-
     FilterRow fr;
     const uintptr_t addr = (uintptr_t)row;
     fr.head = (int32_t)((addr & 15) / ES);
@@ -384,10 +402,8 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
     fr.V = p.V;
     fr.nchunks = ((int64_t)p.V + fr.head + N - 1) / N;
     fr.sc = make_scale(kLog2e / (double)p.temperature);
-    const double L = lse / kLn2;
-    fr.ref = ref_for_norm<BF16>(L, fr.sc);
-    const double beta = ref_offset<BF16>(fr.ref, fr.sc);
-    fr.scale = exp2(-L - beta);
+    fr.ref = 0.f;
+    fr.scale = 1.0;
 
     const uint64_t kbig = ~0ull;
     const bool want_k = p.top_k > 0 && p.top_k < p.V;
@@ -399,9 +415,9 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
     int idx_cut = 0x7fffffff;                                   // every tie is kept
     double S = 0.0, T = 0.0;
 
-    // ---- decisions from a list in LDS that holds every token at or above some first-level bin (the cut among them)
-    auto decide_from_list = [&](int n, uint64_t target_abs) {
-        constexpr int KB = BF16 ? 16 : 32;
+    // ---- decisions from a list in LDS that holds every token at or above some value (the cut among them);
+    // masses and sums use fr.ref / fr.scale; target_list is the nucleus target in the list unit (top-p alone)
+    auto decide_from_list = [&](int n, uint64_t target_list) {
         auto logit_key = [](unsigned long long ent) { return (uint32_t)(ent >> 32); };
         auto every = [](unsigned long long) { return true; };
         uint64_t zk = kbig;
@@ -414,7 +430,7 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
             have_cut = true;
         }
         if (want_p) {
-            uint64_t target = target_abs;
+            uint64_t target = target_list;
             if (zk != kbig) {
                 target = (uint64_t)((double)p.top_p * (double)zk + 0.5);
                 if (target < 1) target = 1;
@@ -432,7 +448,7 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
         theta = key_to_logit<BF16>(cut.key);
         // sums over the kept tokens above theta, in fixed point so that the order of the list does not matter
         uint32_t kmax = 0;
-        for (int i = tid; i < n; i += kFilterThreads) { const uint32_t k = (uint32_t)(sh.cand[i] >> 32); kmax = k > kmax ? k : kmax; }
+        for (int i = tid; i < n; i += kFilterThreads) { const uint32_t kk = (uint32_t)(sh.cand[i] >> 32); kmax = kk > kmax ? kk : kmax; }
 #pragma unroll
         for (int m = 32; m >= 1; m >>= 1) { const uint32_t o = __shfl_xor(kmax, m, 64); kmax = o > kmax ? o : kmax; }
         if (lane == 0) sh.wave_cnt[wave] = kmax;
@@ -445,9 +461,9 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
         unsigned long long Sfix = 0;
         long long Tfix = 0;
         for (int i = tid; i < n; i += kFilterThreads) {
-            const uint32_t k = (uint32_t)(sh.cand[i] >> 32);
-            if (k > cut.key) {
-                const float y = exp_arg<BF16>(key_to_logit<BF16>(k), fr.ref, fr.sc);
+            const uint32_t kk = (uint32_t)(sh.cand[i] >> 32);
+            if (kk > cut.key) {
+                const float y = exp_arg<BF16>(key_to_logit<BF16>(kk), fr.ref, fr.sc);
                 const double ex = (double)fast_exp2(y) * up;
                 Sfix += (unsigned long long)(ex * 562949953421312.0 + 0.5);            // 2^49
                 Tfix += (long long)rint((double)y * ex * 2199023255552.0);            // 2^41
@@ -483,99 +499,180 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
         }
     };
 
-    // ---- one pass on a guess.  A sample of the row (32 evenly spaced blocks of 64 chunks) suggests a value below the cut:
-    // for top-k the sample's k-th largest logit, which bounds the row's from below; for top-p alone the value
-    // above which the sample suggests a list of about 3/8 of the capacity.  One pass then lists the
-    // tokens at or above that value and totals the rest; the guess is checked afterwards (the list must hold at
-    // least k tokens, or the nucleus target must lie inside the list's mass), so a bad guess costs a pass, never
-    // a wrong result.
-    bool solved = false;
-    bool sample_ok = false;
-    float edge_v = -3.4028234e38f;                              // logits below it are not among the k largest of the row
-    {
-        // 32 evenly spaced blocks of 64 chunks (vocabularies tend to put their frequent tokens first)
-        const int64_t sample_chunks = fr.nchunks < 4 * kFilterThreads ? fr.nchunks : 4 * kFilterThreads;
-        int64_t sample_step = 64;
-        if (fr.nchunks > sample_chunks) sample_step = (fr.nchunks - 64) / (sample_chunks / 64 - 1) / 8 * 8;
-        // top-p alone: aim at a list of about 3/8 of its capacity, i.e. that share of the sample
-        uint64_t need_g = (uint64_t)p.top_k;
-        if (!want_k) {
-            need_g = (uint64_t)(kFilterCand * 3 / 8) * (uint64_t)sample_chunks / (uint64_t)fr.nchunks;
-            if (need_g < 1) need_g = 1;
-        }
-        const Cut cs = radix_select<BF16, false>(sh, fr, false, need_g, 0.0, nullptr, (int32_t)sample_chunks, (int32_t)sample_step);
-        const uint64_t samp = cs.cnt_above + cs.n_ties;         // sample logits at or above that value
-        sample_ok = samp >= need_g;                             // else the sample has fewer finite logits than asked
-        edge_v = sample_ok ? key_to_logit<BF16>(cs.key) : -3.4028234e38f;
-        if (!(edge_v >= -3.4028234e38f)) edge_v = -3.4028234e38f;
-        const bool try_it = sample_ok && samp * (uint64_t)fr.nchunks <= (uint64_t)(kFilterCand * 3 / 4) * (uint64_t)sample_chunks;
-        if (try_it) {
-            if (tid == 0) sh.ncand = 0;
-            __syncthreads();
-            unsigned long long below = 0;                       // fixed-point mass of what is not listed (top-p alone)
-            auto to_list = [&](float x, int32_t e) {
-                const unsigned int slot = atomicAdd(&sh.ncand, 1u);
-                if (slot < (unsigned int)kFilterCand) sh.cand[slot] = ((unsigned long long)order_key<BF16>(x) << 32) | (uint32_t)e;
-            };
-            if (want_k) split_pass<BF16, false>(fr, edge_v, to_list, [](float) {});
-            else split_pass<BF16, true>(fr, edge_v, to_list, [&](float x) { below += mass_fixed<BF16>(fr, x); });
+    // ---- sample: a value at or below the cut
+    const int64_t sample_chunks = fr.nchunks < 4 * kFilterThreads ? fr.nchunks : 4 * kFilterThreads;
+    int64_t sample_step = 64;                                   // 32 evenly spaced blocks of 64 chunks
+    if (fr.nchunks > sample_chunks) sample_step = (fr.nchunks - 64) / (sample_chunks / 64 - 1) / 8 * 8;
+    uint64_t need_g = (uint64_t)p.top_k;
+    if (!want_k) {                                              // top-p alone: aim at a list of ~3/8 of its capacity
+        need_g = (uint64_t)(kFilterCand * 3 / 8) * (uint64_t)sample_chunks / (uint64_t)fr.nchunks;
+        if (need_g < 1) need_g = 1;
+    }
+    const Cut cs = radix_select<BF16, false>(sh, fr, false, need_g, 0.0, nullptr, (int32_t)sample_chunks, (int32_t)sample_step);
+    const uint64_t samp = cs.cnt_above + cs.n_ties;             // sample logits at or above that value
+    const bool sample_ok = samp >= need_g;                      // else the sample has fewer finite logits than asked
+    // edge: logits below it are not among the k largest of the row (top-k); without a usable sample every finite
+    // logit is "at or above the edge".  x_low: the sample's value, the reference of the masses of this pass.
+    const float x_low = key_to_logit<BF16>(cs.key);
+    float edge_v = sample_ok ? x_low : -3.4028234e38f;
+    if (!(edge_v >= -3.4028234e38f)) edge_v = -3.4028234e38f;
+    const bool try_list = sample_ok && samp * (uint64_t)fr.nchunks <= (uint64_t)(kFilterCand * 3 / 4) * (uint64_t)sample_chunks;
+    const bool first_pass = (want_p && !want_k) || try_list;    // with top-k no mass outside the list is needed: skip a hopeless list
+
+    // ---- first pass: list at or above the edge, largest key, and (top-p) the mass of everything else
+    const float ref_e = ref_for<BF16>(x_low, fr.sc);
+    const double beta_e = ref_offset<BF16>(ref_e, fr.sc);
+    if (tid == 0) { sh.ncand = 0; sh.kmax = 0; sh.bad = 0; }
+    __syncthreads();
+    double others = 0.0;                                        // mass, relative to the edge reference, outside the list
+    unsigned int n_all = 0;
+    bool solved = false, need_norm = false;
+    if (first_pass) {
+        uint32_t kmax_t = 0;                                    // largest key this thread met at or above the edge
+        auto to_list = [&](float x, int32_t e) {
+            const uint32_t key = order_key<BF16>(x);
+            kmax_t = key > kmax_t ? key : kmax_t;
+            const unsigned int slt = atomicAdd(&sh.ncand, 1u);
+            if (slt < (unsigned int)kFilterCand) sh.cand[slt] = ((unsigned long long)key << 32) | (uint32_t)e;
+            else if (want_p && !want_k) others += exp2((double)x * fr.sc.cstar + beta_e);   // list full: rare
+
+        };
+        bool bad;
+        if (want_p && !want_k) bad = split_pass<BF16, true>(fr, edge_v, to_list, [&](float x) { others += (double)fast_exp2(exp_arg<BF16>(x, ref_e, fr.sc)); });
+        else bad = split_pass<BF16, false>(fr, edge_v, to_list, [](float) {});   // with top-k the masses come from the list
+        if (bad) sh.bad = 1;
+        others = wave_sum(others);
 #pragma unroll
-            for (int m = 32; m >= 1; m >>= 1) below += __shfl_xor(below, m, 64);
-            if (lane == 0) sh.wsum[wave] = below;
-            __syncthreads();
-            below = 0;
-            for (int i = 0; i < kFilterWaves; ++i) below += sh.wsum[i];
-            const unsigned int n_all = sh.ncand;
-            bool ok = n_all <= (unsigned int)kFilterCand;
-            uint64_t target = 0;
-            if (want_k) {
-                ok = ok && n_all >= (unsigned int)p.top_k;
-            } else if (ok) {
-                unsigned long long lm = 0;                      // mass of the list
-                for (int i = tid; i < (int)n_all; i += kFilterThreads)
-                    lm += mass_fixed<BF16>(fr, key_to_logit<BF16>((uint32_t)(sh.cand[i] >> 32)));
-#pragma unroll
-                for (int m = 32; m >= 1; m >>= 1) lm += __shfl_xor(lm, m, 64);
-                __syncthreads();
-                if (lane == 0) sh.wsum[wave] = lm;
-                __syncthreads();
-                lm = 0;
-                for (int i = 0; i < kFilterWaves; ++i) lm += sh.wsum[i];
-                target = (uint64_t)((double)p.top_p * (double)(lm + below) + 0.5);
-                if (target < 1) target = 1;
-                ok = lm >= target;
+        for (int m = 32; m >= 1; m >>= 1) { const uint32_t o = __shfl_xor(kmax_t, m, 64); kmax_t = o > kmax_t ? o : kmax_t; }
+        if (lane == 0) { sh.red[wave] = others; sh.wave_cnt[wave] = kmax_t; }
+        __syncthreads();
+        others = 0.0;
+        for (int i = 0; i < kFilterWaves; ++i) { others += sh.red[i]; kmax_t = sh.wave_cnt[i] > kmax_t ? sh.wave_cnt[i] : kmax_t; }
+        if (tid == 0) sh.kmax = kmax_t;
+        n_all = sh.ncand;
+    }
+    const bool bad_row = first_pass && sh.bad != 0;
+    RowFilter out;
+    out.lse = NAN; out.H = NAN; out.theta = INFINITY; out.idx_cut = -1; out.n_keep = 0; out.pad = 0;
+    if (bad_row || (first_pass && n_all == 0)) {                // NaN / +inf logits, or no finite logit: nothing is kept
+        if (!bad_row) out.lse = -INFINITY;
+        if (tid == 0) { p.filters[slot] = out; if (p.out_keep_count) p.out_keep_count[blockIdx.x] = 0; }
+        return;
+    }
+    __syncthreads();
+
+    if (first_pass) {
+        const int n = (int)(n_all < (unsigned int)kFilterCand ? n_all : (unsigned int)kFilterCand);
+        // from here on masses are taken against the reference of the row's largest logit
+        fr.ref = ref_for<BF16>(key_to_logit<BF16>(sh.kmax), fr.sc);
+        fr.scale = 1.0;
+        const double beta_m = ref_offset<BF16>(fr.ref, fr.sc);
+        bool ok = n_all <= (unsigned int)kFilterCand && try_list;
+        uint64_t target_list = 0;
+        if (want_k) ok = ok && n_all >= (unsigned int)p.top_k;
+        // mass of the list (top-p): in the list unit for the nucleus target, and against the edge reference for
+        // the normaliser of the whole row
+        double list_e = 0.0;
+        unsigned long long lm = 0;
+        if (want_p) {
+            for (int i = tid; i < n; i += kFilterThreads) {
+                const float x = key_to_logit<BF16>((uint32_t)(sh.cand[i] >> 32));
+                lm += list_mass_fixed<BF16>(fr, x);
+                list_e += exp2((double)x * fr.sc.cstar + beta_e);
             }
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) lm += __shfl_xor(lm, m, 64);
+            list_e = wave_sum(list_e);
+            if (lane == 0) { sh.wsum[wave] = lm; sh.red[wave] = list_e; }
             __syncthreads();
-            if (ok) {
-                decide_from_list((int)n_all, target);
-                solved = true;
+            lm = 0; list_e = 0.0;
+            for (int i = 0; i < kFilterWaves; ++i) { lm += sh.wsum[i]; list_e += sh.red[i]; }
+            __syncthreads();
+            if (!want_k) {
+                const double others_list = others * exp2(beta_m - beta_e) * kListMassUnit;   // the rest of the row, list unit
+                target_list = (uint64_t)((double)p.top_p * ((double)lm + others_list) + 0.5);
+                if (target_list < 1) target_list = 1;
+                ok = ok && lm >= target_list;
             }
         }
+        if (ok) {
+            decide_from_list(n, target_list);
+            solved = true;
+        } else if (want_p && !want_k) {
+            // absolute probabilities for the whole-row histograms: the normaliser is what this pass summed
+            const double L = log2(list_e + others) - beta_e;    // log2-sum-exp of the row
+            fr.ref = ref_for_norm<BF16>(L, fr.sc);
+            fr.scale = exp2(-L - ref_offset<BF16>(fr.ref, fr.sc));
+        } else if (want_p) {
+            need_norm = true;
+        }
+    } else {
+        // a list that would not fit: the reference is set once the next pass has met the largest logit
+        fr.ref = ref_for<BF16>(x_low, fr.sc);
+        fr.scale = 1.0;
+        need_norm = want_p;
+    }
+    if (need_norm) {
+        // top-k with top-p after a failed guess: the whole-row histograms need absolute probabilities, so one
+        // pass sums the row's normaliser (against the edge reference; logits above it in double)
+        double tot = 0.0;
+        auto hi = [&](float x, int32_t) { tot += exp2((double)x * fr.sc.cstar + beta_e); };
+        auto lo = [&](float x) { tot += (double)fast_exp2(exp_arg<BF16>(x, ref_e, fr.sc)); };
+        const bool bad = split_pass<BF16, true>(fr, edge_v, hi, lo);
+        if (bad) sh.bad = 1;
+        tot = wave_sum(tot);
+        __syncthreads();
+        if (lane == 0) sh.red[wave] = tot;
+        __syncthreads();
+        tot = 0.0;
+        for (int i = 0; i < kFilterWaves; ++i) tot += sh.red[i];
+        if (sh.bad || !(tot > 0.0)) {
+            if (!sh.bad) out.lse = -INFINITY;
+            if (tid == 0) { p.filters[slot] = out; if (p.out_keep_count) p.out_keep_count[blockIdx.x] = 0; }
+            return;
+        }
+        const double L = log2(tot) - beta_e;
+        fr.ref = ref_for_norm<BF16>(L, fr.sc);
+        fr.scale = exp2(-L - ref_offset<BF16>(fr.ref, fr.sc));
+        __syncthreads();
     }
 
     if (!solved) {
-        // ---- otherwise pass A: first-level histogram of the whole row; the bin that holds the cut, and how many tokens lie at or above it
+        // ---- pass A: first-level histogram of the whole row (top-k: of the logits at or above the edge only);
+        // the bin that holds the cut, and how many tokens lie at or above it
         for (int i = tid; i < kFilterBins; i += kFilterThreads) sh.hist[i] = 0;
         __syncthreads();
-        {
-            constexpr int sh0 = (BF16 ? 16 : 32) - kLevelBits;
-            if (want_p && !want_k)
-                for_each_logit<BF16>(fr, 0, fr.nchunks, [&](float x, int32_t) {
-                    atomicAdd(&sh.hist[order_key<BF16>(x) >> sh0], (1ull << kMassBits) + mass_fixed<BF16>(fr, x));
-                });
-            else if (want_k && want_p)                          // logits below the sample's k-th largest cannot matter
-                split_pass<BF16, false>(fr, edge_v, [&](float x, int32_t) {
-                    atomicAdd(&sh.hist[order_key<BF16>(x) >> sh0], (1ull << kMassBits) + mass_fixed<BF16>(fr, x)); }, [](float) {});
-            else
-                split_pass<BF16, false>(fr, edge_v, [&](float x, int32_t) {
-                    atomicAdd(&sh.hist[order_key<BF16>(x) >> sh0], 1ull << kMassBits); }, [](float) {});
+        if (want_p && !want_k)
+            for_each_logit<BF16>(fr, 0, fr.nchunks, [&](float x, int32_t) {
+                atomicAdd(&sh.hist[order_key<BF16>(x) >> sh0], (1ull << kMassBits) + mass_fixed<BF16>(fr, x));
+            });
+        else if (want_p)                                        // logits below the sample's k-th largest cannot matter
+            split_pass<BF16, false>(fr, edge_v, [&](float x, int32_t) {
+                atomicAdd(&sh.hist[order_key<BF16>(x) >> sh0], (1ull << kMassBits) + mass_fixed<BF16>(fr, x)); }, [](float) {});
+        else {
+            uint32_t kmax_t = 0;
+            const bool bad = split_pass<BF16, false>(fr, edge_v, [&](float x, int32_t) {
+                const uint32_t key = order_key<BF16>(x);
+                kmax_t = key > kmax_t ? key : kmax_t;
+                atomicAdd(&sh.hist[key >> sh0], 1ull << kMassBits); }, [](float) {});
+            if (bad) sh.bad = 1;
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) { const uint32_t o = __shfl_xor(kmax_t, m, 64); kmax_t = o > kmax_t ? o : kmax_t; }
+            if (lane == 0) atomicMax(&sh.kmax, kmax_t);         // one atomic per wavefront
         }
         __syncthreads();
-        uint64_t row_total = 0;                                     // packed count and mass of the whole row
+        if (!first_pass && !want_p) {
+            if (sh.bad) {                                       // NaN / +inf logits: nothing is kept
+                if (tid == 0) { p.filters[slot] = out; if (p.out_keep_count) p.out_keep_count[blockIdx.x] = 0; }
+                return;
+            }
+            fr.ref = ref_for<BF16>(key_to_logit<BF16>(sh.kmax), fr.sc);   // the sums are taken against the largest logit
+        }
+        uint64_t row_total = 0;                                 // packed count and mass of what was tallied
         {
             uint64_t sacc = 0;
             for (int i = tid; i < kFilterBins; i += kFilterThreads) sacc += sh.hist[i];
-    #pragma unroll
+#pragma unroll
             for (int m = 32; m >= 1; m >>= 1) sacc += __shfl_xor((unsigned long long)sacc, m, 64);
             if (lane == 0) sh.wsum[wave] = sacc;
             __syncthreads();
@@ -586,7 +683,7 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
             target_p = (uint64_t)((double)p.top_p * (double)(row_total & kMassMask) + 0.5);
             if (target_p < 1) target_p = 1;
         }
-        if (wave == 0) scan_level(sh, kFilterBins, !want_k, want_k ? (uint64_t)p.top_k : target_p);
+        if (wave == 0) scan_level<kMassBits>(sh, kFilterBins, !want_k, want_k ? (uint64_t)p.top_k : target_p);
         __syncthreads();
         const uint32_t bin0 = sh.bin;
         const uint64_t n_cand = (sh.above >> kMassBits) + (sh.hist[bin0] >> kMassBits);
@@ -594,19 +691,19 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
         __syncthreads();
 
         if (fast) {
-            // ---- pass B: the tokens at or above that bin go to a list in LDS; everything else is decided there
-            constexpr int sh0 = (BF16 ? 16 : 32) - kLevelBits;
+            // ---- pass B: the tokens at or above that bin go to the list; everything else is decided there
             if (tid == 0) sh.ncand = 0;
             __syncthreads();
             for_each_logit<BF16>(fr, 0, fr.nchunks, [&](float x, int32_t e) {
                 const uint32_t key = order_key<BF16>(x);
                 if ((key >> sh0) >= bin0) {
-                    const unsigned int slot = atomicAdd(&sh.ncand, 1u);
-                    if (slot < (unsigned int)kFilterCand) sh.cand[slot] = ((unsigned long long)key << 32) | (uint32_t)e;
+                    const unsigned int slt = atomicAdd(&sh.ncand, 1u);
+                    if (slt < (unsigned int)kFilterCand) sh.cand[slt] = ((unsigned long long)key << 32) | (uint32_t)e;
                 }
             });
             __syncthreads();
-        decide_from_list((int)(sh.ncand < (unsigned int)kFilterCand ? sh.ncand : (unsigned int)kFilterCand), target_p);
+            // the whole-row target (unit 2^-40 of absolute probabilities) in the list unit (2^-38, same scale)
+            decide_from_list((int)(sh.ncand < (unsigned int)kFilterCand ? sh.ncand : (unsigned int)kFilterCand), (target_p + 2) / 4);
         } else {
             // ---- top-k: the k-th largest logit
             uint64_t zk = kbig;                                         // fixed-point mass of the top-k set (kbig: whole row)
@@ -773,7 +870,6 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
                 }
                 idx_cut = sh.idx_cut;
             }
-
         }
     }
 
@@ -782,7 +878,7 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
     out.n_keep = have_cut ? (int32_t)(cut.cnt_above + r_keep) : -1;   // -1: every finite logit
     if (S > 0.0) {
         const double lnS = log(S);
-        out.lse = lnS - beta * kLn2;
+        out.lse = lnS - ref_offset<BF16>(fr.ref, fr.sc) * kLn2;   // the sums were taken against fr.ref
         out.H = lnS - kLn2 * (T / S);
         if (out.H < 0.0) out.H = 0.0;                           // a single kept token: exactly zero
     } else {
@@ -794,15 +890,13 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
 
 hipError_t launch_filter(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                          const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
-                         int32_t top_k, float top_p, const Partial* partials, int nparts, RowFilter* filters,
-                         int32_t* out_keep_count, hipStream_t s)
+                         int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, hipStream_t s)
 {
     if (B <= 0) return hipSuccess;
-    if (nparts > 64) return hipErrorInvalidValue;
     FilterParams p{};
     p.target = target; p.draft = draft; p.target_ld = target_ld; p.draft_ld = draft_ld; p.draft_len = draft_len;
     p.temperature = temperature; p.B = B; p.gamma = gamma; p.V = V; p.top_k = top_k; p.top_p = top_p;
-    p.partials = partials; p.nparts = nparts; p.filters = filters; p.out_keep_count = out_keep_count;
+    p.filters = filters; p.out_keep_count = out_keep_count;
     const int64_t nblk = (int64_t)B * (2 * gamma + 1);
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     if (dtype == HOLA_DTYPE_BF16) hipLaunchKernelGGL((filter_kernel<true>), dim3((unsigned)nblk), dim3(kFilterThreads), 0, s, p);

@@ -228,14 +228,14 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     rs.lse_only_targets = a.target_stats_out ? 0 : 1;           // the accept stage and the sampler use only their lse
     rs.partials = w.partials;
     hipError_t e = hipSuccess;
-    if (rows > 0) { StageTimer t(0, s); e = launch_row_stats(rs, a.dtype, tune, s); }   // nothing to stream when both are supplied
+    // nothing to stream when both statistics are supplied; the filter kernel takes its own from the logits
+    if (rows > 0 && !filtered) { StageTimer t(0, s); e = launch_row_stats(rs, a.dtype, tune, s); }
     if (e != hipSuccess) return hip_fail(e, "row statistics launch");
 
     if (filtered) {
         StageTimer t(7, s);
         e = launch_filter(a.target_logits, a.draft_logits, a.dtype, tld, dld, a.draft_len, a.temperature, a.B, a.gamma, a.V,
-                          a.top_k, (a.top_p > 0.f && a.top_p < 1.f) ? a.top_p : 1.f, w.partials, nsplit * kWaves, w.filters,
-                          a.out_keep_count, s);
+                          a.top_k, (a.top_p > 0.f && a.top_p < 1.f) ? a.top_p : 1.f, w.filters, a.out_keep_count, s);
         if (e != hipSuccess) return hip_fail(e, "filter launch");
         fp.filters = w.filters;
     }

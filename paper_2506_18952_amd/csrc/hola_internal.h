@@ -131,8 +131,7 @@ hipError_t launch_literal(const FusedParams& p, const Partial* partials, int npa
 hipError_t launch_row_stats(const RowStatsParams& p, int dtype, const Tuning& t, hipStream_t s);
 hipError_t launch_filter(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                          const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
-                         int32_t top_k, float top_p, const Partial* partials, int nparts, RowFilter* filters,
-                         int32_t* out_keep_count, hipStream_t s);
+                         int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
 hipError_t launch_merge_tile_stats(const double* ts, int32_t R, int32_t nt, double* out, hipStream_t s);
 hipError_t launch_finalize_rows(const Partial* partials, int nparts, int32_t R, double* out, hipStream_t s);
