@@ -40,6 +40,7 @@ constexpr int kListMassBits = 51;
 constexpr uint64_t kListMassMask = (1ull << kListMassBits) - 1;
 constexpr double kListMassUnit = 274877906944.0;               // 2^38
 constexpr int kFilterCand = 4096;                               // candidate list in LDS (fast path)
+constexpr int kMaximaRank = 448;                                // largest rank looked up among the 512 threads' sample maxima
 
 struct FilterShared {
     unsigned long long hist[kFilterBins];
@@ -140,11 +141,12 @@ __device__ __forceinline__ void for_each_sample_logit(const FilterRow& fr, int32
 }
 
 // One streaming pass that splits the row at a logit value: above(x, index) for x >= edge (edge is finite, so
-// -inf never qualifies), below(x) for the other logits above -inf when BELOW is set.  Non-temporal loads, eight
-// chunks per lane in flight; a chunk without a logit at or above the edge costs one compare per element (which
-// also catches NaN; returns true if the thread met a NaN or +inf logit).
+// -inf never qualifies) and, when BELOW is set, below(s) with s the sum of 2^(exp_arg(x, ref_below)) over some of
+// the other logits above -inf.  Non-temporal loads, eight chunks per lane in flight; a chunk without a
+// logit at or above the edge costs one compare per element (which also catches NaN) and one call of below.
+// Returns true if the thread met a NaN or +inf logit.
 template <bool BF16, bool BELOW, typename FA, typename FB>
-__device__ __forceinline__ bool split_pass(const FilterRow& fr, float edge, FA above, FB below)
+__device__ __forceinline__ bool split_pass(const FilterRow& fr, float edge, float ref_below, FA above, FB below)
 {
     constexpr int N = BF16 ? 8 : 4;
     constexpr int U = 8;
@@ -161,25 +163,51 @@ __device__ __forceinline__ bool split_pass(const FilterRow& fr, float edge, FA a
         for (int u = 0; u < U; ++u) {
             const int64_t c = c0 + (int64_t)u * kFilterThreads;
             if (c >= fr.nchunks) continue;
-            const int32_t e0 = (int32_t)(c * N) - fr.head;
             const bool edge_chunk = (c == 0) || (c == fr.nchunks - 1);
             float x[N];
-            bool any = false;                                   // a logit at or above the edge, or a NaN
+            bool any = edge_chunk;                              // a logit at or above the edge, a NaN, or a ragged chunk
 #pragma unroll
             for (int k = 0; k < N; ++k) { x[k] = chunk_elem<BF16>(v[u], k); any = any || !(x[k] < edge); }
-            if (any || BELOW) {
+            if (any) {
+                const int32_t e0 = (int32_t)(c * N) - fr.head;
 #pragma unroll
                 for (int k = 0; k < N; ++k) {
                     const int32_t e = e0 + k;
                     if (edge_chunk && (e < 0 || e >= fr.V)) continue;
                     if (!(x[k] < INFINITY)) bad = true;
                     else if (x[k] >= edge) above(x[k], e);
-                    else if (BELOW && x[k] > -INFINITY) below(x[k]);
+                    else if (BELOW && x[k] > -INFINITY) below(fast_exp2(exp_arg<BF16>(x[k], ref_below, fr.sc)));
                 }
+            } else if (BELOW) {
+                float s = 0.f;
+#pragma unroll
+                for (int k = 0; k < N; ++k) s += fast_exp2(exp_arg<BF16>(x[k], ref_below, fr.sc));
+                if (!(s >= 0.f)) {                              // a -inf logit can turn its exponent into NaN: leave those out
+                    s = 0.f;
+#pragma unroll
+                    for (int k = 0; k < N; ++k)
+                        if (x[k] > -INFINITY) s += fast_exp2(exp_arg<BF16>(x[k], ref_below, fr.sc));
+                }
+                below(s);
             }
         }
     }
     return bad;
+}
+
+// A sum of powers of two whose exponents may lie anywhere: value = s * 2^m with m the largest exponent met.
+struct RefSum { double m, s; };
+__device__ __forceinline__ void refsum_add(RefSum& r, double y)
+{
+    if (y > r.m) { r.s = r.s * exp2(r.m - y) + 1.0; r.m = y; }
+    else r.s += exp2(y - r.m);
+}
+__device__ __forceinline__ RefSum refsum_merge(const RefSum& a, const RefSum& b)
+{
+    RefSum r;
+    r.m = fmax(a.m, b.m);
+    r.s = (r.m == -INFINITY) ? 0.0 : a.s * exp2(a.m - r.m) + b.s * exp2(b.m - r.m);
+    return r;
 }
 
 // Fixed-point mass of one logit: 2^(exp_arg(x)) * scale in the unit of the whole-row histograms (scale makes it
@@ -499,24 +527,60 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
         }
     };
 
-    // ---- sample: a value at or below the cut
+    // ---- sample: a value at or below the cut.  A row that fits the list needs none: everything is listed.
+    const int64_t row_elems = fr.nchunks * N;
+    const bool tiny = row_elems <= (int64_t)(kFilterCand * 3 / 4);
     const int64_t sample_chunks = fr.nchunks < 4 * kFilterThreads ? fr.nchunks : 4 * kFilterThreads;
     int64_t sample_step = 64;                                   // 32 evenly spaced blocks of 64 chunks
     if (fr.nchunks > sample_chunks) sample_step = (fr.nchunks - 64) / (sample_chunks / 64 - 1) / 8 * 8;
-    uint64_t need_g = (uint64_t)p.top_k;
-    if (!want_k) {                                              // top-p alone: aim at a list of ~3/8 of its capacity
-        need_g = (uint64_t)(kFilterCand * 3 / 8) * (uint64_t)sample_chunks / (uint64_t)fr.nchunks;
-        if (need_g < 1) need_g = 1;
+    bool sample_ok = false;                                     // x_low is at or below the cut (top-k) / a guess (top-p)
+    bool try_list = tiny;                                       // the list is expected to hold the cut
+    float x_low = 0.f;
+    if (!tiny) {
+        const float per_thread = (float)(sample_chunks * N) / (float)kFilterThreads;   // sample logits per thread
+        uint64_t need_g = (uint64_t)p.top_k;
+        if (!want_k) {
+            // top-p alone: the rank among the threads' maxima at which a list of ~3/8 of its capacity is expected
+            const float q = fminf(1.f, (float)(kFilterCand * 3 / 8) / (float)row_elems);
+            need_g = (uint64_t)((float)kFilterThreads * (1.f - powf(1.f - q, per_thread)) + 0.5f);
+            need_g = need_g < 1 ? 1 : (need_g > (uint64_t)kMaximaRank ? (uint64_t)kMaximaRank : need_g);
+        }
+        if (need_g <= (uint64_t)kMaximaRank) {
+            // each thread's largest sample logit: the need_g-th largest of these distinct tokens bounds the row's
+            // need_g-th largest from below, and 512 values select much faster than the whole sample
+            uint32_t km = 0;                                    // no finite logit: key 0 (never a finite logit's key)
+            for_each_sample_logit<BF16>(fr, (int32_t)sample_chunks, (int32_t)sample_step, [&](float x, int32_t) {
+                const uint32_t key = order_key<BF16>(x);
+                km = key > km ? key : km;
+            });
+            sh.cand[tid] = ((unsigned long long)km << 32) | (uint32_t)tid;
+            __syncthreads();
+            auto logit_key = [](unsigned long long ent) { return (uint32_t)(ent >> 32); };
+            auto seen = [](unsigned long long ent) { return (ent >> 32) != 0; };
+            const Cut cs = list_select<BF16, false>(sh, fr, kFilterThreads, KB, seen, logit_key, false, need_g);
+            const uint64_t got = cs.cnt_above + cs.n_ties;      // maxima at or above that value
+            sample_ok = got >= need_g;
+            if (sample_ok) {
+                x_low = key_to_logit<BF16>(cs.key);
+                // fraction of the row expected at or above x_low, from the fraction of threads that met such a logit
+                const float frac = (float)got / (float)kFilterThreads;
+                const float q = frac < 1.f ? 1.f - powf(1.f - frac, 1.f / per_thread) : 1.f;
+                try_list = q * (float)row_elems <= (float)(kFilterCand * 3 / 4);
+            }
+        } else {
+            // a large k: exact select on the whole sample
+            const Cut cs = radix_select<BF16, false>(sh, fr, false, need_g, 0.0, nullptr, (int32_t)sample_chunks, (int32_t)sample_step);
+            const uint64_t samp = cs.cnt_above + cs.n_ties;     // sample logits at or above that value
+            sample_ok = samp >= need_g;                         // else the sample has fewer finite logits than asked
+            if (sample_ok) {
+                x_low = key_to_logit<BF16>(cs.key);
+                try_list = samp * (uint64_t)fr.nchunks <= (uint64_t)(kFilterCand * 3 / 4) * (uint64_t)sample_chunks;
+            }
+        }
     }
-    const Cut cs = radix_select<BF16, false>(sh, fr, false, need_g, 0.0, nullptr, (int32_t)sample_chunks, (int32_t)sample_step);
-    const uint64_t samp = cs.cnt_above + cs.n_ties;             // sample logits at or above that value
-    const bool sample_ok = samp >= need_g;                      // else the sample has fewer finite logits than asked
     // edge: logits below it are not among the k largest of the row (top-k); without a usable sample every finite
-    // logit is "at or above the edge".  x_low: the sample's value, the reference of the masses of this pass.
-    const float x_low = key_to_logit<BF16>(cs.key);
-    float edge_v = sample_ok ? x_low : -3.4028234e38f;
-    if (!(edge_v >= -3.4028234e38f)) edge_v = -3.4028234e38f;
-    const bool try_list = sample_ok && samp * (uint64_t)fr.nchunks <= (uint64_t)(kFilterCand * 3 / 4) * (uint64_t)sample_chunks;
+    // logit is "at or above the edge".  x_low is also the reference of the masses below the edge.
+    const float edge_v = sample_ok ? x_low : -3.4028234e38f;
     const bool first_pass = (want_p && !want_k) || try_list;    // with top-k no mass outside the list is needed: skip a hopeless list
 
     // ---- first pass: list at or above the edge, largest key, and (top-p) the mass of everything else
@@ -534,12 +598,10 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
             kmax_t = key > kmax_t ? key : kmax_t;
             const unsigned int slt = atomicAdd(&sh.ncand, 1u);
             if (slt < (unsigned int)kFilterCand) sh.cand[slt] = ((unsigned long long)key << 32) | (uint32_t)e;
-            else if (want_p && !want_k) others += exp2((double)x * fr.sc.cstar + beta_e);   // list full: rare
-
         };
         bool bad;
-        if (want_p && !want_k) bad = split_pass<BF16, true>(fr, edge_v, to_list, [&](float x) { others += (double)fast_exp2(exp_arg<BF16>(x, ref_e, fr.sc)); });
-        else bad = split_pass<BF16, false>(fr, edge_v, to_list, [](float) {});   // with top-k the masses come from the list
+        if (want_p && !want_k) bad = split_pass<BF16, true>(fr, edge_v, ref_e, to_list, [&](float s) { others += (double)s; });
+        else bad = split_pass<BF16, false>(fr, edge_v, ref_e, to_list, [](float) {});   // with top-k the masses come from the list
         if (bad) sh.bad = 1;
         others = wave_sum(others);
 #pragma unroll
@@ -562,31 +624,32 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
     __syncthreads();
 
     if (first_pass) {
-        const int n = (int)(n_all < (unsigned int)kFilterCand ? n_all : (unsigned int)kFilterCand);
+        const bool complete = n_all <= (unsigned int)kFilterCand;   // every logit at or above the edge is listed
+        const int n = (int)(complete ? n_all : (unsigned int)kFilterCand);
         // from here on masses are taken against the reference of the row's largest logit
         fr.ref = ref_for<BF16>(key_to_logit<BF16>(sh.kmax), fr.sc);
         fr.scale = 1.0;
         const double beta_m = ref_offset<BF16>(fr.ref, fr.sc);
-        bool ok = n_all <= (unsigned int)kFilterCand && try_list;
+        bool ok = complete && try_list;
         uint64_t target_list = 0;
-        if (want_k) ok = ok && n_all >= (unsigned int)p.top_k;
-        // mass of the list (top-p): in the list unit for the nucleus target, and against the edge reference for
-        // the normaliser of the whole row
-        double list_e = 0.0;
+        // fewer than k listed: the guess was wrong, unless the list holds every finite logit of the row
+        if (want_k) ok = ok && (n_all >= (unsigned int)p.top_k || !sample_ok);
+        // mass of the list (top-p): in the list unit for the nucleus target, and in double for the normaliser
+        double list_m = 0.0;
         unsigned long long lm = 0;
-        if (want_p) {
+        if (want_p && complete) {
             for (int i = tid; i < n; i += kFilterThreads) {
                 const float x = key_to_logit<BF16>((uint32_t)(sh.cand[i] >> 32));
                 lm += list_mass_fixed<BF16>(fr, x);
-                list_e += exp2((double)x * fr.sc.cstar + beta_e);
+                list_m += exp2((double)x * fr.sc.cstar + beta_m);   // at most ~1 each
             }
 #pragma unroll
             for (int m = 32; m >= 1; m >>= 1) lm += __shfl_xor(lm, m, 64);
-            list_e = wave_sum(list_e);
-            if (lane == 0) { sh.wsum[wave] = lm; sh.red[wave] = list_e; }
+            list_m = wave_sum(list_m);
+            if (lane == 0) { sh.wsum[wave] = lm; sh.red[wave] = list_m; }
             __syncthreads();
-            lm = 0; list_e = 0.0;
-            for (int i = 0; i < kFilterWaves; ++i) { lm += sh.wsum[i]; list_e += sh.red[i]; }
+            lm = 0; list_m = 0.0;
+            for (int i = 0; i < kFilterWaves; ++i) { lm += sh.wsum[i]; list_m += sh.red[i]; }
             __syncthreads();
             if (!want_k) {
                 const double others_list = others * exp2(beta_m - beta_e) * kListMassUnit;   // the rest of the row, list unit
@@ -598,13 +661,13 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
         if (ok) {
             decide_from_list(n, target_list);
             solved = true;
-        } else if (want_p && !want_k) {
+        } else if (want_p && !want_k && complete) {
             // absolute probabilities for the whole-row histograms: the normaliser is what this pass summed
-            const double L = log2(list_e + others) - beta_e;    // log2-sum-exp of the row
+            const double L = log2(list_m + others * exp2(beta_m - beta_e)) - beta_m;   // log2-sum-exp of the row
             fr.ref = ref_for_norm<BF16>(L, fr.sc);
             fr.scale = exp2(-L - ref_offset<BF16>(fr.ref, fr.sc));
         } else if (want_p) {
-            need_norm = true;
+            need_norm = true;                                   // a list that overflowed did not see every mass
         }
     } else {
         // a list that would not fit: the reference is set once the next pass has met the largest logit
@@ -613,25 +676,45 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
         need_norm = want_p;
     }
     if (need_norm) {
-        // top-k with top-p after a failed guess: the whole-row histograms need absolute probabilities, so one
-        // pass sums the row's normaliser (against the edge reference; logits above it in double)
-        double tot = 0.0;
-        auto hi = [&](float x, int32_t) { tot += exp2((double)x * fr.sc.cstar + beta_e); };
-        auto lo = [&](float x) { tot += (double)fast_exp2(exp_arg<BF16>(x, ref_e, fr.sc)); };
-        const bool bad = split_pass<BF16, true>(fr, edge_v, hi, lo);
+        // the whole-row histograms need absolute probabilities, so one pass sums the row's normaliser: logits
+        // below the edge against the edge reference, the others (which may lie far above it) against their own
+        // running maximum
+        double lo_sum = 0.0;
+        RefSum hi_sum{-INFINITY, 0.0};
+        auto hi = [&](float x, int32_t) { refsum_add(hi_sum, (double)x * fr.sc.cstar); };
+        auto lo = [&](float s) { lo_sum += (double)s; };
+        const bool bad = split_pass<BF16, true>(fr, edge_v, ref_e, hi, lo);
         if (bad) sh.bad = 1;
-        tot = wave_sum(tot);
+        lo_sum = wave_sum(lo_sum);
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            RefSum o;
+            o.m = __shfl_xor(hi_sum.m, m, 64);
+            o.s = __shfl_xor(hi_sum.s, m, 64);
+            hi_sum = refsum_merge(hi_sum, o);
+        }
         __syncthreads();
-        if (lane == 0) sh.red[wave] = tot;
+        if (lane == 0) { sh.red[wave] = lo_sum; sh.red[kFilterWaves + wave] = hi_sum.m; sh.wsum[wave] = (unsigned long long)__double_as_longlong(hi_sum.s); }
         __syncthreads();
-        tot = 0.0;
-        for (int i = 0; i < kFilterWaves; ++i) tot += sh.red[i];
-        if (sh.bad || !(tot > 0.0)) {
+        lo_sum = 0.0;
+        hi_sum.m = -INFINITY; hi_sum.s = 0.0;
+        for (int i = 0; i < kFilterWaves; ++i) {
+            lo_sum += sh.red[i];
+            RefSum o;
+            o.m = sh.red[kFilterWaves + i];
+            o.s = __longlong_as_double((long long)sh.wsum[i]);
+            hi_sum = refsum_merge(hi_sum, o);
+        }
+        if (sh.bad || !(lo_sum > 0.0 || hi_sum.s > 0.0)) {
             if (!sh.bad) out.lse = -INFINITY;
             if (tid == 0) { p.filters[slot] = out; if (p.out_keep_count) p.out_keep_count[blockIdx.x] = 0; }
             return;
         }
-        const double L = log2(tot) - beta_e;
+        // log2-sum-exp of the row from the two parts
+        const double la = hi_sum.s > 0.0 ? hi_sum.m + log2(hi_sum.s) : -INFINITY;
+        const double lb = lo_sum > 0.0 ? log2(lo_sum) - beta_e : -INFINITY;
+        const double lmax = fmax(la, lb), lmin = fmin(la, lb);
+        const double L = lmax + log2(1.0 + exp2(lmin - lmax));
         fr.ref = ref_for_norm<BF16>(L, fr.sc);
         fr.scale = exp2(-L - ref_offset<BF16>(fr.ref, fr.sc));
         __syncthreads();
@@ -647,11 +730,11 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
                 atomicAdd(&sh.hist[order_key<BF16>(x) >> sh0], (1ull << kMassBits) + mass_fixed<BF16>(fr, x));
             });
         else if (want_p)                                        // logits below the sample's k-th largest cannot matter
-            split_pass<BF16, false>(fr, edge_v, [&](float x, int32_t) {
+            split_pass<BF16, false>(fr, edge_v, ref_e, [&](float x, int32_t) {
                 atomicAdd(&sh.hist[order_key<BF16>(x) >> sh0], (1ull << kMassBits) + mass_fixed<BF16>(fr, x)); }, [](float) {});
         else {
             uint32_t kmax_t = 0;
-            const bool bad = split_pass<BF16, false>(fr, edge_v, [&](float x, int32_t) {
+            const bool bad = split_pass<BF16, false>(fr, edge_v, ref_e, [&](float x, int32_t) {
                 const uint32_t key = order_key<BF16>(x);
                 kmax_t = key > kmax_t ? key : kmax_t;
                 atomicAdd(&sh.hist[key >> sh0], 1ull << kMassBits); }, [](float) {});

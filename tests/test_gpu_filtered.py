@@ -115,9 +115,10 @@ FILTERS = [(50, 0.0), (0, 0.9), (40, 0.8), (1, 0.0), (0, 0.05), (0, 0.999), (100
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V", [3001, 9001])                    # a row the candidate list holds whole / one that needs the sample
 @pytest.mark.parametrize("top_k,top_p", FILTERS)
-def test_small_cases(dtype, top_k, top_p):
-    w = wl.small_case(12, 4, 3001, dtype=dtype, temperature=0.8, case_id=300 + top_k % 7)
+def test_small_cases(dtype, top_k, top_p, V):
+    w = wl.small_case(12, 4, V, dtype=dtype, temperature=0.8, case_id=300 + top_k % 7)
     for tau in (-1.0, 0.3 * math.log(w.V)):
         got = run_filtered(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, top_k, top_p)
         listed, dh, ref = compare_filtered(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, top_k, top_p, got)
@@ -239,3 +240,50 @@ def test_extreme_temperatures_and_signs(dtype, T):
     for top_k, top_p in ((20, 0.0), (0, 0.8), (300, 0.9)):
         got = run_filtered(P, D, tok, 3, T, -1.0, top_k, top_p)
         compare_filtered(P, D, tok, 3, T, -1.0, top_k, top_p, got, max_listed=B)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_largest_logit_far_above_the_sampled_values(dtype):
+    """Rows whose sampled values say nothing about the top: thousands of equal logits (the candidate list overflows
+    and the kernel falls back to whole-row histograms, which need the row's normaliser) and a lone logit far above
+    them.  At T = 0.01 that logit's term is 2^1440 times the others': the normaliser must
+    not overflow."""
+    rng = np.random.default_rng(23)
+    B, g, V = 3, 2, 70000
+    P = np.full((B, g + 1, V), -10.0, np.float32)
+    D = np.full((B, g, V), -10.0, np.float32)
+    for a in (P, D):
+        for b in range(B):
+            for j in range(a.shape[1]):
+                a[b, j, rng.choice(V, 5000, replace=False)] = 0.0
+                a[b, j, 77 + 1000 * b + j] = 10.0
+                a[b, j, rng.choice(V, 50, replace=False)] = rng.normal(0, 3, 50).astype(np.float32)
+    tok = np.stack([np.array([77 + 1000 * b + j for j in range(g)]) for b in range(B)]).astype(np.int32)
+    if dtype == "bf16":
+        P, D = wl.f32_to_bf16_bits(P), wl.f32_to_bf16_bits(D)
+    for T in (0.01, 1.0):
+        # at T = 1 one drafted token lies outside q~'s keep set (rejected unless p~ keeps it).  Not at T = 0.01:
+        # there p~ and q~ are the same one-hot up to 1e-100, a rejection has that probability, and the residual
+        # it would sample from is pure cancellation, which no float32 term can resolve
+        tok[1, 0] = 5 if T == 1.0 else 1077
+        for top_k, top_p in ((300, 0.5), (0, 0.5), (0, 0.9999), (6000, 0.0), (6000, 0.99)):
+            got = run_filtered(P, D, tok, 11, T, -1.0, top_k, top_p)
+            compare_filtered(P, D, tok, 11, T, -1.0, top_k, top_p, got, max_listed=B)
+
+
+def test_rows_with_fewer_finite_logits_than_top_k():
+    """Small and large rows that are mostly -inf: everything finite is kept."""
+    rng = np.random.default_rng(29)
+    for V in (2000, 40000):
+        B, g = 3, 2
+        P = np.full((B, g + 1, V), -np.inf, np.float32)
+        D = np.full((B, g, V), -np.inf, np.float32)
+        idx = rng.choice(V, 30, replace=False)
+        P[..., idx] = rng.normal(0, 2, (B, g + 1, 30)).astype(np.float32)
+        D[..., idx] = rng.normal(0, 2, (B, g, 30)).astype(np.float32)
+        tok = idx[rng.integers(0, 30, (B, g))].astype(np.int32)
+        for top_k, top_p in ((100, 0.0), (100, 0.9), (0, 0.9), (10, 0.0)):
+            got = run_filtered(P, D, tok, 13, 0.9, -1.0, top_k, top_p)
+            compare_filtered(P, D, tok, 13, 0.9, -1.0, top_k, top_p, got, max_listed=B)
+            if top_k == 100 and top_p == 0.0:
+                assert np.all(got[3] == 30)
