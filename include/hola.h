@@ -250,6 +250,9 @@ typedef struct {
                                        only; the fused kernel then uses 8), 8 or 16; 0: 16 for the fused
                                        kernel, and for the tail kernel 16 / 8 / 4 as the batch grows past
                                        one / three sequences per compute unit */
+    int32_t filter_path;            /* top-k / top-p keep sets.  0: a split-row scan lists the candidates of every
+                                       row, one wavefront per row decides, and only rows that step cannot settle
+                                       go to the one-workgroup-per-row kernel; 1: that kernel for every row */
 } hola_tuning;
 hola_status hola_set_tuning(const hola_tuning* t /* host; NULL restores defaults */);
 

@@ -72,7 +72,7 @@ class HsdArgs(C.Structure):
 
 class Tuning(C.Structure):
     _fields_ = [("stats_split", C.c_int32), ("stats_unroll", C.c_int32), ("path", C.c_int32),
-                ("fused_waves", C.c_int32)]
+                ("fused_waves", C.c_int32), ("filter_path", C.c_int32)]
 
 
 _lib: Optional[C.CDLL] = None
@@ -302,8 +302,9 @@ def hola_merge_tile_stats(tile_stats, R, ntiles, stats_out, stream=None) -> None
 PATH_AUTO, PATH_SPLIT, PATH_FUSED, PATH_SPLIT4 = 0, 1, 2, 3
 
 
-def hola_set_tuning(stats_split: int = 0, stats_unroll: int = 0, path: int = 0, fused_waves: int = 0) -> None:
-    t = Tuning(int(stats_split), int(stats_unroll), int(path), int(fused_waves))
+def hola_set_tuning(stats_split: int = 0, stats_unroll: int = 0, path: int = 0, fused_waves: int = 0,
+                    filter_path: int = 0) -> None:
+    t = Tuning(int(stats_split), int(stats_unroll), int(path), int(fused_waves), int(filter_path))
     _check(lib().hola_set_tuning(C.byref(t)), "hola_set_tuning")
 
 

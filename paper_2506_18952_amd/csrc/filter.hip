@@ -22,7 +22,7 @@
 // tokens: two passes (first-level histogram of the whole row, then the list), and for very large keep sets a
 // radix select with one pass over the row per level plus a pass for the statistics; those need absolute
 // probabilities, whose normaliser the first pass has already summed.
-#include "sampler_device.h"
+#include "filter_device.h"
 
 namespace hola {
 
@@ -36,9 +36,6 @@ constexpr int kFilterBins = 1 << kLevelBits;
 constexpr int kMassBits = 42;
 constexpr double kMassUnit = 1099511627776.0;                  // 2^40
 constexpr uint64_t kMassMask = (1ull << kMassBits) - 1;
-constexpr int kListMassBits = 51;
-constexpr uint64_t kListMassMask = (1ull << kListMassBits) - 1;
-constexpr double kListMassUnit = 274877906944.0;               // 2^38
 constexpr int kFilterCand = 4096;                               // candidate list in LDS (fast path)
 constexpr int kMaximaRank = 448;                                // largest rank looked up among the 512 threads' sample maxima
 
@@ -53,29 +50,6 @@ struct FilterShared {
     unsigned int wave_cnt[kFilterWaves];
     unsigned int bin; unsigned long long above;                 // result of a level scan
     int idx_cut; unsigned int sb; unsigned int rank_in_sb;
-};
-
-// Order-preserving key of a logit (larger logit, larger key); -0 and +0 share a key.
-template <bool BF16>
-__device__ __forceinline__ uint32_t order_key(float x)
-{
-    if (x == 0.f) x = 0.f;
-    const uint32_t b = __float_as_uint(x);
-    const uint32_t k = b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u);
-    return BF16 ? (k >> 16) : k;
-}
-template <bool BF16>
-__device__ __forceinline__ float key_to_logit(uint32_t key)
-{
-    const uint32_t k = BF16 ? (key << 16) : key;
-    uint32_t b = (k >> 31) ? (k ^ 0x80000000u) : ~k;
-    if (BF16) b &= 0xffff0000u;                                 // the low half of a widened bf16 is zero
-    return __uint_as_float(b);
-}
-
-struct FilterRow {
-    const uint4* rowv; int32_t head, V; int64_t nchunks;
-    ExpScale sc; float ref; double scale;                       // p_i = 2^(exp_arg(x_i)) * scale
 };
 
 // Calls f(x, index) for every element of chunks [c_lo, c_hi) with a logit above -inf, eight chunks per lane in
@@ -218,13 +192,6 @@ __device__ __forceinline__ uint64_t mass_fixed(const FilterRow& fr, float x)
     const double p = (double)fast_exp2(exp_arg<BF16>(x, fr.ref, fr.sc)) * fr.scale;
     return (uint64_t)(p * kMassUnit + 0.5);
 }
-template <bool BF16>
-__device__ __forceinline__ uint64_t list_mass_fixed(const FilterRow& fr, float x)
-{
-    const double p = (double)fast_exp2(exp_arg<BF16>(x, fr.ref, fr.sc)) * fr.scale;
-    return (uint64_t)(p * kListMassUnit + 0.5);
-}
-
 // Wavefront 0: walk the bins from the top and find the first one at which the running (count or mass), added
 // to what lies above the current prefix, reaches `need`.  Leaves the bin and the packed sum of the bins above
 // it in shared memory.
@@ -397,6 +364,7 @@ struct FilterParams {
     int32_t top_k; float top_p;
     RowFilter* filters;
     int32_t* out_keep_count;           // [B, 2 gamma + 1] or null
+    const int32_t* flags;              // [B (2 gamma + 1)] or null: only rows flagged 1 are done here
 };
 
 template <bool BF16>
@@ -408,6 +376,7 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
     constexpr int KB = BF16 ? 16 : 32;
     constexpr int sh0 = KB - kLevelBits;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (p.flags && !p.flags[blockIdx.x]) return;                // settled by the scan (uniform exit)
     const int g = p.gamma;
     const int rows_per_seq = 2 * g + 1;
     const int b = blockIdx.x / rows_per_seq, k = blockIdx.x % rows_per_seq;
@@ -973,13 +942,20 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
 
 hipError_t launch_filter(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                          const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
-                         int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, hipStream_t s)
+                         int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scan_scratch,
+                         hipStream_t s)
 {
     if (B <= 0) return hipSuccess;
+    int32_t* flags = nullptr;
+    if (scan_scratch && filter_scan_applies(dtype, V, top_k)) {
+        const hipError_t e = launch_filter_scan(target, draft, dtype, target_ld, draft_ld, draft_len, temperature, B, gamma, V,
+                                                top_k, top_p, filters, out_keep_count, scan_scratch, &flags, s);
+        if (e != hipSuccess) return e;
+    }
     FilterParams p{};
     p.target = target; p.draft = draft; p.target_ld = target_ld; p.draft_ld = draft_ld; p.draft_len = draft_len;
     p.temperature = temperature; p.B = B; p.gamma = gamma; p.V = V; p.top_k = top_k; p.top_p = top_p;
-    p.filters = filters; p.out_keep_count = out_keep_count;
+    p.filters = filters; p.out_keep_count = out_keep_count; p.flags = flags;
     const int64_t nblk = (int64_t)B * (2 * gamma + 1);
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     if (dtype == HOLA_DTYPE_BF16) hipLaunchKernelGGL((filter_kernel<true>), dim3((unsigned)nblk), dim3(kFilterThreads), 0, s, p);

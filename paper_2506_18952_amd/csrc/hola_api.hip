@@ -130,6 +130,8 @@ static Workspace carve(void* base, int32_t B, int32_t gamma, int32_t V)
     w.seq = (SeqInfo*)(p + off);      off = align_up(off + (size_t)B * sizeof(SeqInfo));
     w.tiles = (double*)(p + off);     off = align_up(off + (size_t)B * ntiles * sizeof(double));
     w.filters = (RowFilter*)(p + off); off = align_up(off + rows * sizeof(RowFilter));
+    const size_t scan_bytes = filter_scan_bytes((int64_t)rows, V);
+    w.filter_scan = scan_bytes ? p + off : nullptr; off = align_up(off + scan_bytes);
     w.bytes = off;
     return w;
 }
@@ -235,7 +237,8 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     if (filtered) {
         StageTimer t(7, s);
         e = launch_filter(a.target_logits, a.draft_logits, a.dtype, tld, dld, a.draft_len, a.temperature, a.B, a.gamma, a.V,
-                          a.top_k, (a.top_p > 0.f && a.top_p < 1.f) ? a.top_p : 1.f, w.filters, a.out_keep_count, s);
+                          a.top_k, (a.top_p > 0.f && a.top_p < 1.f) ? a.top_p : 1.f, w.filters, a.out_keep_count,
+                          tune.filter_path == 1 ? nullptr : w.filter_scan, s);
         if (e != hipSuccess) return hip_fail(e, "filter launch");
         fp.filters = w.filters;
     }
@@ -644,7 +647,9 @@ hola_status hola_set_tuning(const hola_tuning* t)
             return HOLA_ERR_INVALID_ARG;
         if (t->path < 0 || t->path > 3) return HOLA_ERR_INVALID_ARG;
         if (t->fused_waves != 0 && t->fused_waves != 4 && t->fused_waves != 8 && t->fused_waves != 16) return HOLA_ERR_INVALID_ARG;
+        if (t->filter_path < 0 || t->filter_path > 1) return HOLA_ERR_INVALID_ARG;
         n.split = t->stats_split; n.unroll = t->stats_unroll; n.path = t->path; n.fused_waves = t->fused_waves;
+        n.filter_path = t->filter_path;
     }
     std::lock_guard<std::mutex> lk(g_mu);
     g_tuning = n;

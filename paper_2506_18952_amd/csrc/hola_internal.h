@@ -55,6 +55,7 @@ struct Workspace {
     SeqInfo* seq;                      // [B]
     double* tiles;                     // [B, ntiles]
     RowFilter* filters;                // [(B*gamma) + B*(gamma+1)], filtered calls only
+    void* filter_scan;                 // candidate lists, counters, flags and segment records of the filter scan
     size_t bytes;
 };
 
@@ -62,6 +63,7 @@ struct Tuning {
     int split = 0, unroll = 0;
     int path = 0;                      // 0 auto, 1 split rows + tail kernel, 2 fused kernel, 3 split rows + 3 kernels
     int fused_waves = 0;               // 0 (= 16), 8 or 16 wavefronts per workgroup in the fused kernel
+    int filter_path = 0;               // 1: the per-row filter kernel for every row
 };
 
 struct RowStatsParams {
@@ -131,7 +133,16 @@ hipError_t launch_literal(const FusedParams& p, const Partial* partials, int npa
 hipError_t launch_row_stats(const RowStatsParams& p, int dtype, const Tuning& t, hipStream_t s);
 hipError_t launch_filter(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                          const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
-                         int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, hipStream_t s);
+                         int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scan_scratch,
+                         hipStream_t s);
+// The usual course of the filter: a split-row scan that lists candidates and a per-row decide step; rows it
+// cannot settle come back flagged in *flags_out ([B (2 gamma + 1)], 1 = still to do).
+size_t filter_scan_bytes(int64_t rows, int32_t V);
+bool filter_scan_applies(int dtype, int32_t V, int32_t top_k);
+hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
+                              const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
+                              int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch,
+                              int32_t** flags_out, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
 hipError_t launch_merge_tile_stats(const double* ts, int32_t R, int32_t nt, double* out, hipStream_t s);
 hipError_t launch_finalize_rows(const Partial* partials, int nparts, int32_t R, double* out, hipStream_t s);

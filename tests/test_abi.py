@@ -40,7 +40,10 @@ def test_workspace_bytes():
     assert hb.hola_workspace_bytes(-1, 4, 100) == 0
     a, b, c = (hb.hola_workspace_bytes(*s) for s in ((8, 4, 1000), (16, 4, 1000), (16, 8, 128256)))
     assert a < b < c
-    assert hb.hola_workspace_bytes(256, 8, 128256) < 64 << 20
+    # the headline shape: ~9 MB of partial sums plus 16 KB of candidate list per row for filtered calls
+    assert hb.hola_workspace_bytes(256, 8, 128256) < 96 << 20
+    # the candidate lists are left out (and the per-row filter kernel used) before they pass 256 MB
+    assert hb.hola_workspace_bytes(8192, 8, 128256) < hb.hola_workspace_bytes(256, 8, 128256) * 32
     assert hb.hola_hsd_workspace_bytes(3, 128, 8, 151936) > hb.hola_workspace_bytes(128, 9, 151936)
     assert hb.hola_hsd_workspace_bytes(1, 8, 4, 100) == 0    # needs at least two models
     assert hb.hola_hsd_workspace_bytes(3, 8, 32, 100) == 0   # gamma grows past the limit
