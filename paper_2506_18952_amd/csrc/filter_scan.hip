@@ -3,19 +3,24 @@
 // wavefront per row decides the cut from that list.  Rows it cannot settle (a list that overflowed, a nucleus
 // that reaches beyond the list, NaN or +inf logits) are flagged and left to the one-workgroup-per-row kernel.
 //
-// Scan: a workgroup of NT threads owns one segment of NT x 8 chunks of a row and holds it in registers.  Each
-// thread takes the largest of its (up to 64) logits; the rank-th largest of these maxima, found by wavefront 0
-// with a bit-by-bit radix descent on ballots, is at or below the rank-th largest logit of the segment, hence of
-// the row: with rank = top_k no token below this edge is among the row's k largest.  (Top-p alone has no such
-// bound; the rank is chosen so that the lists of a row hold a few hundred tokens, and the decide step checks that
-// the nucleus ends at or above every segment's edge.)  Tokens at or above the edge go to the row's list in global memory as
-// (key << 32 | index), one atomic add on the row's counter per wavefront; for top-p alone the segment also
-// leaves the mass of its other tokens, relative to the edge.
+// Scan: a workgroup of 256 threads owns one segment of up to 256 x 8 chunks of a row (the row's chunks are
+// shared evenly by its segments) and holds it in registers.  Each thread takes the largest logit of each of its
+// chunks and of all of them (bf16: on 16-bit order keys, two per packed operation).  Each wavefront then finds,
+// by a bit-by-bit radix descent on ballots, the r-th largest of its lanes' maxima, r being the wavefront's share
+// of a rank; the lowest of the wavefronts' values, the edge, has at least `rank` distinct tokens of the segment
+// at or above it.  With rank = top_k no token below the edge is among the row's k largest.  (Top-p alone has no
+// such bound: the rank is chosen so that the lists of a row hold a few hundred tokens, and the decide step checks
+// that the nucleus ends at or above every segment's edge.)  Chunks whose maximum reaches the edge are few, but
+// nearly every wavefront has some: it packs them into shared memory and examines their elements with all lanes
+// busy.  Tokens at or above the edge go to the segment's own part of the row's list in global memory as
+// (key << 32 | index); the segment reports their number, its edge, whether it met NaN / +inf, and for top-p alone
+// the mass of its other tokens relative to the edge.  No global atomics, nothing to clear beforehand.
 //
-// Decide: the wavefront holds the list in registers (16 entries per lane) and finds the k-th largest key, the key
-// at which the cumulative mass reaches the nucleus target, and the index of the last kept tie by radix descents
-// over ballots and wavefront sums: no shared memory, no barrier.  Sums over the kept tokens are integers in
-// fixed point, so neither the order of the list nor the number of segments changes a bit of the result.
+// Decide: the wavefront holds the row's list in registers (up to 16 entries per lane) and finds the k-th largest
+// key, the key at which the cumulative mass reaches the nucleus target, and the index of the last kept tie by
+// radix descents over ballots and wavefront sums, skipping the key bits on which all entries agree.  Sums over
+// the kept tokens are integers in fixed point, so neither the order of the list nor the number of segments
+// changes a bit of the result.
 #include "filter_device.h"
 
 namespace hola {
@@ -29,7 +34,7 @@ constexpr int kScanCap = 64 * kScanSlots;                       // list entries 
 constexpr int kScanStore = 2 * kScanCap;                        // list entries per row in memory, shared evenly by its segments
 constexpr int kScanMaxSeg = 16;                                 // segments per row (64 list entries each at least)
 constexpr int kScanTiny = kScanCap * 3 / 4;                     // rows up to this many elements are listed whole
-constexpr int kScanTopPList = kScanCap / 2;                     // list size aimed at for top-p alone
+constexpr int kScanTopPList = kScanCap * 5 / 8;                 // list size aimed at for top-p alone (measured: 512 .. 640 alike, 768 spills)
 
 struct SegInfo {
     double others;                     // mass of the segment's tokens below its edge, relative to ref_for(edge)
@@ -635,27 +640,36 @@ __global__ __launch_bounds__(64) void filter_decide_kernel(ScanParams p)
     }
     const float theta = key_to_logit<BF16>(cut_key);
 
-    // ---- sums over the kept tokens above theta in fixed point, the kept ties added once
-    const float y_top = exp_arg<BF16>(key_to_logit<BF16>(kmax), fr.ref, fr.sc);
+    // ---- sums over the kept tokens above theta, the kept ties added once.  Each term is a float (the library's
+    // terms 2^y are) and is added as an integer in fixed point, so the order of the list does not matter: a float
+    // below 2^31 splits exactly into its integer part and a remainder that the second conversion takes.
+    const float y_top = exp_arg<BF16>(key_to_logit<BF16>(kmax), fr.ref, fr.sc);   // near 0: the reference is the largest logit's
     int sft = (int)floorf(-y_top);
-    sft = sft < -60 ? -60 : (sft > 900 ? 900 : sft);
-    const double up = ldexp(1.0, sft);
-    unsigned long long Sfix = 0;
-    long long Tfix = 0;
+    sft = sft < -8 ? -8 : (sft > 8 ? 8 : sft);
+    unsigned long long Sfix = 0;                                // unit 2^-52 (each term < 2)
+    long long Tfix = 0;                                         // unit 2^-42 (|y 2^y| < 2^9 for a term that does not underflow)
 #pragma unroll
     for (int j = 0; j < E; ++j) {
         const uint32_t kk = logit_key(ent[j]);
         if (j < nslots && valid(ent[j]) && kk > cut_key) {
             const float y = exp_arg<BF16>(key_to_logit<BF16>(kk), fr.ref, fr.sc);
-            const double ex = (double)fast_exp2(y) * up;
-            Sfix += (unsigned long long)(ex * 562949953421312.0 + 0.5);            // 2^49
-            Tfix += (long long)rint((double)y * ex * 2199023255552.0);            // 2^41
+            const float ex = ldexpf(fast_exp2(y), sft);
+            const float a = ex * 1048576.f;                     // 2^20
+            const uint32_t a_hi = (uint32_t)a;
+            const uint32_t a_lo = (uint32_t)((a - (float)a_hi) * 4294967296.f);
+            Sfix += ((unsigned long long)a_hi << 32) | a_lo;
+            const float pt = y * ex;
+            const float bq = fabsf(pt) * 1024.f;                // 2^10
+            const uint32_t b_hi = (uint32_t)bq;
+            const uint32_t b_lo = (uint32_t)((bq - (float)b_hi) * 4294967296.f);
+            const long long mag = (long long)(((unsigned long long)b_hi << 32) | b_lo);
+            Tfix += pt < 0.f ? -mag : mag;
         }
     }
     Sfix = wave_sum_u64(Sfix);
     Tfix = (long long)wave_sum_u64((unsigned long long)Tfix);
-    double S = ldexp((double)Sfix, -49 - sft);
-    double T = ldexp((double)Tfix, -41 - sft);
+    double S = ldexp((double)Sfix, -52 - sft);
+    double T = ldexp((double)Tfix, -42 - sft);
     if (r_keep > 0) {
         const float y = exp_arg<BF16>(theta, fr.ref, fr.sc);
         const double ex = (double)fast_exp2(y);
@@ -663,9 +677,33 @@ __global__ __launch_bounds__(64) void filter_decide_kernel(ScanParams p)
         T += (double)r_keep * ((double)y * ex);
     }
 
-    // ---- the last kept tie: the r-th smallest index among the ties = the r-th largest complemented index
+    // ---- the last kept tie: the r-th smallest index among the ties
     int idx_cut = 0x7fffffff;                                   // every tie is kept
-    if (r_keep < n_ties) {
+    if (r_keep < n_ties && n_ties <= 64) {
+        // few ties (the usual case): their indices go to shared memory, lane l counts those below the l-th
+        __shared__ uint32_t s_tie[64];
+        int nt = 0;
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+            if (j < nslots) {
+                const bool tie = valid(ent[j]) && logit_key(ent[j]) == cut_key;
+                const unsigned long long bl = __ballot(tie);
+                if (bl) {
+                    const int at = nt + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bl >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bl, 0u));
+                    if (tie) s_tie[at] = (uint32_t)(ent[j] & 0xffffffffu);
+                    nt += (int)__popcll(bl);
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t mine = lane < (int)n_ties ? s_tie[lane] : 0xffffffffu;
+        uint32_t below = 0;
+        for (int q = 0; q < (int)n_ties; ++q) below += s_tie[q] < mine ? 1u : 0u;
+        const unsigned long long hit = __ballot(lane < (int)n_ties && (unsigned long long)below + 1 == r_keep);
+        const int src = hit ? __ffsll((long long)hit) - 1 : 0;
+        idx_cut = (int)__shfl(mine, src, 64);
+    } else if (r_keep < n_ties) {
+        // long runs of equal logits: the r-th largest complemented index by radix descent
         const uint32_t tkey = cut_key;
         auto is_tie = [tkey](unsigned long long e) { return e != 0 && (uint32_t)(e >> 32) == tkey; };
         auto inv_index = [](unsigned long long e) { return 0x3fffffu - (uint32_t)(e & 0xffffffffu); };

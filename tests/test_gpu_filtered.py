@@ -18,6 +18,15 @@ from parity import DEV, ENTROPY_ABS_FLOOR, MARGIN, to_dev
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=[0, 1], ids=["scan", "per_row"])
+def filter_path(request):
+    """Every case runs twice: with the library's own course (split-row scan + per-row decide, the one-workgroup-
+    per-row kernel only for rows those cannot settle) and with that kernel for every row."""
+    hb.hola_set_tuning(filter_path=request.param)
+    yield request.param
+    hb.hola_set_tuning()
+
+
 def run_filtered(target, draft, tokens, seed, T, tau, top_k, top_p, draft_len=None, target_ld=0, draft_ld=0,
                  dev=None):
     P, D = dev if dev is not None else (to_dev(target), to_dev(draft))
