@@ -51,6 +51,7 @@ struct ScanParams {
     int32_t B, gamma, V;
     int32_t top_k; float top_p;
     int32_t nseg, cap_seg;             // segments per row; list entries per segment = kScanStore / nseg
+    int32_t seg_len;                   // chunks per segment (the last segments of a row may be short or empty)
     unsigned long long* cand;          // [rows, nseg, cap_seg]
     SegInfo* segs;                     // [rows, nseg]
     int32_t* flags;                    // [rows]: 1 = left to the per-row kernel
@@ -116,9 +117,6 @@ __device__ __forceinline__ short2_t bf16_keys(uint32_t w)
     return __builtin_bit_cast(short2_t, w ^ (__builtin_bit_cast(uint32_t, sign) & 0x7fff7fffu));
 }
 
-// Chunks of a row's segment: the row's chunks are shared evenly by its segments.
-__device__ __forceinline__ int64_t scan_seg_chunks(int64_t nchunks, int nseg) { return (nchunks + nseg - 1) / nseg; }
-
 constexpr int kScanHot = 64;                                    // hot chunks a wavefront packs into shared memory
 
 struct ScanShared {
@@ -132,36 +130,39 @@ struct ScanShared {
 
 // One segment of one row: what a workgroup needs to load it and to interpret the loaded chunks.
 struct ScanItem {
-    const uint4* rowv;
-    int64_t nchunks, c_lo;
+    const uint4* rowv;                                          // chunk c_lo of the row's 16-byte grid
+    int32_t nchunks, c_lo;                                      // V < 2^22, so chunk and element numbers fit 32 bits
     int32_t head, n_c;                                          // n_c <= 0: nothing to do (row unused or segment empty)
     int32_t r, seg;
     bool used;                                                  // the row is needed (an empty segment still reports)
 };
 
+// Segment `seg` of row k (0 .. 2 gamma: the draft rows, then the target rows) of sequence b.  The grid gives the
+// three numbers, and every row uses the same segment length, so nothing here divides by a run-time value.
 template <bool BF16>
-__device__ __forceinline__ ScanItem scan_item(const ScanParams& p, int64_t work, int64_t total)
+__device__ __forceinline__ ScanItem scan_item(const ScanParams& p, int seg, int k, int b)
 {
     ScanItem it;
-    it.rowv = nullptr; it.nchunks = 0; it.c_lo = 0; it.head = 0; it.n_c = 0; it.r = 0; it.seg = 0; it.used = false;
-    if (work >= total) return it;
-    it.r = (int)(work / p.nseg);
-    it.seg = (int)(work % p.nseg);
-    FilterRowId id;
-    if (!filter_row_id(it.r, p.B, p.gamma, p.draft_len, id)) return it;
+    it.rowv = nullptr; it.nchunks = 0; it.c_lo = 0; it.head = 0; it.n_c = 0; it.used = false;
+    it.r = b * (2 * p.gamma + 1) + k;
+    it.seg = seg;
+    const bool is_draft = k < p.gamma;
+    const int j = is_draft ? k : k - p.gamma;
+    int len = p.draft_len ? p.draft_len[b] : p.gamma;
+    len = len < 0 ? 0 : (len > p.gamma ? p.gamma : len);
+    if (is_draft ? (j >= len) : (j > len)) return it;           // row not needed
     it.used = true;
     constexpr int N = BF16 ? 8 : 4;
     constexpr int ES = BF16 ? 2 : 4;
-    const char* row = id.is_draft ? (const char*)p.draft + ((int64_t)id.b * p.gamma + id.j) * p.draft_ld * ES
-                                  : (const char*)p.target + ((int64_t)id.b * (p.gamma + 1) + id.j) * p.target_ld * ES;
+    const char* row = is_draft ? (const char*)p.draft + ((int64_t)b * p.gamma + j) * p.draft_ld * ES
+                               : (const char*)p.target + ((int64_t)b * (p.gamma + 1) + j) * p.target_ld * ES;
     const uintptr_t addr = (uintptr_t)row;
     it.head = (int32_t)((addr & 15) / ES);
-    it.rowv = (const uint4*)(addr & ~(uintptr_t)15);
-    it.nchunks = ((int64_t)p.V + it.head + N - 1) / N;
-    const int64_t seg_len = scan_seg_chunks(it.nchunks, p.nseg);
-    it.c_lo = (int64_t)it.seg * seg_len;
-    const int64_t c_hi = it.c_lo + seg_len < it.nchunks ? it.c_lo + seg_len : it.nchunks;
-    it.n_c = c_hi > it.c_lo ? (int)(c_hi - it.c_lo) : 0;        // <= kScanSegChunks (the launcher's choice of nseg)
+    it.nchunks = (p.V + it.head + N - 1) / N;
+    it.c_lo = seg * p.seg_len;
+    it.rowv = (const uint4*)(addr & ~(uintptr_t)15) + it.c_lo;
+    const int32_t c_hi = it.c_lo + p.seg_len < it.nchunks ? it.c_lo + p.seg_len : it.nchunks;
+    it.n_c = c_hi > it.c_lo ? c_hi - it.c_lo : 0;               // <= kScanSegChunks (the launcher's choice of seg_len)
     return it;
 }
 
@@ -174,7 +175,7 @@ __device__ __forceinline__ void scan_load(const ScanItem& it, uint4 (&v)[kScanU]
     for (int u = 0; u < kScanU; ++u) {
         const int i = (int)threadIdx.x + u * kScanThreads;
         v[u] = make_uint4(ninf, ninf, ninf, ninf);
-        if (i < it.n_c) v[u] = load_stream(it.rowv + it.c_lo + i);
+        if (i < it.n_c) v[u] = load_stream(it.rowv + i);
     }
 }
 
@@ -200,9 +201,9 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int i = tid + u * NT;
-        const int64_t c = it.c_lo + i;
+        const int32_t c = it.c_lo + i;
         if (i < it.n_c && (c == 0 || c == it.nchunks - 1)) {
-            const int32_t e0 = (int32_t)(c * N) - it.head;
+            const int32_t e0 = c * N - it.head;
             uint32_t* w = (uint32_t*)&v[u];
 #pragma unroll
             for (int k = 0; k < N; ++k) {
@@ -251,8 +252,8 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
 
     // ---- edge.  Each wavefront takes its share of the rank among its lanes' maxima; the lowest of the
     // wavefronts' values has at least `rank` distinct tokens of the segment at or above it.
-    const int64_t row_elems = it.nchunks * N;
-    const bool tiny = row_elems <= (int64_t)kScanTiny;
+    const int32_t row_elems = it.nchunks * N;
+    const bool tiny = row_elems <= kScanTiny;
     if (!tiny) {
         const uint32_t key = lane_key;
         const int threads = it.n_c < NT ? it.n_c : NT;          // threads that hold a chunk
@@ -261,7 +262,7 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
         uint32_t rank = (uint32_t)p.top_k;
         if (MASS) {
             // top-p alone: the rank at which about kScanTopPList tokens of the row are expected at or above the edge
-            const float per_thread = (float)((int64_t)it.n_c * N) / (float)threads;
+            const float per_thread = (float)(it.n_c * N) / (float)threads;
             const float q = fminf(1.f, (float)kScanTopPList / (float)row_elems);
             const float rk = (float)threads * (1.f - powf(1.f - q, per_thread));
             const uint32_t top = (uint32_t)((float)threads * 0.75f);
@@ -336,7 +337,7 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
             const int at = nh + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bl >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bl, 0u));
             if (mine && at < kScanHot) {
                 sh.hot_chunk[wave][at] = v[u];
-                sh.hot_e0[wave][at] = (int32_t)((it.c_lo + tid + (int64_t)u * NT) * N) - it.head;
+                sh.hot_e0[wave][at] = (it.c_lo + tid + u * NT) * N - it.head;
             }
             nh += (int)__popcll(bl);
         }
@@ -403,7 +404,7 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (!((hot >> u) & 1u)) continue;
-                const int32_t e0 = (int32_t)((it.c_lo + tid + (int64_t)u * NT) * N) - it.head;
+                const int32_t e0 = (it.c_lo + tid + u * NT) * N - it.head;
 #pragma unroll
                 for (int k = 0; k < N; ++k) {
                     const float x = chunk_elem<BF16>(v[u], k);
@@ -437,14 +438,14 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
 // One workgroup per segment.  (Persistent workgroups that loaded their next segment while working on the current
 // one were slower: twice the registers, and the waits on the stores of the list also waited on the prefetch.)
 template <bool BF16, bool MASS>
-__global__ __launch_bounds__(kScanThreads) void filter_scan_kernel(ScanParams p, int64_t total)
+__global__ __launch_bounds__(kScanThreads) void filter_scan_kernel(ScanParams p)
 {
     __shared__ ScanShared sh;
     if (threadIdx.x == 0) { sh.status = 0; sh.count = 0; }
     ExpScale sc{};
     if (MASS) sc = make_scale(kLog2e / (double)p.temperature);
     uint4 v[kScanU];
-    const ScanItem it = scan_item<BF16>(p, blockIdx.x, total);
+    const ScanItem it = scan_item<BF16>(p, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z);   // grid: nseg x (2 gamma + 1) x B
     scan_load<BF16>(it, v);
     __syncthreads();
     scan_segment<BF16, MASS>(p, it, v, sc, sh);
@@ -774,17 +775,19 @@ hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, 
     if (p.nseg > kScanMaxSeg) return hipErrorInvalidValue;
     const bool want_k = top_k > 0 && top_k < V;
     const bool mass = !want_k;
-    const int64_t total = rows * p.nseg;
     const bool bf16 = dtype == HOLA_DTYPE_BF16;
-    if (total > 0x7fffffffLL) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)total);
+    const int N = bf16 ? 8 : 4;
+    const int64_t nchunks_max = ((int64_t)V + N - 1) / N + 1;   // any alignment of the row
+    p.seg_len = (int32_t)((nchunks_max + p.nseg - 1) / p.nseg);
+    if (p.seg_len > kScanSegChunks || B > 65535) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)p.nseg, (unsigned)(2 * gamma + 1), (unsigned)B);
     if (bf16) {
-        if (mass) hipLaunchKernelGGL((filter_scan_kernel<true, true>), grid, dim3(kScanThreads), 0, s, p, total);
-        else hipLaunchKernelGGL((filter_scan_kernel<true, false>), grid, dim3(kScanThreads), 0, s, p, total);
+        if (mass) hipLaunchKernelGGL((filter_scan_kernel<true, true>), grid, dim3(kScanThreads), 0, s, p);
+        else hipLaunchKernelGGL((filter_scan_kernel<true, false>), grid, dim3(kScanThreads), 0, s, p);
         hipLaunchKernelGGL((filter_decide_kernel<true>), dim3((unsigned)rows), dim3(64), 0, s, p);
     } else {
-        if (mass) hipLaunchKernelGGL((filter_scan_kernel<false, true>), grid, dim3(kScanThreads), 0, s, p, total);
-        else hipLaunchKernelGGL((filter_scan_kernel<false, false>), grid, dim3(kScanThreads), 0, s, p, total);
+        if (mass) hipLaunchKernelGGL((filter_scan_kernel<false, true>), grid, dim3(kScanThreads), 0, s, p);
+        else hipLaunchKernelGGL((filter_scan_kernel<false, false>), grid, dim3(kScanThreads), 0, s, p);
         hipLaunchKernelGGL((filter_decide_kernel<false>), dim3((unsigned)rows), dim3(64), 0, s, p);
     }
     return hipGetLastError();
