@@ -27,7 +27,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 
 # HBM traffic of one launch of the dominant kernel on the headline workload, from rocprofv3 --pmc
 # FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy of known size (see profiles/); None until measured.
-MEASURED_TRAFFIC_BYTES = {"row_stats_kernel": 1117785113, "fused_kernel": None}
+# (filter_scan_kernel: measured with --top-k 50 --top-p 0.95.)
+MEASURED_TRAFFIC_BYTES = {"row_stats_kernel": 1117785113, "fused_kernel": None, "filter_scan_kernel": 1148368282}
 
 
 def log(*a):
@@ -140,7 +141,9 @@ def main() -> int:
     fused = stage_n[5] > 0
     if fused:
         kname, k_ms, k_bytes = "fused_kernel", stage_ms[5] / stage_n[5], pass1_bytes + stop_bytes
-    elif filtered and stage_n[7] > 0:                      # the keep-set kernel dominates: it must read every row once
+    elif filtered and stage_n[8] > 0:                      # the candidate scan dominates: it reads every row once
+        kname, k_ms, k_bytes = "filter_scan_kernel", stage_ms[8] / stage_n[8], pass1_bytes
+    elif filtered and stage_n[7] > 0:                      # the per-row keep-set kernel alone (large top_k)
         kname, k_ms, k_bytes = "filter_kernel", stage_ms[7] / stage_n[7], pass1_bytes
     else:
         kname, k_ms, k_bytes = "row_stats_kernel", stage_ms[0] / max(stage_n[0], 1), pass1_bytes

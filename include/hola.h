@@ -261,8 +261,9 @@ hola_status hola_set_tuning(const hola_tuning* t /* host; NULL restores defaults
  * events, ADDS elapsed milliseconds and launch counts per stage to the host arrays, and
  * forgets the events.  Stages: 0 split-row statistics, 1 accept/first-reject, 2 residual tile sums,
  * 3 inverse-CDF select, 4 level glue / tile merge, 5 fused per-sequence kernel, 6 per-sequence tail kernel,
- * 7 top-k / top-p filter kernel. */
-enum { HOLA_N_STAGES = 8 };
+ * 7 top-k / top-p keep sets by the per-row kernel (every row, or those the next two left), 8 candidate scan,
+ * 9 per-row decide step. */
+enum { HOLA_N_STAGES = 10 };
 hola_status hola_profile_enable(int32_t on);
 hola_status hola_profile_collect(double* ms_out /* host [HOLA_N_STAGES] */, int64_t* launches_out /* host [HOLA_N_STAGES] */);
 

@@ -16,8 +16,9 @@ LIB_PATH = os.path.join(_HERE, "libhola.so")
 
 HOLA_OK, HOLA_ERR_INVALID_ARG, HOLA_ERR_UNSUPPORTED, HOLA_ERR_WORKSPACE, HOLA_ERR_HIP = range(5)
 HOLA_DTYPE_F32, HOLA_DTYPE_BF16 = 0, 1
-HOLA_N_STAGES = 8
-STAGE_NAMES = ("row_stats", "accept", "tile_sums", "select", "glue", "fused", "tail", "filter")
+HOLA_N_STAGES = 10
+STAGE_NAMES = ("row_stats", "accept", "tile_sums", "select", "glue", "fused", "tail", "filter", "filter_scan",
+               "filter_decide")
 
 EXPORTS = (
     "hola_verify_f32", "hola_verify_bf16", "hola_verify_ex", "hola_verify_literal_ex", "hola_workspace_bytes",

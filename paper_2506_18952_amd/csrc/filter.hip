@@ -942,16 +942,10 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
 
 hipError_t launch_filter(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                          const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
-                         int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scan_scratch,
+                         int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, const int32_t* flags,
                          hipStream_t s)
 {
     if (B <= 0) return hipSuccess;
-    int32_t* flags = nullptr;
-    if (scan_scratch && filter_scan_applies(dtype, V, top_k)) {
-        const hipError_t e = launch_filter_scan(target, draft, dtype, target_ld, draft_ld, draft_len, temperature, B, gamma, V,
-                                                top_k, top_p, filters, out_keep_count, scan_scratch, &flags, s);
-        if (e != hipSuccess) return e;
-    }
     FilterParams p{};
     p.target = target; p.draft = draft; p.target_ld = target_ld; p.draft_ld = draft_ld; p.draft_len = draft_len;
     p.temperature = temperature; p.B = B; p.gamma = gamma; p.V = V; p.top_k = top_k; p.top_p = top_p;

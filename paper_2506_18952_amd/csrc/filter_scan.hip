@@ -753,10 +753,9 @@ bool filter_scan_applies(int dtype, int32_t V, int32_t top_k)
     return top_k <= kScanThreads * 3 / 4 && (int64_t)top_k * 5 / 4 <= kScanCap / nseg;
 }
 
-hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
+static ScanParams scan_params(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                               const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
-                              int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch,
-                              int32_t** flags_out, hipStream_t s)
+                              int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch)
 {
     const int64_t rows = (int64_t)B * (2 * gamma + 1);
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
@@ -767,29 +766,46 @@ hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, 
     p.filters = filters; p.out_keep_count = out_keep_count;
     p.nseg = scan_segments(dtype, V);
     p.cap_seg = kScanStore / p.nseg;
+    const int N = dtype == HOLA_DTYPE_BF16 ? 8 : 4;
+    const int64_t nchunks_max = ((int64_t)V + N - 1) / N + 1;   // any alignment of the row
+    p.seg_len = (int32_t)((nchunks_max + p.nseg - 1) / p.nseg);
     size_t off = 0;
     p.cand = (unsigned long long*)(base + off); off += up((size_t)rows * kScanStore * sizeof(unsigned long long));
     p.flags = (int32_t*)(base + off);           off += up((size_t)rows * sizeof(int32_t));
     p.segs = (SegInfo*)(base + off);
-    *flags_out = p.flags;
-    if (p.nseg > kScanMaxSeg) return hipErrorInvalidValue;
-    const bool want_k = top_k > 0 && top_k < V;
-    const bool mass = !want_k;
-    const bool bf16 = dtype == HOLA_DTYPE_BF16;
-    const int N = bf16 ? 8 : 4;
-    const int64_t nchunks_max = ((int64_t)V + N - 1) / N + 1;   // any alignment of the row
-    p.seg_len = (int32_t)((nchunks_max + p.nseg - 1) / p.nseg);
-    if (p.seg_len > kScanSegChunks || B > 65535) return hipErrorInvalidValue;
+    return p;
+}
+
+hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
+                              const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
+                              int32_t top_k, float top_p, void* scratch, hipStream_t s)
+{
+    const ScanParams p = scan_params(target, draft, dtype, target_ld, draft_ld, draft_len, temperature, B, gamma, V, top_k, top_p,
+                                     nullptr, nullptr, scratch);
+    if (p.nseg > kScanMaxSeg || p.seg_len > kScanSegChunks || B > 65535) return hipErrorInvalidValue;
+    const bool mass = !(top_k > 0 && top_k < V);                // top-p alone: the segments also sum the mass below their edges
     const dim3 grid((unsigned)p.nseg, (unsigned)(2 * gamma + 1), (unsigned)B);
-    if (bf16) {
+    if (dtype == HOLA_DTYPE_BF16) {
         if (mass) hipLaunchKernelGGL((filter_scan_kernel<true, true>), grid, dim3(kScanThreads), 0, s, p);
         else hipLaunchKernelGGL((filter_scan_kernel<true, false>), grid, dim3(kScanThreads), 0, s, p);
-        hipLaunchKernelGGL((filter_decide_kernel<true>), dim3((unsigned)rows), dim3(64), 0, s, p);
     } else {
         if (mass) hipLaunchKernelGGL((filter_scan_kernel<false, true>), grid, dim3(kScanThreads), 0, s, p);
         else hipLaunchKernelGGL((filter_scan_kernel<false, false>), grid, dim3(kScanThreads), 0, s, p);
-        hipLaunchKernelGGL((filter_decide_kernel<false>), dim3((unsigned)rows), dim3(64), 0, s, p);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_filter_decide(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
+                                const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
+                                int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch,
+                                int32_t** flags_out, hipStream_t s)
+{
+    const ScanParams p = scan_params(target, draft, dtype, target_ld, draft_ld, draft_len, temperature, B, gamma, V, top_k, top_p,
+                                     filters, out_keep_count, scratch);
+    *flags_out = p.flags;
+    const int64_t rows = (int64_t)B * (2 * gamma + 1);
+    if (dtype == HOLA_DTYPE_BF16) hipLaunchKernelGGL((filter_decide_kernel<true>), dim3((unsigned)rows), dim3(64), 0, s, p);
+    else hipLaunchKernelGGL((filter_decide_kernel<false>), dim3((unsigned)rows), dim3(64), 0, s, p);
     return hipGetLastError();
 }
 

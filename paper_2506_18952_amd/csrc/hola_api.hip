@@ -235,10 +235,21 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     if (e != hipSuccess) return hip_fail(e, "row statistics launch");
 
     if (filtered) {
-        StageTimer t(7, s);
-        e = launch_filter(a.target_logits, a.draft_logits, a.dtype, tld, dld, a.draft_len, a.temperature, a.B, a.gamma, a.V,
-                          a.top_k, (a.top_p > 0.f && a.top_p < 1.f) ? a.top_p : 1.f, w.filters, a.out_keep_count,
-                          tune.filter_path == 1 ? nullptr : w.filter_scan, s);
+        const float top_p = (a.top_p > 0.f && a.top_p < 1.f) ? a.top_p : 1.f;
+        int32_t* flags = nullptr;
+        if (tune.filter_path != 1 && w.filter_scan && filter_scan_applies(a.dtype, a.V, a.top_k)) {
+            { StageTimer t(8, s);
+              e = launch_filter_scan(a.target_logits, a.draft_logits, a.dtype, tld, dld, a.draft_len, a.temperature, a.B, a.gamma,
+                                     a.V, a.top_k, top_p, w.filter_scan, s); }
+            if (e != hipSuccess) return hip_fail(e, "filter scan launch");
+            { StageTimer t(9, s);
+              e = launch_filter_decide(a.target_logits, a.draft_logits, a.dtype, tld, dld, a.draft_len, a.temperature, a.B, a.gamma,
+                                       a.V, a.top_k, top_p, w.filters, a.out_keep_count, w.filter_scan, &flags, s); }
+            if (e != hipSuccess) return hip_fail(e, "filter decide launch");
+        }
+        { StageTimer t(7, s);
+          e = launch_filter(a.target_logits, a.draft_logits, a.dtype, tld, dld, a.draft_len, a.temperature, a.B, a.gamma, a.V,
+                            a.top_k, top_p, w.filters, a.out_keep_count, flags, s); }
         if (e != hipSuccess) return hip_fail(e, "filter launch");
         fp.filters = w.filters;
     }

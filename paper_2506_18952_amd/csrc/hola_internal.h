@@ -131,18 +131,23 @@ bool literal_supported(int32_t gamma, int32_t V, int dtype);
 hipError_t launch_literal(const FusedParams& p, const Partial* partials, int nparts, int32_t* out_tokens,
                           int32_t* out_calls, hipStream_t s);
 hipError_t launch_row_stats(const RowStatsParams& p, int dtype, const Tuning& t, hipStream_t s);
+// Keep sets of top-k / top-p filtered rows by the one-workgroup-per-row kernel: every row, or with `flags`
+// ([B (2 gamma + 1)]) only the rows flagged 1.
 hipError_t launch_filter(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                          const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
-                         int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scan_scratch,
+                         int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, const int32_t* flags,
                          hipStream_t s);
-// The usual course of the filter: a split-row scan that lists candidates and a per-row decide step; rows it
+// The usual course of the filter: a split-row scan that lists candidates, then a per-row decide step; rows it
 // cannot settle come back flagged in *flags_out ([B (2 gamma + 1)], 1 = still to do).
 size_t filter_scan_bytes(int64_t rows, int32_t V);
 bool filter_scan_applies(int dtype, int32_t V, int32_t top_k);
 hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                               const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
-                              int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch,
-                              int32_t** flags_out, hipStream_t s);
+                              int32_t top_k, float top_p, void* scratch, hipStream_t s);
+hipError_t launch_filter_decide(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
+                                const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
+                                int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch,
+                                int32_t** flags_out, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
 hipError_t launch_merge_tile_stats(const double* ts, int32_t R, int32_t nt, double* out, hipStream_t s);
 hipError_t launch_finalize_rows(const Partial* partials, int nparts, int32_t R, double* out, hipStream_t s);
