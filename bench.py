@@ -127,12 +127,29 @@ def main() -> int:
     stage_ms, stage_n = hb.hola_profile_collect()
     hb.hola_profile_enable(False)
 
-    # bytes the sampler re-reads per step, averaged over the threshold cycle
+    # bytes the sampler re-reads per step, averaged over the threshold cycle; what the thresholds do to the batch
+    per_tau = []
     for i in range(len(taus)):
         step(i)
         torch.cuda.synchronize()
-        resid_total += int((acc.cpu().numpy() < g).sum())
+        a_np, h_np = acc.cpu().numpy(), ent.cpu().numpy()
+        resid_total += int((a_np < g).sum())
+        per_tau.append({"tau": round(float(taus[i]), 4),
+                        "accept_len_hist": np.bincount(a_np, minlength=g + 1).tolist(),
+                        "gate_fire_rate": round(float((h_np < np.float32(taus[i])).mean()), 4),
+                        "mean_entropy": round(float(h_np.mean()), 4)})
     resid = resid_total / len(taus)
+
+    # ---- distribution of single-call times (events on the launch stream around each call)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(min(args.steps, 200))]
+    for i, (e0, e1) in enumerate(evs):
+        e0.record(stream)
+        step(i)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    call_us = np.sort(np.array([e0.elapsed_time(e1) * 1e3 for e0, e1 in evs]))
+    call_dist = {"median": round(float(np.median(call_us)), 1), "p10": round(float(np.percentile(call_us, 10)), 1),
+                 "p90": round(float(np.percentile(call_us, 90)), 1), "calls": len(evs)}
 
     # ---- roofline of the dominant kernel.  Algorithmic bytes: every logit of the gamma draft rows and
     # gamma+1 target rows read once (split path); the fused kernel also reads the stop rows once more.
@@ -170,6 +187,8 @@ def main() -> int:
         "algorithmic_bytes_per_step": int(call_bytes),
         "stage_ms": stages,
         "mean_rejections_per_step": round(resid, 1),
+        "per_threshold": per_tau,
+        "call_us": call_dist,
         "roofline": roofline,
     }
 
@@ -197,7 +216,17 @@ def main() -> int:
                                       np.nan_to_num(refs[i].ratio_margin, nan=np.inf).min(axis=1)))
             near += int((m < 1e-6).sum())
         n = B * len(taus)
+        # the same oracle on one thread, on a slice of the batch (a second or two)
+        n1 = min(B, 32)
+        t0 = time.perf_counter()
+        if filtered:
+            orc.verify_filtered(w.target[:n1], w.draft[:n1], w.tokens[:n1], w.seed, w.temperature, taus[0], top_k=args.top_k,
+                                top_p=args.top_p if 0.0 < args.top_p < 1.0 else 1.0, num_threads=1)
+        else:
+            orc.verify(w.target[:n1], w.draft[:n1], w.tokens[:n1], w.seed, w.temperature, taus[0], num_threads=1)
+        cdt1 = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(n * g / cdt, 1), "unit": "positions/s", "cores": threads,
+                               "single_thread_value": round(n1 * g / cdt1, 1),
                                "kind": "oracle",
                                "sample": f"all {B} sequences of the same workload at each of the {len(taus)} thresholds "
                                          f"({len(taus)} oracle calls, {cdt:.2f}s wall, {cdt * threads:.0f} core-seconds); "
