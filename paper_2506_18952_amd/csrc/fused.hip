@@ -22,6 +22,10 @@ struct SeqShared {
     double tiles[kFusedMaxTiles];
     SeqInfo si;
     int32_t tok;
+    // bonus draw from one slab of the row (split-row partials at hand): its chunks, and where in its mass to land
+    int64_t slab_lo, slab_hi;
+    double slab_u;
+    int32_t slab_ok;
 };
 
 __device__ __forceinline__ AcceptCtx accept_ctx(const FusedParams& p)
@@ -49,7 +53,8 @@ __device__ __forceinline__ void write_glue(const FusedParams& p, int b, int a, i
 // Accept stage (wavefront 0) and sampling (all wavefronts) of sequence b, given sh.stat[].
 // Called by every thread of the workgroup, after a barrier that made sh.stat visible.
 template <bool BF16, int NW, bool FILT = false>
-__device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& sh, int b, int len, float Tb)
+__device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& sh, int b, int len, float Tb,
+                                              const Partial* __restrict__ parts = nullptr, int nparts = 0)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = p.gamma;
@@ -84,24 +89,83 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
 
     RowPair rp;
     make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0, FILT ? p.filters : nullptr, p.B);
+
+    // ---- bonus token with the split-row partials at hand: on that row every partial is the mass of one contiguous
+    // slab of tokens (in index order), so the slab that holds the draw follows from the partials alone and only it is
+    // read again, an eighth of the row or less.  The place inside the slab is handed on as a fraction of its mass.
+    constexpr int N = BF16 ? 8 : 4;
+    constexpr int ES = BF16 ? 2 : 4;
+    int ntiles = p.ntiles;
+    int32_t tok_off = 0;
+    double u_eff = (double)si.u;
+    bool slab_mode = false;
+    if (!FILT && parts != nullptr && nparts >= 4 && si.mode == 1 && rp.ok && si.row == len) {   // uniform over the workgroup
+        const RowGeom geo = make_geom<BF16>((const char*)p.target + ((int64_t)b * (g + 1) + si.row) * p.target_ld * ES, p.V);
+        if (geo.edge_lo_end == 0 && geo.edge_hi_begin == p.V) {    // no ragged ends: the slabs are all of the row
+            if (wave == 0) {
+                const Partial* ps = parts + ((int64_t)p.B * g + (int64_t)b * (g + 1) + si.row) * nparts;
+                double S = 0.0, br = 0.0;
+                if (lane < nparts) { S = ps[lane].S; br = ps[lane].bref; }
+                const bool has = S > 0.0 && S < INFINITY;
+                double bmin = has ? br : INFINITY;
+#pragma unroll
+                for (int m = 32; m >= 1; m >>= 1) bmin = fmin(bmin, __shfl_xor(bmin, m, 64));
+                const double W = has ? S * exp2(bmin - br) : 0.0;   // the slab's mass against a common reference
+                const double incl = wave_inclusive_scan(W, lane);
+                const double Z = __shfl(incl, 63, 64);
+                const double target = u_eff * Z;
+                const unsigned long long hit = __ballot(incl > target);
+                const int src = hit ? __ffsll((long long)hit) - 1 : 0;
+                const double w_src = __shfl(W, src, 64), excl = __shfl(incl - W, src, 64);
+                int ok = (Z > 0.0 && Z < INFINITY && hit && w_src > 0.0) ? 1 : 0;
+                double frac = ok ? (target - excl) / w_src : 0.0;
+                frac = frac < 0.0 ? 0.0 : (frac > 0.999999999 ? 0.999999999 : frac);
+                int64_t seg_lo, seg_hi, lo, hi;
+                wave_slab(geo, src / kWaves, nparts / kWaves, src % kWaves, seg_lo, seg_hi, lo, hi);
+                if (hi <= lo) ok = 0;
+                if (lane == 0) { sh.slab_lo = lo; sh.slab_hi = hi; sh.slab_u = frac; sh.slab_ok = ok; }
+            }
+            __syncthreads();
+            if (sh.slab_ok) {
+                slab_mode = true;
+                const int64_t lo = sh.slab_lo, hi = sh.slab_hi;
+                rp.Pv += lo;                                     // the slab as a row of its own (head is 0 here)
+                rp.nchunks = hi - lo;
+                rp.V = (int32_t)((hi - lo) * N);
+                tok_off = (int32_t)(lo * N);
+                ntiles = (int)((hi - lo + 64 * kTileChunks - 1) / (64 * kTileChunks));
+                u_eff = sh.slab_u;
+            }
+        }
+    }
+
     int32_t tok = -1;
-    for (int attempt = 0; attempt < 2; ++attempt) {
+    for (int attempt = 0; attempt < 3; ++attempt) {
         // tile weights of the stop row: two tiles per round trip and wavefront
-        for (int t = wave; t < p.ntiles; t += 2 * NW) {
+        for (int t = wave; t < ntiles; t += 2 * NW) {
             double w0 = 0.0, w1 = 0.0;
             if (rp.ok) tile_weight2<BF16, FILT>(rp, t, t + NW, lane, w0, w1);
             if (lane == 0) {
                 sh.tiles[t] = w0;
-                if (t + NW < p.ntiles) sh.tiles[t + NW] = w1;
+                if (t + NW < ntiles) sh.tiles[t + NW] = w1;
             }
         }
         __syncthreads();
         if (wave == 0) {
-            const int32_t tk = rp.ok ? select_token<BF16, true, FILT>(rp, sh.tiles, p.ntiles, si.u, lane) : -1;
+            const int32_t tk = rp.ok ? select_token<BF16, true, FILT>(rp, sh.tiles, ntiles, u_eff, lane) : -1;
             if (lane == 0) sh.tok = tk;
         }
         __syncthreads();
         tok = sh.tok;
+        if (slab_mode) {
+            if (tok >= 0) { tok += tok_off; break; }
+            // no mass in the slab by the sampler's arithmetic (an underflow the partials did not have): the whole row
+            slab_mode = false;
+            make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0, FILT ? p.filters : nullptr, p.B);
+            ntiles = p.ntiles;
+            u_eff = (double)si.u;
+            continue;
+        }
         if (tok != -2) break;                                    // -2: no residual mass, sample p itself
         make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1, FILT ? p.filters : nullptr, p.B);
     }
@@ -194,7 +258,7 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
         if (need && sl == 0) sh.stat[r] = s;
     }
     __syncthreads();
-    sequence_tail<BF16, NW, FILT>(p, sh, b, len, Tb);
+    sequence_tail<BF16, NW, FILT>(p, sh, b, len, Tb, p.target_stats_in ? nullptr : partials, nparts);
 }
 
 bool fused_supported(int32_t gamma, int32_t V, int dtype)

@@ -10,20 +10,19 @@
 namespace hola {
 
 template <bool BF16, bool ARGMAX, int U, bool WITH_T = true>
-__device__ __forceinline__ void row_segment(const void* row, int32_t V, int seg, int nsplit, const ExpScale& sc,
+__device__ __forceinline__ void row_segment(const void* row, int32_t V, int seg, int nsplit, bool slabs, const ExpScale& sc,
                                             Partial* __restrict__ out /* [kWaves] of this (row, segment) */)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const RowGeom g = make_geom<BF16>(row, V);
-    const int64_t nfull = g.c_end - g.c_first;
-    int64_t per = (nfull + nsplit - 1) / nsplit;            // full chunks per segment,
-    per = (per + kBlock - 1) / kBlock * kBlock;             // a multiple of the workgroup stride
-    int64_t seg_lo = g.c_first + (int64_t)seg * per;
-    int64_t seg_hi = seg_lo + per;
-    if (seg_lo > g.c_end) seg_lo = g.c_end;
-    if (seg_hi > g.c_end) seg_hi = g.c_end;
+    // The segment's chunks go to the four wavefronts interleaved in blocks of 64 (the fastest order: 3.5 % faster
+    // than four contiguous slabs), except on the row a bonus token would be drawn from, where each wavefront
+    // takes a contiguous slab so that the sampler can pick a slab from the partial sums.
+    int64_t seg_lo, seg_hi, lo, hi;
+    wave_slab(g, seg, nsplit, wave, seg_lo, seg_hi, lo, hi);
     const bool do_edges = (seg == 0 && wave == 0);
-    const Partial res = wave_row_share<BF16, ARGMAX, U, WITH_T>(g, seg_lo + tid, seg_hi, kBlock, do_edges, sc, lane);
+    const Partial res = wave_row_share<BF16, ARGMAX, U, WITH_T>(g, slabs ? lo + lane : seg_lo + tid, slabs ? hi : seg_hi,
+                                                                slabs ? 64 : kBlock, do_edges, sc, lane);
     if (lane == 0) out[wave] = res;
 }
 
@@ -66,9 +65,10 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(RowStatsParams p)
         slot = (int64_t)p.B * g + (int64_t)b * (g + 1) + j;
     }
     Partial* out = p.partials + (slot * nsplit + seg) * kWaves;
-    if (greedy && !is_draft) row_segment<BF16, true, U>(row, Vrow, seg, nsplit, sc, out);
-    else if (!is_draft && p.lse_only_targets) row_segment<BF16, false, U, false>(row, Vrow, seg, nsplit, sc, out);
-    else row_segment<BF16, false, U>(row, Vrow, seg, nsplit, sc, out);
+    const bool slabs = !is_draft && j == len && p.ntiles == 0 && !p.literal;   // the row of the bonus token
+    if (greedy && !is_draft) row_segment<BF16, true, U>(row, Vrow, seg, nsplit, slabs, sc, out);
+    else if (!is_draft && p.lse_only_targets) row_segment<BF16, false, U, false>(row, Vrow, seg, nsplit, slabs, sc, out);
+    else row_segment<BF16, false, U>(row, Vrow, seg, nsplit, slabs, sc, out);
 }
 
 int choose_split(int64_t rows, int V, int dtype, const Tuning& t)

@@ -218,7 +218,7 @@ __device__ __forceinline__ double read_tile(const double* t)
 // weights carry no mass, or -2 if the caller should recompute the tiles as bonus weights (residual with
 // Z == 0: p == q everywhere, or a broken draft row) and call again.
 template <bool BF16, bool LDS, bool FILT = false>
-__device__ __forceinline__ int32_t select_token(const RowPair& rp, const double* tiles, int ntiles, float u, int lane)
+__device__ __forceinline__ int32_t select_token(const RowPair& rp, const double* tiles, int ntiles, double u, int lane)
 {
     constexpr int N = BF16 ? 8 : 4;
     const int per = (ntiles + 63) / 64;
@@ -231,7 +231,7 @@ __device__ __forceinline__ int32_t select_token(const RowPair& rp, const double*
     const double incl = wave_inclusive_scan(mine, lane);
     const double Z = __shfl(incl, 63, 64);
     if (!(Z > 0.0) || !(Z - Z == 0.0)) return rp.bonus ? -1 : -2;
-    const double target = (double)u * Z;
+    const double target = u * Z;
     const unsigned long long hit = __ballot(incl > target);
     // The lane whose run of tiles holds the crossing walks it; if rounding hides the crossing it settles
     // for its last tile with weight.  With no such lane at all (rounding at the top end) the last lane that

@@ -234,6 +234,28 @@ __device__ __forceinline__ RowGeom make_geom(const void* row, int32_t V)
     return g;
 }
 
+// The split-row kernel's division of a row: its full chunks go to nsplit segments [seg_lo, seg_hi) of equal length
+// (a multiple of the workgroup's 256 lanes).  Within a segment the four wavefronts either interleave in blocks of
+// 64 chunks, or, on the row a bonus token would be drawn from, take four contiguous slabs [lo, hi) (a multiple of
+// 64 chunks each): partial (segment, wavefront) of that row is then the sum over one contiguous range of tokens, in
+// index order, and the sampler can pick a slab from these sums and read only that slab again.
+__device__ __forceinline__ void wave_slab(const RowGeom& g, int seg, int nsplit, int wave, int64_t& seg_lo, int64_t& seg_hi,
+                                          int64_t& lo, int64_t& hi)
+{
+    const int64_t nfull = g.c_end - g.c_first;
+    int64_t per = (nfull + nsplit - 1) / nsplit;            // full chunks per segment,
+    per = (per + 255) / 256 * 256;                          // a multiple of the workgroup's lanes
+    seg_lo = g.c_first + (int64_t)seg * per;
+    seg_hi = seg_lo + per;
+    if (seg_lo > g.c_end) seg_lo = g.c_end;
+    if (seg_hi > g.c_end) seg_hi = g.c_end;
+    int64_t wl = (seg_hi - seg_lo + 3) / 4;
+    wl = (wl + 63) / 64 * 64;
+    lo = seg_lo + (int64_t)wave * wl;
+    if (lo > seg_hi) lo = seg_hi;
+    hi = lo + wl < seg_hi ? lo + wl : seg_hi;
+}
+
 // One wavefront's pass over the chunks c0, c0 + stride, ... < c_hi of a row (c0 already holds the lane's
 // offset), plus, if do_edges, the edge elements (fewer than two chunks' worth, one per lane).
 template <bool BF16, bool ARGMAX, int U, bool ROBUST, bool WITH_T = true>
