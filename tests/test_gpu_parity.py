@@ -434,3 +434,35 @@ def test_graph_capture_and_replay():
             assert torch.equal(o, e), f"replay {rep} differs from the eager call"
         call()                                              # eager work between the replays
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V", [2048, 16384, 100000, 131072])
+def test_bonus_draw_with_mass_at_slab_boundaries(V, dtype):
+    """Every draft kept (tau = +inf), so each sequence draws its bonus token from target row gamma.  With the
+    split-row partials at hand that draw picks one contiguous slab of the row and re-reads only it; here most of
+    the mass sits on tokens at multiples of 512 elements and their neighbours, which is where slabs begin and
+    end whatever the split, and some rows hold a whole slab of -inf."""
+    rng = np.random.default_rng(V % 97 + (7 if dtype == "bf16" else 0))
+    B, g = 96, 2
+    P = rng.normal(0, 1, (B, g + 1, V)).astype(np.float32)
+    D = (P[:, :g] + rng.normal(0, 0.3, (B, g, V))).astype(np.float32)
+    edges = np.arange(0, V, 512)
+    for b in range(B):
+        k = rng.choice(edges, size=min(6, edges.size), replace=False)
+        P[b, g, k] += 9.0
+        P[b, g, np.minimum(k + 511, V - 1)] += 9.0
+        P[b, g, np.maximum(k - 1, 0)] += 8.5
+        if b % 8 == 0:
+            P[b, g, (V // 4):(V // 2)] = -np.inf                 # whole slabs without mass
+        if b % 16 == 1:
+            P[b, g, :] = -30.0
+            P[b, g, V - 1] = 5.0                                 # all the mass on the last token
+    tok = rng.integers(0, V, (B, g)).astype(np.int32)
+    if dtype == "bf16":
+        P, D = wl.f32_to_bf16_bits(P), wl.f32_to_bf16_bits(D)
+    for seed in (3, 4):
+        out = run_gpu_level(P, D, tok, seed, 1.0, float("inf"))
+        assert np.all(out.accept_len == g)
+        rep = compare_level(P, D, tok, seed, 1.0, float("inf"), out)
+        _report(f"bonus slabs V={V} {dtype} seed={seed}", rep)
