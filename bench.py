@@ -154,7 +154,10 @@ def main() -> int:
     # ---- roofline of the dominant kernel.  Algorithmic bytes: every logit of the gamma draft rows and
     # gamma+1 target rows read once (split path); the fused kernel also reads the stop rows once more.
     pass1_bytes = B * (2 * g + 1) * V * 2
-    stop_bytes = (2 * resid + (B - resid)) * V * 2
+    # Stop rows: a rejection re-reads the target and the draft row; a bonus draw re-reads one slab of the target
+    # row (an eighth of it on this shape) when the split-row partials are at hand, the whole row otherwise.
+    bonus_row_fraction = 1.0 if (args.path == "fused" or filtered) else 0.125
+    stop_bytes = (2 * resid + (B - resid) * bonus_row_fraction) * V * 2
     fused = stage_n[5] > 0
     if fused:
         kname, k_ms, k_bytes = "fused_kernel", stage_ms[5] / stage_n[5], pass1_bytes + stop_bytes
