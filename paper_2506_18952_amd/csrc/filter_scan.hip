@@ -3,7 +3,7 @@
 // wavefront per row decides the cut from that list.  Rows it cannot settle (a list that overflowed, a nucleus
 // that reaches beyond the list, NaN or +inf logits) are flagged and left to the one-workgroup-per-row kernel.
 //
-// Scan: a workgroup of 256 threads owns one segment of up to 256 x 8 chunks of a row (the row's chunks are
+// Scan: a workgroup of 256 threads owns one segment of up to 256 x 64 logits of a row (the row's chunks are
 // shared evenly by its segments) and holds it in registers.  Each thread takes the largest logit of each of its
 // chunks and of all of them (bf16: on 16-bit order keys, two per packed operation).  Each wavefront then finds,
 // by a bit-by-bit radix descent on ballots, the r-th largest of its lanes' maxima, r being the wavefront's share
@@ -27,8 +27,10 @@ namespace hola {
 
 constexpr int kScanThreads = 256;
 constexpr int kScanWaves = kScanThreads / 64;
-constexpr int kScanU = 8;                                       // chunks per thread
-constexpr int kScanSegChunks = kScanThreads * kScanU;
+// Chunks per thread: 64 logits in registers for either type (8 chunks of 8 bf16, 16 chunks of 4 floats), so a
+// segment is 16 384 logits and rows of one vocabulary have the same number of segments in both types.
+template <bool BF16> struct ScanU { static constexpr int value = BF16 ? 8 : 16; };
+constexpr int scan_seg_chunks(int dtype) { return kScanThreads * (dtype == HOLA_DTYPE_BF16 ? 8 : 16); }
 constexpr int kScanSlots = 16;                                  // list entries per lane in the decide step
 constexpr int kScanCap = 64 * kScanSlots;                       // list entries per row that the decide step holds
 constexpr int kScanStore = 2 * kScanCap;                        // list entries per row in memory, shared evenly by its segments
@@ -162,17 +164,17 @@ __device__ __forceinline__ ScanItem scan_item(const ScanParams& p, int seg, int 
     it.c_lo = seg * p.seg_len;
     it.rowv = (const uint4*)(addr & ~(uintptr_t)15) + it.c_lo;
     const int32_t c_hi = it.c_lo + p.seg_len < it.nchunks ? it.c_lo + p.seg_len : it.nchunks;
-    it.n_c = c_hi > it.c_lo ? c_hi - it.c_lo : 0;               // <= kScanSegChunks (the launcher's choice of seg_len)
+    it.n_c = c_hi > it.c_lo ? c_hi - it.c_lo : 0;               // <= 256 x ScanU (the launcher's choice of seg_len)
     return it;
 }
 
-// The segment's chunks, kScanU per thread; chunks past its end read as -inf.
+// The segment's chunks, ScanU per thread; chunks past its end read as -inf.
 template <bool BF16>
-__device__ __forceinline__ void scan_load(const ScanItem& it, uint4 (&v)[kScanU])
+__device__ __forceinline__ void scan_load(const ScanItem& it, uint4 (&v)[ScanU<BF16>::value])
 {
     const uint32_t ninf = BF16 ? 0xff80ff80u : 0xff800000u;
 #pragma unroll
-    for (int u = 0; u < kScanU; ++u) {
+    for (int u = 0; u < ScanU<BF16>::value; ++u) {
         const int i = (int)threadIdx.x + u * kScanThreads;
         v[u] = make_uint4(ninf, ninf, ninf, ninf);
         if (i < it.n_c) v[u] = load_stream(it.rowv + i);
@@ -182,12 +184,12 @@ __device__ __forceinline__ void scan_load(const ScanItem& it, uint4 (&v)[kScanU]
 // Edge, list and report of one loaded segment.  Two barriers; the shared words are free for the next segment once
 // thread 0 has written the report.
 template <bool BF16, bool MASS>
-__device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem& it, uint4 (&v)[kScanU], const ExpScale& sc,
+__device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem& it, uint4 (&v)[ScanU<BF16>::value], const ExpScale& sc,
                                              ScanShared& sh)
 {
     constexpr int N = BF16 ? 8 : 4;
     constexpr int KB = BF16 ? 16 : 32;
-    constexpr int U = kScanU;
+    constexpr int U = ScanU<BF16>::value;
     constexpr int NT = kScanThreads;
     constexpr int NW = kScanWaves;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -444,7 +446,7 @@ __global__ __launch_bounds__(kScanThreads) void filter_scan_kernel(ScanParams p)
     if (threadIdx.x == 0) { sh.status = 0; sh.count = 0; }
     ExpScale sc{};
     if (MASS) sc = make_scale(kLog2e / (double)p.temperature);
-    uint4 v[kScanU];
+    uint4 v[ScanU<BF16>::value];
     const ScanItem it = scan_item<BF16>(p, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z);   // grid: nseg x (2 gamma + 1) x B
     scan_load<BF16>(it, v);
     __syncthreads();
@@ -729,7 +731,7 @@ static int scan_segments(int dtype, int32_t V)
 {
     const int N = dtype == HOLA_DTYPE_BF16 ? 8 : 4;
     const int64_t nchunks_max = ((int64_t)V + N - 1) / N + 1;
-    return (int)((nchunks_max + kScanSegChunks - 1) / kScanSegChunks);
+    return (int)((nchunks_max + scan_seg_chunks(dtype) - 1) / scan_seg_chunks(dtype));
 }
 
 // Scratch of the scan + decide pair: 16 KB of candidate list per row, which is why very large batches (beyond
@@ -750,7 +752,8 @@ bool filter_scan_applies(int dtype, int32_t V, int32_t top_k)
     if (nseg > kScanMaxSeg) return false;
     const bool want_k = top_k > 0 && top_k < V;
     if (!want_k || (int64_t)V <= kScanTiny) return true;
-    return top_k <= kScanThreads * 3 / 4 && (int64_t)top_k * 5 / 4 <= kScanCap / nseg;
+    // the lowest of four wavefronts' values lets ~1.45 k tokens of a segment through
+    return top_k <= kScanThreads * 3 / 4 && (int64_t)top_k * 3 / 2 <= kScanCap / nseg;
 }
 
 static ScanParams scan_params(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
@@ -782,7 +785,7 @@ hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, 
 {
     const ScanParams p = scan_params(target, draft, dtype, target_ld, draft_ld, draft_len, temperature, B, gamma, V, top_k, top_p,
                                      nullptr, nullptr, scratch);
-    if (p.nseg > kScanMaxSeg || p.seg_len > kScanSegChunks || B > 65535) return hipErrorInvalidValue;
+    if (p.nseg > kScanMaxSeg || p.seg_len > scan_seg_chunks(dtype) || B > 65535) return hipErrorInvalidValue;
     const bool mass = !(top_k > 0 && top_k < V);                // top-p alone: the segments also sum the mass below their edges
     const dim3 grid((unsigned)p.nseg, (unsigned)(2 * gamma + 1), (unsigned)B);
     if (dtype == HOLA_DTYPE_BF16) {
