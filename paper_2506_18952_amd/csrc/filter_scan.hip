@@ -454,7 +454,7 @@ __global__ __launch_bounds__(kScanThreads) void filter_scan_kernel(ScanParams p)
 }
 
 template <bool BF16>
-__global__ __launch_bounds__(64) void filter_decide_kernel(ScanParams p)
+__global__ __launch_bounds__(64, 5) void filter_decide_kernel(ScanParams p)
 {
     constexpr int KB = BF16 ? 16 : 32;
     constexpr int E = kScanSlots;
@@ -503,7 +503,7 @@ __global__ __launch_bounds__(64) void filter_decide_kernel(ScanParams p)
     int run = my_count;                                         // inclusive running count over the segments (lanes)
 #pragma unroll
     for (int d = 1; d < kScanMaxSeg; d <<= 1) { const int o = __shfl_up(run, d, 64); if (lane >= d) run += o; }
-    const int nslots = (n + 63) / 64;
+    int nslots = (n + 63) / 64;
     unsigned long long ent[E];
     const unsigned long long* list = p.cand + (int64_t)r * p.nseg * p.cap_seg;
 #pragma unroll
@@ -535,14 +535,67 @@ __global__ __launch_bounds__(64) void filter_decide_kernel(ScanParams p)
     fr.ref = ref_for<BF16>(key_to_logit<BF16>(kmax), fr.sc);
     fr.scale = 1.0;
     const double beta_m = ref_offset<BF16>(fr.ref, fr.sc);
+    // Shorter lists make every later step cheaper: entries that cannot matter are dropped and the rest packed into
+    // the first slots (through shared memory; the order of a list never matters).
+    __shared__ unsigned long long s_pack[64 * E];
+    auto pack = [&](auto keep_key) {
+        int cnt = 0;
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+            if (j < nslots) {
+                const bool keep = valid(ent[j]) && keep_key(logit_key(ent[j]));
+                const unsigned long long bl = __ballot(keep);
+                if (bl) {
+                    const int at = cnt + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bl >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bl, 0u));
+                    if (keep) s_pack[at] = ent[j];
+                    cnt += (int)__popcll(bl);
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        n = cnt;
+        nslots = (cnt + 63) / 64;
+#pragma unroll
+        for (int j = 0; j < E; ++j) ent[j] = (j < nslots && j * 64 + lane < cnt) ? s_pack[j * 64 + lane] : 0ull;
+        __builtin_amdgcn_wave_barrier();
+    };
     // key bits on which every listed token agrees (the list spans a narrow range of logits): the descents skip them
-    uint32_t k_or = 0, k_and = 0xffffffffu;
+    uint32_t same = 0, same_bits = 0;
+    auto agree = [&]() {
+        uint32_t k_or = 0, k_and = 0xffffffffu;
 #pragma unroll
-    for (int j = 0; j < E; ++j)
-        if (valid(ent[j])) { k_or |= logit_key(ent[j]); k_and &= logit_key(ent[j]); }
+        for (int j = 0; j < E; ++j)
+            if (j < nslots && valid(ent[j])) { k_or |= logit_key(ent[j]); k_and &= logit_key(ent[j]); }
 #pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) { k_or |= __shfl_xor(k_or, m, 64); k_and &= __shfl_xor(k_and, m, 64); }
-    const uint32_t same = ~(k_or ^ k_and), same_bits = k_and;
+        for (int m = 32; m >= 1; m >>= 1) { k_or |= __shfl_xor(k_or, m, 64); k_and &= __shfl_xor(k_and, m, 64); }
+        same = ~(k_or ^ k_and);
+        same_bits = k_and;
+    };
+    auto count_where = [&](auto pred) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int j = 0; j < E; ++j)
+            if (j < nslots) c += (uint32_t)__popcll(__ballot(valid(ent[j]) && pred(logit_key(ent[j]))));
+        return c;
+    };
+
+    bool have_cut = false;
+    uint32_t cut_key = 0, n_ties = 0, cnt_above = 0;
+    unsigned long long r_keep = 0, zk = ~0ull;
+    if (want_k) {
+        // the segment with the highest edge alone holds k tokens at or above it: nothing below that edge is kept
+        if (partial) pack([&](uint32_t kk) { return kk >= edge_max; });
+        agree();
+        const uint32_t need = (uint32_t)p.top_k < (uint32_t)n ? (uint32_t)p.top_k : (uint32_t)n;
+        cut_key = wave_select_by_count<E>(ent, nslots, KB, valid, logit_key, need, same, same_bits);
+        pack([&](uint32_t kk) { return kk >= cut_key; });        // the kept tokens and the ties at the cut
+        cnt_above = count_where([&](uint32_t kk) { return kk > cut_key; });
+        n_ties = count_where([&](uint32_t kk) { return kk == cut_key; });
+        const unsigned long long total = (unsigned long long)cnt_above + n_ties;
+        r_keep = total >= (unsigned long long)p.top_k ? (unsigned long long)p.top_k - cnt_above : n_ties;
+        have_cut = true;
+    }
+    agree();
 
     unsigned long long mass[E];
     unsigned long long lm = 0;                                  // mass of the whole list
@@ -553,13 +606,6 @@ __global__ __launch_bounds__(64) void filter_decide_kernel(ScanParams p)
         lm += mass[j];
     }
     if (want_p) lm = wave_sum_u64(lm);
-    auto count_where = [&](auto pred) {
-        uint32_t c = 0;
-#pragma unroll
-        for (int j = 0; j < E; ++j)
-            if (j < nslots) c += (uint32_t)__popcll(__ballot(valid(ent[j]) && pred(logit_key(ent[j]))));
-        return c;
-    };
     auto mass_where = [&](auto pred) {
         unsigned long long s = 0;
 #pragma unroll
@@ -567,22 +613,9 @@ __global__ __launch_bounds__(64) void filter_decide_kernel(ScanParams p)
             if (j < nslots && valid(ent[j]) && pred(logit_key(ent[j]))) s += mass[j];
         return wave_sum_u64(s);
     };
-
-    bool have_cut = false;
-    uint32_t cut_key = 0, n_ties = 0, cnt_above = 0;
-    unsigned long long r_keep = 0, zk = ~0ull;
-    if (want_k) {
-        const uint32_t need = (uint32_t)p.top_k < (uint32_t)n ? (uint32_t)p.top_k : (uint32_t)n;
-        cut_key = wave_select_by_count<E>(ent, nslots, KB, valid, logit_key, need, same, same_bits);
-        cnt_above = count_where([&](uint32_t kk) { return kk > cut_key; });
-        n_ties = count_where([&](uint32_t kk) { return kk == cut_key; });
-        const unsigned long long total = (unsigned long long)cnt_above + n_ties;
-        r_keep = total >= (unsigned long long)p.top_k ? (unsigned long long)p.top_k - cnt_above : n_ties;
-        if (want_p) {
-            const unsigned long long f_theta = list_mass_fixed<BF16>(fr, key_to_logit<BF16>(cut_key));
-            zk = mass_where([&](uint32_t kk) { return kk > cut_key; }) + r_keep * f_theta;
-        }
-        have_cut = true;
+    if (want_k && want_p) {
+        const unsigned long long f_theta = list_mass_fixed<BF16>(fr, key_to_logit<BF16>(cut_key));
+        zk = mass_where([&](uint32_t kk) { return kk > cut_key; }) + r_keep * f_theta;
     }
     if (want_p) {
         unsigned long long target;
