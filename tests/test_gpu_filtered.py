@@ -296,3 +296,41 @@ def test_rows_with_fewer_finite_logits_than_top_k():
             compare_filtered(P, D, tok, 13, 0.9, -1.0, top_k, top_p, got, max_listed=B)
             if top_k == 100 and top_p == 0.0:
                 assert np.all(got[3] == 30)
+
+
+def test_filtered_call_in_a_hip_graph():
+    """A filtered call enqueues kernels only (its scratch needs no clearing), so it can be captured in a HIP
+    graph; every replay must reproduce the eager result, keep counts included."""
+    w = wl.small_case(24, 3, 20011, dtype="bf16", temperature=0.8, case_id=311)
+    B, g, V = w.B, w.gamma, w.V
+    P, D, tok = to_dev(w.target), to_dev(w.draft), to_dev(w.tokens)
+    ws = hb.alloc_workspace(hb.hola_workspace_bytes(B, g, V), DEV)
+    outs = [torch.zeros(B, dtype=torch.int32, device=DEV), torch.zeros(B, dtype=torch.int32, device=DEV),
+            torch.zeros((B, g), dtype=torch.float32, device=DEV), torch.zeros((B, 2 * g + 1), dtype=torch.int32, device=DEV)]
+
+    def call(stream=None):
+        hb.hola_verify_ex(target_logits=P, draft_logits=D, draft_tokens=tok, seed=w.seed, B=B, gamma=g, V=V,
+                          temperature=w.temperature, entropy_threshold=1.0, out_accept_len=outs[0],
+                          out_next_token=outs[1], out_entropy=outs[2], workspace=ws, stream=stream, top_k=40, top_p=0.9,
+                          out_keep_count=outs[3])
+
+    call()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            call(stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for o in outs:
+            o.fill_(-5)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert torch.equal(o, e), f"replay {rep} differs from the eager call"
+        call()                                              # eager work between the replays
+        torch.cuda.synchronize()
