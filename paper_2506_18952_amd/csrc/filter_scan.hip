@@ -111,6 +111,7 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
 
 // Signed 16-bit order keys of two packed bf16 logits (larger logit, larger key; -0 one below +0).
 typedef short short2_t __attribute__((ext_vector_type(2)));
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 constexpr int kBf16NegInfKey = -32641;                          // key of -inf (0xff80 ^ 0x7fff as a signed 16-bit number)
 __device__ __forceinline__ short2_t bf16_keys(uint32_t w)
 {
@@ -224,18 +225,31 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
     bool bad = false;
     uint32_t lane_key = 0;                                      // unsigned order key of the thread's maximum; 0: no finite logit
     if constexpr (BF16) {
-        short2_t kmin = {32767, 32767};
+        // A positive bf16 is its own key, and as 16-bit integers the positives lie above the negatives, so the largest
+        // raw pattern (signed) of a chunk is its largest key unless every logit in it is negative: only then are the
+        // keys formed.  The largest raw pattern taken unsigned exposes a NaN with the sign set (above -inf = 0xff80).
+        ushort2_t umax = {0, 0};
         int tmax = -32768;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const short2_t k0 = bf16_keys(v[u].x), k1 = bf16_keys(v[u].y), k2 = bf16_keys(v[u].z), k3 = bf16_keys(v[u].w);
-            const short2_t mx = __builtin_elementwise_max(__builtin_elementwise_max(k0, k1), __builtin_elementwise_max(k2, k3));
-            kmin = __builtin_elementwise_min(kmin, __builtin_elementwise_min(__builtin_elementwise_min(k0, k1), __builtin_elementwise_min(k2, k3)));
-            cm_key[u] = (int)mx.x > (int)mx.y ? (int)mx.x : (int)mx.y;
-            tmax = cm_key[u] > tmax ? cm_key[u] : tmax;
+            const short2_t r0 = __builtin_bit_cast(short2_t, v[u].x), r1 = __builtin_bit_cast(short2_t, v[u].y);
+            const short2_t r2 = __builtin_bit_cast(short2_t, v[u].z), r3 = __builtin_bit_cast(short2_t, v[u].w);
+            const short2_t mx = __builtin_elementwise_max(__builtin_elementwise_max(r0, r1), __builtin_elementwise_max(r2, r3));
+            umax = __builtin_elementwise_max(__builtin_elementwise_max(umax, __builtin_bit_cast(ushort2_t, r0)),
+                                             __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, r1),
+                                                                       __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, r2),
+                                                                                                 __builtin_bit_cast(ushort2_t, r3))));
+            int cm = (int)mx.x > (int)mx.y ? (int)mx.x : (int)mx.y;
+            if (cm < 0) {                                       // all negative (or -0): the smallest magnitude is the largest
+                const short2_t k0 = bf16_keys(v[u].x), k1 = bf16_keys(v[u].y), k2 = bf16_keys(v[u].z), k3 = bf16_keys(v[u].w);
+                const short2_t km = __builtin_elementwise_max(__builtin_elementwise_max(k0, k1), __builtin_elementwise_max(k2, k3));
+                cm = (int)km.x > (int)km.y ? (int)km.x : (int)km.y;
+            }
+            cm_key[u] = cm;
+            tmax = cm > tmax ? cm : tmax;
         }
-        const int tmin = (int)kmin.x < (int)kmin.y ? (int)kmin.x : (int)kmin.y;
-        bad = tmax >= 0x7f80 || tmin < kBf16NegInfKey;          // +inf or NaN; NaN with the sign set
+        const uint32_t top_raw = (uint32_t)umax.x > (uint32_t)umax.y ? (uint32_t)umax.x : (uint32_t)umax.y;
+        bad = tmax >= 0x7f80 || top_raw > 0xff80u;               // +inf or NaN; NaN with the sign set
         lane_key = tmax > kBf16NegInfKey ? ((uint32_t)tmax ^ 0x8000u) & 0xffffu : 0u;
     } else {
         float tmax = -INFINITY;
