@@ -57,6 +57,8 @@ struct ScanParams {
     unsigned long long* cand;          // [rows, nseg, cap_seg]
     SegInfo* segs;                     // [rows, nseg]
     int32_t* flags;                    // [rows]: 1 = left to the per-row kernel
+    unsigned long long* kept;          // [rows, kKeptList]: the keep set itself, (key << 32 | index), when it is that short
+    int32_t* kept_n;                   // [rows]: its length, -1 when not written
     RowFilter* filters;
     int32_t* out_keep_count;
 };
@@ -120,6 +122,7 @@ __device__ __forceinline__ short2_t bf16_keys(uint32_t w)
     return __builtin_bit_cast(short2_t, w ^ (__builtin_bit_cast(uint32_t, sign) & 0x7fff7fffu));
 }
 
+constexpr int kKeptList = 64;                                   // longest keep set handed to the sampler as a list
 constexpr int kScanHot = 64;                                    // hot chunks a wavefront packs into shared memory
 
 struct ScanShared {
@@ -476,12 +479,13 @@ __global__ __launch_bounds__(64, 5) void filter_decide_kernel(ScanParams p)
     const int r = blockIdx.x;
     FilterRowId id;
     if (!filter_row_id(r, p.B, p.gamma, p.draft_len, id)) {     // row not needed
-        if (lane == 0) { p.flags[r] = 0; if (p.out_keep_count) p.out_keep_count[r] = -1; }
+        if (lane == 0) { p.flags[r] = 0; p.kept_n[r] = -1; if (p.out_keep_count) p.out_keep_count[r] = -1; }
         return;
     }
     FilterRow fr = make_filter_row<BF16>(p.target, p.draft, p.target_ld, p.draft_ld, p.gamma, p.V, p.temperature, id);
     const bool want_k = p.top_k > 0 && p.top_k < p.V;
     const bool want_p = p.top_p > 0.f && p.top_p < 1.f;
+    if (lane == 0) p.kept_n[r] = -1;                            // until the keep set itself has been written
 
     // lane s holds the record of segment s (at most kScanMaxSeg of them)
     SegInfo si;
@@ -761,6 +765,27 @@ __global__ __launch_bounds__(64, 5) void filter_decide_kernel(ScanParams p)
         idx_cut = (int)(0x3fffffu - ci);
     }
 
+    // ---- a short keep set of a target row is written out itself: the sampler then needs no sweep of the row
+    const long long n_keep = have_cut ? (long long)cnt_above + (long long)r_keep : -1;
+    if (!id.is_draft && n_keep >= 1 && n_keep <= kKeptList) {
+        unsigned long long* kl = p.kept + (int64_t)r * kKeptList;
+        int nk = 0;
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+            if (j < nslots) {
+                const uint32_t kk = logit_key(ent[j]);
+                const bool keep = valid(ent[j]) && (kk > cut_key || (kk == cut_key && (int)(uint32_t)(ent[j] & 0xffffffffu) <= idx_cut));
+                const unsigned long long bl = __ballot(keep);
+                if (bl) {
+                    const int at = nk + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(bl >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bl, 0u));
+                    if (keep && at < kKeptList) kl[at] = ent[j];
+                    nk += (int)__popcll(bl);
+                }
+            }
+        }
+        if (lane == 0) p.kept_n[r] = nk == (int)n_keep ? nk : -1;
+    }
+
     out.theta = theta;
     out.idx_cut = idx_cut;
     out.n_keep = have_cut ? (int32_t)(cnt_above + r_keep) : -1;
@@ -787,8 +812,8 @@ size_t filter_scan_bytes(int64_t rows, int32_t V)
 {
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     if (rows <= 0 || (size_t)rows * kScanStore * sizeof(unsigned long long) > ((size_t)256 << 20)) return 0;
-    return up((size_t)rows * kScanStore * sizeof(unsigned long long)) + up((size_t)rows * sizeof(int32_t)) +
-           up((size_t)rows * kScanMaxSeg * sizeof(SegInfo));
+    return up((size_t)rows * kScanStore * sizeof(unsigned long long)) + 2 * up((size_t)rows * sizeof(int32_t)) +
+           up((size_t)rows * kKeptList * sizeof(unsigned long long)) + up((size_t)rows * kScanMaxSeg * sizeof(SegInfo));
 }
 
 // Whether the scan + decide pair is worth running: the row's segments share a list of kScanCap entries, and
@@ -822,6 +847,8 @@ static ScanParams scan_params(const void* target, const void* draft, int dtype, 
     size_t off = 0;
     p.cand = (unsigned long long*)(base + off); off += up((size_t)rows * kScanStore * sizeof(unsigned long long));
     p.flags = (int32_t*)(base + off);           off += up((size_t)rows * sizeof(int32_t));
+    p.kept_n = (int32_t*)(base + off);          off += up((size_t)rows * sizeof(int32_t));
+    p.kept = (unsigned long long*)(base + off); off += up((size_t)rows * kKeptList * sizeof(unsigned long long));
     p.segs = (SegInfo*)(base + off);
     return p;
 }
@@ -848,11 +875,13 @@ hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, 
 hipError_t launch_filter_decide(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                                 const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
                                 int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch,
-                                int32_t** flags_out, hipStream_t s)
+                                int32_t** flags_out, const unsigned long long** kept_out, const int32_t** kept_n_out, hipStream_t s)
 {
     const ScanParams p = scan_params(target, draft, dtype, target_ld, draft_ld, draft_len, temperature, B, gamma, V, top_k, top_p,
                                      filters, out_keep_count, scratch);
     *flags_out = p.flags;
+    *kept_out = p.kept;
+    *kept_n_out = p.kept_n;
     const int64_t rows = (int64_t)B * (2 * gamma + 1);
     if (dtype == HOLA_DTYPE_BF16) hipLaunchKernelGGL((filter_decide_kernel<true>), dim3((unsigned)rows), dim3(64), 0, s, p);
     else hipLaunchKernelGGL((filter_decide_kernel<false>), dim3((unsigned)rows), dim3(64), 0, s, p);

@@ -11,6 +11,7 @@
 //
 // HBM-bound: every logit is read once, the stop row pair once more.  No atomics, no spin waits.
 #include "accept_device.h"
+#include "filter_device.h"
 #include "sampler_device.h"
 
 namespace hola {
@@ -26,7 +27,53 @@ struct SeqShared {
     int64_t slab_lo, slab_hi;
     double slab_u;
     int32_t slab_ok;
+    // draw from a keep set handed over as a list (filtered calls): indices and weights, put in index order
+    int32_t list_idx[64];
+    int32_t list_tok[64];
+    double list_w[64];
 };
+
+// Next token of a filtered stop row whose keep set (at most 64 tokens) is at hand as a list of (order key << 32 |
+// index): the weights of these tokens alone, by the sampler's own element formula, summed in index order as the
+// row sweep would (every other token has weight 0).  One wavefront.  Returns the token, -1 if the weights carry
+// no mass, or -2 if the caller should draw from the target's distribution itself (residual without mass).
+template <bool BF16>
+__device__ __forceinline__ int32_t sample_kept_list(const RowPair& rp, const unsigned long long* kept, int nk, double u, int lane,
+                                                    SeqShared& sh)
+{
+    unsigned long long ent = 0;
+    if (lane < nk) ent = kept[lane];
+    const int32_t idx = lane < nk ? (int32_t)(uint32_t)(ent & 0xffffffffu) : 0x7fffffff;
+    float wk = 0.f;
+    if (lane < nk) {
+        const float xp = key_to_logit<BF16>((uint32_t)(ent >> 32));
+        const float ep = fast_exp2(exp_arg<BF16>(xp, rp.refP, rp.sc));
+        if (rp.bonus) {
+            wk = fmaxf(ep, 0.f);
+        } else {
+            const float xd = load_logit<BF16>(rp.D, idx);
+            float eq = fast_exp2(exp_arg<BF16>(xd, rp.refQ, rp.sc));
+            if (!(xd > rp.thQ || (xd == rp.thQ && idx <= rp.cutQ))) eq = 0.f;   // outside the draft's keep set
+            wk = fmaxf(0.f, __builtin_fmaf(-rp.k_lo, eq, __builtin_fmaf(-rp.k_hi, eq, ep)));
+        }
+    }
+    sh.list_idx[lane] = idx;
+    __builtin_amdgcn_wave_barrier();
+    int rank = 0;
+    for (int q = 0; q < nk; ++q) rank += sh.list_idx[q] < idx ? 1 : 0;
+    if (lane < nk) { sh.list_w[rank] = (double)wk * rp.scale; sh.list_tok[rank] = idx; }
+    __builtin_amdgcn_wave_barrier();
+    const double v = lane < nk ? sh.list_w[lane] : 0.0;
+    const double incl = wave_inclusive_scan(v, lane);
+    const double Z = __shfl(incl, 63, 64);
+    if (!(Z > 0.0) || !(Z - Z == 0.0)) return rp.bonus ? -1 : -2;
+    const double target = u * Z;
+    const unsigned long long hit = __ballot(lane < nk && incl > target);
+    const unsigned long long haveW = __ballot(v > 0.0);
+    if (!haveW) return -1;
+    const int src = hit ? (__ffsll((long long)hit) - 1) : (63 - __clzll((long long)haveW));   // rounding at the top end: the last weight
+    return sh.list_tok[src];
+}
 
 __device__ __forceinline__ AcceptCtx accept_ctx(const FusedParams& p)
 {
@@ -139,8 +186,30 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
         }
     }
 
+    // ---- filtered call whose stop row's keep set is at hand as a short list: no sweep of the row at all
+    int list_n = 0;
+    const unsigned long long* list = nullptr;
+    if (FILT && p.kept != nullptr && rp.ok) {
+        const int64_t rid = (int64_t)b * (2 * g + 1) + g + si.row;
+        list_n = p.kept_n[rid];
+        list = p.kept + rid * 64;
+        if (list_n < 1 || list_n > 64) list_n = 0;
+    }
+
     int32_t tok = -1;
     for (int attempt = 0; attempt < 3; ++attempt) {
+        if (FILT && list_n > 0) {
+            if (wave == 0) {
+                const int32_t tk = sample_kept_list<BF16>(rp, list, list_n, u_eff, lane, sh);
+                if (lane == 0) sh.tok = tk;
+            }
+            __syncthreads();
+            tok = sh.tok;
+            if (tok != -2) break;
+            __syncthreads();
+            make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1, FILT ? p.filters : nullptr, p.B);
+            continue;
+        }
         // tile weights of the stop row: two tiles per round trip and wavefront
         for (int t = wave; t < ntiles; t += 2 * NW) {
             double w0 = 0.0, w1 = 0.0;

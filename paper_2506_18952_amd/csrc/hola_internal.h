@@ -122,6 +122,9 @@ struct FusedParams {
     int32_t* glue_tok; int32_t* glue_len; int64_t glue_ld;
     int32_t glue_keep_next;            // 1: append the next token; 0: the kept tokens only
     const RowFilter* filters;          // top-k / top-p keep sets (slots as the partials), or null
+    // short keep sets written out as lists of (order key << 32 | index), 64 entries per row r = b (2 gamma + 1) + k,
+    // and their lengths (-1: no list); null when the filter's scan did not run
+    const unsigned long long* kept; const int32_t* kept_n;
 };
 
 hipError_t launch_fused(const FusedParams& p, const Tuning& t, hipStream_t s);
@@ -147,7 +150,8 @@ hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, 
 hipError_t launch_filter_decide(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                                 const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
                                 int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch,
-                                int32_t** flags_out, hipStream_t s);
+                                int32_t** flags_out, const unsigned long long** kept_out, const int32_t** kept_n_out,
+                                hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
 hipError_t launch_merge_tile_stats(const double* ts, int32_t R, int32_t nt, double* out, hipStream_t s);
 hipError_t launch_finalize_rows(const Partial* partials, int nparts, int32_t R, double* out, hipStream_t s);
