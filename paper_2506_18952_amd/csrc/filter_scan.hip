@@ -228,9 +228,10 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
     bool bad = false;
     uint32_t lane_key = 0;                                      // unsigned order key of the thread's maximum; 0: no finite logit
     if constexpr (BF16) {
-        // A positive bf16 is its own key, and as 16-bit integers the positives lie above the negatives, so the largest
-        // raw pattern (signed) of a chunk is its largest key unless every logit in it is negative: only then are the
-        // keys formed.  The largest raw pattern taken unsigned exposes a NaN with the sign set (above -inf = 0xff80).
+        // A positive bf16 is its own key, and as signed 16-bit integers the positives lie above the negatives, so the
+        // largest raw pattern of a chunk is its largest key unless every logit in it is negative; then the largest
+        // logit is the one of smallest magnitude, the smallest raw pattern, whose key is that pattern with its low
+        // 15 bits flipped.  The largest raw pattern taken unsigned exposes a NaN with the sign set (above -inf = 0xff80).
         ushort2_t umax = {0, 0};
         int tmax = -32768;
 #pragma unroll
@@ -238,16 +239,14 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
             const short2_t r0 = __builtin_bit_cast(short2_t, v[u].x), r1 = __builtin_bit_cast(short2_t, v[u].y);
             const short2_t r2 = __builtin_bit_cast(short2_t, v[u].z), r3 = __builtin_bit_cast(short2_t, v[u].w);
             const short2_t mx = __builtin_elementwise_max(__builtin_elementwise_max(r0, r1), __builtin_elementwise_max(r2, r3));
+            const short2_t mn = __builtin_elementwise_min(__builtin_elementwise_min(r0, r1), __builtin_elementwise_min(r2, r3));
             umax = __builtin_elementwise_max(__builtin_elementwise_max(umax, __builtin_bit_cast(ushort2_t, r0)),
                                              __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, r1),
                                                                        __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, r2),
                                                                                                  __builtin_bit_cast(ushort2_t, r3))));
-            int cm = (int)mx.x > (int)mx.y ? (int)mx.x : (int)mx.y;
-            if (cm < 0) {                                       // all negative (or -0): the smallest magnitude is the largest
-                const short2_t k0 = bf16_keys(v[u].x), k1 = bf16_keys(v[u].y), k2 = bf16_keys(v[u].z), k3 = bf16_keys(v[u].w);
-                const short2_t km = __builtin_elementwise_max(__builtin_elementwise_max(k0, k1), __builtin_elementwise_max(k2, k3));
-                cm = (int)km.x > (int)km.y ? (int)km.x : (int)km.y;
-            }
+            const int hi = (int)mx.x > (int)mx.y ? (int)mx.x : (int)mx.y;
+            const int lo = (int)mn.x < (int)mn.y ? (int)mn.x : (int)mn.y;
+            const int cm = hi >= 0 ? hi : (int)(short)(lo ^ 0x7fff);
             cm_key[u] = cm;
             tmax = cm > tmax ? cm : tmax;
         }
