@@ -5,7 +5,7 @@
 //
 // Scan: a workgroup of 256 threads owns one segment of up to 256 x 64 logits of a row (the row's chunks are
 // shared evenly by its segments) and holds it in registers.  Each thread takes the largest logit of each of its
-// chunks and of all of them (bf16: on 16-bit order keys, two per packed operation).  Each wavefront then finds,
+// chunks and of all of them (bf16: from the raw 16-bit patterns, two per packed operation).  Each wavefront then finds,
 // by a bit-by-bit radix descent on ballots, the r-th largest of its lanes' maxima, r being the wavefront's share
 // of a rank; the lowest of the wavefronts' values, the edge, has at least `rank` distinct tokens of the segment
 // at or above it.  With rank = top_k no token below the edge is among the row's k largest.  (Top-p alone has no
@@ -220,9 +220,9 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
         }
     }
 
-    // ---- largest logit of every chunk and of the thread, NaN / +inf detection.  bf16: on signed 16-bit order
-    // keys, two per packed operation (a NaN is the largest or, with the sign set, the smallest key); float: a
-    // maximum that skips NaN, which the largest magnitude pattern then reveals.
+    // ---- largest logit of every chunk and of the thread, NaN / +inf detection.  bf16: from the raw 16-bit
+    // patterns, two per packed operation, the result as a signed order key; float: a maximum that skips NaN,
+    // which the largest magnitude pattern then reveals.
     int cm_key[U];                                              // bf16: chunk maximum as a signed key
     float cm_val[U];                                            // float: chunk maximum
     bool bad = false;
