@@ -469,7 +469,9 @@ __global__ __launch_bounds__(kScanThreads) void filter_scan_kernel(ScanParams p)
     scan_segment<BF16, MASS>(p, it, v, sc, sh);
 }
 
-template <bool BF16>
+// WANT_K / WANT_P: which of the two filters is on (at least one is), so that each combination carries only its own
+// code and registers.
+template <bool BF16, bool WANT_K, bool WANT_P>
 __global__ __launch_bounds__(64, 5) void filter_decide_kernel(ScanParams p)
 {
     constexpr int KB = BF16 ? 16 : 32;
@@ -482,8 +484,7 @@ __global__ __launch_bounds__(64, 5) void filter_decide_kernel(ScanParams p)
         return;
     }
     FilterRow fr = make_filter_row<BF16>(p.target, p.draft, p.target_ld, p.draft_ld, p.gamma, p.V, p.temperature, id);
-    const bool want_k = p.top_k > 0 && p.top_k < p.V;
-    const bool want_p = p.top_p > 0.f && p.top_p < 1.f;
+    constexpr bool want_k = WANT_K, want_p = WANT_P;
     if (lane == 0) p.kept_n[r] = -1;                            // until the keep set itself has been written
 
     // lane s holds the record of segment s (at most kScanMaxSeg of them)
@@ -612,17 +613,58 @@ __global__ __launch_bounds__(64, 5) void filter_decide_kernel(ScanParams p)
         r_keep = total >= (unsigned long long)p.top_k ? (unsigned long long)p.top_k - cnt_above : n_ties;
         have_cut = true;
     }
-    agree();
+    // ---- top-k with top-p, the kept tokens and the ties at the cut on one lane each (the usual case): put them in
+    // the order of the definition (logit descending, equal logits by ascending index) and walk the cumulative mass.
+    // The first k of them are the top-k set; the nucleus is the shortest prefix that reaches top_p of their mass.
+    bool nucleus_done = false;
+    int idx_cut = 0x7fffffff;                                   // every tie is kept
+    if (want_k && want_p && n <= 64) {
+        __shared__ unsigned long long s_ord_e[64], s_ord_m[64];
+        const unsigned long long e = ent[0];
+        const uint32_t key = logit_key(e), idx = (uint32_t)(e & 0xffffffffu);
+        s_pack[lane] = e;
+        __builtin_amdgcn_wave_barrier();
+        int rank = 0;
+        for (int q = 0; q < n; ++q) {
+            const unsigned long long o = s_pack[q];
+            const uint32_t ok = logit_key(o), oi = (uint32_t)(o & 0xffffffffu);
+            rank += (ok > key || (ok == key && oi < idx)) ? 1 : 0;
+        }
+        if (valid(e)) {
+            s_ord_e[rank] = e;
+            s_ord_m[rank] = list_mass_fixed<BF16>(fr, key_to_logit<BF16>(key));
+        }
+        __builtin_amdgcn_wave_barrier();
+        const unsigned long long er = lane < n ? s_ord_e[lane] : 0ull;
+        unsigned long long incl = lane < n ? s_ord_m[lane] : 0ull;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) { const unsigned long long o = __shfl_up(incl, d, 64); if (lane >= d) incl += o; }
+        const int kk = p.top_k < n ? p.top_k : n;               // the top-k set: the first kk in this order
+        zk = __shfl(incl, kk - 1, 64);
+        unsigned long long target = (unsigned long long)((double)p.top_p * (double)zk + 0.5);
+        if (target < 1) target = 1;
+        const unsigned long long hit = __ballot(lane < kk && incl >= target);
+        const int last = hit ? __ffsll((long long)hit) - 1 : kk - 1;   // the last kept token
+        const unsigned long long ec = __shfl(er, last, 64);
+        cut_key = logit_key(ec);
+        idx_cut = (int)(uint32_t)(ec & 0xffffffffu);            // kept ties have indices up to this one
+        cnt_above = (uint32_t)__popcll(__ballot(lane <= last && logit_key(er) > cut_key));
+        r_keep = (unsigned long long)(last + 1) - cnt_above;
+        n_ties = (uint32_t)r_keep;                              // nothing left for the tie search below
+        have_cut = true;
+        nucleus_done = true;
+    }
+    if (!nucleus_done) agree();
 
     unsigned long long mass[E];
     unsigned long long lm = 0;                                  // mass of the whole list
 #pragma unroll
     for (int j = 0; j < E; ++j) {
         mass[j] = 0ull;
-        if (want_p && j < nslots && valid(ent[j])) mass[j] = list_mass_fixed<BF16>(fr, key_to_logit<BF16>(logit_key(ent[j])));
+        if (want_p && !nucleus_done && j < nslots && valid(ent[j])) mass[j] = list_mass_fixed<BF16>(fr, key_to_logit<BF16>(logit_key(ent[j])));
         lm += mass[j];
     }
-    if (want_p) lm = wave_sum_u64(lm);
+    if (want_p && !nucleus_done) lm = wave_sum_u64(lm);
     auto mass_where = [&](auto pred) {
         unsigned long long s = 0;
 #pragma unroll
@@ -630,11 +672,11 @@ __global__ __launch_bounds__(64, 5) void filter_decide_kernel(ScanParams p)
             if (j < nslots && valid(ent[j]) && pred(logit_key(ent[j]))) s += mass[j];
         return wave_sum_u64(s);
     };
-    if (want_k && want_p) {
+    if (want_k && want_p && !nucleus_done) {
         const unsigned long long f_theta = list_mass_fixed<BF16>(fr, key_to_logit<BF16>(cut_key));
         zk = mass_where([&](uint32_t kk) { return kk > cut_key; }) + r_keep * f_theta;
     }
-    if (want_p) {
+    if (want_p && !nucleus_done) {
         unsigned long long target;
         if (zk != ~0ull) {
             target = (unsigned long long)((double)p.top_p * (double)zk + 0.5);
@@ -731,7 +773,6 @@ __global__ __launch_bounds__(64, 5) void filter_decide_kernel(ScanParams p)
     }
 
     // ---- the last kept tie: the r-th smallest index among the ties
-    int idx_cut = 0x7fffffff;                                   // every tie is kept
     if (r_keep < n_ties && n_ties <= 64) {
         // few ties (the usual case): their indices go to shared memory, lane l counts those below the l-th
         __shared__ uint32_t s_tie[64];
@@ -882,8 +923,19 @@ hipError_t launch_filter_decide(const void* target, const void* draft, int dtype
     *kept_out = p.kept;
     *kept_n_out = p.kept_n;
     const int64_t rows = (int64_t)B * (2 * gamma + 1);
-    if (dtype == HOLA_DTYPE_BF16) hipLaunchKernelGGL((filter_decide_kernel<true>), dim3((unsigned)rows), dim3(64), 0, s, p);
-    else hipLaunchKernelGGL((filter_decide_kernel<false>), dim3((unsigned)rows), dim3(64), 0, s, p);
+    const bool want_k = top_k > 0 && top_k < V, want_p = top_p > 0.f && top_p < 1.f;
+    const dim3 grid((unsigned)rows), block(64);
+#define HOLA_DECIDE(BF, K, P) hipLaunchKernelGGL((filter_decide_kernel<BF, K, P>), grid, block, 0, s, p)
+    if (dtype == HOLA_DTYPE_BF16) {
+        if (want_k && want_p) HOLA_DECIDE(true, true, true);
+        else if (want_k) HOLA_DECIDE(true, true, false);
+        else HOLA_DECIDE(true, false, true);
+    } else {
+        if (want_k && want_p) HOLA_DECIDE(false, true, true);
+        else if (want_k) HOLA_DECIDE(false, true, false);
+        else HOLA_DECIDE(false, false, true);
+    }
+#undef HOLA_DECIDE
     return hipGetLastError();
 }
 
