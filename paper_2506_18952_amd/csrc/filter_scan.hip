@@ -472,7 +472,7 @@ __global__ __launch_bounds__(kScanThreads) void filter_scan_kernel(ScanParams p)
 // WANT_K / WANT_P: which of the two filters is on (at least one is), so that each combination carries only its own
 // code and registers.
 template <bool BF16, bool WANT_K, bool WANT_P>
-__global__ __launch_bounds__(64, 5) void filter_decide_kernel(ScanParams p)
+__global__ __launch_bounds__(64, (WANT_K && WANT_P) ? 4 : 5) void filter_decide_kernel(ScanParams p)
 {
     constexpr int KB = BF16 ? 16 : 32;
     constexpr int E = kScanSlots;
