@@ -5,7 +5,10 @@
 // prefix of those whose probability, as a fraction of the top-k mass, reaches top_p.  Logits of -inf are never
 // kept.  The kept set is described by (theta, idx_cut): x > theta, or x == theta and index <= idx_cut.
 //
-// One workgroup of 512 threads per row; the kernel needs nothing but the logits (no earlier statistics pass).
+// This kernel settles any row by itself, one workgroup of 512 threads per row, from nothing but the logits.  It is
+// the course of last resort: a filtered call first lets the split-row scan and the per-row decide step of
+// filter_scan.hip try, which settle the usual rows several times faster, and runs this kernel only on the rows those
+// flagged (or on every row when the scan does not apply: a large top_k, a very large batch, or on request).
 // Selection is a radix select over order-preserving integer keys of the logits (16 key bits for bf16, 32 for
 // float), 11 bits per level, most significant first.  A level builds a histogram in LDS whose 64-bit entries
 // pack an element count and a probability mass in fixed point, so one integer LDS atomic per element serves both
