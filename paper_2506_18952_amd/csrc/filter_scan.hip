@@ -32,6 +32,7 @@ constexpr int kScanWaves = kScanThreads / 64;
 template <bool BF16> struct ScanU { static constexpr int value = BF16 ? 8 : 16; };
 constexpr int scan_seg_chunks(int dtype) { return kScanThreads * (dtype == HOLA_DTYPE_BF16 ? 8 : 16); }
 constexpr int kScanSlots = 16;                                  // list entries per lane in the decide step
+constexpr int kScanSlotsWide = 32;                              // the same for a large top_k, whose lists are longer
 constexpr int kScanCap = 64 * kScanSlots;                       // list entries per row that the decide step holds
 constexpr int kScanStore = 2 * kScanCap;                        // list entries per row in memory, shared evenly by its segments
 constexpr int kScanMaxSeg = 16;                                 // segments per row (64 list entries each at least)
@@ -54,6 +55,7 @@ struct ScanParams {
     int32_t top_k; float top_p;
     int32_t nseg, cap_seg;             // segments per row; list entries per segment = kScanStore / nseg
     int32_t seg_len;                   // chunks per segment (the last segments of a row may be short or empty)
+    int32_t two_maxima;                // the edge is looked up among two maxima per lane (large top_k)
     unsigned long long* cand;          // [rows, nseg, cap_seg]
     SegInfo* segs;                     // [rows, nseg]
     int32_t* flags;                    // [rows]: 1 = left to the per-row kernel
@@ -122,7 +124,7 @@ __device__ __forceinline__ short2_t bf16_keys(uint32_t w)
     return __builtin_bit_cast(short2_t, w ^ (__builtin_bit_cast(uint32_t, sign) & 0x7fff7fffu));
 }
 
-constexpr int kKeptList = 64;                                   // longest keep set handed to the sampler as a list
+constexpr int kKeptList = kKeptListMax;                         // longest keep set handed to the sampler as a list
 constexpr int kScanHot = 64;                                    // hot chunks a wavefront packs into shared memory
 
 struct ScanShared {
@@ -273,7 +275,25 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
     const int32_t row_elems = it.nchunks * N;
     const bool tiny = row_elems <= kScanTiny;
     if (!tiny) {
-        const uint32_t key = lane_key;
+        // the values the rank is looked up among: each lane's maximum, or (a large top_k, where 64 maxima per
+        // wavefront run out) the maxima of the two halves of its chunks, which are disjoint sets of tokens too
+        uint32_t keys[2] = {lane_key, 0u};
+        if (p.two_maxima) {
+            if constexpr (BF16) {
+                int h0 = -32768, h1 = -32768;
+#pragma unroll
+                for (int u = 0; u < U / 2; ++u) { h0 = cm_key[u] > h0 ? cm_key[u] : h0; h1 = cm_key[U / 2 + u] > h1 ? cm_key[U / 2 + u] : h1; }
+                keys[0] = h0 > kBf16NegInfKey ? ((uint32_t)h0 ^ 0x8000u) & 0xffffu : 0u;
+                keys[1] = h1 > kBf16NegInfKey ? ((uint32_t)h1 ^ 0x8000u) & 0xffffu : 0u;
+            } else {
+                float h0 = -INFINITY, h1 = -INFINITY;
+#pragma unroll
+                for (int u = 0; u < U / 2; ++u) { h0 = fmaxf(h0, cm_val[u]); h1 = fmaxf(h1, cm_val[U / 2 + u]); }
+                keys[0] = h0 > -INFINITY ? order_key<false>(h0) : 0u;
+                keys[1] = h1 > -INFINITY ? order_key<false>(h1) : 0u;
+            }
+        }
+        const int nkeys = p.two_maxima ? 2 : 1;
         const int threads = it.n_c < NT ? it.n_c : NT;          // threads that hold a chunk
         int my_lanes = threads - 64 * wave;
         my_lanes = my_lanes < 0 ? 0 : (my_lanes > 64 ? 64 : my_lanes);
@@ -291,12 +311,10 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
         uint32_t wkey = 0xffffffffu;                            // a wavefront without lanes does not bound the edge
         if (my_lanes > 0) {
             const uint32_t need = (rank * (uint32_t)my_lanes + (uint32_t)threads - 1) / (uint32_t)threads;   // shares add up to >= rank
-            const uint32_t have = (uint32_t)__popcll(__ballot(key != 0));
+            const uint32_t have = (uint32_t)__popcll(__ballot(keys[0] != 0)) + (uint32_t)__popcll(__ballot(keys[1] != 0));
             wkey = 0;                                           // too few maxima: the whole segment is listed
-            if (have >= need) {
-                const uint32_t one[1] = {key};
-                wkey = wave_select_by_count<1>(one, 1, KB, [](uint32_t e) { return e != 0; }, [](uint32_t e) { return e; }, need);
-            }
+            if (have >= need)
+                wkey = wave_select_by_count<2>(keys, nkeys, KB, [](uint32_t e) { return e != 0; }, [](uint32_t e) { return e; }, need);
         }
         if (lane == 0) sh.edge[wave] = wkey;
     }
@@ -471,11 +489,10 @@ __global__ __launch_bounds__(kScanThreads) void filter_scan_kernel(ScanParams p)
 
 // WANT_K / WANT_P: which of the two filters is on (at least one is), so that each combination carries only its own
 // code and registers.
-template <bool BF16, bool WANT_K, bool WANT_P>
-__global__ __launch_bounds__(64, (WANT_K && WANT_P) ? 4 : 5) void filter_decide_kernel(ScanParams p)
+template <bool BF16, bool WANT_K, bool WANT_P, int E>
+__global__ __launch_bounds__(64, E > kScanSlots ? 2 : ((WANT_K && WANT_P) ? 4 : 5)) void filter_decide_kernel(ScanParams p)
 {
     constexpr int KB = BF16 ? 16 : 32;
-    constexpr int E = kScanSlots;
     const int lane = threadIdx.x;
     const int r = blockIdx.x;
     FilterRowId id;
@@ -856,17 +873,26 @@ size_t filter_scan_bytes(int64_t rows, int32_t V)
            up((size_t)rows * kKeptList * sizeof(unsigned long long)) + up((size_t)rows * kScanMaxSeg * sizeof(SegInfo));
 }
 
-// Whether the scan + decide pair is worth running: the row's segments share a list of kScanCap entries, and
-// with top-k every segment lists at least k tokens.
-bool filter_scan_applies(int dtype, int32_t V, int32_t top_k)
+// Entries per lane the decide step needs for this call (0: the scan + decide pair is not worth running).  A segment
+// lists about 1.45 top_k tokens for top_k up to ~64 (the lowest of four wavefronts' values lets that many through)
+// and more beyond, as the lanes' maxima run out (1.7 top_k at 136), give or take 20 %; a segment that lists more than
+// its share of the stored list (kScanStore / nseg) sends its row to the per-row kernel, which costs more than the
+// scan saves once it happens in a call.  Measured on 8 segments: no such row up to top_k = 85, some at 100, most
+// at 136.
+static int scan_decide_slots(int dtype, int32_t V, int32_t top_k)
 {
     const int nseg = scan_segments(dtype, V);
-    if (nseg > kScanMaxSeg) return false;
+    if (nseg > kScanMaxSeg) return 0;
     const bool want_k = top_k > 0 && top_k < V;
-    if (!want_k || (int64_t)V <= kScanTiny) return true;
-    // the lowest of four wavefronts' values lets ~1.45 k tokens of a segment through
-    return top_k <= kScanThreads * 3 / 4 && (int64_t)top_k * 3 / 2 <= kScanCap / nseg;
+    if (!want_k || (int64_t)V <= kScanTiny) return kScanSlots;
+    const int64_t listed = (int64_t)top_k * nseg;
+    // a wavefront looks its share of top_k (a quarter) up among its 64 maxima, or 128 with two per lane
+    if (top_k <= kScanThreads * 3 / 4 && listed * 3 / 2 * 5 / 4 <= 64 * kScanSlots) return kScanSlots;   // top_k <= 68 on 8 segments
+    if (top_k <= kScanThreads * 3 / 2 && listed <= 1100) return kScanSlotsWide;   // top_k <= 137 on 8 segments (two maxima per lane)
+    return 0;
 }
+
+bool filter_scan_applies(int dtype, int32_t V, int32_t top_k) { return scan_decide_slots(dtype, V, top_k) > 0; }
 
 static ScanParams scan_params(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                               const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
@@ -884,6 +910,7 @@ static ScanParams scan_params(const void* target, const void* draft, int dtype, 
     const int N = dtype == HOLA_DTYPE_BF16 ? 8 : 4;
     const int64_t nchunks_max = ((int64_t)V + N - 1) / N + 1;   // any alignment of the row
     p.seg_len = (int32_t)((nchunks_max + p.nseg - 1) / p.nseg);
+    p.two_maxima = scan_decide_slots(dtype, V, top_k) > kScanSlots ? 1 : 0;
     size_t off = 0;
     p.cand = (unsigned long long*)(base + off); off += up((size_t)rows * kScanStore * sizeof(unsigned long long));
     p.flags = (int32_t*)(base + off);           off += up((size_t)rows * sizeof(int32_t));
@@ -925,15 +952,16 @@ hipError_t launch_filter_decide(const void* target, const void* draft, int dtype
     const int64_t rows = (int64_t)B * (2 * gamma + 1);
     const bool want_k = top_k > 0 && top_k < V, want_p = top_p > 0.f && top_p < 1.f;
     const dim3 grid((unsigned)rows), block(64);
-#define HOLA_DECIDE(BF, K, P) hipLaunchKernelGGL((filter_decide_kernel<BF, K, P>), grid, block, 0, s, p)
+    const bool wide = scan_decide_slots(dtype, V, top_k) > kScanSlots;   // only with top-k
+#define HOLA_DECIDE(BF, K, P, EE) hipLaunchKernelGGL((filter_decide_kernel<BF, K, P, EE>), grid, block, 0, s, p)
     if (dtype == HOLA_DTYPE_BF16) {
-        if (want_k && want_p) HOLA_DECIDE(true, true, true);
-        else if (want_k) HOLA_DECIDE(true, true, false);
-        else HOLA_DECIDE(true, false, true);
+        if (want_k && want_p) { if (wide) HOLA_DECIDE(true, true, true, kScanSlotsWide); else HOLA_DECIDE(true, true, true, kScanSlots); }
+        else if (want_k) { if (wide) HOLA_DECIDE(true, true, false, kScanSlotsWide); else HOLA_DECIDE(true, true, false, kScanSlots); }
+        else HOLA_DECIDE(true, false, true, kScanSlots);
     } else {
-        if (want_k && want_p) HOLA_DECIDE(false, true, true);
-        else if (want_k) HOLA_DECIDE(false, true, false);
-        else HOLA_DECIDE(false, false, true);
+        if (want_k && want_p) { if (wide) HOLA_DECIDE(false, true, true, kScanSlotsWide); else HOLA_DECIDE(false, true, true, kScanSlots); }
+        else if (want_k) { if (wide) HOLA_DECIDE(false, true, false, kScanSlotsWide); else HOLA_DECIDE(false, true, false, kScanSlots); }
+        else HOLA_DECIDE(false, false, true, kScanSlots);
     }
 #undef HOLA_DECIDE
     return hipGetLastError();

@@ -28,51 +28,83 @@ struct SeqShared {
     double slab_u;
     int32_t slab_ok;
     // draw from a keep set handed over as a list (filtered calls): indices and weights, put in index order
-    int32_t list_idx[64];
-    int32_t list_tok[64];
-    double list_w[64];
+    int32_t list_idx[kKeptListMax];
+    int32_t list_tok[kKeptListMax];
+    double list_w[kKeptListMax];
 };
 
-// Next token of a filtered stop row whose keep set (at most 64 tokens) is at hand as a list of (order key << 32 |
-// index): the weights of these tokens alone, by the sampler's own element formula, summed in index order as the
-// row sweep would (every other token has weight 0).  One wavefront.  Returns the token, -1 if the weights carry
-// no mass, or -2 if the caller should draw from the target's distribution itself (residual without mass).
+// Next token of a filtered stop row whose keep set (at most kKeptListMax tokens) is at hand as a list of
+// (order key << 32 | index): the weights of these tokens alone, by the sampler's own element formula, summed in
+// index order as the row sweep would (every other token has weight 0).  One wavefront, four entries per lane.
+// Returns the token, -1 if the weights carry no mass, or -2 if the caller should draw from the target's
+// distribution itself (residual without mass).
 template <bool BF16>
 __device__ __forceinline__ int32_t sample_kept_list(const RowPair& rp, const unsigned long long* kept, int nk, double u, int lane,
                                                     SeqShared& sh)
 {
-    unsigned long long ent = 0;
-    if (lane < nk) ent = kept[lane];
-    const int32_t idx = lane < nk ? (int32_t)(uint32_t)(ent & 0xffffffffu) : 0x7fffffff;
-    float wk = 0.f;
-    if (lane < nk) {
-        const float xp = key_to_logit<BF16>((uint32_t)(ent >> 32));
-        const float ep = fast_exp2(exp_arg<BF16>(xp, rp.refP, rp.sc));
-        if (rp.bonus) {
-            wk = fmaxf(ep, 0.f);
-        } else {
-            const float xd = load_logit<BF16>(rp.D, idx);
-            float eq = fast_exp2(exp_arg<BF16>(xd, rp.refQ, rp.sc));
-            if (!(xd > rp.thQ || (xd == rp.thQ && idx <= rp.cutQ))) eq = 0.f;   // outside the draft's keep set
-            wk = fmaxf(0.f, __builtin_fmaf(-rp.k_lo, eq, __builtin_fmaf(-rp.k_hi, eq, ep)));
+    constexpr int KL = kKeptListMax / 64;
+    int32_t idx[KL];
+    float wk[KL];
+#pragma unroll
+    for (int j = 0; j < KL; ++j) {
+        const int i = j * 64 + lane;
+        idx[j] = 0x7fffffff;
+        wk[j] = 0.f;
+        if (i < nk) {
+            const unsigned long long ent = kept[i];
+            idx[j] = (int32_t)(uint32_t)(ent & 0xffffffffu);
+            const float xp = key_to_logit<BF16>((uint32_t)(ent >> 32));
+            const float ep = fast_exp2(exp_arg<BF16>(xp, rp.refP, rp.sc));
+            if (rp.bonus) {
+                wk[j] = fmaxf(ep, 0.f);
+            } else {
+                const float xd = load_logit<BF16>(rp.D, idx[j]);
+                float eq = fast_exp2(exp_arg<BF16>(xd, rp.refQ, rp.sc));
+                if (!(xd > rp.thQ || (xd == rp.thQ && idx[j] <= rp.cutQ))) eq = 0.f;   // outside the draft's keep set
+                wk[j] = fmaxf(0.f, __builtin_fmaf(-rp.k_lo, eq, __builtin_fmaf(-rp.k_hi, eq, ep)));
+            }
         }
+        sh.list_idx[i] = idx[j];
     }
-    sh.list_idx[lane] = idx;
     __builtin_amdgcn_wave_barrier();
-    int rank = 0;
-    for (int q = 0; q < nk; ++q) rank += sh.list_idx[q] < idx ? 1 : 0;
-    if (lane < nk) { sh.list_w[rank] = (double)wk * rp.scale; sh.list_tok[rank] = idx; }
+    // place in index order = number of listed tokens with a smaller index
+    int rank[KL];
+#pragma unroll
+    for (int j = 0; j < KL; ++j) rank[j] = 0;
+    for (int q = 0; q < nk; ++q) {
+        const int32_t o = sh.list_idx[q];
+#pragma unroll
+        for (int j = 0; j < KL; ++j) rank[j] += o < idx[j] ? 1 : 0;
+    }
+#pragma unroll
+    for (int j = 0; j < KL; ++j)
+        if (j * 64 + lane < nk) { sh.list_w[rank[j]] = (double)wk[j] * rp.scale; sh.list_tok[rank[j]] = idx[j]; }
     __builtin_amdgcn_wave_barrier();
-    const double v = lane < nk ? sh.list_w[lane] : 0.0;
-    const double incl = wave_inclusive_scan(v, lane);
+    // lane l holds places KL l .. KL l + KL - 1
+    double v[KL], mine = 0.0;
+#pragma unroll
+    for (int j = 0; j < KL; ++j) { const int i = lane * KL + j; v[j] = i < nk ? sh.list_w[i] : 0.0; mine += v[j]; }
+    const double incl = wave_inclusive_scan(mine, lane);
     const double Z = __shfl(incl, 63, 64);
     if (!(Z > 0.0) || !(Z - Z == 0.0)) return rp.bonus ? -1 : -2;
     const double target = u * Z;
-    const unsigned long long hit = __ballot(lane < nk && incl > target);
-    const unsigned long long haveW = __ballot(v > 0.0);
+    const unsigned long long hit = __ballot(incl > target);
+    const unsigned long long haveW = __ballot(mine > 0.0);
     if (!haveW) return -1;
     const int src = hit ? (__ffsll((long long)hit) - 1) : (63 - __clzll((long long)haveW));   // rounding at the top end: the last weight
-    return sh.list_tok[src];
+    int32_t tok = -1;
+    if (lane == src) {
+        double run = incl - mine;
+        int last = -1;
+#pragma unroll
+        for (int j = 0; j < KL; ++j) {
+            if (v[j] > 0.0) last = j;
+            run += v[j];
+            if (tok < 0 && hit && run > target) tok = sh.list_tok[lane * KL + j];
+        }
+        if (tok < 0 && last >= 0) tok = sh.list_tok[lane * KL + last];
+    }
+    return __shfl(tok, src, 64);
 }
 
 __device__ __forceinline__ AcceptCtx accept_ctx(const FusedParams& p)
@@ -192,8 +224,8 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
     if (FILT && p.kept != nullptr && rp.ok) {
         const int64_t rid = (int64_t)b * (2 * g + 1) + g + si.row;
         list_n = p.kept_n[rid];
-        list = p.kept + rid * 64;
-        if (list_n < 1 || list_n > 64) list_n = 0;
+        list = p.kept + rid * kKeptListMax;
+        if (list_n < 1 || list_n > kKeptListMax) list_n = 0;
     }
 
     int32_t tok = -1;

@@ -10,6 +10,7 @@ constexpr int kWaves = 4;              // wavefronts per workgroup in the stream
 constexpr int kBlock = 64 * kWaves;    // 256 threads
 constexpr int kMaxSplit = 16;          // workgroups per row, upper bound (sizes the partials)
 constexpr int kTileChunks = 4;         // 16-byte chunks per lane in one sampler tile
+constexpr int kKeptListMax = 256;      // longest top-k / top-p keep set handed from the filter to the sampler as a list
 
 // One wavefront's share of a row: the sums are S = sum 2^(x*c + bref), T = sum (x*c + bref) 2^(x*c + bref)
 // with c = log2(e)/T and bref an integer-valued reference chosen so the largest term is O(1).
@@ -122,7 +123,7 @@ struct FusedParams {
     int32_t* glue_tok; int32_t* glue_len; int64_t glue_ld;
     int32_t glue_keep_next;            // 1: append the next token; 0: the kept tokens only
     const RowFilter* filters;          // top-k / top-p keep sets (slots as the partials), or null
-    // short keep sets written out as lists of (order key << 32 | index), 64 entries per row r = b (2 gamma + 1) + k,
+    // short keep sets written out as lists of (order key << 32 | index), kKeptListMax entries per row r = b (2 gamma + 1) + k,
     // and their lengths (-1: no list); null when the filter's scan did not run
     const unsigned long long* kept; const int32_t* kept_n;
 };

@@ -120,7 +120,7 @@ def compare_filtered(target, draft, tokens, seed, T, tau, top_k, top_p, got, dra
     return listed, max_dh, ref
 
 
-FILTERS = [(50, 0.0), (0, 0.9), (40, 0.8), (1, 0.0), (0, 0.05), (0, 0.999), (1000, 0.97)]
+FILTERS = [(50, 0.0), (0, 0.9), (40, 0.8), (1, 0.0), (0, 0.05), (0, 0.999), (1000, 0.97), (100, 0.0), (120, 0.9)]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
