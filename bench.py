@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # HBM traffic of one launch of the dominant kernel on the headline workload, from rocprofv3 --pmc
 # FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy of known size (see profiles/); None until measured.
 # (filter_scan_kernel: measured with --top-k 50 --top-p 0.95.)
-MEASURED_TRAFFIC_BYTES = {"row_stats_kernel": 1117785113, "fused_kernel": None, "filter_scan_kernel": 1148460442}
+MEASURED_TRAFFIC_BYTES = {"row_stats_kernel": 1117785113, "fused_kernel": None, "filter_scan_kernel": 1154513715}
 
 
 def log(*a):
