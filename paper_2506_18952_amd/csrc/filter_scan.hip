@@ -16,11 +16,17 @@
 // (key << 32 | index); the segment reports their number, its edge, whether it met NaN / +inf, and for top-p alone
 // the mass of its other tokens relative to the edge.  No global atomics, nothing to clear beforehand.
 //
-// Decide: the wavefront holds the row's list in registers (up to 16 entries per lane) and finds the k-th largest
-// key, the key at which the cumulative mass reaches the nucleus target, and the index of the last kept tie by
-// radix descents over ballots and wavefront sums, skipping the key bits on which all entries agree.  Sums over
-// the kept tokens are integers in fixed point, so neither the order of the list nor the number of segments
-// changes a bit of the result.
+// For a larger top_k (69 .. 137 on eight segments) the 64 maxima of a wavefront run out: the rank is then looked up
+// among two maxima per lane (those of the two halves of its chunks, disjoint sets of tokens as well).
+//
+// Decide: the wavefront holds the row's list in registers (16 entries per lane, 32 for the larger top_k), drops what
+// lies below the highest segment edge, finds the k-th largest key by a radix descent over ballots (skipping the key
+// bits on which all entries agree), keeps the tokens at or above it, and finds the end of the nucleus either by
+// walking the cumulative mass of those tokens in the order of the definition (when they fit one lane each) or by a
+// radix descent with wavefront sums.  Sums over the kept tokens are integers in fixed point, so neither the order
+// of the list nor the number of segments changes a bit of the result.  A keep set of at most 256 tokens is also
+// written out as a list: the sampler then draws from those tokens alone.  The kernel is compiled per combination
+// of filters, so each carries only its own code and registers.
 #include "filter_device.h"
 
 namespace hola {
