@@ -160,3 +160,38 @@ def test_supplied_target_statistics_argument_checks():
     assert hb.lib().hola_verify_ex(C.byref(a)) == hb.HOLA_ERR_UNSUPPORTED
     a = _args(target_stats_in=0x2000, temperature=0.0)
     assert hb.lib().hola_verify_ex(C.byref(a)) == hb.HOLA_ERR_UNSUPPORTED
+
+
+def test_header_is_plain_c_and_matches_the_binding(tmp_path):
+    """include/hola.h compiles as C99 without warnings, and every structure of the binding has the size and the
+    field offsets the C compiler gives the header's (same field names, same order)."""
+    import ctypes as C
+    import re
+    import shutil
+    import subprocess
+
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pairs = [("hola_verify_args", hb.VerifyArgs), ("hola_model_logits", hb.ModelLogits), ("hola_hsd_args", hb.HsdArgs),
+             ("hola_tuning", hb.Tuning)]
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "hola.h"', 'int main(void) {']
+    for cname, cls in pairs:
+        lines.append(f'  printf("{cname} size %zu\\n", sizeof({cname}));')
+        for fname, _ in cls._fields_:
+            lines.append(f'  printf("{cname} {fname} %zu\\n", offsetof({cname}, {fname}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    got = {}
+    for m in re.finditer(r"(\w+) (\w+) (\d+)", out):
+        got[(m.group(1), m.group(2))] = int(m.group(3))
+    for cname, cls in pairs:
+        assert got[(cname, "size")] == C.sizeof(cls), cname
+        for fname, _ in cls._fields_:
+            assert got[(cname, fname)] == getattr(cls, fname).offset, (cname, fname)
