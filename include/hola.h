@@ -206,6 +206,9 @@ typedef struct {
     int32_t* out_accept_len; int32_t* out_next_token;   /* device [B] */
     float* out_entropy;               /* device [n_models-1, B, gamma+n_models-2] or NULL */
     void* workspace; size_t workspace_bytes; hola_stream_t stream;
+    int32_t top_k; float top_p;       /* as in hola_verify_args, applied to both models of every level (0 / 0: off).
+                                         Filtered levels take no statistics from one another: each finds the keep
+                                         sets and statistics of its own rows.  Needs row_temperature == NULL. */
 } hola_hsd_args;
 hola_status hola_hsd_verify_ex(const hola_hsd_args* args /* host */);
 

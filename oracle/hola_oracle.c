@@ -692,7 +692,7 @@ int32_t oracle_sample_interval(const oracle_verify_args* a, int32_t b, int32_t a
 /* with survivors_only, its accepted tokens alone: the other reading of "the   */
 /* target verifies the survivors", which is not lossless).                     */
 /* models[k] has gamma+k rows per sequence; tau[k-1] gates level k on the      */
-/* entropy of models[k-1].                                                     */
+/* entropy of models[k-1] (of its filtered distribution when filters are on).  */
 /* ------------------------------------------------------------------------- */
 int32_t oracle_hsd_verify(const void* const* model_logits, const int64_t* model_ld, int32_t n_models,
                           int32_t dtype, const int32_t* draft_tokens, uint64_t seed, int64_t seq_base,
@@ -705,6 +705,7 @@ int32_t oracle_hsd_verify(const void* const* model_logits, const int64_t* model_
                           int32_t* out_level_accept,/* [n_models-1, B] or NULL */
                           int32_t* out_level_next,  /* [n_models-1, B] or NULL */
                           int32_t survivors_only,   /* alternative reading: pass on the kept tokens only */
+                          int32_t top_k, double top_p, /* filters on both models of every level; 0 and 1: none */
                           int32_t num_threads)
 {
     if (n_models < 2 || B < 0 || gamma < 1 || gamma + n_models - 2 > 63) return -1;
@@ -749,7 +750,11 @@ int32_t oracle_hsd_verify(const void* const* model_logits, const int64_t* model_
         a.out_next_token = nxt;
         a.out_entropy = ent;
         a.num_threads = num_threads;
-        rc = oracle_verify(&a);
+        /* A level on filtered distributions is the filtered step with that level's pair of models: both sides
+           of its ratio test and its residual are the renormalised kept sets, so each level stays exact with
+           respect to its own filtered verifier. */
+        const int filtered = (top_k > 0 && top_k < V) || top_p < 1.0;
+        rc = filtered ? oracle_verify_filtered(&a, top_k, top_p, NULL, NULL, NULL) : oracle_verify(&a);
         for (int32_t b = 0; b < B && rc == 0; ++b) {
             if (out_entropy)
                 for (int32_t j = 0; j < gk; ++j)

@@ -93,7 +93,7 @@ def lib() -> C.CDLL:
                                         C.c_uint64, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                         C.c_void_p, C.c_float, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                        C.c_void_p, C.c_void_p, C.c_int32, C.c_int32]
+                                        C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_int32]
         L.oracle_hsd_verify.restype = C.c_int32
         L.oracle_verify_literal.argtypes = [C.POINTER(_Args), C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_verify_literal.restype = C.c_int32
@@ -338,8 +338,10 @@ class HsdResult:
 
 
 def hsd_verify(models: Sequence[np.ndarray], draft_tokens, seed, temperature, tau: Sequence[float],
-               row_temperature=None, seq_base=0, survivors_only=False, num_threads=0) -> HsdResult:
-    """Hierarchical verify: models[0] is the smallest drafter [B,gamma,V], models[k] has gamma+k rows."""
+               row_temperature=None, seq_base=0, survivors_only=False, num_threads=0,
+               top_k=0, top_p=1.0) -> HsdResult:
+    """Hierarchical verify: models[0] is the smallest drafter [B,gamma,V], models[k] has gamma+k rows.
+    top_k / top_p: every level runs the filtered step on its pair of models."""
     arrs, dts = zip(*[_logits(m) for m in models])
     assert len(set(dts)) == 1
     n = len(arrs)
@@ -358,7 +360,8 @@ def hsd_verify(models: Sequence[np.ndarray], draft_tokens, seed, temperature, ta
     rc = lib().oracle_hsd_verify(C.addressof(ptrs), None, n, dts[0], _ptr(tok), int(seed), int(seq_base),
                                  B, g, V, _ptr(rowT), float(temperature), _ptr(tau_a),
                                  _ptr(r.tokens), _ptr(r.accept_len), _ptr(r.next_token), _ptr(r.entropy),
-                                 _ptr(r.level_accept), _ptr(r.level_next), int(bool(survivors_only)), int(num_threads))
+                                 _ptr(r.level_accept), _ptr(r.level_next), int(bool(survivors_only)),
+                                 int(top_k or 0), float(1.0 if top_p is None else top_p), int(num_threads))
     if rc != 0:
         raise ValueError("oracle_hsd_verify rejected its arguments")
     return r

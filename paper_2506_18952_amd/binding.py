@@ -68,6 +68,7 @@ class HsdArgs(C.Structure):
         ("out_tokens", C.c_void_p), ("out_accept_len", C.c_void_p), ("out_next_token", C.c_void_p),
         ("out_entropy", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p),
+        ("top_k", C.c_int32), ("top_p", C.c_float),
     ]
 
 
@@ -257,7 +258,8 @@ def hola_hsd_verify(models: Sequence, draft_tokens, seed, B, gamma, V, temperatu
 
 def hola_hsd_verify_ex(models: Sequence, draft_tokens, seed, B, gamma, V, temperature, tau: Sequence[float],
                        out_tokens, out_accept_len, out_next_token, out_entropy, workspace, survivors_only=False,
-                       row_temperature=None, seq_base=0, lds: Optional[Sequence[int]] = None, stream=None) -> None:
+                       row_temperature=None, seq_base=0, lds: Optional[Sequence[int]] = None, stream=None,
+                       top_k=0, top_p=0.0) -> None:
     n = len(models)
     arr = (ModelLogits * n)()
     for k, m in enumerate(models):
@@ -274,6 +276,7 @@ def hola_hsd_verify_ex(models: Sequence, draft_tokens, seed, B, gamma, V, temper
     a.out_entropy = _ptr(out_entropy)
     a.workspace, a.workspace_bytes = _ptr(workspace), workspace.numel() * workspace.element_size()
     a.stream = _stream_handle(stream)
+    a.top_k, a.top_p = int(top_k), float(top_p)
     _check(lib().hola_hsd_verify_ex(C.byref(a)), "hola_hsd_verify_ex")
 
 

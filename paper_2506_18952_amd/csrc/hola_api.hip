@@ -513,8 +513,10 @@ hola_status hola_hsd_verify_ex(const hola_hsd_args* args)
         a.target_logits = models[k].logits; a.draft_logits = models[k - 1].logits; a.dtype = dtype;
         a.target_ld = models[k].ld; a.draft_ld = models[k - 1].ld;
         a.draft_tokens = cur_tok; a.draft_len = cur_len; a.row_temperature = row_temperature;
-        a.draft_stats_in = cur_stats;
-        a.target_stats_out = (k < L) ? h.stats[k & 1] : nullptr;
+        a.top_k = args->top_k; a.top_p = args->top_p;
+        const bool filtered = (args->top_k != 0 && args->top_k < V) || (args->top_p != 0.f && !(args->top_p >= 1.f));
+        a.draft_stats_in = filtered ? nullptr : cur_stats;
+        a.target_stats_out = (k < L && !filtered) ? h.stats[k & 1] : nullptr;
         a.seed = seed; a.level = (uint32_t)(k - 1); a.seq_base = seq_base;
         a.B = B; a.gamma = gk; a.V = V; a.temperature = temperature; a.entropy_threshold = tau[k - 1];
         a.out_accept_len = out_accept_len; a.out_next_token = out_next_token;

@@ -28,7 +28,7 @@ def filter_path(request):
 
 
 def run_filtered(target, draft, tokens, seed, T, tau, top_k, top_p, draft_len=None, target_ld=0, draft_ld=0,
-                 dev=None):
+                 dev=None, level=0):
     P, D = dev if dev is not None else (to_dev(target), to_dev(draft))
     B, g = tokens.shape
     V = target.shape[-1]
@@ -42,7 +42,7 @@ def run_filtered(target, draft, tokens, seed, T, tau, top_k, top_p, draft_len=No
     hb.hola_verify_ex(target_logits=P, draft_logits=D, draft_tokens=tok, seed=seed, B=B, gamma=g, V=V, temperature=T,
                       entropy_threshold=tau, out_accept_len=acc, out_next_token=nxt, out_entropy=ent, workspace=ws,
                       draft_len=dl, top_k=top_k, top_p=top_p, target_ld=target_ld, draft_ld=draft_ld,
-                      out_keep_count=keep)
+                      out_keep_count=keep, level=level)
     torch.cuda.synchronize()
     return acc.cpu().numpy(), nxt.cpu().numpy(), ent.cpu().numpy(), keep.cpu().numpy()
 
@@ -66,14 +66,16 @@ def _cut_is_within_tolerance(row, T, top_k, top_p, m_gpu):
     return bool(reaches and shortest)
 
 
-def compare_filtered(target, draft, tokens, seed, T, tau, top_k, top_p, got, draft_len=None, max_listed=None):
+def compare_filtered(target, draft, tokens, seed, T, tau, top_k, top_p, got, draft_len=None, max_listed=None,
+                     level=0):
     """Keep counts: equal to the oracle's (top-k alone: always; nucleus: unless the rule holds for the GPU's count
     within CUT_TOL).  Then the oracle follows the GPU's cuts and every decision must match outside the listed
     near-threshold comparisons (gate, ratio, sampling uniform)."""
     acc, nxt, ent, keep = got
     T = float(np.float32(T))
     tp = top_p if 0.0 < top_p < 1.0 else 1.0
-    ref0 = orc.verify_filtered(target, draft, tokens, seed, T, tau, top_k=top_k, top_p=tp, draft_len=draft_len)
+    ref0 = orc.verify_filtered(target, draft, tokens, seed, T, tau, top_k=top_k, top_p=tp, draft_len=draft_len,
+                               level=level)
     B, g = tokens.shape
     lens = np.full(B, g, np.int32) if draft_len is None else np.asarray(draft_len, np.int32)
     moved = 0
@@ -93,7 +95,7 @@ def compare_filtered(target, draft, tokens, seed, T, tau, top_k, top_p, got, dra
                 assert _cut_is_within_tolerance(row, T, top_k, tp, int(keep[b, k])), (b, k, keep[b, k], ref0.keep_count[b, k])
                 moved += 1
     ref = ref0 if moved == 0 else orc.verify_filtered(target, draft, tokens, seed, T, tau, top_k=top_k, top_p=tp,
-                                                      draft_len=draft_len, force_keep_count=keep)
+                                                      draft_len=draft_len, force_keep_count=keep, level=level)
     rtol = 1e-5 if np.asarray(target).dtype == np.float32 else 2e-3
     gm = np.where(np.isnan(ref.gate_margin), np.inf, ref.gate_margin)
     rm = np.where(np.isnan(ref.ratio_margin), np.inf, ref.ratio_margin)
@@ -334,3 +336,86 @@ def test_filtered_call_in_a_hip_graph():
             assert torch.equal(o, e), f"replay {rep} differs from the eager call"
         call()                                              # eager work between the replays
         torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------- filters in the hierarchy driver
+def _filtered_chain(models, tokens, seed, T, taus, top_k, top_p, name):
+    """hola_hsd_verify_ex with filters against a walk of stand-alone filtered levels, each compared with the oracle's
+    filtered step on the same inputs; without near-threshold cases the whole chain equals the oracle's chain."""
+    ms = [to_dev(m) for m in models]
+    n = len(ms)
+    B, g, V = models[0].shape
+    L, gmax = n - 1, g + n - 2
+    out_tok = torch.full((B, g + n - 1), -7, dtype=torch.int32, device=DEV)
+    acc = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    nxt = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    ent = torch.full((L, B, gmax), -7.0, dtype=torch.float32, device=DEV)
+    ws = hb.alloc_workspace(hb.hola_hsd_workspace_bytes(n, B, g, V), DEV)
+    hb.hola_hsd_verify_ex(ms, to_dev(tokens), seed, B, g, V, T, taus, out_tok, acc, nxt, ent, ws,
+                          top_k=top_k, top_p=top_p)
+    torch.cuda.synchronize()
+    out_tok, acc, nxt, ent = out_tok.cpu().numpy(), acc.cpu().numpy(), nxt.cpu().numpy(), ent.cpu().numpy()
+    cur_tok, cur_len = np.asarray(tokens, np.int32), np.full(B, g, np.int32)
+    listed_all = 0
+    for k in range(1, n):
+        gk = g + k - 1
+        got = run_filtered(models[k], models[k - 1], cur_tok, seed, T, taus[k - 1], top_k, top_p, draft_len=cur_len,
+                           level=k - 1)
+        listed, dh, ref = compare_filtered(models[k], models[k - 1], cur_tok, seed, T, taus[k - 1], top_k, top_p, got,
+                                           draft_len=cur_len, level=k - 1)
+        print(f"[parity] filtered chain {name} k={top_k} p={top_p} level {k}: listed={listed} max|dH|={dh:.2e} "
+              f"accept hist {np.bincount(got[0], minlength=gk + 1).tolist()}", flush=True)
+        listed_all += listed
+        a_k, n_k, e_k, _ = got
+        np.testing.assert_array_equal(ent[k - 1][:, :gk], e_k)      # the driver's level is the stand-alone level
+        assert np.all(ent[k - 1][:, gk:] == -1.0)
+        if k < n - 1:
+            nt = np.full((B, gk + 1), -1, np.int32)
+            for b in range(B):
+                nt[b, :a_k[b]] = cur_tok[b, :a_k[b]]
+                nt[b, a_k[b]] = n_k[b]
+            cur_tok, cur_len = nt, a_k + 1
+        else:
+            np.testing.assert_array_equal(acc, a_k)
+            np.testing.assert_array_equal(nxt, n_k)
+            for b in range(B):
+                assert np.array_equal(out_tok[b, :cur_len[b]], cur_tok[b, :cur_len[b]])
+                assert np.all(out_tok[b, cur_len[b]:] == -1)
+    if listed_all == 0 and not (0.0 < top_p < 1.0):               # a nucleus cut may sit within its own tolerance
+        ref = orc.hsd_verify(models, tokens, seed, T, taus, top_k=top_k, top_p=1.0)
+        np.testing.assert_array_equal(acc, ref.accept_len)
+        np.testing.assert_array_equal(nxt, ref.next_token)
+        np.testing.assert_array_equal(out_tok, ref.tokens)
+
+
+@pytest.mark.parametrize("top_k,top_p", [(50, 0.0), (0, 0.9), (40, 0.95)])
+def test_two_level_chain_with_filters_bf16(top_k, top_p):
+    w = wl.config4(B=24, V=30011, gamma=5)
+    _filtered_chain(w.models, w.tokens, w.seed, w.temperature, w.taus, top_k, top_p, w.name)
+
+
+def test_three_level_chain_with_filters_f32():
+    rng = np.random.default_rng(6)
+    B, g, V = 9, 3, 4099
+    base = (2 * rng.standard_normal((B, g + 3, V))).astype(np.float32)
+    models = [(base[:, :g + k] + (0.9 - 0.3 * k) * rng.standard_normal((B, g + k, V))).astype(np.float32)
+              for k in range(3)] + [base]
+    tok = np.argsort(-models[0], axis=-1, kind="stable")[:, :, :4][np.arange(B)[:, None], np.arange(g)[None, :],
+                                                                  rng.integers(0, 4, (B, g))].astype(np.int32)
+    _filtered_chain(models, tok, 13, 1.0, [2.0, 3.0, 4.0], 20, 0.0, "three-level f32")
+    _filtered_chain(models, tok, 13, 1.0, [2.0, 3.0, 4.0], 0, 0.5, "three-level f32")
+
+
+def test_chain_with_filters_refuses_row_temperature():
+    w = wl.config4(B=4, V=1001, gamma=2)
+    ms = [to_dev(m) for m in w.models]
+    B, g, V = w.models[0].shape
+    n = len(ms)
+    out_tok = torch.zeros((B, g + n - 1), dtype=torch.int32, device=DEV)
+    acc = torch.zeros((B,), dtype=torch.int32, device=DEV)
+    nxt = torch.zeros((B,), dtype=torch.int32, device=DEV)
+    ws = hb.alloc_workspace(hb.hola_hsd_workspace_bytes(n, B, g, V), DEV)
+    rt = to_dev(np.full(B, 0.7, np.float32))
+    with pytest.raises(hb.HolaError):
+        hb.hola_hsd_verify_ex(ms, to_dev(w.tokens), 1, B, g, V, 1.0, w.taus, out_tok, acc, nxt, None, ws,
+                              row_temperature=rt, top_k=5)

@@ -190,3 +190,87 @@ def test_forced_keep_count_moves_only_the_cut():
     mask = np.ones_like(base.keep_count, bool); mask[2, 0] = False
     assert np.array_equal(moved.keep_count[mask], base.keep_count[mask])
     assert np.array_equal(np.delete(moved.entropy64.ravel(), 2 * 3), np.delete(base.entropy64.ravel(), 2 * 3))
+
+
+# ----------------------------------------------------------------------------- filters in the hierarchy driver
+def _hier_case(B=24, g=3, V=60, seed=8):
+    rng = np.random.default_rng(seed)
+    base = (1.5 * rng.standard_normal((B, g + 2, V))).astype(np.float32)
+    small = (base[:, :g] + rng.standard_normal((B, g, V))).astype(np.float32)
+    mid = (base[:, :g + 1] + 0.4 * rng.standard_normal((B, g + 1, V))).astype(np.float32)
+    tok = np.zeros((B, g), np.int32)
+    return [small, mid, base], tok, rng
+
+
+def test_hierarchy_with_filters_off_is_the_unfiltered_chain():
+    models, tok, rng = _hier_case()
+    tok[:] = rng.integers(0, models[0].shape[-1], tok.shape)
+    taus = [1.0, 2.0]
+    plain = orc.hsd_verify(models, tok, 5, 0.9, taus)
+    for top_k, top_p in ((0, 1.0), (models[0].shape[-1], 1.0), (10 ** 6, 1.0)):
+        h = orc.hsd_verify(models, tok, 5, 0.9, taus, top_k=top_k, top_p=top_p)
+        for f in ("tokens", "accept_len", "next_token", "entropy", "level_accept", "level_next"):
+            np.testing.assert_array_equal(getattr(h, f), getattr(plain, f))
+
+
+@pytest.mark.parametrize("top_k,top_p", [(5, 1.0), (0, 0.8), (12, 0.9)])
+def test_filtered_hierarchy_is_one_filtered_step_per_level(top_k, top_p):
+    models, tok, rng = _hier_case()
+    B, g, V = models[0].shape
+    for b in range(B):
+        for j in range(g):
+            keep, _, _, _ = orc.filter_row(models[0][b, j], 1.0, top_k, top_p)
+            tok[b, j] = rng.choice(np.flatnonzero(keep))
+    taus = [0.3 * math.log(V), 0.5 * math.log(V)]
+    h = orc.hsd_verify(models, tok, 3, 1.0, taus, top_k=top_k, top_p=top_p)
+    l1 = orc.verify_filtered(models[1], models[0], tok, 3, 1.0, taus[0], top_k=top_k, top_p=top_p, level=0)
+    np.testing.assert_array_equal(h.level_accept[0], l1.accept_len)
+    np.testing.assert_array_equal(h.level_next[0], l1.next_token)
+    tok2 = np.full((B, g + 1), -1, np.int32)
+    for b in range(B):
+        a = l1.accept_len[b]
+        tok2[b, :a] = tok[b, :a]
+        tok2[b, a] = l1.next_token[b]
+    l2 = orc.verify_filtered(models[2], models[1], tok2, 3, 1.0, taus[1], top_k=top_k, top_p=top_p,
+                             draft_len=l1.accept_len + 1, level=1)
+    np.testing.assert_array_equal(h.accept_len, l2.accept_len)
+    np.testing.assert_array_equal(h.next_token, l2.next_token)
+    np.testing.assert_array_equal(h.tokens[:, :g + 1], tok2)
+    np.testing.assert_array_equal(h.entropy[0][:, :g], l1.entropy)
+    np.testing.assert_array_equal(h.entropy[1], l2.entropy)
+    # every token a level hands on lies in that level's verifier's keep set, so the next level's ratio test
+    # never divides by a filtered-out draft probability
+    for b in range(B):
+        a = l1.accept_len[b]
+        keep, _, _, _ = orc.filter_row(models[1][b, a], 1.0, top_k, top_p)
+        assert keep[l1.next_token[b]]
+    plain = orc.hsd_verify(models, tok, 3, 1.0, taus)
+    assert not np.array_equal(plain.next_token, h.next_token)    # the filters matter on this case
+
+
+def test_filtered_two_level_first_token_follows_filtered_final_target():
+    """Gate off, tiny V: drafts drawn from the smallest model's filtered distribution; the first token the
+    two-level chain emits is distributed as the final target's filtered p_0."""
+    rng = np.random.default_rng(23)
+    V, g, N, top_k = 6, 1, 150_000, 3
+    base = (1.3 * rng.standard_normal((g + 2, V))).astype(np.float32)
+    small1 = (base[:g] + rng.standard_normal((g, V))).astype(np.float32)
+    mid1 = (base[:g + 1] + 0.6 * rng.standard_normal((g + 1, V))).astype(np.float32)
+    models = [np.broadcast_to(m, (N,) + m.shape).copy() for m in (small1, mid1, base)]
+
+    def filtered(row):
+        z = row.astype(np.float64)
+        keep = _np_keep(z, top_k, 1.0)
+        p = np.where(keep, np.exp(z - z.max()), 0.0)
+        return p / p.sum()
+
+    tok = rng.choice(V, size=(N, 1), p=filtered(small1[0])).astype(np.int32)
+    h = orc.hsd_verify(models, tok, 41, 1.0, [0.0, 0.0], top_k=top_k)
+    first = np.where(h.accept_len >= 1, h.tokens[:, 0], h.next_token)
+    want = filtered(base[0])
+    counts = np.bincount(first, minlength=V)
+    assert np.all(counts[want == 0] == 0)
+    assert scipy.stats.chisquare(counts[want > 0], N * want[want > 0]).pvalue > 1e-3
+    full = scipy.special.softmax(base[0].astype(np.float64))    # the unfiltered target is told apart
+    assert scipy.stats.chisquare(counts, N * full).pvalue < 1e-6
+    assert set(np.flatnonzero(filtered(mid1[0]))) != set(np.flatnonzero(want))   # the keep sets differ by level
