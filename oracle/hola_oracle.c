@@ -37,7 +37,9 @@
  * tile merge = statistics of the whole row (itself pinned to scipy); top-k /
  * top-p keep sets = numpy stable sort + cumsum, filtered statistics = scipy on
  * the kept subset, filters off = the unfiltered step, output marginal = the
- * filtered target.
+ * filtered target; token trees: a chain = the one-token step, several
+ * candidates = a direct numpy restatement, closed-form accept rates, output
+ * marginal = p by brute force over the candidates.
  * No function in this file is "parity unpinned".
  */
 #include <math.h>
@@ -841,6 +843,188 @@ int32_t oracle_verify_literal(const oracle_verify_args* a, int32_t* out_tokens /
         if (out_calls) out_calls[b] = calls;
     }
     free(w);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Token trees (several drafted tokens per position).  The paper drafts one    */
+/* token per position; this is the multi-candidate generalisation of the same  */
+/* step, with the published recursive rejection rule for several candidates    */
+/* drawn independently from the same draft distribution (Miao et al.,          */
+/* "SpecInfer", multi-step speculative sampling):                              */
+/*   context c = the prefix plus the tokens on the path to node c-1 (c = 0:    */
+/*   the prefix alone); q_c, p_c = the two models' distributions after it.     */
+/*   The children of a context are tried in node order against a running       */
+/*   distribution r, r = p_c at first: child x is kept iff u q_c(x) < r(x);    */
+/*   after a rejection r <- max(0, r - q_c) / its sum.  A kept child becomes   */
+/*   the context; when every child is rejected the next token is drawn from    */
+/*   r and the walk stops; a context without children draws from p_c.          */
+/* The gate of Algorithm 1, Step 1 acts on the context's draft entropy: with   */
+/* H(q_c) < tau the first child is kept without a test (Equation (1), draft    */
+/* branch).  A chain (node n's parent is n-1) is exactly the one-token step    */
+/* above, uniforms included: node n's test uses word 0 of block (n, level),    */
+/* the draw at context c uses word 1 of block (c, level).                      */
+/* A residual without mass after a rejection (impossible in exact arithmetic)  */
+/* ends the walk with a draw from p_c, like the one-token step.                */
+/* Margins: gate |H - tau| per context; test |u - r(x)/q(x)| scaled by         */
+/* Z / max(1, C), Z the product of the residual sums so far and C the sum of   */
+/* those products before it (the size of the test in the unnormalised terms    */
+/* max(0, p - C q) that an implementation may use); both 1, 0 for a first      */
+/* child.                                                                      */
+/* ------------------------------------------------------------------------- */
+typedef struct {
+    const void* target_logits;      /* [B, N+1, V] row c: context c */
+    const void* draft_logits;       /* [B, N, V]   row c: context c (rows of contexts without children are not read) */
+    int32_t dtype;
+    int64_t target_ld, draft_ld;
+    const int32_t* node_token;      /* [B, N] */
+    const int32_t* node_parent;     /* [B, N] -1: child of the prefix; else an earlier node */
+    const int32_t* n_nodes;         /* [B] in [0, N] or NULL => N */
+    uint64_t seed;
+    uint32_t level;
+    int64_t seq_base;
+    int32_t B, N, V;
+    float temperature, entropy_threshold;
+    /* outputs; any may be NULL */
+    int32_t* out_accept_len;        /* [B] kept nodes */
+    int32_t* out_path;              /* [B, N] kept nodes from the prefix on, -1 beyond */
+    int32_t* out_next_token;        /* [B] */
+    float* out_entropy;             /* [B, N] H(q_c) of contexts with children, -1 elsewhere */
+    double* out_entropy64;          /* [B, N] NaN elsewhere */
+    double* out_gate_margin;        /* [B, N] per context, NaN where unused or not visited */
+    double* out_ratio_margin;       /* [B, N] per node, NaN where not tested */
+    double* out_sample_margin;      /* [B] */
+    int32_t num_threads;
+} oracle_tree_args;
+
+static void tree_one_sequence(const oracle_tree_args* a, int32_t b, double* pr, double* q, double* w)
+{
+    const int32_t N = a->N, V = a->V;
+    const int64_t tld = a->target_ld ? a->target_ld : V;
+    const int64_t dld = a->draft_ld ? a->draft_ld : V;
+    int32_t len = a->n_nodes ? a->n_nodes[b] : N;
+    if (len < 0) len = 0;
+    if (len > N) len = N;
+    const double T = (double)a->temperature;
+    const double tau = (double)a->entropy_threshold;
+    const int64_t seq = a->seq_base + b;
+    const int32_t* tok = a->node_token + (int64_t)b * N;
+    const int32_t* par = a->node_parent + (int64_t)b * N;
+
+    for (int32_t c = 0; c < N; ++c) {
+        const int64_t o = (int64_t)b * N + c;
+        if (a->out_path) a->out_path[o] = -1;
+        if (a->out_entropy) a->out_entropy[o] = -1.0f;
+        if (a->out_entropy64) a->out_entropy64[o] = NAN;
+        if (a->out_gate_margin) a->out_gate_margin[o] = NAN;
+        if (a->out_ratio_margin) a->out_ratio_margin[o] = NAN;
+    }
+    /* the draft entropy of every context that has a child */
+    for (int32_t c = 0; c < len; ++c) {
+        int has = 0;
+        for (int32_t n = c; n < len; ++n) if (par[n] == c - 1) has = 1;
+        if (!has) continue;
+        double lse, H;
+        oracle_row_stats(a->draft_logits, a->dtype, ((int64_t)b * N + c) * dld, V, T, &lse, &H, NULL);
+        if (a->out_entropy) a->out_entropy[(int64_t)b * N + c] = (float)H;
+        if (a->out_entropy64) a->out_entropy64[(int64_t)b * N + c] = H;
+    }
+
+    int32_t ctx = 0, depth = 0, next = -1;
+    double smargin = NAN;
+    for (;;) {
+        const int64_t t_off = ((int64_t)b * (N + 1) + ctx) * tld;
+        double lseP, HP;
+        oracle_row_stats(a->target_logits, a->dtype, t_off, V, T, &lseP, &HP, NULL);
+        for (int32_t i = 0; i < V; ++i) pr[i] = prob_at(a->target_logits, a->dtype, t_off, i, T, lseP);
+        int32_t nkids = 0;
+        for (int32_t n = ctx; n < len; ++n) if (par[n] == ctx - 1) ++nkids;
+        uint32_t rb[4];
+        hsd_random_block(a->seed, seq, (uint32_t)ctx, a->level, rb);
+        const double u2 = oracle_u24(rb[1]);
+        double Zs;
+        if (nkids == 0) {                                  /* nothing drafted here: the token is the verifier's */
+            next = oracle_inverse_cdf(pr, V, u2, &Zs, &smargin);
+            break;
+        }
+        const int64_t d_off = ((int64_t)b * N + ctx) * dld;
+        double lseD, HD;
+        oracle_row_stats(a->draft_logits, a->dtype, d_off, V, T, &lseD, &HD, NULL);
+        for (int32_t i = 0; i < V; ++i) q[i] = prob_at(a->draft_logits, a->dtype, d_off, i, T, lseD);
+        const int gate = (HD < tau) ? 1 : 0;
+        if (a->out_gate_margin) a->out_gate_margin[(int64_t)b * N + ctx] = fabs(HD - tau);
+        int32_t kept = -1, first = 1, dead = 0, rejected = 0;
+        double Zprod = 1.0, Csum = 0.0;
+        for (int32_t n = ctx; n < len && kept < 0 && !dead; ++n) {
+            if (par[n] != ctx - 1) continue;
+            const int32_t x = tok[n];
+            int ok;
+            if (first && gate) {
+                ok = 1;
+            } else {
+                uint32_t r[4];
+                hsd_random_block(a->seed, seq, (uint32_t)n, a->level, r);
+                const double u = oracle_u24(r[0]);
+                double r_x = 0.0, q_x = 1.0;
+                if (x >= 0 && x < V) { r_x = pr[x]; q_x = q[x]; }
+                ok = oracle_ratio_accept(u, r_x, q_x);
+                if (a->out_ratio_margin && q_x > 0.0)
+                    a->out_ratio_margin[(int64_t)b * N + n] = fabs(u - r_x / q_x) * Zprod / (Csum > 1.0 ? Csum : 1.0);
+            }
+            first = 0;
+            if (ok) { kept = n; break; }
+            double z = 0.0;                                /* r <- max(0, r - q) / its sum */
+            for (int32_t i = 0; i < V; ++i) { const double d = pr[i] - q[i]; w[i] = d > 0.0 ? d : 0.0; z += w[i]; }
+            if (!(z > 0.0)) { dead = 1; break; }
+            rejected = 1;
+            for (int32_t i = 0; i < V; ++i) pr[i] = w[i] / z;
+            Csum += Zprod;
+            Zprod *= z;
+        }
+        if (kept >= 0) {
+            if (a->out_path) a->out_path[(int64_t)b * N + depth] = kept;
+            ++depth;
+            ctx = kept + 1;
+            continue;
+        }
+        if (dead) {                                        /* no residual mass: the verifier's own distribution */
+            for (int32_t i = 0; i < V; ++i) pr[i] = prob_at(a->target_logits, a->dtype, t_off, i, T, lseP);
+            rejected = 0;
+        }
+        /* the draw needs no normalised weights: the last residual as it was before its division */
+        next = oracle_inverse_cdf(rejected ? w : pr, V, u2, &Zs, &smargin);
+        break;
+    }
+    if (a->out_accept_len) a->out_accept_len[b] = depth;
+    if (a->out_next_token) a->out_next_token[b] = next;
+    if (a->out_sample_margin) a->out_sample_margin[b] = smargin;
+}
+
+/* Returns 0, or -1 on arguments it does not take (a parent that is not an earlier node included). */
+int32_t oracle_verify_tree(const oracle_tree_args* a)
+{
+    if (!a || a->B < 0 || a->N < 1 || a->N > 63 || a->V < 1 || !(a->temperature > 0.f)) return -1;
+    if (!a->node_token || !a->node_parent) return -1;
+    for (int32_t b = 0; b < a->B; ++b) {
+        int32_t len = a->n_nodes ? a->n_nodes[b] : a->N;
+        if (len > a->N) len = a->N;
+        for (int32_t n = 0; n < len; ++n) {
+            const int32_t p = a->node_parent[(int64_t)b * a->N + n];
+            if (p < -1 || p >= n) return -1;
+        }
+    }
+    int nthreads = 1;
+#ifdef _OPENMP
+    nthreads = a->num_threads > 0 ? a->num_threads : omp_get_max_threads();
+#endif
+    (void)nthreads;
+#pragma omp parallel num_threads(nthreads)
+    {
+        double* buf = (double*)malloc((size_t)a->V * 3 * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int32_t b = 0; b < a->B; ++b) tree_one_sequence(a, b, buf, buf + a->V, buf + 2 * (size_t)a->V);
+        free(buf);
+    }
     return 0;
 }
 

@@ -50,6 +50,21 @@ class _Args(C.Structure):
     ]
 
 
+class _TreeArgs(C.Structure):
+    _fields_ = [
+        ("target_logits", C.c_void_p), ("draft_logits", C.c_void_p), ("dtype", C.c_int32),
+        ("target_ld", C.c_int64), ("draft_ld", C.c_int64),
+        ("node_token", C.c_void_p), ("node_parent", C.c_void_p), ("n_nodes", C.c_void_p),
+        ("seed", C.c_uint64), ("level", C.c_uint32), ("seq_base", C.c_int64),
+        ("B", C.c_int32), ("N", C.c_int32), ("V", C.c_int32),
+        ("temperature", C.c_float), ("entropy_threshold", C.c_float),
+        ("out_accept_len", C.c_void_p), ("out_path", C.c_void_p), ("out_next_token", C.c_void_p),
+        ("out_entropy", C.c_void_p), ("out_entropy64", C.c_void_p),
+        ("out_gate_margin", C.c_void_p), ("out_ratio_margin", C.c_void_p), ("out_sample_margin", C.c_void_p),
+        ("num_threads", C.c_int32),
+    ]
+
+
 _lib = None
 
 
@@ -97,6 +112,8 @@ def lib() -> C.CDLL:
         L.oracle_hsd_verify.restype = C.c_int32
         L.oracle_verify_literal.argtypes = [C.POINTER(_Args), C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_verify_literal.restype = C.c_int32
+        L.oracle_verify_tree.argtypes = [C.POINTER(_TreeArgs)]
+        L.oracle_verify_tree.restype = C.c_int32
         L.oracle_max_threads.argtypes = []
         L.oracle_max_threads.restype = C.c_int32
         _lib = L
@@ -392,6 +409,53 @@ def verify_literal(target_logits, draft_logits, draft_tokens, seed, temperature,
     rc = lib().oracle_verify_literal(C.byref(a), _ptr(r.tokens), _ptr(r.calls), _ptr(r.sample_margin))
     if rc != 0:
         raise ValueError("oracle_verify_literal rejected its arguments")
+    return r
+
+
+@dataclass
+class TreeResult:
+    accept_len: np.ndarray       # [B] kept nodes
+    path: np.ndarray             # [B, N] kept nodes from the prefix on, -1 beyond
+    next_token: np.ndarray       # [B]
+    entropy: np.ndarray          # float32 [B, N], -1 for contexts without children
+    entropy64: np.ndarray
+    gate_margin: np.ndarray      # [B, N] per context, NaN where not visited
+    ratio_margin: np.ndarray     # [B, N] per node, NaN where not tested
+    sample_margin: np.ndarray    # [B]
+
+
+def verify_tree(target_logits, draft_logits, node_token, node_parent, seed, temperature, entropy_threshold,
+                n_nodes=None, level=0, seq_base=0, num_threads=0) -> TreeResult:
+    """Verify step over token trees: target [B,N+1,V] and draft [B,N,V] rows by context (0: the prefix,
+    n+1: after node n), node_parent -1 or an earlier node; children are tried in node order."""
+    P, dt = _logits(target_logits)
+    D, dt2 = _logits(draft_logits)
+    assert dt == dt2
+    B, N1, V = P.shape
+    N = N1 - 1
+    assert D.shape == (B, N, V), (D.shape, (B, N, V))
+    tok = np.ascontiguousarray(node_token, dtype=np.int32)
+    par = np.ascontiguousarray(node_parent, dtype=np.int32)
+    assert tok.shape == (B, N) and par.shape == (B, N)
+    nn = None if n_nodes is None else np.ascontiguousarray(n_nodes, dtype=np.int32)
+    r = TreeResult(accept_len=np.zeros(B, np.int32), path=np.zeros((B, N), np.int32), next_token=np.zeros(B, np.int32),
+                   entropy=np.zeros((B, N), np.float32), entropy64=np.zeros((B, N), np.float64),
+                   gate_margin=np.zeros((B, N), np.float64), ratio_margin=np.zeros((B, N), np.float64),
+                   sample_margin=np.zeros(B, np.float64))
+    a = _TreeArgs()
+    a.target_logits, a.draft_logits, a.dtype = _ptr(P), _ptr(D), dt
+    a.target_ld = a.draft_ld = 0
+    a.node_token, a.node_parent, a.n_nodes = _ptr(tok), _ptr(par), _ptr(nn)
+    a.seed, a.level, a.seq_base = int(seed), int(level), int(seq_base)
+    a.B, a.N, a.V = B, N, V
+    a.temperature, a.entropy_threshold = float(temperature), float(entropy_threshold)
+    a.out_accept_len, a.out_path, a.out_next_token = _ptr(r.accept_len), _ptr(r.path), _ptr(r.next_token)
+    a.out_entropy, a.out_entropy64 = _ptr(r.entropy), _ptr(r.entropy64)
+    a.out_gate_margin, a.out_ratio_margin = _ptr(r.gate_margin), _ptr(r.ratio_margin)
+    a.out_sample_margin = _ptr(r.sample_margin)
+    a.num_threads = int(num_threads)
+    if lib().oracle_verify_tree(C.byref(a)) != 0:
+        raise ValueError("oracle_verify_tree rejected its arguments")
     return r
 
 

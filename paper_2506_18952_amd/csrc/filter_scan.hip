@@ -871,7 +871,7 @@ static int scan_segments(int dtype, int32_t V)
 
 // Scratch of the scan + decide pair: 16 KB of candidate list per row, which is why very large batches (beyond
 // 256 MB of lists) go without it and use the per-row kernel alone.
-size_t filter_scan_bytes(int64_t rows, int32_t V)
+size_t filter_scan_bytes(int64_t rows)
 {
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     if (rows <= 0 || (size_t)rows * kScanStore * sizeof(unsigned long long) > ((size_t)256 << 20)) return 0;

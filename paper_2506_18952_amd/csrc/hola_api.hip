@@ -77,14 +77,15 @@ struct StageTimer {
         std::lock_guard<std::mutex> lk(g_mu);
         if (!g_prof_free.empty()) { a = g_prof_free.back().first; b = g_prof_free.back().second; g_prof_free.pop_back(); }
         else if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
-        hipEventRecord(a, s);
+        if (hipEventRecord(a, s) != hipSuccess) { g_prof_free.emplace_back(a, b); on = false; }
     }
     ~StageTimer()
     {
         if (!on) return;
-        hipEventRecord(b, s);
+        const bool timed = hipEventRecord(b, s) == hipSuccess;
         std::lock_guard<std::mutex> lk(g_mu);
-        g_prof_live.push_back(ProfEvent{stage, a, b});
+        if (timed) g_prof_live.push_back(ProfEvent{stage, a, b});
+        else g_prof_free.emplace_back(a, b);
     }
 };
 
@@ -130,7 +131,7 @@ static Workspace carve(void* base, int32_t B, int32_t gamma, int32_t V)
     w.seq = (SeqInfo*)(p + off);      off = align_up(off + (size_t)B * sizeof(SeqInfo));
     w.tiles = (double*)(p + off);     off = align_up(off + (size_t)B * ntiles * sizeof(double));
     w.filters = (RowFilter*)(p + off); off = align_up(off + rows * sizeof(RowFilter));
-    const size_t scan_bytes = filter_scan_bytes((int64_t)rows, V);
+    const size_t scan_bytes = filter_scan_bytes((int64_t)rows);
     w.filter_scan = scan_bytes ? p + off : nullptr; off = align_up(off + scan_bytes);
     w.bytes = off;
     return w;
@@ -702,13 +703,13 @@ void hola_shutdown(void)
     bool have_dev = hipGetDevice(&cur) == hipSuccess;
     for (int d = 0; d < 64; ++d) {
         if (!g_ws[d].ptr) continue;
-        if (have_dev) hipSetDevice(d);
-        hipFree(g_ws[d].ptr);
+        if (have_dev) (void)hipSetDevice(d);
+        (void)hipFree(g_ws[d].ptr);
         g_ws[d].ptr = nullptr; g_ws[d].bytes = 0;
     }
-    if (have_dev) hipSetDevice(cur);
-    for (auto& ev : g_prof_live) { hipEventDestroy(ev.a); hipEventDestroy(ev.b); }
-    for (auto& ev : g_prof_free) { hipEventDestroy(ev.first); hipEventDestroy(ev.second); }
+    if (have_dev) (void)hipSetDevice(cur);
+    for (auto& ev : g_prof_live) { (void)hipEventDestroy(ev.a); (void)hipEventDestroy(ev.b); }
+    for (auto& ev : g_prof_free) { (void)hipEventDestroy(ev.first); (void)hipEventDestroy(ev.second); }
     g_prof_live.clear();
     g_prof_free.clear();
 }

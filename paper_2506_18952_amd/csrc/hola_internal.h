@@ -143,7 +143,7 @@ hipError_t launch_filter(const void* target, const void* draft, int dtype, int64
                          hipStream_t s);
 // The usual course of the filter: a split-row scan that lists candidates, then a per-row decide step; rows it
 // cannot settle come back flagged in *flags_out ([B (2 gamma + 1)], 1 = still to do).
-size_t filter_scan_bytes(int64_t rows, int32_t V);
+size_t filter_scan_bytes(int64_t rows);
 bool filter_scan_applies(int dtype, int32_t V, int32_t top_k);
 hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                               const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,

@@ -223,3 +223,72 @@ def small_case(B: int, gamma: int, V: int, dtype: str = "f32", temperature: floa
     return _make(case_id, f"small_B{B}_g{gamma}_V{V}_{dtype}", B, gamma, V, dtype, temperature, [tau_frac],
                  seed, sigma=sigma, zipf_slope=zipf_slope, draft_sigma=draft_sigma, peak_prob=peak_prob,
                  greedy_below=greedy_below)
+
+
+# --------------------------------------------------------------------------- token trees
+@dataclass
+class TreeWorkload:
+    name: str
+    B: int
+    N: int                             # nodes per sequence
+    V: int
+    dtype: str
+    temperature: float
+    tau: float
+    seed: int
+    widths: List[int]                  # nodes per depth
+    target: np.ndarray                 # [B, N+1, V] row c: context c (0 = the prefix, n+1 = after node n)
+    draft: np.ndarray                  # [B, N, V]
+    node_token: np.ndarray             # [B, N] int32
+    node_parent: np.ndarray            # [B, N] int32, -1 = child of the prefix
+
+    @property
+    def logit_bytes(self) -> int:
+        return self.target.nbytes + self.draft.nbytes
+
+
+def tree_parents(widths: Sequence[int]) -> np.ndarray:
+    """Breadth-first numbering: the i-th node of a depth hangs under node i mod (width of the depth above)."""
+    par: List[int] = []
+    first_prev, w_prev = -1, 1
+    for d, w in enumerate(widths):
+        first = len(par)
+        for i in range(w):
+            par.append(-1 if d == 0 else first_prev + (i % w_prev))
+        first_prev, w_prev = first, w
+    return np.asarray(par, dtype=np.int32)
+
+
+def tree_case(B: int, widths: Sequence[int], V: int, dtype: str = "f32", temperature: float = 1.0,
+              tau_frac: float = 0.5, seed: int = 9, sigma: float = 2.0, zipf_slope: Optional[float] = 1.1,
+              draft_sigma: float = 0.75, peak_prob: float = 0.2, peak_boost: float = 12.0,
+              case_id: int = 700) -> TreeWorkload:
+    """Token trees with the recipe of the chains: every context has its own target row and a draft row that is
+    the target row plus noise; the children of a context are independent draws from its draft row."""
+    par = tree_parents(widths)
+    N = len(par)
+    np_dt = np.uint16 if dtype == "bf16" else np.float32
+    target = np.empty((B, N + 1, V), dtype=np_dt)
+    draft = np.empty((B, N, V), dtype=np_dt)
+    tokens = np.empty((B, N), dtype=np.int32)
+    table = None if zipf_slope is None else _zipf_table(V, zipf_slope)
+
+    def one(b: int) -> None:
+        rng = _rng(case_id, b)
+        P = _zipf_rows(rng, N + 1, V, sigma, zipf_slope or 0.0, table)
+        if peak_prob > 0.0:
+            hit = rng.random(N + 1) < peak_prob
+            where = rng.integers(0, V, size=N + 1)
+            for j in range(N + 1):
+                if hit[j]:
+                    P[j, where[j]] += np.float32(peak_boost)
+        D = P[:N] + np.float32(draft_sigma) * rng.standard_normal(size=(N, V), dtype=np.float32)
+        _store(target, b, P, dtype)
+        Dq = _store(draft, b, D, dtype)
+        tokens[b] = _gumbel_argmax(rng, Dq[par + 1], temperature)
+
+    _parallel(one, list(range(B)))
+    return TreeWorkload(name=f"tree_B{B}_w{'-'.join(str(w) for w in widths)}_V{V}_{dtype}", B=B, N=N, V=V, dtype=dtype,
+                        temperature=temperature, tau=float(np.float32(tau_frac * math.log(V))), seed=seed,
+                        widths=list(widths), target=target, draft=draft, node_token=tokens,
+                        node_parent=np.tile(par, (B, 1)))
