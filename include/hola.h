@@ -212,6 +212,42 @@ typedef struct {
 } hola_hsd_args;
 hola_status hola_hsd_verify_ex(const hola_hsd_args* args /* host */);
 
+/* Token trees: several drafted tokens per position (the paper drafts one; Section 3.1's gate and
+ * Equation (1)'s two branches carry over as stated below).  A sequence has N nodes; node n holds a token and
+ * a parent, -1 (the prefix) or an earlier node.  Context c is the prefix (c = 0) or the prefix followed by the
+ * path to node c - 1; target row c and draft row c are the two models' logits after context c, laid out as
+ * for hola_verify_ex with gamma = N (draft rows of contexts without children are never read).  From the
+ * prefix on, the children of the current context are tried in node order: with H(q_c) < tau (strict) the
+ * first child is kept without a test; otherwise child x is kept iff u q_c(x) < r(x), r = p_c at first and
+ * after every rejection r <- max(0, r - q_c) renormalised (the rule for candidates drawn independently from
+ * q_c, under which the kept token follows p_c whatever their number).  A kept child becomes the context; when
+ * every child is rejected the next token is drawn from r, and at a context without children from p_c.
+ * A chain (parent[n] = n - 1) gives exactly hola_verify_ex's results, uniforms included: node n's test takes
+ * word 0 of Philox block (n, seq, level), the draw at context c word 1 of block (c, seq, level).
+ * A node whose parent is neither -1 nor an earlier node is ignored, like the nodes beyond n_nodes[b].
+ * Stochastic rows with one temperature > 0 only (HOLA_ERR_UNSUPPORTED otherwise); N <= HOLA_MAX_GAMMA.
+ * All pointers but the struct itself are device memory; outputs are written on `stream`; the caller owns
+ * every buffer; workspace: 256-byte aligned, >= hola_tree_workspace_bytes(B, N, V). */
+typedef struct {
+    const void* target_logits;        /* [B, N+1, V] */
+    const void* draft_logits;         /* [B, N, V] */
+    int32_t dtype;                    /* HOLA_DTYPE_* */
+    int64_t target_ld, draft_ld;      /* row strides in elements, 0 = V */
+    const int32_t* node_token;        /* [B, N] */
+    const int32_t* node_parent;       /* [B, N] */
+    const int32_t* n_nodes;           /* [B] in [0, N], or NULL = N */
+    uint64_t seed; uint32_t level; int64_t seq_base;
+    int32_t B, N, V;
+    float temperature, entropy_threshold;
+    int32_t* out_accept_len;          /* [B] number of kept nodes */
+    int32_t* out_path;                /* [B, N] kept nodes from the prefix on, -1 beyond; or NULL */
+    int32_t* out_next_token;          /* [B]; -1 if the stop row has no finite logit */
+    float* out_entropy;               /* [B, N] H(q_c) in nats for contexts with children, -1 elsewhere; or NULL */
+    void* workspace; size_t workspace_bytes; hola_stream_t stream;
+} hola_tree_args;
+hola_status hola_verify_tree(const hola_tree_args* args /* host */);
+size_t hola_tree_workspace_bytes(int32_t B, int32_t N, int32_t V);   /* 0 on invalid shape */
+
 /* Row statistics alone (steps 1-2): (lse, H) in nats of softmax(logits[r, :] / T) for R rows,
  * written to stats_out as device [R, 2] doubles.  Greedy convention does not apply (T > 0).
  * workspace as for hola_verify_ex with B = R, gamma = 1. */

@@ -22,7 +22,8 @@ STAGE_NAMES = ("row_stats", "accept", "tile_sums", "select", "glue", "fused", "t
 
 EXPORTS = (
     "hola_verify_f32", "hola_verify_bf16", "hola_verify_ex", "hola_verify_literal_ex", "hola_workspace_bytes",
-    "hola_hsd_verify", "hola_hsd_verify_ex", "hola_hsd_workspace_bytes", "hola_row_stats", "hola_tile_stats",
+    "hola_hsd_verify", "hola_hsd_verify_ex", "hola_hsd_workspace_bytes", "hola_verify_tree",
+    "hola_tree_workspace_bytes", "hola_row_stats", "hola_tile_stats",
     "hola_tile_stats_workspace_bytes", "hola_merge_tile_stats", "hola_set_tuning",
     "hola_profile_enable", "hola_profile_collect", "hola_copy_bytes", "hola_shutdown", "hola_status_string",
     "hola_last_hip_error", "hola_version",
@@ -72,6 +73,20 @@ class HsdArgs(C.Structure):
     ]
 
 
+class TreeArgs(C.Structure):
+    _fields_ = [
+        ("target_logits", C.c_void_p), ("draft_logits", C.c_void_p), ("dtype", C.c_int32),
+        ("target_ld", C.c_int64), ("draft_ld", C.c_int64),
+        ("node_token", C.c_void_p), ("node_parent", C.c_void_p), ("n_nodes", C.c_void_p),
+        ("seed", C.c_uint64), ("level", C.c_uint32), ("seq_base", C.c_int64),
+        ("B", C.c_int32), ("N", C.c_int32), ("V", C.c_int32),
+        ("temperature", C.c_float), ("entropy_threshold", C.c_float),
+        ("out_accept_len", C.c_void_p), ("out_path", C.c_void_p), ("out_next_token", C.c_void_p),
+        ("out_entropy", C.c_void_p),
+        ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p),
+    ]
+
+
 class Tuning(C.Structure):
     _fields_ = [("stats_split", C.c_int32), ("stats_unroll", C.c_int32), ("path", C.c_int32),
                 ("fused_waves", C.c_int32), ("filter_path", C.c_int32)]
@@ -105,6 +120,10 @@ def lib() -> C.CDLL:
         L.hola_hsd_verify_ex.restype = C.c_int32
         L.hola_hsd_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
         L.hola_hsd_workspace_bytes.restype = C.c_size_t
+        L.hola_verify_tree.argtypes = [C.POINTER(TreeArgs)]
+        L.hola_verify_tree.restype = C.c_int32
+        L.hola_tree_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+        L.hola_tree_workspace_bytes.restype = C.c_size_t
         L.hola_row_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_float,
                                      C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.hola_tile_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_float,
@@ -278,6 +297,27 @@ def hola_hsd_verify_ex(models: Sequence, draft_tokens, seed, B, gamma, V, temper
     a.stream = _stream_handle(stream)
     a.top_k, a.top_p = int(top_k), float(top_p)
     _check(lib().hola_hsd_verify_ex(C.byref(a)), "hola_hsd_verify_ex")
+
+
+def hola_tree_workspace_bytes(B: int, N: int, V: int) -> int:
+    return int(lib().hola_tree_workspace_bytes(B, N, V))
+
+
+def hola_verify_tree(target_logits, draft_logits, node_token, node_parent, seed, B, N, V, temperature,
+                     entropy_threshold, out_accept_len, out_next_token, workspace, out_path=None, out_entropy=None,
+                     n_nodes=None, level=0, seq_base=0, target_ld=0, draft_ld=0, stream=None) -> None:
+    a = TreeArgs()
+    a.target_logits, a.draft_logits, a.dtype = _ptr(target_logits), _ptr(draft_logits), _logit_dtype(target_logits)
+    a.target_ld, a.draft_ld = int(target_ld), int(draft_ld)
+    a.node_token, a.node_parent, a.n_nodes = _ptr(node_token), _ptr(node_parent), _ptr(n_nodes)
+    a.seed, a.level, a.seq_base = int(seed), int(level), int(seq_base)
+    a.B, a.N, a.V = int(B), int(N), int(V)
+    a.temperature, a.entropy_threshold = float(temperature), float(entropy_threshold)
+    a.out_accept_len, a.out_path, a.out_next_token = _ptr(out_accept_len), _ptr(out_path), _ptr(out_next_token)
+    a.out_entropy = _ptr(out_entropy)
+    a.workspace, a.workspace_bytes = _ptr(workspace), workspace.numel() * workspace.element_size()
+    a.stream = _stream_handle(stream)
+    _check(lib().hola_verify_tree(C.byref(a)), "hola_verify_tree")
 
 
 def hola_row_stats(logits, R, V, temperature, stats_out, workspace, ld=0, stream=None) -> None:

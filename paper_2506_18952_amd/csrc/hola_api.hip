@@ -554,6 +554,67 @@ hola_status hola_hsd_verify_ex(const hola_hsd_args* args)
     return HOLA_OK;
 }
 
+size_t hola_tree_workspace_bytes(int32_t B, int32_t N, int32_t V)
+{
+    if (!shape_ok(B, N, V)) return 0;
+    return align_up(carve(nullptr, B, N, V).bytes) + align_up((size_t)B * N) + 256;
+}
+
+hola_status hola_verify_tree(const hola_tree_args* args)
+{
+    if (!args) return HOLA_ERR_INVALID_ARG;
+    const hola_tree_args& a = *args;
+    if (!shape_ok(a.B, a.N, a.V)) return HOLA_ERR_INVALID_ARG;
+    if (a.dtype != HOLA_DTYPE_F32 && a.dtype != HOLA_DTYPE_BF16) return HOLA_ERR_UNSUPPORTED;
+    if (a.B == 0) return HOLA_OK;
+    if (!a.target_logits || !a.draft_logits || !a.node_token || !a.node_parent || !a.out_accept_len || !a.out_next_token)
+        return HOLA_ERR_INVALID_ARG;
+    const size_t es = a.dtype == HOLA_DTYPE_BF16 ? 2 : 4;
+    if (((uintptr_t)a.target_logits % es) || ((uintptr_t)a.draft_logits % es)) return HOLA_ERR_INVALID_ARG;
+    if ((a.target_ld && a.target_ld < a.V) || (a.draft_ld && a.draft_ld < a.V)) return HOLA_ERR_INVALID_ARG;
+    if (std::isnan(a.temperature) || std::isinf(a.temperature) || a.temperature < 0.f) return HOLA_ERR_INVALID_ARG;
+    if (std::isnan(a.entropy_threshold)) return HOLA_ERR_INVALID_ARG;
+    if (!(a.temperature > 0.f) || !tree_supported(a.N, a.V, a.dtype)) return HOLA_ERR_UNSUPPORTED;
+    if (!a.workspace || ((uintptr_t)a.workspace & 255)) return HOLA_ERR_WORKSPACE;
+    if (a.workspace_bytes < hola_tree_workspace_bytes(a.B, a.N, a.V)) return HOLA_ERR_WORKSPACE;
+
+    hipStream_t s = (hipStream_t)a.stream;
+    const Workspace w = carve(a.workspace, a.B, a.N, a.V);
+    uint8_t* used = (uint8_t*)a.workspace + align_up(w.bytes);
+    const int64_t tld = a.target_ld ? a.target_ld : a.V, dld = a.draft_ld ? a.draft_ld : a.V;
+    Tuning tune;
+    { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
+    const int64_t rows = (int64_t)a.B * (2 * (int64_t)a.N + 1);
+    const int nsplit = choose_split(rows, a.V, a.dtype, tune);
+
+    hipError_t e;
+    { StageTimer t(4, s); e = launch_tree_prepare(a.node_parent, a.n_nodes, a.B, a.N, used, s); }
+    if (e != hipSuccess) return hip_fail(e, "tree prepare launch");
+
+    RowStatsParams rs{};
+    rs.target = a.target_logits; rs.draft = a.draft_logits; rs.target_ld = tld; rs.draft_ld = dld;
+    rs.draft_len = a.n_nodes; rs.temperature = a.temperature;
+    rs.B = a.B; rs.gamma = a.N; rs.V = a.V; rs.nsplit = nsplit;
+    rs.lse_only_targets = 1;                                    // only the drafts' entropy gates
+    rs.draft_used = used;
+    rs.partials = w.partials;
+    { StageTimer t(0, s); e = launch_row_stats(rs, a.dtype, tune, s); }
+    if (e != hipSuccess) return hip_fail(e, "row statistics launch");
+
+    TreeParams tp{};
+    tp.target = a.target_logits; tp.draft = a.draft_logits; tp.dtype = a.dtype; tp.target_ld = tld; tp.draft_ld = dld;
+    tp.tokens = a.node_token; tp.parent = a.node_parent; tp.n_nodes = a.n_nodes; tp.used = used;
+    tp.seed = a.seed; tp.level = a.level; tp.seq_base = a.seq_base;
+    tp.B = a.B; tp.N = a.N; tp.V = a.V; tp.ntiles = sampler_tiles(a.V, a.dtype);
+    tp.temperature = a.temperature; tp.tau = a.entropy_threshold;
+    tp.out_accept_len = a.out_accept_len; tp.out_path = a.out_path; tp.out_next_token = a.out_next_token;
+    tp.out_entropy = a.out_entropy;
+    const int waves = tune.fused_waves ? tune.fused_waves : (a.B <= device_cu_count() ? 16 : 8);
+    { StageTimer t(6, s); e = launch_tree_tail(tp, w.partials, nsplit * kWaves, waves, s); }
+    if (e != hipSuccess) return hip_fail(e, "tree tail launch");
+    return HOLA_OK;
+}
+
 hola_status hola_row_stats(const void* logits, int32_t dtype, int64_t ld, int32_t R, int32_t V, float temperature,
                            double* stats_out, void* workspace, size_t workspace_bytes, hola_stream_t stream)
 {

@@ -43,6 +43,7 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(RowStatsParams p)
     int len = p.draft_len ? p.draft_len[b] : g;
     len = len < 0 ? 0 : (len > g ? g : len);
     if (is_draft ? (j >= len) : (p.literal ? (j >= len) : (j > len))) return;   // row not needed (uniform exit)
+    if (is_draft && p.draft_used && !p.draft_used[(int64_t)b * g + j]) return;  // a tree context without children
 
     const float Tb = p.row_temperature ? p.row_temperature[b] : p.temperature;
     const bool greedy = !(Tb > 0.f);

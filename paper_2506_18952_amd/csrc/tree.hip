@@ -1,0 +1,244 @@
+// Verify step over token trees: several drafted tokens per position, each with the rows of its own context.
+//
+// Rows are laid out as in the one-token step with gamma = N nodes: draft row c and target row c belong to context c
+// (0: the prefix, n + 1: the prefix followed by the path to node n), so the split-row statistics kernel serves
+// unchanged; only draft rows of contexts without children are masked out of it (tree_prepare_kernel).
+//
+// tree_tail_kernel, one workgroup per sequence: merges the row partials, gathers the two logits of every node's
+// token in one go, then walks from the prefix.  The children of a context are tried in node order by the recursive
+// rejection rule for candidates drawn independently from the same draft distribution: after i rejections the
+// running distribution is max(0, p - C q) / Z with Z its sum and C the sum of the earlier Z's (C = 0, Z = 1 at
+// first, which is the acceptance test u q(x) < p(x) of Equation (1)'s verifier branch); the strict gate H(q) < tau
+// (Algorithm 1, Step 1) keeps the first child without a test.  Every rejection but the last costs one sweep of
+// the context's row pair for the next Z; after the last the next token is drawn from max(0, p - C q) by the
+// sampler of the one-token step, whose weights take C through the factor it already applies to q.
+// The walk is wavefront 0's; the sweeps are the whole workgroup's, handed over through shared memory.
+// HBM-bound like the tail of the one-token step: no atomics, no spin waits, every loop bounded by the node count.
+#include "accept_device.h"
+#include "sampler_device.h"
+
+namespace hola {
+
+constexpr int kTreeMaxTiles = 2048;
+
+// used[b, c] = 1 iff context c < N of sequence b has a child among its first len nodes.  A node whose parent is
+// not -1 or an earlier node is no one's child.
+__global__ __launch_bounds__(64) void tree_prepare_kernel(const int32_t* __restrict__ parent, const int32_t* __restrict__ n_nodes,
+                                                          int32_t N, uint8_t* __restrict__ used)
+{
+    const int b = blockIdx.x, n = threadIdx.x;
+    int len = n_nodes ? n_nodes[b] : N;
+    len = len < 0 ? 0 : (len > N ? N : len);
+    int ctx = -1;
+    if (n < len) {
+        const int32_t pr = parent[(int64_t)b * N + n];
+        if (pr >= -1 && pr < n) ctx = pr + 1;
+    }
+    __shared__ int s_ctx[64];
+    s_ctx[n] = ctx;
+    __syncthreads();
+    if (n < N) {
+        int any = 0;
+        for (int m = n; m < len; ++m) any |= (s_ctx[m] == n) ? 1 : 0;   // children come after their parent
+        used[(int64_t)b * N + n] = (uint8_t)any;
+    }
+}
+
+struct TreeShared {
+    RowStat stat[2 * HOLA_MAX_GAMMA + 1];      // draft contexts 0..N-1, target contexts N..2N
+    double tiles[kTreeMaxTiles];
+    double px[64], qx[64], u[64];              // per node: the two probabilities of its token, its test uniform
+    int32_t path[64];                          // kept nodes, from the prefix on
+    // the row operation wavefront 0 asks of the workgroup
+    int32_t op_ctx, op_bonus, op_sample, done;
+    double op_C;
+    int32_t tok;
+};
+
+// Sum of the tile weights, in the order the selecting wavefront adds them.
+__device__ __forceinline__ double tiles_total(const double* tiles, int ntiles, int lane)
+{
+    const int per = (ntiles + 63) / 64;
+    double mine = 0.0;
+    for (int i = 0; i < per; ++i) {
+        const int t = lane * per + i;
+        if (t < ntiles) mine += read_tile<true>(tiles + t);
+    }
+    const double incl = wave_inclusive_scan(mine, lane);
+    return __shfl(incl, 63, 64);
+}
+
+template <bool BF16, int NW>
+__global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const Partial* __restrict__ partials, int nparts)
+{
+    __shared__ TreeShared sh;
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int N = p.N;
+    int len = p.n_nodes ? p.n_nodes[b] : N;
+    len = len < 0 ? 0 : (len > N ? N : len);
+    const float Tb = p.temperature;
+    const uint8_t* used = p.used + (int64_t)b * N;
+
+    // ---- row statistics from the split-row partials: `width` lanes per row, 64 / width rows per wavefront
+    int width = 4;
+    while (width < nparts) width <<= 1;
+    const int per_wave = 64 / width, seg = lane / width, sl = lane % width;
+    for (int r0 = wave * per_wave; r0 < 2 * N + 1; r0 += NW * per_wave) {
+        const int r = r0 + seg;
+        const bool is_draft = r < N;
+        const int c = is_draft ? r : r - N;
+        const bool need = r < 2 * N + 1 && (is_draft ? (c < len && used[c]) : (c <= len));
+        const int64_t slot = is_draft ? (int64_t)b * N + c : (int64_t)p.B * N + (int64_t)b * (N + 1) + c;
+        const RowStat s = merge_partials_seg(need ? partials + slot * nparts : nullptr, nparts, sl, width);
+        if (need && sl == 0) sh.stat[r] = s;
+    }
+    __syncthreads();
+
+    // ---- per node (lane n of wavefront 0): context, probabilities of its token, test uniform
+    const uint64_t seq = (uint64_t)(p.seq_base + b);
+    int my_ctx = -1;
+    if (wave == 0) {
+        const int n = lane;
+        double p_x = 0.0, q_x = 1.0, un = 0.0;
+        if (n < len) {
+            const int32_t pr = p.parent[(int64_t)b * N + n];
+            if (pr >= -1 && pr < n) my_ctx = pr + 1;
+        }
+        if (my_ctx >= 0) {
+            const int32_t x = p.tokens[(int64_t)b * N + n];
+            if (x >= 0 && x < p.V) {
+                const double invT = 1.0 / (double)Tb;
+                const float xp = load_logit<BF16>(p.target, ((int64_t)b * (N + 1) + my_ctx) * p.target_ld + x);
+                const float xq = load_logit<BF16>(p.draft, ((int64_t)b * N + my_ctx) * p.draft_ld + x);
+                p_x = exp((double)xp * invT - sh.stat[N + my_ctx].lse);
+                q_x = exp((double)xq * invT - sh.stat[my_ctx].lse);
+            }
+            const Philox4 r = philox4x32_10((uint32_t)n, (uint32_t)seq, (uint32_t)(seq >> 32), p.level,
+                                            (uint32_t)p.seed, (uint32_t)(p.seed >> 32));
+            un = (double)u24(r.x);
+        }
+        sh.px[n] = p_x; sh.qx[n] = q_x; sh.u[n] = un;
+        if (p.out_entropy && n < N) p.out_entropy[(int64_t)b * N + n] = (n < len && used[n]) ? (float)sh.stat[n].H : -1.0f;
+        if (lane == 0) sh.done = 0;
+    }
+    __builtin_amdgcn_wave_barrier();
+
+    // ---- the walk (wavefront 0, every lane the same values) and the row sweeps it asks for (all wavefronts)
+    int ctx = 0, depth = 0;
+    bool first = true, dead = false;
+    double C = 0.0, Z = 1.0;
+    unsigned long long kids = 0, all_kids = 0;
+    if (wave == 0) { all_kids = __ballot(my_ctx == 0); kids = all_kids; }
+    const double tau = (double)p.tau;
+    for (int it = 0; it < 2 * 64 + 4; ++it) {                   // every round ends the walk or uses up a child
+        if (wave == 0) {
+            int sample = 1, bonus = 1;
+            for (;;) {
+                if (dead || all_kids == 0) { bonus = 1; break; } // nothing drafted here (or a residual without mass)
+                if (kids == 0) { bonus = 0; break; }             // every child rejected
+                const int n = __ffsll((long long)kids) - 1;
+                kids &= kids - 1;
+                const double q_x = sh.qx[n], p_x = sh.px[n], un = sh.u[n];
+                bool ok;
+                if (first) ok = (sh.stat[ctx].H < tau) || (un * q_x < p_x);
+                else ok = (un * q_x * Z < fmax(0.0, p_x - C * q_x));
+                first = false;
+                if (ok) {
+                    if (lane == 0) sh.path[depth] = n;
+                    ++depth;
+                    ctx = n + 1;
+                    all_kids = __ballot(my_ctx == ctx);
+                    kids = all_kids;
+                    C = 0.0; Z = 1.0; first = true;
+                    continue;
+                }
+                C += Z;
+                if (kids == 0) { bonus = 0; break; }
+                sample = 0; bonus = 0;                           // more children to try: the next Z
+                break;
+            }
+            if (lane == 0) { sh.op_ctx = ctx; sh.op_bonus = bonus; sh.op_sample = sample; sh.op_C = C; }
+        }
+        __syncthreads();
+        const int o_ctx = sh.op_ctx, o_bonus = sh.op_bonus, o_sample = sh.op_sample;
+        const double o_C = sh.op_C;
+        SeqInfo si;
+        si.row = o_ctx;
+        si.lseP = sh.stat[N + o_ctx].lse;
+        si.lseD = o_bonus ? 0.0 : sh.stat[o_ctx].lse;
+        si.mode = o_bonus ? 1 : 0;
+        si.u = 0.f; si.greedy_tok = -1;
+        RowPair rp;
+        make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, N, p.V, Tb, b, si, o_bonus);
+        if (!rp.bonus && o_C != 1.0) {                           // weights max(0, p - C q): C joins the factor on q
+            const double kappa = ((double)rp.k_hi + (double)rp.k_lo) * o_C;
+            rp.k_hi = (float)kappa;
+            rp.k_lo = (float)(kappa - (double)rp.k_hi);
+        }
+        for (int t = wave; t < p.ntiles; t += 2 * NW) {
+            double w0 = 0.0, w1 = 0.0;
+            if (rp.ok) tile_weight2<BF16>(rp, t, t + NW, lane, w0, w1);
+            if (lane == 0) {
+                sh.tiles[t] = w0;
+                if (t + NW < p.ntiles) sh.tiles[t + NW] = w1;
+            }
+        }
+        __syncthreads();
+        if (wave == 0) {
+            if (!o_sample) {
+                Z = rp.ok ? tiles_total(sh.tiles, p.ntiles, lane) : 0.0;
+                if (!(Z > 0.0) || !(Z - Z == 0.0) || rp.bonus) dead = true;   // no residual mass: draw from p itself
+            } else {
+                const Philox4 r = philox4x32_10((uint32_t)o_ctx, (uint32_t)seq, (uint32_t)(seq >> 32), p.level,
+                                                (uint32_t)p.seed, (uint32_t)(p.seed >> 32));
+                const int32_t tk = rp.ok ? select_token<BF16, true>(rp, sh.tiles, p.ntiles, (double)u24(r.y), lane) : -1;
+                if (tk == -2 && !dead) {
+                    dead = true;                                  // residual without mass: once more, as a draw from p
+                } else if (lane == 0) {
+                    sh.tok = tk < 0 ? -1 : tk;
+                    sh.done = 1;
+                }
+            }
+        }
+        __syncthreads();
+        if (sh.done) break;
+    }
+    if (wave == 0) {                                            // depth is wavefront 0's
+        if (lane == 0) {
+            p.out_next_token[b] = sh.done ? sh.tok : -1;
+            p.out_accept_len[b] = depth;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (p.out_path && lane < N) p.out_path[(int64_t)b * N + lane] = lane < depth ? sh.path[lane] : -1;
+    }
+}
+
+bool tree_supported(int32_t N, int32_t V, int dtype)
+{
+    return N >= 1 && N <= HOLA_MAX_GAMMA && sampler_tiles(V, dtype) <= kTreeMaxTiles;
+}
+
+hipError_t launch_tree_prepare(const int32_t* parent, const int32_t* n_nodes, int32_t B, int32_t N, uint8_t* used, hipStream_t s)
+{
+    if (B <= 0) return hipSuccess;
+    hipLaunchKernelGGL(tree_prepare_kernel, dim3((unsigned)B), dim3(64), 0, s, parent, n_nodes, N, used);
+    return hipGetLastError();
+}
+
+hipError_t launch_tree_tail(const TreeParams& p, const Partial* partials, int nparts, int waves, hipStream_t s)
+{
+    if (p.B <= 0) return hipSuccess;
+    if (nparts > 64 || p.ntiles > kTreeMaxTiles) return hipErrorInvalidValue;
+    dim3 grid((unsigned)p.B);
+    if (p.dtype == HOLA_DTYPE_BF16) {
+        if (waves <= 8) hipLaunchKernelGGL((tree_tail_kernel<true, 8>), grid, dim3(512), 0, s, p, partials, nparts);
+        else hipLaunchKernelGGL((tree_tail_kernel<true, 16>), grid, dim3(1024), 0, s, p, partials, nparts);
+    } else {
+        if (waves <= 8) hipLaunchKernelGGL((tree_tail_kernel<false, 8>), grid, dim3(512), 0, s, p, partials, nparts);
+        else hipLaunchKernelGGL((tree_tail_kernel<false, 16>), grid, dim3(1024), 0, s, p, partials, nparts);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace hola

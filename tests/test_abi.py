@@ -174,7 +174,7 @@ def test_header_is_plain_c_and_matches_the_binding(tmp_path):
     if gcc is None:
         pytest.skip("no gcc")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    pairs = [("hola_verify_args", hb.VerifyArgs), ("hola_model_logits", hb.ModelLogits), ("hola_hsd_args", hb.HsdArgs),
+    pairs = [("hola_verify_args", hb.VerifyArgs), ("hola_model_logits", hb.ModelLogits), ("hola_hsd_args", hb.HsdArgs), ("hola_tree_args", hb.TreeArgs),
              ("hola_tuning", hb.Tuning)]
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "hola.h"', 'int main(void) {']
     for cname, cls in pairs:

@@ -1,0 +1,195 @@
+"""GPU parity of the token-tree verify step (hola_verify_tree) against the oracle's walk.
+
+Bar: kept path, accept length and next token bit-exact unless the oracle lists a deciding comparison of its own walk
+as near-threshold (a gate |H - tau|, a test in the unnormalised units max(0, p - C q), or the sampling uniform within
+1e-6 of an interval end); entropies as for the one-token step.  A chain must reproduce hola_verify_ex exactly."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import hola_oracle as orc
+from paper_2506_18952_amd import binding as hb, workloads as wl
+from parity import DEV, ENTROPY_ABS_FLOOR, MARGIN, run_gpu_level, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def run_tree(target, draft, tok, par, seed, T, tau, n_nodes=None, level=0, seq_base=0, dev=None, want_path=True):
+    P, D = dev if dev is not None else (to_dev(target), to_dev(draft))
+    B, N1, V = P.shape
+    N = N1 - 1
+    acc = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    nxt = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    path = torch.full((B, N), -7, dtype=torch.int32, device=DEV) if want_path else None
+    ent = torch.full((B, N), -7.0, dtype=torch.float32, device=DEV)
+    ws = hb.alloc_workspace(hb.hola_tree_workspace_bytes(B, N, V), DEV)
+    nn = None if n_nodes is None else to_dev(np.ascontiguousarray(n_nodes, np.int32))
+    hb.hola_verify_tree(P, D, to_dev(np.ascontiguousarray(tok, np.int32)), to_dev(np.ascontiguousarray(par, np.int32)),
+                        seed, B, N, V, T, tau, acc, nxt, ws, out_path=path, out_entropy=ent, n_nodes=nn, level=level,
+                        seq_base=seq_base)
+    torch.cuda.synchronize()
+    return acc.cpu().numpy(), (path.cpu().numpy() if want_path else None), nxt.cpu().numpy(), ent.cpu().numpy()
+
+
+def compare_tree(target, draft, tok, par, seed, T, tau, got, n_nodes=None, level=0, seq_base=0, max_listed=None):
+    acc, path, nxt, ent = got
+    ref = orc.verify_tree(target, draft, tok, par, seed, T, tau, n_nodes=n_nodes, level=level, seq_base=seq_base)
+    B, N = tok.shape
+    rtol = 1e-5 if np.asarray(target).dtype == np.float32 else 2e-3
+    listed, max_dh = 0, 0.0
+    for b in range(B):
+        for c in range(N):
+            if ref.entropy[b, c] < 0:
+                assert ent[b, c] == -1.0, (b, c, ent[b, c])
+                continue
+            h, hg = ref.entropy64[b, c], float(ent[b, c])
+            err = abs(hg - h)
+            max_dh = max(max_dh, err)
+            assert err <= max(rtol * abs(h), ENTROPY_ABS_FLOOR) and err < 1e-6, (b, c, hg, h)
+        m = np.r_[ref.gate_margin[b], ref.ratio_margin[b], ref.sample_margin[b]]
+        if np.nanmin(np.r_[m, np.inf]) < MARGIN:
+            listed += 1
+            a = acc[b]
+            assert 0 <= a <= N and np.all(path[b, a:] == -1) and np.all(path[b, :a] >= 0)
+            continue
+        assert acc[b] == ref.accept_len[b], (b, acc[b], ref.accept_len[b], path[b], ref.path[b])
+        np.testing.assert_array_equal(path[b], ref.path[b])
+        assert nxt[b] == ref.next_token[b], (b, nxt[b], ref.next_token[b], ref.sample_margin[b])
+    if max_listed is None:
+        max_listed = max(2, B // 20)
+    assert listed <= max_listed, f"{listed} of {B} sequences near a threshold"
+    return listed, max_dh, ref
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_chain_reproduces_the_one_token_step(dtype):
+    w = wl.small_case(40, 6, 5003, dtype=dtype, temperature=0.9, case_id=41)
+    par = np.tile(np.arange(-1, w.gamma - 1, dtype=np.int32), (w.B, 1))
+    dl = np.array([b % (w.gamma + 1) for b in range(w.B)], np.int32)
+    for tau in (-1.0, w.taus[0]):
+        for kw in ({}, {"level": 2, "seq_base": 1 << 34}):
+            one = run_gpu_level(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, draft_len=dl, **kw)
+            acc, path, nxt, ent = run_tree(w.target, w.draft, w.tokens, par, w.seed, w.temperature, tau, n_nodes=dl, **kw)
+            np.testing.assert_array_equal(acc, one.accept_len)
+            np.testing.assert_array_equal(nxt, one.next_token)
+            np.testing.assert_array_equal(ent, one.entropy)
+            for b in range(w.B):
+                assert path[b, :acc[b]].tolist() == list(range(acc[b])) and np.all(path[b, acc[b]:] == -1)
+    assert len(set(acc.tolist())) > 2
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("widths,V", [([3], 1001), ([2, 4, 4], 3001), ([4, 3, 2, 1, 1], 9001), ([1, 2, 1, 3], 2049),
+                                      ([4, 4, 4, 4, 4, 4, 4, 4], 1500)])
+def test_small_trees(dtype, widths, V):
+    w = wl.tree_case(16, widths, V, dtype=dtype, temperature=0.8, draft_sigma=1.0, case_id=750 + len(widths))
+    nn = np.array([w.N - (b % 3) for b in range(w.B)], np.int32)
+    for tau in (-1.0, w.tau):
+        got = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, tau, n_nodes=nn)
+        listed, dh, ref = compare_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, tau, got,
+                                       n_nodes=nn)
+        print(f"[parity] {w.name} tau={tau:.2f}: listed={listed} max|dH|={dh:.2e} "
+              f"depth hist {np.bincount(got[0], minlength=len(widths) + 1).tolist()}", flush=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_many_rejected_candidates_at_one_context(dtype):
+    """A drafter far from the verifier: most candidates are rejected, so the later tests and the final draw run on
+    max(0, p - C q) with C well above 1."""
+    w = wl.tree_case(48, [12, 6], 4001, dtype=dtype, temperature=1.0, draft_sigma=3.0, peak_prob=0.0, case_id=760)
+    got = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, -1.0)
+    listed, dh, ref = compare_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, -1.0, got)
+    tested = (~np.isnan(ref.ratio_margin)).sum(axis=1)
+    assert (tested >= 6).sum() >= 5 and (ref.accept_len == 0).sum() >= 3
+    print(f"[parity] {w.name}: listed={listed} tests per sequence {np.bincount(tested).tolist()}", flush=True)
+
+
+def test_duplicate_and_out_of_range_candidates():
+    w = wl.tree_case(24, [4, 4], 2001, dtype="bf16", temperature=1.0, draft_sigma=1.5, case_id=770)
+    tok = w.node_token.copy()
+    tok[:, 1] = tok[:, 0]                                       # the same token offered twice
+    tok[::3, 2] = -1
+    tok[1::3, 3] = w.V
+    got = run_tree(w.target, w.draft, tok, w.node_parent, w.seed, 1.0, -1.0)
+    compare_tree(w.target, w.draft, tok, w.node_parent, w.seed, 1.0, -1.0, got)
+
+
+def test_a_node_with_an_invalid_parent_is_ignored():
+    w = wl.tree_case(12, [3, 3], 1001, dtype="f32", case_id=771)
+    par = w.node_parent.copy()
+    par[:, -1] = w.N - 1                                        # the last node names itself: no one's child
+    got = run_tree(w.target, w.draft, w.node_token, par, w.seed, 1.0, -1.0)
+    nn = np.full(w.B, w.N - 1, np.int32)
+    acc, path, nxt, ent = got
+    ref = orc.verify_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, 1.0, -1.0, n_nodes=nn)
+    near = np.nanmin(np.c_[ref.ratio_margin, ref.gate_margin, ref.sample_margin], axis=1) < MARGIN
+    np.testing.assert_array_equal(acc[~near], ref.accept_len[~near])
+    np.testing.assert_array_equal(nxt[~near], ref.next_token[~near])
+    np.testing.assert_array_equal(path[~near], ref.path[~near])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V", [1, 7, 64, 70001])
+def test_edge_shapes(dtype, V):
+    w = wl.tree_case(5, [2, 3], V, dtype=dtype, case_id=780 + V % 13)
+    for nn in (None, np.zeros(w.B, np.int32), np.array([0, 1, 2, 4, 5], np.int32)):
+        got = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, 1.0, 0.3 * math.log(max(V, 2)), n_nodes=nn)
+        compare_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, 1.0, 0.3 * math.log(max(V, 2)), got,
+                     n_nodes=nn, max_listed=w.B)
+
+
+def test_gate_everywhere_keeps_the_first_children():
+    w = wl.tree_case(10, [3, 2, 2, 2], 3001, dtype="bf16", case_id=790)
+    acc, path, nxt, ent = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, 1.0, 1e30)
+    ref = orc.verify_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, 1.0, 1e30)
+    np.testing.assert_array_equal(acc, ref.accept_len)
+    np.testing.assert_array_equal(path, ref.path)
+    assert np.all(acc == 4)
+
+
+def test_without_path_output_and_determinism():
+    w = wl.tree_case(20, [4, 2, 2], 6001, dtype="bf16", case_id=791)
+    a = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, 0.7, w.tau)
+    b = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, 0.7, w.tau, want_path=False)
+    c = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, 0.7, w.tau)
+    for x, y in ((a[0], b[0]), (a[2], b[2]), (a[0], c[0]), (a[1], c[1]), (a[2], c[2]), (a[3], c[3])):
+        np.testing.assert_array_equal(x, y)
+
+
+def test_unsupported_and_invalid_arguments():
+    w = wl.tree_case(3, [2], 101, case_id=792)
+    P, D = to_dev(w.target), to_dev(w.draft)
+    tok, par = to_dev(w.node_token), to_dev(w.node_parent)
+    acc = torch.zeros(3, dtype=torch.int32, device=DEV)
+    nxt = torch.zeros(3, dtype=torch.int32, device=DEV)
+    ws = hb.alloc_workspace(hb.hola_tree_workspace_bytes(3, w.N, w.V), DEV)
+    with pytest.raises(hb.HolaError):                           # greedy rows are not taken
+        hb.hola_verify_tree(P, D, tok, par, 1, 3, w.N, w.V, 0.0, 0.0, acc, nxt, ws)
+    with pytest.raises(hb.HolaError):                           # workspace too small
+        hb.hola_verify_tree(P, D, tok, par, 1, 3, w.N, w.V, 1.0, 0.0, acc, nxt, ws[:256])
+    with pytest.raises(hb.HolaError):
+        hb.hola_verify_tree(P, D, tok, par, 1, 3, 33, w.V, 1.0, 0.0, acc, nxt, ws)
+    assert hb.hola_tree_workspace_bytes(3, 33, 101) == 0 and hb.hola_tree_workspace_bytes(3, 0, 101) == 0
+
+
+@pytest.mark.timeout(600)
+def test_headline_vocabulary_tree_sampled_against_the_oracle():
+    """128256-wide bf16 rows, 64 sequences of a 16-node tree in one call; the oracle walks a sample of them."""
+    w = wl.tree_case(64, [4, 4, 4, 2, 2], 128256, dtype="bf16", temperature=0.8, zipf_slope=1.2, peak_prob=0.3, case_id=795)
+    dev = (to_dev(w.target), to_dev(w.draft))
+    for tau in (-1.0, 0.25 * math.log(w.V)):
+        got = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, tau, dev=dev)
+        acc, path, nxt, ent = got
+        idx = list(range(0, w.B, 8))
+        listed = 0
+        for b in idx:
+            sub = (acc[b:b + 1], path[b:b + 1], nxt[b:b + 1], ent[b:b + 1])
+            l, dh, ref = compare_tree(w.target[b:b + 1], w.draft[b:b + 1], w.node_token[b:b + 1], w.node_parent[b:b + 1],
+                                      w.seed, w.temperature, tau, sub, seq_base=b, max_listed=1)
+            listed += l
+        assert listed <= 2
+        assert np.all((nxt >= 0) & (nxt < w.V)) and np.all((acc >= 0) & (acc <= 5))
+        print(f"[parity] {w.name} tau={tau:.2f}: sampled {len(idx)} sequences, listed={listed}, "
+              f"depth hist {np.bincount(acc, minlength=6).tolist()}", flush=True)
