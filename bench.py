@@ -8,6 +8,7 @@ through {0.25, 0.5, 0.75} ln V from step to step.  Inputs are synthetic (seeded,
 and resident in HBM before the timed region.  Prints ONE JSON line.
 
   python bench.py [--steps K] [--warmup W]      the benchmark
+  python bench.py --tree 4,4,4,2,2              the same step over token trees (nodes per depth; not the headline)
   python bench.py --copy-calibration            only a plain copy kernel of known size, for scaling the
                                                 FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run
 """
@@ -50,6 +51,101 @@ def copy_calibration() -> int:
     return 0
 
 
+def bench_tree(args) -> int:
+    """The verify step over token trees: B sequences of one tree shape on 128256-wide bf16 rows, thresholds cycling
+    through (off, 0.25 ln V).  A step is one hola_verify_tree call; the unit of work is a tree node."""
+    import numpy as np
+    import torch
+    from paper_2506_18952_amd import binding as hb
+    from paper_2506_18952_amd import workloads as wl
+    dev = "cuda:0"
+    widths = [int(x) for x in args.tree.split(",")]
+    t0 = time.perf_counter()
+    w = wl.tree_case(args.batch, widths, 128256, dtype="bf16", temperature=0.8, zipf_slope=1.2, peak_prob=0.3, case_id=795)
+    log(f"workload {w.name}: generated in {time.perf_counter() - t0:.1f}s, {w.logit_bytes / 1e9:.3f} GB of logits")
+    B, N, V = w.B, w.N, w.V
+    P = torch.from_numpy(w.target.view(np.int16)).to(dev)
+    D = torch.from_numpy(w.draft.view(np.int16)).to(dev)
+    tok, par = torch.from_numpy(w.node_token).to(dev), torch.from_numpy(w.node_parent).to(dev)
+    acc = torch.empty(B, dtype=torch.int32, device=dev)
+    nxt = torch.empty(B, dtype=torch.int32, device=dev)
+    path = torch.empty((B, N), dtype=torch.int32, device=dev)
+    ent = torch.empty((B, N), dtype=torch.float32, device=dev)
+    ws = hb.alloc_workspace(hb.hola_tree_workspace_bytes(B, N, V), dev)
+    stream = torch.cuda.current_stream()
+    taus = [-1.0, float(np.float32(0.25 * np.log(V)))]
+
+    def step(i, seed_offset=True):
+        hb.hola_verify_tree(P, D, tok, par, w.seed + (i if seed_offset else 0), B, N, V, w.temperature, taus[i % len(taus)],
+                            acc, nxt, ws, out_path=path, out_entropy=ent, stream=stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    hb.hola_profile_enable(True)
+    hb.hola_profile_collect()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    stage_ms, stage_n = hb.hola_profile_collect()
+    hb.hola_profile_enable(False)
+    per_tau = []
+    for i in range(len(taus)):
+        step(i)
+        torch.cuda.synchronize()
+        a_np = acc.cpu().numpy()
+        per_tau.append({"tau": round(taus[i], 4), "depth_hist": np.bincount(a_np, minlength=len(widths) + 1).tolist(),
+                        "emitted_tokens": int(a_np.sum()) + B})
+    # algorithmic bytes of the statistics pass: every target row, and the draft rows of contexts with children
+    used = int(sum(1 for c in range(N) if (w.node_parent[0] == c - 1).any()))
+    k_bytes = B * (used + N + 1) * V * 2
+    k_ms = stage_ms[0] / max(stage_n[0], 1)
+    achieved = k_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0
+    out = {
+        "metric": "verified tree nodes/sec + achieved HBM GB/s (% of MI355X peak)",
+        "value": round(B * N * args.steps / dt, 1), "unit": "nodes/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"token trees (not the headline workload): B={B}, nodes per depth {widths} (N={N}), V={V} bf16 "
+                               f"logits T=0.8, tau cycling (off, 0.25 ln V)",
+                   "entry_point": "hola_verify_tree", "parallelism": "single GPU"},
+        "stage_ms": {hb.STAGE_NAMES[i]: round(stage_ms[i] / stage_n[i], 5) for i in range(hb.HOLA_N_STAGES) if stage_n[i]},
+        "per_threshold": per_tau,
+        "roofline": {"bound": "hbm", "kernel": "row_stats_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": int(k_bytes), "avg_launch_ms": round(k_ms, 5)},
+    }
+    if not args.no_cpu:
+        from oracle import hola_oracle as orc
+        threads = orc.max_threads()
+        n = min(B, 64)                                          # a slice of the batch: a few seconds of oracle time
+        t0 = time.perf_counter()
+        refs = [orc.verify_tree(w.target[:n], w.draft[:n], w.node_token[:n], w.node_parent[:n], w.seed, w.temperature, tau,
+                                num_threads=threads) for tau in taus]
+        cdt = time.perf_counter() - t0
+        same = near = 0
+        for i in range(len(taus)):
+            step(i, seed_offset=False)
+            torch.cuda.synchronize()
+            ok = (acc.cpu().numpy()[:n] == refs[i].accept_len) & (nxt.cpu().numpy()[:n] == refs[i].next_token) \
+                & (path.cpu().numpy()[:n] == refs[i].path).all(axis=1)
+            same += int(ok.sum())
+            m = np.nanmin(np.c_[refs[i].gate_margin, refs[i].ratio_margin, refs[i].sample_margin, np.full(n, np.inf)], axis=1)
+            near += int((m < 1e-6).sum())
+        out["cpu_baseline"] = {"value": round(n * N * len(taus) / cdt, 1), "unit": "nodes/s", "cores": threads, "kind": "oracle",
+                               "sample": f"the first {n} sequences of the same workload at each of the {len(taus)} thresholds "
+                                         f"({cdt:.2f}s wall); float64 C oracle, OpenMP over sequences",
+                               "agree_path_and_next_token": f"{same}/{n * len(taus)}", "oracle_listed_near_threshold": near}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +155,8 @@ def main() -> int:
     ap.add_argument("--path", choices=["auto", "split", "fused"], default="auto", help="kernel path (auto: library's choice)")
     ap.add_argument("--top-k", type=int, default=0, help="top-k filter on both models (0: off; not the headline workload)")
     ap.add_argument("--top-p", type=float, default=0.0, help="top-p filter on both models (0: off; not the headline workload)")
+    ap.add_argument("--tree", type=str, default="", help="token trees with this many nodes per depth, e.g. 4,4,4,2,2 "
+                                                          "(hola_verify_tree; not the headline workload)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-baseline leg")
     ap.add_argument("--copy-calibration", action="store_true")
     args = ap.parse_args()
@@ -81,6 +179,8 @@ def main() -> int:
     if args.copy_calibration:
         return copy_calibration()
     hb.hola_set_tuning(path={"auto": hb.PATH_AUTO, "split": hb.PATH_SPLIT, "fused": hb.PATH_FUSED}[args.path])
+    if args.tree:
+        return bench_tree(args)
 
     t0 = time.perf_counter()
     w = wl.config3(B=args.batch)

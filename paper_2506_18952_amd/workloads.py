@@ -262,11 +262,14 @@ def tree_parents(widths: Sequence[int]) -> np.ndarray:
 def tree_case(B: int, widths: Sequence[int], V: int, dtype: str = "f32", temperature: float = 1.0,
               tau_frac: float = 0.5, seed: int = 9, sigma: float = 2.0, zipf_slope: Optional[float] = 1.1,
               draft_sigma: float = 0.75, peak_prob: float = 0.2, peak_boost: float = 12.0,
-              case_id: int = 700) -> TreeWorkload:
+              case_id: int = 700, random_topology: bool = False) -> TreeWorkload:
     """Token trees with the recipe of the chains: every context has its own target row and a draft row that is
-    the target row plus noise; the children of a context are independent draws from its draft row."""
+    the target row plus noise; the children of a context are independent draws from its draft row.
+    random_topology: every sequence draws its own tree of sum(widths) nodes, node n under a uniformly chosen
+    earlier node or the prefix."""
     par = tree_parents(widths)
     N = len(par)
+    parents = np.tile(par, (B, 1))
     np_dt = np.uint16 if dtype == "bf16" else np.float32
     target = np.empty((B, N + 1, V), dtype=np_dt)
     draft = np.empty((B, N, V), dtype=np_dt)
@@ -285,10 +288,12 @@ def tree_case(B: int, widths: Sequence[int], V: int, dtype: str = "f32", tempera
         D = P[:N] + np.float32(draft_sigma) * rng.standard_normal(size=(N, V), dtype=np.float32)
         _store(target, b, P, dtype)
         Dq = _store(draft, b, D, dtype)
-        tokens[b] = _gumbel_argmax(rng, Dq[par + 1], temperature)
+        if random_topology:
+            parents[b] = [int(rng.integers(-1, n)) for n in range(N)]
+        tokens[b] = _gumbel_argmax(rng, Dq[parents[b] + 1], temperature)
 
     _parallel(one, list(range(B)))
     return TreeWorkload(name=f"tree_B{B}_w{'-'.join(str(w) for w in widths)}_V{V}_{dtype}", B=B, N=N, V=V, dtype=dtype,
                         temperature=temperature, tau=float(np.float32(tau_frac * math.log(V))), seed=seed,
                         widths=list(widths), target=target, draft=draft, node_token=tokens,
-                        node_parent=np.tile(par, (B, 1)))
+                        node_parent=parents)

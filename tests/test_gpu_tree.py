@@ -193,3 +193,51 @@ def test_headline_vocabulary_tree_sampled_against_the_oracle():
         assert np.all((nxt >= 0) & (nxt < w.V)) and np.all((acc >= 0) & (acc <= 5))
         print(f"[parity] {w.name} tau={tau:.2f}: sampled {len(idx)} sequences, listed={listed}, "
               f"depth hist {np.bincount(acc, minlength=6).tolist()}", flush=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_random_topologies_per_sequence(dtype, seed):
+    """Every sequence its own random tree (chains, stars, bushes), ragged node counts, shapes off the tile grid."""
+    rng = np.random.default_rng(900 + seed)
+    N = int(rng.integers(1, 33))
+    V = int(rng.choice([37, 1000, 4097, 12289]))
+    B = int(rng.integers(1, 40))
+    w = wl.tree_case(B, [N], V, dtype=dtype, temperature=float(rng.choice([0.6, 1.0, 1.7])),
+                     draft_sigma=float(rng.choice([0.5, 1.5])), case_id=800 + seed, random_topology=True)
+    nn = rng.integers(0, N + 1, B).astype(np.int32)
+    for tau in (-1.0, 0.4 * math.log(V)):
+        got = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, tau, n_nodes=nn,
+                       level=seed, seq_base=seed * 1000)
+        listed, dh, ref = compare_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, tau, got,
+                                       n_nodes=nn, level=seed, seq_base=seed * 1000, max_listed=max(2, B // 10))
+        print(f"[parity] random trees B={B} N={N} V={V} {dtype} tau={tau:.2f}: listed={listed} "
+              f"depth hist {np.bincount(got[0]).tolist()}", flush=True)
+
+
+def test_tree_call_in_a_hip_graph():
+    """The three launches of a call captured once and replayed with the program's own work in between."""
+    w = wl.tree_case(12, [3, 3, 2], 5001, dtype="bf16", case_id=796)
+    P, D = to_dev(w.target), to_dev(w.draft)
+    tok, par = to_dev(w.node_token), to_dev(w.node_parent)
+    B, N, V = w.B, w.N, w.V
+    acc = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    nxt = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    path = torch.full((B, N), -7, dtype=torch.int32, device=DEV)
+    ws = hb.alloc_workspace(hb.hola_tree_workspace_bytes(B, N, V), DEV)
+    eager = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, 1.0, w.tau, dev=(P, D))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            hb.hola_verify_tree(P, D, tok, par, w.seed, B, N, V, 1.0, w.tau, acc, nxt, ws, out_path=path, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(3):
+        acc.fill_(-7); nxt.fill_(-7); path.fill_(-7)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(acc.cpu().numpy(), eager[0])
+        np.testing.assert_array_equal(path.cpu().numpy(), eager[1])
+        np.testing.assert_array_equal(nxt.cpu().numpy(), eager[2])
