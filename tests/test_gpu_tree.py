@@ -241,3 +241,38 @@ def test_tree_call_in_a_hip_graph():
         np.testing.assert_array_equal(acc.cpu().numpy(), eager[0])
         np.testing.assert_array_equal(path.cpu().numpy(), eager[1])
         np.testing.assert_array_equal(nxt.cpu().numpy(), eager[2])
+
+
+def test_more_sequences_than_compute_units_and_strided_rows():
+    """Beyond one sequence per compute unit the tail kernel runs 8 wavefronts per workgroup; rows may sit in wider
+    buffers (row strides above V, rows not 16-byte aligned)."""
+    w = wl.tree_case(300, [3, 2, 2], 1003, dtype="bf16", temperature=0.9, draft_sigma=1.2, case_id=797)
+    got = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, -1.0)
+    compare_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, -1.0, got)
+    hb.hola_set_tuning(fused_waves=8)
+    try:
+        got8 = run_tree(w.target[:40], w.draft[:40], w.node_token[:40], w.node_parent[:40], w.seed, w.temperature, -1.0)
+    finally:
+        hb.hola_set_tuning()
+    for x, y in zip(got, got8):
+        np.testing.assert_array_equal(x[:40], y)
+    # the same rows inside buffers with a stride of V + 5 elements
+    B, N, V = 40, w.N, w.V
+    ld = V + 5
+    Pw = np.zeros((B, N + 1, ld), np.uint16)
+    Dw = np.zeros((B, N, ld), np.uint16)
+    Pw[:, :, :V], Dw[:, :, :V] = w.target[:B], w.draft[:B]
+    Pw[:, :, V:], Dw[:, :, V:] = 0x7f80, 0x7f80                 # +inf beside the rows: must never be read as logits
+    P, D = to_dev(Pw), to_dev(Dw)
+    acc = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    nxt = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    path = torch.full((B, N), -7, dtype=torch.int32, device=DEV)
+    ent = torch.full((B, N), -7.0, dtype=torch.float32, device=DEV)
+    ws = hb.alloc_workspace(hb.hola_tree_workspace_bytes(B, N, V), DEV)
+    hb.hola_verify_tree(P, D, to_dev(w.node_token[:B]), to_dev(w.node_parent[:B]), w.seed, B, N, V, w.temperature, -1.0,
+                        acc, nxt, ws, out_path=path, out_entropy=ent, target_ld=ld, draft_ld=ld)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(acc.cpu().numpy(), got[0][:B])
+    np.testing.assert_array_equal(path.cpu().numpy(), got[1][:B])
+    np.testing.assert_array_equal(nxt.cpu().numpy(), got[2][:B])
+    np.testing.assert_allclose(ent.cpu().numpy(), got[3][:B], rtol=1e-5, atol=1e-6)
