@@ -30,7 +30,7 @@
  *   draft_logits  [B, gamma,   V]
  *   draft_tokens  [B, gamma]        int32
  *   out_accept_len[B], out_next_token[B]  int32;  out_entropy [B, gamma] float (nats)
- * bf16 logits are passed as raw 16-bit patterns.  gamma <= 32.
+ * bf16 logits are passed as raw 16-bit patterns.  gamma <= HOLA_MAX_GAMMA = 63.
  *
  * Ownership and memory spaces.  Every pointer named "device" is caller-owned DEVICE memory
  * (for PyTorch: tensor.data_ptr()); host pointers are marked "host".  The library never
@@ -76,7 +76,7 @@ typedef enum {
 } hola_status;
 
 enum { HOLA_DTYPE_F32 = 0, HOLA_DTYPE_BF16 = 1 };
-enum { HOLA_MAX_GAMMA = 32 };
+enum { HOLA_MAX_GAMMA = 63 };   /* drafted positions (or tree nodes) per sequence: one lane of a wavefront each */
 
 /* One verify level on float logits.  Steps 1-6 above with a single temperature (> 0) and
  * threshold; seq_base = 0, level = 0.  All pointers device; stream may be NULL. */
@@ -281,7 +281,7 @@ typedef struct {
     int32_t stats_split;            /* workgroups per logits row in the split-row statistics kernel (1..16) */
     int32_t stats_unroll;           /* 16-byte loads in flight per lane while streaming a row: 2, 4, 8 or 16 */
     int32_t path;                   /* 1: split-row statistics + per-sequence tail kernel (2 launches);
-                                       2: fused per-sequence kernel (1 launch);
+                                       2: fused per-sequence kernel (1 launch; gamma <= 32, else as 1);
                                        3: split-row statistics, accept, tile sums, select (4 launches);
                                        0: the library's choice for the shape (path 1 whenever the
                                           per-sequence kernels support it, else path 3) */

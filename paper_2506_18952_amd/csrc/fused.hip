@@ -17,6 +17,7 @@
 namespace hola {
 
 constexpr int kFusedMaxTiles = 2048;
+constexpr int kFusedMaxGamma = 32;           // the fused kernel parks the partials of its 2 gamma + 1 rows in shared memory
 
 struct SeqShared {
     RowStat stat[2 * HOLA_MAX_GAMMA + 1];      // per row: draft rows 0..g-1, target rows g..2g
@@ -277,7 +278,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
 template <bool BF16, int NW, int U>
 __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedParams p)
 {
-    __shared__ Partial s_part[2 * HOLA_MAX_GAMMA + 1][NW];
+    __shared__ Partial s_part[2 * kFusedMaxGamma + 1][NW];
     __shared__ SeqShared sh;
     __shared__ int32_t s_prog[NW];
 
@@ -363,6 +364,11 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
 }
 
 bool fused_supported(int32_t gamma, int32_t V, int dtype)
+{
+    return gamma <= kFusedMaxGamma && sampler_tiles(V, dtype) <= kFusedMaxTiles;
+}
+
+bool tail_supported(int32_t gamma, int32_t V, int dtype)
 {
     return gamma <= HOLA_MAX_GAMMA && sampler_tiles(V, dtype) <= kFusedMaxTiles;
 }

@@ -165,7 +165,7 @@ static hola_status check_args(const hola_verify_args& a, bool literal = false)
     if (filters_on(a)) {
         if (a.top_k < 0 || !(a.top_p >= 0.f)) return HOLA_ERR_INVALID_ARG;
         if (literal || a.row_temperature || !(a.temperature > 0.f) || a.draft_stats_in || a.target_stats_in ||
-            a.target_stats_out || a.V >= (1 << 22) || !fused_supported(a.gamma, a.V, a.dtype))
+            a.target_stats_out || a.V >= (1 << 22) || !tail_supported(a.gamma, a.V, a.dtype))
             return HOLA_ERR_UNSUPPORTED;
     }
     // Supplied target statistics carry no argmax, which greedy rows need.
@@ -198,7 +198,7 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     const int nsplit = choose_split(rows > 0 ? rows : 1, a.V, a.dtype, tune);
 
     // Per-sequence parameters shared by the fused kernel and the tail kernel.
-    const bool per_seq_ok = fused_supported(a.gamma, a.V, a.dtype);
+    const bool per_seq_ok = tail_supported(a.gamma, a.V, a.dtype);
     if (skip_target && !per_seq_ok) return HOLA_ERR_UNSUPPORTED;    // only the tail kernel takes them
     if (skip_target) tune.path = 1;
     FusedParams fp{};
@@ -217,7 +217,7 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     if (filtered) tune.path = 1;                                  // statistics, keep sets, then the tail kernel
     // Path 2: one fused launch per level (one workgroup per sequence streams its own rows).
     const bool want_fused = tune.path == 2;
-    if (want_fused && per_seq_ok) {
+    if (want_fused && fused_supported(a.gamma, a.V, a.dtype)) {
         hipError_t fe;
         { StageTimer t(5, s); fe = launch_fused(fp, tune, s); }
         if (fe != hipSuccess) return hip_fail(fe, "fused verify launch");

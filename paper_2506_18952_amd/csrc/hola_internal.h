@@ -146,7 +146,8 @@ hipError_t launch_tree_tail(const TreeParams& p, const Partial* partials, int np
 
 hipError_t launch_fused(const FusedParams& p, const Tuning& t, hipStream_t s);
 hipError_t launch_tail(const FusedParams& p, const Partial* partials, int nparts, const Tuning& t, hipStream_t s);
-bool fused_supported(int32_t gamma, int32_t V, int dtype);
+bool fused_supported(int32_t gamma, int32_t V, int dtype);   // the one-launch fused kernel
+bool tail_supported(int32_t gamma, int32_t V, int dtype);    // the per-sequence tail kernel after the split-row pass
 bool literal_supported(int32_t gamma, int32_t V, int dtype);
 hipError_t launch_literal(const FusedParams& p, const Partial* partials, int nparts, int32_t* out_tokens,
                           int32_t* out_calls, hipStream_t s);

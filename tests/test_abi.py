@@ -35,7 +35,8 @@ def test_status_strings_and_version():
 def test_workspace_bytes():
     assert hb.hola_workspace_bytes(0, 4, 100) > 0
     assert hb.hola_workspace_bytes(4, 0, 100) == 0           # gamma < 1
-    assert hb.hola_workspace_bytes(4, 33, 100) == 0          # gamma > 32
+    assert hb.hola_workspace_bytes(4, 64, 100) == 0          # gamma > 63
+    assert hb.hola_workspace_bytes(4, 63, 100) > 0
     assert hb.hola_workspace_bytes(4, 4, 0) == 0
     assert hb.hola_workspace_bytes(-1, 4, 100) == 0
     a, b, c = (hb.hola_workspace_bytes(*s) for s in ((8, 4, 1000), (16, 4, 1000), (16, 8, 128256)))
@@ -46,7 +47,7 @@ def test_workspace_bytes():
     assert hb.hola_workspace_bytes(8192, 8, 128256) < hb.hola_workspace_bytes(256, 8, 128256) * 32
     assert hb.hola_hsd_workspace_bytes(3, 128, 8, 151936) > hb.hola_workspace_bytes(128, 9, 151936)
     assert hb.hola_hsd_workspace_bytes(1, 8, 4, 100) == 0    # needs at least two models
-    assert hb.hola_hsd_workspace_bytes(3, 8, 32, 100) == 0   # gamma grows past the limit
+    assert hb.hola_hsd_workspace_bytes(3, 8, 63, 100) == 0   # gamma grows past the limit
 
 
 def _args(**kw):
@@ -65,7 +66,7 @@ def _args(**kw):
 @pytest.mark.parametrize("kw,want", [
     (dict(B=-1), hb.HOLA_ERR_INVALID_ARG),
     (dict(gamma=0), hb.HOLA_ERR_INVALID_ARG),
-    (dict(gamma=33), hb.HOLA_ERR_INVALID_ARG),
+    (dict(gamma=64), hb.HOLA_ERR_INVALID_ARG),
     (dict(V=0), hb.HOLA_ERR_INVALID_ARG),
     (dict(dtype=7), hb.HOLA_ERR_UNSUPPORTED),
     (dict(target_logits=None), hb.HOLA_ERR_INVALID_ARG),

@@ -138,7 +138,7 @@ def test_small_cases(dtype, top_k, top_p, V):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("B,g,V", [(3, 1, 7), (2, 2, 8), (5, 3, 1001), (4, 4, 2049), (3, 2, 70001), (2, 1, 1)])
+@pytest.mark.parametrize("B,g,V", [(3, 1, 7), (2, 2, 8), (5, 3, 1001), (4, 4, 2049), (3, 2, 70001), (2, 1, 1), (2, 45, 301)])
 def test_ragged_shapes(B, g, V, dtype):
     w = wl.small_case(B, g, V, dtype=dtype, temperature=1.1, case_id=400 + V % 31)
     dl = np.array([(b * 2 + 1) % (g + 1) for b in range(B)], np.int32)

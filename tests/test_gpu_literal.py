@@ -66,6 +66,12 @@ def test_literal_small_and_ragged(dtype):
         _check(w, tau, draft_len=lens, seq_base=(1 << 33) + 7)
 
 
+def test_literal_long_drafts():
+    """More drafted positions than half a wavefront (the limit is 63)."""
+    w = wl.small_case(3, 63, 333, dtype="bf16", temperature=1.0, case_id=412)
+    _check(w, 0.5 * math.log(w.V))
+
+
 def test_literal_greedy_rows():
     w = wl.small_case(8, 4, 3001, dtype="bf16", greedy_below=4, temperature=0.7, case_id=411)
     for tau in (0.0, 0.5 * math.log(w.V)):

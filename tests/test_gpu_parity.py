@@ -256,7 +256,7 @@ def test_row_stats_entry_closed_forms_and_oracle():
 # ----------------------------------------------------------------------------- ragged shapes and edge cases
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("B,g,V", [(1, 1, 1), (3, 1, 7), (2, 2, 8), (5, 3, 1001), (4, 4, 2049), (7, 5, 4099),
-                                   (3, 32, 517), (2, 2, 70001)])
+                                   (3, 32, 517), (5, 33, 300), (3, 63, 517), (2, 2, 70001)])
 def test_ragged_shapes(B, g, V, dtype):
     w = wl.small_case(B, g, V, dtype=dtype, temperature=0.9, case_id=200 + V % 97)
     for tau in (0.0, w.taus[0]):

@@ -82,7 +82,7 @@ def test_chain_reproduces_the_one_token_step(dtype):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("widths,V", [([3], 1001), ([2, 4, 4], 3001), ([4, 3, 2, 1, 1], 9001), ([1, 2, 1, 3], 2049),
-                                      ([4, 4, 4, 4, 4, 4, 4, 4], 1500)])
+                                      ([4, 4, 4, 4, 4, 4, 4, 4], 1500), ([8, 8, 8, 8, 8, 8, 8, 7], 1200)])
 def test_small_trees(dtype, widths, V):
     w = wl.tree_case(16, widths, V, dtype=dtype, temperature=0.8, draft_sigma=1.0, case_id=750 + len(widths))
     nn = np.array([w.N - (b % 3) for b in range(w.B)], np.int32)
@@ -170,8 +170,8 @@ def test_unsupported_and_invalid_arguments():
     with pytest.raises(hb.HolaError):                           # workspace too small
         hb.hola_verify_tree(P, D, tok, par, 1, 3, w.N, w.V, 1.0, 0.0, acc, nxt, ws[:256])
     with pytest.raises(hb.HolaError):
-        hb.hola_verify_tree(P, D, tok, par, 1, 3, 33, w.V, 1.0, 0.0, acc, nxt, ws)
-    assert hb.hola_tree_workspace_bytes(3, 33, 101) == 0 and hb.hola_tree_workspace_bytes(3, 0, 101) == 0
+        hb.hola_verify_tree(P, D, tok, par, 1, 3, 64, w.V, 1.0, 0.0, acc, nxt, ws)
+    assert hb.hola_tree_workspace_bytes(3, 64, 101) == 0 and hb.hola_tree_workspace_bytes(3, 0, 101) == 0
 
 
 @pytest.mark.timeout(600)
@@ -200,7 +200,7 @@ def test_headline_vocabulary_tree_sampled_against_the_oracle():
 def test_random_topologies_per_sequence(dtype, seed):
     """Every sequence its own random tree (chains, stars, bushes), ragged node counts, shapes off the tile grid."""
     rng = np.random.default_rng(900 + seed)
-    N = int(rng.integers(1, 33))
+    N = int(rng.integers(1, 64))
     V = int(rng.choice([37, 1000, 4097, 12289]))
     B = int(rng.integers(1, 40))
     w = wl.tree_case(B, [N], V, dtype=dtype, temperature=float(rng.choice([0.6, 1.0, 1.7])),
