@@ -49,6 +49,11 @@ struct TreeShared {
     double tiles[kTreeMaxTiles];
     double px[64], qx[64], u[64];              // per node: the two probabilities of its token, its test uniform
     int32_t path[64];                          // kept nodes, from the prefix on
+    int32_t ctx_of[64];                        // per node: the context it hangs under, -1: no node
+    // the walk's state between rounds
+    int32_t w_ctx, w_depth, w_first, w_dead;
+    double w_C, w_Z;
+    unsigned long long w_kids, w_all;
     // the row operation wavefront 0 asks of the workgroup
     int32_t op_ctx, op_bonus, op_sample, done;
     double op_C;
@@ -96,9 +101,9 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
     __syncthreads();
 
     // ---- per node (lane n of wavefront 0): context, probabilities of its token, test uniform
-    const uint64_t seq = (uint64_t)(p.seq_base + b);
     int my_ctx = -1;
     if (wave == 0) {
+        const uint64_t seq = (uint64_t)(p.seq_base + b);
         const int n = lane;
         double p_x = 0.0, q_x = 1.0, un = 0.0;
         if (n < len) {
@@ -124,15 +129,26 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
     }
     __builtin_amdgcn_wave_barrier();
 
-    // ---- the walk (wavefront 0, every lane the same values) and the row sweeps it asks for (all wavefronts)
-    int ctx = 0, depth = 0;
-    bool first = true, dead = false;
-    double C = 0.0, Z = 1.0;
-    unsigned long long kids = 0, all_kids = 0;
-    if (wave == 0) { all_kids = __ballot(my_ctx == 0); kids = all_kids; }
-    const double tau = (double)p.tau;
+    // ---- the walk (wavefront 0, every lane the same values) and the row sweeps it asks for (all wavefronts).
+    // Between rounds the walk's state rests in shared memory, so that no register holds it during a sweep.
+    if (wave == 0) {
+        sh.ctx_of[lane] = my_ctx;
+        const unsigned long long k0 = __ballot(my_ctx == 0);    // the children of the prefix
+        if (lane == 0) {
+            sh.w_ctx = 0; sh.w_depth = 0; sh.w_first = 1; sh.w_dead = 0; sh.w_C = 0.0; sh.w_Z = 1.0;
+            sh.w_kids = k0; sh.w_all = k0;
+        }
+    }
     for (int it = 0; it < 2 * 64 + 4; ++it) {                   // every round ends the walk or uses up a child
         if (wave == 0) {
+            __builtin_amdgcn_wave_barrier();
+            const int mine = sh.ctx_of[lane];
+            int ctx = sh.w_ctx, depth = sh.w_depth;
+            bool first = sh.w_first != 0;
+            const bool dead = sh.w_dead != 0;
+            double C = sh.w_C;
+            const double Z = sh.w_Z, tau = (double)p.tau;
+            unsigned long long kids = sh.w_kids, all_kids = sh.w_all;
             int sample = 1, bonus = 1;
             for (;;) {
                 if (dead || all_kids == 0) { bonus = 1; break; } // nothing drafted here (or a residual without mass)
@@ -143,22 +159,27 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
                 bool ok;
                 if (first) ok = (sh.stat[ctx].H < tau) || (un * q_x < p_x);
                 else ok = (un * q_x * Z < fmax(0.0, p_x - C * q_x));
-                first = false;
                 if (ok) {
                     if (lane == 0) sh.path[depth] = n;
                     ++depth;
                     ctx = n + 1;
-                    all_kids = __ballot(my_ctx == ctx);
+                    all_kids = __ballot(mine == ctx);
                     kids = all_kids;
-                    C = 0.0; Z = 1.0; first = true;
-                    continue;
+                    C = 0.0; first = true;
+                    continue;                                    // Z is not read before the next rejection's sweep
                 }
-                C += Z;
+                C += first ? 1.0 : Z;
+                first = false;
                 if (kids == 0) { bonus = 0; break; }
                 sample = 0; bonus = 0;                           // more children to try: the next Z
                 break;
             }
-            if (lane == 0) { sh.op_ctx = ctx; sh.op_bonus = bonus; sh.op_sample = sample; sh.op_C = C; }
+            __builtin_amdgcn_wave_barrier();
+            if (lane == 0) {
+                sh.op_ctx = ctx; sh.op_bonus = bonus; sh.op_sample = sample; sh.op_C = C;
+                sh.w_ctx = ctx; sh.w_depth = depth; sh.w_first = first ? 1 : 0; sh.w_C = C;
+                sh.w_kids = kids; sh.w_all = all_kids;
+            }
         }
         __syncthreads();
         const int o_ctx = sh.op_ctx, o_bonus = sh.op_bonus, o_sample = sh.op_sample;
@@ -187,29 +208,35 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
         __syncthreads();
         if (wave == 0) {
             if (!o_sample) {
-                Z = rp.ok ? tiles_total(sh.tiles, p.ntiles, lane) : 0.0;
-                if (!(Z > 0.0) || !(Z - Z == 0.0) || rp.bonus) dead = true;   // no residual mass: draw from p itself
+                const double Z = rp.ok ? tiles_total(sh.tiles, p.ntiles, lane) : 0.0;
+                if (lane == 0) {
+                    sh.w_Z = Z;
+                    if (!(Z > 0.0) || !(Z - Z == 0.0) || rp.bonus) sh.w_dead = 1;   // no residual mass: draw from p itself
+                }
             } else {
+                const uint64_t seq = (uint64_t)(p.seq_base + b);
                 const Philox4 r = philox4x32_10((uint32_t)o_ctx, (uint32_t)seq, (uint32_t)(seq >> 32), p.level,
                                                 (uint32_t)p.seed, (uint32_t)(p.seed >> 32));
                 const int32_t tk = rp.ok ? select_token<BF16, true>(rp, sh.tiles, p.ntiles, (double)u24(r.y), lane) : -1;
-                if (tk == -2 && !dead) {
-                    dead = true;                                  // residual without mass: once more, as a draw from p
-                } else if (lane == 0) {
-                    sh.tok = tk < 0 ? -1 : tk;
-                    sh.done = 1;
+                if (lane == 0) {
+                    if (tk == -2 && !sh.w_dead) {
+                        sh.w_dead = 1;                            // residual without mass: once more, as a draw from p
+                    } else {
+                        sh.tok = tk < 0 ? -1 : tk;
+                        sh.done = 1;
+                    }
                 }
             }
         }
         __syncthreads();
         if (sh.done) break;
     }
-    if (wave == 0) {                                            // depth is wavefront 0's
+    if (wave == 0) {
+        const int depth = sh.w_depth;
         if (lane == 0) {
             p.out_next_token[b] = sh.done ? sh.tok : -1;
             p.out_accept_len[b] = depth;
         }
-        __builtin_amdgcn_wave_barrier();
         if (p.out_path && lane < N) p.out_path[(int64_t)b * N + lane] = lane < depth ? sh.path[lane] : -1;
     }
 }
