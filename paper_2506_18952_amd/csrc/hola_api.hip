@@ -557,7 +557,7 @@ hola_status hola_hsd_verify_ex(const hola_hsd_args* args)
 size_t hola_tree_workspace_bytes(int32_t B, int32_t N, int32_t V)
 {
     if (!shape_ok(B, N, V)) return 0;
-    return align_up(carve(nullptr, B, N, V).bytes) + align_up((size_t)B * N) + 256;
+    return carve(nullptr, B, N, V).bytes + 256;
 }
 
 hola_status hola_verify_tree(const hola_tree_args* args)
@@ -580,7 +580,6 @@ hola_status hola_verify_tree(const hola_tree_args* args)
 
     hipStream_t s = (hipStream_t)a.stream;
     const Workspace w = carve(a.workspace, a.B, a.N, a.V);
-    uint8_t* used = (uint8_t*)a.workspace + align_up(w.bytes);
     const int64_t tld = a.target_ld ? a.target_ld : a.V, dld = a.draft_ld ? a.draft_ld : a.V;
     Tuning tune;
     { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
@@ -588,22 +587,19 @@ hola_status hola_verify_tree(const hola_tree_args* args)
     const int nsplit = choose_split(rows, a.V, a.dtype, tune);
 
     hipError_t e;
-    { StageTimer t(4, s); e = launch_tree_prepare(a.node_parent, a.n_nodes, a.B, a.N, used, s); }
-    if (e != hipSuccess) return hip_fail(e, "tree prepare launch");
-
     RowStatsParams rs{};
     rs.target = a.target_logits; rs.draft = a.draft_logits; rs.target_ld = tld; rs.draft_ld = dld;
     rs.draft_len = a.n_nodes; rs.temperature = a.temperature;
     rs.B = a.B; rs.gamma = a.N; rs.V = a.V; rs.nsplit = nsplit;
     rs.lse_only_targets = 1;                                    // only the drafts' entropy gates
-    rs.draft_used = used;
+    rs.tree_parent = a.node_parent;                             // draft rows of childless contexts are not read
     rs.partials = w.partials;
     { StageTimer t(0, s); e = launch_row_stats(rs, a.dtype, tune, s); }
     if (e != hipSuccess) return hip_fail(e, "row statistics launch");
 
     TreeParams tp{};
     tp.target = a.target_logits; tp.draft = a.draft_logits; tp.dtype = a.dtype; tp.target_ld = tld; tp.draft_ld = dld;
-    tp.tokens = a.node_token; tp.parent = a.node_parent; tp.n_nodes = a.n_nodes; tp.used = used;
+    tp.tokens = a.node_token; tp.parent = a.node_parent; tp.n_nodes = a.n_nodes;
     tp.seed = a.seed; tp.level = a.level; tp.seq_base = a.seq_base;
     tp.B = a.B; tp.N = a.N; tp.V = a.V; tp.ntiles = sampler_tiles(a.V, a.dtype);
     tp.temperature = a.temperature; tp.tau = a.entropy_threshold;

@@ -80,7 +80,8 @@ struct RowStatsParams {
     int32_t lse_only_targets;          // nobody asks for the entropy of the target rows: their pass leaves T out
     int32_t tile_cols, ntiles;         // ntiles > 0: "sequence" b is column tile b % ntiles of plain row b / ntiles
     int32_t literal;                   // Equation (1) literal mode: target row j is needed only for j < len
-    const uint8_t* draft_used;         // device [B, gamma] or null: draft rows marked 0 are skipped (token trees)
+    const int32_t* tree_parent;        // device [B, gamma] or null: token trees, node parents; draft rows of
+                                       // contexts without children are skipped
     Partial* partials;
 };
 
@@ -134,14 +135,12 @@ struct TreeParams {
     const void* target; const void* draft; int32_t dtype;
     int64_t target_ld, draft_ld;
     const int32_t* tokens; const int32_t* parent; const int32_t* n_nodes;
-    const uint8_t* used;               // [B, N] contexts with children (tree_prepare_kernel)
     uint64_t seed; uint32_t level; int64_t seq_base;
     int32_t B, N, V, ntiles;
     float temperature, tau;
     int32_t* out_accept_len; int32_t* out_path; int32_t* out_next_token; float* out_entropy;
 };
 bool tree_supported(int32_t N, int32_t V, int dtype);
-hipError_t launch_tree_prepare(const int32_t* parent, const int32_t* n_nodes, int32_t B, int32_t N, uint8_t* used, hipStream_t s);
 hipError_t launch_tree_tail(const TreeParams& p, const Partial* partials, int nparts, int waves, hipStream_t s);
 
 hipError_t launch_fused(const FusedParams& p, const Tuning& t, hipStream_t s);

@@ -43,7 +43,11 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(RowStatsParams p)
     int len = p.draft_len ? p.draft_len[b] : g;
     len = len < 0 ? 0 : (len > g ? g : len);
     if (is_draft ? (j >= len) : (p.literal ? (j >= len) : (j > len))) return;   // row not needed (uniform exit)
-    if (is_draft && p.draft_used && !p.draft_used[(int64_t)b * g + j]) return;  // a tree context without children
+    if (is_draft && p.tree_parent) {                             // token trees: context j needs a child among the nodes
+        const int n = threadIdx.x & 63;                          // (node n hangs under context parent[n] + 1, n >= j)
+        const bool child = n >= j && n < len && p.tree_parent[(int64_t)b * g + n] == j - 1;
+        if (!__ballot(child)) return;                            // the same answer in every wavefront
+    }
 
     const float Tb = p.row_temperature ? p.row_temperature[b] : p.temperature;
     const bool greedy = !(Tb > 0.f);

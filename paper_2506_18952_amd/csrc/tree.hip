@@ -2,7 +2,7 @@
 //
 // Rows are laid out as in the one-token step with gamma = N nodes: draft row c and target row c belong to context c
 // (0: the prefix, n + 1: the prefix followed by the path to node n), so the split-row statistics kernel serves
-// unchanged; only draft rows of contexts without children are masked out of it (tree_prepare_kernel).
+// unchanged; only the draft rows of contexts without children leave it at once (it looks the children up itself).
 //
 // tree_tail_kernel, one workgroup per sequence: merges the row partials, gathers the two logits of every node's
 // token in one go, then walks from the prefix.  The children of a context are tried in node order by the recursive
@@ -21,35 +21,13 @@ namespace hola {
 
 constexpr int kTreeMaxTiles = 2048;
 
-// used[b, c] = 1 iff context c < N of sequence b has a child among its first len nodes.  A node whose parent is
-// not -1 or an earlier node is no one's child.
-__global__ __launch_bounds__(64) void tree_prepare_kernel(const int32_t* __restrict__ parent, const int32_t* __restrict__ n_nodes,
-                                                          int32_t N, uint8_t* __restrict__ used)
-{
-    const int b = blockIdx.x, n = threadIdx.x;
-    int len = n_nodes ? n_nodes[b] : N;
-    len = len < 0 ? 0 : (len > N ? N : len);
-    int ctx = -1;
-    if (n < len) {
-        const int32_t pr = parent[(int64_t)b * N + n];
-        if (pr >= -1 && pr < n) ctx = pr + 1;
-    }
-    __shared__ int s_ctx[64];
-    s_ctx[n] = ctx;
-    __syncthreads();
-    if (n < N) {
-        int any = 0;
-        for (int m = n; m < len; ++m) any |= (s_ctx[m] == n) ? 1 : 0;   // children come after their parent
-        used[(int64_t)b * N + n] = (uint8_t)any;
-    }
-}
-
 struct TreeShared {
     RowStat stat[2 * HOLA_MAX_GAMMA + 1];      // draft contexts 0..N-1, target contexts N..2N
     double tiles[kTreeMaxTiles];
     double px[64], qx[64], u[64];              // per node: the two probabilities of its token, its test uniform
     int32_t path[64];                          // kept nodes, from the prefix on
     int32_t ctx_of[64];                        // per node: the context it hangs under, -1: no node
+    int32_t used[64];                          // per context: it has a child
     // the walk's state between rounds
     int32_t w_ctx, w_depth, w_first, w_dead;
     double w_C, w_Z;
@@ -83,7 +61,21 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
     int len = p.n_nodes ? p.n_nodes[b] : N;
     len = len < 0 ? 0 : (len > N ? N : len);
     const float Tb = p.temperature;
-    const uint8_t* used = p.used + (int64_t)b * N;
+
+    // ---- every node's context; contexts with children (a node whose parent is not -1 or an earlier node hangs
+    // under none)
+    if (tid < 64) sh.used[tid] = 0;
+    __syncthreads();
+    if (wave == 0) {
+        int c = -1;
+        if (lane < len) {
+            const int32_t pr = p.parent[(int64_t)b * N + lane];
+            if (pr >= -1 && pr < lane) c = pr + 1;
+        }
+        sh.ctx_of[lane] = c;
+        if (c >= 0) sh.used[c] = 1;                              // the same value from every child
+    }
+    __syncthreads();
 
     // ---- row statistics from the split-row partials: `width` lanes per row, 64 / width rows per wavefront
     int width = 4;
@@ -93,7 +85,7 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
         const int r = r0 + seg;
         const bool is_draft = r < N;
         const int c = is_draft ? r : r - N;
-        const bool need = r < 2 * N + 1 && (is_draft ? (c < len && used[c]) : (c <= len));
+        const bool need = r < 2 * N + 1 && (is_draft ? (c < len && sh.used[c]) : (c <= len));
         const int64_t slot = is_draft ? (int64_t)b * N + c : (int64_t)p.B * N + (int64_t)b * (N + 1) + c;
         const RowStat s = merge_partials_seg(need ? partials + slot * nparts : nullptr, nparts, sl, width);
         if (need && sl == 0) sh.stat[r] = s;
@@ -106,10 +98,7 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
         const uint64_t seq = (uint64_t)(p.seq_base + b);
         const int n = lane;
         double p_x = 0.0, q_x = 1.0, un = 0.0;
-        if (n < len) {
-            const int32_t pr = p.parent[(int64_t)b * N + n];
-            if (pr >= -1 && pr < n) my_ctx = pr + 1;
-        }
+        my_ctx = sh.ctx_of[n];
         if (my_ctx >= 0) {
             const int32_t x = p.tokens[(int64_t)b * N + n];
             if (x >= 0 && x < p.V) {
@@ -124,7 +113,7 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
             un = (double)u24(r.x);
         }
         sh.px[n] = p_x; sh.qx[n] = q_x; sh.u[n] = un;
-        if (p.out_entropy && n < N) p.out_entropy[(int64_t)b * N + n] = (n < len && used[n]) ? (float)sh.stat[n].H : -1.0f;
+        if (p.out_entropy && n < N) p.out_entropy[(int64_t)b * N + n] = (n < len && sh.used[n]) ? (float)sh.stat[n].H : -1.0f;
         if (lane == 0) sh.done = 0;
     }
     __builtin_amdgcn_wave_barrier();
@@ -132,7 +121,6 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
     // ---- the walk (wavefront 0, every lane the same values) and the row sweeps it asks for (all wavefronts).
     // Between rounds the walk's state rests in shared memory, so that no register holds it during a sweep.
     if (wave == 0) {
-        sh.ctx_of[lane] = my_ctx;
         const unsigned long long k0 = __ballot(my_ctx == 0);    // the children of the prefix
         if (lane == 0) {
             sh.w_ctx = 0; sh.w_depth = 0; sh.w_first = 1; sh.w_dead = 0; sh.w_C = 0.0; sh.w_Z = 1.0;
@@ -244,13 +232,6 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
 bool tree_supported(int32_t N, int32_t V, int dtype)
 {
     return N >= 1 && N <= HOLA_MAX_GAMMA && sampler_tiles(V, dtype) <= kTreeMaxTiles;
-}
-
-hipError_t launch_tree_prepare(const int32_t* parent, const int32_t* n_nodes, int32_t B, int32_t N, uint8_t* used, hipStream_t s)
-{
-    if (B <= 0) return hipSuccess;
-    hipLaunchKernelGGL(tree_prepare_kernel, dim3((unsigned)B), dim3(64), 0, s, parent, n_nodes, N, used);
-    return hipGetLastError();
 }
 
 hipError_t launch_tree_tail(const TreeParams& p, const Partial* partials, int nparts, int waves, hipStream_t s)
