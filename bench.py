@@ -118,7 +118,9 @@ def bench_tree(args) -> int:
         "stage_ms": {hb.STAGE_NAMES[i]: round(stage_ms[i] / stage_n[i], 5) for i in range(hb.HOLA_N_STAGES) if stage_n[i]},
         "per_threshold": per_tau,
         "roofline": {"bound": "hbm", "kernel": "row_stats_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     # measured for this one shape only (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, see profiles/)
+                     "traffic": 1971660000 if (B == 256 and widths == [4, 4, 4, 2, 2]) else None,
                      "algorithmic_bytes_per_launch": int(k_bytes), "avg_launch_ms": round(k_ms, 5)},
     }
     if not args.no_cpu:
