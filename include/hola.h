@@ -19,6 +19,10 @@
  *      position; when all drafts were kept, a bonus token drawn from p at position len;
  *   7. "Hierarchical": the kept tokens plus the next token of one level are the drafts of
  *      the next level, verified by the next larger model (hola_hsd_verify).
+ * Beyond the paper's step, declared further down with their own definitions: top-k / top-p filtered
+ * distributions (hola_verify_args.top_k / top_p), Equation (1) taken literally (hola_verify_literal_ex),
+ * several drafted candidates per position (hola_verify_tree), statistics by column tiles (hola_tile_stats,
+ * hola_merge_tile_stats).
  *
  * Uniforms: Philox4x32-10 with key = (seed low, seed high) and counter =
  * (position, sequence low, sequence high, level), sequence = seq_base + b; output word 0
@@ -45,7 +49,7 @@
  * (or otherwise ordered).
  *
  * Errors.  Return codes only.  Argument errors (a required pointer NULL, B < 0, gamma < 1 or
- * > 32, V < 1, a negative or NaN temperature, NaN tau, a leading dimension < V, a logits
+ * > HOLA_MAX_GAMMA, V < 1, a negative or NaN temperature, NaN tau, a leading dimension < V, a logits
  * pointer not aligned to its element size, a workspace that is too small or not 256-byte
  * aligned) are detected on the host before any launch and leave the outputs untouched.
  * HIP launch or allocation failures return HOLA_ERR_HIP; hola_last_hip_error() names the last
