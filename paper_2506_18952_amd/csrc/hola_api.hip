@@ -557,7 +557,8 @@ hola_status hola_hsd_verify_ex(const hola_hsd_args* args)
 size_t hola_tree_workspace_bytes(int32_t B, int32_t N, int32_t V)
 {
     if (!shape_ok(B, N, V)) return 0;
-    return carve(nullptr, B, N, V).bytes + 256;
+    // the wavefront partials of the N draft and N + 1 target rows of every sequence; nothing else
+    return align_up((size_t)B * (2 * (size_t)N + 1) * kMaxSplit * kWaves * sizeof(Partial)) + 256;
 }
 
 hola_status hola_verify_tree(const hola_tree_args* args)
@@ -579,7 +580,7 @@ hola_status hola_verify_tree(const hola_tree_args* args)
     if (a.workspace_bytes < hola_tree_workspace_bytes(a.B, a.N, a.V)) return HOLA_ERR_WORKSPACE;
 
     hipStream_t s = (hipStream_t)a.stream;
-    const Workspace w = carve(a.workspace, a.B, a.N, a.V);
+    Partial* partials = (Partial*)a.workspace;
     const int64_t tld = a.target_ld ? a.target_ld : a.V, dld = a.draft_ld ? a.draft_ld : a.V;
     Tuning tune;
     { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
@@ -593,7 +594,7 @@ hola_status hola_verify_tree(const hola_tree_args* args)
     rs.B = a.B; rs.gamma = a.N; rs.V = a.V; rs.nsplit = nsplit;
     rs.lse_only_targets = 1;                                    // only the drafts' entropy gates
     rs.tree_parent = a.node_parent;                             // draft rows of childless contexts are not read
-    rs.partials = w.partials;
+    rs.partials = partials;
     { StageTimer t(0, s); e = launch_row_stats(rs, a.dtype, tune, s); }
     if (e != hipSuccess) return hip_fail(e, "row statistics launch");
 
@@ -606,7 +607,7 @@ hola_status hola_verify_tree(const hola_tree_args* args)
     tp.out_accept_len = a.out_accept_len; tp.out_path = a.out_path; tp.out_next_token = a.out_next_token;
     tp.out_entropy = a.out_entropy;
     const int waves = tune.fused_waves ? tune.fused_waves : (a.B <= device_cu_count() ? 16 : 8);
-    { StageTimer t(6, s); e = launch_tree_tail(tp, w.partials, nsplit * kWaves, waves, s); }
+    { StageTimer t(6, s); e = launch_tree_tail(tp, partials, nsplit * kWaves, waves, s); }
     if (e != hipSuccess) return hip_fail(e, "tree tail launch");
     return HOLA_OK;
 }

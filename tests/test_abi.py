@@ -92,6 +92,55 @@ def test_verify_ex_argument_errors(kw, want):
     assert hb.lib().hola_verify_ex(C.byref(a)) == want
 
 
+def _tree_args(**kw):
+    a = hb.TreeArgs()
+    fake = 0x1000
+    a.target_logits = a.draft_logits = a.node_token = a.node_parent = fake
+    a.out_accept_len = a.out_next_token = fake
+    a.dtype, a.B, a.N, a.V = hb.HOLA_DTYPE_BF16, 4, 6, 100
+    a.temperature, a.entropy_threshold = 1.0, 2.0
+    a.workspace, a.workspace_bytes = 0x10000, 1 << 30
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(B=-1), hb.HOLA_ERR_INVALID_ARG),
+    (dict(N=0), hb.HOLA_ERR_INVALID_ARG),
+    (dict(N=64), hb.HOLA_ERR_INVALID_ARG),
+    (dict(V=0), hb.HOLA_ERR_INVALID_ARG),
+    (dict(dtype=3), hb.HOLA_ERR_UNSUPPORTED),
+    (dict(target_logits=None), hb.HOLA_ERR_INVALID_ARG),
+    (dict(draft_logits=None), hb.HOLA_ERR_INVALID_ARG),
+    (dict(node_token=None), hb.HOLA_ERR_INVALID_ARG),
+    (dict(node_parent=None), hb.HOLA_ERR_INVALID_ARG),
+    (dict(out_accept_len=None), hb.HOLA_ERR_INVALID_ARG),
+    (dict(out_next_token=None), hb.HOLA_ERR_INVALID_ARG),
+    (dict(draft_logits=0x1001), hb.HOLA_ERR_INVALID_ARG),
+    (dict(target_ld=99), hb.HOLA_ERR_INVALID_ARG),
+    (dict(temperature=float("nan")), hb.HOLA_ERR_INVALID_ARG),
+    (dict(temperature=-1.0), hb.HOLA_ERR_INVALID_ARG),
+    (dict(temperature=0.0), hb.HOLA_ERR_UNSUPPORTED),         # greedy rows are not taken on trees
+    (dict(entropy_threshold=float("nan")), hb.HOLA_ERR_INVALID_ARG),
+    (dict(V=1 << 23, dtype=hb.HOLA_DTYPE_F32), hb.HOLA_ERR_UNSUPPORTED),   # more sampler tiles than the tail kernel holds
+    (dict(workspace=None), hb.HOLA_ERR_WORKSPACE),
+    (dict(workspace=0x10040), hb.HOLA_ERR_WORKSPACE),
+    (dict(workspace_bytes=4096), hb.HOLA_ERR_WORKSPACE),
+    (dict(B=0), hb.HOLA_OK),
+])
+def test_verify_tree_argument_errors(kw, want):
+    a = _tree_args(**kw)
+    assert hb.lib().hola_verify_tree(C.byref(a)) == want
+    assert hb.lib().hola_verify_tree(None) == hb.HOLA_ERR_INVALID_ARG
+
+
+def test_tree_workspace_bytes():
+    assert hb.hola_tree_workspace_bytes(4, 0, 100) == 0 and hb.hola_tree_workspace_bytes(4, 64, 100) == 0
+    assert 0 < hb.hola_tree_workspace_bytes(4, 63, 100) <= hb.hola_workspace_bytes(4, 63, 100)
+    assert hb.hola_tree_workspace_bytes(256, 16, 128256) < 20 << 20      # the row partials alone
+
+
 def test_null_args_and_short_forms():
     L = hb.lib()
     assert L.hola_verify_ex(None) == hb.HOLA_ERR_INVALID_ARG
