@@ -419,3 +419,27 @@ def test_chain_with_filters_refuses_row_temperature():
     with pytest.raises(hb.HolaError):
         hb.hola_hsd_verify_ex(ms, to_dev(w.tokens), 1, B, g, V, 1.0, w.taus, out_tok, acc, nxt, None, ws,
                               row_temperature=rt, top_k=5)
+
+
+def test_two_level_chain_with_filters_survivors_only():
+    """The kept-tokens-only reading of the hierarchy with filters on: the driver's last level equals a stand-alone
+    filtered level on what the first level kept."""
+    w = wl.config4(B=16, V=20011, gamma=4)
+    ms = [to_dev(m) for m in w.models]
+    B, g, V = w.models[0].shape
+    out_tok = torch.full((B, g + 2), -7, dtype=torch.int32, device=DEV)
+    acc = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    nxt = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    ws = hb.alloc_workspace(hb.hola_hsd_workspace_bytes(3, B, g, V), DEV)
+    hb.hola_hsd_verify_ex(ms, to_dev(w.tokens), w.seed, B, g, V, w.temperature, [0.0, w.taus[1]], out_tok, acc, nxt, None,
+                          ws, survivors_only=True, top_k=30, top_p=0.9)
+    torch.cuda.synchronize()
+    a1, n1, _, _ = run_filtered(w.models[1], w.models[0], w.tokens, w.seed, w.temperature, 0.0, 30, 0.9, level=0)
+    tok2 = np.full((B, g + 1), -1, np.int32)
+    for b in range(B):
+        tok2[b, :a1[b]] = w.tokens[b, :a1[b]]
+    got = run_filtered(w.models[2], w.models[1], tok2, w.seed, w.temperature, w.taus[1], 30, 0.9, draft_len=a1, level=1)
+    compare_filtered(w.models[2], w.models[1], tok2, w.seed, w.temperature, w.taus[1], 30, 0.9, got, draft_len=a1, level=1)
+    np.testing.assert_array_equal(acc.cpu().numpy(), got[0])
+    np.testing.assert_array_equal(nxt.cpu().numpy(), got[1])
+    np.testing.assert_array_equal(out_tok.cpu().numpy()[:, :g + 1], tok2)

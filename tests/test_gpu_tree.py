@@ -276,3 +276,19 @@ def test_more_sequences_than_compute_units_and_strided_rows():
     np.testing.assert_array_equal(path.cpu().numpy(), got[1][:B])
     np.testing.assert_array_equal(nxt.cpu().numpy(), got[2][:B])
     np.testing.assert_allclose(ent.cpu().numpy(), got[3][:B], rtol=1e-5, atol=1e-6)
+
+
+def test_empty_batch_and_single_node():
+    w = wl.tree_case(2, [1], 129, dtype="f32", case_id=798)
+    P, D = to_dev(w.target), to_dev(w.draft)
+    acc = torch.full((2,), -7, dtype=torch.int32, device=DEV)
+    nxt = torch.full((2,), -7, dtype=torch.int32, device=DEV)
+    ws = hb.alloc_workspace(hb.hola_tree_workspace_bytes(2, 1, w.V), DEV)
+    hb.hola_verify_tree(P, D, to_dev(w.node_token), to_dev(w.node_parent), w.seed, 0, 1, w.V, 1.0, 0.0, acc, nxt, ws)
+    torch.cuda.synchronize()
+    assert np.all(acc.cpu().numpy() == -7) and np.all(nxt.cpu().numpy() == -7)     # B = 0: nothing is written
+    got = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, 1.0, 0.0)
+    compare_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, 1.0, 0.0, got, max_listed=2)
+    one = run_gpu_level(w.target, w.draft, w.node_token, w.seed, 1.0, 0.0)          # one node = one drafted position
+    np.testing.assert_array_equal(got[0], one.accept_len)
+    np.testing.assert_array_equal(got[2], one.next_token)
