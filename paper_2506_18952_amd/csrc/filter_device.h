@@ -78,4 +78,31 @@ __device__ __forceinline__ FilterRow make_filter_row(const void* target, const v
     return fr;
 }
 
+// Sum over the wavefront of a 64-bit integer, the same value in every lane.  Four data-parallel-primitive steps
+// (lane ^ 1, lane ^ 2, reversal within 8, reversal within 16) leave each lane with the sum of its row of 16
+// lanes; the four row sums are read into scalars and added there.  An order of magnitude less latency than six
+// cross-lane permutes through the LDS crossbar, which matters where a radix descent needs one sum per key bit.
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
+{
+#define HOLA_DPP_STEP(ctrl)                                                                                       \
+    {                                                                                                             \
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, ctrl, 0xf, 0xf, true);     \
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), ctrl, 0xf, 0xf, true); \
+        v += ((unsigned long long)hi << 32) | lo;                                                                 \
+    }
+    HOLA_DPP_STEP(0xb1)                                         // quad_perm [1,0,3,2]
+    HOLA_DPP_STEP(0x4e)                                         // quad_perm [2,3,0,1]
+    HOLA_DPP_STEP(0x141)                                        // row_half_mirror
+    HOLA_DPP_STEP(0x140)                                        // row_mirror
+#undef HOLA_DPP_STEP
+    unsigned long long total = 0;
+#pragma unroll
+    for (int row = 0; row < 4; ++row) {
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, 16 * row);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), 16 * row);
+        total += ((unsigned long long)hi << 32) | lo;
+    }
+    return total;
+}
+
 }  // namespace hola

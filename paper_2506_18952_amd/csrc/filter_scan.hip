@@ -65,7 +65,6 @@ struct ScanParams {
     unsigned long long* cand;          // [rows, nseg, cap_seg]
     SegInfo* segs;                     // [rows, nseg]
     int32_t* flags;                    // [rows]: 1 = left to the per-row kernel
-    unsigned long long* kept;          // [rows, kKeptList]: the keep set itself, (key << 32 | index), when it is that short
     int32_t* kept_n;                   // [rows]: its length, -1 when not written
     RowFilter* filters;
     int32_t* out_keep_count;
@@ -90,33 +89,6 @@ __device__ __forceinline__ uint32_t wave_select_by_count(const T (&ent)[E], int 
         else need -= cnt;
     }
     return prefix;
-}
-
-// Sum over the wavefront of a 64-bit integer, the same value in every lane.  Four data-parallel-primitive steps
-// (lane ^ 1, lane ^ 2, reversal within 8, reversal within 16) leave each lane with the sum of its row of 16
-// lanes; the four row sums are read into scalars and added there.  An order of magnitude less latency than six
-// cross-lane permutes through the LDS crossbar, which matters where a radix descent needs one sum per key bit.
-__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
-{
-#define HOLA_DPP_STEP(ctrl)                                                                                       \
-    {                                                                                                             \
-        const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, ctrl, 0xf, 0xf, true);     \
-        const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), ctrl, 0xf, 0xf, true); \
-        v += ((unsigned long long)hi << 32) | lo;                                                                 \
-    }
-    HOLA_DPP_STEP(0xb1)                                         // quad_perm [1,0,3,2]
-    HOLA_DPP_STEP(0x4e)                                         // quad_perm [2,3,0,1]
-    HOLA_DPP_STEP(0x141)                                        // row_half_mirror
-    HOLA_DPP_STEP(0x140)                                        // row_mirror
-#undef HOLA_DPP_STEP
-    unsigned long long total = 0;
-#pragma unroll
-    for (int row = 0; row < 4; ++row) {
-        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, 16 * row);
-        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), 16 * row);
-        total += ((unsigned long long)hi << 32) | lo;
-    }
-    return total;
 }
 
 // Signed 16-bit order keys of two packed bf16 logits (larger logit, larger key; -0 one below +0).
@@ -831,7 +803,8 @@ __global__ __launch_bounds__(64, E > kScanSlots ? 2 : ((WANT_K && WANT_P) ? 4 : 
     // ---- a short keep set of a target row is written out itself: the sampler then needs no sweep of the row
     const long long n_keep = have_cut ? (long long)cnt_above + (long long)r_keep : -1;
     if (!id.is_draft && n_keep >= 1 && n_keep <= kKeptList) {
-        unsigned long long* kl = p.kept + (int64_t)r * kKeptList;
+        // (into the row's own candidate area: every entry of it has been in registers since the start)
+        unsigned long long* kl = p.cand + (int64_t)r * p.nseg * p.cap_seg;
         int nk = 0;
 #pragma unroll
         for (int j = 0; j < E; ++j) {
@@ -876,7 +849,7 @@ size_t filter_scan_bytes(int64_t rows)
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     if (rows <= 0 || (size_t)rows * kScanStore * sizeof(unsigned long long) > ((size_t)256 << 20)) return 0;
     return up((size_t)rows * kScanStore * sizeof(unsigned long long)) + 2 * up((size_t)rows * sizeof(int32_t)) +
-           up((size_t)rows * kKeptList * sizeof(unsigned long long)) + up((size_t)rows * kScanMaxSeg * sizeof(SegInfo));
+           up((size_t)rows * kScanMaxSeg * sizeof(SegInfo));
 }
 
 // Entries per lane the decide step needs for this call (0: the scan + decide pair is not worth running).  A segment
@@ -921,7 +894,6 @@ static ScanParams scan_params(const void* target, const void* draft, int dtype, 
     p.cand = (unsigned long long*)(base + off); off += up((size_t)rows * kScanStore * sizeof(unsigned long long));
     p.flags = (int32_t*)(base + off);           off += up((size_t)rows * sizeof(int32_t));
     p.kept_n = (int32_t*)(base + off);          off += up((size_t)rows * sizeof(int32_t));
-    p.kept = (unsigned long long*)(base + off); off += up((size_t)rows * kKeptList * sizeof(unsigned long long));
     p.segs = (SegInfo*)(base + off);
     return p;
 }
@@ -948,12 +920,14 @@ hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, 
 hipError_t launch_filter_decide(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                                 const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
                                 int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch,
-                                int32_t** flags_out, const unsigned long long** kept_out, const int32_t** kept_n_out, hipStream_t s)
+                                int32_t** flags_out, const unsigned long long** kept_out, int64_t* kept_stride_out,
+                                const int32_t** kept_n_out, hipStream_t s)
 {
     const ScanParams p = scan_params(target, draft, dtype, target_ld, draft_ld, draft_len, temperature, B, gamma, V, top_k, top_p,
                                      filters, out_keep_count, scratch);
     *flags_out = p.flags;
-    *kept_out = p.kept;
+    *kept_out = p.cand;                                         // a short keep set replaces the row's candidates
+    *kept_stride_out = (int64_t)p.nseg * p.cap_seg;
     *kept_n_out = p.kept_n;
     const int64_t rows = (int64_t)B * (2 * gamma + 1);
     const bool want_k = top_k > 0 && top_k < V, want_p = top_p > 0.f && top_p < 1.f;

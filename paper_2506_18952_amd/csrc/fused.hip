@@ -28,84 +28,82 @@ struct SeqShared {
     int64_t slab_lo, slab_hi;
     double slab_u;
     int32_t slab_ok;
-    // draw from a keep set handed over as a list (filtered calls): indices and weights, put in index order
-    int32_t list_idx[kKeptListMax];
-    int32_t list_tok[kKeptListMax];
-    double list_w[kKeptListMax];
 };
 
 // Next token of a filtered stop row whose keep set (at most kKeptListMax tokens) is at hand as a list of
-// (order key << 32 | index): the weights of these tokens alone, by the sampler's own element formula, summed in
-// index order as the row sweep would (every other token has weight 0).  One wavefront, four entries per lane.
+// (order key << 32 | index): the weights of these tokens alone, by the sampler's own element formula (every other
+// token has weight 0).  The draw is the inverse CDF in index order, found without putting the list in order: the
+// weights become integers in fixed point (2^60 for the total, so sums are exact and the same in any order) and the
+// index of the token is built bit by bit, each bit from one sum over the wavefront of the weights that lie below
+// the half of the index range in question.  One wavefront, up to 16 entries per lane.
 // Returns the token, -1 if the weights carry no mass, or -2 if the caller should draw from the target's
 // distribution itself (residual without mass).
-template <bool BF16>
-__device__ __forceinline__ int32_t sample_kept_list(const RowPair& rp, const unsigned long long* kept, int nk, double u, int lane,
-                                                    SeqShared& sh)
+template <bool BF16, int KL>
+__device__ __forceinline__ int32_t sample_kept_list_n(const RowPair& rp, const unsigned long long* kept, int nk, double u, int lane)
 {
-    constexpr int KL = kKeptListMax / 64;
-    int32_t idx[KL];
+    const int nslots = (nk + 63) / 64;
+    uint32_t idx[KL];
     float wk[KL];
+    double mine = 0.0;
 #pragma unroll
     for (int j = 0; j < KL; ++j) {
-        const int i = j * 64 + lane;
-        idx[j] = 0x7fffffff;
+        idx[j] = 0xffffffffu;
         wk[j] = 0.f;
-        if (i < nk) {
+        const int i = j * 64 + lane;
+        if (j < nslots && i < nk) {
             const unsigned long long ent = kept[i];
-            idx[j] = (int32_t)(uint32_t)(ent & 0xffffffffu);
+            idx[j] = (uint32_t)(ent & 0xffffffffu);
             const float xp = key_to_logit<BF16>((uint32_t)(ent >> 32));
             const float ep = fast_exp2(exp_arg<BF16>(xp, rp.refP, rp.sc));
             if (rp.bonus) {
                 wk[j] = fmaxf(ep, 0.f);
             } else {
-                const float xd = load_logit<BF16>(rp.D, idx[j]);
+                const float xd = load_logit<BF16>(rp.D, (int32_t)idx[j]);
                 float eq = fast_exp2(exp_arg<BF16>(xd, rp.refQ, rp.sc));
-                if (!(xd > rp.thQ || (xd == rp.thQ && idx[j] <= rp.cutQ))) eq = 0.f;   // outside the draft's keep set
+                if (!(xd > rp.thQ || (xd == rp.thQ && (int32_t)idx[j] <= rp.cutQ))) eq = 0.f;   // outside the draft's keep set
                 wk[j] = fmaxf(0.f, __builtin_fmaf(-rp.k_lo, eq, __builtin_fmaf(-rp.k_hi, eq, ep)));
             }
+            mine += (double)wk[j];
         }
-        sh.list_idx[i] = idx[j];
     }
-    __builtin_amdgcn_wave_barrier();
-    // place in index order = number of listed tokens with a smaller index
-    int rank[KL];
-#pragma unroll
-    for (int j = 0; j < KL; ++j) rank[j] = 0;
-    for (int q = 0; q < nk; ++q) {
-        const int32_t o = sh.list_idx[q];
-#pragma unroll
-        for (int j = 0; j < KL; ++j) rank[j] += o < idx[j] ? 1 : 0;
-    }
-#pragma unroll
-    for (int j = 0; j < KL; ++j)
-        if (j * 64 + lane < nk) { sh.list_w[rank[j]] = (double)wk[j] * rp.scale; sh.list_tok[rank[j]] = idx[j]; }
-    __builtin_amdgcn_wave_barrier();
-    // lane l holds places KL l .. KL l + KL - 1
-    double v[KL], mine = 0.0;
-#pragma unroll
-    for (int j = 0; j < KL; ++j) { const int i = lane * KL + j; v[j] = i < nk ? sh.list_w[i] : 0.0; mine += v[j]; }
-    const double incl = wave_inclusive_scan(mine, lane);
-    const double Z = __shfl(incl, 63, 64);
+    const double Zs = wave_sum(mine);                            // in the weights' own unit (the common factor left out)
+    const double Z = Zs * rp.scale;
     if (!(Z > 0.0) || !(Z - Z == 0.0)) return rp.bonus ? -1 : -2;
-    const double target = u * Z;
-    const unsigned long long hit = __ballot(incl > target);
-    const unsigned long long haveW = __ballot(mine > 0.0);
-    if (!haveW) return -1;
-    const int src = hit ? (__ffsll((long long)hit) - 1) : (63 - __clzll((long long)haveW));   // rounding at the top end: the last weight
-    int32_t tok = -1;
-    if (lane == src) {
-        double run = incl - mine;
-        int last = -1;
+    const double unit = 1152921504606846976.0 / Zs;              // 2^60 for the whole list
+    unsigned long long fx[KL], fsum = 0ull;
 #pragma unroll
-        for (int j = 0; j < KL; ++j) {
-            if (v[j] > 0.0) last = j;
-            run += v[j];
-            if (tok < 0 && hit && run > target) tok = sh.list_tok[lane * KL + j];
-        }
-        if (tok < 0 && last >= 0) tok = sh.list_tok[lane * KL + last];
+    for (int j = 0; j < KL; ++j) {
+        fx[j] = (j < nslots) ? (unsigned long long)((double)wk[j] * unit) : 0ull;
+        fsum += fx[j];
     }
-    return __shfl(tok, src, 64);
+    const unsigned long long total = wave_sum_u64(fsum);
+    if (total == 0ull) return -1;
+    unsigned long long target = (unsigned long long)(u * (double)total);
+    if (target >= total) target = total - 1;                     // u < 1: the draw lies inside the mass
+    // smallest index x with (sum of the weights at indices <= x) > target
+    int vbits = 0;
+    while (vbits < 31 && ((int64_t)1 << vbits) < (int64_t)rp.V) ++vbits;
+    uint32_t prefix = 0;
+    unsigned long long below = 0ull;                             // mass at indices < prefix
+    for (int bit = vbits - 1; bit >= 0; --bit) {
+        const uint32_t want = prefix >> bit;                     // the half with this bit clear
+        unsigned long long s0 = 0ull;
+#pragma unroll
+        for (int j = 0; j < KL; ++j)
+            if (j < nslots && (idx[j] >> bit) == want) s0 += fx[j];
+        s0 = wave_sum_u64(s0);
+        if (below + s0 <= target) { below += s0; prefix |= 1u << bit; }
+    }
+    return (int32_t)prefix;
+}
+
+// Lists of up to 64, 256 and kKeptListMax tokens, each with as many entries per lane as it needs.
+template <bool BF16>
+__device__ __forceinline__ int32_t sample_kept_list(const RowPair& rp, const unsigned long long* kept, int nk, double u, int lane)
+{
+    if (nk <= 64) return sample_kept_list_n<BF16, 1>(rp, kept, nk, u, lane);
+    if (nk <= 256) return sample_kept_list_n<BF16, 4>(rp, kept, nk, u, lane);
+    return sample_kept_list_n<BF16, kKeptListMax / 64>(rp, kept, nk, u, lane);
 }
 
 __device__ __forceinline__ AcceptCtx accept_ctx(const FusedParams& p)
@@ -225,7 +223,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
     if (FILT && p.kept != nullptr && rp.ok) {
         const int64_t rid = (int64_t)b * (2 * g + 1) + g + si.row;
         list_n = p.kept_n[rid];
-        list = p.kept + rid * kKeptListMax;
+        list = p.kept + rid * p.kept_stride;
         if (list_n < 1 || list_n > kKeptListMax) list_n = 0;
     }
 
@@ -233,7 +231,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
     for (int attempt = 0; attempt < 3; ++attempt) {
         if (FILT && list_n > 0) {
             if (wave == 0) {
-                const int32_t tk = sample_kept_list<BF16>(rp, list, list_n, u_eff, lane, sh);
+                const int32_t tk = sample_kept_list<BF16>(rp, list, list_n, u_eff, lane);
                 if (lane == 0) sh.tok = tk;
             }
             __syncthreads();

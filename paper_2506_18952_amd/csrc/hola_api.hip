@@ -246,7 +246,7 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
             { StageTimer t(9, s);
               e = launch_filter_decide(a.target_logits, a.draft_logits, a.dtype, tld, dld, a.draft_len, a.temperature, a.B, a.gamma,
                                        a.V, a.top_k, top_p, w.filters, a.out_keep_count, w.filter_scan, &flags, &fp.kept,
-                                       &fp.kept_n, s); }
+                                       &fp.kept_stride, &fp.kept_n, s); }
             if (e != hipSuccess) return hip_fail(e, "filter decide launch");
         }
         { StageTimer t(7, s);

@@ -10,7 +10,7 @@ constexpr int kWaves = 4;              // wavefronts per workgroup in the stream
 constexpr int kBlock = 64 * kWaves;    // 256 threads
 constexpr int kMaxSplit = 16;          // workgroups per row, upper bound (sizes the partials)
 constexpr int kTileChunks = 4;         // 16-byte chunks per lane in one sampler tile
-constexpr int kKeptListMax = 256;      // longest top-k / top-p keep set handed from the filter to the sampler as a list
+constexpr int kKeptListMax = 1024;     // longest top-k / top-p keep set handed from the filter to the sampler as a list
 
 // One wavefront's share of a row: the sums are S = sum 2^(x*c + bref), T = sum (x*c + bref) 2^(x*c + bref)
 // with c = log2(e)/T and bref an integer-valued reference chosen so the largest term is O(1).
@@ -125,9 +125,9 @@ struct FusedParams {
     int32_t* glue_tok; int32_t* glue_len; int64_t glue_ld;
     int32_t glue_keep_next;            // 1: append the next token; 0: the kept tokens only
     const RowFilter* filters;          // top-k / top-p keep sets (slots as the partials), or null
-    // short keep sets written out as lists of (order key << 32 | index), kKeptListMax entries per row r = b (2 gamma + 1) + k,
-    // and their lengths (-1: no list); null when the filter's scan did not run
-    const unsigned long long* kept; const int32_t* kept_n;
+    // short keep sets written out as lists of (order key << 32 | index), at most kKeptListMax entries, kept_stride
+    // apart, for row r = b (2 gamma + 1) + k, and their lengths (-1: no list); null when the filter's scan did not run
+    const unsigned long long* kept; const int32_t* kept_n; int64_t kept_stride;
 };
 
 // Token trees: N nodes per sequence, rows by context as the one-token step lays them out with gamma = N.
@@ -167,8 +167,8 @@ hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, 
 hipError_t launch_filter_decide(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                                 const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
                                 int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch,
-                                int32_t** flags_out, const unsigned long long** kept_out, const int32_t** kept_n_out,
-                                hipStream_t s);
+                                int32_t** flags_out, const unsigned long long** kept_out, int64_t* kept_stride_out,
+                                const int32_t** kept_n_out, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
 hipError_t launch_merge_tile_stats(const double* ts, int32_t R, int32_t nt, double* out, hipStream_t s);
 hipError_t launch_finalize_rows(const Partial* partials, int nparts, int32_t R, double* out, hipStream_t s);
