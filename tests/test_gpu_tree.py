@@ -246,7 +246,7 @@ def test_tree_call_in_a_hip_graph():
 def test_more_sequences_than_compute_units_and_strided_rows():
     """Beyond one sequence per compute unit the tail kernel runs 8 wavefronts per workgroup; rows may sit in wider
     buffers (row strides above V, rows not 16-byte aligned)."""
-    w = wl.tree_case(300, [3, 2, 2], 1003, dtype="bf16", temperature=0.9, draft_sigma=1.2, case_id=797)
+    w = wl.tree_case(2100, [3, 2, 2], 1003, dtype="bf16", temperature=0.9, draft_sigma=1.2, case_id=797)
     got = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, -1.0)
     compare_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, -1.0, got)
     hb.hola_set_tuning(fused_waves=8)
