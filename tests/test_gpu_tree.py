@@ -292,3 +292,18 @@ def test_empty_batch_and_single_node():
     one = run_gpu_level(w.target, w.draft, w.node_token, w.seed, 1.0, 0.0)          # one node = one drafted position
     np.testing.assert_array_equal(got[0], one.accept_len)
     np.testing.assert_array_equal(got[2], one.next_token)
+
+
+@pytest.mark.parametrize("split", [1, 4, 16])
+def test_statistics_split_does_not_change_the_walk(split):
+    """Rows cut into 1, 4 or 16 segments by the statistics pass: other partial sums, the same decisions."""
+    w = wl.tree_case(10, [3, 3, 2], 70001, dtype="bf16", temperature=0.8, case_id=799)
+    base = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, w.tau)
+    compare_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, w.tau, base)
+    hb.hola_set_tuning(stats_split=split)
+    try:
+        got = run_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, w.tau)
+    finally:
+        hb.hola_set_tuning()
+    compare_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, w.tau, got)
+    np.testing.assert_allclose(got[3], base[3], rtol=1e-6, atol=1e-6)

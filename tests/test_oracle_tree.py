@@ -253,3 +253,20 @@ def test_edge_cases():
     # q == p: the first child is always kept (u q < p fails only for u >= 1)
     t = orc.verify_tree(w.target, w.target[:, :w.N].copy(), w.node_token, w.node_parent, 1, 1.0, -1.0)
     assert np.all(t.path[:, 0] == 0)
+
+
+def test_batch_rows_are_independent_and_thread_count_does_not_matter():
+    w = wl.tree_case(12, [3, 2, 2], 151, dtype="bf16", temperature=0.9, case_id=740)
+    full = orc.verify_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, w.tau, seq_base=100,
+                           num_threads=4)
+    one = orc.verify_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, w.tau, seq_base=100,
+                          num_threads=1)
+    for f in ("accept_len", "path", "next_token", "entropy", "sample_margin"):
+        np.testing.assert_array_equal(getattr(full, f), getattr(one, f))
+    for b in (0, 5, 11):                                        # a row alone, under its global sequence index
+        r = orc.verify_tree(w.target[b:b + 1], w.draft[b:b + 1], w.node_token[b:b + 1], w.node_parent[b:b + 1], w.seed,
+                            w.temperature, w.tau, seq_base=100 + b)
+        assert r.accept_len[0] == full.accept_len[b] and r.next_token[0] == full.next_token[b]
+        np.testing.assert_array_equal(r.path[0], full.path[b])
+    other = orc.verify_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, w.tau, seq_base=0)
+    assert not (np.array_equal(other.next_token, full.next_token) and np.array_equal(other.accept_len, full.accept_len))
