@@ -112,7 +112,11 @@ static double scaled(double x, double T) { return T > 0.0 ? x / T : x; }
 /* p_i = exp(z_i - lse) and log p_i = z_i - lse, so                            */
 /*   H = lse - sum_i z_i exp(z_i - lse);   a term whose probability is 0       */
 /* (including z_i = -inf) contributes 0.                                       */
-/* A row with no finite maximum has no distribution: lse = -inf, H = NaN.      */
+/* A row with no finite logit has no distribution: lse = -inf, H = NaN; a row   */
+/* holding +inf or NaN has no softmax either: lse = NaN, H = NaN.              */
+/* Shannon entropy is >= 0; on a nearly one-hot row the subtraction above can  */
+/* leave a rounding residue below zero, which is returned as 0 (so a threshold */
+/* of 0 with the strict gate never fires).                                     */
 /* ------------------------------------------------------------------------- */
 void oracle_row_stats(const void* logits, int32_t dtype, int64_t offset, int32_t V, double T,
                       double* lse_out, double* H_out, int32_t* argmax_out)
@@ -124,8 +128,8 @@ void oracle_row_stats(const void* logits, int32_t dtype, int64_t offset, int32_t
         if (z > m) { m = z; am = i; }          /* strict: lowest index wins ties */
     }
     if (argmax_out) *argmax_out = am;
-    if (!(m > -INFINITY) || !(m < INFINITY)) {  /* all -inf, or NaN / +inf present */
-        if (lse_out) *lse_out = (m == INFINITY) ? INFINITY : -INFINITY;
+    if (!(m > -INFINITY) || !(m < INFINITY)) {  /* all -inf, or +inf present */
+        if (lse_out) *lse_out = (m == INFINITY) ? NAN : -INFINITY;
         if (H_out) *H_out = NAN;
         return;
     }
@@ -141,8 +145,10 @@ void oracle_row_stats(const void* logits, int32_t dtype, int64_t offset, int32_t
         double p = exp(z - lse);
         if (p > 0.0) acc += z * p;
     }
+    double H = lse - acc;
+    if (H < 0.0) H = 0.0;                       /* rounding residue; NaN passes through */
     if (lse_out) *lse_out = lse;
-    if (H_out) *H_out = lse - acc;
+    if (H_out) *H_out = H;
 }
 
 /* ------------------------------------------------------------------------- */
@@ -154,7 +160,7 @@ void oracle_row_stats(const void* logits, int32_t dtype, int64_t offset, int32_t
 /*   lse = log sum_t exp(lse_t).                                               */
 /* A tile with lse_t = -inf (no finite logit) has w_t = 0 and contributes      */
 /* nothing, whatever its H_t; a row of such tiles gives lse = -inf, H = NaN.   */
-/* A NaN or +inf lse_t makes the row NaN / (+inf, NaN) as oracle_row_stats.    */
+/* A NaN or +inf lse_t makes the row (NaN, NaN), as in oracle_row_stats.       */
 /* ------------------------------------------------------------------------- */
 void oracle_merge_tile_stats(const double* tile_stats /* [ntiles][2] = (lse_t, H_t) */, int32_t ntiles,
                              double* lse_out, double* H_out)
@@ -167,7 +173,7 @@ void oracle_merge_tile_stats(const double* tile_stats /* [ntiles][2] = (lse_t, H
         if (l > m) m = l;
     }
     if (bad) { *lse_out = NAN; *H_out = NAN; return; }
-    if (!(m > -INFINITY) || !(m < INFINITY)) { *lse_out = (m == INFINITY) ? INFINITY : -INFINITY; *H_out = NAN; return; }
+    if (!(m > -INFINITY) || !(m < INFINITY)) { *lse_out = (m == INFINITY) ? NAN : -INFINITY; *H_out = NAN; return; }
     double S = 0.0;
     for (int32_t t = 0; t < ntiles; ++t) S += exp(tile_stats[2 * t] - m);
     double lse = m + log(S);
@@ -687,6 +693,75 @@ int32_t oracle_sample_interval(const oracle_verify_args* a, int32_t b, int32_t a
     return 0;
 }
 
+/* The same interval on filtered distributions (test aid): the keep sets of the
+ * stop row pair are those of oracle_filter_row with the given top_k / top_p,
+ * their lengths overridden by force_keep_count where that is given and >= 0. */
+int32_t oracle_sample_interval_filtered(const oracle_verify_args* a, int32_t top_k, double top_p,
+                                        const int32_t* force_keep_count /* [B, 2 gamma + 1] or NULL */,
+                                        int32_t b, int32_t acc_len, int32_t tok, double* lo_out, double* hi_out)
+{
+    const int32_t g = a->gamma, V = a->V, R = 2 * g + 1;
+    if (tok < 0 || tok >= V || acc_len < 0 || acc_len > g) return -1;
+    const int64_t tld = a->target_ld ? a->target_ld : V;
+    const int64_t dld = a->draft_ld ? a->draft_ld : V;
+    const int32_t len = a->draft_len ? a->draft_len[b] : g;
+    const double T = (double)(a->row_temperature ? a->row_temperature[b] : a->temperature);
+    if (!(T > 0.0)) return -1;
+    const int32_t bonus = (acc_len >= len);
+    const int64_t t_off = ((int64_t)b * (g + 1) + acc_len) * tld;
+    const int64_t d_off = ((int64_t)b * g + (bonus ? 0 : acc_len)) * dld;
+    uint8_t* kP = (uint8_t*)malloc((size_t)V);
+    uint8_t* kD = (uint8_t*)malloc((size_t)V);
+    double* w = (double*)malloc((size_t)V * sizeof(double));
+    double lseP, lseD = 0.0, H, mg;
+    oracle_filter_row(a->target_logits, a->dtype, t_off, V, T, top_k, top_p,
+                      force_keep_count ? force_keep_count[(int64_t)b * R + g + acc_len] : -1, kP, &lseP, &H, &mg);
+    if (!bonus)
+        oracle_filter_row(a->draft_logits, a->dtype, d_off, V, T, top_k, top_p,
+                          force_keep_count ? force_keep_count[(int64_t)b * R + acc_len] : -1, kD, &lseD, &H, &mg);
+    double Z = 0.0;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int as_bonus = bonus || pass == 1;
+        Z = 0.0;
+        for (int32_t i = 0; i < V; ++i) {
+            double p = filtered_prob_at(a->target_logits, a->dtype, t_off, i, T, kP, lseP);
+            if (as_bonus) { w[i] = p; Z += p; continue; }
+            double q = filtered_prob_at(a->draft_logits, a->dtype, d_off, i, T, kD, lseD);
+            double d = p - q;
+            w[i] = d > 0.0 ? d : 0.0;
+            Z += w[i];
+        }
+        if (as_bonus || Z > 0.0) break;
+    }
+    double C = 0.0, prev = 0.0;
+    for (int32_t i = 0; i <= tok; ++i) { prev = C; C += w[i]; }
+    free(w); free(kP); free(kD);
+    if (!(Z > 0.0)) return -1;
+    *lo_out = prev / Z;
+    *hi_out = C / Z;
+    return 0;
+}
+
+/* The interval [C_{tok-1}, C_tok] / Z of token `tok` under softmax(row / T) itself
+ * (test aid for draws taken straight from a target row). */
+int32_t oracle_row_interval(const void* logits, int32_t dtype, int64_t offset, int32_t V, double T, int32_t tok,
+                            double* lo_out, double* hi_out)
+{
+    if (tok < 0 || tok >= V || !(T > 0.0)) return -1;
+    double lse;
+    oracle_row_stats(logits, dtype, offset, V, T, &lse, NULL, NULL);
+    double Z = 0.0, C = 0.0, prev = 0.0;
+    for (int32_t i = 0; i < V; ++i) {
+        const double p = prob_at(logits, dtype, offset, i, T, lse);
+        Z += p;
+        if (i <= tok) { prev = C; C += p; }
+    }
+    if (!(Z > 0.0)) return -1;
+    *lo_out = prev / Z;
+    *hi_out = C / Z;
+    return 0;
+}
+
 /* ------------------------------------------------------------------------- */
 /* Hierarchical verify over n_models logit sets, smallest drafter first.       */
 /* Level k (k = 1 .. n_models-1) verifies with models[k] the drafts that       */
@@ -798,7 +873,8 @@ int32_t oracle_hsd_verify(const void* const* model_logits, const int64_t* model_
 /* ratio outputs are ignored.                                                  */
 /* ------------------------------------------------------------------------- */
 int32_t oracle_verify_literal(const oracle_verify_args* a, int32_t* out_tokens /* [B, gamma], -1 beyond len */,
-                              int32_t* out_calls /* [B] */, double* out_pos_sample_margin /* [B, gamma] or NULL */)
+                              int32_t* out_calls /* [B] */, double* out_pos_sample_margin /* [B, gamma] or NULL */,
+                              const int8_t* force_gate /* [B, gamma] or NULL; 0 / 1 overrides that gate (test aid) */)
 {
     if (!a || a->B < 0 || a->gamma < 1 || a->gamma > 63 || a->V < 1) return -1;
     const int32_t g = a->gamma, V = a->V;
@@ -822,7 +898,8 @@ int32_t oracle_verify_literal(const oracle_verify_args* a, int32_t* out_tokens /
             if (t >= len) continue;
             double lseD, HD;
             oracle_row_stats(a->draft_logits, a->dtype, o * dld, V, T, &lseD, &HD, NULL);
-            const int gate = (HD < tau) ? 1 : 0;
+            int gate = (HD < tau) ? 1 : 0;
+            if (force_gate && force_gate[o] >= 0) gate = force_gate[o] ? 1 : 0;
             if (a->out_entropy) a->out_entropy[o] = (float)HD;
             if (a->out_entropy64) a->out_entropy64[o] = HD;
             if (a->out_gate) a->out_gate[o] = (uint8_t)gate;
@@ -895,6 +972,12 @@ typedef struct {
     double* out_ratio_margin;       /* [B, N] per node, NaN where not tested */
     double* out_sample_margin;      /* [B] */
     int32_t num_threads;
+    /* test aids; any may be NULL */
+    const int32_t* force_node;      /* [B] node whose decision (gate or test) is overridden, -1: none */
+    const int32_t* force_outcome;   /* [B] 1: that node is kept, 0: it is rejected */
+    const int32_t* probe_token;     /* [B] token whose interval in the walk's final draw is wanted, -1: none */
+    double* out_probe_lo;           /* [B] its interval [C_{tok-1}, C_tok] / Z, NaN when not asked or without mass */
+    double* out_probe_hi;
 } oracle_tree_args;
 
 static void tree_one_sequence(const oracle_tree_args* a, int32_t b, double* pr, double* q, double* w)
@@ -932,6 +1015,7 @@ static void tree_one_sequence(const oracle_tree_args* a, int32_t b, double* pr, 
 
     int32_t ctx = 0, depth = 0, next = -1;
     double smargin = NAN;
+    const double* final_w = pr;                            /* the weights the final draw was taken from (probe aid) */
     for (;;) {
         const int64_t t_off = ((int64_t)b * (N + 1) + ctx) * tld;
         double lseP, HP;
@@ -945,6 +1029,7 @@ static void tree_one_sequence(const oracle_tree_args* a, int32_t b, double* pr, 
         double Zs;
         if (nkids == 0) {                                  /* nothing drafted here: the token is the verifier's */
             next = oracle_inverse_cdf(pr, V, u2, &Zs, &smargin);
+            final_w = pr;
             break;
         }
         const int64_t d_off = ((int64_t)b * N + ctx) * dld;
@@ -971,6 +1056,7 @@ static void tree_one_sequence(const oracle_tree_args* a, int32_t b, double* pr, 
                 if (a->out_ratio_margin && q_x > 0.0)
                     a->out_ratio_margin[(int64_t)b * N + n] = fabs(u - r_x / q_x) * Zprod / (Csum > 1.0 ? Csum : 1.0);
             }
+            if (a->force_node && a->force_node[b] == n) ok = a->force_outcome[b] ? 1 : 0;
             first = 0;
             if (ok) { kept = n; break; }
             double z = 0.0;                                /* r <- max(0, r - q) / its sum */
@@ -993,7 +1079,17 @@ static void tree_one_sequence(const oracle_tree_args* a, int32_t b, double* pr, 
         }
         /* the draw needs no normalised weights: the last residual as it was before its division */
         next = oracle_inverse_cdf(rejected ? w : pr, V, u2, &Zs, &smargin);
+        final_w = rejected ? w : pr;
         break;
+    }
+    if (a->out_probe_lo) a->out_probe_lo[b] = NAN;
+    if (a->out_probe_hi) a->out_probe_hi[b] = NAN;
+    if (a->probe_token && a->out_probe_lo && a->out_probe_hi && a->probe_token[b] >= 0 && a->probe_token[b] < V) {
+        const int32_t t = a->probe_token[b];
+        double Z = 0.0, C = 0.0, prev = 0.0;
+        for (int32_t i = 0; i < V; ++i) Z += final_w[i];
+        for (int32_t i = 0; i <= t; ++i) { prev = C; C += final_w[i]; }
+        if (Z > 0.0) { a->out_probe_lo[b] = prev / Z; a->out_probe_hi[b] = C / Z; }
     }
     if (a->out_accept_len) a->out_accept_len[b] = depth;
     if (a->out_next_token) a->out_next_token[b] = next;

@@ -62,6 +62,8 @@ class _TreeArgs(C.Structure):
         ("out_entropy", C.c_void_p), ("out_entropy64", C.c_void_p),
         ("out_gate_margin", C.c_void_p), ("out_ratio_margin", C.c_void_p), ("out_sample_margin", C.c_void_p),
         ("num_threads", C.c_int32),
+        ("force_node", C.c_void_p), ("force_outcome", C.c_void_p), ("probe_token", C.c_void_p),
+        ("out_probe_lo", C.c_void_p), ("out_probe_hi", C.c_void_p),
     ]
 
 
@@ -104,13 +106,19 @@ def lib() -> C.CDLL:
         L.oracle_sample_interval.argtypes = [C.POINTER(_Args), C.c_int32, C.c_int32, C.c_int32,
                                              C.c_void_p, C.c_void_p]
         L.oracle_sample_interval.restype = C.c_int32
+        L.oracle_sample_interval_filtered.argtypes = [C.POINTER(_Args), C.c_int32, C.c_double, C.c_void_p, C.c_int32,
+                                                      C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.oracle_sample_interval_filtered.restype = C.c_int32
+        L.oracle_row_interval.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_double, C.c_int32,
+                                          C.c_void_p, C.c_void_p]
+        L.oracle_row_interval.restype = C.c_int32
         L.oracle_hsd_verify.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                         C.c_uint64, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                         C.c_void_p, C.c_float, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_int32]
         L.oracle_hsd_verify.restype = C.c_int32
-        L.oracle_verify_literal.argtypes = [C.POINTER(_Args), C.c_void_p, C.c_void_p, C.c_void_p]
+        L.oracle_verify_literal.argtypes = [C.POINTER(_Args), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.oracle_verify_literal.restype = C.c_int32
         L.oracle_verify_tree.argtypes = [C.POINTER(_TreeArgs)]
         L.oracle_verify_tree.restype = C.c_int32
@@ -315,10 +323,20 @@ class VerifyCall:
             raise ValueError("the oracle rejected its arguments")
         return r
 
-    def sample_interval(self, b: int, acc_len: int, tok: int) -> Optional[tuple[float, float]]:
+    def sample_interval(self, b: int, acc_len: int, tok: int, top_k: Optional[int] = None,
+                        top_p: Optional[float] = None, force_keep_count: Optional[np.ndarray] = None
+                        ) -> Optional[tuple[float, float]]:
+        """CDF interval of `tok` in the distribution the stop row `acc_len` of sequence b is sampled from
+        (top_k / top_p given: on the filtered distributions, keep counts as forced)."""
         lo, hi = C.c_double(), C.c_double()
-        rc = lib().oracle_sample_interval(C.byref(self.args), int(b), int(acc_len), int(tok),
-                                          C.addressof(lo), C.addressof(hi))
+        if top_k is None and top_p is None:
+            rc = lib().oracle_sample_interval(C.byref(self.args), int(b), int(acc_len), int(tok),
+                                              C.addressof(lo), C.addressof(hi))
+        else:
+            fk = None if force_keep_count is None else np.ascontiguousarray(force_keep_count, np.int32)
+            rc = lib().oracle_sample_interval_filtered(C.byref(self.args), int(top_k or 0),
+                                                       float(1.0 if top_p is None else top_p), _ptr(fk), int(b),
+                                                       int(acc_len), int(tok), C.addressof(lo), C.addressof(hi))
         return None if rc != 0 else (lo.value, hi.value)
 
 
@@ -395,8 +413,18 @@ class LiteralResult:
     sample_margin: np.ndarray    # [B, gamma], NaN where no sample was drawn
 
 
-def verify_literal(target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold, **kw) -> LiteralResult:
-    """Equation (1) without stopping: gate keeps the draft token, otherwise a draw from the target row."""
+def row_interval(row: np.ndarray, T: float, tok: int) -> Optional[tuple[float, float]]:
+    """CDF interval [C_{tok-1}, C_tok] / Z of `tok` under softmax(row / T), ascending index order."""
+    row, dt = _logits(row)
+    lo, hi = C.c_double(), C.c_double()
+    rc = lib().oracle_row_interval(_ptr(row), dt, 0, row.shape[-1], float(T), int(tok), C.addressof(lo), C.addressof(hi))
+    return None if rc != 0 else (lo.value, hi.value)
+
+
+def verify_literal(target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold, force_gate=None,
+                   **kw) -> LiteralResult:
+    """Equation (1) without stopping: gate keeps the draft token, otherwise a draw from the target row.
+    force_gate [B, gamma] int8 (test aid): 0 / 1 overrides that position's gate, -1 leaves it."""
     call = VerifyCall(target_logits, draft_logits, draft_tokens, seed, temperature, entropy_threshold, **kw)
     B, g = call.B, call.g
     r = LiteralResult(tokens=np.zeros((B, g), np.int32), calls=np.zeros(B, np.int32),
@@ -406,7 +434,8 @@ def verify_literal(target_logits, draft_logits, draft_tokens, seed, temperature,
     a = call.args
     a.out_entropy, a.out_entropy64 = _ptr(r.entropy), _ptr(r.entropy64)
     a.out_gate, a.out_gate_margin = _ptr(r.gate), _ptr(r.gate_margin)
-    rc = lib().oracle_verify_literal(C.byref(a), _ptr(r.tokens), _ptr(r.calls), _ptr(r.sample_margin))
+    fg = None if force_gate is None else np.ascontiguousarray(force_gate, np.int8).reshape(B, g)
+    rc = lib().oracle_verify_literal(C.byref(a), _ptr(r.tokens), _ptr(r.calls), _ptr(r.sample_margin), _ptr(fg))
     if rc != 0:
         raise ValueError("oracle_verify_literal rejected its arguments")
     return r
@@ -422,10 +451,13 @@ class TreeResult:
     gate_margin: np.ndarray      # [B, N] per context, NaN where not visited
     ratio_margin: np.ndarray     # [B, N] per node, NaN where not tested
     sample_margin: np.ndarray    # [B]
+    probe_lo: Optional[np.ndarray] = None   # [B] CDF interval of probe_token in the final draw (NaN: not asked)
+    probe_hi: Optional[np.ndarray] = None
 
 
 def verify_tree(target_logits, draft_logits, node_token, node_parent, seed, temperature, entropy_threshold,
-                n_nodes=None, level=0, seq_base=0, num_threads=0) -> TreeResult:
+                n_nodes=None, level=0, seq_base=0, num_threads=0, force_node=None, force_outcome=None,
+                probe_token=None) -> TreeResult:
     """Verify step over token trees: target [B,N+1,V] and draft [B,N,V] rows by context (0: the prefix,
     n+1: after node n), node_parent -1 or an earlier node; children are tried in node order."""
     P, dt = _logits(target_logits)
@@ -454,6 +486,15 @@ def verify_tree(target_logits, draft_logits, node_token, node_parent, seed, temp
     a.out_gate_margin, a.out_ratio_margin = _ptr(r.gate_margin), _ptr(r.ratio_margin)
     a.out_sample_margin = _ptr(r.sample_margin)
     a.num_threads = int(num_threads)
+    # test aids: one node's decision overridden, the interval of a given token in the final draw
+    fn = None if force_node is None else np.ascontiguousarray(force_node, dtype=np.int32)
+    fo = None if force_outcome is None else np.ascontiguousarray(force_outcome, dtype=np.int32)
+    pt = None if probe_token is None else np.ascontiguousarray(probe_token, dtype=np.int32)
+    assert (fn is None) == (fo is None)
+    a.force_node, a.force_outcome, a.probe_token = _ptr(fn), _ptr(fo), _ptr(pt)
+    if pt is not None:
+        r.probe_lo, r.probe_hi = np.zeros(B, np.float64), np.zeros(B, np.float64)
+        a.out_probe_lo, a.out_probe_hi = _ptr(r.probe_lo), _ptr(r.probe_hi)
     if lib().oracle_verify_tree(C.byref(a)) != 0:
         raise ValueError("oracle_verify_tree rejected its arguments")
     return r

@@ -251,3 +251,66 @@ def test_residual_weights_definition_and_invariants(dtype):
     np.testing.assert_allclose(wb, p, rtol=1e-13, atol=0)
     # identical rows leave no residual at all
     assert orc.residual_weights(P, P, T).sum() == 0.0
+
+
+def _entropy_unclamped(row, T):
+    """lse - sum z p in IEEE double, ascending index order, exactly as Section 3.1's definition is evaluated."""
+    z = [float(x) / T for x in np.asarray(row, np.float32).astype(np.float64)]
+    m = max(z)
+    S = 0.0
+    for x in z:
+        S += math.exp(x - m)
+    lse = m + math.log(S)
+    acc = 0.0
+    for x in z:
+        pr = math.exp(x - lse)
+        if pr > 0.0:
+            acc += x * pr
+    return lse - acc
+
+
+def test_entropy_is_never_negative_and_tau_zero_never_gates():
+    """Shannon entropy (Section 3.1) is >= 0.  On nearly one-hot rows lse - sum z p cancels to rounding; whatever
+    is left below zero is not entropy, so the oracle returns 0 there and a threshold of 0 (strict <) gates nothing."""
+    rows = [np.array([35.14083480834961, -0.257364958524704, -1.2592607736587524, 1.5822691917419434], np.float32),
+            np.array([1.6672909259796143, 35.24894332885742, -0.6074924468994141], np.float32),
+            np.array([0.8733947277069092, 0.8153969049453735, 36.382686614990234, -0.076581209897995, 2.817026376724243],
+                     np.float32)]
+    for row in rows:
+        assert _entropy_unclamped(row, 1.0) < 0.0              # rounding alone goes below zero on these rows
+        lse, H, _ = orc.row_stats(row, 1.0)
+        assert H == 0.0
+    rng = np.random.default_rng(5)
+    n_neg = 0
+    for trial in range(3000):
+        V = int(rng.integers(2, 6))
+        row = rng.normal(0, 1, V).astype(np.float32)
+        row[rng.integers(0, V)] += np.float32(rng.uniform(20, 40))
+        T = float(rng.choice([0.7, 1.0, 1.3]))
+        naive = _entropy_unclamped(row, T)
+        n_neg += naive < 0.0
+        lse, H, _ = orc.row_stats(row, T)
+        assert H >= 0.0 and H == max(naive, 0.0)               # the clamp and nothing else
+    # through the entry point: such rows are never gated at tau = 0
+    P = np.zeros((3, 2, 5), np.float32)
+    D = np.zeros((3, 1, 5), np.float32)
+    for b, row in enumerate(rows):
+        D[b, 0, :row.shape[0]] = row
+        D[b, 0, row.shape[0]:] = -np.inf
+    r = orc.verify(P, D, np.zeros((3, 1), np.int32), 0, 1.0, 0.0)
+    assert not r.gate.any() and np.all(r.entropy64 == 0.0)
+
+
+def test_plus_inf_or_nan_logit_gives_nan_statistics():
+    """A row holding +inf or NaN has no softmax: both statistics are NaN (and a NaN entropy never gates)."""
+    for bad in (np.inf, np.nan):
+        row = np.array([0.5, bad, -1.0, 2.0], np.float32)
+        lse, H, _ = orc.row_stats(row, 1.0)
+        assert math.isnan(lse) and math.isnan(H)
+        bits = wl.f32_to_bf16_bits(row)
+        lse, H, _ = orc.row_stats(bits, 0.8)
+        assert math.isnan(lse) and math.isnan(H)
+    P = np.zeros((1, 2, 4), np.float32); D = np.zeros((1, 1, 4), np.float32)
+    D[0, 0, 1] = np.inf
+    r = orc.verify(P, D, np.zeros((1, 1), np.int32), 0, 1.0, 1e30)
+    assert not r.gate.any()
