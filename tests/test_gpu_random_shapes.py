@@ -40,6 +40,6 @@ def test_random_case(seed):
         hb.hola_set_tuning(filter_path=path)
         try:
             got = run_filtered(w.target, w.draft, w.tokens, w.seed, T, tau, top_k, top_p, draft_len=dl)
-            compare_filtered(w.target, w.draft, w.tokens, w.seed, T, tau, top_k, top_p, got, draft_len=dl, max_listed=B)
+            compare_filtered(w.target, w.draft, w.tokens, w.seed, T, tau, top_k, top_p, got, draft_len=dl)
         finally:
             hb.hola_set_tuning()

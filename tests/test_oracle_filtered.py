@@ -274,3 +274,51 @@ def test_filtered_two_level_first_token_follows_filtered_final_target():
     full = scipy.special.softmax(base[0].astype(np.float64))    # the unfiltered target is told apart
     assert scipy.stats.chisquare(counts, N * full).pvalue < 1e-6
     assert set(np.flatnonzero(filtered(mid1[0]))) != set(np.flatnonzero(want))   # the keep sets differ by level
+
+
+def test_filtered_sample_interval_brackets_the_sampling_uniform():
+    """Test aid: the CDF interval of a token in the filtered distribution a stop row is sampled from equals a numpy
+    restatement (kept sets by stable sort, renormalised, residual or bonus), follows forced keep counts, and holds
+    the sampling uniform for the oracle's own token."""
+    w = wl.small_case(12, 3, 257, dtype="f32", temperature=0.8, case_id=601)
+    T = float(np.float32(0.8))
+    top_k, top_p = 40, 0.9
+    call = orc.VerifyCall(w.target, w.draft, w.tokens, w.seed, T, -1.0)
+    r = call.run(top_k=top_k, top_p=top_p)
+
+    def kept_probs(row, m):
+        z = row.astype(np.float64) / T
+        order = np.argsort(-z, kind="stable")[:m]
+        p = np.zeros_like(z)
+        p[order] = np.exp(z[order] - np.logaddexp.reduce(z[order]))
+        return p
+
+    g = w.gamma
+    for b in range(w.B):
+        a = int(r.accept_len[b])
+        p = kept_probs(w.target[b, a], int(r.keep_count[b, g + a]))
+        wgt = p if a >= g else np.maximum(0.0, p - kept_probs(w.draft[b, a], int(r.keep_count[b, a])))
+        C = np.cumsum(wgt)
+        k = int(r.next_token[b])
+        lo, hi = call.sample_interval(b, a, k, top_k=top_k, top_p=top_p)
+        assert lo == pytest.approx((C[k - 1] if k else 0.0) / C[-1], abs=1e-12) and hi == pytest.approx(C[k] / C[-1], abs=1e-12)
+        u2 = orc.hsd_uniforms(w.seed, b, a, 0)[1]
+        assert lo <= u2 < hi or r.sample_margin[b] < 1e-12
+    # forced keep counts move the interval with the cut
+    fk = r.keep_count.copy()
+    b = int(np.flatnonzero(r.accept_len < g)[0]) if (r.accept_len < g).any() else 0
+    a = int(r.accept_len[b])
+    fk[b, g + a] = 3
+    p3 = kept_probs(w.target[b, a], 3)
+    wgt = p3 if a >= g else np.maximum(0.0, p3 - kept_probs(w.draft[b, a], int(fk[b, a])))
+    k = int(np.argmax(wgt))
+    C = np.cumsum(wgt)
+    lo, hi = call.sample_interval(b, a, k, top_k=top_k, top_p=top_p, force_keep_count=fk)
+    assert hi - lo == pytest.approx(wgt[k] / C[-1], abs=1e-12)
+    # filters off: the unfiltered interval
+    call0 = orc.VerifyCall(w.target, w.draft, w.tokens, w.seed, T, -1.0)
+    r0 = call0.run()
+    for b in range(4):
+        i1 = call0.sample_interval(b, int(r0.accept_len[b]), int(r0.next_token[b]))
+        i2 = call0.sample_interval(b, int(r0.accept_len[b]), int(r0.next_token[b]), top_k=0, top_p=1.0)
+        assert i1 == pytest.approx(i2, abs=1e-13)

@@ -76,3 +76,38 @@ def test_literal_sampled_positions_follow_the_target_distribution():
     r = orc.verify_literal(P, D, tok, 99, 1.0, 0.0)
     p = _softmax(P1[0])
     assert scipy.stats.chisquare(np.bincount(r.tokens[:, 0], minlength=V), N * p).pvalue > 1e-3
+
+
+def test_forced_gates_and_the_row_interval_aid():
+    """Test aids: a forced gate only swaps the branch of Equation (1) at that position; the CDF interval of a token
+    under softmax(row / T) is numpy's cumsum, and the oracle's own draw lies inside its interval."""
+    w = wl.small_case(10, 4, 151, dtype="bf16", temperature=0.9, case_id=402)
+    T = float(np.float32(0.9))
+    tau = 0.5 * math.log(w.V)
+    base = orc.verify_literal(w.target, w.draft, w.tokens, w.seed, T, tau)
+    all_draft = orc.verify_literal(w.target, w.draft, w.tokens, w.seed, T, tau, force_gate=np.ones((w.B, w.gamma), np.int8))
+    all_drawn = orc.verify_literal(w.target, w.draft, w.tokens, w.seed, T, tau, force_gate=np.zeros((w.B, w.gamma), np.int8))
+    never = orc.verify_literal(w.target, w.draft, w.tokens, w.seed, T, -1.0)
+    np.testing.assert_array_equal(all_draft.tokens, w.tokens)
+    assert np.all(all_draft.calls == 0)
+    np.testing.assert_array_equal(all_drawn.tokens, never.tokens)
+    np.testing.assert_array_equal(all_drawn.calls, never.calls)
+    unforced = orc.verify_literal(w.target, w.draft, w.tokens, w.seed, T, tau, force_gate=np.full((w.B, w.gamma), -1, np.int8))
+    np.testing.assert_array_equal(unforced.tokens, base.tokens)
+    one = np.full((w.B, w.gamma), -1, np.int8)
+    b, t = 3, 2
+    one[b, t] = 0 if base.gate[b, t] else 1
+    flipped = orc.verify_literal(w.target, w.draft, w.tokens, w.seed, T, tau, force_gate=one)
+    same = np.ones((w.B, w.gamma), bool); same[b, t] = False
+    np.testing.assert_array_equal(flipped.tokens[same], base.tokens[same])
+    assert flipped.tokens[b, t] == (never.tokens[b, t] if base.gate[b, t] else w.tokens[b, t])
+    for b in range(w.B):
+        for t in range(w.gamma):
+            p = _softmax(wl.as_f32(w.target[b, t]), T)
+            C = np.cumsum(p)
+            k = int(never.tokens[b, t])
+            lo, hi = orc.row_interval(w.target[b, t], T, k)
+            assert lo == pytest.approx((C[k - 1] if k else 0.0) / C[-1], abs=1e-13) and hi == pytest.approx(C[k] / C[-1], abs=1e-13)
+            u2 = orc.hsd_uniforms(w.seed, b, t, 0)[1]
+            assert lo <= u2 < hi or never.sample_margin[b, t] < 1e-12
+    assert orc.row_interval(w.target[0, 0], T, w.V) is None and orc.row_interval(w.target[0, 0], T, -1) is None

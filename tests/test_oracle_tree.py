@@ -270,3 +270,66 @@ def test_batch_rows_are_independent_and_thread_count_does_not_matter():
         np.testing.assert_array_equal(r.path[0], full.path[b])
     other = orc.verify_tree(w.target, w.draft, w.node_token, w.node_parent, w.seed, w.temperature, w.tau, seq_base=0)
     assert not (np.array_equal(other.next_token, full.next_token) and np.array_equal(other.accept_len, full.accept_len))
+
+
+def test_forced_node_and_probe_aids():
+    """Test aids: forcing a node to the decision it takes anyway changes nothing; forcing the other decision changes
+    the walk from that node on exactly as the rule says; the probed interval of the walk's own next token holds the
+    sampling uniform and equals a numpy restatement of the final draw's weights."""
+    w = wl.tree_case(24, [3, 3, 2], 401, dtype="f32", temperature=0.9, draft_sigma=1.2, case_id=720)
+    T = float(np.float32(0.9))
+    args = (w.target, w.draft, w.node_token, w.node_parent, w.seed, T, -1.0)
+    base = orc.verify_tree(*args, probe_token=None)
+    B, N = w.B, w.N
+    # (a) a forced decision equal to the walk's own
+    fn, fo = np.full(B, -1, np.int32), np.zeros(B, np.int32)
+    for b in range(B):
+        if base.accept_len[b] > 0:
+            fn[b], fo[b] = base.path[b, 0], 1
+    same = orc.verify_tree(*args, force_node=fn, force_outcome=fo)
+    np.testing.assert_array_equal(same.path, base.path)
+    np.testing.assert_array_equal(same.next_token, base.next_token)
+    # (b) the first kept node forced to a rejection: the path no longer starts with it, and equals the numpy walk
+    # over the tree with that node's token made unacceptable (r(x) = 0 rejects for every u)
+    fo[:] = 0
+    flipped = orc.verify_tree(*args, force_node=fn, force_outcome=fo)
+    for b in range(B):
+        if fn[b] >= 0:
+            assert flipped.accept_len[b] == 0 or flipped.path[b, 0] != fn[b]
+            assert flipped.accept_len[b] == 0 or flipped.path[b, 0] > fn[b]      # a later child of the prefix
+        else:
+            assert np.array_equal(flipped.path[b], base.path[b]) and flipped.next_token[b] == base.next_token[b]
+    # (c) a rejected first child forced to be kept: the walk goes on below it
+    fn2, fo2 = np.full(B, -1, np.int32), np.ones(B, np.int32)
+    for b in range(B):
+        if base.accept_len[b] == 0 or base.path[b, 0] != 0:
+            fn2[b] = 0                                       # node 0 is the prefix's first child and was rejected
+    kept = orc.verify_tree(*args, force_node=fn2, force_outcome=fo2)
+    assert (fn2 >= 0).any()
+    for b in range(B):
+        if fn2[b] >= 0:
+            assert kept.accept_len[b] >= 1 and kept.path[b, 0] == 0
+    # (d) probe: the interval of the oracle's own next token
+    pr = orc.verify_tree(*args, probe_token=base.next_token)
+    for b in range(B):
+        a = int(base.accept_len[b])
+        ctx = int(base.path[b, a - 1]) + 1 if a else 0
+        u2 = orc.hsd_uniforms(w.seed, b, ctx, 0)[1]
+        assert pr.probe_lo[b] <= u2 < pr.probe_hi[b] or base.sample_margin[b] < 1e-12
+        # numpy restatement of the final weights: max(0, p - C q) after the rejections at ctx
+        p = scipy.special.softmax(w.target[b, ctx].astype(np.float64) / T)
+        kids = [n for n in range(N) if w.node_parent[b, n] == ctx - 1]
+        wgt = p
+        if kids:
+            q = scipy.special.softmax(w.draft[b, ctx].astype(np.float64) / T)
+            C, Z = 0.0, 1.0
+            for _ in kids:
+                C += Z
+                Z = np.maximum(0.0, p - C * q).sum()
+            wgt = np.maximum(0.0, p - C * q)
+        cs = np.cumsum(wgt)
+        k = int(base.next_token[b])
+        assert pr.probe_hi[b] - pr.probe_lo[b] == pytest.approx(wgt[k] / cs[-1], rel=1e-9, abs=1e-15)
+        assert pr.probe_lo[b] == pytest.approx((cs[k - 1] if k else 0.0) / cs[-1], abs=1e-11)
+    none = orc.verify_tree(*args, probe_token=np.full(B, -1, np.int32))
+    assert np.all(np.isnan(none.probe_lo))

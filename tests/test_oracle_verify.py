@@ -379,3 +379,38 @@ def test_three_level_runs_and_shapes():
     h = orc.hsd_verify(models, tok, 1, 1.0, [1.0, 2.0, 3.0])
     assert h.tokens.shape == (B, g + 3) and h.entropy.shape == (3, B, g + 2)
     assert np.all(h.accept_len <= h.level_accept[1] + 1) and np.all(h.level_accept[1] <= h.level_accept[0] + 1)
+
+
+def test_three_level_is_three_one_level_calls():
+    """The driver's loop at k = 1, 2, 3: each level is the one-level step on the previous level's kept tokens
+    followed by its next token, with Philox level word k - 1 and the middle model as the draft."""
+    rng = np.random.default_rng(21)
+    B, g, V = 24, 3, 61
+    base = (1.5 * rng.standard_normal((B, g + 3, V))).astype(np.float32)
+    models = [(base[:, :g + k] + (0.9 - 0.3 * k) * rng.standard_normal((B, g + k, V))).astype(np.float32)
+              for k in range(3)] + [base]
+    q = _softmax(models[0])
+    tok = np.array([[rng.choice(V, p=q[b, j]) for j in range(g)] for b in range(B)], np.int32)
+    taus = [0.3 * math.log(V), 0.5 * math.log(V), 0.7 * math.log(V)]
+    for survivors_only in (False, True):
+        h = orc.hsd_verify(models, tok, 9, 1.0, taus, seq_base=1000, survivors_only=survivors_only)
+        cur, lens = tok, np.full(B, g, np.int32)
+        for k in range(1, 4):
+            lv = orc.verify(models[k], models[k - 1], cur, 9, 1.0, taus[k - 1], draft_len=lens, level=k - 1, seq_base=1000)
+            np.testing.assert_array_equal(h.level_accept[k - 1], lv.accept_len)
+            np.testing.assert_array_equal(h.level_next[k - 1], lv.next_token)
+            np.testing.assert_array_equal(h.entropy[k - 1][:, :g + k - 1], lv.entropy)
+            assert np.all(h.entropy[k - 1][:, g + k - 1:] == -1.0)
+            if k < 3:
+                nxt = np.full((B, g + k), -1, np.int32)
+                for b in range(B):
+                    a = lv.accept_len[b]
+                    nxt[b, :a] = cur[b, :a]
+                    if not survivors_only:
+                        nxt[b, a] = lv.next_token[b]
+                cur, lens = nxt, lv.accept_len + (0 if survivors_only else 1)
+        np.testing.assert_array_equal(h.accept_len, lv.accept_len)
+        np.testing.assert_array_equal(h.next_token, lv.next_token)
+        for b in range(B):
+            assert np.array_equal(h.tokens[b, :lens[b]], cur[b, :lens[b]]) and np.all(h.tokens[b, lens[b]:] == -1)
+        assert len(set(h.level_accept[0].tolist())) > 1 and len(set(h.accept_len.tolist())) > 1
