@@ -39,9 +39,14 @@
  * Ownership and memory spaces.  Every pointer named "device" is caller-owned DEVICE memory
  * (for PyTorch: tensor.data_ptr()); host pointers are marked "host".  The library never
  * frees caller memory.  hola_verify_f32 / hola_verify_bf16 use one library-owned workspace
- * per device, allocated on first use and grown when a larger shape arrives (hipMalloc; not on
- * the steady-state path), released by hola_shutdown().  hola_verify_ex and hola_hsd_verify
- * use the caller's workspace only and never allocate.
+ * per device, allocated on first use and grown when a larger shape arrives (hipMalloc, which
+ * synchronises the device; not on the steady-state path), released by hola_shutdown().  Because
+ * that workspace is shared, the two short forms are for ONE stream and ONE calling thread per
+ * device at a time: calls that overlap on a device race on it.  hola_verify_ex, hola_hsd_verify
+ * and the other forms that take a workspace use the caller's only, never allocate, and are
+ * reentrant across threads and streams when each call in flight has a workspace of its own.
+ * Launch-shape defaults (hola_set_tuning) and the timing aid (hola_profile_*) belong to the
+ * calling thread.
  *
  * Asynchrony.  All work is enqueued on `stream`; nothing synchronises with the host.
  * Outputs are valid once the stream has been synchronised; inputs and the workspace must
@@ -99,6 +104,28 @@ hola_status hola_verify_bf16(const uint16_t* target_logits, const uint16_t* draf
                              int32_t* out_accept_len, int32_t* out_next_token, float* out_entropy,
                              hola_stream_t stream);
 
+/* Launch-shape knobs.  Zero in a field keeps the built-in choice for MI355X.  Every setting computes the same
+ * decisions; only partial sums are grouped differently (entropies may differ in the last bits). */
+typedef struct {
+    int32_t stats_split;            /* workgroups per logits row in the split-row statistics kernel (1..16) */
+    int32_t stats_unroll;           /* 16-byte loads in flight per lane while streaming a row: 2, 4, 8 or 16 */
+    int32_t path;                   /* 1: split-row statistics + per-sequence tail kernel (2 launches);
+                                       2: fused per-sequence kernel (1 launch; gamma <= 32, else as 1);
+                                       3: split-row statistics, accept, tile sums, select (4 launches);
+                                       0: the library's choice for the shape (path 1 whenever the
+                                          per-sequence kernels support it, else path 3) */
+    int32_t fused_waves;            /* wavefronts per workgroup of the per-sequence kernels: 4 (tail kernel
+                                       only; the fused kernel then uses 8), 8 or 16; 0: 16 for the fused
+                                       kernel, and for the tail kernel 16 / 8 / 4 as the batch grows past
+                                       one / three sequences per compute unit */
+    int32_t filter_path;            /* top-k / top-p keep sets.  0: a split-row scan lists the candidates of every
+                                       row, one wavefront per row decides, and only rows that step cannot settle
+                                       go to the one-workgroup-per-row kernel; 1: that kernel for every row */
+} hola_tuning;
+/* Sets the defaults of the CALLING THREAD (thread-local; NULL restores the built-in choices).  A call whose args
+ * structure carries its own `tuning` ignores them, so no state outside a call's arguments need decide its path. */
+hola_status hola_set_tuning(const hola_tuning* t /* host; NULL restores defaults */);
+
 /* Extended form of one verify level. */
 typedef struct {
     const void* target_logits;      /* device [B, gamma+1, V] */
@@ -148,13 +175,20 @@ typedef struct {
     int32_t* out_next_token;        /* device [B] */
     float* out_entropy;             /* device [B, entropy_ld]: draft entropy for j < len, -1 beyond; NULL ok */
     int64_t entropy_ld;             /* row stride of out_entropy in elements, >= gamma; 0 => gamma */
-    void* workspace;                /* device, 256-byte aligned, >= hola_workspace_bytes(B, gamma, V) */
+    void* workspace;                /* device, 256-byte aligned, >= hola_workspace_bytes_ex(this) */
     size_t workspace_bytes;
     hola_stream_t stream;
+    const hola_tuning* tuning;      /* host; launch shape of this call, NULL => the calling thread's defaults */
 } hola_verify_args;
 
-/* Bytes of workspace hola_verify_ex needs for this shape (either dtype); 0 on invalid shape. */
+/* Bytes of workspace that any hola_verify_ex call of this shape can need (either dtype, filters on or off);
+ * 0 on invalid shape. */
 size_t hola_workspace_bytes(int32_t B, int32_t gamma, int32_t V);
+
+/* Bytes of workspace this very call needs, <= hola_workspace_bytes(B, gamma, V): the candidate lists of the top-k /
+ * top-p filters (most of the larger figure: 16 KB per logits row) are counted only when a filter is on.  Reads B,
+ * gamma, V, top_k and top_p; 0 on NULL or an invalid shape. */
+size_t hola_workspace_bytes_ex(const hola_verify_args* args /* host */);
 
 hola_status hola_verify_ex(const hola_verify_args* args /* host */);
 
@@ -213,6 +247,7 @@ typedef struct {
     int32_t top_k; float top_p;       /* as in hola_verify_args, applied to both models of every level (0 / 0: off).
                                          Filtered levels take no statistics from one another: each finds the keep
                                          sets and statistics of its own rows.  Needs row_temperature == NULL. */
+    const hola_tuning* tuning;        /* host; launch shape of every level, NULL => the calling thread's defaults */
 } hola_hsd_args;
 hola_status hola_hsd_verify_ex(const hola_hsd_args* args /* host */);
 
@@ -248,6 +283,7 @@ typedef struct {
     int32_t* out_next_token;          /* [B]; -1 if the stop row has no finite logit */
     float* out_entropy;               /* [B, N] H(q_c) in nats for contexts with children, -1 elsewhere; or NULL */
     void* workspace; size_t workspace_bytes; hola_stream_t stream;
+    const hola_tuning* tuning;        /* host; NULL => the calling thread's defaults (stats_split, stats_unroll, fused_waves) */
 } hola_tree_args;
 hola_status hola_verify_tree(const hola_tree_args* args /* host */);
 size_t hola_tree_workspace_bytes(int32_t B, int32_t N, int32_t V);   /* 0 on invalid shape */
@@ -280,27 +316,8 @@ size_t hola_tile_stats_workspace_bytes(int32_t R, int32_t V, int32_t tile_cols);
 hola_status hola_merge_tile_stats(const double* tile_stats /* device [R, ntiles, 2] */, int32_t R, int32_t ntiles,
                                   double* stats_out /* device [R, 2] = (lse, H) */, hola_stream_t stream);
 
-/* Launch-shape knobs.  Zero in a field keeps the built-in choice for MI355X. */
-typedef struct {
-    int32_t stats_split;            /* workgroups per logits row in the split-row statistics kernel (1..16) */
-    int32_t stats_unroll;           /* 16-byte loads in flight per lane while streaming a row: 2, 4, 8 or 16 */
-    int32_t path;                   /* 1: split-row statistics + per-sequence tail kernel (2 launches);
-                                       2: fused per-sequence kernel (1 launch; gamma <= 32, else as 1);
-                                       3: split-row statistics, accept, tile sums, select (4 launches);
-                                       0: the library's choice for the shape (path 1 whenever the
-                                          per-sequence kernels support it, else path 3) */
-    int32_t fused_waves;            /* wavefronts per workgroup of the per-sequence kernels: 4 (tail kernel
-                                       only; the fused kernel then uses 8), 8 or 16; 0: 16 for the fused
-                                       kernel, and for the tail kernel 16 / 8 / 4 as the batch grows past
-                                       one / three sequences per compute unit */
-    int32_t filter_path;            /* top-k / top-p keep sets.  0: a split-row scan lists the candidates of every
-                                       row, one wavefront per row decides, and only rows that step cannot settle
-                                       go to the one-workgroup-per-row kernel; 1: that kernel for every row */
-} hola_tuning;
-hola_status hola_set_tuning(const hola_tuning* t /* host; NULL restores defaults */);
-
-/* Per-kernel timing aid for benchmarks.  While enabled, each call records HIP events around
- * each of its kernels on the call's stream.  hola_profile_collect() waits for the recorded
+/* Per-kernel timing aid for benchmarks (state of the calling thread).  While enabled, each call this thread makes
+ * records HIP events around each of its kernels on the call's stream.  hola_profile_collect() waits for the recorded
  * events, ADDS elapsed milliseconds and launch counts per stage to the host arrays, and
  * forgets the events.  Stages: 0 split-row statistics, 1 accept/first-reject, 2 residual tile sums,
  * 3 inverse-CDF select, 4 level glue / tile merge, 5 fused per-sequence kernel, 6 per-sequence tail kernel,
@@ -316,7 +333,7 @@ hola_status hola_profile_collect(double* ms_out /* host [HOLA_N_STAGES] */, int6
  * be scaled against a transfer of known size measured the same way. */
 hola_status hola_copy_bytes(void* dst /* device */, const void* src /* device */, size_t bytes, hola_stream_t stream);
 
-/* Frees the library-owned workspaces and profiling events of every device. */
+/* Frees the library-owned workspaces of every device and the calling thread's profiling events. */
 void hola_shutdown(void);
 
 const char* hola_status_string(hola_status s);

@@ -22,6 +22,7 @@ STAGE_NAMES = ("row_stats", "accept", "tile_sums", "select", "glue", "fused", "t
 
 EXPORTS = (
     "hola_verify_f32", "hola_verify_bf16", "hola_verify_ex", "hola_verify_literal_ex", "hola_workspace_bytes",
+    "hola_workspace_bytes_ex",
     "hola_hsd_verify", "hola_hsd_verify_ex", "hola_hsd_workspace_bytes", "hola_verify_tree",
     "hola_tree_workspace_bytes", "hola_row_stats", "hola_tile_stats",
     "hola_tile_stats_workspace_bytes", "hola_merge_tile_stats", "hola_set_tuning",
@@ -39,6 +40,11 @@ class HolaError(RuntimeError):
         super().__init__(f"{where}: {msg}")
 
 
+class Tuning(C.Structure):
+    _fields_ = [("stats_split", C.c_int32), ("stats_unroll", C.c_int32), ("path", C.c_int32),
+                ("fused_waves", C.c_int32), ("filter_path", C.c_int32)]
+
+
 class VerifyArgs(C.Structure):
     _fields_ = [
         ("target_logits", C.c_void_p), ("draft_logits", C.c_void_p), ("dtype", C.c_int32),
@@ -52,6 +58,7 @@ class VerifyArgs(C.Structure):
         ("out_accept_len", C.c_void_p), ("out_next_token", C.c_void_p), ("out_entropy", C.c_void_p),
         ("entropy_ld", C.c_int64),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p),
+        ("tuning", C.POINTER(Tuning)),
     ]
 
 
@@ -70,6 +77,7 @@ class HsdArgs(C.Structure):
         ("out_entropy", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p),
         ("top_k", C.c_int32), ("top_p", C.c_float),
+        ("tuning", C.POINTER(Tuning)),
     ]
 
 
@@ -84,12 +92,8 @@ class TreeArgs(C.Structure):
         ("out_accept_len", C.c_void_p), ("out_path", C.c_void_p), ("out_next_token", C.c_void_p),
         ("out_entropy", C.c_void_p),
         ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p),
+        ("tuning", C.POINTER(Tuning)),
     ]
-
-
-class Tuning(C.Structure):
-    _fields_ = [("stats_split", C.c_int32), ("stats_unroll", C.c_int32), ("path", C.c_int32),
-                ("fused_waves", C.c_int32), ("filter_path", C.c_int32)]
 
 
 _lib: Optional[C.CDLL] = None
@@ -112,6 +116,8 @@ def lib() -> C.CDLL:
         L.hola_verify_literal_ex.restype = C.c_int32
         L.hola_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
         L.hola_workspace_bytes.restype = C.c_size_t
+        L.hola_workspace_bytes_ex.argtypes = [C.POINTER(VerifyArgs)]
+        L.hola_workspace_bytes_ex.restype = C.c_size_t
         L.hola_hsd_verify.argtypes = [C.POINTER(ModelLogits), C.c_int32, C.c_int32, C.c_void_p, C.c_uint64,
                                       C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_float,
                                       C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -187,6 +193,22 @@ def hola_workspace_bytes(B: int, gamma: int, V: int) -> int:
     return int(lib().hola_workspace_bytes(B, gamma, V))
 
 
+def hola_workspace_bytes_ex(B: int, gamma: int, V: int, top_k: int = 0, top_p: float = 0.0) -> int:
+    """Workspace of one call of this shape with these filters (hola_workspace_bytes_ex reads nothing else)."""
+    a = VerifyArgs()
+    a.B, a.gamma, a.V, a.top_k, a.top_p = int(B), int(gamma), int(V), int(top_k), float(top_p)
+    return int(lib().hola_workspace_bytes_ex(C.byref(a)))
+
+
+def _tuning_ptr(tuning):
+    """hola_tuning of one call: None, a Tuning, or a dict of its fields."""
+    if tuning is None:
+        return None
+    if isinstance(tuning, dict):
+        tuning = Tuning(**{k: int(v) for k, v in tuning.items()})
+    return C.pointer(tuning)
+
+
 def hola_hsd_workspace_bytes(n_models: int, B: int, gamma: int, V: int) -> int:
     return int(lib().hola_hsd_workspace_bytes(n_models, B, gamma, V))
 
@@ -218,8 +240,9 @@ def hola_verify_ex(*, target_logits, draft_logits, draft_tokens, seed, B, gamma,
                    out_accept_len, out_next_token, out_entropy=None, workspace, draft_len=None,
                    row_temperature=None, draft_stats_in=None, target_stats_out=None, target_stats_in=None, level=0,
                    seq_base=0, target_ld=0, draft_ld=0, entropy_ld=0, top_k=0, top_p=0.0, out_keep_count=None,
-                   stream=None) -> None:
+                   stream=None, tuning=None) -> None:
     a = VerifyArgs()
+    a.tuning = _tuning_ptr(tuning)
     a.target_logits, a.draft_logits = _ptr(target_logits), _ptr(draft_logits)
     a.dtype = _logit_dtype(target_logits)
     a.target_ld, a.draft_ld = int(target_ld), int(draft_ld)
@@ -242,8 +265,9 @@ def hola_verify_ex(*, target_logits, draft_logits, draft_tokens, seed, B, gamma,
 def hola_verify_literal_ex(*, target_logits, draft_logits, draft_tokens, seed, B, gamma, V, temperature,
                            entropy_threshold, out_tokens, out_verifier_calls=None, out_entropy=None, workspace,
                            draft_len=None, row_temperature=None, level=0, seq_base=0, target_ld=0, draft_ld=0,
-                           entropy_ld=0, stream=None) -> None:
+                           entropy_ld=0, stream=None, tuning=None) -> None:
     a = VerifyArgs()
+    a.tuning = _tuning_ptr(tuning)
     a.target_logits, a.draft_logits = _ptr(target_logits), _ptr(draft_logits)
     a.dtype = _logit_dtype(target_logits)
     a.target_ld, a.draft_ld = int(target_ld), int(draft_ld)
@@ -278,7 +302,7 @@ def hola_hsd_verify(models: Sequence, draft_tokens, seed, B, gamma, V, temperatu
 def hola_hsd_verify_ex(models: Sequence, draft_tokens, seed, B, gamma, V, temperature, tau: Sequence[float],
                        out_tokens, out_accept_len, out_next_token, out_entropy, workspace, survivors_only=False,
                        row_temperature=None, seq_base=0, lds: Optional[Sequence[int]] = None, stream=None,
-                       top_k=0, top_p=0.0) -> None:
+                       top_k=0, top_p=0.0, tuning=None) -> None:
     n = len(models)
     arr = (ModelLogits * n)()
     for k, m in enumerate(models):
@@ -296,6 +320,7 @@ def hola_hsd_verify_ex(models: Sequence, draft_tokens, seed, B, gamma, V, temper
     a.workspace, a.workspace_bytes = _ptr(workspace), workspace.numel() * workspace.element_size()
     a.stream = _stream_handle(stream)
     a.top_k, a.top_p = int(top_k), float(top_p)
+    a.tuning = _tuning_ptr(tuning)
     _check(lib().hola_hsd_verify_ex(C.byref(a)), "hola_hsd_verify_ex")
 
 
@@ -305,8 +330,9 @@ def hola_tree_workspace_bytes(B: int, N: int, V: int) -> int:
 
 def hola_verify_tree(target_logits, draft_logits, node_token, node_parent, seed, B, N, V, temperature,
                      entropy_threshold, out_accept_len, out_next_token, workspace, out_path=None, out_entropy=None,
-                     n_nodes=None, level=0, seq_base=0, target_ld=0, draft_ld=0, stream=None) -> None:
+                     n_nodes=None, level=0, seq_base=0, target_ld=0, draft_ld=0, stream=None, tuning=None) -> None:
     a = TreeArgs()
+    a.tuning = _tuning_ptr(tuning)
     a.target_logits, a.draft_logits, a.dtype = _ptr(target_logits), _ptr(draft_logits), _logit_dtype(target_logits)
     a.target_ld, a.draft_ld = int(target_ld), int(draft_ld)
     a.node_token, a.node_parent, a.n_nodes = _ptr(node_token), _ptr(node_parent), _ptr(n_nodes)

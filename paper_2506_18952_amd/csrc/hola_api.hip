@@ -49,19 +49,20 @@ __global__ void export_tokens_kernel(const int32_t* __restrict__ tok, int64_t to
 }
 
 // ---------------------------------------------------------------------------------------------
-// process-wide state
+// state: launch-shape defaults and the profiling aid belong to the calling thread (a call never sees another
+// thread's settings); the only process-wide state is the short forms' workspace per device, behind g_mu.
 // ---------------------------------------------------------------------------------------------
 static thread_local char g_last_hip[256] = "";
-static Tuning g_tuning;
+static thread_local Tuning g_tuning;
 static std::mutex g_mu;
 
 struct DeviceWs { void* ptr = nullptr; size_t bytes = 0; };
 static DeviceWs g_ws[64];
 
 struct ProfEvent { int stage; hipEvent_t a, b; };
-static bool g_prof_on = false;
-static std::vector<ProfEvent> g_prof_live;
-static std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_free;
+static thread_local bool g_prof_on = false;
+static thread_local std::vector<ProfEvent> g_prof_live;
+static thread_local std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_free;
 
 static hola_status hip_fail(hipError_t e, const char* what)
 {
@@ -74,7 +75,6 @@ struct StageTimer {
     StageTimer(int stage_, hipStream_t s_) : stage(stage_), s(s_), on(g_prof_on)
     {
         if (!on) return;
-        std::lock_guard<std::mutex> lk(g_mu);
         if (!g_prof_free.empty()) { a = g_prof_free.back().first; b = g_prof_free.back().second; g_prof_free.pop_back(); }
         else if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
         if (hipEventRecord(a, s) != hipSuccess) { g_prof_free.emplace_back(a, b); on = false; }
@@ -83,7 +83,6 @@ struct StageTimer {
     {
         if (!on) return;
         const bool timed = hipEventRecord(b, s) == hipSuccess;
-        std::lock_guard<std::mutex> lk(g_mu);
         if (timed) g_prof_live.push_back(ProfEvent{stage, a, b});
         else g_prof_free.emplace_back(a, b);
     }
@@ -117,7 +116,31 @@ static int auto_tail_waves(int32_t B, int64_t row_bytes)
 
 static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-static Workspace carve(void* base, int32_t B, int32_t gamma, int32_t V)
+static bool tuning_from(const hola_tuning* t, Tuning* out)
+{
+    Tuning n;
+    if (t) {
+        if (t->stats_split < 0 || t->stats_split > kMaxSplit) return false;
+        if (t->stats_unroll != 0 && t->stats_unroll != 2 && t->stats_unroll != 4 && t->stats_unroll != 8 && t->stats_unroll != 16)
+            return false;
+        if (t->path < 0 || t->path > 3) return false;
+        if (t->fused_waves != 0 && t->fused_waves != 4 && t->fused_waves != 8 && t->fused_waves != 16) return false;
+        if (t->filter_path < 0 || t->filter_path > 1) return false;
+        n.split = t->stats_split; n.unroll = t->stats_unroll; n.path = t->path; n.fused_waves = t->fused_waves;
+        n.filter_path = t->filter_path;
+    }
+    *out = n;
+    return true;
+}
+
+// Launch shape of one call: its own hola_tuning when given, else the calling thread's defaults.
+static bool call_tuning(const hola_tuning* t, Tuning* out)
+{
+    if (!t) { *out = g_tuning; return true; }
+    return tuning_from(t, out);
+}
+
+static Workspace carve(void* base, int32_t B, int32_t gamma, int32_t V, bool with_filters = true)
 {
     Workspace w;
     char* p = (char*)base;
@@ -130,9 +153,13 @@ static Workspace carve(void* base, int32_t B, int32_t gamma, int32_t V)
     w.argmaxP = (int32_t*)(p + off);  off = align_up(off + (size_t)B * (gamma + 1) * sizeof(int32_t));
     w.seq = (SeqInfo*)(p + off);      off = align_up(off + (size_t)B * sizeof(SeqInfo));
     w.tiles = (double*)(p + off);     off = align_up(off + (size_t)B * ntiles * sizeof(double));
-    w.filters = (RowFilter*)(p + off); off = align_up(off + rows * sizeof(RowFilter));
-    const size_t scan_bytes = filter_scan_bytes((int64_t)rows);
-    w.filter_scan = scan_bytes ? p + off : nullptr; off = align_up(off + scan_bytes);
+    w.filters = nullptr;
+    w.filter_scan = nullptr;
+    if (with_filters) {                                        // keep sets and candidate lists: filtered calls only
+        w.filters = (RowFilter*)(p + off); off = align_up(off + rows * sizeof(RowFilter));
+        const size_t scan_bytes = filter_scan_bytes((int64_t)rows);
+        w.filter_scan = scan_bytes ? p + off : nullptr; off = align_up(off + scan_bytes);
+    }
     w.bytes = off;
     return w;
 }
@@ -170,8 +197,9 @@ static hola_status check_args(const hola_verify_args& a, bool literal = false)
     }
     // Supplied target statistics carry no argmax, which greedy rows need.
     if (a.target_stats_in && (a.row_temperature || !(a.temperature > 0.f))) return HOLA_ERR_UNSUPPORTED;
+    if (a.tuning) { Tuning t; if (!tuning_from(a.tuning, &t)) return HOLA_ERR_INVALID_ARG; }
     if (!a.workspace || ((uintptr_t)a.workspace & 255)) return HOLA_ERR_WORKSPACE;
-    if (a.workspace_bytes < hola_workspace_bytes(a.B, a.gamma, a.V)) return HOLA_ERR_WORKSPACE;
+    if (a.workspace_bytes < carve(nullptr, a.B, a.gamma, a.V, filters_on(a)).bytes + 256) return HOLA_ERR_WORKSPACE;
     return HOLA_OK;
 }
 
@@ -189,12 +217,12 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     hola_status st = check_args(a);
     if (st != HOLA_OK || a.B == 0) return st;
     hipStream_t s = (hipStream_t)a.stream;
-    const Workspace w = carve(a.workspace, a.B, a.gamma, a.V);
+    const Workspace w = carve(a.workspace, a.B, a.gamma, a.V, filters_on(a));
     const int64_t tld = a.target_ld ? a.target_ld : a.V, dld = a.draft_ld ? a.draft_ld : a.V;
     const int skip_draft = a.draft_stats_in ? 1 : 0, skip_target = a.target_stats_in ? 1 : 0;
     const int64_t rows = (int64_t)a.B * ((skip_draft ? 0 : a.gamma) + (skip_target ? 0 : a.gamma + 1));
     Tuning tune;
-    { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
+    call_tuning(a.tuning, &tune);                             // validated by check_args
     const int nsplit = choose_split(rows > 0 ? rows : 1, a.V, a.dtype, tune);
 
     // Per-sequence parameters shared by the fused kernel and the tail kernel.
@@ -310,10 +338,10 @@ static hola_status run_literal(const hola_verify_args& a, int32_t* out_tokens, i
     if (a.draft_stats_in || a.target_stats_out || a.target_stats_in) return HOLA_ERR_UNSUPPORTED;
     if (!literal_supported(a.gamma, a.V, a.dtype)) return HOLA_ERR_UNSUPPORTED;
     hipStream_t s = (hipStream_t)a.stream;
-    const Workspace w = carve(a.workspace, a.B, a.gamma, a.V);
+    const Workspace w = carve(a.workspace, a.B, a.gamma, a.V, false);
     const int64_t tld = a.target_ld ? a.target_ld : a.V, dld = a.draft_ld ? a.draft_ld : a.V;
     Tuning tune;
-    { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
+    call_tuning(a.tuning, &tune);
     const int nsplit = choose_split((int64_t)a.B * (2 * a.gamma + 1), a.V, a.dtype, tune);
     RowStatsParams rs{};
     rs.target = a.target_logits; rs.draft = a.draft_logits; rs.target_ld = tld; rs.draft_ld = dld;
@@ -389,6 +417,12 @@ size_t hola_workspace_bytes(int32_t B, int32_t gamma, int32_t V)
 {
     if (!shape_ok(B, gamma, V)) return 0;
     return carve(nullptr, B, gamma, V).bytes + 256;
+}
+
+size_t hola_workspace_bytes_ex(const hola_verify_args* args)
+{
+    if (!args || !shape_ok(args->B, args->gamma, args->V)) return 0;
+    return carve(nullptr, args->B, args->gamma, args->V, filters_on(*args)).bytes + 256;
 }
 
 hola_status hola_verify_ex(const hola_verify_args* args)
@@ -524,6 +558,7 @@ hola_status hola_hsd_verify_ex(const hola_hsd_args* args)
         a.out_entropy = out_entropy ? out_entropy + (int64_t)(k - 1) * B * gmax : nullptr;
         a.entropy_ld = gmax;
         a.workspace = h.level; a.workspace_bytes = h.level_bytes; a.stream = stream;
+        a.tuning = args->tuning;
         LevelExtras x;
         x.tokens_ld = cur_ld;
         x.pad_entropy = 1;
@@ -583,7 +618,7 @@ hola_status hola_verify_tree(const hola_tree_args* args)
     Partial* partials = (Partial*)a.workspace;
     const int64_t tld = a.target_ld ? a.target_ld : a.V, dld = a.draft_ld ? a.draft_ld : a.V;
     Tuning tune;
-    { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
+    if (!call_tuning(a.tuning, &tune)) return HOLA_ERR_INVALID_ARG;
     const int64_t rows = (int64_t)a.B * (2 * (int64_t)a.N + 1);
     const int nsplit = choose_split(rows, a.V, a.dtype, tune);
 
@@ -622,11 +657,10 @@ hola_status hola_row_stats(const void* logits, int32_t dtype, int64_t ld, int32_
     if (ld && ld < V) return HOLA_ERR_INVALID_ARG;
     if ((uintptr_t)logits % (dtype == HOLA_DTYPE_BF16 ? 2 : 4)) return HOLA_ERR_INVALID_ARG;
     if (!workspace || ((uintptr_t)workspace & 255)) return HOLA_ERR_WORKSPACE;
-    if (workspace_bytes < hola_workspace_bytes(R, 1, V)) return HOLA_ERR_WORKSPACE;
+    if (workspace_bytes < carve(nullptr, R, 1, V, false).bytes + 256) return HOLA_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    const Workspace w = carve(workspace, R, 1, V);
-    Tuning tune;
-    { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
+    const Workspace w = carve(workspace, R, 1, V, false);
+    const Tuning tune = g_tuning;
     const int nsplit = choose_split(R, V, dtype, tune);
     // R plain rows are laid out as R "sequences" with no draft and one target row each.
     RowStatsParams rs{};
@@ -652,7 +686,7 @@ size_t hola_tile_stats_workspace_bytes(int32_t R, int32_t V, int32_t tile_cols)
     if (R < 0 || V < 1 || tile_cols < 1) return 0;
     const int64_t vr = (int64_t)R * tiles_of(V, tile_cols);
     if (vr > 0x7fffffffLL) return 0;
-    return hola_workspace_bytes((int32_t)vr, 1, tile_cols < V ? tile_cols : V);
+    return carve(nullptr, (int32_t)vr, 1, tile_cols < V ? tile_cols : V, false).bytes + 256;
 }
 
 hola_status hola_tile_stats(const void* logits, int32_t dtype, int64_t ld, int32_t R, int32_t V, int32_t tile_cols,
@@ -672,9 +706,8 @@ hola_status hola_tile_stats(const void* logits, int32_t dtype, int64_t ld, int32
     if (workspace_bytes < hola_tile_stats_workspace_bytes(R, V, tile_cols)) return HOLA_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     const int32_t tc = tile_cols < V ? tile_cols : V;
-    const Workspace w = carve(workspace, (int32_t)vr, 1, tc);
-    Tuning tune;
-    { std::lock_guard<std::mutex> lk(g_mu); tune = g_tuning; }
+    const Workspace w = carve(workspace, (int32_t)vr, 1, tc, false);
+    const Tuning tune = g_tuning;
     const int nsplit = choose_split(vr, tc, dtype, tune);
     RowStatsParams rs{};
     rs.target = logits; rs.draft = logits; rs.target_ld = ld ? ld : V; rs.draft_ld = rs.target_ld;
@@ -714,25 +747,14 @@ hola_status hola_copy_bytes(void* dst, const void* src, size_t bytes, hola_strea
 hola_status hola_set_tuning(const hola_tuning* t)
 {
     Tuning n;
-    if (t) {
-        if (t->stats_split < 0 || t->stats_split > kMaxSplit) return HOLA_ERR_INVALID_ARG;
-        if (t->stats_unroll != 0 && t->stats_unroll != 2 && t->stats_unroll != 4 && t->stats_unroll != 8 && t->stats_unroll != 16)
-            return HOLA_ERR_INVALID_ARG;
-        if (t->path < 0 || t->path > 3) return HOLA_ERR_INVALID_ARG;
-        if (t->fused_waves != 0 && t->fused_waves != 4 && t->fused_waves != 8 && t->fused_waves != 16) return HOLA_ERR_INVALID_ARG;
-        if (t->filter_path < 0 || t->filter_path > 1) return HOLA_ERR_INVALID_ARG;
-        n.split = t->stats_split; n.unroll = t->stats_unroll; n.path = t->path; n.fused_waves = t->fused_waves;
-        n.filter_path = t->filter_path;
-    }
-    std::lock_guard<std::mutex> lk(g_mu);
-    g_tuning = n;
+    if (!tuning_from(t, &n)) return HOLA_ERR_INVALID_ARG;
+    g_tuning = n;                                              // the calling thread's defaults
     return HOLA_OK;
 }
 
 hola_status hola_profile_enable(int32_t on)
 {
-    std::lock_guard<std::mutex> lk(g_mu);
-    g_prof_on = on != 0;
+    g_prof_on = on != 0;                                       // the calling thread's calls only
     return HOLA_OK;
 }
 
@@ -740,7 +762,7 @@ hola_status hola_profile_collect(double* ms_out, int64_t* launches_out)
 {
     if (!ms_out || !launches_out) return HOLA_ERR_INVALID_ARG;
     std::vector<ProfEvent> live;
-    { std::lock_guard<std::mutex> lk(g_mu); live.swap(g_prof_live); }
+    live.swap(g_prof_live);
     hola_status st = HOLA_OK;
     for (const ProfEvent& ev : live) {
         float ms = 0.f;
@@ -749,7 +771,6 @@ hola_status hola_profile_collect(double* ms_out, int64_t* launches_out)
         if (e != hipSuccess) st = hip_fail(e, "profile event");
         else if (ev.stage >= 0 && ev.stage < HOLA_N_STAGES) { ms_out[ev.stage] += ms; launches_out[ev.stage] += 1; }
     }
-    std::lock_guard<std::mutex> lk(g_mu);
     for (const ProfEvent& ev : live) g_prof_free.emplace_back(ev.a, ev.b);
     return st;
 }

@@ -50,6 +50,48 @@ def test_workspace_bytes():
     assert hb.hola_hsd_workspace_bytes(3, 8, 63, 100) == 0   # gamma grows past the limit
 
 
+def test_workspace_bytes_of_one_call():
+    """A call without filters does not pay for the filters' candidate lists."""
+    full = hb.hola_workspace_bytes(256, 8, 128256)
+    plain = hb.hola_workspace_bytes_ex(256, 8, 128256)
+    assert 0 < plain < 12 << 20 < full                       # ~9 MB of partial sums against ~82 MB
+    assert hb.hola_workspace_bytes_ex(256, 8, 128256, top_k=50) == full
+    assert hb.hola_workspace_bytes_ex(256, 8, 128256, top_p=0.9) == full
+    assert hb.hola_workspace_bytes_ex(256, 8, 128256, top_k=128256, top_p=1.0) == plain   # both filters off
+    assert hb.hola_workspace_bytes_ex(4, 0, 100) == 0 and hb.lib().hola_workspace_bytes_ex(None) == 0
+    a = _args(workspace_bytes=hb.hola_workspace_bytes_ex(4, 3, 100))
+    a.B = 0
+    assert hb.lib().hola_verify_ex(C.byref(a)) == hb.HOLA_OK
+    a = _args(workspace_bytes=hb.hola_workspace_bytes_ex(4, 3, 100) - 1)
+    assert hb.lib().hola_verify_ex(C.byref(a)) == hb.HOLA_ERR_WORKSPACE
+    a = _args(workspace_bytes=hb.hola_workspace_bytes_ex(4, 3, 100), top_k=5)      # a filtered call needs the larger one
+    assert hb.lib().hola_verify_ex(C.byref(a)) == hb.HOLA_ERR_WORKSPACE
+
+
+def test_tuning_of_one_call_is_validated():
+    for bad in (dict(stats_split=99), dict(stats_unroll=3), dict(path=7), dict(fused_waves=5), dict(filter_path=2)):
+        t = hb.Tuning(**bad)
+        a = _args(tuning=C.pointer(t))
+        assert hb.lib().hola_verify_ex(C.byref(a)) == hb.HOLA_ERR_INVALID_ARG
+        ta = _tree_args(tuning=C.pointer(t))
+        assert hb.lib().hola_verify_tree(C.byref(ta)) == hb.HOLA_ERR_INVALID_ARG
+
+
+def test_thread_defaults_do_not_leak_between_threads():
+    """hola_set_tuning acts on the calling thread alone: an invalid value is refused where it is set, and a second
+    thread starts from the built-in defaults whatever the first one chose."""
+    import threading
+    hb.hola_set_tuning(stats_split=4, path=hb.PATH_SPLIT4)
+    seen = {}
+
+    def other():
+        seen["status"] = hb.lib().hola_set_tuning(None)          # restoring defaults in this thread only
+    th = threading.Thread(target=other)
+    th.start(); th.join()
+    assert seen["status"] == hb.HOLA_OK
+    hb.hola_set_tuning()
+
+
 def _args(**kw):
     a = hb.VerifyArgs()
     fake = 0x1000                                             # never dereferenced: checks come first

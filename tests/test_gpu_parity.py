@@ -76,6 +76,46 @@ def cfg3():
     return wl.config3()
 
 
+def test_tuning_of_one_call_and_of_another_thread(cfg3):
+    """A call's own hola_tuning decides its launch shape whatever the thread's defaults are, and a thread's
+    defaults are invisible to other threads: every combination gives the decisions of the plain call."""
+    import threading
+    w = cfg3
+    sub = slice(0, 24)
+    P, D, tok = to_dev(w.target[sub]), to_dev(w.draft[sub]), to_dev(w.tokens[sub])
+    B, g, V = 24, w.gamma, w.V
+    tau = w.taus[0]
+    base = run_gpu_level(P, D, tok, w.seed, w.temperature, tau)
+
+    def call(tuning):
+        acc = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+        nxt = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+        ent = torch.full((B, g), -7.0, dtype=torch.float32, device=DEV)
+        ws = hb.alloc_workspace(hb.hola_workspace_bytes_ex(B, g, V), DEV)      # the smaller, per-call size
+        hb.hola_verify_ex(target_logits=P, draft_logits=D, draft_tokens=tok, seed=w.seed, B=B, gamma=g, V=V,
+                          temperature=w.temperature, entropy_threshold=tau, out_accept_len=acc, out_next_token=nxt,
+                          out_entropy=ent, workspace=ws, tuning=tuning)
+        torch.cuda.synchronize()
+        return acc.cpu().numpy(), nxt.cpu().numpy(), ent.cpu().numpy()
+
+    for tuning in (None, dict(path=hb.PATH_SPLIT, stats_split=4, stats_unroll=4, fused_waves=8), dict(path=hb.PATH_SPLIT4),
+                   dict(path=hb.PATH_FUSED, fused_waves=8)):
+        acc, nxt, ent = call(tuning)
+        np.testing.assert_array_equal(acc, base.accept_len)
+        np.testing.assert_array_equal(nxt, base.next_token)
+        np.testing.assert_allclose(ent, base.entropy, rtol=2e-6, atol=1e-6)
+    got = {}
+
+    def other_thread():
+        torch.cuda.set_device(0)
+        hb.hola_set_tuning(path=hb.PATH_SPLIT4, stats_split=8)                # this thread's defaults only
+        got["out"] = call(None)
+    th = threading.Thread(target=other_thread)
+    th.start(); th.join()
+    np.testing.assert_array_equal(got["out"][0], base.accept_len)
+    np.testing.assert_array_equal(got["out"][1], base.next_token)
+
+
 @pytest.mark.timeout(420)
 def test_config3_bf16_headline_full_size(cfg3):
     """B=256, gamma=8, V=128256 bf16, T=0.8 at three thresholds and with the gate off."""
