@@ -192,6 +192,19 @@ size_t hola_workspace_bytes_ex(const hola_verify_args* args /* host */);
 
 hola_status hola_verify_ex(const hola_verify_args* args /* host */);
 
+/* hola_verify_ex for callers that cannot allocate device memory and have no workspace to hand over: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  args->workspace and workspace_bytes
+ * are ignored; the workspace is an array of HOLA_STATIC_SCRATCH_BYTES in the library's device image (each GPU the
+ * library runs on holds its copy until the process ends).  The call allocates and frees nothing (keep the timing
+ * aid off: it creates events) and enqueues the same kernels as hola_verify_ex, so the outputs are bit-identical.
+ * HOLA_ERR_WORKSPACE when hola_workspace_bytes_ex(args) exceeds HOLA_STATIC_SCRATCH_BYTES (the headline shape
+ * B=256, gamma=8 needs 9 MB and fits; filtered calls need 16 KB more per logits row and fit up to ~900 rows);
+ * other errors as hola_verify_ex.  Nothing in the array has to start at zero and no call relies on what an
+ * earlier one left there, but every call on a GPU uses that GPU's one array: calls that overlap on a GPU (two
+ * streams, two threads) race on it. */
+enum { HOLA_STATIC_SCRATCH_BYTES = 16 << 20 };
+hola_status hola_verify_ex_static(const hola_verify_args* args /* host */);
+
 /* Equation (1) of the paper taken literally, as an alternative to steps 4-6: no ratio test and no stop.
  * For every drafted position t < len, y_t = the drafted token if H(draft_t) < tau, otherwise
  * f_ver(x, draft_<t): a draw from softmax(target_logits[b, t] / T) with the sampling uniform of position t

@@ -22,7 +22,7 @@ STAGE_NAMES = ("row_stats", "accept", "tile_sums", "select", "glue", "fused", "t
 
 EXPORTS = (
     "hola_verify_f32", "hola_verify_bf16", "hola_verify_ex", "hola_verify_literal_ex", "hola_workspace_bytes",
-    "hola_workspace_bytes_ex",
+    "hola_workspace_bytes_ex", "hola_verify_ex_static",
     "hola_hsd_verify", "hola_hsd_verify_ex", "hola_hsd_workspace_bytes", "hola_verify_tree",
     "hola_tree_workspace_bytes", "hola_row_stats", "hola_tile_stats",
     "hola_tile_stats_workspace_bytes", "hola_merge_tile_stats", "hola_set_tuning",
@@ -112,6 +112,8 @@ def lib() -> C.CDLL:
         L.hola_verify_f32.argtypes = short
         L.hola_verify_bf16.argtypes = short
         L.hola_verify_ex.argtypes = [C.POINTER(VerifyArgs)]
+        L.hola_verify_ex_static.argtypes = [C.POINTER(VerifyArgs)]
+        L.hola_verify_ex_static.restype = C.c_int32
         L.hola_verify_literal_ex.argtypes = [C.POINTER(VerifyArgs), C.c_void_p, C.c_void_p]
         L.hola_verify_literal_ex.restype = C.c_int32
         L.hola_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
@@ -240,7 +242,7 @@ def hola_verify_ex(*, target_logits, draft_logits, draft_tokens, seed, B, gamma,
                    out_accept_len, out_next_token, out_entropy=None, workspace, draft_len=None,
                    row_temperature=None, draft_stats_in=None, target_stats_out=None, target_stats_in=None, level=0,
                    seq_base=0, target_ld=0, draft_ld=0, entropy_ld=0, top_k=0, top_p=0.0, out_keep_count=None,
-                   stream=None, tuning=None) -> None:
+                   stream=None, tuning=None, _entry="hola_verify_ex") -> None:
     a = VerifyArgs()
     a.tuning = _tuning_ptr(tuning)
     a.target_logits, a.draft_logits = _ptr(target_logits), _ptr(draft_logits)
@@ -259,7 +261,16 @@ def hola_verify_ex(*, target_logits, draft_logits, draft_tokens, seed, B, gamma,
     a.workspace = _ptr(workspace)
     a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     a.stream = _stream_handle(stream)
-    _check(lib().hola_verify_ex(C.byref(a)), "hola_verify_ex")
+    _check(getattr(lib(), _entry)(C.byref(a)), _entry)
+
+
+HOLA_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def hola_verify_ex_static(**kw) -> None:
+    """hola_verify_ex on the library's static scratch array: same keyword arguments, no workspace."""
+    kw.setdefault("workspace", None)
+    hola_verify_ex(_entry="hola_verify_ex_static", **kw)
 
 
 def hola_verify_literal_ex(*, target_logits, draft_logits, draft_tokens, seed, B, gamma, V, temperature,

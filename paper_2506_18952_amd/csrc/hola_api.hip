@@ -50,7 +50,8 @@ __global__ void export_tokens_kernel(const int32_t* __restrict__ tok, int64_t to
 
 // ---------------------------------------------------------------------------------------------
 // state: launch-shape defaults and the profiling aid belong to the calling thread (a call never sees another
-// thread's settings); the only process-wide state is the short forms' workspace per device, behind g_mu.
+// thread's settings); the only process-wide state is the short forms' workspace per device and the address of
+// the static scratch array per device, both behind g_mu.
 // ---------------------------------------------------------------------------------------------
 static thread_local char g_last_hip[256] = "";
 static thread_local Tuning g_tuning;
@@ -407,6 +408,31 @@ static hola_status verify_short(const void* target, const void* draft, int dtype
     return run_level(a);
 }
 
+// ---------------------------------------------------------------------------------------------
+// The entry point that allocates nothing: its workspace is this array in the library's own device image.  In host
+// code the array's name is only a handle; the device address comes from hipGetSymbolAddress, once per device
+// (every GPU holds its own copy at its own address), and is what the kernels are given.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[HOLA_STATIC_SCRATCH_BYTES];
+static void* g_scratch_addr[64];                             // per device, behind g_mu
+
+static hola_status static_scratch(void** out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= 64) return HOLA_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_scratch_addr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_addr[dev] = ptr;
+    }
+    *out = g_scratch_addr[dev];
+    return HOLA_OK;
+}
+
 }  // namespace hola
 
 using namespace hola;
@@ -429,6 +455,20 @@ hola_status hola_verify_ex(const hola_verify_args* args)
 {
     if (!args) return HOLA_ERR_INVALID_ARG;
     return run_level(*args);
+}
+
+hola_status hola_verify_ex_static(const hola_verify_args* args)
+{
+    if (!args) return HOLA_ERR_INVALID_ARG;
+    hola_verify_args a = *args;
+    a.workspace = (void*)(uintptr_t)256; a.workspace_bytes = (size_t)-1;   // argument errors first; the fields are ignored
+    hola_status st = check_args(a);
+    if (st != HOLA_OK || a.B == 0) return st;
+    if (hola_workspace_bytes_ex(&a) > (size_t)HOLA_STATIC_SCRATCH_BYTES) return HOLA_ERR_WORKSPACE;
+    st = static_scratch(&a.workspace);
+    if (st != HOLA_OK) return st;
+    a.workspace_bytes = (size_t)HOLA_STATIC_SCRATCH_BYTES;
+    return run_level(a);                                       // kernels only: every partial a call reads it has written
 }
 
 hola_status hola_verify_literal_ex(const hola_verify_args* args, int32_t* out_tokens, int32_t* out_verifier_calls)
