@@ -336,15 +336,28 @@ hola_status hola_merge_tile_stats(const double* tile_stats /* device [R, ntiles,
  * 3 inverse-CDF select, 4 level glue / tile merge, 5 fused per-sequence kernel, 6 per-sequence tail kernel,
  * 7 top-k / top-p keep sets by the per-row kernel (every row, or those the next two left), 8 candidate scan,
  * 9 per-row decide step. */
-enum { HOLA_N_STAGES = 10 };
+enum { HOLA_N_STAGES = 11 };      /* stage 10: the read probe below */
 hola_status hola_profile_enable(int32_t on);
 hola_status hola_profile_collect(double* ms_out /* host [HOLA_N_STAGES] */, int64_t* launches_out /* host [HOLA_N_STAGES] */);
+/* The same per launch instead of per stage: for the i-th kernel recorded since the last collect, its stage and its
+ * elapsed milliseconds (i < capacity; later ones are dropped); *n_out = kernels recorded.  Forgets the events. */
+hola_status hola_profile_collect_launches(int32_t* stage_out /* host [capacity] */, float* ms_out /* host [capacity] */,
+                                          int64_t capacity, int64_t* n_out /* host */);
 
 /* A plain copy kernel (16-byte vector loads and stores, nothing else): bytes of device memory from src
  * to dst, bytes a multiple of 16, both 16-byte aligned.  It is not part of the verify step; it exists so
  * that hardware byte counters read for the verify kernels (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) can
  * be scaled against a transfer of known size measured the same way. */
 hola_status hola_copy_bytes(void* dst /* device */, const void* src /* device */, size_t bytes, hola_stream_t stream);
+
+/* A read-only streaming kernel (not part of the verify step): reads `bytes` of device memory once, in 16-byte
+ * loads, with the launch shape of the statistics pass (workgroups of 256 threads, each over block_bytes contiguous
+ * bytes, eight loads in flight per lane), and keeps nothing.  nontemporal != 0: the loads carry the non-temporal
+ * hint the statistics pass uses; arithmetic != 0: every 16 bytes also go through the arithmetic that pass performs
+ * on eight bf16 logits (24 FMAs, 8 exp2, 7 adds, a running maximum, 2 double adds).  Its rate is the practical
+ * ceiling the benchmark quotes beside the published HBM peak.  bytes a multiple of 16, src 16-byte aligned. */
+hola_status hola_read_probe(const void* src /* device */, size_t bytes, size_t block_bytes, int32_t nontemporal,
+                            int32_t arithmetic, hola_stream_t stream);
 
 /* Frees the library-owned workspaces of every device and the calling thread's profiling events. */
 void hola_shutdown(void);

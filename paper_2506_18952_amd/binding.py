@@ -16,9 +16,9 @@ LIB_PATH = os.path.join(_HERE, "libhola.so")
 
 HOLA_OK, HOLA_ERR_INVALID_ARG, HOLA_ERR_UNSUPPORTED, HOLA_ERR_WORKSPACE, HOLA_ERR_HIP = range(5)
 HOLA_DTYPE_F32, HOLA_DTYPE_BF16 = 0, 1
-HOLA_N_STAGES = 10
+HOLA_N_STAGES = 11
 STAGE_NAMES = ("row_stats", "accept", "tile_sums", "select", "glue", "fused", "tail", "filter", "filter_scan",
-               "filter_decide")
+               "filter_decide", "read_probe")
 
 EXPORTS = (
     "hola_verify_f32", "hola_verify_bf16", "hola_verify_ex", "hola_verify_literal_ex", "hola_workspace_bytes",
@@ -26,7 +26,7 @@ EXPORTS = (
     "hola_hsd_verify", "hola_hsd_verify_ex", "hola_hsd_workspace_bytes", "hola_verify_tree",
     "hola_tree_workspace_bytes", "hola_row_stats", "hola_tile_stats",
     "hola_tile_stats_workspace_bytes", "hola_merge_tile_stats", "hola_set_tuning",
-    "hola_profile_enable", "hola_profile_collect", "hola_copy_bytes", "hola_shutdown", "hola_status_string",
+    "hola_profile_enable", "hola_profile_collect", "hola_profile_collect_launches", "hola_copy_bytes", "hola_read_probe", "hola_shutdown", "hola_status_string",
     "hola_last_hip_error", "hola_version",
 )
 
@@ -146,6 +146,10 @@ def lib() -> C.CDLL:
         L.hola_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.hola_copy_bytes.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.hola_copy_bytes.restype = C.c_int32
+        L.hola_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_size_t, C.c_int32, C.c_int32, C.c_void_p]
+        L.hola_read_probe.restype = C.c_int32
+        L.hola_profile_collect_launches.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int64, C.POINTER(C.c_int64)]
+        L.hola_profile_collect_launches.restype = C.c_int32
         L.hola_shutdown.argtypes = []
         L.hola_shutdown.restype = None
         for name in ("hola_status_string", "hola_last_hip_error", "hola_version"):
@@ -398,6 +402,21 @@ def hola_profile_collect() -> tuple[list[float], list[int]]:
     n = (C.c_int64 * HOLA_N_STAGES)()
     _check(lib().hola_profile_collect(ms, n), "hola_profile_collect")
     return list(ms), list(n)
+
+
+def hola_profile_collect_launches(capacity: int = 1 << 16) -> list[tuple[int, float]]:
+    """(stage, milliseconds) of every kernel recorded since the last collect, in launch order."""
+    st = (C.c_int32 * capacity)()
+    ms = (C.c_float * capacity)()
+    n = C.c_int64(0)
+    _check(lib().hola_profile_collect_launches(st, ms, capacity, C.byref(n)), "hola_profile_collect_launches")
+    k = min(int(n.value), capacity)
+    return [(int(st[i]), float(ms[i])) for i in range(k)]
+
+
+def hola_read_probe(src, nbytes: int, block_bytes: int, nontemporal: bool = True, arithmetic: bool = False, stream=None) -> None:
+    _check(lib().hola_read_probe(_ptr(src), int(nbytes), int(block_bytes), 1 if nontemporal else 0, 1 if arithmetic else 0,
+                                 _stream_handle(stream)), "hola_read_probe")
 
 
 def hola_copy_bytes(dst, src, nbytes: int, stream=None) -> None:

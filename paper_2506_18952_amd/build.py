@@ -8,7 +8,7 @@ import sys
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libhola.so")
-SOURCES = ["hola_api.hip", "row_stats.hip", "accept.hip", "sampler.hip", "fused.hip", "literal.hip", "filter.hip", "filter_scan.hip", "tree.hip"]
+SOURCES = ["hola_api.hip", "row_stats.hip", "accept.hip", "sampler.hip", "fused.hip", "literal.hip", "filter.hip", "filter_scan.hip", "tree.hip", "probe.hip"]
 HEADERS = ["hola_internal.h", "device_common.h", "stats_device.h", "sampler_device.h", "accept_device.h", "filter_device.h", os.path.join("..", "..", "include", "hola.h")]
 
 # Packed-fp32 instruction selection is switched off for every device compile.

@@ -32,12 +32,38 @@ __device__ __forceinline__ bool filter_keeps(float x, int32_t i, float theta, in
     return x > theta || (x == theta && i <= idx_cut);
 }
 
-// Called by all 64 lanes of one wavefront.  sd / sp: statistics of draft row j (valid for j < len) and
-// target row j (valid for j <= len).  Writes accept_len, the entropies, the optional target statistics
-// and, for greedy rows, the next token; the lane at the stop row fills *si_out.
+// What lane j needs from memory for its position, none of which depends on the row statistics: the drafted token
+// and, on stochastic rows, its logit in both models.  Kept apart from the decision so that a caller can have these
+// loads in flight while the statistics are still being merged.
+struct TokenGather {
+    int32_t x;                         // drafted token (-1 beyond len)
+    float xp, xq;                      // its target and draft logits (0 where not loaded)
+};
+
 template <bool BF16>
-__device__ __forceinline__ void accept_wave(const AcceptCtx& c, int b, int j, int len, float Tb,
-                                            const RowStat& sd_in, const RowStat& sp_in, SeqInfo* si_out)
+__device__ __forceinline__ TokenGather accept_gather(const AcceptCtx& c, int b, int j, int len, float Tb)
+{
+    TokenGather t;
+    t.x = -1; t.xp = 0.f; t.xq = 0.f;
+    const int g = c.gamma;
+    if (j < len) {
+        t.x = c.tokens[(int64_t)b * c.tokens_ld + j];
+        if (Tb > 0.f && t.x >= 0 && t.x < c.V) {
+            t.xp = load_logit<BF16>(c.target, ((int64_t)b * (g + 1) + j) * c.target_ld + t.x);
+            t.xq = load_logit<BF16>(c.draft, ((int64_t)b * g + j) * c.draft_ld + t.x);
+        }
+    }
+    return t;
+}
+
+// Called by all 64 lanes of one wavefront.  sd / sp: statistics of draft row j (valid for j < len) and
+// target row j (valid for j <= len); tg: what accept_gather returned for this lane.  Writes accept_len, the
+// entropies, the optional target statistics and, for greedy rows, the next token; the lane at the stop row fills
+// *si_out.
+template <bool BF16>
+__device__ __forceinline__ void accept_decide(const AcceptCtx& c, int b, int j, int len, float Tb,
+                                              const RowStat& sd_in, const RowStat& sp_in, const TokenGather& tg,
+                                              SeqInfo* si_out)
 {
     const int g = c.gamma;
     RowStat sd = sd_in, sp = sp_in;
@@ -70,20 +96,18 @@ __device__ __forceinline__ void accept_wave(const AcceptCtx& c, int b, int j, in
     bool reject = false;
     if (j < len) {
         const bool gate = sd.H < tau;                   // strict; NaN never gates
-        const int32_t x = c.tokens[(int64_t)b * c.tokens_ld + j];
+        const int32_t x = tg.x;
         bool ok;
         if (greedy) {
             ok = (x == sp.argmax);
         } else {
             double p_x = 0.0, q_x = 1.0;
             if (x >= 0 && x < c.V) {
-                const float xp = load_logit<BF16>(c.target, ((int64_t)b * (g + 1) + j) * c.target_ld + x);
-                const float xq = load_logit<BF16>(c.draft, ((int64_t)b * g + j) * c.draft_ld + x);
-                p_x = exp((double)xp * invT - sp.lse);
-                q_x = exp((double)xq * invT - sd.lse);
+                p_x = exp((double)tg.xp * invT - sp.lse);
+                q_x = exp((double)tg.xq * invT - sd.lse);
                 if (c.filters) {
-                    if (!filter_keeps(xp, x, thP, cutP)) p_x = 0.0;
-                    if (!filter_keeps(xq, x, thD, cutD)) q_x = 0.0;
+                    if (!filter_keeps(tg.xp, x, thP, cutP)) p_x = 0.0;
+                    if (!filter_keeps(tg.xq, x, thD, cutD)) q_x = 0.0;
                 }
             }
             const Philox4 r = philox4x32_10((uint32_t)j, (uint32_t)seq, (uint32_t)(seq >> 32), c.level,
@@ -115,6 +139,15 @@ __device__ __forceinline__ void accept_wave(const AcceptCtx& c, int b, int j, in
         }
         *si_out = si;
     }
+}
+
+// Gather and decision in one step.
+template <bool BF16>
+__device__ __forceinline__ void accept_wave(const AcceptCtx& c, int b, int j, int len, float Tb,
+                                            const RowStat& sd, const RowStat& sp, SeqInfo* si_out)
+{
+    const TokenGather tg = accept_gather<BF16>(c, b, j, len, Tb);
+    accept_decide<BF16>(c, b, j, len, Tb, sd, sp, tg, si_out);
 }
 
 }  // namespace hola

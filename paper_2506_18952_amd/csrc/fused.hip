@@ -128,14 +128,73 @@ __device__ __forceinline__ void write_glue(const FusedParams& p, int b, int a, i
     if (threadIdx.x == 0) p.glue_len[b] = a + (p.glue_keep_next ? 1 : 0);
 }
 
-// Accept stage (wavefront 0) and sampling (all wavefronts) of sequence b, given sh.stat[].
-// Called by every thread of the workgroup, after a barrier that made sh.stat visible.
+// Bonus draw from one slab of the row, decided before the accept stage has run.  On the row a bonus token would come
+// from (target row len) every split-row partial is the mass of one contiguous slab of tokens, in index order, so the
+// slab that holds the draw follows from the partials and the sampling uniform of position len alone; neither depends
+// on the accept stage, so one wavefront does this while the others merge statistics and gather the drafted tokens'
+// logits, and the slab can be swept while the accept stage decides.  If the sequence turns out rejected, the work
+// is dropped.  Called by one whole wavefront; fills sh.slab_*.
+template <bool BF16>
+__device__ __forceinline__ void pick_bonus_slab(const FusedParams& p, SeqShared& sh, int b, int len,
+                                                const Partial* __restrict__ parts, int nparts, int lane)
+{
+    constexpr int ES = BF16 ? 2 : 4;
+    const int g = p.gamma;
+    int ok = 0;
+    int64_t lo = 0, hi = 0;
+    double frac = 0.0;
+    const RowGeom geo = make_geom<BF16>((const char*)p.target + ((int64_t)b * (g + 1) + len) * p.target_ld * ES, p.V);
+    if (geo.edge_lo_end == 0 && geo.edge_hi_begin == p.V) {        // no ragged ends: the slabs are all of the row
+        const uint64_t seq = (uint64_t)(p.seq_base + b);
+        const Philox4 r = philox4x32_10((uint32_t)len, (uint32_t)seq, (uint32_t)(seq >> 32), p.level,
+                                        (uint32_t)p.seed, (uint32_t)(p.seed >> 32));
+        const double u = (double)u24(r.y);                         // the sampling uniform of position len
+        const Partial* ps = parts + ((int64_t)p.B * g + (int64_t)b * (g + 1) + len) * nparts;
+        double S = 0.0, br = 0.0;
+        if (lane < nparts) { S = ps[lane].S; br = ps[lane].bref; }
+        const bool has = S > 0.0 && S < INFINITY;
+        const double bmin = wave_min(has ? br : (double)INFINITY);
+        const double W = has ? S * exp2(bmin - br) : 0.0;          // the slab's mass against a common reference
+        const double incl = wave_inclusive_scan(W, lane);
+        const double Z = __shfl(incl, 63, 64);
+        const double target = u * Z;
+        const unsigned long long hit = __ballot(incl > target);
+        const int src = hit ? __ffsll((long long)hit) - 1 : 0;
+        const double w_src = __shfl(W, src, 64), excl = __shfl(incl - W, src, 64);
+        ok = (Z > 0.0 && Z < INFINITY && hit && w_src > 0.0) ? 1 : 0;
+        frac = ok ? (target - excl) / w_src : 0.0;
+        frac = frac < 0.0 ? 0.0 : (frac > 0.999999999 ? 0.999999999 : frac);
+        int64_t seg_lo, seg_hi;
+        wave_slab(geo, src / kWaves, nparts / kWaves, src % kWaves, seg_lo, seg_hi, lo, hi);
+        if (hi <= lo) ok = 0;
+    }
+    if (lane == 0) { sh.slab_lo = lo; sh.slab_hi = hi; sh.slab_u = frac; sh.slab_ok = ok; }
+}
+
+// A row pair narrowed to the chunks [lo, hi) of the target row, as a row of its own (bonus weights only).
+template <bool BF16>
+__device__ __forceinline__ void narrow_to_slab(RowPair& rp, int64_t lo, int64_t hi)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    rp.Pv += lo;                                                   // head is 0 on rows that have slabs
+    rp.nchunks = hi - lo;
+    rp.V = (int32_t)((hi - lo) * N);
+}
+
+// Accept stage (wavefront 0) and sampling (all wavefronts) of sequence b, given sh.stat[] and, in wavefront 0, the
+// gathered token logits tg.  Called by every thread of the workgroup, after a barrier that made sh.stat (and, with
+// pre_slab, sh.slab_*) visible.  pre_slab: pick_bonus_slab has run; while wavefront 0 decides, the others sweep the
+// slab it chose, so that a sequence whose drafts are all kept finds its tile weights ready.
 template <bool BF16, int NW, bool FILT = false>
 __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& sh, int b, int len, float Tb,
-                                              const Partial* __restrict__ parts = nullptr, int nparts = 0)
+                                              const TokenGather& tg, bool pre_slab = false)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = p.gamma;
+    constexpr int N = BF16 ? 8 : 4;
+    const bool slab_ready = pre_slab && sh.slab_ok;                 // uniform over the workgroup
+    const int64_t slab_lo = slab_ready ? sh.slab_lo : 0, slab_hi = slab_ready ? sh.slab_hi : 0;
+    const int slab_tiles = (int)((slab_hi - slab_lo + 64 * kTileChunks - 1) / (64 * kTileChunks));
     if (wave == 0) {
         const int j = lane;
         RowStat sd = {NAN, NAN, -1}, sp = {NAN, NAN, -1};
@@ -156,7 +215,24 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
             }
         }
         const AcceptCtx c = accept_ctx(p);
-        accept_wave<BF16>(c, b, j, len, Tb, sd, sp, &sh.si);
+        accept_decide<BF16>(c, b, j, len, Tb, sd, sp, tg, &sh.si);
+    } else if (slab_ready) {
+        // the slab's tile weights as bonus weights of target row len, by the wavefronts that do not decide
+        SeqInfo sb;
+        sb.lseP = sh.stat[g + len].lse; sb.lseD = 0.0; sb.u = 0.f; sb.row = len; sb.mode = 1; sb.greedy_tok = -1;
+        RowPair rq;
+        make_row_pair<BF16>(rq, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, sb, 0, nullptr, p.B);
+        if (rq.ok) {
+            narrow_to_slab<BF16>(rq, slab_lo, slab_hi);
+            for (int t = wave - 1; t < slab_tiles; t += 2 * (NW - 1)) {
+                double w0 = 0.0, w1 = 0.0;
+                tile_weight2<BF16, false>(rq, t, t + (NW - 1), lane, w0, w1);
+                if (lane == 0) {
+                    sh.tiles[t] = w0;
+                    if (t + (NW - 1) < slab_tiles) sh.tiles[t + (NW - 1)] = w1;
+                }
+            }
+        }
     }
     __syncthreads();
     const SeqInfo si = sh.si;
@@ -168,53 +244,16 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
     RowPair rp;
     make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0, FILT ? p.filters : nullptr, p.B);
 
-    // ---- bonus token with the split-row partials at hand: on that row every partial is the mass of one contiguous
-    // slab of tokens (in index order), so the slab that holds the draw follows from the partials alone and only it is
-    // read again, an eighth of the row or less.  The place inside the slab is handed on as a fraction of its mass.
-    constexpr int N = BF16 ? 8 : 4;
-    constexpr int ES = BF16 ? 2 : 4;
     int ntiles = p.ntiles;
     int32_t tok_off = 0;
     double u_eff = (double)si.u;
     bool slab_mode = false;
-    if (!FILT && parts != nullptr && nparts >= 4 && si.mode == 1 && rp.ok && si.row == len) {   // uniform over the workgroup
-        const RowGeom geo = make_geom<BF16>((const char*)p.target + ((int64_t)b * (g + 1) + si.row) * p.target_ld * ES, p.V);
-        if (geo.edge_lo_end == 0 && geo.edge_hi_begin == p.V) {    // no ragged ends: the slabs are all of the row
-            if (wave == 0) {
-                const Partial* ps = parts + ((int64_t)p.B * g + (int64_t)b * (g + 1) + si.row) * nparts;
-                double S = 0.0, br = 0.0;
-                if (lane < nparts) { S = ps[lane].S; br = ps[lane].bref; }
-                const bool has = S > 0.0 && S < INFINITY;
-                double bmin = has ? br : INFINITY;
-#pragma unroll
-                for (int m = 32; m >= 1; m >>= 1) bmin = fmin(bmin, __shfl_xor(bmin, m, 64));
-                const double W = has ? S * exp2(bmin - br) : 0.0;   // the slab's mass against a common reference
-                const double incl = wave_inclusive_scan(W, lane);
-                const double Z = __shfl(incl, 63, 64);
-                const double target = u_eff * Z;
-                const unsigned long long hit = __ballot(incl > target);
-                const int src = hit ? __ffsll((long long)hit) - 1 : 0;
-                const double w_src = __shfl(W, src, 64), excl = __shfl(incl - W, src, 64);
-                int ok = (Z > 0.0 && Z < INFINITY && hit && w_src > 0.0) ? 1 : 0;
-                double frac = ok ? (target - excl) / w_src : 0.0;
-                frac = frac < 0.0 ? 0.0 : (frac > 0.999999999 ? 0.999999999 : frac);
-                int64_t seg_lo, seg_hi, lo, hi;
-                wave_slab(geo, src / kWaves, nparts / kWaves, src % kWaves, seg_lo, seg_hi, lo, hi);
-                if (hi <= lo) ok = 0;
-                if (lane == 0) { sh.slab_lo = lo; sh.slab_hi = hi; sh.slab_u = frac; sh.slab_ok = ok; }
-            }
-            __syncthreads();
-            if (sh.slab_ok) {
-                slab_mode = true;
-                const int64_t lo = sh.slab_lo, hi = sh.slab_hi;
-                rp.Pv += lo;                                     // the slab as a row of its own (head is 0 here)
-                rp.nchunks = hi - lo;
-                rp.V = (int32_t)((hi - lo) * N);
-                tok_off = (int32_t)(lo * N);
-                ntiles = (int)((hi - lo + 64 * kTileChunks - 1) / (64 * kTileChunks));
-                u_eff = sh.slab_u;
-            }
-        }
+    if (slab_ready && si.mode == 1 && rp.ok && si.row == len) {  // every draft kept: the slab's tiles are there
+        slab_mode = true;
+        narrow_to_slab<BF16>(rp, slab_lo, slab_hi);
+        tok_off = (int32_t)(slab_lo * N);
+        ntiles = slab_tiles;
+        u_eff = sh.slab_u;
     }
 
     // ---- filtered call whose stop row's keep set is at hand as a short list: no sweep of the row at all
@@ -241,16 +280,18 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
             make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1, FILT ? p.filters : nullptr, p.B);
             continue;
         }
-        // tile weights of the stop row: two tiles per round trip and wavefront
-        for (int t = wave; t < ntiles; t += 2 * NW) {
-            double w0 = 0.0, w1 = 0.0;
-            if (rp.ok) tile_weight2<BF16, FILT>(rp, t, t + NW, lane, w0, w1);
-            if (lane == 0) {
-                sh.tiles[t] = w0;
-                if (t + NW < ntiles) sh.tiles[t + NW] = w1;
+        if (!(slab_mode && attempt == 0)) {
+            // tile weights of the stop row: two tiles per round trip and wavefront
+            for (int t = wave; t < ntiles; t += 2 * NW) {
+                double w0 = 0.0, w1 = 0.0;
+                if (rp.ok) tile_weight2<BF16, FILT>(rp, t, t + NW, lane, w0, w1);
+                if (lane == 0) {
+                    sh.tiles[t] = w0;
+                    if (t + NW < ntiles) sh.tiles[t + NW] = w1;
+                }
             }
+            __syncthreads();
         }
-        __syncthreads();
         if (wave == 0) {
             const int32_t tk = rp.ok ? select_token<BF16, true, FILT>(rp, sh.tiles, ntiles, u_eff, lane) : -1;
             if (lane == 0) sh.tok = tk;
@@ -327,11 +368,16 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedParams p)
         const RowStat rs = merge_partials_wave(&s_part[r][0], NW, lane);
         if (lane == 0) sh.stat[r] = rs;
     }
+    TokenGather tg = {-1, 0.f, 0.f};
+    if (wave == 0) tg = accept_gather<BF16>(accept_ctx(p), b, lane, len, Tb);
     __syncthreads();
-    sequence_tail<BF16, NW>(p, sh, b, len, Tb);
+    sequence_tail<BF16, NW>(p, sh, b, len, Tb, tg);
 }
 
-// Accept + sampling of one sequence from the row partials of the split-row kernel.
+// Accept + sampling of one sequence from the row partials of the split-row kernel.  What does not depend on the
+// statistics is started first and by wavefronts of its own, so that the memory round trips of a sequence overlap
+// instead of following one another: wavefront 0 fetches the drafted tokens and their logits, the last wavefront
+// picks the slab a bonus token would come from, the ones between merge the rows' partials.
 template <bool BF16, int NW, bool FILT = false>
 __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Partial* __restrict__ partials, int nparts)
 {
@@ -344,21 +390,30 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
     const float Tb = p.row_temperature ? p.row_temperature[b] : p.temperature;
     const int first_row = p.draft_stats_in ? g : 0;
     const int end_row = (p.target_stats_in || FILT) ? g : 2 * g + 1;   // supplied or filtered statistics are not merged here
-    // `width` lanes per row (one lane per partial), 64 / width rows per wavefront
-    int width = 4;
-    while (width < nparts) width <<= 1;
-    const int per_wave = 64 / width, seg = lane / width, sl = lane % width;
-    for (int r0 = (FILT ? g : first_row) + wave * per_wave; r0 < end_row; r0 += NW * per_wave) {
-        const int r = r0 + seg;
-        const bool is_draft = r < g;
-        const int j = is_draft ? r : r - g;
-        const bool need = r < end_row && (is_draft ? (j < len) : (j <= len));
-        const int64_t slot = is_draft ? (int64_t)b * g + j : (int64_t)p.B * g + (int64_t)b * (g + 1) + j;
-        const RowStat s = merge_partials_seg(need ? partials + slot * nparts : nullptr, nparts, sl, width);
-        if (need && sl == 0) sh.stat[r] = s;
+    const bool pre_slab = !FILT && !p.target_stats_in && nparts >= 4 && Tb > 0.f;
+    TokenGather tg = {-1, 0.f, 0.f};
+    if (wave == 0) {
+        tg = accept_gather<BF16>(accept_ctx(p), b, lane, len, Tb);
+    } else if (wave == NW - 1 && pre_slab) {
+        pick_bonus_slab<BF16>(p, sh, b, len, partials, nparts, lane);
+    } else {
+        // `width` lanes per row (one lane per partial), 64 / width rows per wavefront
+        const int mergers = pre_slab ? NW - 2 : NW - 1, mw = wave - 1;
+        int width = 4;
+        while (width < nparts) width <<= 1;
+        const int per_wave = 64 / width, seg = lane / width, sl = lane % width;
+        for (int r0 = (FILT ? g : first_row) + mw * per_wave; r0 < end_row; r0 += mergers * per_wave) {
+            const int r = r0 + seg;
+            const bool is_draft = r < g;
+            const int j = is_draft ? r : r - g;
+            const bool need = r < end_row && (is_draft ? (j < len) : (j <= len));
+            const int64_t slot = is_draft ? (int64_t)b * g + j : (int64_t)p.B * g + (int64_t)b * (g + 1) + j;
+            const RowStat s = merge_partials_seg(need ? partials + slot * nparts : nullptr, nparts, sl, width);
+            if (need && sl == 0) sh.stat[r] = s;
+        }
     }
     __syncthreads();
-    sequence_tail<BF16, NW, FILT>(p, sh, b, len, Tb, p.target_stats_in ? nullptr : partials, nparts);
+    sequence_tail<BF16, NW, FILT>(p, sh, b, len, Tb, tg, pre_slab);
 }
 
 bool fused_supported(int32_t gamma, int32_t V, int dtype)

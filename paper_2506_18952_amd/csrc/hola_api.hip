@@ -784,6 +784,16 @@ hola_status hola_copy_bytes(void* dst, const void* src, size_t bytes, hola_strea
     return e == hipSuccess ? HOLA_OK : hip_fail(e, "copy launch");
 }
 
+hola_status hola_read_probe(const void* src, size_t bytes, size_t block_bytes, int32_t nontemporal, int32_t arithmetic,
+                            hola_stream_t stream)
+{
+    if (bytes == 0) return HOLA_OK;
+    if (!src || (bytes & 15) || ((uintptr_t)src & 15) || block_bytes < 16 || block_bytes > ((size_t)1 << 40)) return HOLA_ERR_INVALID_ARG;
+    hipError_t e;
+    { StageTimer t(10, (hipStream_t)stream); e = launch_read_probe(src, bytes, (int64_t)block_bytes, nontemporal, arithmetic, (hipStream_t)stream); }
+    return e == hipSuccess ? HOLA_OK : hip_fail(e, "read probe launch");
+}
+
 hola_status hola_set_tuning(const hola_tuning* t)
 {
     Tuning n;
@@ -811,6 +821,26 @@ hola_status hola_profile_collect(double* ms_out, int64_t* launches_out)
         if (e != hipSuccess) st = hip_fail(e, "profile event");
         else if (ev.stage >= 0 && ev.stage < HOLA_N_STAGES) { ms_out[ev.stage] += ms; launches_out[ev.stage] += 1; }
     }
+    for (const ProfEvent& ev : live) g_prof_free.emplace_back(ev.a, ev.b);
+    return st;
+}
+
+hola_status hola_profile_collect_launches(int32_t* stage_out, float* ms_out, int64_t capacity, int64_t* n_out)
+{
+    if (!stage_out || !ms_out || !n_out || capacity < 0) return HOLA_ERR_INVALID_ARG;
+    std::vector<ProfEvent> live;
+    live.swap(g_prof_live);
+    hola_status st = HOLA_OK;
+    int64_t n = 0;
+    for (const ProfEvent& ev : live) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(ev.b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.a, ev.b);
+        if (e != hipSuccess) { st = hip_fail(e, "profile event"); continue; }
+        if (n < capacity) { stage_out[n] = ev.stage; ms_out[n] = ms; }
+        ++n;
+    }
+    *n_out = n;
     for (const ProfEvent& ev : live) g_prof_free.emplace_back(ev.a, ev.b);
     return st;
 }
@@ -846,6 +876,6 @@ const char* hola_status_string(hola_status s)
 }
 
 const char* hola_last_hip_error(void) { return g_last_hip; }
-const char* hola_version(void) { return "hola-verify 0.1 (gfx950)"; }
+const char* hola_version(void) { return "hola-verify 0.2 (gfx950)"; }
 
 }  // extern "C"

@@ -175,6 +175,9 @@ hipError_t launch_finalize_rows(const Partial* partials, int nparts, int32_t R, 
 hipError_t launch_tile_sums(const SamplerParams& p, hipStream_t s);
 hipError_t launch_select(const SamplerParams& p, hipStream_t s);
 
+// Read-only streaming probe (measurement aid): workgroups of kBlock threads, each over block_bytes of src.
+hipError_t launch_read_probe(const void* src, size_t bytes, int64_t block_bytes, int nontemporal, int arith, hipStream_t s);
+
 int choose_split(int64_t rows, int V, int dtype, const Tuning& t);
 int sampler_tiles(int V, int dtype);
 

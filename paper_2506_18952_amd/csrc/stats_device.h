@@ -150,6 +150,36 @@ __device__ __forceinline__ void accum_chunk(LaneState& st, const uint4& v, int32
     if (WITH_T) st.Td += (double)(t[0] + t[1]);
 }
 
+// The sums of one chunk's terms against the lane's reference, added to its state; no trigger.
+template <bool BF16, bool WITH_T>
+__device__ __forceinline__ void accum_chunk_terms(LaneState& st, const uint4& v, const ExpScale& sc)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    float e[N], t[2] = {0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const float y = exp_arg<BF16>(chunk_elem<BF16>(v, k), st.ref, sc);
+        e[k] = fast_exp2(y);
+        if (WITH_T) t[k & 1] = __builtin_fmaf(y, e[k], t[k & 1]);
+    }
+    float s;
+    if (N == 8) s = ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
+    else s = (e[0] + e[1]) + (e[2] + e[3]);
+    st.Sd += (double)s;
+    if (WITH_T) st.Td += (double)(t[0] + t[1]);
+}
+
+// Largest logit of a chunk (NaN elements are passed over, as everywhere the reference is chosen).
+template <bool BF16>
+__device__ __forceinline__ float chunk_max(const uint4& v)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    float mx = chunk_elem<BF16>(v, 0);
+#pragma unroll
+    for (int k = 1; k < N; ++k) mx = fmaxf(mx, chunk_elem<BF16>(v, k));
+    return mx;
+}
+
 template <bool BF16, bool ARGMAX>
 __device__ __forceinline__ void accum_chunk_robust(LaneState& st, const uint4& v, int32_t elem0, const ExpScale& sc)
 {
@@ -164,9 +194,7 @@ __device__ __forceinline__ Partial wave_merge(const LaneState& st, const ExpScal
 {
     const bool has = !(st.Sd == 0.0 && st.Td == 0.0);   // also true for NaN
     const double beta = ref_offset<BF16>(st.ref, sc);
-    double bmin = has ? beta : INFINITY;
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) bmin = fmin(bmin, __shfl_xor(bmin, m, 64));
+    const double bmin = wave_min(has ? beta : (double)INFINITY);
     double S = 0.0, T = 0.0;
     if (has) {
         const double diff = bmin - beta;                // <= 0
@@ -293,11 +321,24 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
             }
             need_ref = false;
         }
+        if (!ROBUST && !ARGMAX) {
+            // The lane's reference is looked at once per group of loads: the largest logit of the whole group
+            // decides whether it has to move (one test, rarely taken once the reference sits near the row's
+            // top), and then the terms of all the group's chunks are formed against one reference in a single
+            // piece of straight-line code.
+            float mx = chunk_max<BF16>(buf[0]);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int32_t e0 = (int32_t)((c + u * stride) * N) - g.head;
-            if (ROBUST) accum_chunk_robust<BF16, ARGMAX>(st, buf[u], e0, sc);
-            else accum_chunk<BF16, ARGMAX, WITH_T>(st, buf[u], e0, sc);
+            for (int u = 1; u < U; ++u) mx = fmaxf(mx, chunk_max<BF16>(buf[u]));
+            if (mx > st.thr) on_exceed<BF16, ARGMAX>(st, mx, 0, sc);
+#pragma unroll
+            for (int u = 0; u < U; ++u) accum_chunk_terms<BF16, WITH_T>(st, buf[u], sc);
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int32_t e0 = (int32_t)((c + u * stride) * N) - g.head;
+                if (ROBUST) accum_chunk_robust<BF16, ARGMAX>(st, buf[u], e0, sc);
+                else accum_chunk<BF16, ARGMAX, WITH_T>(st, buf[u], e0, sc);
+            }
         }
         w += (int64_t)U * stride;
         wb += (int64_t)U * sb;
@@ -408,9 +449,7 @@ __device__ __forceinline__ RowStat merge_partials_wave(const Partial* __restrict
     q.bref = 0.0; q.S = 0.0; q.T = 0.0; q.vmax = -INFINITY; q.imax = -1;
     if (lane < n) q = ps[lane];
     const bool bad = __any(!(q.S == q.S));
-    double bmin = (q.S > 0.0) ? q.bref : INFINITY;
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) bmin = fmin(bmin, __shfl_xor(bmin, m, 64));
+    const double bmin = wave_min((q.S > 0.0) ? q.bref : (double)INFINITY);
     double S = 0.0, T = 0.0;
     if (q.S > 0.0) {
         const double d = bmin - q.bref;
@@ -442,7 +481,7 @@ __device__ __forceinline__ RowStat merge_partials_wave(const Partial* __restrict
 // The same merge on a segment of the wavefront: `width` (a power of two >= n) consecutive lanes hold the
 // partials of one row, so a wavefront merges 64 / width rows at once.  ps is the row's first partial (null:
 // the segment has no row), sl the lane's index inside its segment.  Butterflies with masks below `width` stay
-// inside a segment and add in the same order as the whole-wavefront merge, so the results are bit-identical.
+// inside a segment (the whole-wavefront merge adds in another order: the two agree to rounding, not to the bit).
 __device__ __forceinline__ RowStat merge_partials_seg(const Partial* __restrict__ ps, int n, int sl, int width)
 {
     Partial q;
