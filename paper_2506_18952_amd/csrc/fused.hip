@@ -19,6 +19,8 @@ namespace hola {
 constexpr int kFusedMaxTiles = 2048;
 constexpr int kFusedMaxGamma = 32;           // the fused kernel parks the partials of its 2 gamma + 1 rows in shared memory
 
+constexpr int kSlabKeepChunks = 8 * 64 * kTileChunks;   // a slab of up to eight tiles is kept in shared memory (32 KB)
+
 struct SeqShared {
     RowStat stat[2 * HOLA_MAX_GAMMA + 1];      // per row: draft rows 0..g-1, target rows g..2g
     double tiles[kFusedMaxTiles];
@@ -185,9 +187,11 @@ __device__ __forceinline__ void narrow_to_slab(RowPair& rp, int64_t lo, int64_t 
 // gathered token logits tg.  Called by every thread of the workgroup, after a barrier that made sh.stat (and, with
 // pre_slab, sh.slab_*) visible.  pre_slab: pick_bonus_slab has run; while wavefront 0 decides, the others sweep the
 // slab it chose, so that a sequence whose drafts are all kept finds its tile weights ready.
+// slab_raw: kSlabKeepChunks chunks of shared memory in which the sweep of a slab that fits leaves the chunks it
+// loaded, so that the selection does not read its tile from global memory again; or null.
 template <bool BF16, int NW, bool FILT = false>
 __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& sh, int b, int len, float Tb,
-                                              const TokenGather& tg, bool pre_slab = false)
+                                              const TokenGather& tg, bool pre_slab = false, uint4* slab_raw = nullptr)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = p.gamma;
@@ -195,6 +199,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
     const bool slab_ready = pre_slab && sh.slab_ok;                 // uniform over the workgroup
     const int64_t slab_lo = slab_ready ? sh.slab_lo : 0, slab_hi = slab_ready ? sh.slab_hi : 0;
     const int slab_tiles = (int)((slab_hi - slab_lo + 64 * kTileChunks - 1) / (64 * kTileChunks));
+    uint4* keep = (slab_ready && slab_hi - slab_lo <= kSlabKeepChunks) ? slab_raw : nullptr;
     if (wave == 0) {
         const int j = lane;
         RowStat sd = {NAN, NAN, -1}, sp = {NAN, NAN, -1};
@@ -216,7 +221,8 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
         }
         const AcceptCtx c = accept_ctx(p);
         accept_decide<BF16>(c, b, j, len, Tb, sd, sp, tg, &sh.si);
-    } else if (slab_ready) {
+    }
+    else if (slab_ready) {
         // the slab's tile weights as bonus weights of target row len, by the wavefronts that do not decide
         SeqInfo sb;
         sb.lseP = sh.stat[g + len].lse; sb.lseD = 0.0; sb.u = 0.f; sb.row = len; sb.mode = 1; sb.greedy_tok = -1;
@@ -224,13 +230,9 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
         make_row_pair<BF16>(rq, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, sb, 0, nullptr, p.B);
         if (rq.ok) {
             narrow_to_slab<BF16>(rq, slab_lo, slab_hi);
-            for (int t = wave - 1; t < slab_tiles; t += 2 * (NW - 1)) {
-                double w0 = 0.0, w1 = 0.0;
-                tile_weight2<BF16, false>(rq, t, t + (NW - 1), lane, w0, w1);
-                if (lane == 0) {
-                    sh.tiles[t] = w0;
-                    if (t + (NW - 1) < slab_tiles) sh.tiles[t + (NW - 1)] = w1;
-                }
+            for (int t = wave - 1; t < slab_tiles; t += NW - 1) {   // a slab is a few tiles: one per wavefront
+                const double w0 = tile_weight<BF16>(rq, t, lane, keep);
+                if (lane == 0) sh.tiles[t] = w0;
             }
         }
     }
@@ -243,7 +245,6 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
 
     RowPair rp;
     make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0, FILT ? p.filters : nullptr, p.B);
-
     int ntiles = p.ntiles;
     int32_t tok_off = 0;
     double u_eff = (double)si.u;
@@ -293,7 +294,8 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
             __syncthreads();
         }
         if (wave == 0) {
-            const int32_t tk = rp.ok ? select_token<BF16, true, FILT>(rp, sh.tiles, ntiles, u_eff, lane) : -1;
+            const int32_t tk = rp.ok ? select_token<BF16, true, FILT>(rp, sh.tiles, ntiles, u_eff, lane,
+                                                                      (slab_mode && attempt == 0) ? keep : nullptr) : -1;
             if (lane == 0) sh.tok = tk;
         }
         __syncthreads();
@@ -382,6 +384,10 @@ template <bool BF16, int NW, bool FILT = false>
 __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Partial* __restrict__ partials, int nparts)
 {
     __shared__ SeqShared sh;
+    // the chunks of the slab a bonus token comes from, kept for the selection; only where a workgroup has a compute
+    // unit to itself (smaller workgroups share one, and there the shared memory is better left to more of them)
+    __shared__ uint4 s_raw[(NW == 16 && !FILT) ? kSlabKeepChunks : 1];
+    uint4* const slab_raw = (NW == 16 && !FILT) ? s_raw : nullptr;
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = p.gamma;
@@ -413,7 +419,7 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
         }
     }
     __syncthreads();
-    sequence_tail<BF16, NW, FILT>(p, sh, b, len, Tb, tg, pre_slab);
+    sequence_tail<BF16, NW, FILT>(p, sh, b, len, Tb, tg, pre_slab, slab_raw);
 }
 
 bool fused_supported(int32_t gamma, int32_t V, int dtype)

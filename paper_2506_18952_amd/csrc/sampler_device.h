@@ -166,13 +166,21 @@ __device__ __forceinline__ float chunk_weights(const RowPair& rp, int64_t c, flo
 }
 
 // Weight of one tile: lanes take chunks tile*256 + g*64 + lane, g = 0..3.  Every lane returns the sum.
+// keep: shared-memory copy of the target row's chunks for select_token (indexed by chunk), or null.
 template <bool BF16>
-__device__ __forceinline__ double tile_weight(const RowPair& rp, int64_t tile, int lane)
+__device__ __forceinline__ double tile_weight(const RowPair& rp, int64_t tile, int lane, uint4* keep = nullptr)
 {
     constexpr int N = BF16 ? 8 : 4;
     uint4 vp[kTileChunks], vd[kTileChunks];
 #pragma unroll
     for (int g = 0; g < kTileChunks; ++g) load_chunk_pair<BF16>(rp, tile * (64 * kTileChunks) + g * 64 + lane, vp[g], vd[g]);
+    if (keep != nullptr) {
+#pragma unroll
+        for (int g = 0; g < kTileChunks; ++g) {
+            const int64_t c = tile * (64 * kTileChunks) + g * 64 + lane;
+            if (c < rp.nchunks) keep[c] = vp[g];
+        }
+    }
     double acc = 0.0;
 #pragma unroll
     for (int g = 0; g < kTileChunks; ++g) {
@@ -193,6 +201,7 @@ __device__ __forceinline__ void tile_weight2(const RowPair& rp, int64_t t0, int6
         load_chunk_pair<BF16>(rp, t0 * (64 * kTileChunks) + g * 64 + lane, vp[0][g], vd[0][g]);
         load_chunk_pair<BF16>(rp, t1 * (64 * kTileChunks) + g * 64 + lane, vp[1][g], vd[1][g]);
     }
+
     double a0 = 0.0, a1 = 0.0;
 #pragma unroll
     for (int g = 0; g < kTileChunks; ++g) {
@@ -217,8 +226,11 @@ __device__ __forceinline__ double read_tile(const double* t)
 // One wavefront selects the token from the tile weights: returns the token (all lanes), -1 if the
 // weights carry no mass, or -2 if the caller should recompute the tiles as bonus weights (residual with
 // Z == 0: p == q everywhere, or a broken draft row) and call again.
+// raw: the target row's chunks as the sweep loaded them, kept in shared memory (bonus weights, whole chunks: the
+// crossing tile is then not read from global memory again), or null.
 template <bool BF16, bool LDS, bool FILT = false>
-__device__ __forceinline__ int32_t select_token(const RowPair& rp, const double* tiles, int ntiles, double u, int lane)
+__device__ __forceinline__ int32_t select_token(const RowPair& rp, const double* tiles, int ntiles, double u, int lane,
+                                                const uint4* raw = nullptr)
 {
     constexpr int N = BF16 ? 8 : 4;
     const int per = (ntiles + 63) / 64;
@@ -259,8 +271,15 @@ __device__ __forceinline__ int32_t select_token(const RowPair& rp, const double*
     float w[kTileChunks][N];
     float cs[kTileChunks];
 #pragma unroll
-    for (int g = 0; g < kTileChunks; ++g)
-        cs[g] = chunk_weights<BF16, FILT>(rp, (int64_t)tile * (64 * kTileChunks) + g * 64 + lane, w[g]);
+    for (int g = 0; g < kTileChunks; ++g) {
+        const int64_t c = (int64_t)tile * (64 * kTileChunks) + g * 64 + lane;
+        if (raw != nullptr) {
+            const uint4 none = make_uint4(0, 0, 0, 0);
+            cs[g] = chunk_weights_loaded<BF16, FILT>(rp, c, c < rp.nchunks ? raw[c] : none, none, w[g]);
+        } else {
+            cs[g] = chunk_weights<BF16, FILT>(rp, c, w[g]);
+        }
+    }
     double base = before;
     int found_g = -1, found_lane = -1;
     double found_excl = 0.0;
