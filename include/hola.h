@@ -258,8 +258,9 @@ typedef struct {
     float* out_entropy;               /* device [n_models-1, B, gamma+n_models-2] or NULL */
     void* workspace; size_t workspace_bytes; hola_stream_t stream;
     int32_t top_k; float top_p;       /* as in hola_verify_args, applied to both models of every level (0 / 0: off).
-                                         Filtered levels take no statistics from one another: each finds the keep
-                                         sets and statistics of its own rows.  Needs row_temperature == NULL. */
+                                         A middle model's keep sets and filtered statistics are found once, at the
+                                         level where it is the target, and handed to the level where it is the draft,
+                                         as the unfiltered statistics are.  Needs row_temperature == NULL. */
     const hola_tuning* tuning;        /* host; launch shape of every level, NULL => the calling thread's defaults */
 } hola_hsd_args;
 hola_status hola_hsd_verify_ex(const hola_hsd_args* args /* host */);

@@ -23,6 +23,7 @@ struct AcceptCtx {
     int32_t* out_accept_len; int32_t* out_next_token;
     float* out_entropy; int64_t entropy_ld;
     const RowFilter* filters = nullptr; // top-k / top-p keep sets and statistics, slots as the partials; or null
+    const RowFilter* draft_filters = nullptr;   // the draft rows' ([B, gamma]): `filters` itself unless handed over
     int32_t B = 0;
 };
 
@@ -71,7 +72,7 @@ __device__ __forceinline__ void accept_decide(const AcceptCtx& c, int b, int j, 
     int32_t cutD = 0x7fffffff, cutP = 0x7fffffff;
     if (c.filters) {                                    // filtered distributions: their own statistics and keep sets
         if (j < len) {
-            const RowFilter f = c.filters[(int64_t)b * g + j];
+            const RowFilter f = c.draft_filters[(int64_t)b * g + j];
             sd.lse = f.lse; sd.H = f.H; thD = f.theta; cutD = f.idx_cut;
         }
         if (j <= len) {

@@ -368,6 +368,7 @@ struct FilterParams {
     RowFilter* filters;
     int32_t* out_keep_count;           // [B, 2 gamma + 1] or null
     const int32_t* flags;              // [B (2 gamma + 1)] or null: only rows flagged 1 are done here
+    int32_t skip_draft;                // the draft rows' keep sets are given: only target rows are done here
 };
 
 template <bool BF16>
@@ -387,7 +388,7 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
     const int j = is_draft ? k : k - g;
     int len = p.draft_len ? p.draft_len[b] : g;
     len = len < 0 ? 0 : (len > g ? g : len);
-    if (is_draft ? (j >= len) : (j > len)) {                    // row not needed (uniform exit)
+    if (is_draft ? (p.skip_draft || j >= len) : (j > len)) {    // row not needed (uniform exit)
         if (p.out_keep_count && threadIdx.x == 0) p.out_keep_count[blockIdx.x] = -1;
         return;
     }
@@ -946,13 +947,13 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
 hipError_t launch_filter(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                          const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
                          int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, const int32_t* flags,
-                         hipStream_t s)
+                         int32_t skip_draft, hipStream_t s)
 {
     if (B <= 0) return hipSuccess;
     FilterParams p{};
     p.target = target; p.draft = draft; p.target_ld = target_ld; p.draft_ld = draft_ld; p.draft_len = draft_len;
     p.temperature = temperature; p.B = B; p.gamma = gamma; p.V = V; p.top_k = top_k; p.top_p = top_p;
-    p.filters = filters; p.out_keep_count = out_keep_count; p.flags = flags;
+    p.filters = filters; p.out_keep_count = out_keep_count; p.flags = flags; p.skip_draft = skip_draft;
     const int64_t nblk = (int64_t)B * (2 * gamma + 1);
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     if (dtype == HOLA_DTYPE_BF16) hipLaunchKernelGGL((filter_kernel<true>), dim3((unsigned)nblk), dim3(kFilterThreads), 0, s, p);

@@ -43,9 +43,11 @@ __device__ __forceinline__ uint64_t list_mass_fixed(const FilterRow& fr, float x
 }
 
 // Row r of a filtered call, r in [0, B (2 gamma + 1)): per sequence the gamma draft rows, then the gamma + 1
-// target rows.  Returns false for a row the call does not use (beyond the sequence's draft length).
+// target rows.  Returns false for a row the call does not use (beyond the sequence's draft length, or a draft row
+// when the draft rows' keep sets were handed over by the previous level: skip_draft).
 struct FilterRowId { int b, j; bool is_draft; int64_t slot; };
-__device__ __forceinline__ bool filter_row_id(int r, int32_t B, int32_t gamma, const int32_t* draft_len, FilterRowId& id)
+__device__ __forceinline__ bool filter_row_id(int r, int32_t B, int32_t gamma, const int32_t* draft_len, FilterRowId& id,
+                                              int32_t skip_draft = 0)
 {
     const int rows_per_seq = 2 * gamma + 1;
     id.b = r / rows_per_seq;
@@ -55,7 +57,7 @@ __device__ __forceinline__ bool filter_row_id(int r, int32_t B, int32_t gamma, c
     int len = draft_len ? draft_len[id.b] : gamma;
     len = len < 0 ? 0 : (len > gamma ? gamma : len);
     id.slot = id.is_draft ? (int64_t)id.b * gamma + id.j : (int64_t)B * gamma + (int64_t)id.b * (gamma + 1) + id.j;
-    return id.is_draft ? (id.j < len) : (id.j <= len);
+    return id.is_draft ? (!skip_draft && id.j < len) : (id.j <= len);
 }
 
 template <bool BF16>

@@ -68,6 +68,7 @@ struct ScanParams {
     int32_t* kept_n;                   // [rows]: its length, -1 when not written
     RowFilter* filters;
     int32_t* out_keep_count;
+    int32_t skip_draft;                // the draft rows' keep sets are given: only target rows are scanned and decided
 };
 
 // The need-th largest of the keys (kbits wide) that satisfy pred, need >= 1 and at most their number, over a
@@ -136,7 +137,7 @@ __device__ __forceinline__ ScanItem scan_item(const ScanParams& p, int seg, int 
     const int j = is_draft ? k : k - p.gamma;
     int len = p.draft_len ? p.draft_len[b] : p.gamma;
     len = len < 0 ? 0 : (len > p.gamma ? p.gamma : len);
-    if (is_draft ? (j >= len) : (j > len)) return it;           // row not needed
+    if (is_draft ? (p.skip_draft || j >= len) : (j > len)) return it;   // row not needed
     it.used = true;
     constexpr int N = BF16 ? 8 : 4;
     constexpr int ES = BF16 ? 2 : 4;
@@ -474,7 +475,7 @@ __global__ __launch_bounds__(64, E > kScanSlots ? 2 : ((WANT_K && WANT_P) ? 4 : 
     const int lane = threadIdx.x;
     const int r = blockIdx.x;
     FilterRowId id;
-    if (!filter_row_id(r, p.B, p.gamma, p.draft_len, id)) {     // row not needed
+    if (!filter_row_id(r, p.B, p.gamma, p.draft_len, id, p.skip_draft)) {   // row not needed
         if (lane == 0) { p.flags[r] = 0; p.kept_n[r] = -1; if (p.out_keep_count) p.out_keep_count[r] = -1; }
         return;
     }
@@ -875,7 +876,8 @@ bool filter_scan_applies(int dtype, int32_t V, int32_t top_k) { return scan_deci
 
 static ScanParams scan_params(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                               const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
-                              int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch)
+                              int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch,
+                              int32_t skip_draft)
 {
     const int64_t rows = (int64_t)B * (2 * gamma + 1);
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
@@ -883,7 +885,7 @@ static ScanParams scan_params(const void* target, const void* draft, int dtype, 
     ScanParams p{};
     p.target = target; p.draft = draft; p.target_ld = target_ld; p.draft_ld = draft_ld; p.draft_len = draft_len;
     p.temperature = temperature; p.B = B; p.gamma = gamma; p.V = V; p.top_k = top_k; p.top_p = top_p;
-    p.filters = filters; p.out_keep_count = out_keep_count;
+    p.filters = filters; p.out_keep_count = out_keep_count; p.skip_draft = skip_draft;
     p.nseg = scan_segments(dtype, V);
     p.cap_seg = kScanStore / p.nseg;
     const int N = dtype == HOLA_DTYPE_BF16 ? 8 : 4;
@@ -900,10 +902,10 @@ static ScanParams scan_params(const void* target, const void* draft, int dtype, 
 
 hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                               const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
-                              int32_t top_k, float top_p, void* scratch, hipStream_t s)
+                              int32_t top_k, float top_p, void* scratch, int32_t skip_draft, hipStream_t s)
 {
     const ScanParams p = scan_params(target, draft, dtype, target_ld, draft_ld, draft_len, temperature, B, gamma, V, top_k, top_p,
-                                     nullptr, nullptr, scratch);
+                                     nullptr, nullptr, scratch, skip_draft);
     if (p.nseg > kScanMaxSeg || p.seg_len > scan_seg_chunks(dtype) || B > 65535) return hipErrorInvalidValue;
     const bool mass = !(top_k > 0 && top_k < V);                // top-p alone: the segments also sum the mass below their edges
     const dim3 grid((unsigned)p.nseg, (unsigned)(2 * gamma + 1), (unsigned)B);
@@ -921,10 +923,10 @@ hipError_t launch_filter_decide(const void* target, const void* draft, int dtype
                                 const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
                                 int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch,
                                 int32_t** flags_out, const unsigned long long** kept_out, int64_t* kept_stride_out,
-                                const int32_t** kept_n_out, hipStream_t s)
+                                const int32_t** kept_n_out, int32_t skip_draft, hipStream_t s)
 {
     const ScanParams p = scan_params(target, draft, dtype, target_ld, draft_ld, draft_len, temperature, B, gamma, V, top_k, top_p,
-                                     filters, out_keep_count, scratch);
+                                     filters, out_keep_count, scratch, skip_draft);
     *flags_out = p.flags;
     *kept_out = p.cand;                                         // a short keep set replaces the row's candidates
     *kept_stride_out = (int64_t)p.nseg * p.cap_seg;

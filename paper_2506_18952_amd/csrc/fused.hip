@@ -116,7 +116,7 @@ __device__ __forceinline__ AcceptCtx accept_ctx(const FusedParams& p)
     c.gamma = p.gamma; c.V = p.V; c.tau = p.tau; c.target_stats_out = p.target_stats_out;
     c.out_accept_len = p.out_accept_len; c.out_next_token = p.out_next_token;
     c.out_entropy = p.out_entropy; c.entropy_ld = p.entropy_ld;
-    c.filters = p.filters; c.B = p.B;
+    c.filters = p.filters; c.draft_filters = p.draft_filters ? p.draft_filters : p.filters; c.B = p.B;
     return c;
 }
 
@@ -244,7 +244,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
     }
 
     RowPair rp;
-    make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0, FILT ? p.filters : nullptr, p.B);
+    make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0, FILT ? p.filters : nullptr, p.B, FILT ? p.draft_filters : nullptr);
     int ntiles = p.ntiles;
     int32_t tok_off = 0;
     double u_eff = (double)si.u;
@@ -278,7 +278,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
             tok = sh.tok;
             if (tok != -2) break;
             __syncthreads();
-            make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1, FILT ? p.filters : nullptr, p.B);
+            make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1, FILT ? p.filters : nullptr, p.B, FILT ? p.draft_filters : nullptr);
             continue;
         }
         if (!(slab_mode && attempt == 0)) {
@@ -304,13 +304,13 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
             if (tok >= 0) { tok += tok_off; break; }
             // no mass in the slab by the sampler's arithmetic (an underflow the partials did not have): the whole row
             slab_mode = false;
-            make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0, FILT ? p.filters : nullptr, p.B);
+            make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0, FILT ? p.filters : nullptr, p.B, FILT ? p.draft_filters : nullptr);
             ntiles = p.ntiles;
             u_eff = (double)si.u;
             continue;
         }
         if (tok != -2) break;                                    // -2: no residual mass, sample p itself
-        make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1, FILT ? p.filters : nullptr, p.B);
+        make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1, FILT ? p.filters : nullptr, p.B, FILT ? p.draft_filters : nullptr);
     }
     if (tid == 0) p.out_next_token[b] = tok < 0 ? -1 : tok;
     write_glue(p, b, si.row, tok < 0 ? -1 : tok);

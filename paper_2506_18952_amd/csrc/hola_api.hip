@@ -211,6 +211,11 @@ struct LevelExtras {
     int32_t pad_entropy = 0;
     int32_t* glue_tok = nullptr; int32_t* glue_len = nullptr; int64_t glue_ld = 0;
     int32_t glue_keep_next = 1;
+    // filtered levels: the keep sets and statistics of the draft rows as the previous level found them when that
+    // model was its target ([B, gamma], so those rows are not scanned again), and where this level leaves its
+    // target rows' ([B, gamma + 1]) for the next one
+    const RowFilter* draft_filters_in = nullptr;
+    RowFilter* target_filters_out = nullptr;
 };
 
 static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = LevelExtras())
@@ -266,23 +271,25 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
 
     if (filtered) {
         const float top_p = (a.top_p > 0.f && a.top_p < 1.f) ? a.top_p : 1.f;
+        const int32_t skip_d = x.draft_filters_in ? 1 : 0;     // the draft rows' keep sets are handed over
         int32_t* flags = nullptr;
         if (tune.filter_path != 1 && w.filter_scan && filter_scan_applies(a.dtype, a.V, a.top_k)) {
             { StageTimer t(8, s);
               e = launch_filter_scan(a.target_logits, a.draft_logits, a.dtype, tld, dld, a.draft_len, a.temperature, a.B, a.gamma,
-                                     a.V, a.top_k, top_p, w.filter_scan, s); }
+                                     a.V, a.top_k, top_p, w.filter_scan, skip_d, s); }
             if (e != hipSuccess) return hip_fail(e, "filter scan launch");
             { StageTimer t(9, s);
               e = launch_filter_decide(a.target_logits, a.draft_logits, a.dtype, tld, dld, a.draft_len, a.temperature, a.B, a.gamma,
                                        a.V, a.top_k, top_p, w.filters, a.out_keep_count, w.filter_scan, &flags, &fp.kept,
-                                       &fp.kept_stride, &fp.kept_n, s); }
+                                       &fp.kept_stride, &fp.kept_n, skip_d, s); }
             if (e != hipSuccess) return hip_fail(e, "filter decide launch");
         }
         { StageTimer t(7, s);
           e = launch_filter(a.target_logits, a.draft_logits, a.dtype, tld, dld, a.draft_len, a.temperature, a.B, a.gamma, a.V,
-                            a.top_k, top_p, w.filters, a.out_keep_count, flags, s); }
+                            a.top_k, top_p, w.filters, a.out_keep_count, flags, skip_d, s); }
         if (e != hipSuccess) return hip_fail(e, "filter launch");
         fp.filters = w.filters;
+        fp.draft_filters = x.draft_filters_in ? x.draft_filters_in : w.filters;
     }
 
     // Paths 0/1: the split-row pass spreads the rows over the chip, then one per-sequence tail kernel does
@@ -291,6 +298,14 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
         if (tune.fused_waves == 0) tune.fused_waves = auto_tail_waves(a.B, (int64_t)a.V * (a.dtype == HOLA_DTYPE_BF16 ? 2 : 4));
         { StageTimer t(6, s); e = launch_tail(fp, w.partials, nsplit * kWaves, tune, s); }
         if (e != hipSuccess) return hip_fail(e, "tail launch");
+        if (filtered && x.target_filters_out) {                // this level's target rows are the next level's draft rows
+            StageTimer t(4, s);
+            const size_t n16 = (size_t)a.B * (a.gamma + 1) * sizeof(RowFilter) / 16;
+            hipLaunchKernelGGL(copy_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s, (uint4*)x.target_filters_out,
+                               (const uint4*)(w.filters + (size_t)a.B * a.gamma), n16);
+            e = hipGetLastError();
+            if (e != hipSuccess) return hip_fail(e, "filter hand-over launch");
+        }
         return HOLA_OK;
     }
 
@@ -501,6 +516,7 @@ namespace {
 struct HsdWs {
     void* level; size_t level_bytes;
     int32_t* tok[2]; int32_t* len[2]; double* stats[2];
+    RowFilter* filt[2];                 // filtered chains: a middle model's keep sets, from the level where it is the target
     size_t bytes;
 };
 HsdWs carve_hsd(void* base, int32_t n_models, int32_t B, int32_t gamma, int32_t V)
@@ -513,6 +529,7 @@ HsdWs carve_hsd(void* base, int32_t n_models, int32_t B, int32_t gamma, int32_t 
     for (int i = 0; i < 2; ++i) { h.tok[i] = (int32_t*)(p + off); off = align_up(off + (size_t)B * (gmax + 1) * sizeof(int32_t)); }
     for (int i = 0; i < 2; ++i) { h.len[i] = (int32_t*)(p + off); off = align_up(off + (size_t)B * sizeof(int32_t)); }
     for (int i = 0; i < 2; ++i) { h.stats[i] = (double*)(p + off); off = align_up(off + (size_t)B * (gmax + 1) * 2 * sizeof(double)); }
+    for (int i = 0; i < 2; ++i) { h.filt[i] = (RowFilter*)(p + off); off = align_up(off + (size_t)B * (gmax + 1) * sizeof(RowFilter)); }
     h.bytes = off;
     return h;
 }
@@ -581,6 +598,7 @@ hola_status hola_hsd_verify_ex(const hola_hsd_args* args)
     int64_t cur_ld = gamma;
     const int32_t* cur_len = nullptr;
     const double* cur_stats = nullptr;
+    const RowFilter* cur_filt = nullptr;
     for (int k = 1; k <= L; ++k) {
         const int32_t gk = gamma + k - 1;
         hola_verify_args a;
@@ -603,6 +621,10 @@ hola_status hola_hsd_verify_ex(const hola_hsd_args* args)
         x.tokens_ld = cur_ld;
         x.pad_entropy = 1;
         x.glue_keep_next = args->survivors_only ? 0 : 1;
+        if (filtered) {
+            x.draft_filters_in = cur_filt;                     // null at the first level: it scans its draft rows itself
+            x.target_filters_out = k < L ? h.filt[k & 1] : nullptr;
+        }
         if (k < L) {
             // The next level's drafts are written by this level.  The last middle level writes them
             // straight into out_tokens (when given), which the last level then reads in place.
@@ -616,6 +638,7 @@ hola_status hola_hsd_verify_ex(const hola_hsd_args* args)
             cur_tok = x.glue_tok; cur_ld = x.glue_ld;
             cur_len = x.glue_len;
             cur_stats = h.stats[k & 1];
+            cur_filt = filtered ? h.filt[k & 1] : nullptr;
         }
     }
     if (out_tokens && cur_tok != out_tokens) {          // a single level: its drafts are the caller's tokens

@@ -125,6 +125,8 @@ struct FusedParams {
     int32_t* glue_tok; int32_t* glue_len; int64_t glue_ld;
     int32_t glue_keep_next;            // 1: append the next token; 0: the kept tokens only
     const RowFilter* filters;          // top-k / top-p keep sets (slots as the partials), or null
+    const RowFilter* draft_filters;    // where the draft rows' keep sets are read from: `filters`, or an array [B, gamma]
+                                       // handed over by the previous level of a hierarchy
     // short keep sets written out as lists of (order key << 32 | index), at most kKeptListMax entries, kept_stride
     // apart, for row r = b (2 gamma + 1) + k, and their lengths (-1: no list); null when the filter's scan did not run
     const unsigned long long* kept; const int32_t* kept_n; int64_t kept_stride;
@@ -152,23 +154,24 @@ hipError_t launch_literal(const FusedParams& p, const Partial* partials, int npa
                           int32_t* out_calls, hipStream_t s);
 hipError_t launch_row_stats(const RowStatsParams& p, int dtype, const Tuning& t, hipStream_t s);
 // Keep sets of top-k / top-p filtered rows by the one-workgroup-per-row kernel: every row, or with `flags`
-// ([B (2 gamma + 1)]) only the rows flagged 1.
+// ([B (2 gamma + 1)]) only the rows flagged 1.  skip_draft (here and in the two launchers below): the draft rows'
+// keep sets come from elsewhere (the level of a hierarchy at which that model was the target); only target rows are done.
 hipError_t launch_filter(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                          const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
                          int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, const int32_t* flags,
-                         hipStream_t s);
+                         int32_t skip_draft, hipStream_t s);
 // The usual course of the filter: a split-row scan that lists candidates, then a per-row decide step; rows it
 // cannot settle come back flagged in *flags_out ([B (2 gamma + 1)], 1 = still to do).
 size_t filter_scan_bytes(int64_t rows);
 bool filter_scan_applies(int dtype, int32_t V, int32_t top_k);
 hipError_t launch_filter_scan(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                               const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
-                              int32_t top_k, float top_p, void* scratch, hipStream_t s);
+                              int32_t top_k, float top_p, void* scratch, int32_t skip_draft, hipStream_t s);
 hipError_t launch_filter_decide(const void* target, const void* draft, int dtype, int64_t target_ld, int64_t draft_ld,
                                 const int32_t* draft_len, float temperature, int32_t B, int32_t gamma, int32_t V,
                                 int32_t top_k, float top_p, RowFilter* filters, int32_t* out_keep_count, void* scratch,
                                 int32_t** flags_out, const unsigned long long** kept_out, int64_t* kept_stride_out,
-                                const int32_t** kept_n_out, hipStream_t s);
+                                const int32_t** kept_n_out, int32_t skip_draft, hipStream_t s);
 hipError_t launch_accept(const AcceptParams& p, hipStream_t s);
 hipError_t launch_merge_tile_stats(const double* ts, int32_t R, int32_t nt, double* out, hipStream_t s);
 hipError_t launch_finalize_rows(const Partial* partials, int nparts, int32_t R, double* out, hipStream_t s);

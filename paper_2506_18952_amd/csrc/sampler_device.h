@@ -42,7 +42,7 @@ template <bool BF16>
 __device__ __forceinline__ void make_row_pair(RowPair& rp, const void* target, const void* draft, int64_t target_ld,
                                               int64_t draft_ld, int32_t gamma, int32_t V, float Tb, int b,
                                               const SeqInfo& si, int force_bonus, const RowFilter* filters = nullptr,
-                                              int32_t B = 0)
+                                              int32_t B = 0, const RowFilter* draft_filters = nullptr)
 {
     constexpr int N = BF16 ? 8 : 4;
     constexpr int ES = BF16 ? 2 : 4;
@@ -66,7 +66,7 @@ __device__ __forceinline__ void make_row_pair(RowPair& rp, const void* target, c
         const RowFilter f = filters[(int64_t)B * g + (int64_t)b * (g + 1) + si.row];
         rp.thP = f.theta; rp.cutP = f.idx_cut;
         if (!rp.bonus) {
-            const RowFilter fq = filters[(int64_t)b * g + (si.row < g ? si.row : g - 1)];
+            const RowFilter fq = (draft_filters ? draft_filters : filters)[(int64_t)b * g + (si.row < g ? si.row : g - 1)];
             rp.thQ = fq.theta; rp.cutQ = fq.idx_cut;
         }
     }
