@@ -87,11 +87,14 @@ int choose_split(int64_t rows, int V, int dtype, const Tuning& t)
     if (max_useful < 1) max_useful = 1;
     int s = t.split;
     if (s <= 0) {
-        // Few rows: split until ~2048 workgroups (8 per compute unit) exist, down to 4 chunks per lane.  Beyond
-        // that, split towards 8192 workgroups only while a lane keeps at least 24 chunks (three groups of 8
-        // loads): shorter segments cost more in ramp-up than the shorter last round of the grid gains.
+        // Workgroups cost dispatch time (about 1.3 us per thousand on MI355X), so a row is split only as far as it
+        // pays.  Fewer rows than compute units: split down to two chunks per lane, so that every unit gets work.
+        // Up to ~2048 workgroups (8 per compute unit): split while a lane keeps two groups of 8 loads.  Beyond
+        // that, towards 8192 workgroups, only while a lane keeps at least 24 chunks (three groups of 8 loads):
+        // shorter segments cost more in ramp-up than the shorter last round of the grid gains.
         s = 1;
-        while (rows * s < 2048 && s < kMaxSplit && chunks / (s * 2) >= (int64_t)kBlock * 4) s *= 2;
+        while (rows * s < 256 && s < kMaxSplit && chunks / (s * 2) >= (int64_t)kBlock * 2) s *= 2;
+        while (rows * s < 2048 && s < kMaxSplit && chunks / (s * 2) >= (int64_t)kBlock * 8) s *= 2;
         while (rows * s < 8192 && s < kMaxSplit && chunks / (s * 2) >= (int64_t)kBlock * 24) s *= 2;
     }
     if (s > kMaxSplit) s = kMaxSplit;
