@@ -56,7 +56,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
             print(out)
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,-z,defs", "-o", LIB, *objs]   # no undefined symbols
     subprocess.run(cmd, check=True)
     return LIB
 
