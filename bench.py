@@ -45,9 +45,10 @@ STAGE_ROW_STATS, STAGE_FUSED, STAGE_TAIL, STAGE_FILTER, STAGE_SCAN, STAGE_PROBE 
 # plain copy of known size (see profiles/).  Keyed by the library version the counters were read with and by the
 # workload: a figure is reported only for the very kernels it was measured on, otherwise null.
 MEASURED_TRAFFIC_BYTES = {
-    ("hola-verify 0.1 (gfx950)", "cfg3", "row_stats_kernel"): 1117785113,
-    ("hola-verify 0.1 (gfx950)", "cfg3 top_k=50 top_p=0.95", "filter_scan_kernel"): 1154513715,
-    ("hola-verify 0.1 (gfx950)", "tree 4,4,4,2,2", "row_stats_kernel"): 1971637248,
+    ("hola-verify 0.2 (gfx950)", "cfg3", "row_stats_kernel"): 1117849267,
+    ("hola-verify 0.2 (gfx950)", "cfg5", "row_stats_kernel"): 9438750813,
+    ("hola-verify 0.2 (gfx950)", "cfg3 top_k=50 top_p=0.95", "filter_scan_kernel"): 1154354396,
+    ("hola-verify 0.2 (gfx950)", "tree 4,4,4,2,2", "row_stats_kernel"): 1971565278,
 }
 
 
@@ -382,7 +383,7 @@ def bench_config(args) -> int:
         out["algorithmic_bytes_per_step"] = int(call_bytes)
         out["stage_ms"] = {hb.STAGE_NAMES[s]: round(float(np.median(v)), 5) for s, v in sorted(per_stage.items())}
         out["rejections"] = resid
-        out["roofline"] = _roofline(hb, per_stage, STAGE_ROW_STATS, "row_stats_kernel", pass1, "cfg5")
+        out["roofline"] = _roofline(hb, per_stage, STAGE_ROW_STATS, "row_stats_kernel", pass1, "cfg5" if args.batch5 == 1024 else "")
         oracle_case = None
         if not args.no_cpu:
             from oracle import hola_oracle as orc
