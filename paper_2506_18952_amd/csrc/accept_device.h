@@ -94,6 +94,11 @@ __device__ __forceinline__ void accept_decide(const AcceptCtx& c, int b, int j, 
             c.out_entropy[(int64_t)b * eld + jj] = (jj < len) ? (float)sd.H : -1.0f;
     }
     const uint64_t seq = (uint64_t)(c.seq_base + b);
+    // Position j's Philox block: word 0 decides the acceptance test of drafted position j, word 1 draws the next token
+    // if the sequence stops at row j, so the lane that turns out to hold the stop row has its uniform at hand.
+    Philox4 r = {0u, 0u, 0u, 0u};
+    if (!greedy && j <= len)
+        r = philox4x32_10((uint32_t)j, (uint32_t)seq, (uint32_t)(seq >> 32), c.level, (uint32_t)c.seed, (uint32_t)(c.seed >> 32));
     bool reject = false;
     if (j < len) {
         const bool gate = sd.H < tau;                   // strict; NaN never gates
@@ -111,8 +116,6 @@ __device__ __forceinline__ void accept_decide(const AcceptCtx& c, int b, int j, 
                     if (!filter_keeps(tg.xq, x, thD, cutD)) q_x = 0.0;
                 }
             }
-            const Philox4 r = philox4x32_10((uint32_t)j, (uint32_t)seq, (uint32_t)(seq >> 32), c.level,
-                                            (uint32_t)c.seed, (uint32_t)(c.seed >> 32));
             const double u = (double)u24(r.x);
             ok = (u * q_x < p_x);
         }
@@ -133,9 +136,7 @@ __device__ __forceinline__ void accept_decide(const AcceptCtx& c, int b, int j, 
             si.greedy_tok = sp.argmax;
             c.out_next_token[b] = sp.argmax;
         } else {
-            const Philox4 r = philox4x32_10((uint32_t)a, (uint32_t)seq, (uint32_t)(seq >> 32), c.level,
-                                            (uint32_t)c.seed, (uint32_t)(c.seed >> 32));
-            si.u = u24(r.y);
+            si.u = u24(r.y);                             // j == a: this lane's own block
             si.mode = (a < len) ? 0 : 1;
         }
         *si_out = si;

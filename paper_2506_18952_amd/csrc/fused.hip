@@ -20,6 +20,7 @@ constexpr int kFusedMaxTiles = 2048;
 constexpr int kFusedMaxGamma = 32;           // the fused kernel parks the partials of its 2 gamma + 1 rows in shared memory
 
 constexpr int kSlabKeepChunks = 8 * 64 * kTileChunks;   // a slab of up to eight tiles is kept in shared memory (32 KB)
+constexpr int kSumsKeepTiles = 80;                       // the lanes' chunk sums of up to 80 tiles are kept there too (80 KB)
 
 struct SeqShared {
     RowStat stat[2 * HOLA_MAX_GAMMA + 1];      // per row: draft rows 0..g-1, target rows g..2g
@@ -189,9 +190,12 @@ __device__ __forceinline__ void narrow_to_slab(RowPair& rp, int64_t lo, int64_t 
 // slab it chose, so that a sequence whose drafts are all kept finds its tile weights ready.
 // slab_raw: kSlabKeepChunks chunks of shared memory in which the sweep of a slab that fits leaves the chunks it
 // loaded, so that the selection does not read its tile from global memory again; or null.
+// chunk_sums: kSumsKeepTiles x 64 entries of shared memory in which a sweep of at most that many tiles leaves every
+// lane's chunk sums, so that the selection rebuilds one chunk of the crossing tile instead of four; or null.
 template <bool BF16, int NW, bool FILT = false>
 __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& sh, int b, int len, float Tb,
-                                              const TokenGather& tg, bool pre_slab = false, uint4* slab_raw = nullptr)
+                                              const TokenGather& tg, bool pre_slab = false, uint4* slab_raw = nullptr,
+                                              float4* chunk_sums = nullptr)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = p.gamma;
@@ -231,7 +235,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
         if (rq.ok) {
             narrow_to_slab<BF16>(rq, slab_lo, slab_hi);
             for (int t = wave - 1; t < slab_tiles; t += NW - 1) {   // a slab is a few tiles: one per wavefront
-                const double w0 = tile_weight<BF16>(rq, t, lane, keep);
+                const double w0 = tile_weight<BF16>(rq, t, lane, keep, slab_tiles <= kSumsKeepTiles ? chunk_sums : nullptr);
                 if (lane == 0) sh.tiles[t] = w0;
             }
         }
@@ -269,6 +273,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
 
     int32_t tok = -1;
     for (int attempt = 0; attempt < 3; ++attempt) {
+        float4* const sums = (ntiles <= kSumsKeepTiles) ? chunk_sums : nullptr;   // uniform over the workgroup
         if (FILT && list_n > 0) {
             if (wave == 0) {
                 const int32_t tk = sample_kept_list<BF16>(rp, list, list_n, u_eff, lane);
@@ -285,7 +290,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
             // tile weights of the stop row: two tiles per round trip and wavefront
             for (int t = wave; t < ntiles; t += 2 * NW) {
                 double w0 = 0.0, w1 = 0.0;
-                if (rp.ok) tile_weight2<BF16, FILT>(rp, t, t + NW, lane, w0, w1);
+                if (rp.ok) tile_weight2<BF16, FILT>(rp, t, t + NW, lane, w0, w1, sums, ntiles);
                 if (lane == 0) {
                     sh.tiles[t] = w0;
                     if (t + NW < ntiles) sh.tiles[t + NW] = w1;
@@ -295,7 +300,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
         }
         if (wave == 0) {
             const int32_t tk = rp.ok ? select_token<BF16, true, FILT>(rp, sh.tiles, ntiles, u_eff, lane,
-                                                                      (slab_mode && attempt == 0) ? keep : nullptr) : -1;
+                                                                      (slab_mode && attempt == 0) ? keep : nullptr, sums) : -1;
             if (lane == 0) sh.tok = tk;
         }
         __syncthreads();
@@ -388,6 +393,8 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
     // unit to itself (smaller workgroups share one, and there the shared memory is better left to more of them)
     __shared__ uint4 s_raw[(NW == 16 && !FILT) ? kSlabKeepChunks : 1];
     uint4* const slab_raw = (NW == 16 && !FILT) ? s_raw : nullptr;
+    __shared__ float4 s_sums[(NW == 16 && !FILT) ? kSumsKeepTiles * 64 : 1];   // likewise
+    float4* const chunk_sums = (NW == 16 && !FILT) ? s_sums : nullptr;
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = p.gamma;
@@ -419,7 +426,7 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
         }
     }
     __syncthreads();
-    sequence_tail<BF16, NW, FILT>(p, sh, b, len, Tb, tg, pre_slab, slab_raw);
+    sequence_tail<BF16, NW, FILT>(p, sh, b, len, Tb, tg, pre_slab, slab_raw, chunk_sums);
 }
 
 bool fused_supported(int32_t gamma, int32_t V, int dtype)

@@ -167,8 +167,11 @@ __device__ __forceinline__ float chunk_weights(const RowPair& rp, int64_t c, flo
 
 // Weight of one tile: lanes take chunks tile*256 + g*64 + lane, g = 0..3.  Every lane returns the sum.
 // keep: shared-memory copy of the target row's chunks for select_token (indexed by chunk), or null.
+// sums: shared memory for the lanes' four chunk sums of every tile ([tile][lane]), which select_token then need
+// not rebuild from the row; or null.
 template <bool BF16>
-__device__ __forceinline__ double tile_weight(const RowPair& rp, int64_t tile, int lane, uint4* keep = nullptr)
+__device__ __forceinline__ double tile_weight(const RowPair& rp, int64_t tile, int lane, uint4* keep = nullptr,
+                                              float4* sums = nullptr)
 {
     constexpr int N = BF16 ? 8 : 4;
     uint4 vp[kTileChunks], vd[kTileChunks];
@@ -182,17 +185,21 @@ __device__ __forceinline__ double tile_weight(const RowPair& rp, int64_t tile, i
         }
     }
     double acc = 0.0;
+    float cs[kTileChunks];
 #pragma unroll
     for (int g = 0; g < kTileChunks; ++g) {
         float w[N];
-        acc += (double)chunk_weights_loaded<BF16>(rp, tile * (64 * kTileChunks) + g * 64 + lane, vp[g], vd[g], w);
+        cs[g] = chunk_weights_loaded<BF16>(rp, tile * (64 * kTileChunks) + g * 64 + lane, vp[g], vd[g], w);
+        acc += (double)cs[g];
     }
+    if (sums != nullptr) sums[tile * 64 + lane] = make_float4(cs[0], cs[1], cs[2], cs[3]);
     return wave_sum(acc) * rp.scale;
 }
 
 // Two tiles with all their loads in flight together (twice the bytes per round trip).
 template <bool BF16, bool FILT = false>
-__device__ __forceinline__ void tile_weight2(const RowPair& rp, int64_t t0, int64_t t1, int lane, double& w0, double& w1)
+__device__ __forceinline__ void tile_weight2(const RowPair& rp, int64_t t0, int64_t t1, int lane, double& w0, double& w1,
+                                             float4* sums = nullptr, int ntiles = 0)
 {
     constexpr int N = BF16 ? 8 : 4;
     uint4 vp[2][kTileChunks], vd[2][kTileChunks];
@@ -203,11 +210,18 @@ __device__ __forceinline__ void tile_weight2(const RowPair& rp, int64_t t0, int6
     }
 
     double a0 = 0.0, a1 = 0.0;
+    float c0[kTileChunks], c1[kTileChunks];
 #pragma unroll
     for (int g = 0; g < kTileChunks; ++g) {
         float w[N];
-        a0 += (double)chunk_weights_loaded<BF16, FILT>(rp, t0 * (64 * kTileChunks) + g * 64 + lane, vp[0][g], vd[0][g], w);
-        a1 += (double)chunk_weights_loaded<BF16, FILT>(rp, t1 * (64 * kTileChunks) + g * 64 + lane, vp[1][g], vd[1][g], w);
+        c0[g] = chunk_weights_loaded<BF16, FILT>(rp, t0 * (64 * kTileChunks) + g * 64 + lane, vp[0][g], vd[0][g], w);
+        c1[g] = chunk_weights_loaded<BF16, FILT>(rp, t1 * (64 * kTileChunks) + g * 64 + lane, vp[1][g], vd[1][g], w);
+        a0 += (double)c0[g];
+        a1 += (double)c1[g];
+    }
+    if (sums != nullptr) {
+        sums[t0 * 64 + lane] = make_float4(c0[0], c0[1], c0[2], c0[3]);
+        if (t1 < ntiles) sums[t1 * 64 + lane] = make_float4(c1[0], c1[1], c1[2], c1[3]);
     }
     w0 = wave_sum(a0) * rp.scale;
     w1 = wave_sum(a1) * rp.scale;
@@ -228,9 +242,11 @@ __device__ __forceinline__ double read_tile(const double* t)
 // Z == 0: p == q everywhere, or a broken draft row) and call again.
 // raw: the target row's chunks as the sweep loaded them, kept in shared memory (bonus weights, whole chunks: the
 // crossing tile is then not read from global memory again), or null.
+// sums: every lane's four chunk sums of every tile as the sweep left them in shared memory ([tile][lane]), or null;
+// with them only the one chunk that holds the crossing is rebuilt element by element.
 template <bool BF16, bool LDS, bool FILT = false>
 __device__ __forceinline__ int32_t select_token(const RowPair& rp, const double* tiles, int ntiles, double u, int lane,
-                                                const uint4* raw = nullptr)
+                                                const uint4* raw = nullptr, const float4* sums = nullptr)
 {
     constexpr int N = BF16 ? 8 : 4;
     const int per = (ntiles + 63) / 64;
@@ -268,17 +284,24 @@ __device__ __forceinline__ int32_t select_token(const RowPair& rp, const double*
     const double before = __shfl(run, src, 64);
     if (tile < 0) return -1;
     // ---- inside the tile
-    float w[kTileChunks][N];
-    float cs[kTileChunks];
-#pragma unroll
-    for (int g = 0; g < kTileChunks; ++g) {
+    // the weights of the lane's chunk g of the tile, element by element (and their sum)
+    auto chunk_w = [&](int g, float* wout) -> float {
         const int64_t c = (int64_t)tile * (64 * kTileChunks) + g * 64 + lane;
         if (raw != nullptr) {
             const uint4 none = make_uint4(0, 0, 0, 0);
-            cs[g] = chunk_weights_loaded<BF16, FILT>(rp, c, c < rp.nchunks ? raw[c] : none, none, w[g]);
-        } else {
-            cs[g] = chunk_weights<BF16, FILT>(rp, c, w[g]);
+            return chunk_weights_loaded<BF16, FILT>(rp, c, c < rp.nchunks ? raw[c] : none, none, wout);
         }
+        return chunk_weights<BF16, FILT>(rp, c, wout);
+    };
+    const bool have_sums = sums != nullptr;                          // the sweep left every lane's chunk sums
+    float w[kTileChunks][N];
+    float cs[kTileChunks];
+    if (have_sums) {
+        const float4 k = sums[tile * 64 + lane];
+        cs[0] = k.x; cs[1] = k.y; cs[2] = k.z; cs[3] = k.w;
+    } else {
+#pragma unroll
+        for (int g = 0; g < kTileChunks; ++g) cs[g] = chunk_w(g, w[g]);
     }
     double base = before;
     int found_g = -1, found_lane = -1;
@@ -297,25 +320,38 @@ __device__ __forceinline__ int32_t select_token(const RowPair& rp, const double*
     }
     int32_t tok = -1;
     if (found_g >= 0) {
-        if (lane == found_lane) {
-            double r = found_excl;
-            int32_t lastpos = -1;
+        // the elements of the one chunk that holds the crossing: rebuilt now (one chunk per lane instead of the
+        // tile's four) when the sums came from the sweep
+        float ws[N];
+        if (have_sums) {
+            chunk_w(found_g, ws);
+        } else {
 #pragma unroll
             for (int g = 0; g < kTileChunks; ++g) {
                 if (g != found_g) continue;
-                const int64_t c = (int64_t)tile * (64 * kTileChunks) + g * 64 + lane;
 #pragma unroll
-                for (int k = 0; k < N; ++k) {
-                    if (w[g][k] > 0.f) lastpos = (int32_t)(c * N) + k - rp.head;
-                    r += (double)w[g][k] * rp.scale;
-                    if (tok < 0 && r > target) tok = (int32_t)(c * N) + k - rp.head;
-                }
+                for (int k = 0; k < N; ++k) ws[k] = w[g][k];
+            }
+        }
+        if (lane == found_lane) {
+            double r = found_excl;
+            int32_t lastpos = -1;
+            const int64_t c = (int64_t)tile * (64 * kTileChunks) + found_g * 64 + lane;
+#pragma unroll
+            for (int k = 0; k < N; ++k) {
+                if (ws[k] > 0.f) lastpos = (int32_t)(c * N) + k - rp.head;
+                r += (double)ws[k] * rp.scale;
+                if (tok < 0 && r > target) tok = (int32_t)(c * N) + k - rp.head;
             }
             if (tok < 0) tok = lastpos;
         }
         tok = __shfl(tok, found_lane, 64);
     } else {
         // the last element of the tile with positive weight
+        if (have_sums) {
+#pragma unroll
+            for (int g = 0; g < kTileChunks; ++g) chunk_w(g, w[g]);
+        }
         int32_t lastpos = -1;
 #pragma unroll
         for (int g = 0; g < kTileChunks; ++g) {
