@@ -69,6 +69,7 @@ struct ScanParams {
     RowFilter* filters;
     int32_t* out_keep_count;
     int32_t skip_draft;                // the draft rows' keep sets are given: only target rows are scanned and decided
+    ExpScale sc;                       // of the call's temperature
 };
 
 // The need-th largest of the keys (kbits wide) that satisfy pred, need >= 1 and at most their number, over a
@@ -281,7 +282,8 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
             // top-p alone: the rank at which about kScanTopPList tokens of the row are expected at or above the edge
             const float per_thread = (float)(it.n_c * N) / (float)threads;
             const float q = fminf(1.f, (float)kScanTopPList / (float)row_elems);
-            const float rk = (float)threads * (1.f - powf(1.f - q, per_thread));
+            // (1 - q)^per_thread on the transcendental unit: the rank only sizes the lists, it decides nothing
+            const float rk = (float)threads * (1.f - __builtin_amdgcn_exp2f(per_thread * __builtin_amdgcn_logf(1.f - q)));
             const uint32_t top = (uint32_t)((float)threads * 0.75f);
             rank = (uint32_t)(rk + 0.5f);
             rank = rank > top ? top : rank;
@@ -457,8 +459,7 @@ __global__ __launch_bounds__(kScanThreads) void filter_scan_kernel(ScanParams p)
 {
     __shared__ ScanShared sh;
     if (threadIdx.x == 0) { sh.status = 0; sh.count = 0; }
-    ExpScale sc{};
-    if (MASS) sc = make_scale(kLog2e / (double)p.temperature);
+    const ExpScale sc = p.sc;
     uint4 v[ScanU<BF16>::value];
     const ScanItem it = scan_item<BF16>(p, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z);   // grid: nseg x (2 gamma + 1) x B
     scan_load<BF16>(it, v);
@@ -886,6 +887,7 @@ static ScanParams scan_params(const void* target, const void* draft, int dtype, 
     p.target = target; p.draft = draft; p.target_ld = target_ld; p.draft_ld = draft_ld; p.draft_len = draft_len;
     p.temperature = temperature; p.B = B; p.gamma = gamma; p.V = V; p.top_k = top_k; p.top_p = top_p;
     p.filters = filters; p.out_keep_count = out_keep_count; p.skip_draft = skip_draft;
+    p.sc = host_scale((double)temperature);
     p.nseg = scan_segments(dtype, V);
     p.cap_seg = kScanStore / p.nseg;
     const int N = dtype == HOLA_DTYPE_BF16 ? 8 : 4;

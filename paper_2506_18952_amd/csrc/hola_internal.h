@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 #include "../../include/hola.h"
 
 namespace hola {
@@ -38,6 +39,29 @@ struct RowFilter {
     int32_t n_keep;                    // kept tokens (-1: every finite logit)
     int32_t pad;
 };
+
+// Constants of the exponent argument y = x * cstar + b.  make_scale (device) and host_scale compute the same bits:
+// a call with one temperature has them made once on the host instead of by every wavefront.
+struct ExpScale {
+    double cstar;          // log2(e) / temperature
+    float c_hi, c_lo;      // cstar = c_hi + c_lo (fp32 pair)
+    float c1, c2;          // cstar = c1 + c2 with c1 of 16 significant bits (bf16 path)
+    float inv_c;           // 1 / c_hi
+};
+inline ExpScale host_scale(double temperature)
+{
+    ExpScale s;
+    s.cstar = 1.4426950408889634074 / temperature;
+    s.c_hi = (float)s.cstar;
+    s.c_lo = (float)(s.cstar - (double)s.c_hi);
+    uint32_t bits;
+    memcpy(&bits, &s.c_hi, 4);
+    bits = (bits + 0x80u) & 0xffffff00u;
+    memcpy(&s.c1, &bits, 4);
+    s.c2 = (float)(s.cstar - (double)s.c1);
+    s.inv_c = 1.0f / s.c_hi;
+    return s;
+}
 
 struct Shape {
     int32_t B, gamma, V, dtype;
@@ -83,6 +107,8 @@ struct RowStatsParams {
     const int32_t* tree_parent;        // device [B, gamma] or null: token trees, node parents; draft rows of
                                        // contexts without children are skipped
     Partial* partials;
+    ExpScale sc;                       // set by the launcher when the call has one temperature > 0 (sc_given)
+    int32_t sc_given;
 };
 
 struct AcceptParams {

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(RowStatsParams p)
 
     const float Tb = p.row_temperature ? p.row_temperature[b] : p.temperature;
     const bool greedy = !(Tb > 0.f);
-    const ExpScale sc = make_scale(greedy ? kLog2e : kLog2e / (double)Tb);
+    const ExpScale sc = p.sc_given ? p.sc : make_scale(greedy ? kLog2e : kLog2e / (double)Tb);
     constexpr int ES = BF16 ? 2 : 4;
     const char* row;
     int64_t slot;
@@ -103,8 +103,11 @@ int choose_split(int64_t rows, int V, int dtype, const Tuning& t)
 }
 
 template <bool BF16>
-static hipError_t launch_typed(const RowStatsParams& p, const Tuning& t, hipStream_t s)
+static hipError_t launch_typed(const RowStatsParams& p_in, const Tuning& t, hipStream_t s)
 {
+    RowStatsParams p = p_in;
+    p.sc_given = (p.row_temperature == nullptr && p.temperature > 0.f) ? 1 : 0;
+    if (p.sc_given) p.sc = host_scale((double)p.temperature);
     const int g = p.gamma;
     const int64_t rows = (int64_t)p.B * ((p.skip_draft ? 0 : g) + (p.skip_target ? 0 : g + 1));
     const int64_t nblk = rows * p.nsplit;

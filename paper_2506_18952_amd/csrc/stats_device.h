@@ -18,13 +18,6 @@
 
 namespace hola {
 
-struct ExpScale {
-    double cstar;          // log2(e) / temperature
-    float c_hi, c_lo;      // cstar = c_hi + c_lo (fp32 pair)
-    float c1, c2;          // cstar = c1 + c2 with c1 of 16 significant bits (bf16 path)
-    float inv_c;           // 1 / c_hi
-};
-
 __device__ __forceinline__ ExpScale make_scale(double cstar)
 {
     ExpScale s;
