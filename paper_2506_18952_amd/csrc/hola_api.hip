@@ -141,25 +141,31 @@ static bool call_tuning(const hola_tuning* t, Tuning* out)
     return tuning_from(t, out);
 }
 
+// base == nullptr: only the size is wanted (no pointer is formed).
 static Workspace carve(void* base, int32_t B, int32_t gamma, int32_t V, bool with_filters = true)
 {
-    Workspace w;
-    char* p = (char*)base;
+    Workspace w{};
     size_t off = 0;
+    auto take = [&](size_t bytes) -> char* {
+        char* at = base ? (char*)base + off : nullptr;
+        off = align_up(off + bytes);
+        return at;
+    };
     const size_t rows = (size_t)B * (2 * (size_t)gamma + 1);
     const int ntiles = sampler_tiles(V, HOLA_DTYPE_F32);       // the larger of the two dtypes
-    w.partials = (Partial*)(p + off); off = align_up(off + rows * kMaxSplit * kWaves * sizeof(Partial));
-    w.statsD = (double*)(p + off);    off = align_up(off + (size_t)B * gamma * 2 * sizeof(double));
-    w.statsP = (double*)(p + off);    off = align_up(off + (size_t)B * (gamma + 1) * 2 * sizeof(double));
-    w.argmaxP = (int32_t*)(p + off);  off = align_up(off + (size_t)B * (gamma + 1) * sizeof(int32_t));
-    w.seq = (SeqInfo*)(p + off);      off = align_up(off + (size_t)B * sizeof(SeqInfo));
-    w.tiles = (double*)(p + off);     off = align_up(off + (size_t)B * ntiles * sizeof(double));
+    w.partials = (Partial*)take(rows * kMaxSplit * kWaves * sizeof(Partial));
+    w.statsD = (double*)take((size_t)B * gamma * 2 * sizeof(double));
+    w.statsP = (double*)take((size_t)B * (gamma + 1) * 2 * sizeof(double));
+    w.argmaxP = (int32_t*)take((size_t)B * (gamma + 1) * sizeof(int32_t));
+    w.seq = (SeqInfo*)take((size_t)B * sizeof(SeqInfo));
+    w.tiles = (double*)take((size_t)B * ntiles * sizeof(double));
     w.filters = nullptr;
     w.filter_scan = nullptr;
     if (with_filters) {                                        // keep sets and candidate lists: filtered calls only
-        w.filters = (RowFilter*)(p + off); off = align_up(off + rows * sizeof(RowFilter));
+        w.filters = (RowFilter*)take(rows * sizeof(RowFilter));
         const size_t scan_bytes = filter_scan_bytes((int64_t)rows);
-        w.filter_scan = scan_bytes ? p + off : nullptr; off = align_up(off + scan_bytes);
+        char* at = take(scan_bytes);
+        w.filter_scan = scan_bytes ? at : nullptr;
     }
     w.bytes = off;
     return w;
@@ -523,13 +529,18 @@ HsdWs carve_hsd(void* base, int32_t n_models, int32_t B, int32_t gamma, int32_t 
 {
     HsdWs h;
     const int32_t gmax = gamma + n_models - 2;
-    char* p = (char*)base;
     size_t off = 0;
-    h.level = p; h.level_bytes = hola_workspace_bytes(B, gmax, V); off = align_up(h.level_bytes);
-    for (int i = 0; i < 2; ++i) { h.tok[i] = (int32_t*)(p + off); off = align_up(off + (size_t)B * (gmax + 1) * sizeof(int32_t)); }
-    for (int i = 0; i < 2; ++i) { h.len[i] = (int32_t*)(p + off); off = align_up(off + (size_t)B * sizeof(int32_t)); }
-    for (int i = 0; i < 2; ++i) { h.stats[i] = (double*)(p + off); off = align_up(off + (size_t)B * (gmax + 1) * 2 * sizeof(double)); }
-    for (int i = 0; i < 2; ++i) { h.filt[i] = (RowFilter*)(p + off); off = align_up(off + (size_t)B * (gmax + 1) * sizeof(RowFilter)); }
+    auto take = [&](size_t bytes) -> char* {                   // base == nullptr: only the size is wanted
+        char* at = base ? (char*)base + off : nullptr;
+        off = align_up(off + bytes);
+        return at;
+    };
+    h.level_bytes = hola_workspace_bytes(B, gmax, V);
+    h.level = take(h.level_bytes);
+    for (int i = 0; i < 2; ++i) h.tok[i] = (int32_t*)take((size_t)B * (gmax + 1) * sizeof(int32_t));
+    for (int i = 0; i < 2; ++i) h.len[i] = (int32_t*)take((size_t)B * sizeof(int32_t));
+    for (int i = 0; i < 2; ++i) h.stats[i] = (double*)take((size_t)B * (gmax + 1) * 2 * sizeof(double));
+    for (int i = 0; i < 2; ++i) h.filt[i] = (RowFilter*)take((size_t)B * (gmax + 1) * sizeof(RowFilter));
     h.bytes = off;
     return h;
 }
