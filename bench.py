@@ -127,6 +127,20 @@ def _roofline(hb, per_stage, stage, kname, k_bytes, traffic_key):
             "statistic": "median launch of the kernel, HIP events on the launch stream"}
 
 
+def _host_info():
+    """The host the CPU baseline ran on: logical CPUs visible and the processor's model name."""
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {"nproc": os.cpu_count(), "cpu_model": model}
+
+
 def _to_dev(a, dev="cuda:0"):
     import numpy as np
     import torch
@@ -636,7 +650,7 @@ def main() -> int:
                                          f"({len(taus)} oracle calls, {cdt:.2f}s wall, {cdt * threads:.0f} core-seconds); "
                                          f"float64 C oracle, OpenMP over sequences",
                                "agree_accept_len": f"{same}/{n}", "agree_next_token": f"{same_t}/{n}",
-                               "oracle_listed_near_threshold": near}
+                               "oracle_listed_near_threshold": near, "host": _host_info()}
     print(json.dumps(out), flush=True)
     return 0
 
