@@ -1,4 +1,4 @@
-// Per-sequence kernels: one workgroup of 8 or 16 wavefronts owns one sequence.
+// Per-sequence kernels: one workgroup of 4, 8 or 16 wavefronts owns one sequence.
 //
 // fused_kernel runs the whole verify step for its sequence without leaving the compute unit: row
 // statistics of its gamma draft and gamma+1 target rows (streamed once from HBM, wavefront partials
@@ -6,8 +6,9 @@
 // the stop row (all wavefronts, tile weights in LDS) and the inverse-CDF selection (wavefront 0).
 //
 // tail_kernel is the same minus the streaming pass: it takes the row partials the split-row kernel
-// left in HBM (one wavefront merges one row, a lane per partial) and does accept + sampling, so the
-// split path is two launches instead of four.
+// left in HBM (a segment of lanes merges one row, a lane per partial) and does accept + sampling, so the
+// split path is two launches instead of four.  Its phases are arranged so that memory round trips overlap:
+// see tail_kernel and sequence_tail.
 //
 // HBM-bound: every logit is read once, the stop row pair once more.  No atomics, no spin waits.
 #include "accept_device.h"
