@@ -109,9 +109,31 @@ __device__ __forceinline__ void accum_elem(LaneState& st, float x, int32_t idx, 
     st.Td += (double)(y * e);
 }
 
+// The sums of one chunk's terms with -inf logits left out, in the order of the fast path.  A -inf logit (a masked
+// or padded vocabulary entry) carries no mass, but the unguarded arithmetic turns it into NaN: y 2^y = -inf x 0, and
+// y itself when the low part of the scale constant is negative (-inf x c2 = +inf, added to -inf).
+template <bool BF16, bool WITH_T>
+__device__ __forceinline__ void chunk_sums_guarded(const uint4& v, float ref, const ExpScale& sc, float& s_out, float& t_out)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    float s = 0.f, t[2] = {0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const float x = chunk_elem<BF16>(v, k);
+        if (x == -INFINITY) continue;
+        const float y = exp_arg<BF16>(x, ref, sc);
+        const float e = fast_exp2(y);
+        s += e;
+        if (WITH_T) t[k & 1] = __builtin_fmaf(y, e, t[k & 1]);
+    }
+    s_out = s;
+    t_out = t[0] + t[1];
+}
+
 // Fast path: one 16-byte chunk, no per-element guards.  WITH_T = false leaves out T = sum y 2^y (rows of which
-// only the normaliser is wanted: a -inf logit then simply adds nothing).
-template <bool BF16, bool ARGMAX, bool WITH_T = true>
+// only the normaliser is wanted).  GUARDED: -inf logits are left out of the sums (the second try of a wavefront
+// whose unguarded sums came out NaN).
+template <bool BF16, bool ARGMAX, bool WITH_T = true, bool GUARDED = false>
 __device__ __forceinline__ void accum_chunk(LaneState& st, const uint4& v, int32_t elem0, const ExpScale& sc)
 {
     constexpr int N = BF16 ? 8 : 4;
@@ -129,6 +151,13 @@ __device__ __forceinline__ void accum_chunk(LaneState& st, const uint4& v, int32
         }
         on_exceed<BF16, ARGMAX>(st, mx, idx, sc);
     }
+    if (GUARDED) {
+        float s, tt;
+        chunk_sums_guarded<BF16, WITH_T>(v, st.ref, sc, s, tt);
+        st.Sd += (double)s;
+        if (WITH_T) st.Td += (double)tt;
+        return;
+    }
     float e[N], t[2] = {0.f, 0.f};
 #pragma unroll
     for (int k = 0; k < N; ++k) {
@@ -144,10 +173,17 @@ __device__ __forceinline__ void accum_chunk(LaneState& st, const uint4& v, int32
 }
 
 // The sums of one chunk's terms against the lane's reference, added to its state; no trigger.
-template <bool BF16, bool WITH_T>
+template <bool BF16, bool WITH_T, bool GUARDED = false>
 __device__ __forceinline__ void accum_chunk_terms(LaneState& st, const uint4& v, const ExpScale& sc)
 {
     constexpr int N = BF16 ? 8 : 4;
+    if (GUARDED) {
+        float s, tt;
+        chunk_sums_guarded<BF16, WITH_T>(v, st.ref, sc, s, tt);
+        st.Sd += (double)s;
+        if (WITH_T) st.Td += (double)tt;
+        return;
+    }
     float e[N], t[2] = {0.f, 0.f};
 #pragma unroll
     for (int k = 0; k < N; ++k) {
@@ -279,7 +315,7 @@ __device__ __forceinline__ void wave_slab(const RowGeom& g, int seg, int nsplit,
 
 // One wavefront's pass over the chunks c0, c0 + stride, ... < c_hi of a row (c0 already holds the lane's
 // offset), plus, if do_edges, the edge elements (fewer than two chunks' worth, one per lane).
-template <bool BF16, bool ARGMAX, int U, bool ROBUST, bool WITH_T = true>
+template <bool BF16, bool ARGMAX, int U, bool ROBUST, bool WITH_T = true, bool GUARDED = false>
 __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64_t c0, int64_t c_hi_in, int64_t stride_in,
                                           bool do_edges, const ExpScale& sc, int lane)
 {
@@ -324,13 +360,13 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
             for (int u = 1; u < U; ++u) mx = fmaxf(mx, chunk_max<BF16>(buf[u]));
             if (mx > st.thr) on_exceed<BF16, ARGMAX>(st, mx, 0, sc);
 #pragma unroll
-            for (int u = 0; u < U; ++u) accum_chunk_terms<BF16, WITH_T>(st, buf[u], sc);
+            for (int u = 0; u < U; ++u) accum_chunk_terms<BF16, WITH_T, GUARDED>(st, buf[u], sc);
         } else {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int32_t e0 = (int32_t)((c + u * stride) * N) - g.head;
                 if (ROBUST) accum_chunk_robust<BF16, ARGMAX>(st, buf[u], e0, sc);
-                else accum_chunk<BF16, ARGMAX, WITH_T>(st, buf[u], e0, sc);
+                else accum_chunk<BF16, ARGMAX, WITH_T, GUARDED>(st, buf[u], e0, sc);
             }
         }
         w += (int64_t)U * stride;
@@ -363,7 +399,7 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
             if (c + u * stride < c_hi) {
                 const int32_t e0 = (int32_t)((c + u * stride) * N) - g.head;
                 if (ROBUST) accum_chunk_robust<BF16, ARGMAX>(st, buf[u], e0, sc);
-                else accum_chunk<BF16, ARGMAX, WITH_T>(st, buf[u], e0, sc);
+                else accum_chunk<BF16, ARGMAX, WITH_T, GUARDED>(st, buf[u], e0, sc);
             }
         }
     }
@@ -376,8 +412,10 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
     }
 }
 
-// A wavefront's share of a row, with the fallback pass when the fast pass meets a -inf logit (its
-// y * 2^y is NaN) or anything else non-finite.
+// A wavefront's share of a row.  The fast pass has no guards; if its sums are not finite the wavefront goes over
+// its share again: first with -inf logits left out of the sums (masked or padded vocabulary entries, whose
+// unguarded terms are NaN: the usual cause, and this second try costs about as much as the first), and only if that
+// fails too (a NaN or +inf logit, an overflow) element by element with every guard.
 template <bool BF16, bool ARGMAX, int U, bool WITH_T = true>
 __device__ __forceinline__ Partial wave_row_share(const RowGeom& g, int64_t c0, int64_t c_hi, int64_t stride,
                                                   bool do_edges, const ExpScale& sc, int lane)
@@ -385,8 +423,13 @@ __device__ __forceinline__ Partial wave_row_share(const RowGeom& g, int64_t c0, 
     LaneState st;
     wave_pass<BF16, ARGMAX, U, false, WITH_T>(st, g, c0, c_hi, stride, do_edges, sc, lane);
     Partial res = wave_merge<BF16, ARGMAX>(st, sc);
-    const bool finite = (res.S - res.S == 0.0) && (res.T - res.T == 0.0);
+    bool finite = (res.S - res.S == 0.0) && (res.T - res.T == 0.0);
     if (!finite) {                                      // wavefront-uniform
+        wave_pass<BF16, ARGMAX, U, false, WITH_T, true>(st, g, c0, c_hi, stride, do_edges, sc, lane);
+        res = wave_merge<BF16, ARGMAX>(st, sc);
+        finite = (res.S - res.S == 0.0) && (res.T - res.T == 0.0);
+    }
+    if (!finite) {
         wave_pass<BF16, ARGMAX, 2, true>(st, g, c0, c_hi, stride, do_edges, sc, lane);
         res = wave_merge<BF16, ARGMAX>(st, sc);
     }
