@@ -390,6 +390,35 @@ def test_masked_vocabulary_and_degenerate_rows():
     assert g2.accept_len[2] == r2.accept_len[2] == 0 and g2.next_token[2] == r2.next_token[2] == -1
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("temperature", [0.8, 1.0, 1.3])
+def test_padded_and_masked_vocabulary_on_wide_rows(dtype, temperature):
+    """Rows of headline width whose last 256 entries are -inf (a padded vocabulary) and rows with 30 % of the entries
+    masked: the wavefronts that meet them repeat their share with -inf left out of the sums.  Several temperatures,
+    because the sign of the scale constant's low part decides whether a -inf logit spoils S as well as T."""
+    B, g, V = 6, 3, 128256
+    w = wl.small_case(B, g, V, dtype=dtype, temperature=temperature, case_id=305)
+    P, D, tok = w.target.copy(), w.draft.copy(), w.tokens.copy()
+    neg = np.uint16(0xff80) if dtype == "bf16" else np.float32(-np.inf)
+    mask = np.zeros(V, bool)
+    mask[V - 256:] = True
+    rnd = np.random.default_rng(7).random(V) < 0.3
+    for b in range(B):
+        m = mask | rnd if b % 2 else mask                    # odd sequences: also 30 % masked at random
+        P[b, :, m] = neg
+        D[b, :, m] = neg
+        ok = np.flatnonzero(~m)
+        for j in range(g):
+            if m[tok[b, j]]:
+                tok[b, j] = int(ok[(b * 7 + j) % ok.size])
+    for tau in (0.0, 0.5 * math.log(V), float("inf")):
+        gpu = run_gpu_level(P, D, tok, 11, temperature, tau)
+        rep = compare_level(P, D, tok, 11, temperature, tau, gpu)
+        _report(f"padded/masked wide rows {dtype} T={temperature} tau={tau:.3f}", rep)
+        assert rep.max_entropy_abs < 1e-6
+        assert np.all((gpu.next_token < V - 256) & (gpu.next_token >= 0))
+
+
 def test_huge_dynamic_range_and_identical_models():
     rng = np.random.default_rng(2)
     B, g, V = 4, 3, 5000
