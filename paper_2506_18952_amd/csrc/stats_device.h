@@ -168,8 +168,13 @@ __device__ __forceinline__ void accum_chunk(LaneState& st, const uint4& v, int32
     float s;
     if (N == 8) s = ((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]));
     else s = (e[0] + e[1]) + (e[2] + e[3]);
+    float tt = WITH_T ? t[0] + t[1] : 0.f;
+    if (!ARGMAX) {                                              // the few chunks of a wavefront's last, partial group
+        const float chk = WITH_T ? tt : s;
+        if (!(chk == chk)) chunk_sums_guarded<BF16, WITH_T>(v, st.ref, sc, s, tt);   // a -inf logit in the chunk (a NaN stays one)
+    }
     st.Sd += (double)s;
-    if (WITH_T) st.Td += (double)(t[0] + t[1]);
+    if (WITH_T) st.Td += (double)tt;
 }
 
 // The sums of one chunk's terms against the lane's reference, added to its state; no trigger.
@@ -331,12 +336,35 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
     global_byte_ptr wb = (global_byte_ptr)wave_uniform((int64_t)(uintptr_t)(g.rowv + w0));
     const uint32_t voff = (uint32_t)lane * 16u;
     const int64_t sb = stride * 16;
+    // The fast pass looks after -inf logits (masked or padded vocabulary entries, whose unguarded terms are NaN)
+    // one group late: once the NEXT group's loads are in flight, a lane whose sums the previous group spoiled takes
+    // them back to what they were before it and redoes that group's chunks with the guarded sums (loaded again:
+    // keeping them would cost the loop 28 registers).  Looked at right after the group, the same test held up the
+    // next loads behind the group's last addition (+2 us on the headline); here it costs nothing measurable.
+    constexpr bool REPAIR = !ROBUST && !ARGMAX && !GUARDED;
+    double Sd_before = 0.0, Td_before = 0.0;                    // the lane's sums before the terms of the previous group
+    bool have_prev = false;                                     // wavefront-uniform
+    auto repair_previous = [&]() {
+        const double chk = WITH_T ? st.Td : st.Sd;              // one sum tells: a -inf logit always spoils T, and S when it spoils y
+        if (!(chk == chk)) {
+            st.Sd = Sd_before; st.Td = Td_before;
+            const global_byte_ptr pb = wb - (int64_t)U * sb;
+#pragma unroll 1
+            for (int u = 0; u < U; ++u) {                       // a rolled loop: few registers matter more here than speed
+                float s1, t1;
+                chunk_sums_guarded<BF16, WITH_T>(load_stream((global_chunk_ptr)(pb + u * sb + voff)), st.ref, sc, s1, t1);
+                st.Sd += (double)s1;
+                if (WITH_T) st.Td += (double)t1;
+            }
+        }
+    };
     // groups in which every lane of the wavefront has U chunks: no guards
     while (w + 63 + (int64_t)(U - 1) * stride < c_hi) {
         uint4 buf[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) buf[u] = load_stream((global_chunk_ptr)(wb + u * sb + voff));
         __builtin_amdgcn_sched_barrier(0);                      // every load of the group is issued before any is used
+        if (REPAIR && have_prev) repair_previous();
         const int64_t c = w + lane;
         if (need_ref) {
             float mx = -INFINITY;
@@ -359,6 +387,7 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
 #pragma unroll
             for (int u = 1; u < U; ++u) mx = fmaxf(mx, chunk_max<BF16>(buf[u]));
             if (mx > st.thr) on_exceed<BF16, ARGMAX>(st, mx, 0, sc);
+            if (REPAIR) { Sd_before = st.Sd; Td_before = st.Td; have_prev = true; }
 #pragma unroll
             for (int u = 0; u < U; ++u) accum_chunk_terms<BF16, WITH_T, GUARDED>(st, buf[u], sc);
         } else {
@@ -372,6 +401,7 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
         w += (int64_t)U * stride;
         wb += (int64_t)U * sb;
     }
+    if (REPAIR && have_prev) repair_previous();                 // the last full group
     // the last, partial group: all its loads are issued together, each one guarded
     if (w < c_hi) {
         const int64_t c = w + lane;
