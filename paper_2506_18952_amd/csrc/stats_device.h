@@ -349,12 +349,19 @@ __device__ __forceinline__ void wave_pass(LaneState& st, const RowGeom& g, int64
         if (!(chk == chk)) {
             st.Sd = Sd_before; st.Td = Td_before;
             const global_byte_ptr pb = wb - (int64_t)U * sb;
-#pragma unroll 1
-            for (int u = 0; u < U; ++u) {                       // a rolled loop: few registers matter more here than speed
-                float s1, t1;
-                chunk_sums_guarded<BF16, WITH_T>(load_stream((global_chunk_ptr)(pb + u * sb + voff)), st.ref, sc, s1, t1);
-                st.Sd += (double)s1;
-                if (WITH_T) st.Td += (double)t1;
+            constexpr int R = U >= 2 ? 2 : U;                   // chunks loaded together: a rolled loop over U / R rounds, because
+#pragma unroll 1                                                // few registers matter more here than speed
+            for (int u0 = 0; u0 < U; u0 += R) {
+                uint4 again[R];
+#pragma unroll
+                for (int r = 0; r < R; ++r) again[r] = load_stream((global_chunk_ptr)(pb + (u0 + r) * sb + voff));
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float s1, t1;
+                    chunk_sums_guarded<BF16, WITH_T>(again[r], st.ref, sc, s1, t1);
+                    st.Sd += (double)s1;
+                    if (WITH_T) st.Td += (double)t1;
+                }
             }
         }
     };
