@@ -21,7 +21,6 @@ constexpr int kFusedMaxTiles = 2048;
 constexpr int kFusedMaxGamma = 32;           // the fused kernel parks the partials of its 2 gamma + 1 rows in shared memory
 
 constexpr int kSlabKeepChunks = 8 * 64 * kTileChunks;   // a slab of up to eight tiles is kept in shared memory (32 KB)
-constexpr int kSumsKeepTiles = 80;                       // the lanes' chunk sums of up to 80 tiles are kept there too (80 KB)
 
 struct SeqShared {
     RowStat stat[2 * HOLA_MAX_GAMMA + 1];      // per row: draft rows 0..g-1, target rows g..2g

@@ -23,6 +23,7 @@ __global__ __launch_bounds__(NW * 64) void literal_kernel(FusedParams p, const P
                                                           int32_t* __restrict__ out_tokens, int32_t* __restrict__ out_calls)
 {
     __shared__ LiteralShared sh;
+    __shared__ float4 s_sums[NW == 16 ? kSumsKeepTiles * 64 : 1];   // the lanes' chunk sums of a sweep, for its selection
     const int b = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = p.gamma;
@@ -78,9 +79,10 @@ __global__ __launch_bounds__(NW * 64) void literal_kernel(FusedParams p, const P
         si.u = u24(r.y);
         RowPair rp;
         make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1);
+        float4* const sums = (NW == 16 && p.ntiles <= kSumsKeepTiles) ? s_sums : nullptr;   // uniform
         for (int tl = wave; tl < p.ntiles; tl += 2 * NW) {
             double w0 = 0.0, w1 = 0.0;
-            if (rp.ok) tile_weight2<BF16>(rp, tl, tl + NW, lane, w0, w1);
+            if (rp.ok) tile_weight2<BF16>(rp, tl, tl + NW, lane, w0, w1, sums, p.ntiles);
             if (lane == 0) {
                 sh.tiles[tl] = w0;
                 if (tl + NW < p.ntiles) sh.tiles[tl + NW] = w1;
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(NW * 64) void literal_kernel(FusedParams p, const P
         }
         __syncthreads();
         if (wave == 0) {
-            const int32_t tk = rp.ok ? select_token<BF16, true>(rp, sh.tiles, p.ntiles, si.u, lane) : -1;
+            const int32_t tk = rp.ok ? select_token<BF16, true>(rp, sh.tiles, p.ntiles, si.u, lane, nullptr, sums) : -1;
             if (lane == 0) out_tokens[(int64_t)b * g + t] = tk < 0 ? -1 : tk;
         }
         __syncthreads();

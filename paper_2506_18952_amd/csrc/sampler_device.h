@@ -165,6 +165,10 @@ __device__ __forceinline__ float chunk_weights(const RowPair& rp, int64_t c, flo
     return chunk_weights_loaded<BF16, FILT>(rp, c, vp, vd, w);
 }
 
+// A sweep of up to this many tiles can leave every lane's chunk sums in shared memory (1 KB per tile) for
+// select_token, in the kernels whose workgroup has a compute unit to itself.
+constexpr int kSumsKeepTiles = 80;
+
 // Weight of one tile: lanes take chunks tile*256 + g*64 + lane, g = 0..3.  Every lane returns the sum.
 // keep: shared-memory copy of the target row's chunks for select_token (indexed by chunk), or null.
 // sums: shared memory for the lanes' four chunk sums of every tile ([tile][lane]), which select_token then need
