@@ -131,57 +131,23 @@ __device__ __forceinline__ void write_glue(const FusedParams& p, int b, int a, i
     if (threadIdx.x == 0) p.glue_len[b] = a + (p.glue_keep_next ? 1 : 0);
 }
 
-// Bonus draw from one slab of the row, decided before the accept stage has run.  On the row a bonus token would come
-// from (target row len) every split-row partial is the mass of one contiguous slab of tokens, in index order, so the
-// slab that holds the draw follows from the partials and the sampling uniform of position len alone; neither depends
-// on the accept stage, so one wavefront does this while the others merge statistics and gather the drafted tokens'
-// logits, and the slab can be swept while the accept stage decides.  If the sequence turns out rejected, the work
-// is dropped.  Called by one whole wavefront; fills sh.slab_*.
+// Bonus draw from one slab of the row, decided before the accept stage has run: pick_row_slab (sampler_device.h) for
+// target row len with the sampling uniform of position len.  Neither depends on the accept stage, so one wavefront
+// does this while the others merge statistics and gather the drafted tokens' logits, and the slab can be swept while
+// the accept stage decides.  If the sequence turns out rejected, the work is dropped.  Called by one whole
+// wavefront; fills sh.slab_*.
 template <bool BF16>
 __device__ __forceinline__ void pick_bonus_slab(const FusedParams& p, SeqShared& sh, int b, int len,
-                                                const Partial* __restrict__ parts, int nparts, int lane)
+                                                const Partial* parts, int nparts, int lane)
 {
-    constexpr int ES = BF16 ? 2 : 4;
-    const int g = p.gamma;
-    int ok = 0;
+    const uint64_t seq = (uint64_t)(p.seq_base + b);
+    const Philox4 r = philox4x32_10((uint32_t)len, (uint32_t)seq, (uint32_t)(seq >> 32), p.level,
+                                    (uint32_t)p.seed, (uint32_t)(p.seed >> 32));
     int64_t lo = 0, hi = 0;
     double frac = 0.0;
-    const RowGeom geo = make_geom<BF16>((const char*)p.target + ((int64_t)b * (g + 1) + len) * p.target_ld * ES, p.V);
-    if (geo.edge_lo_end == 0 && geo.edge_hi_begin == p.V) {        // no ragged ends: the slabs are all of the row
-        const uint64_t seq = (uint64_t)(p.seq_base + b);
-        const Philox4 r = philox4x32_10((uint32_t)len, (uint32_t)seq, (uint32_t)(seq >> 32), p.level,
-                                        (uint32_t)p.seed, (uint32_t)(p.seed >> 32));
-        const double u = (double)u24(r.y);                         // the sampling uniform of position len
-        const Partial* ps = parts + ((int64_t)p.B * g + (int64_t)b * (g + 1) + len) * nparts;
-        double S = 0.0, br = 0.0;
-        if (lane < nparts) { S = ps[lane].S; br = ps[lane].bref; }
-        const bool has = S > 0.0 && S < INFINITY;
-        const double bmin = wave_min(has ? br : (double)INFINITY);
-        const double W = has ? S * exp2(bmin - br) : 0.0;          // the slab's mass against a common reference
-        const double incl = wave_inclusive_scan(W, lane);
-        const double Z = __shfl(incl, 63, 64);
-        const double target = u * Z;
-        const unsigned long long hit = __ballot(incl > target);
-        const int src = hit ? __ffsll((long long)hit) - 1 : 0;
-        const double w_src = __shfl(W, src, 64), excl = __shfl(incl - W, src, 64);
-        ok = (Z > 0.0 && Z < INFINITY && hit && w_src > 0.0) ? 1 : 0;
-        frac = ok ? (target - excl) / w_src : 0.0;
-        frac = frac < 0.0 ? 0.0 : (frac > 0.999999999 ? 0.999999999 : frac);
-        int64_t seg_lo, seg_hi;
-        wave_slab(geo, src / kWaves, nparts / kWaves, src % kWaves, seg_lo, seg_hi, lo, hi);
-        if (hi <= lo) ok = 0;
-    }
+    const int ok = pick_row_slab<BF16>(p.target, p.target_ld, p.gamma, p.V, p.B, b, len, parts, nparts, (double)u24(r.y), lane,
+                                       lo, hi, frac) ? 1 : 0;
     if (lane == 0) { sh.slab_lo = lo; sh.slab_hi = hi; sh.slab_u = frac; sh.slab_ok = ok; }
-}
-
-// A row pair narrowed to the chunks [lo, hi) of the target row, as a row of its own (bonus weights only).
-template <bool BF16>
-__device__ __forceinline__ void narrow_to_slab(RowPair& rp, int64_t lo, int64_t hi)
-{
-    constexpr int N = BF16 ? 8 : 4;
-    rp.Pv += lo;                                                   // head is 0 on rows that have slabs
-    rp.nchunks = hi - lo;
-    rp.V = (int32_t)((hi - lo) * N);
 }
 
 // Accept stage (wavefront 0) and sampling (all wavefronts) of sequence b, given sh.stat[] and, in wavefront 0, the

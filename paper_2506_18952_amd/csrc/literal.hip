@@ -3,7 +3,8 @@
 // y_t = f_ver(x, draft_<t), a draw from the verifier's distribution at position t (argmax on greedy
 // rows).  There is no ratio test and no stop at a replaced token; the number of verifier draws per
 // sequence is the k of Section 3.1.  Row statistics come from the split-row kernel's partials; each
-// non-gated position costs one more sweep of its target row (tile weights in LDS) and one tile re-read.
+// non-gated position costs one more sweep of a slab of its target row by one wavefront (or, where the row has no
+// slabs, of the whole row by the workgroup).
 #include "accept_device.h"
 #include "sampler_device.h"
 
@@ -11,10 +12,14 @@ namespace hola {
 
 constexpr int kLiteralMaxTiles = 2048;
 
+constexpr int kWaveSlabTiles = 16;     // largest slab a single wavefront sweeps for a draw of its own
+
 struct LiteralShared {
     RowStat stat[2 * HOLA_MAX_GAMMA + 1];
     double tiles[kLiteralMaxTiles];
+    double wave_tiles[16][kWaveSlabTiles];   // per wavefront: the tile weights of the slab it sweeps
     unsigned long long mask;
+    unsigned long long mask_left;      // draws left to the whole-workgroup loop
     int32_t tok;
 };
 
@@ -61,6 +66,7 @@ __global__ __launch_bounds__(NW * 64) void literal_kernel(FusedParams p, const P
         }
         const unsigned long long m = __ballot(need);
         if (lane == 0) {
+            sh.mask_left = 0ull;
             sh.mask = greedy ? 0ull : m;
             if (out_calls) out_calls[b] = __popcll(m);
         }
@@ -68,6 +74,58 @@ __global__ __launch_bounds__(NW * 64) void literal_kernel(FusedParams p, const P
     __syncthreads();
     unsigned long long mask = sh.mask;
     const uint64_t seq = (uint64_t)(p.seq_base + b);
+
+    // ---- the verifier draws of a sequence do not depend on one another, so each wavefront takes one and does it by
+    // itself: the statistics pass took this mode's target rows over contiguous slabs, so the slab that holds the draw
+    // follows from the row's partials and the position's sampling uniform (pick_row_slab), and a wavefront sweeps and
+    // searches that slab (an eighth of the row on the headline shape) alone.  Draws that cannot go this way (ragged
+    // rows, a slab of more than kWaveSlabTiles tiles, no mass found by the sampler's arithmetic) are left to the
+    // loop below, which gives the whole workgroup to one draw after the other.
+    if (nparts >= 4 && mask) {
+        unsigned long long todo = mask, left = 0ull;
+        int nth = 0;
+        while (todo) {                                           // workgroup-uniform
+            const int t = __ffsll((long long)todo) - 1;
+            todo &= todo - 1;
+            if ((nth++ % NW) != wave) continue;
+            const Philox4 r = philox4x32_10((uint32_t)t, (uint32_t)seq, (uint32_t)(seq >> 32), p.level,
+                                            (uint32_t)p.seed, (uint32_t)(p.seed >> 32));
+            int64_t lo = 0, hi = 0;
+            double frac = 0.0;
+            bool ok = pick_row_slab<BF16>(p.target, p.target_ld, g, p.V, p.B, b, t, partials, nparts, (double)u24(r.y), lane, lo, hi, frac);
+            const int slab_tiles = (int)((hi - lo + 64 * kTileChunks - 1) / (64 * kTileChunks));
+            if (ok && slab_tiles > kWaveSlabTiles) ok = false;
+            int32_t tk = -1;
+            if (ok) {
+                SeqInfo si;
+                si.row = t; si.mode = 1; si.greedy_tok = -1; si.u = 0.f;
+                si.lseP = sh.stat[g + t].lse; si.lseD = 0.0;
+                RowPair rp;
+                make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1);
+                if (rp.ok) {
+                    narrow_to_slab<BF16>(rp, lo, hi);
+                    double* const my_tiles = sh.wave_tiles[wave];
+                    for (int tl = 0; tl < slab_tiles; tl += 2) {
+                        double w0 = 0.0, w1 = 0.0;
+                        tile_weight2<BF16>(rp, tl, tl + 1, lane, w0, w1);
+                        if (lane == 0) {
+                            my_tiles[tl] = w0;
+                            if (tl + 1 < slab_tiles) my_tiles[tl + 1] = w1;
+                        }
+                    }
+                    __builtin_amdgcn_wave_barrier();             // the wavefront reads what its own lane 0 stored
+                    tk = select_token<BF16, true>(rp, my_tiles, slab_tiles, frac, lane);
+                    if (tk >= 0) tk += (int32_t)(lo * (BF16 ? 8 : 4));
+                }
+            }
+            if (tk >= 0) { if (lane == 0) out_tokens[(int64_t)b * g + t] = tk; }
+            else left |= 1ull << t;
+        }
+        __syncthreads();
+        if (lane == 0 && left) atomicOr(&sh.mask_left, left);
+        __syncthreads();
+        mask = sh.mask_left;
+    }
     while (mask) {                                               // workgroup-uniform
         const int t = __ffsll((long long)mask) - 1;
         mask &= mask - 1;

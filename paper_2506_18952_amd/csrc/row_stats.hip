@@ -73,7 +73,9 @@ __global__ __launch_bounds__(kBlock) void row_stats_kernel(RowStatsParams p)
         slot = (int64_t)p.B * g + (int64_t)b * (g + 1) + j;
     }
     Partial* out = p.partials + (slot * nsplit + seg) * kWaves;
-    const bool slabs = !is_draft && j == len && p.ntiles == 0 && !p.literal;   // the row of the bonus token
+    // rows a token may be drawn from with p itself as the weights: the row of the bonus token, or, in the literal mode,
+    // every target row (a verifier draw at each position that is not gated)
+    const bool slabs = !is_draft && p.ntiles == 0 && (p.literal ? true : j == len);
     if (GREEDY && greedy && !is_draft) row_segment<BF16, true, U>(row, Vrow, seg, nsplit, slabs, sc, out);
     else if (!is_draft && p.lse_only_targets) row_segment<BF16, false, U, false>(row, Vrow, seg, nsplit, slabs, sc, out);
     else row_segment<BF16, false, U>(row, Vrow, seg, nsplit, slabs, sc, out);

@@ -165,6 +165,55 @@ __device__ __forceinline__ float chunk_weights(const RowPair& rp, int64_t c, flo
     return chunk_weights_loaded<BF16, FILT>(rp, c, vp, vd, w);
 }
 
+// A draw from p itself (bonus weights) out of ONE slab of target row j.  On a row whose split-row partials were taken
+// over contiguous slabs (the statistics pass does that for the rows such a draw can come from), every partial is the
+// mass of one contiguous range of tokens, in index order, so the slab that holds the draw follows from the partials
+// and the sampling uniform u alone: an inverse CDF over at most 64 slab masses.  Returns false when the row has
+// ragged ends or the partials carry no usable mass (the caller then sweeps the whole row); otherwise the slab's
+// chunks [lo, hi) and where in its mass to land (frac, to be used as the uniform of a draw from the slab alone).
+// Called by one whole wavefront; the results are wavefront-uniform.
+template <bool BF16>
+__device__ __forceinline__ bool pick_row_slab(const void* target, int64_t target_ld, int32_t gamma, int32_t V, int32_t B, int b, int j,
+                                              const Partial* parts, int nparts, double u, int lane,
+                                              int64_t& lo, int64_t& hi, double& frac)
+{
+    constexpr int ES = BF16 ? 2 : 4;
+    const int g = gamma;
+    lo = 0; hi = 0; frac = 0.0;
+    const RowGeom geo = make_geom<BF16>((const char*)target + ((int64_t)b * (g + 1) + j) * target_ld * ES, V);
+    if (!(geo.edge_lo_end == 0 && geo.edge_hi_begin == V)) return false;   // ragged ends: the slabs are not all of the row
+    const Partial* ps = parts + ((int64_t)B * g + (int64_t)b * (g + 1) + j) * nparts;
+    double S = 0.0, br = 0.0;
+    if (lane < nparts) { S = ps[lane].S; br = ps[lane].bref; }
+    const bool has = S > 0.0 && S < INFINITY;
+    const double bmin = wave_min(has ? br : (double)INFINITY);
+    const double W = has ? S * exp2(bmin - br) : 0.0;              // the slab's mass against a common reference
+    const double incl = wave_inclusive_scan(W, lane);
+    const double Z = __shfl(incl, 63, 64);
+    const double target_mass = u * Z;
+    const unsigned long long hit = __ballot(incl > target_mass);
+    const int src = hit ? __ffsll((long long)hit) - 1 : 0;
+    const double w_src = __shfl(W, src, 64), excl = __shfl(incl - W, src, 64);
+    bool ok = Z > 0.0 && Z < INFINITY && hit && w_src > 0.0;
+    double f = ok ? (target_mass - excl) / w_src : 0.0;
+    f = f < 0.0 ? 0.0 : (f > 0.999999999 ? 0.999999999 : f);
+    int64_t seg_lo, seg_hi;
+    wave_slab(geo, src / kWaves, nparts / kWaves, src % kWaves, seg_lo, seg_hi, lo, hi);
+    if (hi <= lo) ok = false;
+    frac = f;
+    return ok;
+}
+
+// A row pair narrowed to the chunks [lo, hi) of the target row, as a row of its own (bonus weights only).
+template <bool BF16>
+__device__ __forceinline__ void narrow_to_slab(RowPair& rp, int64_t lo, int64_t hi)
+{
+    constexpr int N = BF16 ? 8 : 4;
+    rp.Pv += lo;                                                   // head is 0 on rows that have slabs
+    rp.nchunks = hi - lo;
+    rp.V = (int32_t)((hi - lo) * N);
+}
+
 // A sweep of up to this many tiles can leave every lane's chunk sums in shared memory (1 KB per tile) for
 // select_token, in the kernels whose workgroup has a compute unit to itself.
 constexpr int kSumsKeepTiles = 80;

@@ -108,6 +108,23 @@ def test_literal_headline_shape_subset():
     _check(w, 0.0)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_literal_aligned_rows_one_wavefront_per_draw(dtype):
+    """Rows whose ends fall on the 16-byte grid, so that every verifier draw goes the quick way (one wavefront picks
+    the slab from the row's partials and sweeps it alone): every position drawn (tau = 0), more draws than
+    wavefronts (gamma = 20), whole slabs without mass, and a masked tail."""
+    import dataclasses
+    w = wl.small_case(6, 20, 16384, dtype=dtype, temperature=0.9, case_id=413)
+    tgt, drf = w.target.copy(), w.draft.copy()
+    neg = np.uint16(0xff80) if dtype == "bf16" else np.float32(-np.inf)
+    tgt[1, :, 4096:8192] = neg                                   # a quarter of every row of sequence 1 carries no mass
+    tgt[2, :, 16000:] = neg
+    drf[2, :, 16000:] = neg
+    w2 = dataclasses.replace(w, target=tgt, draft=drf)
+    for tau in (0.0, 0.5 * math.log(w.V)):
+        _check(w2, tau)
+
+
 def test_literal_argument_errors():
     w = wl.small_case(2, 2, 100, case_id=412)
     P, D, tok = to_dev(w.target), to_dev(w.draft), to_dev(w.tokens)
