@@ -483,6 +483,63 @@ def bench_config(args) -> int:
 
 
 # ----------------------------------------------------------------------------------------------------------------
+def bench_variant(args) -> int:
+    """The headline shape on inputs or through an entry point other than the headline's (labelled so)."""
+    import numpy as np
+    import torch
+    from paper_2506_18952_amd import binding as hb
+    from paper_2506_18952_amd import workloads as wl
+    dev = "cuda:0"
+    w = wl.config3(B=args.batch)
+    B, g, V = w.B, w.gamma, w.V
+    tgt, drf, toks = w.target, w.draft, w.tokens
+    what = "hola_verify_literal_ex (every non-gated position takes a draw from its target row)"
+    if args.variant in ("padded", "masked"):
+        tgt, drf, toks = tgt.copy(), drf.copy(), toks.copy()
+        mask = np.zeros(V, bool)
+        mask[V - 256:] = True
+        if args.variant == "masked":
+            mask |= np.random.default_rng(1).random(V) < 0.3
+        tgt[..., mask] = np.uint16(0xff80)                       # bf16 -inf
+        drf[..., mask] = np.uint16(0xff80)
+        ok = np.flatnonzero(~mask)
+        toks = ok[np.random.default_rng(2).integers(0, ok.size, size=toks.shape)].astype(np.int32)
+        what = ("the last 256 vocabulary entries of every row at -inf" if args.variant == "padded"
+                else "30 % of the vocabulary entries (and the last 256) at -inf")
+    P, D, tok = _to_dev(tgt), _to_dev(drf), _to_dev(toks)
+    acc = torch.empty(B, dtype=torch.int32, device=dev)
+    nxt = torch.empty(B, dtype=torch.int32, device=dev)
+    ent = torch.empty((B, g), dtype=torch.float32, device=dev)
+    out = torch.empty((B, g), dtype=torch.int32, device=dev)
+    ws = hb.alloc_workspace(hb.hola_workspace_bytes_ex(B, g, V), dev)
+    stream = torch.cuda.current_stream()
+    taus = w.taus
+
+    def step(i):
+        common = dict(target_logits=P, draft_logits=D, draft_tokens=tok, seed=w.seed + i, B=B, gamma=g, V=V,
+                      temperature=w.temperature, entropy_threshold=taus[i % len(taus)], out_entropy=ent, workspace=ws, stream=stream)
+        if args.variant == "literal":
+            hb.hola_verify_literal_ex(out_tokens=out, out_verifier_calls=acc, **common)
+        else:
+            hb.hola_verify_ex(out_accept_len=acc, out_next_token=nxt, **common)
+
+    _settle(step)
+    dt = _timed(step, args.steps, args.warmup)
+    per_stage = _kernel_launches(hb, step, max(args.steps, ROOFLINE_MIN_LAUNCHES))
+    line = _base_line("verified draft positions/sec + achieved HBM GB/s (% of MI355X peak)", B * g * args.steps / dt, "positions/s",
+                      args.steps, args.warmup, dt * 1e3 / args.steps,
+                      f"cfg3 shape (not the headline workload): B={B} gamma={g} V={V} bf16 logits T={w.temperature}, tau cycling "
+                      f"(0.25,0.5,0.75) ln V; {what}",
+                      {"entry_point": "hola_verify_literal_ex" if args.variant == "literal" else "hola_verify_ex", "logit_dtype": "bf16"})
+    line["stage_ms"] = {hb.STAGE_NAMES[s_]: round(float(np.median(v)), 5) for s_, v in sorted(per_stage.items())}
+    line["stage_ms_statistic"] = "median launch"
+    rows = B * ((2 * g) if args.variant == "literal" else (2 * g + 1))
+    line["roofline"] = _roofline(hb, per_stage, STAGE_ROW_STATS, "row_stats_kernel", rows * V * 2, "")
+    line["call_us"] = _dist(_event_timed(step, max(args.steps, ROOFLINE_MIN_LAUNCHES), stream))
+    print(json.dumps(line), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -496,6 +553,10 @@ def main() -> int:
                                                           "(hola_verify_tree; not the headline workload)")
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5], help="named workload (3 = the headline)")
     ap.add_argument("--batch5", type=int, default=1024, help=argparse.SUPPRESS)
+    ap.add_argument("--variant", choices=["literal", "padded", "masked"], default="",
+                    help="not the headline workload: the headline shape through hola_verify_literal_ex (Equation (1) taken "
+                         "literally), or through hola_verify_ex with the last 256 vocabulary entries of every row at -inf "
+                         "(padded) / 30 %% of the entries at -inf (masked)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-baseline leg")
     ap.add_argument("--copy-calibration", action="store_true")
     ap.add_argument("--read-ceiling", action="store_true")
@@ -523,6 +584,8 @@ def main() -> int:
     hb.hola_set_tuning(path={"auto": hb.PATH_AUTO, "split": hb.PATH_SPLIT, "fused": hb.PATH_FUSED}[args.path])
     if args.tree:
         return bench_tree(args)
+    if args.variant:
+        return bench_variant(args)
     if args.config != 3:
         return bench_config(args)
 
