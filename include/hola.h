@@ -121,6 +121,11 @@ typedef struct {
     int32_t filter_path;            /* top-k / top-p keep sets.  0: a split-row scan lists the candidates of every
                                        row, one wavefront per row decides, and only rows that step cannot settle
                                        go to the one-workgroup-per-row kernel; 1: that kernel for every row */
+    int32_t tail_split;             /* workgroups that share one sequence's tail (the sweep of its stop rows): 1, 2, 4
+                                       or 8; 0: the library's choice (more than one only for small batches of wide
+                                       rows, where compute units would otherwise idle while one of them sweeps).  A
+                                       wish: where B * tail_split exceeds the compute units, or the call is filtered,
+                                       one workgroup is used.  The result does not depend on it. */
 } hola_tuning;
 /* Sets the defaults of the CALLING THREAD (thread-local; NULL restores the built-in choices).  A call whose args
  * structure carries its own `tuning` ignores them, so no state outside a call's arguments need decide its path. */

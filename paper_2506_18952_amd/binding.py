@@ -42,7 +42,7 @@ class HolaError(RuntimeError):
 
 class Tuning(C.Structure):
     _fields_ = [("stats_split", C.c_int32), ("stats_unroll", C.c_int32), ("path", C.c_int32),
-                ("fused_waves", C.c_int32), ("filter_path", C.c_int32)]
+                ("fused_waves", C.c_int32), ("filter_path", C.c_int32), ("tail_split", C.c_int32)]
 
 
 class VerifyArgs(C.Structure):
@@ -388,8 +388,8 @@ PATH_AUTO, PATH_SPLIT, PATH_FUSED, PATH_SPLIT4 = 0, 1, 2, 3
 
 
 def hola_set_tuning(stats_split: int = 0, stats_unroll: int = 0, path: int = 0, fused_waves: int = 0,
-                    filter_path: int = 0) -> None:
-    t = Tuning(int(stats_split), int(stats_unroll), int(path), int(fused_waves), int(filter_path))
+                    filter_path: int = 0, tail_split: int = 0) -> None:
+    t = Tuning(int(stats_split), int(stats_unroll), int(path), int(fused_waves), int(filter_path), int(tail_split))
     _check(lib().hola_set_tuning(C.byref(t)), "hola_set_tuning")
 
 

@@ -25,6 +25,7 @@ struct AcceptCtx {
     const RowFilter* filters = nullptr; // top-k / top-p keep sets and statistics, slots as the partials; or null
     const RowFilter* draft_filters = nullptr;   // the draft rows' ([B, gamma]): `filters` itself unless handed over
     int32_t B = 0;
+    int32_t write_outputs = 1;         // 0: decide only (a workgroup that shares a sequence's tail with the one that writes)
 };
 
 // Membership of token i with logit x in a filtered row's keep set.
@@ -83,11 +84,11 @@ __device__ __forceinline__ void accept_decide(const AcceptCtx& c, int b, int j, 
     const bool greedy = !(Tb > 0.f);
     const double invT = greedy ? 1.0 : 1.0 / (double)Tb;
     const double tau = (double)c.tau;
-    if (c.target_stats_out && j <= len) {
+    if (c.write_outputs && c.target_stats_out && j <= len) {
         c.target_stats_out[((int64_t)b * (g + 1) + j) * 2 + 0] = sp.lse;
         c.target_stats_out[((int64_t)b * (g + 1) + j) * 2 + 1] = sp.H;
     }
-    if (c.out_entropy) {
+    if (c.write_outputs && c.out_entropy) {
         const int64_t eld = c.entropy_ld ? c.entropy_ld : g;
         const int64_t width = c.pad_entropy ? eld : g;
         for (int64_t jj = j; jj < width; jj += 64)
@@ -124,7 +125,7 @@ __device__ __forceinline__ void accept_decide(const AcceptCtx& c, int b, int j, 
     const unsigned long long rej = __ballot(reject);
     const int a = rej ? (__ffsll((long long)rej) - 1) : len;
     if (j == a) {                                       // exactly one lane: a <= len <= gamma < 64
-        c.out_accept_len[b] = a;
+        if (c.write_outputs) c.out_accept_len[b] = a;
         SeqInfo si;
         si.row = a;
         si.lseP = sp.lse;
@@ -134,7 +135,7 @@ __device__ __forceinline__ void accept_decide(const AcceptCtx& c, int b, int j, 
             si.mode = 2;
             si.u = 0.f;
             si.greedy_tok = sp.argmax;
-            c.out_next_token[b] = sp.argmax;
+            if (c.write_outputs) c.out_next_token[b] = sp.argmax;
         } else {
             si.u = u24(r.y);                             // j == a: this lane's own block
             si.mode = (a < len) ? 0 : 1;

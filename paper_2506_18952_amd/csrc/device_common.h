@@ -133,6 +133,48 @@ __device__ __forceinline__ double wave_min(double v)
     return lane63(v);
 }
 
+// ---- values that cross from one workgroup to another INSIDE a launch ------------------------------------------
+// The compute units' vector caches and the chip's eight second-level caches are not coherent with one another
+// within a launch.  Such a value is therefore written and read with device-scope relaxed atomic accesses: the
+// store goes through to memory, the load comes from it, and no cache has to be written back or emptied as a whole
+// (which is what a device-scope fence does: measured at 10 x the cost of a whole launch when every workgroup
+// does it).  Ordering is the caller's business: wait for the stores (stores_through_done) before telling anybody,
+// and load only after having been told.
+__device__ __forceinline__ void store_through(double* dst, double v)
+{
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(dst), (unsigned long long)__double_as_longlong(v),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double load_through(const double* src)
+{
+    return __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<const unsigned long long*>(src),
+                                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+// Every store this wavefront has issued has been acknowledged by the memory system.
+__device__ __forceinline__ void stores_through_done()
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// A sequence's completion ticket: one 64-bit word in the workspace, (tag << 16 | count).  The workspace arrives with
+// any contents, so a word counts only if it carries this call's tag (48 bits, drawn per call); anything else reads
+// as count 0.  Whoever takes the last of `expected` tickets is told so (returns true) and leaves the word at 0, so
+// that a replay of a captured launch (same tag) starts afresh.  Nobody waits for anybody; one load and one
+// single-shot atomic per caller (only the first ticket of a call swaps).  Called by one thread per workgroup.
+__device__ __forceinline__ bool take_ticket(unsigned long long* word, unsigned long long tag, uint32_t expected)
+{
+    const unsigned long long mine = tag << 16;
+    unsigned long long cur = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned long long prev;                                     // the word before this ticket
+    if ((cur >> 16) == tag) prev = __hip_atomic_fetch_add(word, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else if (__hip_atomic_compare_exchange_strong(word, &cur, mine | 1ull, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        prev = mine;
+    else prev = __hip_atomic_fetch_add(word, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const bool last = (uint32_t)(prev & 0xffffu) + 1u >= expected;
+    if (last) __hip_atomic_store(word, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return last;
+}
+
 // ---- Philox4x32-10 (Salmon et al., SC'11) ---------------------------------------------------
 struct Philox4 { uint32_t x, y, z, w; };
 

@@ -158,11 +158,18 @@ __device__ __forceinline__ void pick_bonus_slab(const FusedParams& p, SeqShared&
 // loaded, so that the selection does not read its tile from global memory again; or null.
 // chunk_sums: kSumsKeepTiles x 64 entries of shared memory in which a sweep of at most that many tiles leaves every
 // lane's chunk sums, so that the selection rebuilds one chunk of the crossing tile instead of four; or null.
+// part, G: this workgroup is one of G that share sequence b's tail (G = 1: the usual case).  Every one of them
+// decides (the decision costs little and all need it); only part 0 writes the decision's outputs.  Where the
+// stop row must be swept whole, each part sweeps a contiguous G-th of its tiles, leaves the tile weights in
+// p.coop_tiles and takes a ticket; the last to arrive reads the others' weights and draws the token.  The weights
+// and the draw are those of a workgroup on its own: every tile is summed by one wavefront either way.
 template <bool BF16, int NW, bool FILT = false>
 __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& sh, int b, int len, float Tb,
                                               const TokenGather& tg, bool pre_slab = false, uint4* slab_raw = nullptr,
-                                              float4* chunk_sums = nullptr)
+                                              float4* chunk_sums = nullptr, int part = 0, int G = 1)
 {
+    constexpr bool COOP = (NW == 16 && !FILT);                      // the only variant launched with G > 1
+    if (!COOP) { part = 0; G = 1; }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = p.gamma;
     constexpr int N = BF16 ? 8 : 4;
@@ -189,10 +196,11 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
                 sp = sh.stat[g + j];
             }
         }
-        const AcceptCtx c = accept_ctx(p);
+        AcceptCtx c = accept_ctx(p);
+        c.write_outputs = part == 0;
         accept_decide<BF16>(c, b, j, len, Tb, sd, sp, tg, &sh.si);
     }
-    else if (slab_ready) {
+    else if (slab_ready && part == 0) {
         // the slab's tile weights as bonus weights of target row len, by the wavefronts that do not decide
         SeqInfo sb;
         sb.lseP = sh.stat[g + len].lse; sb.lseD = 0.0; sb.u = 0.f; sb.row = len; sb.mode = 1; sb.greedy_tok = -1;
@@ -209,7 +217,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
     __syncthreads();
     const SeqInfo si = sh.si;
     if (si.mode == 2) {                                          // greedy: next token already written
-        write_glue(p, b, si.row, si.greedy_tok);
+        if (part == 0) write_glue(p, b, si.row, si.greedy_tok);
         return;
     }
 
@@ -226,6 +234,11 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
         ntiles = slab_tiles;
         u_eff = sh.slab_u;
     }
+
+    // the sweep of the whole stop row is shared; a draw from a slab, or a row without mass, is part 0's alone
+    bool coop_now = COOP && G > 1 && !slab_mode && rp.ok;
+    if (COOP && G > 1 && !coop_now && part != 0) return;
+    int own_lo = 0, own_hi = 0x7fffffff;                         // the tiles whose chunk sums this workgroup holds
 
     // ---- filtered call whose stop row's keep set is at hand as a short list: no sweep of the row at all
     int list_n = 0;
@@ -253,20 +266,48 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
             continue;
         }
         if (!(slab_mode && attempt == 0)) {
+            int t_lo = 0, t_hi = ntiles;
+            if (COOP && coop_now) {
+                const int per = (ntiles + G - 1) / G;
+                t_lo = part * per;
+                t_hi = t_lo + per < ntiles ? t_lo + per : ntiles;
+                own_lo = t_lo; own_hi = t_hi;
+            } else {
+                own_lo = 0; own_hi = 0x7fffffff;
+            }
+            double* const shared_tiles = (COOP && coop_now) ? p.coop_tiles + (int64_t)b * p.ntiles : nullptr;
             // tile weights of the stop row: two tiles per round trip and wavefront
-            for (int t = wave; t < ntiles; t += 2 * NW) {
+            for (int t = t_lo + wave; t < t_hi; t += 2 * NW) {
                 double w0 = 0.0, w1 = 0.0;
-                if (rp.ok) tile_weight2<BF16, FILT>(rp, t, t + NW, lane, w0, w1, sums, ntiles);
+                const int t1 = t + NW < t_hi ? t + NW : p.ntiles;    // p.ntiles: past the row, no loads and no weight
+                if (rp.ok) tile_weight2<BF16, FILT>(rp, t, t1, lane, w0, w1, sums, t_hi);
                 if (lane == 0) {
                     sh.tiles[t] = w0;
-                    if (t + NW < ntiles) sh.tiles[t + NW] = w1;
+                    if (t + NW < t_hi) sh.tiles[t + NW] = w1;
+                    if (COOP && coop_now) {                      // and for the other parts, straight to memory
+                        store_through(shared_tiles + t, w0);
+                        if (t + NW < t_hi) store_through(shared_tiles + t + NW, w1);
+                    }
                 }
             }
+            if (COOP && coop_now) stores_through_done();         // this wavefront's stores have reached memory
             __syncthreads();
+            if (COOP && coop_now) {
+                if (tid == 0) sh.tok = take_ticket(p.coop_tickets + b, p.coop_tag, (uint32_t)G) ? 1 : 0;
+                __syncthreads();
+                const bool last = sh.tok != 0;
+                __syncthreads();                                 // sh.tok is written again below
+                if (!last) return;
+                for (int t = tid; t < ntiles; t += NW * 64)
+                    if (t < t_lo || t >= t_hi) sh.tiles[t] = load_through(shared_tiles + t);
+                __syncthreads();
+                coop_now = false;                                // a later sweep, if any, is this workgroup's alone
+            }
         }
         if (wave == 0) {
             const int32_t tk = rp.ok ? select_token<BF16, true, FILT>(rp, sh.tiles, ntiles, u_eff, lane,
-                                                                      (slab_mode && attempt == 0) ? keep : nullptr, sums) : -1;
+                                                                      (slab_mode && attempt == 0) ? keep : nullptr, sums,
+                                                                      own_lo, own_hi) : -1;
             if (lane == 0) sh.tok = tk;
         }
         __syncthreads();
@@ -361,7 +402,8 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
     uint4* const slab_raw = (NW == 16 && !FILT) ? s_raw : nullptr;
     __shared__ float4 s_sums[(NW == 16 && !FILT) ? kSumsKeepTiles * 64 : 1];   // likewise
     float4* const chunk_sums = (NW == 16 && !FILT) ? s_sums : nullptr;
-    const int b = blockIdx.x;
+    const int G = (NW == 16 && !FILT && p.coop > 1) ? p.coop : 1;   // workgroups per sequence (see sequence_tail)
+    const int b = (int)blockIdx.x / G, part = (int)blockIdx.x % G;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = p.gamma;
     int len = p.draft_len ? p.draft_len[b] : g;
@@ -392,7 +434,7 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
         }
     }
     __syncthreads();
-    sequence_tail<BF16, NW, FILT>(p, sh, b, len, Tb, tg, pre_slab, slab_raw, chunk_sums);
+    sequence_tail<BF16, NW, FILT>(p, sh, b, len, Tb, tg, pre_slab, slab_raw, chunk_sums, part, G);
 }
 
 bool fused_supported(int32_t gamma, int32_t V, int dtype)
@@ -428,8 +470,9 @@ hipError_t launch_tail(const FusedParams& p, const Partial* partials, int nparts
 {
     if (p.B <= 0) return hipSuccess;
     if (nparts > 64) return hipErrorInvalidValue;
-    dim3 grid((unsigned)p.B);
     const int nw = t.fused_waves ? t.fused_waves : 16;
+    const bool coop = p.coop > 1 && nw == 16 && !p.filters;      // the caller checked the rest (hola_api.hip)
+    dim3 grid((unsigned)p.B * (coop ? (unsigned)p.coop : 1u));
     if (p.filters) {                                             // filtered distributions: 8 wavefronts, more registers
         if (p.dtype == HOLA_DTYPE_BF16) hipLaunchKernelGGL((tail_kernel<true, 8, true>), grid, dim3(512), 0, s, p, partials, nparts);
         else hipLaunchKernelGGL((tail_kernel<false, 8, true>), grid, dim3(512), 0, s, p, partials, nparts);

@@ -3,6 +3,8 @@
 // steady-state path; everything is enqueued on the caller's stream.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -56,6 +58,22 @@ __global__ void export_tokens_kernel(const int32_t* __restrict__ tok, int64_t to
 static thread_local char g_last_hip[256] = "";
 static thread_local Tuning g_tuning;
 static std::mutex g_mu;
+
+// Tag of a call's completion tickets (a tail shared by several workgroups per sequence): 48 bits, never 0, different
+// from call to call and (by the start value) from process to process, so that nothing a workspace may hold from
+// before reads as a ticket of this call.
+static unsigned long long next_ticket_tag()
+{
+    static std::atomic<unsigned long long> counter{0};
+    static const unsigned long long salt = [] {
+        unsigned long long x = (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count();
+        x ^= (unsigned long long)(uintptr_t)&counter * 0x9E3779B97F4A7C15ull;
+        x ^= x >> 29; x *= 0xBF58476D1CE4E5B9ull; x ^= x >> 32;
+        return x;
+    }();
+    const unsigned long long t = (salt + counter.fetch_add(1, std::memory_order_relaxed) * 0x9E3779B97F4A7C15ull) & 0xffffffffffffull;
+    return t ? t : 1ull;
+}
 
 struct DeviceWs { void* ptr = nullptr; size_t bytes = 0; };
 static DeviceWs g_ws[64];
@@ -115,6 +133,19 @@ static int auto_tail_waves(int32_t B, int64_t row_bytes)
     return (B > 3 * cus && row_bytes < (512 << 10)) ? 4 : 8;   // 1 MB rows: 8 beats 4 by 2 % (sweep is bandwidth-bound)
 }
 
+// Workgroups that share one sequence's tail.  One compute unit sweeps a sequence's stop rows at what its vector
+// units allow (~20 us for two 256 KB rows); with few sequences most of the chip idles meanwhile, so their sweeps are
+// split over two, four or eight compute units, at the price of ~5 us for handing the tile weights over through memory.
+static int auto_tail_split(int32_t B, int64_t row_bytes)
+{
+    const int cus = device_cu_count();
+    if (row_bytes < (128 << 10)) return 1;
+    if ((int64_t)B * 8 <= cus) return 8;
+    if ((int64_t)B * 4 <= cus) return 4;
+    if ((int64_t)B * 2 <= cus) return 2;
+    return 1;
+}
+
 static inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static bool tuning_from(const hola_tuning* t, Tuning* out)
@@ -127,8 +158,9 @@ static bool tuning_from(const hola_tuning* t, Tuning* out)
         if (t->path < 0 || t->path > 3) return false;
         if (t->fused_waves != 0 && t->fused_waves != 4 && t->fused_waves != 8 && t->fused_waves != 16) return false;
         if (t->filter_path < 0 || t->filter_path > 1) return false;
+        if (t->tail_split != 0 && t->tail_split != 1 && t->tail_split != 2 && t->tail_split != 4 && t->tail_split != 8) return false;
         n.split = t->stats_split; n.unroll = t->stats_unroll; n.path = t->path; n.fused_waves = t->fused_waves;
-        n.filter_path = t->filter_path;
+        n.filter_path = t->filter_path; n.tail_split = t->tail_split;
     }
     *out = n;
     return true;
@@ -159,6 +191,7 @@ static Workspace carve(void* base, int32_t B, int32_t gamma, int32_t V, bool wit
     w.argmaxP = (int32_t*)take((size_t)B * (gamma + 1) * sizeof(int32_t));
     w.seq = (SeqInfo*)take((size_t)B * sizeof(SeqInfo));
     w.tiles = (double*)take((size_t)B * ntiles * sizeof(double));
+    w.tickets = (unsigned long long*)take((size_t)B * sizeof(unsigned long long));
     w.filters = nullptr;
     w.filter_scan = nullptr;
     if (with_filters) {                                        // keep sets and candidate lists: filtered calls only
@@ -301,7 +334,13 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     // Paths 0/1: the split-row pass spreads the rows over the chip, then one per-sequence tail kernel does
     // accept + sampling.  Path 3 keeps accept, tile sums and select as three kernels of their own.
     if (tune.path != 3 && per_seq_ok) {
-        if (tune.fused_waves == 0) tune.fused_waves = auto_tail_waves(a.B, (int64_t)a.V * (a.dtype == HOLA_DTYPE_BF16 ? 2 : 4));
+        const int64_t row_bytes = (int64_t)a.V * (a.dtype == HOLA_DTYPE_BF16 ? 2 : 4);
+        if (tune.fused_waves == 0) tune.fused_waves = auto_tail_waves(a.B, row_bytes);
+        // several workgroups per sequence: only the 16-wavefront tail of unfiltered calls, each on a compute unit of its own
+        int coop = tune.tail_split ? tune.tail_split : auto_tail_split(a.B, row_bytes);
+        if (filtered || tune.fused_waves != 16 || (int64_t)a.B * coop > device_cu_count() || fp.ntiles < 2 * coop) coop = 1;
+        fp.coop = coop;
+        if (coop > 1) { fp.coop_tiles = w.tiles; fp.coop_tickets = w.tickets; fp.coop_tag = next_ticket_tag(); }
         { StageTimer t(6, s); e = launch_tail(fp, w.partials, nsplit * kWaves, tune, s); }
         if (e != hipSuccess) return hip_fail(e, "tail launch");
         if (filtered && x.target_filters_out) {                // this level's target rows are the next level's draft rows

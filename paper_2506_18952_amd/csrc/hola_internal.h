@@ -80,6 +80,7 @@ struct Workspace {
     SeqInfo* seq;                      // [B]
     double* tiles;                     // [B, ntiles]
     RowFilter* filters;                // [(B*gamma) + B*(gamma+1)], filtered calls only
+    unsigned long long* tickets;       // [B] completion tickets of a tail shared by several workgroups per sequence
     void* filter_scan;                 // candidate lists, counters, flags and segment records of the filter scan
     size_t bytes;
 };
@@ -88,6 +89,7 @@ struct Tuning {
     int split = 0, unroll = 0;
     int path = 0;                      // 0 auto, 1 split rows + tail kernel, 2 fused kernel, 3 split rows + 3 kernels
     int fused_waves = 0;               // 0 (= 16), 8 or 16 wavefronts per workgroup in the fused kernel
+    int tail_split = 0;                // workgroups per sequence in the tail kernel: 0 auto, 1, 2, 4 or 8
     int filter_path = 0;               // 1: the per-row filter kernel for every row
 };
 
@@ -156,6 +158,10 @@ struct FusedParams {
     // short keep sets written out as lists of (order key << 32 | index), at most kKeptListMax entries, kept_stride
     // apart, for row r = b (2 gamma + 1) + k, and their lengths (-1: no list); null when the filter's scan did not run
     const unsigned long long* kept; const int32_t* kept_n; int64_t kept_stride;
+    // a tail shared by `coop` workgroups per sequence (1: one workgroup, as ever): where they leave their tile weights
+    // for each other ([B, ntiles]), the sequences' completion tickets ([B], any contents) and this call's tag for them
+    int32_t coop;
+    double* coop_tiles; unsigned long long* coop_tickets; unsigned long long coop_tag;
 };
 
 // Token trees: N nodes per sequence, rows by context as the one-token step lays them out with gamma = N.

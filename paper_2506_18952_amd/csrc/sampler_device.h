@@ -295,11 +295,12 @@ __device__ __forceinline__ double read_tile(const double* t)
 // Z == 0: p == q everywhere, or a broken draft row) and call again.
 // raw: the target row's chunks as the sweep loaded them, kept in shared memory (bonus weights, whole chunks: the
 // crossing tile is then not read from global memory again), or null.
-// sums: every lane's four chunk sums of every tile as the sweep left them in shared memory ([tile][lane]), or null;
-// with them only the one chunk that holds the crossing is rebuilt element by element.
+// sums: every lane's four chunk sums of the tiles [sums_lo, sums_hi) as the sweep left them in shared memory
+// ([tile][lane]), or null; with them only the one chunk that holds the crossing is rebuilt element by element.
 template <bool BF16, bool LDS, bool FILT = false>
 __device__ __forceinline__ int32_t select_token(const RowPair& rp, const double* tiles, int ntiles, double u, int lane,
-                                                const uint4* raw = nullptr, const float4* sums = nullptr)
+                                                const uint4* raw = nullptr, const float4* sums = nullptr,
+                                                int sums_lo = 0, int sums_hi = 0x7fffffff)
 {
     constexpr int N = BF16 ? 8 : 4;
     const int per = (ntiles + 63) / 64;
@@ -346,7 +347,7 @@ __device__ __forceinline__ int32_t select_token(const RowPair& rp, const double*
         }
         return chunk_weights<BF16, FILT>(rp, c, wout);
     };
-    const bool have_sums = sums != nullptr;                          // the sweep left every lane's chunk sums
+    const bool have_sums = sums != nullptr && tile >= sums_lo && tile < sums_hi;   // the sweep left every lane's chunk sums
     float w[kTileChunks][N];
     float cs[kTileChunks];
     if (have_sums) {

@@ -106,6 +106,8 @@ int main(void)
         t.stats_unroll = 0; t.path = 9; EXPECT(hola_verify_ex(&a), HOLA_ERR_INVALID_ARG);
         t.path = 0; t.fused_waves = 5; EXPECT(hola_verify_ex(&a), HOLA_ERR_INVALID_ARG);
         t.fused_waves = 0; t.filter_path = 2; EXPECT(hola_verify_ex(&a), HOLA_ERR_INVALID_ARG);
+        t.filter_path = 0; t.tail_split = 3; EXPECT(hola_verify_ex(&a), HOLA_ERR_INVALID_ARG);
+        t.tail_split = 0;
         for (int path = 0; path <= 3; ++path) {
             memset(&t, 0, sizeof t); t.path = path; t.stats_split = 4; t.stats_unroll = 4; t.fused_waves = 8;
             EXPECT_RAN(hola_verify_ex(&a));

@@ -69,7 +69,8 @@ def test_workspace_bytes_of_one_call():
 
 
 def test_tuning_of_one_call_is_validated():
-    for bad in (dict(stats_split=99), dict(stats_unroll=3), dict(path=7), dict(fused_waves=5), dict(filter_path=2)):
+    for bad in (dict(stats_split=99), dict(stats_unroll=3), dict(path=7), dict(fused_waves=5), dict(filter_path=2),
+                dict(tail_split=3), dict(tail_split=16)):
         t = hb.Tuning(**bad)
         a = _args(tuning=C.pointer(t))
         assert hb.lib().hola_verify_ex(C.byref(a)) == hb.HOLA_ERR_INVALID_ARG
