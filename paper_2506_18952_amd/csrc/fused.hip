@@ -163,12 +163,12 @@ __device__ __forceinline__ void pick_bonus_slab(const FusedParams& p, SeqShared&
 // stop row must be swept whole, each part sweeps a contiguous G-th of its tiles, leaves the tile weights in
 // p.coop_tiles and takes a ticket; the last to arrive reads the others' weights and draws the token.  The weights
 // and the draw are those of a workgroup on its own: every tile is summed by one wavefront either way.
-template <bool BF16, int NW, bool FILT = false>
+template <bool BF16, int NW, bool FILT = false, bool COOP = false>
 __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& sh, int b, int len, float Tb,
                                               const TokenGather& tg, bool pre_slab = false, uint4* slab_raw = nullptr,
                                               float4* chunk_sums = nullptr, int part = 0, int G = 1)
 {
-    constexpr bool COOP = (NW == 16 && !FILT);                      // the only variant launched with G > 1
+    static_assert(!COOP || (NW == 16 && !FILT), "a shared tail is the 16-wavefront unfiltered variant's alone");
     if (!COOP) { part = 0; G = 1; }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = p.gamma;
@@ -196,11 +196,16 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
                 sp = sh.stat[g + j];
             }
         }
-        AcceptCtx c = accept_ctx(p);
-        c.write_outputs = part == 0;
-        accept_decide<BF16>(c, b, j, len, Tb, sd, sp, tg, &sh.si);
+        if constexpr (COOP) {
+            AcceptCtx c = accept_ctx(p);
+            c.write_outputs = part == 0;
+            accept_decide<BF16>(c, b, j, len, Tb, sd, sp, tg, &sh.si);
+        } else {
+            const AcceptCtx c = accept_ctx(p);
+            accept_decide<BF16>(c, b, j, len, Tb, sd, sp, tg, &sh.si);
+        }
     }
-    else if (slab_ready && part == 0) {
+    else if (slab_ready && (!COOP || part == 0)) {
         // the slab's tile weights as bonus weights of target row len, by the wavefronts that do not decide
         SeqInfo sb;
         sb.lseP = sh.stat[g + len].lse; sb.lseD = 0.0; sb.u = 0.f; sb.row = len; sb.mode = 1; sb.greedy_tok = -1;
@@ -217,7 +222,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
     __syncthreads();
     const SeqInfo si = sh.si;
     if (si.mode == 2) {                                          // greedy: next token already written
-        if (part == 0) write_glue(p, b, si.row, si.greedy_tok);
+        if (!COOP || part == 0) write_glue(p, b, si.row, si.greedy_tok);
         return;
     }
 
@@ -239,6 +244,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
     bool coop_now = COOP && G > 1 && !slab_mode && rp.ok;
     if (COOP && G > 1 && !coop_now && part != 0) return;
     int own_lo = 0, own_hi = 0x7fffffff;                         // the tiles whose chunk sums this workgroup holds
+    (void)own_lo; (void)own_hi;
 
     // ---- filtered call whose stop row's keep set is at hand as a short list: no sweep of the row at all
     int list_n = 0;
@@ -266,48 +272,63 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
             continue;
         }
         if (!(slab_mode && attempt == 0)) {
-            int t_lo = 0, t_hi = ntiles;
-            if (COOP && coop_now) {
-                const int per = (ntiles + G - 1) / G;
-                t_lo = part * per;
-                t_hi = t_lo + per < ntiles ? t_lo + per : ntiles;
+            if constexpr (COOP) {
+                int t_lo = 0, t_hi = ntiles;
+                if (coop_now) {
+                    const int per = (ntiles + G - 1) / G;
+                    t_lo = part * per;
+                    t_hi = t_lo + per < ntiles ? t_lo + per : ntiles;
+                }
                 own_lo = t_lo; own_hi = t_hi;
-            } else {
-                own_lo = 0; own_hi = 0x7fffffff;
-            }
-            double* const shared_tiles = (COOP && coop_now) ? p.coop_tiles + (int64_t)b * p.ntiles : nullptr;
-            // tile weights of the stop row: two tiles per round trip and wavefront
-            for (int t = t_lo + wave; t < t_hi; t += 2 * NW) {
-                double w0 = 0.0, w1 = 0.0;
-                const int t1 = t + NW < t_hi ? t + NW : p.ntiles;    // p.ntiles: past the row, no loads and no weight
-                if (rp.ok) tile_weight2<BF16, FILT>(rp, t, t1, lane, w0, w1, sums, t_hi);
-                if (lane == 0) {
-                    sh.tiles[t] = w0;
-                    if (t + NW < t_hi) sh.tiles[t + NW] = w1;
-                    if (COOP && coop_now) {                      // and for the other parts, straight to memory
-                        store_through(shared_tiles + t, w0);
-                        if (t + NW < t_hi) store_through(shared_tiles + t + NW, w1);
+                double* const shared_tiles = p.coop_tiles + (int64_t)b * p.ntiles;
+                for (int t = t_lo + wave; t < t_hi; t += 2 * NW) {
+                    double w0 = 0.0, w1 = 0.0;
+                    const int t1 = t + NW < t_hi ? t + NW : p.ntiles;    // p.ntiles: past the row, no loads and no weight
+                    if (rp.ok) tile_weight2<BF16, FILT>(rp, t, t1, lane, w0, w1, sums, t_hi);
+                    if (lane == 0) {
+                        sh.tiles[t] = w0;
+                        if (t + NW < t_hi) sh.tiles[t + NW] = w1;
+                        if (coop_now) {                          // and for the other parts, straight to memory
+                            store_through(shared_tiles + t, w0);
+                            if (t + NW < t_hi) store_through(shared_tiles + t + NW, w1);
+                        }
                     }
                 }
-            }
-            if (COOP && coop_now) stores_through_done();         // this wavefront's stores have reached memory
-            __syncthreads();
-            if (COOP && coop_now) {
-                if (tid == 0) sh.tok = take_ticket(p.coop_tickets + b, p.coop_tag, (uint32_t)G) ? 1 : 0;
+                if (coop_now) stores_through_done();             // this wavefront's stores have reached memory
                 __syncthreads();
-                const bool last = sh.tok != 0;
-                __syncthreads();                                 // sh.tok is written again below
-                if (!last) return;
-                for (int t = tid; t < ntiles; t += NW * 64)
-                    if (t < t_lo || t >= t_hi) sh.tiles[t] = load_through(shared_tiles + t);
+                if (coop_now) {
+                    if (tid == 0) sh.tok = take_ticket(p.coop_tickets + b, p.coop_tag, (uint32_t)G) ? 1 : 0;
+                    __syncthreads();
+                    const bool last = sh.tok != 0;
+                    __syncthreads();                             // sh.tok is written again below
+                    if (!last) return;
+                    for (int t = tid; t < ntiles; t += NW * 64)
+                        if (t < t_lo || t >= t_hi) sh.tiles[t] = load_through(shared_tiles + t);
+                    __syncthreads();
+                    coop_now = false;                            // a later sweep, if any, is this workgroup's alone
+                }
+            } else {
+                // tile weights of the stop row: two tiles per round trip and wavefront
+                for (int t = wave; t < ntiles; t += 2 * NW) {
+                    double w0 = 0.0, w1 = 0.0;
+                    if (rp.ok) tile_weight2<BF16, FILT>(rp, t, t + NW, lane, w0, w1, sums, ntiles);
+                    if (lane == 0) {
+                        sh.tiles[t] = w0;
+                        if (t + NW < ntiles) sh.tiles[t + NW] = w1;
+                    }
+                }
                 __syncthreads();
-                coop_now = false;                                // a later sweep, if any, is this workgroup's alone
             }
         }
         if (wave == 0) {
-            const int32_t tk = rp.ok ? select_token<BF16, true, FILT>(rp, sh.tiles, ntiles, u_eff, lane,
-                                                                      (slab_mode && attempt == 0) ? keep : nullptr, sums,
-                                                                      own_lo, own_hi) : -1;
+            int32_t tk = -1;
+            if constexpr (COOP) {
+                if (rp.ok) tk = select_token<BF16, true, FILT>(rp, sh.tiles, ntiles, u_eff, lane,
+                                                               (slab_mode && attempt == 0) ? keep : nullptr, sums, own_lo, own_hi);
+            } else {
+                if (rp.ok) tk = select_token<BF16, true, FILT>(rp, sh.tiles, ntiles, u_eff, lane,
+                                                               (slab_mode && attempt == 0) ? keep : nullptr, sums);
+            }
             if (lane == 0) sh.tok = tk;
         }
         __syncthreads();
@@ -392,7 +413,7 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedParams p)
 // statistics is started first and by wavefronts of its own, so that the memory round trips of a sequence overlap
 // instead of following one another: wavefront 0 fetches the drafted tokens and their logits, the last wavefront
 // picks the slab a bonus token would come from, the ones between merge the rows' partials.
-template <bool BF16, int NW, bool FILT = false>
+template <bool BF16, int NW, bool FILT = false, bool COOP = false>
 __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Partial* __restrict__ partials, int nparts)
 {
     __shared__ SeqShared sh;
@@ -402,7 +423,7 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
     uint4* const slab_raw = (NW == 16 && !FILT) ? s_raw : nullptr;
     __shared__ float4 s_sums[(NW == 16 && !FILT) ? kSumsKeepTiles * 64 : 1];   // likewise
     float4* const chunk_sums = (NW == 16 && !FILT) ? s_sums : nullptr;
-    const int G = (NW == 16 && !FILT && p.coop > 1) ? p.coop : 1;   // workgroups per sequence (see sequence_tail)
+    const int G = (COOP && p.coop > 1) ? p.coop : 1;             // workgroups per sequence (see sequence_tail)
     const int b = (int)blockIdx.x / G, part = (int)blockIdx.x % G;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = p.gamma;
@@ -434,7 +455,7 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
         }
     }
     __syncthreads();
-    sequence_tail<BF16, NW, FILT>(p, sh, b, len, Tb, tg, pre_slab, slab_raw, chunk_sums, part, G);
+    sequence_tail<BF16, NW, FILT, COOP>(p, sh, b, len, Tb, tg, pre_slab, slab_raw, chunk_sums, part, G);
 }
 
 bool fused_supported(int32_t gamma, int32_t V, int dtype)
@@ -481,10 +502,12 @@ hipError_t launch_tail(const FusedParams& p, const Partial* partials, int nparts
     if (p.dtype == HOLA_DTYPE_BF16) {
         if (nw == 4) hipLaunchKernelGGL((tail_kernel<true, 4>), grid, dim3(256), 0, s, p, partials, nparts);
         else if (nw == 8) hipLaunchKernelGGL((tail_kernel<true, 8>), grid, dim3(512), 0, s, p, partials, nparts);
+        else if (coop) hipLaunchKernelGGL((tail_kernel<true, 16, false, true>), grid, dim3(1024), 0, s, p, partials, nparts);
         else hipLaunchKernelGGL((tail_kernel<true, 16>), grid, dim3(1024), 0, s, p, partials, nparts);
     } else {
         if (nw == 4) hipLaunchKernelGGL((tail_kernel<false, 4>), grid, dim3(256), 0, s, p, partials, nparts);
         else if (nw == 8) hipLaunchKernelGGL((tail_kernel<false, 8>), grid, dim3(512), 0, s, p, partials, nparts);
+        else if (coop) hipLaunchKernelGGL((tail_kernel<false, 16, false, true>), grid, dim3(1024), 0, s, p, partials, nparts);
         else hipLaunchKernelGGL((tail_kernel<false, 16>), grid, dim3(1024), 0, s, p, partials, nparts);
     }
     return hipGetLastError();
