@@ -88,7 +88,14 @@ __device__ __forceinline__ void make_row_pair(RowPair& rp, const void* target, c
 // The 16-byte chunks c of the target row and (when it shares the alignment) of the draft row.  In the first
 // and last chunk the elements that lie outside the row are replaced by -inf logits (weight 0), so the weight
 // loop needs no guard.
-template <bool BF16>
+//
+// MODE (here and in chunk_weights_loaded): what kind of weights the row pair asks for is the same for every chunk of
+// a sweep, so the sweep decides it once and runs straight-line code.  kModeAny: look at rp for every chunk (same
+// arithmetic, for the few chunks of a selection); kModeBonus: p itself; kModeResidualVec: max(0, p - kappa q) with
+// the draft row on the target row's chunk grid; kModeResidualElem: the same with element loads of the draft row.
+constexpr int kModeAny = 0, kModeBonus = 1, kModeResidualVec = 2, kModeResidualElem = 3;
+
+template <bool BF16, int MODE = kModeAny>
 __device__ __forceinline__ void load_chunk_pair(const RowPair& rp, int64_t c, uint4& vp, uint4& vd)
 {
     constexpr int N = BF16 ? 8 : 4;
@@ -96,7 +103,7 @@ __device__ __forceinline__ void load_chunk_pair(const RowPair& rp, int64_t c, ui
     vd = make_uint4(0, 0, 0, 0);
     if (c < rp.nchunks) {
         vp = load_stream(rp.Pv + c);
-        const bool dvec = !rp.bonus && rp.Dv != nullptr;
+        const bool dvec = MODE == kModeAny ? (!rp.bonus && rp.Dv != nullptr) : MODE == kModeResidualVec;
         if (dvec) vd = load_stream(rp.Dv + c);
         if (c == 0 || c == rp.nchunks - 1) {
             const int32_t e0 = (int32_t)(c * N) - rp.head;
@@ -120,7 +127,7 @@ __device__ __forceinline__ void load_chunk_pair(const RowPair& rp, int64_t c, ui
 
 // Weights of the N elements of chunk c (0 for elements outside the row) and their fp32 sum in index
 // order, from chunks already loaded.
-template <bool BF16, bool FILT = false>
+template <bool BF16, bool FILT = false, int MODE = kModeAny>
 __device__ __forceinline__ float chunk_weights_loaded(const RowPair& rp, int64_t c, const uint4& vp, const uint4& vd, float* w)
 {
     constexpr int N = BF16 ? 8 : 4;
@@ -130,7 +137,8 @@ __device__ __forceinline__ float chunk_weights_loaded(const RowPair& rp, int64_t
         return 0.f;
     }
     const int32_t e0 = (int32_t)(c * N) - rp.head;
-    const bool dvec = !rp.bonus && rp.Dv != nullptr;
+    const bool bonus = MODE == kModeAny ? rp.bonus != 0 : MODE == kModeBonus;
+    const bool dvec = MODE == kModeAny ? (!rp.bonus && rp.Dv != nullptr) : MODE == kModeResidualVec;
     // Out-of-row elements of an edge chunk arrive as -inf logits (load_chunk_pair), so the loop carries no
     // per-element guard; a NaN weight is dropped by the max with 0.
     float sum = 0.f;
@@ -141,7 +149,7 @@ __device__ __forceinline__ float chunk_weights_loaded(const RowPair& rp, int64_t
         float ep = fast_exp2(exp_arg<BF16>(xp, rp.refP, rp.sc));
         if (FILT && !(xp > rp.thP || (xp == rp.thP && e <= rp.cutP))) ep = 0.f;
         float wk;
-        if (rp.bonus) {
+        if (bonus) {
             wk = fmaxf(ep, 0.f);
         } else {
             float xd;
@@ -250,16 +258,16 @@ __device__ __forceinline__ double tile_weight(const RowPair& rp, int64_t tile, i
 }
 
 // Two tiles with all their loads in flight together (twice the bytes per round trip).
-template <bool BF16, bool FILT = false>
-__device__ __forceinline__ void tile_weight2(const RowPair& rp, int64_t t0, int64_t t1, int lane, double& w0, double& w1,
-                                             float4* sums = nullptr, int ntiles = 0)
+template <bool BF16, bool FILT, int MODE>
+__device__ __forceinline__ void tile_weight2_mode(const RowPair& rp, int64_t t0, int64_t t1, int lane, double& w0, double& w1,
+                                                  float4* sums, int ntiles)
 {
     constexpr int N = BF16 ? 8 : 4;
     uint4 vp[2][kTileChunks], vd[2][kTileChunks];
 #pragma unroll
     for (int g = 0; g < kTileChunks; ++g) {
-        load_chunk_pair<BF16>(rp, t0 * (64 * kTileChunks) + g * 64 + lane, vp[0][g], vd[0][g]);
-        load_chunk_pair<BF16>(rp, t1 * (64 * kTileChunks) + g * 64 + lane, vp[1][g], vd[1][g]);
+        load_chunk_pair<BF16, MODE>(rp, t0 * (64 * kTileChunks) + g * 64 + lane, vp[0][g], vd[0][g]);
+        load_chunk_pair<BF16, MODE>(rp, t1 * (64 * kTileChunks) + g * 64 + lane, vp[1][g], vd[1][g]);
     }
 
     double a0 = 0.0, a1 = 0.0;
@@ -267,8 +275,8 @@ __device__ __forceinline__ void tile_weight2(const RowPair& rp, int64_t t0, int6
 #pragma unroll
     for (int g = 0; g < kTileChunks; ++g) {
         float w[N];
-        c0[g] = chunk_weights_loaded<BF16, FILT>(rp, t0 * (64 * kTileChunks) + g * 64 + lane, vp[0][g], vd[0][g], w);
-        c1[g] = chunk_weights_loaded<BF16, FILT>(rp, t1 * (64 * kTileChunks) + g * 64 + lane, vp[1][g], vd[1][g], w);
+        c0[g] = chunk_weights_loaded<BF16, FILT, MODE>(rp, t0 * (64 * kTileChunks) + g * 64 + lane, vp[0][g], vd[0][g], w);
+        c1[g] = chunk_weights_loaded<BF16, FILT, MODE>(rp, t1 * (64 * kTileChunks) + g * 64 + lane, vp[1][g], vd[1][g], w);
         a0 += (double)c0[g];
         a1 += (double)c1[g];
     }
@@ -278,6 +286,17 @@ __device__ __forceinline__ void tile_weight2(const RowPair& rp, int64_t t0, int6
     }
     w0 = wave_sum(a0) * rp.scale;
     w1 = wave_sum(a1) * rp.scale;
+}
+
+// The kind of weights is looked up once per pair of tiles (see kModeAny above): the element loops then carry no
+// branch on it.
+template <bool BF16, bool FILT = false>
+__device__ __forceinline__ void tile_weight2(const RowPair& rp, int64_t t0, int64_t t1, int lane, double& w0, double& w1,
+                                             float4* sums = nullptr, int ntiles = 0)
+{
+    if (rp.bonus) tile_weight2_mode<BF16, FILT, kModeBonus>(rp, t0, t1, lane, w0, w1, sums, ntiles);
+    else if (rp.Dv != nullptr) tile_weight2_mode<BF16, FILT, kModeResidualVec>(rp, t0, t1, lane, w0, w1, sums, ntiles);
+    else tile_weight2_mode<BF16, FILT, kModeResidualElem>(rp, t0, t1, lane, w0, w1, sums, ntiles);
 }
 
 // Tile weights may be rewritten by one lane and read by the others of the same wavefront (fallback
