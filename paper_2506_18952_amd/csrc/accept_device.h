@@ -34,27 +34,42 @@ __device__ __forceinline__ bool filter_keeps(float x, int32_t i, float theta, in
     return x > theta || (x == theta && i <= idx_cut);
 }
 
-// What lane j needs from memory for its position, none of which depends on the row statistics: the drafted token
-// and, on stochastic rows, its logit in both models.  Kept apart from the decision so that a caller can have these
-// loads in flight while the statistics are still being merged.
+// What lane j can have ready for its position before the row statistics are: the drafted token and, on stochastic
+// rows, its logit in both models (also divided by the temperature) and the position's Philox block.  Kept apart from
+// the decision so that a caller has the loads in flight, and this arithmetic done, while the statistics are still
+// being merged.
 struct TokenGather {
     int32_t x;                         // drafted token (-1 beyond len)
     float xp, xq;                      // its target and draft logits (0 where not loaded)
+    double ap, aq;                     // xp / T and xq / T as the decision uses them
+    float u_test, u_draw;              // words 0 and 1 of position j's Philox block as uniforms (0 where there is none)
 };
 
 template <bool BF16>
 __device__ __forceinline__ TokenGather accept_gather(const AcceptCtx& c, int b, int j, int len, float Tb)
 {
     TokenGather t;
-    t.x = -1; t.xp = 0.f; t.xq = 0.f;
+    t.x = -1; t.xp = 0.f; t.xq = 0.f; t.ap = 0.0; t.aq = 0.0; t.u_test = 0.f; t.u_draw = 0.f;
     const int g = c.gamma;
+    const bool greedy = !(Tb > 0.f);
     if (j < len) {
         t.x = c.tokens[(int64_t)b * c.tokens_ld + j];
-        if (Tb > 0.f && t.x >= 0 && t.x < c.V) {
+        if (!greedy && t.x >= 0 && t.x < c.V) {
             t.xp = load_logit<BF16>(c.target, ((int64_t)b * (g + 1) + j) * c.target_ld + t.x);
             t.xq = load_logit<BF16>(c.draft, ((int64_t)b * g + j) * c.draft_ld + t.x);
         }
     }
+    // Position j's Philox block: word 0 decides the acceptance test of drafted position j, word 1 draws the next token
+    // if the sequence stops at row j, so the lane that turns out to hold the stop row has its uniform at hand.
+    if (!greedy && j <= len) {
+        const uint64_t seq = (uint64_t)(c.seq_base + b);
+        const Philox4 r = philox4x32_10((uint32_t)j, (uint32_t)seq, (uint32_t)(seq >> 32), c.level, (uint32_t)c.seed, (uint32_t)(c.seed >> 32));
+        t.u_test = u24(r.x);
+        t.u_draw = u24(r.y);
+    }
+    const double invT = greedy ? 1.0 : 1.0 / (double)Tb;
+    t.ap = (double)t.xp * invT;
+    t.aq = (double)t.xq * invT;
     return t;
 }
 
@@ -82,7 +97,6 @@ __device__ __forceinline__ void accept_decide(const AcceptCtx& c, int b, int j, 
         }
     }
     const bool greedy = !(Tb > 0.f);
-    const double invT = greedy ? 1.0 : 1.0 / (double)Tb;
     const double tau = (double)c.tau;
     if (c.write_outputs && c.target_stats_out && j <= len) {
         c.target_stats_out[((int64_t)b * (g + 1) + j) * 2 + 0] = sp.lse;
@@ -94,12 +108,6 @@ __device__ __forceinline__ void accept_decide(const AcceptCtx& c, int b, int j, 
         for (int64_t jj = j; jj < width; jj += 64)
             c.out_entropy[(int64_t)b * eld + jj] = (jj < len) ? (float)sd.H : -1.0f;
     }
-    const uint64_t seq = (uint64_t)(c.seq_base + b);
-    // Position j's Philox block: word 0 decides the acceptance test of drafted position j, word 1 draws the next token
-    // if the sequence stops at row j, so the lane that turns out to hold the stop row has its uniform at hand.
-    Philox4 r = {0u, 0u, 0u, 0u};
-    if (!greedy && j <= len)
-        r = philox4x32_10((uint32_t)j, (uint32_t)seq, (uint32_t)(seq >> 32), c.level, (uint32_t)c.seed, (uint32_t)(c.seed >> 32));
     bool reject = false;
     if (j < len) {
         const bool gate = sd.H < tau;                   // strict; NaN never gates
@@ -110,14 +118,14 @@ __device__ __forceinline__ void accept_decide(const AcceptCtx& c, int b, int j, 
         } else {
             double p_x = 0.0, q_x = 1.0;
             if (x >= 0 && x < c.V) {
-                p_x = exp((double)tg.xp * invT - sp.lse);
-                q_x = exp((double)tg.xq * invT - sd.lse);
+                p_x = exp(tg.ap - sp.lse);
+                q_x = exp(tg.aq - sd.lse);
                 if (c.filters) {
                     if (!filter_keeps(tg.xp, x, thP, cutP)) p_x = 0.0;
                     if (!filter_keeps(tg.xq, x, thD, cutD)) q_x = 0.0;
                 }
             }
-            const double u = (double)u24(r.x);
+            const double u = (double)tg.u_test;
             ok = (u * q_x < p_x);
         }
         reject = !(gate || ok);
@@ -137,7 +145,7 @@ __device__ __forceinline__ void accept_decide(const AcceptCtx& c, int b, int j, 
             si.greedy_tok = sp.argmax;
             if (c.write_outputs) c.out_next_token[b] = sp.argmax;
         } else {
-            si.u = u24(r.y);                             // j == a: this lane's own block
+            si.u = tg.u_draw;                            // j == a: this lane's own block
             si.mode = (a < len) ? 0 : 1;
         }
         *si_out = si;

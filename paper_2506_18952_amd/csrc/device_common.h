@@ -66,6 +66,16 @@ __device__ __forceinline__ int64_t wave_uniform(int64_t v)
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
+// Lanes of ONE wavefront hand values to one another through memory (one lane stores, the others load): the hardware
+// keeps a wavefront's accesses to one kind of memory in order, but to the compiler a lane's load is unrelated to
+// another lane's store and may be moved ahead of it.  The fence (wavefront scope: no instruction of its own) pins
+// the order in the program; the barrier keeps the lanes' code together.
+__device__ __forceinline__ void wave_handoff()
+{
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // ---- 64-lane wavefront collectives (not on the streaming path) ------------------------------
 // Sums, scans, maxima and minima over the wavefront move data with data-parallel-primitive controls of the vector
 // unit (shifts inside the rows of 16 lanes, then the last lane of a row broadcast into the rows after it) instead of

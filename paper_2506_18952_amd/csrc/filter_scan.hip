@@ -361,7 +361,7 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
     }
     unsigned long long* list = p.cand + ((int64_t)it.r * p.nseg + it.seg) * p.cap_seg;
     if (nh <= kScanHot) {
-        __builtin_amdgcn_wave_barrier();                        // the wavefront reads what its own lanes stored
+        wave_handoff();                        // the wavefront reads what its own lanes stored
         constexpr int IT = kScanHot * N / 64;
         const int nel = nh * N;
         float xs[IT];
@@ -567,12 +567,12 @@ __global__ __launch_bounds__(64, E > kScanSlots ? 2 : ((WANT_K && WANT_P) ? 4 : 
                 }
             }
         }
-        __builtin_amdgcn_wave_barrier();
+        wave_handoff();
         n = cnt;
         nslots = (cnt + 63) / 64;
 #pragma unroll
         for (int j = 0; j < E; ++j) ent[j] = (j < nslots && j * 64 + lane < cnt) ? s_pack[j * 64 + lane] : 0ull;
-        __builtin_amdgcn_wave_barrier();
+        wave_handoff();
     };
     // key bits on which every listed token agrees (the list spans a narrow range of logits): the descents skip them
     uint32_t same = 0, same_bits = 0;
@@ -620,7 +620,7 @@ __global__ __launch_bounds__(64, E > kScanSlots ? 2 : ((WANT_K && WANT_P) ? 4 : 
         const unsigned long long e = ent[0];
         const uint32_t key = logit_key(e), idx = (uint32_t)(e & 0xffffffffu);
         s_pack[lane] = e;
-        __builtin_amdgcn_wave_barrier();
+        wave_handoff();
         int rank = 0;
         for (int q = 0; q < n; ++q) {
             const unsigned long long o = s_pack[q];
@@ -631,7 +631,7 @@ __global__ __launch_bounds__(64, E > kScanSlots ? 2 : ((WANT_K && WANT_P) ? 4 : 
             s_ord_e[rank] = e;
             s_ord_m[rank] = list_mass_fixed<BF16>(fr, key_to_logit<BF16>(key));
         }
-        __builtin_amdgcn_wave_barrier();
+        wave_handoff();
         const unsigned long long er = lane < n ? s_ord_e[lane] : 0ull;
         unsigned long long incl = lane < n ? s_ord_m[lane] : 0ull;
 #pragma unroll
@@ -786,7 +786,7 @@ __global__ __launch_bounds__(64, E > kScanSlots ? 2 : ((WANT_K && WANT_P) ? 4 : 
                 }
             }
         }
-        __builtin_amdgcn_wave_barrier();
+        wave_handoff();
         const uint32_t mine = lane < (int)n_ties ? s_tie[lane] : 0xffffffffu;
         uint32_t below = 0;
         for (int q = 0; q < (int)n_ties; ++q) below += s_tie[q] < mine ? 1u : 0u;

@@ -137,17 +137,14 @@ __device__ __forceinline__ void write_glue(const FusedParams& p, int b, int a, i
 // the accept stage decides.  If the sequence turns out rejected, the work is dropped.  Called by one whole
 // wavefront; fills sh.slab_*.
 template <bool BF16>
-__device__ __forceinline__ void pick_bonus_slab(const FusedParams& p, SeqShared& sh, int b, int len,
-                                                const Partial* parts, int nparts, int lane)
+__device__ __forceinline__ bool pick_bonus_slab(const FusedParams& p, int b, int len, const Partial* parts, int nparts, int lane,
+                                                int64_t& lo, int64_t& hi, double& frac)
 {
     const uint64_t seq = (uint64_t)(p.seq_base + b);
     const Philox4 r = philox4x32_10((uint32_t)len, (uint32_t)seq, (uint32_t)(seq >> 32), p.level,
                                     (uint32_t)p.seed, (uint32_t)(p.seed >> 32));
-    int64_t lo = 0, hi = 0;
-    double frac = 0.0;
-    const int ok = pick_row_slab<BF16>(p.target, p.target_ld, p.gamma, p.V, p.B, b, len, parts, nparts, (double)u24(r.y), lane,
-                                       lo, hi, frac) ? 1 : 0;
-    if (lane == 0) { sh.slab_lo = lo; sh.slab_hi = hi; sh.slab_u = frac; sh.slab_ok = ok; }
+    return pick_row_slab<BF16>(p.target, p.target_ld, p.gamma, p.V, p.B, b, len, parts, nparts, (double)u24(r.y), lane,
+                               lo, hi, frac);
 }
 
 // Accept stage (wavefront 0) and sampling (all wavefronts) of sequence b, given sh.stat[] and, in wavefront 0, the
@@ -166,13 +163,15 @@ __device__ __forceinline__ void pick_bonus_slab(const FusedParams& p, SeqShared&
 template <bool BF16, int NW, bool FILT = false, bool COOP = false>
 __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& sh, int b, int len, float Tb,
                                               const TokenGather& tg, bool pre_slab = false, uint4* slab_raw = nullptr,
-                                              float4* chunk_sums = nullptr, int part = 0, int G = 1)
+                                              float4* chunk_sums = nullptr, int part = 0, int G = 1,
+                                              const TilePre pre = TilePre{})
 {
     static_assert(!COOP || (NW == 16 && !FILT), "a shared tail is the 16-wavefront unfiltered variant's alone");
     if (!COOP) { part = 0; G = 1; }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = p.gamma;
     constexpr int N = BF16 ? 8 : 4;
+    const ExpScale* const scp = p.sc_given ? &p.sc : nullptr;       // one temperature: the host made the constants
     const bool slab_ready = pre_slab && sh.slab_ok;                 // uniform over the workgroup
     const int64_t slab_lo = slab_ready ? sh.slab_lo : 0, slab_hi = slab_ready ? sh.slab_hi : 0;
     const int slab_tiles = (int)((slab_hi - slab_lo + 64 * kTileChunks - 1) / (64 * kTileChunks));
@@ -210,11 +209,20 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
         SeqInfo sb;
         sb.lseP = sh.stat[g + len].lse; sb.lseD = 0.0; sb.u = 0.f; sb.row = len; sb.mode = 1; sb.greedy_tok = -1;
         RowPair rq;
-        make_row_pair<BF16>(rq, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, sb, 0, nullptr, p.B);
+        make_row_pair<BF16>(rq, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, sb, 0, nullptr, p.B, nullptr, scp);
         if (rq.ok) {
             narrow_to_slab<BF16>(rq, slab_lo, slab_hi);
-            for (int t = wave - 1; t < slab_tiles; t += NW - 1) {   // a slab is a few tiles: one per wavefront
-                const double w0 = tile_weight<BF16>(rq, t, lane, keep, slab_tiles <= kSumsKeepTiles ? chunk_sums : nullptr);
+            // a slab is a few tiles: one per wavefront, the last wavefront first (those are the ones with nothing to
+            // merge, which had their tile's chunks in flight since before the statistics were there: pre)
+            float4* const ssums = slab_tiles <= kSumsKeepTiles ? chunk_sums : nullptr;
+            int t = (NW - 1) - wave;
+            if (pre.ok) {
+                const double w0 = tile_weight_preloaded<BF16>(rq, t, lane, pre, keep, ssums);
+                if (lane == 0) sh.tiles[t] = w0;
+                t += NW - 1;
+            }
+            for (; t < slab_tiles; t += NW - 1) {
+                const double w0 = tile_weight<BF16>(rq, t, lane, keep, ssums);
                 if (lane == 0) sh.tiles[t] = w0;
             }
         }
@@ -227,7 +235,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
     }
 
     RowPair rp;
-    make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0, FILT ? p.filters : nullptr, p.B, FILT ? p.draft_filters : nullptr);
+    make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0, FILT ? p.filters : nullptr, p.B, FILT ? p.draft_filters : nullptr, scp);
     int ntiles = p.ntiles;
     int32_t tok_off = 0;
     double u_eff = (double)si.u;
@@ -268,7 +276,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
             tok = sh.tok;
             if (tok != -2) break;
             __syncthreads();
-            make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1, FILT ? p.filters : nullptr, p.B, FILT ? p.draft_filters : nullptr);
+            make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1, FILT ? p.filters : nullptr, p.B, FILT ? p.draft_filters : nullptr, scp);
             continue;
         }
         if (!(slab_mode && attempt == 0)) {
@@ -337,13 +345,13 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
             if (tok >= 0) { tok += tok_off; break; }
             // no mass in the slab by the sampler's arithmetic (an underflow the partials did not have): the whole row
             slab_mode = false;
-            make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0, FILT ? p.filters : nullptr, p.B, FILT ? p.draft_filters : nullptr);
+            make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 0, FILT ? p.filters : nullptr, p.B, FILT ? p.draft_filters : nullptr, scp);
             ntiles = p.ntiles;
             u_eff = (double)si.u;
             continue;
         }
         if (tok != -2) break;                                    // -2: no residual mass, sample p itself
-        make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1, FILT ? p.filters : nullptr, p.B, FILT ? p.draft_filters : nullptr);
+        make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, g, p.V, Tb, b, si, 1, FILT ? p.filters : nullptr, p.B, FILT ? p.draft_filters : nullptr, scp);
     }
     if (tid == 0) p.out_next_token[b] = tok < 0 ? -1 : tok;
     write_glue(p, b, si.row, tok < 0 ? -1 : tok);
@@ -403,7 +411,8 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedParams p)
         const RowStat rs = merge_partials_wave(&s_part[r][0], NW, lane);
         if (lane == 0) sh.stat[r] = rs;
     }
-    TokenGather tg = {-1, 0.f, 0.f};
+    TokenGather tg{};
+    tg.x = -1;
     if (wave == 0) tg = accept_gather<BF16>(accept_ctx(p), b, lane, len, Tb);
     __syncthreads();
     sequence_tail<BF16, NW>(p, sh, b, len, Tb, tg);
@@ -433,18 +442,21 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
     const int first_row = p.draft_stats_in ? g : 0;
     const int end_row = (p.target_stats_in || FILT) ? g : 2 * g + 1;   // supplied or filtered statistics are not merged here
     const bool pre_slab = !FILT && !p.target_stats_in && nparts >= 4 && Tb > 0.f;
-    TokenGather tg = {-1, 0.f, 0.f};
+    TokenGather tg{};
+    tg.x = -1;
+    // `width` lanes per row (one lane per partial), 64 / width rows per wavefront; with pre_slab the last wavefront
+    // never merges
+    const int mergers = pre_slab ? NW - 2 : NW - 1, mw = wave - 1;
+    int width = 4;
+    while (width < nparts) width <<= 1;
+    const int per_wave = 64 / width, seg = lane / width, sl = lane % width;
+    const int base_row = FILT ? g : first_row;
+    const bool merges = wave >= 1 && wave <= mergers && base_row + mw * per_wave < end_row;
+    TilePre pre{};                                               // ok = false
     if (wave == 0) {
         tg = accept_gather<BF16>(accept_ctx(p), b, lane, len, Tb);
-    } else if (wave == NW - 1 && pre_slab) {
-        pick_bonus_slab<BF16>(p, sh, b, len, partials, nparts, lane);
-    } else {
-        // `width` lanes per row (one lane per partial), 64 / width rows per wavefront
-        const int mergers = pre_slab ? NW - 2 : NW - 1, mw = wave - 1;
-        int width = 4;
-        while (width < nparts) width <<= 1;
-        const int per_wave = 64 / width, seg = lane / width, sl = lane % width;
-        for (int r0 = (FILT ? g : first_row) + mw * per_wave; r0 < end_row; r0 += mergers * per_wave) {
+    } else if (merges) {
+        for (int r0 = base_row + mw * per_wave; r0 < end_row; r0 += mergers * per_wave) {
             const int r = r0 + seg;
             const bool is_draft = r < g;
             const int j = is_draft ? r : r - g;
@@ -453,9 +465,23 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
             const RowStat s = merge_partials_seg(need ? partials + slot * nparts : nullptr, nparts, sl, width);
             if (need && sl == 0) sh.stat[r] = s;
         }
+    } else if (pre_slab) {
+        // Nothing to merge: pick the slab a bonus token would come from (every such wavefront by itself: the same
+        // loads and arithmetic, the same answer, and no trip through shared memory) and put this wavefront's tile of it
+        // in flight, so that its chunks are there when the statistics are.
+        int64_t lo = 0, hi = 0;
+        double frac = 0.0;
+        const bool ok = pick_bonus_slab<BF16>(p, b, len, partials, nparts, lane, lo, hi, frac);
+        if (wave == NW - 1 && lane == 0) { sh.slab_lo = lo; sh.slab_hi = hi; sh.slab_u = frac; sh.slab_ok = ok ? 1 : 0; }
+        const int64_t t = (NW - 1) - wave;
+        if (ok && (!COOP || part == 0) && t * (64 * kTileChunks) < hi - lo) {
+            constexpr int ES = BF16 ? 2 : 4;
+            const char* row = (const char*)p.target + ((int64_t)b * (g + 1) + len) * p.target_ld * ES;
+            pre = tile_preload((const uint4*)row, lo, hi - lo, t, lane);   // rows with slabs start on the chunk grid
+        }
     }
     __syncthreads();
-    sequence_tail<BF16, NW, FILT, COOP>(p, sh, b, len, Tb, tg, pre_slab, slab_raw, chunk_sums, part, G);
+    sequence_tail<BF16, NW, FILT, COOP>(p, sh, b, len, Tb, tg, pre_slab, slab_raw, chunk_sums, part, G, pre);
 }
 
 bool fused_supported(int32_t gamma, int32_t V, int dtype)

@@ -283,6 +283,8 @@ static hola_status run_level(const hola_verify_args& a, const LevelExtras& x = L
     fp.tokens_ld = x.tokens_ld ? x.tokens_ld : a.gamma; fp.pad_entropy = x.pad_entropy;
     fp.glue_tok = x.glue_tok; fp.glue_len = x.glue_len; fp.glue_ld = x.glue_ld; fp.glue_keep_next = x.glue_keep_next;
     fp.temperature = a.temperature; fp.tau = a.entropy_threshold;
+    fp.sc_given = (a.row_temperature == nullptr && a.temperature > 0.f) ? 1 : 0;
+    if (fp.sc_given) fp.sc = host_scale((double)a.temperature);
     fp.out_accept_len = a.out_accept_len; fp.out_next_token = a.out_next_token;
     fp.out_entropy = a.out_entropy; fp.entropy_ld = a.entropy_ld;
 
@@ -418,6 +420,8 @@ static hola_status run_literal(const hola_verify_args& a, int32_t* out_tokens, i
     fp.seed = a.seed; fp.level = a.level; fp.seq_base = a.seq_base;
     fp.B = a.B; fp.gamma = a.gamma; fp.V = a.V; fp.ntiles = sampler_tiles(a.V, a.dtype);
     fp.tokens_ld = a.gamma; fp.temperature = a.temperature; fp.tau = a.entropy_threshold;
+    fp.sc_given = (a.row_temperature == nullptr && a.temperature > 0.f) ? 1 : 0;
+    if (fp.sc_given) fp.sc = host_scale((double)a.temperature);
     fp.out_entropy = a.out_entropy; fp.entropy_ld = a.entropy_ld;
     { StageTimer t(6, s); e = launch_literal(fp, w.partials, nsplit * kWaves, out_tokens, out_calls, s); }
     if (e != hipSuccess) return hip_fail(e, "literal launch");
@@ -752,6 +756,7 @@ hola_status hola_verify_tree(const hola_tree_args* args)
     tp.seed = a.seed; tp.level = a.level; tp.seq_base = a.seq_base;
     tp.B = a.B; tp.N = a.N; tp.V = a.V; tp.ntiles = sampler_tiles(a.V, a.dtype);
     tp.temperature = a.temperature; tp.tau = a.entropy_threshold;
+    tp.sc = host_scale((double)a.temperature);
     tp.out_accept_len = a.out_accept_len; tp.out_path = a.out_path; tp.out_next_token = a.out_next_token;
     tp.out_entropy = a.out_entropy;
     const int waves = tune.fused_waves ? tune.fused_waves : (a.B <= device_cu_count() ? 16 : 8);

@@ -162,6 +162,8 @@ struct FusedParams {
     // for each other ([B, ntiles]), the sequences' completion tickets ([B], any contents) and this call's tag for them
     int32_t coop;
     double* coop_tiles; unsigned long long* coop_tickets; unsigned long long coop_tag;
+    // the scale constants of a call with one temperature > 0, made once on the host (sc_given), as in RowStatsParams
+    ExpScale sc; int32_t sc_given;
 };
 
 // Token trees: N nodes per sequence, rows by context as the one-token step lays them out with gamma = N.
@@ -173,6 +175,7 @@ struct TreeParams {
     int32_t B, N, V, ntiles;
     float temperature, tau;
     int32_t* out_accept_len; int32_t* out_path; int32_t* out_next_token; float* out_entropy;
+    ExpScale sc;                       // host_scale(temperature)
 };
 bool tree_supported(int32_t N, int32_t V, int dtype);
 hipError_t launch_tree_tail(const TreeParams& p, const Partial* partials, int nparts, int waves, hipStream_t s);

@@ -113,7 +113,7 @@ __global__ __launch_bounds__(NW * 64) void literal_kernel(FusedParams p, const P
                             if (tl + 1 < slab_tiles) my_tiles[tl + 1] = w1;
                         }
                     }
-                    __builtin_amdgcn_wave_barrier();             // the wavefront reads what its own lane 0 stored
+                    wave_handoff();             // the wavefront reads what its own lane 0 stored
                     tk = select_token<BF16, true>(rp, my_tiles, slab_tiles, frac, lane);
                     if (tk >= 0) tk += (int32_t)(lo * (BF16 ? 8 : 4));
                 }

@@ -42,12 +42,13 @@ template <bool BF16>
 __device__ __forceinline__ void make_row_pair(RowPair& rp, const void* target, const void* draft, int64_t target_ld,
                                               int64_t draft_ld, int32_t gamma, int32_t V, float Tb, int b,
                                               const SeqInfo& si, int force_bonus, const RowFilter* filters = nullptr,
-                                              int32_t B = 0, const RowFilter* draft_filters = nullptr)
+                                              int32_t B = 0, const RowFilter* draft_filters = nullptr,
+                                              const ExpScale* sc = nullptr /* the constants for Tb, if the caller has them */)
 {
     constexpr int N = BF16 ? 8 : 4;
     constexpr int ES = BF16 ? 2 : 4;
     const int g = gamma;
-    rp.sc = make_scale(kLog2e / (double)Tb);
+    rp.sc = sc ? *sc : make_scale(kLog2e / (double)Tb);
     rp.V = V;
     const char* rowP = (const char*)target + ((int64_t)b * (g + 1) + si.row) * target_ld * ES;
     const uintptr_t aP = (uintptr_t)rowP;
@@ -195,7 +196,7 @@ __device__ __forceinline__ bool pick_row_slab(const void* target, int64_t target
     if (lane < nparts) { S = ps[lane].S; br = ps[lane].bref; }
     const bool has = S > 0.0 && S < INFINITY;
     const double bmin = wave_min(has ? br : (double)INFINITY);
-    const double W = has ? S * exp2(bmin - br) : 0.0;              // the slab's mass against a common reference
+    const double W = has ? S * exp2_offset_diff(bmin - br) : 0.0;              // the slab's mass against a common reference
     const double incl = wave_inclusive_scan(W, lane);
     const double Z = __shfl(incl, 63, 64);
     const double target_mass = u * Z;
@@ -231,13 +232,10 @@ constexpr int kSumsKeepTiles = 80;
 // sums: shared memory for the lanes' four chunk sums of every tile ([tile][lane]), which select_token then need
 // not rebuild from the row; or null.
 template <bool BF16>
-__device__ __forceinline__ double tile_weight(const RowPair& rp, int64_t tile, int lane, uint4* keep = nullptr,
-                                              float4* sums = nullptr)
+__device__ __forceinline__ double tile_weight_of(const RowPair& rp, int64_t tile, int lane, const uint4* vp, const uint4* vd,
+                                                 uint4* keep, float4* sums)
 {
     constexpr int N = BF16 ? 8 : 4;
-    uint4 vp[kTileChunks], vd[kTileChunks];
-#pragma unroll
-    for (int g = 0; g < kTileChunks; ++g) load_chunk_pair<BF16>(rp, tile * (64 * kTileChunks) + g * 64 + lane, vp[g], vd[g]);
     if (keep != nullptr) {
 #pragma unroll
         for (int g = 0; g < kTileChunks; ++g) {
@@ -255,6 +253,51 @@ __device__ __forceinline__ double tile_weight(const RowPair& rp, int64_t tile, i
     }
     if (sums != nullptr) sums[tile * 64 + lane] = make_float4(cs[0], cs[1], cs[2], cs[3]);
     return wave_sum(acc) * rp.scale;
+}
+
+template <bool BF16>
+__device__ __forceinline__ double tile_weight(const RowPair& rp, int64_t tile, int lane, uint4* keep = nullptr,
+                                              float4* sums = nullptr)
+{
+    uint4 vp[kTileChunks], vd[kTileChunks];
+#pragma unroll
+    for (int g = 0; g < kTileChunks; ++g) load_chunk_pair<BF16>(rp, tile * (64 * kTileChunks) + g * 64 + lane, vp[g], vd[g]);
+    return tile_weight_of<BF16>(rp, tile, lane, vp, vd, keep, sums);
+}
+
+// One tile's chunks of a lane, fetched ahead of the weights (ok: wavefront-uniform, the chunks are there).  Four named
+// members rather than an array, so that the chunks stay in registers on their way through the callers.
+struct TilePre {
+    uint4 v0, v1, v2, v3;
+    bool ok;
+};
+static_assert(kTileChunks == 4, "TilePre holds one tile's four chunks per lane");
+
+// The lane's chunks of tile `tile` of a slab [lo, lo + n) of a target row whose chunk grid starts at rowv (a row with
+// slabs: no ragged ends, so no chunk needs patching), loaded before the row pair exists; zeros past the slab.
+__device__ __forceinline__ TilePre tile_preload(const uint4* rowv, int64_t lo, int64_t n, int64_t tile, int lane)
+{
+    const int64_t c = tile * (64 * kTileChunks) + lane;
+    TilePre t;
+    t.v0 = t.v1 = t.v2 = t.v3 = make_uint4(0, 0, 0, 0);
+    if (c < n) t.v0 = load_stream(rowv + lo + c);
+    if (c + 64 < n) t.v1 = load_stream(rowv + lo + c + 64);
+    if (c + 128 < n) t.v2 = load_stream(rowv + lo + c + 128);
+    if (c + 192 < n) t.v3 = load_stream(rowv + lo + c + 192);
+    t.ok = true;
+    return t;
+}
+
+// Bonus weight of a tile of a row pair narrowed to that slab, from chunks tile_preload fetched.
+template <bool BF16>
+__device__ __forceinline__ double tile_weight_preloaded(const RowPair& rp, int64_t tile, int lane, const TilePre& pre,
+                                                        uint4* keep = nullptr, float4* sums = nullptr)
+{
+    const uint4 vp[kTileChunks] = {pre.v0, pre.v1, pre.v2, pre.v3};
+    uint4 vd[kTileChunks];
+#pragma unroll
+    for (int g = 0; g < kTileChunks; ++g) vd[g] = make_uint4(0, 0, 0, 0);
+    return tile_weight_of<BF16>(rp, tile, lane, vp, vd, keep, sums);
 }
 
 // Two tiles with all their loads in flight together (twice the bytes per round trip).

@@ -222,6 +222,14 @@ __device__ __forceinline__ void accum_chunk_robust(LaneState& st, const uint4& v
     for (int k = 0; k < N; ++k) accum_elem<BF16, ARGMAX>(st, chunk_elem<BF16>(v, k), elem0 + k, sc);
 }
 
+// 2^d for d <= 0 in the merges of partial sums.  The offsets of bf16 rows are integers, so their differences are
+// too, and the factor is a power of two that needs no polynomial (the same value: 2^d is exact there).
+__device__ __forceinline__ double exp2_offset_diff(double d)
+{
+    if (d == rint(d)) return ldexp(1.0, (int)fmax(d, -4096.0));
+    return exp2(d);
+}
+
 // Merge the 64 lane states in double; every lane returns the wavefront's Partial.
 template <bool BF16, bool ARGMAX>
 __device__ __forceinline__ Partial wave_merge(const LaneState& st, const ExpScale& sc)
@@ -234,7 +242,7 @@ __device__ __forceinline__ Partial wave_merge(const LaneState& st, const ExpScal
         const double diff = bmin - beta;                // <= 0
         S = st.Sd; T = st.Td;
         if (diff != 0.0) {
-            const double f = exp2(diff);
+            const double f = exp2_offset_diff(diff);
             T = (T + diff * S) * f;
             S *= f;
         }
@@ -493,7 +501,7 @@ __device__ __forceinline__ RowStat merge_partials(const Partial* __restrict__ ps
         if (q.S > 0.0) {
             const double d = bmin - q.bref;             // <= 0
             if (d == 0.0) { S += q.S; T += q.T; }
-            else { const double f = exp2(d); S += q.S * f; T += (q.T + d * q.S) * f; }
+            else { const double f = exp2_offset_diff(d); S += q.S * f; T += (q.T + d * q.S) * f; }
         }
         if (q.imax >= 0 && (imax < 0 || q.vmax > vmax || (q.vmax == vmax && q.imax < imax))) {
             vmax = q.vmax;
@@ -527,7 +535,7 @@ __device__ __forceinline__ RowStat merge_partials_wave(const Partial* __restrict
     if (q.S > 0.0) {
         const double d = bmin - q.bref;
         if (d == 0.0) { S = q.S; T = q.T; }
-        else { const double f = exp2(d); S = q.S * f; T = (q.T + d * q.S) * f; }
+        else { const double f = exp2_offset_diff(d); S = q.S * f; T = (q.T + d * q.S) * f; }
     }
     S = wave_sum(S);
     T = wave_sum(T);
@@ -570,7 +578,7 @@ __device__ __forceinline__ RowStat merge_partials_seg(const Partial* __restrict_
     if (q.S > 0.0) {
         const double d = bmin - q.bref;
         if (d == 0.0) { S = q.S; T = q.T; }
-        else { const double f = exp2(d); S = q.S * f; T = (q.T + d * q.S) * f; }
+        else { const double f = exp2_offset_diff(d); S = q.S * f; T = (q.T + d * q.S) * f; }
     }
     float v = q.vmax;
     int32_t i = q.imax;

@@ -116,7 +116,7 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
         if (p.out_entropy && n < N) p.out_entropy[(int64_t)b * N + n] = (n < len && sh.used[n]) ? (float)sh.stat[n].H : -1.0f;
         if (lane == 0) sh.done = 0;
     }
-    __builtin_amdgcn_wave_barrier();
+    wave_handoff();
 
     // ---- the walk (wavefront 0, every lane the same values) and the row sweeps it asks for (all wavefronts).
     // Between rounds the walk's state rests in shared memory, so that no register holds it during a sweep.
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
     }
     for (int it = 0; it < 2 * 64 + 4; ++it) {                   // every round ends the walk or uses up a child
         if (wave == 0) {
-            __builtin_amdgcn_wave_barrier();
+            wave_handoff();
             const int mine = sh.ctx_of[lane];
             int ctx = sh.w_ctx, depth = sh.w_depth;
             bool first = sh.w_first != 0;
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
                 sample = 0; bonus = 0;                           // more children to try: the next Z
                 break;
             }
-            __builtin_amdgcn_wave_barrier();
+            wave_handoff();
             if (lane == 0) {
                 sh.op_ctx = ctx; sh.op_bonus = bonus; sh.op_sample = sample; sh.op_C = C;
                 sh.w_ctx = ctx; sh.w_depth = depth; sh.w_first = first ? 1 : 0; sh.w_C = C;
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
         si.mode = o_bonus ? 1 : 0;
         si.u = 0.f; si.greedy_tok = -1;
         RowPair rp;
-        make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, N, p.V, Tb, b, si, o_bonus);
+        make_row_pair<BF16>(rp, p.target, p.draft, p.target_ld, p.draft_ld, N, p.V, Tb, b, si, o_bonus, nullptr, 0, nullptr, &p.sc);
         if (!rp.bonus && o_C != 1.0) {                           // weights max(0, p - C q): C joins the factor on q
             const double kappa = ((double)rp.k_hi + (double)rp.k_lo) * o_C;
             rp.k_hi = (float)kappa;
