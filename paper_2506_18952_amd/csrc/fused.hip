@@ -168,7 +168,7 @@ __device__ __forceinline__ void sequence_tail(const FusedParams& p, SeqShared& s
 {
     static_assert(!COOP || (NW == 16 && !FILT), "a shared tail is the 16-wavefront unfiltered variant's alone");
     if (!COOP) { part = 0; G = 1; }
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: a scalar
     const int g = p.gamma;
     constexpr int N = BF16 ? 8 : 4;
     const ExpScale* const scp = p.sc_given ? &p.sc : nullptr;       // one temperature: the host made the constants
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedParams p)
     __shared__ int32_t s_prog[NW];
 
     const int b = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: a scalar
     const int g = p.gamma;
     int len = p.draft_len ? p.draft_len[b] : g;
     len = len < 0 ? 0 : (len > g ? g : len);
@@ -434,7 +434,7 @@ __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Part
     float4* const chunk_sums = (NW == 16 && !FILT) ? s_sums : nullptr;
     const int G = (COOP && p.coop > 1) ? p.coop : 1;             // workgroups per sequence (see sequence_tail)
     const int b = (int)blockIdx.x / G, part = (int)blockIdx.x % G;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: a scalar
     const int g = p.gamma;
     int len = p.draft_len ? p.draft_len[b] : g;
     len = len < 0 ? 0 : (len > g ? g : len);

@@ -30,7 +30,7 @@ __global__ __launch_bounds__(NW * 64) void literal_kernel(FusedParams p, const P
     __shared__ LiteralShared sh;
     __shared__ float4 s_sums[NW == 16 ? kSumsKeepTiles * 64 : 1];   // the lanes' chunk sums of a sweep, for its selection
     const int b = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: a scalar
     const int g = p.gamma;
     int len = p.draft_len ? p.draft_len[b] : g;
     len = len < 0 ? 0 : (len > g ? g : len);

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(NW * 64) void tree_tail_kernel(TreeParams p, const 
 {
     __shared__ TreeShared sh;
     const int b = blockIdx.x;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: a scalar
     const int N = p.N;
     int len = p.n_nodes ? p.n_nodes[b] : N;
     len = len < 0 ? 0 : (len > N ? N : len);
