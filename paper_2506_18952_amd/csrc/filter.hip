@@ -379,7 +379,7 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
     constexpr int ES = BF16 ? 2 : 4;
     constexpr int KB = BF16 ? 16 : 32;
     constexpr int sh0 = KB - kLevelBits;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: a scalar
     if (p.flags && !p.flags[blockIdx.x]) return;                // settled by the scan (uniform exit)
     const int g = p.gamma;
     const int rows_per_seq = 2 * g + 1;

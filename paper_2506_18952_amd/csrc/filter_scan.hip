@@ -178,7 +178,7 @@ __device__ __forceinline__ void scan_segment(const ScanParams& p, const ScanItem
     constexpr int U = ScanU<BF16>::value;
     constexpr int NT = kScanThreads;
     constexpr int NW = kScanWaves;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: a scalar
     if (!it.used) return;                                       // uniform
     SegInfo* seg_out = p.segs + (int64_t)it.r * p.nseg + it.seg;
     if (it.n_c <= 0) {                                          // fewer chunks than segments

@@ -13,7 +13,7 @@ template <bool BF16, bool ARGMAX, int U, bool WITH_T = true>
 __device__ __forceinline__ void row_segment(const void* row, int32_t V, int seg, int nsplit, bool slabs, const ExpScale& sc,
                                             Partial* __restrict__ out /* [kWaves] of this (row, segment) */)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in every lane: a scalar
     const RowGeom g = make_geom<BF16>(row, V);
     // The segment's chunks go to the four wavefronts interleaved in blocks of 64 (the fastest order: 3.5 % faster
     // than four contiguous slabs), except on the row a bonus token would be drawn from, where each wavefront
