@@ -701,17 +701,20 @@ def main() -> int:
         else:
             refs = [orc.verify(w.target, w.draft, w.tokens, w.seed, w.temperature, tau, num_threads=threads) for tau in taus]
         cdt = time.perf_counter() - t0
-        same = same_t = near = 0
+        same = same_t = near = unlisted_diff = 0
         for i, tau in enumerate(taus):
             step(i, seed_offset=False)
             torch.cuda.synchronize()
-            same += int((acc.cpu().numpy() == refs[i].accept_len).sum())
-            same_t += int((nxt.cpu().numpy() == refs[i].next_token).sum())
+            ok_a = acc.cpu().numpy() == refs[i].accept_len
+            ok_t = nxt.cpu().numpy() == refs[i].next_token
+            same += int(ok_a.sum())
+            same_t += int(ok_t.sum())
             # sequences with a deciding comparison the oracle lists as near-threshold (margin < 1e-6)
             m = np.minimum(np.nan_to_num(refs[i].sample_margin, nan=np.inf),
                            np.minimum(np.nan_to_num(refs[i].gate_margin, nan=np.inf).min(axis=1),
                                       np.nan_to_num(refs[i].ratio_margin, nan=np.inf).min(axis=1)))
             near += int((m < 1e-6).sum())
+            unlisted_diff += int((~(ok_a & ok_t) & ~(m < 1e-6)).sum())   # differences the parity bar does not allow: must be 0
         n = B * len(taus)
         # the same oracle on one thread, on a slice of the batch (a second or two)
         n1 = min(B, 32)
@@ -729,7 +732,8 @@ def main() -> int:
                                          f"({len(taus)} oracle calls, {cdt:.2f}s wall, {cdt * threads:.0f} core-seconds); "
                                          f"float64 C oracle, OpenMP over sequences",
                                "agree_accept_len": f"{same}/{n}", "agree_next_token": f"{same_t}/{n}",
-                               "oracle_listed_near_threshold": near, "host": _host_info()}
+                               "oracle_listed_near_threshold": near, "differences_outside_the_listed": unlisted_diff,
+                               "host": _host_info()}
     print(json.dumps(out), flush=True)
     return 0
 
