@@ -134,3 +134,51 @@ def test_shared_tail_in_a_hip_graph():
         np.testing.assert_array_equal(got.entropy, base.entropy)
         _call(P, D, tok, w, tau, 2, ws)                        # eager work on the same workspace between the replays
         torch.cuda.synchronize()
+
+
+def test_two_batches_in_flight_on_two_streams():
+    """Two independent batches, each with its own workspace and outputs, issued alternately on two streams (their
+    kernels overlap on the chip, shared tails and their tickets included): every call gives what it gives alone."""
+    w = wl.config3(B=24)
+    B, g, V = w.B, w.gamma, w.V
+    nbytes = hb.hola_workspace_bytes(B, g, V)
+    n_calls = 12
+    sets = []
+    for k in range(2):
+        sub = slice(0, B) if k == 0 else slice(None, None, -1)     # the second batch: the same sequences in reverse order
+        sets.append(dict(P=to_dev(np.ascontiguousarray(w.target[sub])), D=to_dev(np.ascontiguousarray(w.draft[sub])),
+                         tok=to_dev(np.ascontiguousarray(w.tokens[sub])), ws=_dirty_workspace(nbytes, "random"),
+                         stream=torch.cuda.Stream()))
+
+    def call(k, i, stream, outs):
+        s = sets[k]
+        hb.hola_verify_ex(target_logits=s["P"], draft_logits=s["D"], draft_tokens=s["tok"], seed=w.seed + i, B=B, gamma=g, V=V,
+                          temperature=w.temperature, entropy_threshold=w.taus[0], out_accept_len=outs[0], out_next_token=outs[1],
+                          out_entropy=outs[2], workspace=s["ws"], stream=stream)
+
+    def fresh():
+        return (torch.full((B,), -7, dtype=torch.int32, device=DEV), torch.full((B,), -7, dtype=torch.int32, device=DEV),
+                torch.full((B, g), -7.0, dtype=torch.float32, device=DEV))
+
+    alone = {}
+    for k in range(2):
+        for i in range(n_calls):
+            o = fresh()
+            call(k, i, torch.cuda.current_stream(), o)
+            alone[(k, i)] = _host(o)
+    torch.cuda.synchronize()
+    together = {}
+    for i in range(n_calls):
+        for k in range(2):
+            o = fresh()
+            call(k, i, sets[k]["stream"], o)
+            together[(k, i)] = o
+    torch.cuda.synchronize()
+    rejected = 0
+    for key, o in together.items():
+        got, ref = _host(o), alone[key]
+        np.testing.assert_array_equal(got.accept_len, ref.accept_len, err_msg=str(key))
+        np.testing.assert_array_equal(got.next_token, ref.next_token, err_msg=str(key))
+        np.testing.assert_array_equal(got.entropy, ref.entropy)
+        rejected += int((ref.accept_len < g).sum())
+    assert rejected > 0                                           # residual draws, hence shared sweeps, took part
