@@ -54,6 +54,14 @@ def test_static_scratch_entry_matches_the_workspace_entry_twice_in_a_row():
     ex, st = _both(small, 0.0, top_k=40, top_p=0.9)
     for a, b in zip(ex, st):
         np.testing.assert_array_equal(a, b)
+    # a small batch of wide rows: several workgroups share a sequence's tail, their tickets lie in the static array,
+    # which by now holds whatever the calls above left there; twice, so that the second call meets the first one's
+    wide = wl.config3(B=6)
+    for _ in range(2):
+        ex, st = _both(wide, wide.taus[0])
+        for a, b in zip(ex, st):
+            np.testing.assert_array_equal(a, b)
+    assert (st[0] < wide.gamma).any()                            # residual draws took part
 
 
 def test_static_scratch_entry_refuses_what_does_not_fit():
