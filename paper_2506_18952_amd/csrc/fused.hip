@@ -10,7 +10,9 @@
 // split path is two launches instead of four.  Its phases are arranged so that memory round trips overlap:
 // see tail_kernel and sequence_tail.
 //
-// HBM-bound: every logit is read once, the stop row pair once more.  No atomics, no spin waits.
+// HBM-bound: every logit is read once, the stop row pair once more.  No spin waits anywhere; the one atomic is the
+// completion ticket of a tail that several workgroups share (small batches of wide rows, see sequence_tail), which
+// nobody waits for: whoever takes the last ticket carries on, the others leave.
 #include "accept_device.h"
 #include "filter_device.h"
 #include "sampler_device.h"
@@ -420,8 +422,9 @@ __global__ __launch_bounds__(NW * 64) void fused_kernel(FusedParams p)
 
 // Accept + sampling of one sequence from the row partials of the split-row kernel.  What does not depend on the
 // statistics is started first and by wavefronts of its own, so that the memory round trips of a sequence overlap
-// instead of following one another: wavefront 0 fetches the drafted tokens and their logits, the last wavefront
-// picks the slab a bonus token would come from, the ones between merge the rows' partials.
+// instead of following one another: wavefront 0 fetches the drafted tokens and their logits and computes the
+// positions' Philox blocks, the first few of the others merge the rows' partials, and every wavefront with nothing to
+// merge picks the slab a bonus token would come from and puts its tile of that slab in flight.
 template <bool BF16, int NW, bool FILT = false, bool COOP = false>
 __global__ __launch_bounds__(NW * 64) void tail_kernel(FusedParams p, const Partial* __restrict__ partials, int nparts)
 {
